@@ -1,0 +1,315 @@
+"""CPU oracle for the Highway-BP backward pass (arXiv 2501.17086).
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain, fp64 definition that
+the GPU library is checked against.  Nothing in the product path may import it;
+only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg do.  It
+shares no code with the HIP path and never receives values computed by it.
+
+Every function is written from the paper's definitions (numpy fp64; a matmul
+and erf are the only library steps; no blocking, fusion or reordering):
+
+  model      Section "Notations and assumptions": h_i = f_i(h_{i-1}),
+             f_i(x) = r_i(x, g_i(x)), Jacobian J_i + K_i.  Here the residual
+             function is r(x, z) = lam (.) x + z, so K = diag(lam), and the
+             block is  g(x) = W2 . act(W1 . norm(x) [+ U . xin]).
+  exact BP   Section "Backpropagation as a system of equations" and the first
+             line of the proof of Theorem 1 (chain rule through J + K).
+  Highway-BP Theorem 2 (w^0 and the recursion for w^{k+1}) in its two-step
+             "Parallel computation" form: v_i = w_{i+1} J_{i+1} for all i,
+             then u_i = v_i + u_{i+1} K_{i+1}, and w^{k+1} = w^0 + u.
+  CumSumProd its definition in Section "Parallel computation"
+             (sum_{j>=i} a_j M_j ... M_{i+1}); Algorithm 1 (Hillis-Steele) is
+             reproduced separately for cross-checking.
+  param grad sentence after Theorem 2: dL/dtheta_i = w_i . df_i/dtheta_i.
+
+Indexing (0-based states x_0..x_L, blocks l = 0..L-1, x_{l+1} = lam_l (.) x_l +
+block_l(x_l)): the paper's h_i is x_i, its layer i is block i-1, K_i =
+diag(lam_{i-1}), J_i = d block_{i-1} / d x at x_{i-1}, dL_i/dh_i is e_i.
+Gradients are stored as rows [N, d] (one row per token), matching the paper's
+row-vector convention  w J.
+
+Parity status: every function below is pinned by tests/test_oracle_pins.py
+(finite differences, closed forms, path enumeration, an independent autograd
+library) -- no function is "parity unpinned".
+"""
+from __future__ import annotations
+
+import math
+from dataclasses import dataclass
+from typing import Dict, Optional
+
+import numpy as np
+from scipy.special import erf as _erf
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------
+# model description
+# --------------------------------------------------------------------------
+@dataclass
+class Stack:
+    """A residual stack.
+
+    kind   'mlp'  per-block weights W1[L,d_ff,d], W2[L,d,d_ff]
+           'rnn'  weights shared by all L (= T) blocks: W1 = W_h [d_ff,d],
+                  W2 = W_o [d,d_ff], U [d_ff,d_in]; block l maps state l to
+                  l+1 and consumes xin[l]
+    act    'gelu' (exact erf form) | 'tanh' | 'identity'
+    norm   'none' | 'rms'  (no gain, eps inside the square root)
+    lam    None (lambda = 1) or [L, d]
+    """
+    kind: str
+    act: str
+    norm: str
+    W1: np.ndarray
+    W2: np.ndarray
+    lam: Optional[np.ndarray] = None
+    U: Optional[np.ndarray] = None
+    eps: float = 1e-6
+    L: int = 0
+
+    def __post_init__(self):
+        assert self.kind in ("mlp", "rnn")
+        assert self.act in ("gelu", "tanh", "identity")
+        assert self.norm in ("none", "rms")
+        self.W1 = np.asarray(self.W1, dtype=F64)
+        self.W2 = np.asarray(self.W2, dtype=F64)
+        if self.lam is not None:
+            self.lam = np.asarray(self.lam, dtype=F64)
+        if self.U is not None:
+            self.U = np.asarray(self.U, dtype=F64)
+        if self.kind == "mlp":
+            assert self.W1.ndim == 3 and self.W2.ndim == 3
+            self.L = self.W1.shape[0]
+        else:
+            assert self.W1.ndim == 2 and self.W2.ndim == 2
+            assert self.L > 0, "rnn stacks need L (= T) given"
+
+    @property
+    def d(self) -> int:
+        return self.W2.shape[-2]
+
+    @property
+    def d_ff(self) -> int:
+        return self.W1.shape[-2]
+
+    def w1(self, l: int) -> np.ndarray:
+        return self.W1[l] if self.kind == "mlp" else self.W1
+
+    def w2(self, l: int) -> np.ndarray:
+        return self.W2[l] if self.kind == "mlp" else self.W2
+
+    def lam_row(self, l: int) -> np.ndarray:
+        if self.lam is None:
+            return np.ones(self.d, dtype=F64)
+        return self.lam[l]
+
+
+# --------------------------------------------------------------------------
+# activations
+# --------------------------------------------------------------------------
+def act_fn(name: str, a: np.ndarray) -> np.ndarray:
+    if name == "gelu":          # a * Phi(a), Phi = standard normal CDF
+        return 0.5 * a * (1.0 + _erf(a / math.sqrt(2.0)))
+    if name == "tanh":
+        return np.tanh(a)
+    return a
+
+
+def act_grad(name: str, a: np.ndarray) -> np.ndarray:
+    if name == "gelu":          # Phi(a) + a * pdf(a)
+        return 0.5 * (1.0 + _erf(a / math.sqrt(2.0))) + a * np.exp(-0.5 * a * a) / math.sqrt(2.0 * math.pi)
+    if name == "tanh":
+        t = np.tanh(a)
+        return 1.0 - t * t
+    return np.ones_like(a)
+
+
+# --------------------------------------------------------------------------
+# forward: produces the states and what the backward pass needs
+# --------------------------------------------------------------------------
+def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+    """x_{l+1} = lam_l (.) x_l + W2_l . act(W1_l . norm(x_l) [+ U . xin_l]).
+
+    Returns x[L+1,N,d] and the saved tensors y = norm(x_l) [L,N,d],
+    rinv = 1/rms [L,N] (ones without a norm), a (pre-activation), z = act(a),
+    dphi = act'(a), all [L,N,d_ff].
+    """
+    x0 = np.asarray(x0, dtype=F64)
+    N, d = x0.shape
+    L, dff = st.L, st.d_ff
+    x = np.zeros((L + 1, N, d), F64)
+    y = np.zeros((L, N, d), F64)
+    rinv = np.ones((L, N), F64)
+    a = np.zeros((L, N, dff), F64)
+    x[0] = x0
+    for l in range(L):
+        if st.norm == "rms":
+            r = np.sqrt(np.mean(x[l] * x[l], axis=1) + st.eps)
+            rinv[l] = 1.0 / r
+            y[l] = x[l] / r[:, None]
+        else:
+            y[l] = x[l]
+        a[l] = y[l] @ st.w1(l).T
+        if st.kind == "rnn":
+            a[l] += np.asarray(xin[l], dtype=F64) @ st.U.T
+        x[l + 1] = st.lam_row(l)[None, :] * x[l] + act_fn(st.act, a[l]) @ st.w2(l).T
+    return {"x": x, "y": y, "rinv": rinv, "a": a,
+            "z": act_fn(st.act, a), "dphi": act_grad(st.act, a)}
+
+
+# --------------------------------------------------------------------------
+# step (i): vector-Jacobian product through one block,  v_l = g_{l+1} J_{l+1}
+# --------------------------------------------------------------------------
+def block_preact_grad(st: Stack, l: int, saved: Dict[str, np.ndarray], g_next: np.ndarray) -> np.ndarray:
+    """Gradient w.r.t. the pre-activation of block l: (g W2) (.) act'(a)."""
+    return (g_next @ st.w2(l)) * saved["dphi"][l]
+
+
+def block_vjp(st: Stack, l: int, saved: Dict[str, np.ndarray], g_next: np.ndarray) -> np.ndarray:
+    da = block_preact_grad(st, l, saved, g_next)
+    dn = da @ st.w1(l)
+    if st.norm == "rms":
+        # y = x / r, r = sqrt(mean(x^2) + eps):  dx = (dn - y * mean(dn (.) y)) / r
+        y = saved["y"][l]
+        m = np.mean(dn * y, axis=1, keepdims=True)
+        return (dn - y * m) * saved["rinv"][l][:, None]
+    return dn
+
+
+def _e_full(st: Stack, e: np.ndarray, N: int) -> np.ndarray:
+    """Per-state loss gradients e_0..e_L.  A [N,d] array means only e_L != 0."""
+    e = np.asarray(e, dtype=F64)
+    if e.ndim == 2:
+        full = np.zeros((st.L + 1, N, st.d), F64)
+        full[st.L] = e
+        return full
+    assert e.shape[0] == st.L + 1
+    return e
+
+
+# --------------------------------------------------------------------------
+# exact sequential backpropagation
+# --------------------------------------------------------------------------
+def exact_backward(st: Stack, saved: Dict[str, np.ndarray], e: np.ndarray) -> np.ndarray:
+    """G_L = e_L ; G_l = e_l + G_{l+1} (K_{l+1} + J_{l+1}),  l = L-1 .. 0."""
+    N = saved["y"].shape[1]
+    ef = _e_full(st, e, N)
+    G = np.zeros_like(ef)
+    G[st.L] = ef[st.L]
+    for l in range(st.L - 1, -1, -1):
+        G[l] = ef[l] + st.lam_row(l)[None, :] * G[l + 1] + block_vjp(st, l, saved, G[l + 1])
+    return G
+
+
+# --------------------------------------------------------------------------
+# CumSumProd along the residual path (sequential form of the recurrence)
+# --------------------------------------------------------------------------
+def cumsumprod_reverse(a: np.ndarray, lam_rows) -> np.ndarray:
+    """u_i = sum_{j>=i} a_j M_j ... M_{i+1} with diagonal M: the multiplier that
+    carries position i+1 to position i is lam_rows(i).
+
+    a has shape [P, N, d] (positions 0..P-1); returns u of the same shape,
+    computed by u_{P-1} = a_{P-1}, u_i = a_i + lam_i (.) u_{i+1}.
+    """
+    P = a.shape[0]
+    u = np.zeros_like(a)
+    u[P - 1] = a[P - 1]
+    for i in range(P - 2, -1, -1):
+        u[i] = a[i] + lam_rows(i)[None, :] * u[i + 1]
+    return u
+
+
+# --------------------------------------------------------------------------
+# Highway-BP, k iterations (Theorem 2, two-step form)
+# --------------------------------------------------------------------------
+def hbp_backward(st: Stack, saved: Dict[str, np.ndarray], e: np.ndarray, k: int,
+                 return_all: bool = False):
+    """w^0 = CumSumProd(e, K);  repeat k times: v_l = w_{l+1} J_{l+1} for every
+    l from the current estimate, u = CumSumProd(v, K), w <- w^0 + u."""
+    assert k >= 0
+    N = saved["y"].shape[1]
+    L = st.L
+    ef = _e_full(st, e, N)
+    w0 = cumsumprod_reverse(ef, st.lam_row)
+    w = w0.copy()
+    hist = [w0.copy()]
+    for _ in range(k):
+        v = np.zeros_like(w)                       # v_L = 0: no block above x_L
+        for l in range(L):
+            v[l] = block_vjp(st, l, saved, w[l + 1])
+        u = cumsumprod_reverse(v, st.lam_row)
+        w = w0 + u
+        hist.append(w.copy())
+    return hist if return_all else w
+
+
+# --------------------------------------------------------------------------
+# parameter gradients from a given state-gradient estimate
+# --------------------------------------------------------------------------
+def param_grads(st: Stack, saved: Dict[str, np.ndarray], g: np.ndarray,
+                xin: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
+    """dW2_l = sum_n g_{l+1}[n]^T z_l[n] ; dW1_l = sum_n da_l[n]^T y_l[n] ;
+    dU = sum da^T xin, with da from the given g.  Shared weights (rnn) sum
+    over l as well."""
+    L = st.L
+    if st.kind == "mlp":
+        dW1 = np.zeros_like(st.W1)
+        dW2 = np.zeros_like(st.W2)
+        for l in range(L):
+            da = block_preact_grad(st, l, saved, g[l + 1])
+            dW2[l] = g[l + 1].T @ saved["z"][l]
+            dW1[l] = da.T @ saved["y"][l]
+        return {"dW1": dW1, "dW2": dW2}
+    dW1 = np.zeros_like(st.W1)
+    dW2 = np.zeros_like(st.W2)
+    dU = np.zeros_like(st.U)
+    for l in range(L):
+        da = block_preact_grad(st, l, saved, g[l + 1])
+        dW2 += g[l + 1].T @ saved["z"][l]
+        dW1 += da.T @ saved["y"][l]
+        dU += da.T @ np.asarray(xin[l], dtype=F64)
+    return {"dW1": dW1, "dW2": dW2, "dU": dU}
+
+
+# --------------------------------------------------------------------------
+# Algorithm 1 (Hillis-Steele CumSumProd) -- only used to cross-check the scan
+# --------------------------------------------------------------------------
+def cumsumprod_hillis_steele(a: np.ndarray, lam_rows) -> np.ndarray:
+    """ceil(log2 P) sweeps over pairs (u_i, P_i); P_i starts as the multiplier
+    that carries position i+1 to i (the reading that matches the algorithm's
+    stated post-condition), and a sweep with stride s does
+    u_i += u_{i+s} P_i ; P_i <- P_{i+s} P_i  for i + s < P."""
+    P = a.shape[0]
+    u = a.astype(F64).copy()
+    d = a.shape[-1]
+    Pm = np.ones((P, d), F64)
+    for i in range(P - 1):
+        Pm[i] = lam_rows(i)
+    s = 1
+    while s < P:
+        un, Pn = u.copy(), Pm.copy()
+        for i in range(P - s):
+            un[i] = u[i] + Pm[i][None, :] * u[i + s]
+            Pn[i] = Pm[i + s] * Pm[i]
+        u, Pm = un, Pn
+        s *= 2
+    return u
+
+
+# --------------------------------------------------------------------------
+# error measures used in reports
+# --------------------------------------------------------------------------
+def rel_l2(a: np.ndarray, b: np.ndarray) -> float:
+    """||a - b||_2 / ||b||_2 (b is the reference)."""
+    a = np.asarray(a, F64).ravel()
+    b = np.asarray(b, F64).ravel()
+    nb = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / nb) if nb > 0 else float(np.linalg.norm(a - b))
+
+
+def cosine(a: np.ndarray, b: np.ndarray) -> float:
+    a = np.asarray(a, F64).ravel()
+    b = np.asarray(b, F64).ravel()
+    return float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b)))

@@ -1,0 +1,163 @@
+"""Seeded synthetic inputs for the Highway-BP workloads.
+
+This module only draws random tensors (and rounds them to the storage type).
+It holds none of the method's arithmetic and serves both the GPU library's
+callers (tests, bench) and the CPU oracle's callers, so that both sides see
+the same bits.
+
+Generator: numpy's counter-based Philox, keyed by (seed, tensor id, block
+index), so any block's tensor can be regenerated on its own and in any order.
+
+Workloads follow the five stacks the benchmark names: a small fp32 residual
+MLP stack, a ResNet-like and two Transformer-depth pre-RMSNorm MLP stacks in
+bf16, and a gated RNN along time with shared weights.  Conventions: N(0, 1/fan_in)
+gives the variance; N(0, 0.02) gives the standard deviation (the usual
+transformer initialisation); lambda is per (block, channel) and shared by all
+tokens; in the RNN lambda_t = sigmoid(N(3, 0.5^2)) is constant data.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, replace
+from typing import Dict, Optional
+
+import numpy as np
+
+# tensor ids for the Philox key
+_T_W1, _T_W2, _T_U, _T_LAM, _T_X0, _T_XIN, _T_E = 1, 2, 3, 4, 5, 6, 7
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    kind: str            # 'mlp' | 'rnn'
+    dtype: str           # 'f32' | 'bf16'   (storage; accumulation is fp32 on the GPU)
+    act: str             # 'gelu' | 'tanh' | 'identity'
+    norm: str            # 'none' | 'rms'
+    L: int               # blocks (depth) or time steps T
+    N: int               # tokens (rnn: batch rows per step)
+    d: int               # state width (rnn: hidden H)
+    d_ff: int            # block inner width (rnn: H)
+    d_in: int = 0        # rnn input width
+    lam: str = "one"     # 'one' | 'uniform' | 'sigmoid'
+    lam_lo: float = 1.0
+    lam_hi: float = 1.0
+    w1_std: float = 0.0  # 0 -> 1/sqrt(fan_in)
+    w2_std: float = 0.0
+    w2_scale: float = 1.0
+    rec_scale: float = 1.0   # extra factor on W_h and W_o (rnn variants)
+    loss_every_state: bool = False
+    eps: float = 1e-6
+    ks: tuple = (1, 2, 3, 4)
+    seed: int = 0
+
+    @property
+    def tokens(self) -> int:
+        return self.N * self.L if self.kind == "rnn" else self.N
+
+
+WORKLOADS: Dict[str, Workload] = {
+    # small fp32 residual MLP stack, lambda = 1, no norm
+    "mlp_small_f32": Workload("mlp_small_f32", "mlp", "f32", "gelu", "none", L=8, N=128, d=64, d_ff=256,
+                              ks=(0, 1, 2, 8)),
+    # ResNet-like: per-channel lambda ~ U(0.9,1), W2 scaled by 1/sqrt(L)
+    "resnet_like": Workload("resnet_like", "mlp", "bf16", "gelu", "rms", L=32, N=8192, d=512, d_ff=2048,
+                            lam="uniform", lam_lo=0.9, lam_hi=1.0, w2_scale=1.0 / np.sqrt(32.0)),
+    # Transformer-depth MLP stack, lambda = 1
+    "transformer_mlp": Workload("transformer_mlp", "mlp", "bf16", "gelu", "rms", L=48, N=16384, d=1024,
+                                d_ff=4096, w1_std=0.02, w2_std=0.02, w2_scale=1.0 / np.sqrt(96.0)),
+    # gated RNN along time, shared weights, a loss at every step
+    "gated_rnn": Workload("gated_rnn", "rnn", "bf16", "tanh", "none", L=4096, N=32, d=1024, d_ff=1024,
+                          d_in=1024, lam="sigmoid", lam_lo=3.0, lam_hi=0.5, loss_every_state=True),
+    # large deep stack
+    "deep_large": Workload("deep_large", "mlp", "bf16", "gelu", "rms", L=96, N=16384, d=2048, d_ff=8192,
+                           lam="uniform", lam_lo=0.8, lam_hi=1.0, w1_std=0.02, w2_std=0.02,
+                           w2_scale=1.0 / np.sqrt(192.0), ks=(1, 2, 3)),
+}
+# contractive variant of the RNN (recurrent weights x 0.25): the stack as
+# specified is chaotic, so exact BPTT gradients overflow over 4096 steps.
+WORKLOADS["gated_rnn_contractive"] = replace(WORKLOADS["gated_rnn"], name="gated_rnn_contractive",
+                                             rec_scale=0.25)
+
+
+def scaled(w: Workload, **kw) -> Workload:
+    """The same recipe at other sizes (for parity tests)."""
+    return replace(w, **kw)
+
+
+def round_bf16(a: np.ndarray) -> np.ndarray:
+    """Round fp32 values to the nearest bf16-representable value (ties to even)."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    u = a.view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).reshape(a.shape)
+
+
+def storage_round(w: Workload, a: np.ndarray) -> np.ndarray:
+    return round_bf16(a) if w.dtype == "bf16" else np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _rng(w: Workload, tid: int, idx: int = 0) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(key=[(w.seed << 8) | tid, idx]))
+
+
+def _normal(w: Workload, tid: int, idx: int, shape, std: float) -> np.ndarray:
+    return _rng(w, tid, idx).standard_normal(shape, dtype=np.float32) * np.float32(std)
+
+
+def weights_block(w: Workload, l: int):
+    """(W1_l [d_ff,d], W2_l [d,d_ff]) for block l (rnn: l is ignored)."""
+    idx = 0 if w.kind == "rnn" else l
+    s1 = w.w1_std if w.w1_std > 0 else 1.0 / np.sqrt(w.d)
+    s2 = (w.w2_std if w.w2_std > 0 else 1.0 / np.sqrt(w.d_ff)) * w.w2_scale
+    W1 = _normal(w, _T_W1, idx, (w.d_ff, w.d), s1 * w.rec_scale)
+    W2 = _normal(w, _T_W2, idx, (w.d, w.d_ff), s2 * w.rec_scale)
+    return storage_round(w, W1), storage_round(w, W2)
+
+
+def make_lambda(w: Workload) -> Optional[np.ndarray]:
+    """lambda [L,d] fp32, or None when lambda = 1."""
+    if w.lam == "one":
+        return None
+    g = _rng(w, _T_LAM)
+    if w.lam == "uniform":
+        return g.uniform(w.lam_lo, w.lam_hi, (w.L, w.d)).astype(np.float32)
+    a = g.standard_normal((w.L, w.d), dtype=np.float32) * np.float32(w.lam_hi) + np.float32(w.lam_lo)
+    return (1.0 / (1.0 + np.exp(-a.astype(np.float64)))).astype(np.float32)
+
+
+def make_inputs(w: Workload, tokens: Optional[slice] = None) -> Dict[str, Optional[np.ndarray]]:
+    """All tensors of a workload as fp32 numpy arrays holding storage-representable
+    values.  `tokens` restricts the token axis (rnn: the batch axis) to a slice;
+    the full tensors are drawn and then cut, so a subset sees the same values
+    as the full run.
+
+    Keys: W1, W2 (mlp: [L,...]; rnn: shared), U (rnn), lam, x0 [N,d],
+    xin [L,N,d_in] (rnn), e ([N,d], or [L+1,N,d] with e[0] = 0 when every state
+    has a loss).
+    """
+    sl = tokens if tokens is not None else slice(None)
+    out: Dict[str, Optional[np.ndarray]] = {}
+    if w.kind == "mlp":
+        W1 = np.empty((w.L, w.d_ff, w.d), np.float32)
+        W2 = np.empty((w.L, w.d, w.d_ff), np.float32)
+        for l in range(w.L):
+            W1[l], W2[l] = weights_block(w, l)
+        out["U"] = None
+        out["xin"] = None
+    else:
+        W1, W2 = weights_block(w, 0)
+        out["U"] = storage_round(w, _normal(w, _T_U, 0, (w.d_ff, w.d_in), 1.0 / np.sqrt(w.d_in)))
+        out["xin"] = storage_round(w, _normal(w, _T_XIN, 0, (w.L, w.N, w.d_in), 1.0)[:, sl])
+    out["W1"], out["W2"] = W1, W2
+    out["lam"] = make_lambda(w)
+    if w.kind == "rnn":
+        out["x0"] = np.zeros((w.N, w.d), np.float32)[sl]
+    else:
+        out["x0"] = storage_round(w, _normal(w, _T_X0, 0, (w.N, w.d), 1.0)[sl])
+    if w.loss_every_state:
+        e = _normal(w, _T_E, 0, (w.L + 1, w.N, w.d), 1.0)
+        e[0] = 0.0
+        out["e"] = storage_round(w, e[:, sl])
+    else:
+        out["e"] = storage_round(w, _normal(w, _T_E, 0, (w.N, w.d), 1.0)[sl])
+    return out

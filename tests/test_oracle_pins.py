@@ -1,0 +1,391 @@
+"""Pins for the CPU oracle: every check compares the oracle with something the
+paper or the mathematics fixes independently of the oracle's own code
+(finite differences, closed forms, explicit path enumeration, an independent
+autograd library), so a dropped term, wrong index, sign or transposed operand
+fails at least one of them.  CPU only.
+"""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import hbp_oracle as O
+
+RNG = np.random.default_rng(1234)
+
+
+def small_mlp(L=4, d=6, dff=10, act="gelu", norm="rms", lam="rand", seed=0):
+    r = np.random.default_rng(seed)
+    W1 = r.standard_normal((L, dff, d)) / math.sqrt(d)
+    W2 = r.standard_normal((L, d, dff)) / math.sqrt(dff)
+    lm = None if lam == "one" else r.uniform(0.5, 1.1, (L, d))
+    return O.Stack("mlp", act, norm, W1, W2, lam=lm)
+
+
+def small_rnn(T=5, H=6, I=4, seed=0):
+    r = np.random.default_rng(seed)
+    Wh = r.standard_normal((H, H)) / math.sqrt(H)
+    Wo = r.standard_normal((H, H)) / math.sqrt(H)
+    U = r.standard_normal((H, I)) / math.sqrt(I)
+    lm = 1.0 / (1.0 + np.exp(-r.normal(3.0, 0.5, (T, H))))
+    return O.Stack("rnn", "tanh", "none", Wh, Wo, lam=lm, U=U, L=T)
+
+
+# ---------------------------------------------------------------- P1
+@pytest.mark.parametrize("family", ["mlp_rms", "mlp_plain", "rnn"])
+def test_finite_termination_and_exact_top_states(family):
+    """Theorem 2, last sentence: w_i^k is exact for k >= L - i.  So k = L is exact
+    everywhere and after k iterations the top k+1 states already are."""
+    r = np.random.default_rng(5)
+    if family == "rnn":
+        st = small_rnn(T=6)
+        N = 3
+        xin = r.standard_normal((st.L, N, 4))
+        sv = O.forward(st, np.zeros((N, st.d)), xin)
+        e = r.standard_normal((st.L + 1, N, st.d))
+        e[0] = 0
+    else:
+        st = small_mlp(L=6, norm="rms" if family == "mlp_rms" else "none",
+                       lam="rand" if family == "mlp_rms" else "one")
+        N = 3
+        sv = O.forward(st, r.standard_normal((N, st.d)))
+        e = r.standard_normal((N, st.d))
+    G = O.exact_backward(st, sv, e)
+    L = st.L
+    for k in range(L + 2):
+        w = O.hbp_backward(st, sv, e, k)
+        lo = max(L - k, 0)
+        np.testing.assert_allclose(w[lo:], G[lo:], rtol=1e-11, atol=1e-12)
+        if k < L - 1:      # and it is a genuine truncation below that
+            assert O.rel_l2(w[0], G[0]) > 1e-6
+    np.testing.assert_allclose(O.hbp_backward(st, sv, e, L), G, rtol=1e-11, atol=1e-12)
+
+
+# ---------------------------------------------------------------- P2
+def test_k0_is_cumulative_product_of_lambda_depth():
+    """Initial estimate of Theorem 2 with a loss on the last state only:
+    w_i^0 = e_L K_L ... K_{i+1}."""
+    st = small_mlp(L=5)
+    N = 4
+    sv = O.forward(st, RNG.standard_normal((N, st.d)))
+    e = RNG.standard_normal((N, st.d))
+    w0 = O.hbp_backward(st, sv, e, 0)
+    for l in range(st.L + 1):
+        prod = np.ones(st.d)
+        for m in range(l, st.L):
+            prod = prod * st.lam[m]
+        np.testing.assert_allclose(w0[l], e * prod[None, :], rtol=1e-13)
+
+
+def test_k0_rnn_double_sum():
+    """w_i^0 = sum_{j>=i} e_j K_j ... K_{i+1} with a loss at every state."""
+    st = small_rnn(T=6)
+    N = 2
+    xin = RNG.standard_normal((st.L, N, 4))
+    sv = O.forward(st, np.zeros((N, st.d)), xin)
+    e = RNG.standard_normal((st.L + 1, N, st.d))
+    w0 = O.hbp_backward(st, sv, e, 0)
+    for i in range(st.L + 1):
+        acc = np.zeros((N, st.d))
+        for j in range(i, st.L + 1):
+            prod = np.ones(st.d)
+            for m in range(i, j):
+                prod = prod * st.lam[m]
+            acc += e[j] * prod[None, :]
+        np.testing.assert_allclose(w0[i], acc, rtol=1e-12, atol=1e-13)
+
+
+# ---------------------------------------------------------------- P3
+def test_zero_block_closed_form():
+    """Blocks with W2 = 0: the stack is x_l = x_0 prod(lam), every iteration
+    returns w^0, dW1 = 0 and dW2_l = sum_n w^0_{l+1}[n]^T act(W1 norm(x_l)[n])."""
+    st = small_mlp(L=4)
+    st.W2[:] = 0.0
+    N = 5
+    x0 = RNG.standard_normal((N, st.d))
+    sv = O.forward(st, x0)
+    e = RNG.standard_normal((N, st.d))
+    prod = np.ones(st.d)
+    for l in range(st.L + 1):
+        np.testing.assert_allclose(sv["x"][l], x0 * prod[None, :], rtol=1e-13)
+        if l < st.L:
+            prod = prod * st.lam[l]
+    w0 = O.hbp_backward(st, sv, e, 0)
+    for k in (1, 3):
+        np.testing.assert_allclose(O.hbp_backward(st, sv, e, k), w0, rtol=0, atol=0)
+    pg = O.param_grads(st, sv, w0)
+    assert np.all(pg["dW1"] == 0)
+    for l in range(st.L):
+        xl = sv["x"][l]
+        yl = xl / np.sqrt(np.mean(xl ** 2, axis=1, keepdims=True) + st.eps)
+        al = yl @ st.W1[l].T
+        zl = np.array([[0.5 * v * (1 + math.erf(v / math.sqrt(2))) for v in row] for row in al])
+        tail = np.ones(st.d)
+        for m in range(l + 1, st.L):
+            tail = tail * st.lam[m]
+        want = (e * tail[None, :]).T @ zl
+        np.testing.assert_allclose(pg["dW2"][l], want, rtol=1e-11, atol=1e-13)
+
+
+# ---------------------------------------------------------------- P4
+def _loss(st, x0, xin, c):
+    sv = O.forward(st, x0, xin)
+    return float(np.sum(c * sv["x"]))
+
+
+@pytest.mark.parametrize("family", ["mlp_rms_gelu", "mlp_none_gelu", "mlp_rms_tanh", "rnn"])
+def test_exact_gradient_by_finite_differences(family):
+    """Central differences of loss = sum_l <c_l, x_l> against exact_backward (state
+    gradient at x_0) and param_grads (every weight entry of a tiny stack)."""
+    r = np.random.default_rng(11)
+    N = 2
+    if family == "rnn":
+        st = small_rnn(T=4, H=5, I=3)
+        xin = r.standard_normal((st.L, N, 3))
+        x0 = r.standard_normal((N, st.d)) * 0.3     # non-zero h_0 exercises g[0]
+    else:
+        _, norm, act = family.split("_")
+        st = small_mlp(L=3, d=5, dff=7, act=act, norm=norm)
+        xin = None
+        x0 = r.standard_normal((N, st.d))
+    c = r.standard_normal((st.L + 1, N, st.d))
+    sv = O.forward(st, x0, xin)
+    G = O.exact_backward(st, sv, c)
+    pg = O.param_grads(st, sv, G, xin)
+    h = 1e-6
+
+    def fd(arr):
+        out = np.zeros_like(arr)
+        it = np.nditer(arr, flags=["multi_index"])
+        for _ in it:
+            i = it.multi_index
+            old = arr[i]
+            arr[i] = old + h
+            lp = _loss(st, x0, xin, c)
+            arr[i] = old - h
+            lm = _loss(st, x0, xin, c)
+            arr[i] = old
+            out[i] = (lp - lm) / (2 * h)
+        return out
+
+    np.testing.assert_allclose(G[0], fd(x0), rtol=2e-6, atol=2e-8)
+    np.testing.assert_allclose(pg["dW1"], fd(st.W1), rtol=2e-6, atol=2e-8)
+    np.testing.assert_allclose(pg["dW2"], fd(st.W2), rtol=2e-6, atol=2e-8)
+    if family == "rnn":
+        np.testing.assert_allclose(pg["dU"], fd(st.U), rtol=2e-6, atol=2e-8)
+
+
+# ---------------------------------------------------------------- P5
+def test_scalar_linear_binomial_closed_form():
+    """J = c I and K = a I: paths with exactly j Jacobians among L - i layers
+    number C(L-i, j), so w_i^k = e_L sum_{j<=min(k,L-i)} C(L-i,j) c^j a^(L-i-j)."""
+    L, d, N = 7, 3, 2
+    c, a = 0.37, 0.9
+    W1 = np.tile(np.eye(d)[None], (L, 1, 1))
+    W2 = np.tile((c * np.eye(d))[None], (L, 1, 1))
+    st = O.Stack("mlp", "identity", "none", W1, W2, lam=np.full((L, d), a))
+    sv = O.forward(st, RNG.standard_normal((N, d)))
+    e = RNG.standard_normal((N, d))
+    for k in range(L + 1):
+        w = O.hbp_backward(st, sv, e, k)
+        for i in range(L + 1):
+            n = L - i
+            coef = sum(math.comb(n, j) * c ** j * a ** (n - j) for j in range(min(k, n) + 1))
+            np.testing.assert_allclose(w[i], coef * e, rtol=1e-12)
+
+
+# ---------------------------------------------------------------- P6
+def _dense_block_jacobians(st, sv, n):
+    """J_l[out, in] = d block_l(x)[out] / d x[in] for token n, by central
+    differences of the block's forward map (independent of block_vjp)."""
+    L, d = st.L, st.d
+    Js = []
+    for l in range(L):
+        x = sv["x"][l][n].copy()
+
+        def blk(xv):
+            if st.norm == "rms":
+                yv = xv / math.sqrt(np.mean(xv * xv) + st.eps)
+            else:
+                yv = xv
+            return O.act_fn(st.act, st.w1(l) @ yv) @ st.w2(l).T
+
+        J = np.zeros((d, d))
+        for i in range(d):
+            h = 1e-6
+            xp, xm = x.copy(), x.copy()
+            xp[i] += h
+            xm[i] -= h
+            J[:, i] = (blk(xp) - blk(xm)) / (2 * h)
+        Js.append(J)
+    return Js
+
+
+def test_path_enumeration_matches_theorem():
+    """Theorems 1 and 2: w_i^k is the sum over end states j >= i and subsets of
+    blocks of size <= k of e_j times the product of J (chosen) or K (not)."""
+    st = small_mlp(L=5, d=3, dff=4)
+    N = 1
+    r = np.random.default_rng(3)
+    sv = O.forward(st, r.standard_normal((N, st.d)))
+    e = r.standard_normal((st.L + 1, N, st.d))
+    e[0] = 0
+    Js = _dense_block_jacobians(st, sv, 0)
+    Ks = [np.diag(st.lam[l]) for l in range(st.L)]
+    L = st.L
+    for k in range(L + 1):
+        w = O.hbp_backward(st, sv, e, k)
+        for i in range(L + 1):
+            acc = np.zeros(st.d)
+            for j in range(i, L + 1):
+                layers = list(range(i, j))          # blocks between state i and state j
+                for size in range(min(k, len(layers)) + 1):
+                    for chosen in itertools.combinations(layers, size):
+                        vec = e[j][0].copy()
+                        for l in reversed(layers):   # row vector times matrices, top block first
+                            vec = vec @ (Js[l] if l in chosen else Ks[l])
+                        acc += vec
+            np.testing.assert_allclose(w[i][0], acc, rtol=2e-6, atol=2e-8)
+    # k = L enumerates all 2^L paths: the full gradient (Theorem 1)
+    G = O.exact_backward(st, sv, e)
+    np.testing.assert_allclose(O.hbp_backward(st, sv, e, L), G, rtol=1e-11, atol=1e-12)
+
+
+# ---------------------------------------------------------------- P7
+@pytest.mark.parametrize("P", [1, 2, 5, 8, 13])
+def test_cumsumprod_definition_and_hillis_steele(P):
+    """CumSumProd(a, M)_i = sum_{j>=i} a_j M_j ... M_{i+1}, and the parallel
+    Hillis-Steele form of the appendix gives the same result."""
+    r = np.random.default_rng(P)
+    d, N = 4, 3
+    a = r.standard_normal((P, N, d))
+    lam = r.uniform(0.3, 1.2, (P, d))
+    rows = lambda i: lam[i]
+    u = O.cumsumprod_reverse(a, rows)
+    want = np.zeros_like(a)
+    for i in range(P):
+        for j in range(i, P):
+            prod = np.ones(d)
+            for m in range(i, j):
+                prod = prod * lam[m]
+            want[i] += a[j] * prod[None, :]
+    np.testing.assert_allclose(u, want, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(O.cumsumprod_hillis_steele(a, rows), want, rtol=1e-12, atol=1e-13)
+
+
+# ---------------------------------------------------------------- P8
+def test_fixed_point_iteration_special_case():
+    """K = 0 (lambda = 0): only the pure-Jacobian path survives, so with a loss
+    on the last state w_i^k is the exact gradient for i >= L - k and 0 below."""
+    st = small_mlp(L=5)
+    st.lam[:] = 0.0
+    N = 2
+    sv = O.forward(st, RNG.standard_normal((N, st.d)))
+    e = RNG.standard_normal((N, st.d))
+    G = O.exact_backward(st, sv, e)
+    for k in range(st.L + 1):
+        w = O.hbp_backward(st, sv, e, k)
+        for i in range(st.L + 1):
+            if i >= st.L - k:
+                np.testing.assert_allclose(w[i], G[i], rtol=1e-12, atol=1e-14)
+            else:
+                assert np.all(w[i] == 0)
+
+
+# ---------------------------------------------------------------- P9
+def test_gamma_reparametrisation_leaves_exact_gradient_unchanged():
+    """Moving gamma*x from the residual connection into the block changes J and K
+    but not J + K, so the exact gradient is the same (identity activation lets
+    the block absorb gamma*x as extra hidden units)."""
+    L, d, dff, N, gamma = 4, 4, 6, 3, 0.2
+    r = np.random.default_rng(9)
+    W1 = r.standard_normal((L, dff, d)) / 2
+    W2 = r.standard_normal((L, d, dff)) / 2
+    lam = r.uniform(0.6, 1.0, (L, d))
+    stA = O.Stack("mlp", "identity", "none", W1, W2, lam=lam)
+    W1b = np.concatenate([W1, np.tile(np.eye(d)[None], (L, 1, 1))], axis=1)
+    W2b = np.concatenate([W2, np.tile((gamma * np.eye(d))[None], (L, 1, 1))], axis=2)
+    stB = O.Stack("mlp", "identity", "none", W1b, W2b, lam=lam - gamma)
+    x0 = r.standard_normal((N, d))
+    e = r.standard_normal((N, d))
+    svA, svB = O.forward(stA, x0), O.forward(stB, x0)
+    np.testing.assert_allclose(svA["x"], svB["x"], rtol=1e-11, atol=1e-13)
+    GA, GB = O.exact_backward(stA, svA, e), O.exact_backward(stB, svB, e)
+    np.testing.assert_allclose(GA, GB, rtol=1e-11, atol=1e-13)
+    # the truncated estimates do differ
+    assert O.rel_l2(O.hbp_backward(stA, svA, e, 1), O.hbp_backward(stB, svB, e, 1)) > 1e-4
+
+
+# ---------------------------------------------------------------- P10
+@pytest.mark.parametrize("family", ["mlp", "rnn"])
+def test_exact_gradient_against_torch_autograd(family):
+    """The same stack written with torch fp64 ops and differentiated by torch's
+    autograd: forward states, all state gradients and all parameter gradients."""
+    r = np.random.default_rng(21)
+    N = 4
+    if family == "mlp":
+        st = small_mlp(L=4, d=8, dff=12)
+        xin = None
+        x0 = r.standard_normal((N, st.d))
+    else:
+        st = small_rnn(T=5, H=8, I=6)
+        xin = r.standard_normal((st.L, N, 6))
+        x0 = np.zeros((N, st.d))
+    c = r.standard_normal((st.L + 1, N, st.d))
+    c[0] = 0
+    sv = O.forward(st, x0, xin)
+    G = O.exact_backward(st, sv, c)
+    pg = O.param_grads(st, sv, G, xin)
+
+    t = lambda a: torch.tensor(a, dtype=torch.float64, requires_grad=True)
+    W1, W2, lam = t(st.W1), t(st.W2), torch.tensor(st.lam)
+    U = t(st.U) if st.U is not None else None
+    xs = [t(x0)]
+    for l in range(st.L):
+        x = xs[-1]
+        if st.norm == "rms":
+            y = x / torch.sqrt((x * x).mean(dim=1, keepdim=True) + st.eps)
+        else:
+            y = x
+        if family == "mlp":
+            a = y @ W1[l].T
+            z = torch.nn.functional.gelu(a)       # exact erf form
+            nxt = lam[l] * x + z @ W2[l].T
+        else:
+            a = y @ W1.T + torch.tensor(xin[l]) @ U.T
+            nxt = lam[l] * x + torch.tanh(a) @ W2.T
+        nxt.retain_grad()
+        xs.append(nxt)
+    loss = sum((torch.tensor(c[l]) * xs[l]).sum() for l in range(st.L + 1))
+    loss.backward()
+    for l in range(st.L + 1):
+        np.testing.assert_allclose(sv["x"][l], xs[l].detach().numpy(), rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(G[l], xs[l].grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(pg["dW1"], W1.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(pg["dW2"], W2.grad.numpy(), rtol=1e-10, atol=1e-12)
+    if U is not None:
+        np.testing.assert_allclose(pg["dU"], U.grad.numpy(), rtol=1e-10, atol=1e-12)
+
+
+# ---------------------------------------------------------------- P11
+def test_param_grads_use_the_given_estimate():
+    """Parameter gradients are linear in the state-gradient estimate handed in
+    (sentence after Theorem 2): dtheta(w^k) for k < L differs from the exact one
+    and equals it at k = L."""
+    st = small_mlp(L=4)
+    N = 3
+    sv = O.forward(st, RNG.standard_normal((N, st.d)))
+    e = RNG.standard_normal((N, st.d))
+    G = O.exact_backward(st, sv, e)
+    full = O.param_grads(st, sv, G)
+    at_L = O.param_grads(st, sv, O.hbp_backward(st, sv, e, st.L))
+    np.testing.assert_allclose(at_L["dW1"], full["dW1"], rtol=1e-11, atol=1e-13)
+    w1 = O.hbp_backward(st, sv, e, 1)
+    p1 = O.param_grads(st, sv, w1)
+    p1b = O.param_grads(st, sv, 2.0 * w1)
+    np.testing.assert_allclose(p1b["dW2"], 2.0 * p1["dW2"], rtol=1e-12)
+    # top block sees the exact gradient at any k; lower ones do not at k = 1
+    np.testing.assert_allclose(p1["dW2"][-1], full["dW2"][-1], rtol=1e-11, atol=1e-13)
+    assert O.rel_l2(p1["dW1"][0], full["dW1"][0]) > 1e-4
