@@ -1,0 +1,134 @@
+/* hbp.h -- C ABI of the Highway-BP backward pass for one MI355X (gfx950).
+ *
+ * The library computes, for a residual stack
+ *       x_{l+1} = lambda_l (.) x_l + block_l(x_l),          l = 0 .. L-1
+ *       block_l(x) = W2_l . act( W1_l . norm(x)  [+ U . xin_l] )
+ * (paper, Section "Notations and assumptions": f_i = r_i(x, g_i(x)) with
+ * r(x, z) = lambda (.) x + z, so K_i = diag(lambda) and J_i is the block's
+ * Jacobian), the state-gradient estimates w^k of Theorem 2 by k iterations of
+ *   (i)  v_l = g_{l+1} J_{l+1} for every block at once   ("Parallel computation", step 1)
+ *   (ii) g_l = (e_l + v_l) + lambda_l (.) g_{l+1}, a reverse scan along the
+ *        residual path                                    ("Parallel computation", step 2)
+ * then the parameter gradients dL/dtheta_l = g_{l+1} . d block_l / d theta_l
+ * (sentence after Theorem 2), and exact sequential backpropagation for
+ * comparison.  kind = HBP_MLP: one weight pair per block, states along depth.
+ * kind = HBP_RNN: one weight set shared by all L = T blocks, states along time,
+ * block l maps state l to state l+1 and consumes xin[l].
+ *
+ * Conventions
+ *  - Every pointer in hbp_buffers is DEVICE memory owned by the caller,
+ *    contiguous, 16-byte aligned, row-major with the channel index fastest.
+ *    "S" below is the storage type desc.dtype (fp32, or bf16 rounded to
+ *    nearest-even at every store); all accumulation is fp32; lambda, rinv and
+ *    the parameter gradients are always fp32.
+ *  - The library never allocates or frees device memory and never
+ *    synchronises: kernels are enqueued on `stream` (a hipStream_t passed as
+ *    void*; NULL = the default stream) and the call returns at once.
+ *  - Inputs are read-only.  g, the workspace and the outputs must not alias
+ *    the inputs or each other.
+ *  - Errors are return codes, found before anything is launched: bad enum or
+ *    struct_size, non-positive size, d / d_ff / d_in not a multiple of 8,
+ *    d > 4096 with HBP_NORM_RMS, k < 0, a required pointer that is NULL, a
+ *    workspace smaller than hbp_workspace_size() reports.  A failed launch
+ *    gives HBP_E_DEVICE.  Calls are stateless and re-entrant; two calls that
+ *    share g or the workspace must be ordered by the caller.
+ */
+#ifndef HBP_H
+#define HBP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  HBP_OK = 0,
+  HBP_E_INVALID_ARG = 1,  /* bad enum, size, k or struct_size */
+  HBP_E_UNSUPPORTED = 2,  /* sizes the kernels cannot take (see above) */
+  HBP_E_WORKSPACE = 3,    /* workspace missing or too small */
+  HBP_E_NULL = 4,         /* a required pointer is NULL */
+  HBP_E_DEVICE = 5        /* a HIP call or launch failed */
+} hbp_status;
+
+typedef enum { HBP_F32 = 0, HBP_BF16 = 1 } hbp_dtype;
+typedef enum { HBP_MLP = 0, HBP_RNN = 1 } hbp_kind;
+/* GELU is the exact erf form a*Phi(a); IDENTITY makes blocks linear (tests). */
+typedef enum { HBP_ACT_GELU_ERF = 0, HBP_ACT_TANH = 1, HBP_ACT_IDENTITY = 2 } hbp_act;
+/* RMS: y = x / sqrt(mean_c(x^2) + eps), no gain. */
+typedef enum { HBP_NORM_NONE = 0, HBP_NORM_RMS = 1 } hbp_norm;
+/* ONE: lambda = 1 (buffers.lambda ignored). CHANNEL: fp32 [L, d], shared by all tokens. */
+typedef enum { HBP_LAMBDA_ONE = 0, HBP_LAMBDA_CHANNEL = 1 } hbp_lambda;
+
+typedef struct {
+  uint32_t struct_size;      /* = sizeof(hbp_desc) */
+  int32_t kind;              /* hbp_kind   */
+  int32_t dtype;             /* hbp_dtype  */
+  int32_t act;               /* hbp_act    */
+  int32_t norm;              /* hbp_norm   */
+  int32_t lambda_kind;       /* hbp_lambda */
+  int32_t loss_every_state;  /* 0: e = dL/dx_L only, [N,d]; 1: e = [L+1,N,d], one row block per state */
+  float eps;                 /* RMS norm epsilon */
+  int64_t L;                 /* blocks (RNN: time steps T) */
+  int64_t N;                 /* tokens (RNN: batch rows per step) */
+  int64_t d;                 /* state width (RNN: hidden size) */
+  int64_t d_ff;              /* inner width of a block (RNN: hidden size of the cell) */
+  int64_t d_in;              /* RNN input width; 0 for HBP_MLP */
+} hbp_desc;
+
+typedef struct {
+  uint32_t struct_size;      /* = sizeof(hbp_buffers) */
+  /* parameters (S).  MLP: W1[L,d_ff,d], W2[L,d,d_ff].  RNN: W1 = W_h[d_ff,d],
+   * W2 = W_o[d,d_ff], U[d_ff,d_in]. */
+  const void* W1;
+  const void* W2;
+  const void* U;
+  const float* lambda;       /* [L,d] fp32: row l carries state l+1 to state l */
+  /* forward state: written by hbp_forward, read by the backward calls. */
+  void* x;                   /* S [L+1,N,d]  states x_0..x_L (x[0] is the input) */
+  void* y;                   /* S [L,N,d]    norm(x_l); unused (may be NULL) with HBP_NORM_NONE, where x is read */
+  float* rinv;               /* [L,N]        1/sqrt(mean(x_l^2)+eps); unused with HBP_NORM_NONE */
+  void* z;                   /* S [L,N,d_ff] act(a_l) */
+  void* dphi;                /* S [L,N,d_ff] act'(a_l); unused with TANH (1 - z^2) and IDENTITY (1) */
+  const void* xin;           /* S [L,N,d_in] RNN inputs; NULL for MLP */
+  /* loss gradients and results */
+  const void* e;             /* S [N,d] or [L+1,N,d] (see loss_every_state) */
+  void* g;                   /* S [L+1,N,d]  out: state-gradient estimates, g[L] = e_L */
+  float* dW1;                /* out, fp32, shape of W1 */
+  float* dW2;                /* out, fp32, shape of W2 */
+  float* dU;                 /* out, fp32, shape of U (RNN) */
+  void* workspace;
+  size_t workspace_bytes;
+} hbp_buffers;
+
+/* Bytes of workspace that any of the calls below may need for this problem. */
+hbp_status hbp_workspace_size(const hbp_desc* desc, size_t* bytes);
+
+/* Validates a descriptor (and, when bufs is not NULL, the pointers the backward
+ * calls need) without touching the device. */
+hbp_status hbp_check(const hbp_desc* desc, const hbp_buffers* bufs);
+
+/* Support: runs the stack forward from x[0] and fills x[1..L], y, rinv, z, dphi. */
+hbp_status hbp_forward(const hbp_desc* desc, hbp_buffers* bufs, void* stream);
+
+/* g := w^k, the sum of all gradient paths through at most k block Jacobians
+ * (Theorem 2).  k = 0 gives the residual-path-only estimate; k >= L is exact.
+ * Reads W1, W2, lambda, y (or x), rinv, z, dphi, e; writes g and the workspace. */
+hbp_status hbp_backward(const hbp_desc* desc, int k, hbp_buffers* bufs, void* stream);
+
+/* g := exact gradient by L sequential block steps,
+ * G_l = e_l + lambda_l (.) G_{l+1} + G_{l+1} J_{l+1}. */
+hbp_status hbp_exact_backward(const hbp_desc* desc, hbp_buffers* bufs, void* stream);
+
+/* dW1, dW2 (and dU) from the g currently in bufs.g:
+ * da_l = (g_{l+1} W2_l) (.) act'(a_l); dW2_l = sum_n g_{l+1}[n]^T z_l[n];
+ * dW1_l = sum_n da_l[n]^T y_l[n]; dU = sum da^T xin.  Shared weights sum over l too. */
+hbp_status hbp_param_grads(const hbp_desc* desc, hbp_buffers* bufs, void* stream);
+
+const char* hbp_status_string(hbp_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HBP_H */

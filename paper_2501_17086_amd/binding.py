@@ -1,0 +1,197 @@
+"""ctypes binding of libhbp (include/hbp.h).  Argument marshalling only: every
+step of the path runs in the library's HIP kernels.  torch is used to hold
+device memory and to name the stream.
+
+The library is opened on first use and a missing build raises: there is no
+fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libhbp.so")
+
+HBP_OK = 0
+STATUS_NAMES = {0: "HBP_OK", 1: "HBP_E_INVALID_ARG", 2: "HBP_E_UNSUPPORTED", 3: "HBP_E_WORKSPACE",
+                4: "HBP_E_NULL", 5: "HBP_E_DEVICE"}
+F32, BF16 = 0, 1
+MLP, RNN = 0, 1
+ACT = {"gelu": 0, "tanh": 1, "identity": 2}
+NORM = {"none": 0, "rms": 1}
+LAMBDA_ONE, LAMBDA_CHANNEL = 0, 1
+
+EXPORTS = ("hbp_workspace_size", "hbp_check", "hbp_forward", "hbp_backward", "hbp_exact_backward",
+           "hbp_param_grads", "hbp_status_string")
+
+
+class hbp_desc(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("kind", C.c_int32), ("dtype", C.c_int32), ("act", C.c_int32),
+                ("norm", C.c_int32), ("lambda_kind", C.c_int32), ("loss_every_state", C.c_int32),
+                ("eps", C.c_float), ("L", C.c_int64), ("N", C.c_int64), ("d", C.c_int64), ("d_ff", C.c_int64),
+                ("d_in", C.c_int64)]
+
+
+class hbp_buffers(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32),
+                ("W1", C.c_void_p), ("W2", C.c_void_p), ("U", C.c_void_p), ("lambda_", C.c_void_p),
+                ("x", C.c_void_p), ("y", C.c_void_p), ("rinv", C.c_void_p), ("z", C.c_void_p),
+                ("dphi", C.c_void_p), ("xin", C.c_void_p), ("e", C.c_void_p), ("g", C.c_void_p),
+                ("dW1", C.c_void_p), ("dW2", C.c_void_p), ("dU", C.c_void_p),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+
+
+class HbpError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {STATUS_NAMES.get(status, status)} ({status_string(status)})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is not built; run `python -m paper_2501_17086_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        L.hbp_workspace_size.argtypes = [C.POINTER(hbp_desc), C.POINTER(C.c_size_t)]
+        L.hbp_check.argtypes = [C.POINTER(hbp_desc), C.POINTER(hbp_buffers)]
+        L.hbp_forward.argtypes = [C.POINTER(hbp_desc), C.POINTER(hbp_buffers), C.c_void_p]
+        L.hbp_backward.argtypes = [C.POINTER(hbp_desc), C.c_int, C.POINTER(hbp_buffers), C.c_void_p]
+        L.hbp_exact_backward.argtypes = [C.POINTER(hbp_desc), C.POINTER(hbp_buffers), C.c_void_p]
+        L.hbp_param_grads.argtypes = [C.POINTER(hbp_desc), C.POINTER(hbp_buffers), C.c_void_p]
+        L.hbp_status_string.argtypes = [C.c_int]
+        L.hbp_status_string.restype = C.c_char_p
+        for n in EXPORTS[:-1]:
+            getattr(L, n).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().hbp_status_string(status).decode()
+
+
+def make_desc(kind: str, dtype: str, act: str, norm: str, L: int, N: int, d: int, d_ff: int, d_in: int = 0,
+              lambda_channel: bool = False, loss_every_state: bool = False, eps: float = 1e-6) -> hbp_desc:
+    return hbp_desc(C.sizeof(hbp_desc), RNN if kind == "rnn" else MLP, BF16 if dtype == "bf16" else F32,
+                    ACT[act], NORM[norm], LAMBDA_CHANNEL if lambda_channel else LAMBDA_ONE,
+                    1 if loss_every_state else 0, eps, L, N, d, d_ff, d_in)
+
+
+def workspace_size(desc: hbp_desc) -> int:
+    n = C.c_size_t(0)
+    st = lib().hbp_workspace_size(C.byref(desc), C.byref(n))
+    if st != HBP_OK:
+        raise HbpError(st, "hbp_workspace_size")
+    return n.value
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+@dataclass
+class Problem:
+    """Device tensors of one stack, laid out as include/hbp.h describes."""
+    desc: hbp_desc
+    W1: "object"
+    W2: "object"
+    U: "object" = None
+    lam: "object" = None
+    x: "object" = None
+    y: "object" = None
+    rinv: "object" = None
+    z: "object" = None
+    dphi: "object" = None
+    xin: "object" = None
+    e: "object" = None
+    g: "object" = None
+    dW1: "object" = None
+    dW2: "object" = None
+    dU: "object" = None
+    workspace: "object" = None
+
+    def buffers(self) -> hbp_buffers:
+        ws = self.workspace
+        return hbp_buffers(C.sizeof(hbp_buffers), _ptr(self.W1), _ptr(self.W2), _ptr(self.U), _ptr(self.lam),
+                           _ptr(self.x), _ptr(self.y), _ptr(self.rinv), _ptr(self.z), _ptr(self.dphi),
+                           _ptr(self.xin), _ptr(self.e), _ptr(self.g), _ptr(self.dW1), _ptr(self.dW2),
+                           _ptr(self.dU), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return stream
+
+
+def _call(name: str, st: int) -> None:
+    if st != HBP_OK:
+        raise HbpError(st, name)
+
+
+def hbp_check(p: Problem) -> int:
+    b = p.buffers()
+    return lib().hbp_check(C.byref(p.desc), C.byref(b))
+
+
+def hbp_forward(p: Problem, stream=None) -> None:
+    b = p.buffers()
+    _call("hbp_forward", lib().hbp_forward(C.byref(p.desc), C.byref(b), _stream(stream)))
+
+
+def hbp_backward(p: Problem, k: int, stream=None) -> None:
+    b = p.buffers()
+    _call("hbp_backward", lib().hbp_backward(C.byref(p.desc), int(k), C.byref(b), _stream(stream)))
+
+
+def hbp_exact_backward(p: Problem, stream=None) -> None:
+    b = p.buffers()
+    _call("hbp_exact_backward", lib().hbp_exact_backward(C.byref(p.desc), C.byref(b), _stream(stream)))
+
+
+def hbp_param_grads(p: Problem, stream=None) -> None:
+    b = p.buffers()
+    _call("hbp_param_grads", lib().hbp_param_grads(C.byref(p.desc), C.byref(b), _stream(stream)))
+
+
+def allocate(w, inputs, device="cuda:0", N: Optional[int] = None) -> Problem:
+    """Device tensors for workload `w` (a synth.Workload) from make_inputs()'s
+    arrays: uploads parameters, x[0], xin and e; allocates the saved state,
+    outputs and workspace."""
+    import torch
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    N = inputs["x0"].shape[0] if N is None else N
+    dev = torch.device(device)
+
+    def up(a, dtype=dt):
+        return None if a is None else torch.from_numpy(a).to(dev).to(dtype).contiguous()
+
+    desc = make_desc(w.kind, w.dtype, w.act, w.norm, w.L, N, w.d, w.d_ff, w.d_in,
+                     lambda_channel=inputs["lam"] is not None, loss_every_state=w.loss_every_state, eps=w.eps)
+    L, d, dff = w.L, w.d, w.d_ff
+    x = torch.zeros((L + 1, N, d), dtype=dt, device=dev)
+    x[0] = up(inputs["x0"])
+    rms = w.norm == "rms"
+    p = Problem(
+        desc=desc, W1=up(inputs["W1"]), W2=up(inputs["W2"]), U=up(inputs["U"]),
+        lam=up(inputs["lam"], torch.float32), x=x,
+        y=torch.zeros((L, N, d), dtype=dt, device=dev) if rms else None,
+        rinv=torch.zeros((L, N), dtype=torch.float32, device=dev) if rms else None,
+        z=torch.zeros((L, N, dff), dtype=dt, device=dev),
+        dphi=torch.zeros((L, N, dff), dtype=dt, device=dev) if w.act == "gelu" else None,
+        xin=up(inputs["xin"]), e=up(inputs["e"]),
+        g=torch.zeros((L + 1, N, d), dtype=dt, device=dev),
+        dW1=torch.zeros(inputs["W1"].shape, dtype=torch.float32, device=dev),
+        dW2=torch.zeros(inputs["W2"].shape, dtype=torch.float32, device=dev),
+        dU=None if inputs["U"] is None else torch.zeros(inputs["U"].shape, dtype=torch.float32, device=dev),
+    )
+    p.workspace = torch.zeros(workspace_size(desc), dtype=torch.uint8, device=dev)
+    return p

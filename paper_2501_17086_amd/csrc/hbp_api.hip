@@ -1,0 +1,399 @@
+// C ABI of libhbp (see include/hbp.h): validation, workspace carving and the
+// launch sequences of the forward pass, Highway-BP, exact BP and the parameter
+// gradients.  Everything is enqueued on the caller's stream; nothing here
+// allocates or synchronises.
+#include "../../include/hbp.h"
+#include "hbp_common.h"
+
+using namespace hbp;
+
+namespace {
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline size_t esize(const hbp_desc* d) { return d->dtype == HBP_F32 ? 4 : 2; }
+inline bool shared_w(const hbp_desc* d) { return d->kind == HBP_RNN; }
+
+struct Workspace {
+  size_t off_v, off_da, off_part, total;
+};
+
+// split-K factor for a parameter-gradient GEMM with `tiles` output tiles and a
+// contraction of length K: enough workgroups to fill 256 CUs twice, at least
+// 2048 rows of the contraction each.
+int pick_split(long tiles, long K) {
+  long want = (512 + tiles - 1) / tiles;
+  long cap = K / 2048;
+  if (cap < 1) cap = 1;
+  if (want > cap) want = cap;
+  if (want > 64) want = 64;
+  if (want < 1) want = 1;
+  return (int)want;
+}
+
+long tiles_of(long M, long N) { return ((M + 255) / 256) * ((N + 255) / 256); }
+
+struct Splits { int s_w2, s_w1, s_u; };
+
+Splits param_splits(const hbp_desc* d) {
+  Splits s{1, 1, 1};
+  const long nb = shared_w(d) ? 1 : d->L;
+  const long K = shared_w(d) ? d->L * d->N : d->N;
+  s.s_w2 = pick_split(tiles_of(d->d, d->d_ff) * nb, K);
+  s.s_w1 = s.s_w2;
+  if (d->kind == HBP_RNN) s.s_u = pick_split(tiles_of(d->d_ff, d->d_in), K);
+  return s;
+}
+
+Workspace carve(const hbp_desc* d) {
+  Workspace w{};
+  const size_t es = esize(d);
+  size_t o = 0;
+  w.off_v = o;  o = align_up(o + (size_t)d->L * d->N * d->d * es, 256);
+  // da [L,N,d_ff] in the storage type; the RNN forward also keeps U.xin here as fp32
+  size_t da_bytes = (size_t)d->L * d->N * d->d_ff * (d->kind == HBP_RNN ? 4 : es);
+  w.off_da = o; o = align_up(o + da_bytes, 256);
+  Splits sp = param_splits(d);
+  const size_t nb = shared_w(d) ? 1 : (size_t)d->L;
+  size_t part = 0;
+  if (sp.s_w2 > 1) part = (size_t)sp.s_w2 * nb * d->d * d->d_ff * 4;
+  if (sp.s_u > 1) {
+    size_t pu = (size_t)sp.s_u * d->d_ff * d->d_in * 4;
+    if (pu > part) part = pu;
+  }
+  w.off_part = o; o = align_up(o + part, 256);
+  w.total = o;
+  return w;
+}
+
+hbp_status check_desc(const hbp_desc* d) {
+  if (!d) return HBP_E_NULL;
+  if (d->struct_size != sizeof(hbp_desc)) return HBP_E_INVALID_ARG;
+  if (d->kind != HBP_MLP && d->kind != HBP_RNN) return HBP_E_INVALID_ARG;
+  if (d->dtype != HBP_F32 && d->dtype != HBP_BF16) return HBP_E_INVALID_ARG;
+  if (d->act < HBP_ACT_GELU_ERF || d->act > HBP_ACT_IDENTITY) return HBP_E_INVALID_ARG;
+  if (d->norm != HBP_NORM_NONE && d->norm != HBP_NORM_RMS) return HBP_E_INVALID_ARG;
+  if (d->lambda_kind != HBP_LAMBDA_ONE && d->lambda_kind != HBP_LAMBDA_CHANNEL) return HBP_E_INVALID_ARG;
+  if (d->loss_every_state != 0 && d->loss_every_state != 1) return HBP_E_INVALID_ARG;
+  if (d->L <= 0 || d->N <= 0 || d->d <= 0 || d->d_ff <= 0 || d->d_in < 0) return HBP_E_INVALID_ARG;
+  if (d->kind == HBP_RNN && d->d_in <= 0) return HBP_E_INVALID_ARG;
+  if (d->kind == HBP_MLP && d->d_in != 0) return HBP_E_INVALID_ARG;
+  if (d->norm == HBP_NORM_RMS && !(d->eps >= 0.f)) return HBP_E_INVALID_ARG;
+  if (d->d % 8 || d->d_ff % 8 || d->d_in % 8) return HBP_E_UNSUPPORTED;
+  if (d->norm == HBP_NORM_RMS && d->d > 4096) return HBP_E_UNSUPPORTED;
+  if (d->L > (1 << 20) || d->N > (1L << 24) || d->d > (1 << 20) || d->d_ff > (1 << 20)) return HBP_E_UNSUPPORTED;
+  return HBP_OK;
+}
+
+enum Need { NEED_FWD = 1, NEED_BWD = 2, NEED_PG = 4 };
+
+hbp_status check_bufs(const hbp_desc* d, const hbp_buffers* b, int need) {
+  if (!b) return HBP_E_NULL;
+  if (b->struct_size != sizeof(hbp_buffers)) return HBP_E_INVALID_ARG;
+  if (!b->W1 || !b->W2) return HBP_E_NULL;
+  if (d->kind == HBP_RNN && (need & (NEED_FWD | NEED_PG)) && (!b->U || !b->xin)) return HBP_E_NULL;
+  if (d->lambda_kind == HBP_LAMBDA_CHANNEL && !b->lambda) return HBP_E_NULL;
+  if (d->norm == HBP_NORM_RMS && (!b->y || !b->rinv)) return HBP_E_NULL;
+  if (d->norm == HBP_NORM_NONE && !b->x) return HBP_E_NULL;
+  if ((need & NEED_FWD) && !b->x) return HBP_E_NULL;
+  if (!b->z) return HBP_E_NULL;
+  if (d->act == HBP_ACT_GELU_ERF && !b->dphi) return HBP_E_NULL;
+  if (need & (NEED_BWD | NEED_PG)) {
+    if (!b->g) return HBP_E_NULL;
+  }
+  if ((need & NEED_BWD) && !b->e) return HBP_E_NULL;
+  if (need & NEED_PG) {
+    if (!b->dW1 || !b->dW2) return HBP_E_NULL;
+    if (d->kind == HBP_RNN && !b->dU) return HBP_E_NULL;
+  }
+  Workspace w = carve(d);
+  if (!b->workspace || b->workspace_bytes < w.total) return HBP_E_WORKSPACE;
+  return HBP_OK;
+}
+
+#define HBP_TRY(expr)                          \
+  do {                                         \
+    hipError_t _e = (expr);                    \
+    if (_e != hipSuccess) return HBP_E_DEVICE; \
+  } while (0)
+
+hbp_status run_gemm(const hbp_desc* d, const GemmArgs& ga, hipStream_t s) {
+  hipError_t err = hipSuccess;
+  if (d->dtype == HBP_BF16 && launch_gemm_mfma(ga, s, &err)) {
+    return err == hipSuccess ? HBP_OK : HBP_E_DEVICE;
+  }
+  HBP_TRY(launch_gemm_generic(d->dtype, ga, s));
+  return HBP_OK;
+}
+
+#define HBP_RUN(expr)                \
+  do {                               \
+    hbp_status _s = (expr);          \
+    if (_s != HBP_OK) return _s;     \
+  } while (0)
+
+inline char* at(void* p, size_t bytes) { return reinterpret_cast<char*>(p) + bytes; }
+inline const char* at(const void* p, size_t bytes) { return reinterpret_cast<const char*>(p) + bytes; }
+
+// da[l] = (g[l+1] . W2_l) (.) act'(a_l) for blocks l_lo..l_hi-1
+hbp_status vjp_stage1(const hbp_desc* d, const hbp_buffers* b, const Workspace& w, long l_lo, long l_hi,
+                      hipStream_t s) {
+  const size_t es = esize(d);
+  const long nl = l_hi - l_lo;
+  GemmArgs ga{};
+  const bool sh = shared_w(d);
+  ga.A = at(b->g, (size_t)(l_lo + 1) * d->N * d->d * es);
+  ga.B = sh ? b->W2 : at(b->W2, (size_t)l_lo * d->d * d->d_ff * es);
+  ga.C = at(b->workspace, w.off_da + (size_t)l_lo * d->N * d->d_ff * es);
+  ga.M = sh ? nl * d->N : d->N;
+  ga.N = d->d_ff;
+  ga.K = d->d;
+  ga.a_sm = d->d; ga.a_sk = 1;
+  ga.b_sk = d->d_ff; ga.b_sn = 1;
+  ga.ldc = d->d_ff;
+  ga.batch = sh ? 1 : nl;
+  ga.a_sb = d->N * d->d; ga.b_sb = d->d * d->d_ff; ga.c_sb = d->N * d->d_ff;
+  ga.split_k = 1;
+  if (d->act == HBP_ACT_GELU_ERF) {
+    ga.mode = EPI_MUL_AUX;
+    ga.aux = at(b->dphi, (size_t)l_lo * d->N * d->d_ff * es);
+  } else if (d->act == HBP_ACT_TANH) {
+    ga.mode = EPI_MUL_1MZ2;
+    ga.aux = at(b->z, (size_t)l_lo * d->N * d->d_ff * es);
+  } else {
+    ga.mode = EPI_STORE;
+  }
+  ga.aux_sb = d->N * d->d_ff;
+  return run_gemm(d, ga, s);
+}
+
+// dn[l] = da[l] . W1_l  (into the v buffer)
+hbp_status vjp_stage2(const hbp_desc* d, const hbp_buffers* b, const Workspace& w, long l_lo, long l_hi,
+                      hipStream_t s) {
+  const size_t es = esize(d);
+  const long nl = l_hi - l_lo;
+  const bool sh = shared_w(d);
+  GemmArgs ga{};
+  ga.A = at(b->workspace, w.off_da + (size_t)l_lo * d->N * d->d_ff * es);
+  ga.B = sh ? b->W1 : at(b->W1, (size_t)l_lo * d->d * d->d_ff * es);
+  ga.C = at(b->workspace, w.off_v + (size_t)l_lo * d->N * d->d * es);
+  ga.M = sh ? nl * d->N : d->N;
+  ga.N = d->d;
+  ga.K = d->d_ff;
+  ga.a_sm = d->d_ff; ga.a_sk = 1;
+  ga.b_sk = d->d; ga.b_sn = 1;
+  ga.ldc = d->d;
+  ga.batch = sh ? 1 : nl;
+  ga.a_sb = d->N * d->d_ff; ga.b_sb = d->d * d->d_ff; ga.c_sb = d->N * d->d;
+  ga.split_k = 1;
+  ga.mode = EPI_STORE;
+  return run_gemm(d, ga, s);
+}
+
+hbp_status scan_stage(const hbp_desc* d, const hbp_buffers* b, const Workspace& w, long l_lo, long l_hi,
+                      bool has_v, hipStream_t s) {
+  ScanArgs sa{};
+  sa.g = b->g;
+  sa.dn = has_v ? at(b->workspace, w.off_v) : nullptr;
+  sa.y = b->y;
+  sa.rinv = b->rinv;
+  sa.e = d->loss_every_state ? b->e : nullptr;
+  sa.lambda = d->lambda_kind == HBP_LAMBDA_CHANNEL ? b->lambda : nullptr;
+  sa.N = d->N; sa.d = d->d;
+  sa.l_lo = l_lo; sa.l_hi = l_hi;
+  sa.norm_rms = d->norm == HBP_NORM_RMS;
+  HBP_TRY(launch_scan(d->dtype, sa, s));
+  return HBP_OK;
+}
+
+// g[L] := e_L
+hbp_status seed_top(const hbp_desc* d, const hbp_buffers* b, hipStream_t s) {
+  const size_t es = esize(d);
+  const size_t row = (size_t)d->N * d->d * es;
+  const void* src = d->loss_every_state ? at(b->e, (size_t)d->L * row) : b->e;
+  HBP_TRY(hipMemcpyAsync(at(b->g, (size_t)d->L * row), src, row, hipMemcpyDeviceToDevice, s));
+  return HBP_OK;
+}
+
+// C[b] (fp32 [M,N]) = sum over `K` rows of A[b](k,m) * B[b](k,n), rows K-major
+hbp_status tn_gemm(const hbp_desc* d, const void* A, long lda, long a_sb, const void* B, long ldb, long b_sb,
+                   float* C, long M, long N, long K, long batch, int split, void* part, hipStream_t s) {
+  GemmArgs ga{};
+  ga.A = A; ga.B = B;
+  ga.M = M; ga.N = N; ga.K = K;
+  ga.a_sm = 1; ga.a_sk = lda;
+  ga.b_sk = ldb; ga.b_sn = 1;
+  ga.ldc = N;
+  ga.batch = batch;
+  ga.a_sb = a_sb; ga.b_sb = b_sb; ga.c_sb = M * N;
+  ga.split_k = split;
+  ga.mode = EPI_STORE;
+  ga.c_is_f32 = 1;
+  ga.C = split > 1 ? part : (void*)C;
+  HBP_RUN(run_gemm(d, ga, s));
+  if (split > 1) HBP_TRY(launch_splitk_reduce((const float*)part, C, batch * M * N, split, s));
+  return HBP_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* hbp_status_string(hbp_status s) {
+  switch (s) {
+    case HBP_OK: return "ok";
+    case HBP_E_INVALID_ARG: return "invalid argument";
+    case HBP_E_UNSUPPORTED: return "unsupported size";
+    case HBP_E_WORKSPACE: return "workspace missing or too small";
+    case HBP_E_NULL: return "required pointer is NULL";
+    case HBP_E_DEVICE: return "HIP launch failed";
+  }
+  return "unknown status";
+}
+
+hbp_status hbp_workspace_size(const hbp_desc* desc, size_t* bytes) {
+  if (!bytes) return HBP_E_NULL;
+  HBP_RUN(check_desc(desc));
+  *bytes = carve(desc).total;
+  return HBP_OK;
+}
+
+hbp_status hbp_check(const hbp_desc* desc, const hbp_buffers* bufs) {
+  HBP_RUN(check_desc(desc));
+  if (bufs) HBP_RUN(check_bufs(desc, bufs, NEED_BWD));
+  return HBP_OK;
+}
+
+hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
+  HBP_RUN(check_desc(d));
+  HBP_RUN(check_bufs(d, b, NEED_FWD));
+  hipStream_t s = (hipStream_t)stream;
+  const Workspace w = carve(d);
+  const size_t es = esize(d);
+  const bool sh = shared_w(d);
+  const bool rms = d->norm == HBP_NORM_RMS;
+  float* ux = reinterpret_cast<float*>(at(b->workspace, w.off_da));
+  if (d->kind == HBP_RNN) {  // U . xin for every step at once
+    GemmArgs ga{};
+    ga.A = b->xin; ga.B = b->U; ga.C = ux;
+    ga.M = d->L * d->N; ga.N = d->d_ff; ga.K = d->d_in;
+    ga.a_sm = d->d_in; ga.a_sk = 1;
+    ga.b_sk = 1; ga.b_sn = d->d_in;
+    ga.ldc = d->d_ff; ga.batch = 1; ga.split_k = 1;
+    ga.mode = EPI_STORE; ga.c_is_f32 = 1;
+    HBP_RUN(run_gemm(d, ga, s));
+  }
+  for (long l = 0; l < d->L; ++l) {
+    const size_t xo = (size_t)l * d->N * d->d * es;
+    const size_t fo = (size_t)l * d->N * d->d_ff * es;
+    const void* yl = at((const void*)b->x, xo);
+    if (rms) {
+      HBP_TRY(launch_rmsnorm_fwd(d->dtype, at((const void*)b->x, xo), at(b->y, xo), b->rinv + l * d->N, d->N, d->d,
+                                 d->eps, s));
+      yl = at((const void*)b->y, xo);
+    }
+    {  // a = y W1^T (+ U xin); z = act(a); dphi = act'(a)
+      GemmArgs ga{};
+      ga.A = yl;
+      ga.B = sh ? b->W1 : at(b->W1, (size_t)l * d->d * d->d_ff * es);
+      ga.C = at(b->z, fo);
+      ga.M = d->N; ga.N = d->d_ff; ga.K = d->d;
+      ga.a_sm = d->d; ga.a_sk = 1;
+      ga.b_sk = 1; ga.b_sn = d->d;
+      ga.ldc = d->d_ff; ga.batch = 1; ga.split_k = 1;
+      if (d->act == HBP_ACT_GELU_ERF) { ga.mode = EPI_ACT_GELU; ga.out2 = at(b->dphi, fo); }
+      else if (d->act == HBP_ACT_TANH) ga.mode = EPI_ACT_TANH;
+      else ga.mode = EPI_STORE;
+      if (d->kind == HBP_RNN) ga.addf = ux + l * d->N * d->d_ff;
+      HBP_RUN(run_gemm(d, ga, s));
+    }
+    {  // x_{l+1} = lambda (.) x_l + z W2^T
+      GemmArgs ga{};
+      ga.A = at((const void*)b->z, fo);
+      ga.B = sh ? b->W2 : at(b->W2, (size_t)l * d->d * d->d_ff * es);
+      ga.C = at(b->x, xo + (size_t)d->N * d->d * es);
+      ga.M = d->N; ga.N = d->d; ga.K = d->d_ff;
+      ga.a_sm = d->d_ff; ga.a_sk = 1;
+      ga.b_sk = 1; ga.b_sn = d->d_ff;
+      ga.ldc = d->d; ga.batch = 1; ga.split_k = 1;
+      ga.mode = EPI_RESID;
+      ga.aux = at((const void*)b->x, xo);
+      ga.lambda = d->lambda_kind == HBP_LAMBDA_CHANNEL ? b->lambda + l * d->d : nullptr;
+      HBP_RUN(run_gemm(d, ga, s));
+    }
+  }
+  return HBP_OK;
+}
+
+hbp_status hbp_backward(const hbp_desc* d, int k, hbp_buffers* b, void* stream) {
+  HBP_RUN(check_desc(d));
+  if (k < 0) return HBP_E_INVALID_ARG;
+  HBP_RUN(check_bufs(d, b, NEED_BWD));
+  hipStream_t s = (hipStream_t)stream;
+  const Workspace w = carve(d);
+  // y aliases x when there is no norm
+  hbp_buffers bb = *b;
+  if (d->norm == HBP_NORM_NONE) bb.y = bb.x;
+  HBP_RUN(seed_top(d, &bb, s));
+  // w^0: the residual path alone
+  HBP_RUN(scan_stage(d, &bb, w, 0, d->L, false, s));
+  // More than L iterations change nothing (Theorem 2: exact for k >= L - i).
+  const long iters = k > d->L ? d->L : k;
+  for (long it = 1; it <= iters; ++it) {
+    // After it-2 iterations the states l+1 >= L-it+2 are already exact (and
+    // bit-identical from then on), so v_l of blocks l >= L-it+1 left by the
+    // previous iteration is still valid: recompute only the blocks below.
+    const long l_hi = d->L - it + 1;
+    HBP_RUN(vjp_stage1(d, &bb, w, 0, l_hi, s));
+    HBP_RUN(vjp_stage2(d, &bb, w, 0, l_hi, s));
+    HBP_RUN(scan_stage(d, &bb, w, 0, d->L, true, s));
+  }
+  return HBP_OK;
+}
+
+hbp_status hbp_exact_backward(const hbp_desc* d, hbp_buffers* b, void* stream) {
+  HBP_RUN(check_desc(d));
+  HBP_RUN(check_bufs(d, b, NEED_BWD));
+  hipStream_t s = (hipStream_t)stream;
+  const Workspace w = carve(d);
+  hbp_buffers bb = *b;
+  if (d->norm == HBP_NORM_NONE) bb.y = bb.x;
+  HBP_RUN(seed_top(d, &bb, s));
+  for (long l = d->L - 1; l >= 0; --l) {
+    HBP_RUN(vjp_stage1(d, &bb, w, l, l + 1, s));
+    HBP_RUN(vjp_stage2(d, &bb, w, l, l + 1, s));
+    HBP_RUN(scan_stage(d, &bb, w, l, l + 1, true, s));
+  }
+  return HBP_OK;
+}
+
+hbp_status hbp_param_grads(const hbp_desc* d, hbp_buffers* b, void* stream) {
+  HBP_RUN(check_desc(d));
+  HBP_RUN(check_bufs(d, b, NEED_PG));
+  hipStream_t s = (hipStream_t)stream;
+  const Workspace w = carve(d);
+  const size_t es = esize(d);
+  const bool sh = shared_w(d);
+  hbp_buffers bb = *b;
+  if (d->norm == HBP_NORM_NONE) bb.y = bb.x;
+  const Splits sp = param_splits(d);
+  // da from the final estimate
+  HBP_RUN(vjp_stage1(d, &bb, w, 0, d->L, s));
+  const long K = sh ? d->L * d->N : d->N;
+  const long nb = sh ? 1 : d->L;
+  void* part = at(b->workspace, w.off_part);
+  const void* g1 = at((const void*)bb.g, (size_t)d->N * d->d * es);
+  const void* da = at((const void*)b->workspace, w.off_da);
+  // dW2[c,j] = sum_n g_{l+1}[n,c] z_l[n,j]
+  HBP_RUN(tn_gemm(d, g1, d->d, d->N * d->d, bb.z, d->d_ff, d->N * d->d_ff, bb.dW2, d->d, d->d_ff, K, nb, sp.s_w2,
+                  part, s));
+  // dW1[j,c] = sum_n da_l[n,j] y_l[n,c]
+  HBP_RUN(tn_gemm(d, da, d->d_ff, d->N * d->d_ff, bb.y, d->d, d->N * d->d, bb.dW1, d->d_ff, d->d, K, nb, sp.s_w1,
+                  part, s));
+  if (d->kind == HBP_RNN) {
+    // dU[j,i] = sum da[n,j] xin[n,i]
+    HBP_RUN(tn_gemm(d, da, d->d_ff, 0, bb.xin, d->d_in, 0, bb.dU, d->d_ff, d->d_in, K, 1, sp.s_u, part, s));
+  }
+  return HBP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,119 @@
+// Shared device helpers and the internal launcher interface of libhbp.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hbp {
+
+typedef unsigned short bf16_t;  // raw bf16 bits
+
+__device__ __forceinline__ float bf16_to_f32(bf16_t h) {
+  return __uint_as_float(((unsigned int)h) << 16);
+}
+// round to nearest, ties to even (inputs here are finite)
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+  unsigned int u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static __device__ __forceinline__ float load(const float* p) { return *p; }
+  static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<bf16_t> {
+  static __device__ __forceinline__ float load(const bf16_t* p) { return bf16_to_f32(*p); }
+  static __device__ __forceinline__ void store(bf16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+// 8 consecutive elements <-> 8 floats (16-byte accesses for bf16, 2 x 16 for fp32)
+__device__ __forceinline__ void load8(const bf16_t* p, float (&o)[8]) {
+  uint4 r = *reinterpret_cast<const uint4*>(p);
+  unsigned int w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    o[2 * i] = __uint_as_float(w[i] << 16);
+    o[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+  }
+}
+__device__ __forceinline__ void load8(const float* p, float (&o)[8]) {
+  float4 a = *reinterpret_cast<const float4*>(p);
+  float4 b = *reinterpret_cast<const float4*>(p + 4);
+  o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+  o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+}
+__device__ __forceinline__ void store8(bf16_t* p, const float (&v)[8]) {
+  unsigned int w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+    w[i] = (unsigned int)f32_to_bf16(v[2 * i]) | ((unsigned int)f32_to_bf16(v[2 * i + 1]) << 16);
+  *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+}
+__device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+
+// ---------------------------------------------------------------------------
+// GEMM:  C[b][m,n] = epilogue( sum_k A[b](m,k) * B[b](k,n) )
+// ---------------------------------------------------------------------------
+enum EpiMode {
+  EPI_STORE = 0,       // C = acc
+  EPI_MUL_AUX = 1,     // C = acc * aux[m,n]                    (da = dz * act'(a))
+  EPI_MUL_1MZ2 = 2,    // C = acc * (1 - aux[m,n]^2)            (tanh: aux = z)
+  EPI_ACT_GELU = 3,    // C = gelu(acc); out2 = gelu'(acc)
+  EPI_ACT_TANH = 4,    // C = tanh(acc)
+  EPI_RESID = 5,       // C = lambda[n] * aux[m,n] + acc        (x_{l+1})
+  EPI_ADD_AUX = 6      // C = acc + aux[m,n]
+};
+
+struct GemmArgs {
+  const void* A; const void* B; void* C;
+  long M, N, K;
+  long a_sm, a_sk;      // element strides of A(m,k)
+  long b_sk, b_sn;      // element strides of B(k,n)
+  long ldc;             // row stride of C, aux, out2, addf
+  long batch;           // grid.z
+  long a_sb, b_sb, c_sb;  // batch strides (elements)
+  int split_k;          // >1: C is fp32 partials [split][batch][M,N] (EPI_STORE only)
+  int mode;
+  const void* aux; long aux_sb;       // storage type
+  void* out2; long out2_sb;           // storage type
+  const float* addf; long addf_sb;    // fp32 [M,N], added to acc before the epilogue
+  const float* lambda; long lambda_sb;  // fp32 [N]
+  int c_is_f32;         // C stored as fp32 regardless of the storage type
+};
+
+// storage type: 0 = fp32, 1 = bf16
+hipError_t launch_gemm_generic(int dtype, const GemmArgs& g, hipStream_t s);
+// fast bf16 MFMA path; returns false when the shape/layout is not covered
+bool launch_gemm_mfma(const GemmArgs& g, hipStream_t s, hipError_t* err);
+
+// out[i] = sum_s part[s][i], i < n
+hipError_t launch_splitk_reduce(const float* part, float* out, long n, int split, hipStream_t s);
+
+// ---------------------------------------------------------------------------
+// residual-path scan:  for l = l_hi-1 .. l_lo:
+//   v_l = has_v ? (norm ? rmsnorm_bwd(dn_l; y_l, rinv_l) : dn_l) : 0
+//   g_l = (e_l) + v_l + lambda_l (.) g_{l+1}
+// g[l_hi] must already hold the incoming state gradient.
+// ---------------------------------------------------------------------------
+struct ScanArgs {
+  void* g;              // [L+1,N,d] storage
+  const void* dn;       // [L,N,d] storage (block input gradient before the norm's backward), or NULL
+  const void* y;        // [L,N,d] storage (RMS only)
+  const float* rinv;    // [L,N]   (RMS only)
+  const void* e;        // [L+1,N,d] storage or NULL
+  const float* lambda;  // [L,d] or NULL
+  long N, d;
+  long l_lo, l_hi;
+  int norm_rms;
+};
+hipError_t launch_scan(int dtype, const ScanArgs& a, hipStream_t s);
+
+// y = x * rinv, rinv = 1/sqrt(mean(x^2)+eps) for `rows` rows of width d
+hipError_t launch_rmsnorm_fwd(int dtype, const void* x, void* y, float* rinv, long rows, long d, float eps,
+                              hipStream_t s);
+
+}  // namespace hbp

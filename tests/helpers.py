@@ -1,0 +1,53 @@
+"""Glue shared by the GPU parity tests: builds the oracle's Stack and the GPU
+Problem from the same seeded inputs and compares results.  Holds no arithmetic
+of the method itself."""
+from __future__ import annotations
+
+import numpy as np
+
+from oracle import hbp_oracle as O
+from paper_2501_17086_amd import synth
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}   # relative L2, GPU vs oracle
+
+
+def oracle_stack(w: synth.Workload, inp) -> O.Stack:
+    return O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], U=inp["U"], eps=w.eps, L=w.L)
+
+
+def to_np(t) -> np.ndarray:
+    return t.detach().float().cpu().numpy().astype(np.float64)
+
+
+def oracle_saved_rounded(w: synth.Workload, sv):
+    """The oracle's forward state rounded to the storage type, as float64
+    arrays: the values a backward call reads from memory."""
+    r = lambda a: synth.storage_round(w, a.astype(np.float32)).astype(np.float64)
+    out = dict(sv)
+    for k in ("x", "y", "z", "dphi"):
+        out[k] = r(sv[k])
+    out["rinv"] = sv["rinv"].astype(np.float32).astype(np.float64)
+    if w.act == "tanh":        # the GPU derives act' from the stored z
+        out["dphi"] = 1.0 - out["z"] ** 2
+    if w.norm == "none":
+        out["y"] = out["x"][:-1]
+    return out
+
+
+def upload_saved(p, w: synth.Workload, sv_r):
+    """Writes a (rounded) forward state into the Problem's device tensors."""
+    import torch
+    dev = p.x.device
+
+    def put(dst, a):
+        if dst is not None:
+            dst.copy_(torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev).to(dst.dtype))
+    put(p.x, sv_r["x"])
+    put(p.y, sv_r["y"])
+    put(p.rinv, sv_r["rinv"])
+    put(p.z, sv_r["z"])
+    put(p.dphi, sv_r["dphi"])
+
+
+def rel(a, b) -> float:
+    return O.rel_l2(a, b)

@@ -1,0 +1,99 @@
+"""CPU-only checks of the C ABI: the library loads, exports every function
+include/hbp.h declares, and rejects bad descriptors before touching a device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2501_17086_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "hbp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(hbp_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    lib = B.lib()
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_struct_layout_matches_header():
+    # field order and sizes as in the header (LP64)
+    assert C.sizeof(B.hbp_desc) == 4 * 8 + 8 * 5
+    assert C.sizeof(B.hbp_buffers) == 8 + 8 * 15 + 8 + 8
+
+
+def _desc(**kw):
+    base = dict(kind="mlp", dtype="bf16", act="gelu", norm="rms", L=4, N=16, d=64, d_ff=128)
+    base.update(kw)
+    return B.make_desc(**base)
+
+
+def test_status_strings():
+    for s in range(6):
+        assert len(B.status_string(s)) > 0
+
+
+def test_workspace_size_scales():
+    a = B.workspace_size(_desc())
+    b = B.workspace_size(_desc(N=32))
+    assert a > 0 and b > a
+    # v [L,N,d] + da [L,N,d_ff] in bf16 at least
+    assert a >= 4 * 16 * (64 + 128) * 2
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("L", 0, 1), ("N", -1, 1), ("d", 0, 1), ("d", 60, 2), ("d_ff", 100, 2), ("kind", 7, 1), ("dtype", 3, 1),
+    ("act", 5, 1), ("norm", 2, 1), ("lambda_kind", 9, 1), ("loss_every_state", 2, 1), ("struct_size", 12, 1),
+    ("d_in", 8, 1),
+])
+def test_bad_descriptor_is_rejected(field, value, status):
+    d = _desc()
+    setattr(d, field, value)
+    n = C.c_size_t(0)
+    assert B.lib().hbp_workspace_size(C.byref(d), C.byref(n)) == status
+
+
+def test_rms_width_limit_and_rnn_needs_input_width():
+    n = C.c_size_t(0)
+    d = _desc(d=8192)
+    assert B.lib().hbp_workspace_size(C.byref(d), C.byref(n)) == 2
+    d = _desc(kind="rnn", act="tanh", norm="none", d_in=0)
+    assert B.lib().hbp_workspace_size(C.byref(d), C.byref(n)) == 1
+
+
+def test_null_pointers_and_workspace_are_checked_before_launch():
+    d = _desc()
+    bufs = B.hbp_buffers(C.sizeof(B.hbp_buffers))
+    lib = B.lib()
+    assert lib.hbp_check(C.byref(d), None) == 0
+    assert lib.hbp_check(C.byref(d), C.byref(bufs)) == 4          # W1 NULL
+    # fake non-null addresses: validation never dereferences them
+    for f in ("W1", "W2", "x", "y", "rinv", "z", "dphi", "e", "g"):
+        setattr(bufs, f, 0x1000)
+    assert lib.hbp_check(C.byref(d), C.byref(bufs)) == 3          # no workspace
+    bufs.workspace = 0x1000
+    bufs.workspace_bytes = B.workspace_size(d) - 1
+    assert lib.hbp_backward(C.byref(d), 1, C.byref(bufs), None) == 3
+    bufs.workspace_bytes = B.workspace_size(d)
+    assert lib.hbp_check(C.byref(d), C.byref(bufs)) == 0
+    assert lib.hbp_backward(C.byref(d), -2, C.byref(bufs), None) == 1
+    assert lib.hbp_param_grads(C.byref(d), C.byref(bufs), None) == 4   # dW1 NULL
+    d2 = _desc(lambda_channel=True)
+    assert lib.hbp_check(C.byref(d2), C.byref(bufs)) == 4         # lambda NULL
+    assert lib.hbp_workspace_size(None, None) == 4
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libhbp.so")
+    with pytest.raises(RuntimeError):
+        B.lib()

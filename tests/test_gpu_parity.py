@@ -1,0 +1,189 @@
+"""GPU parity: the HIP library (through its C ABI) against the fp64 CPU oracle,
+element by element on the same seeded inputs.  Bars: relative L2 of 1e-5 for
+fp32 storage, 2e-2 for bf16 storage.
+
+Two set-ups.  "end to end": each side runs its own forward from x_0.  "shared
+state": the oracle's forward state, rounded to the storage type, is what both
+backward passes read -- the backward calls' own inputs are then identical,
+which is the only meaningful comparison for the chaotic RNN (trajectories of
+two forwards in different precisions separate after a few hundred steps).
+"""
+import numpy as np
+import pytest
+
+from oracle import hbp_oracle as O
+from paper_2501_17086_amd import synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need a GPU (run with -m gpu on an MI355X box)")
+    from paper_2501_17086_amd import binding
+    binding.lib()
+    return binding
+
+
+W = synth.WORKLOADS
+CASES = {
+    # the small fp32 stack at its full size
+    "mlp_small_f32": W["mlp_small_f32"],
+    # fp32, ragged in every dimension the kernels tile
+    "mlp_f32_ragged": synth.scaled(W["mlp_small_f32"], name="mlp_f32_ragged", L=5, N=203, d=72, d_ff=136,
+                                   norm="rms", lam="uniform", lam_lo=0.9, lam_hi=1.0, ks=(0, 1, 3, 5)),
+    # reduced copies of the bf16 stacks: several tiles and a ragged tail
+    "resnet_like_small": synth.scaled(W["resnet_like"], name="resnet_like_small", L=6, N=333, d=512, d_ff=2048,
+                                      w2_scale=1 / np.sqrt(6.0), ks=(0, 1, 2, 4, 6)),
+    "resnet_like_odd": synth.scaled(W["resnet_like"], name="resnet_like_odd", L=4, N=130, d=264, d_ff=520,
+                                    w2_scale=0.5, ks=(1, 3)),
+    "transformer_small": synth.scaled(W["transformer_mlp"], name="transformer_small", L=5, N=257, d=1024,
+                                      d_ff=1024, w2_scale=1 / np.sqrt(10.0), ks=(1, 2)),
+    "deep_small": synth.scaled(W["deep_large"], name="deep_small", L=4, N=192, d=2048, d_ff=512,
+                               w2_scale=1 / np.sqrt(8.0), ks=(1, 3)),
+    "rnn_small": synth.scaled(W["gated_rnn_contractive"], name="rnn_small", L=37, N=5, d=256, d_ff=256,
+                              d_in=128, ks=(0, 1, 2, 4)),
+    "rnn_f32": synth.scaled(W["gated_rnn_contractive"], name="rnn_f32", dtype="f32", L=19, N=3, d=64, d_ff=64,
+                            d_in=40, ks=(0, 2, 19)),
+    "rnn_chaotic_small": synth.scaled(W["gated_rnn"], name="rnn_chaotic_small", L=130, N=4, d=512, d_ff=512,
+                                      d_in=256, ks=(1, 2, 4)),
+}
+
+
+def _setup(B, w):
+    inp = synth.make_inputs(w)
+    st = H.oracle_stack(w, inp)
+    sv = O.forward(st, inp["x0"], inp["xin"])
+    p = B.allocate(w, inp)
+    return inp, st, sv, p
+
+
+@pytest.mark.parametrize("name", ["mlp_small_f32", "mlp_f32_ragged", "resnet_like_small", "resnet_like_odd",
+                                  "transformer_small", "deep_small", "rnn_small", "rnn_f32"])
+def test_forward_parity(B, name):
+    w = CASES[name]
+    inp, st, sv, p = _setup(B, w)
+    B.hbp_forward(p)
+    torch.cuda.synchronize()
+    tol = H.TOL[w.dtype]
+    assert H.rel(H.to_np(p.x), sv["x"]) < tol
+    assert H.rel(H.to_np(p.z), sv["z"]) < tol
+    if p.dphi is not None:
+        assert H.rel(H.to_np(p.dphi), sv["dphi"]) < tol
+    if p.y is not None:
+        assert H.rel(H.to_np(p.y), sv["y"]) < tol
+        assert H.rel(H.to_np(p.rinv), sv["rinv"]) < tol
+
+
+def _check_backward(B, w, p, st, sv_oracle, inp, tag):
+    tol = H.TOL[w.dtype]
+    xin = inp["xin"]
+    worst = 0.0
+    for k in w.ks:
+        B.hbp_backward(p, k)
+        B.hbp_param_grads(p)
+        torch.cuda.synchronize()
+        want = O.hbp_backward(st, sv_oracle, inp["e"], k)
+        err = H.rel(H.to_np(p.g), want)
+        assert err < tol, f"{tag} k={k}: g rel L2 {err:.3e}"
+        # per-state check as well: an error confined to one state must not hide
+        for l in range(w.L + 1):
+            el = H.rel(H.to_np(p.g[l]), want[l])
+            assert el < 2 * tol, f"{tag} k={k} state {l}: {el:.3e}"
+        pg = O.param_grads(st, sv_oracle, want, xin)
+        for nm, t in (("dW1", p.dW1), ("dW2", p.dW2), ("dU", p.dU)):
+            if t is not None:
+                ew = H.rel(H.to_np(t), pg[nm])
+                assert ew < tol, f"{tag} k={k}: {nm} rel L2 {ew:.3e}"
+        worst = max(worst, err)
+    B.hbp_exact_backward(p)
+    B.hbp_param_grads(p)
+    torch.cuda.synchronize()
+    G = O.exact_backward(st, sv_oracle, inp["e"])
+    err = H.rel(H.to_np(p.g), G)
+    assert err < tol, f"{tag} exact: g rel L2 {err:.3e}"
+    pg = O.param_grads(st, sv_oracle, G, xin)
+    for nm, t in (("dW1", p.dW1), ("dW2", p.dW2), ("dU", p.dU)):
+        if t is not None:
+            assert H.rel(H.to_np(t), pg[nm]) < tol, f"{tag} exact: {nm}"
+
+
+@pytest.mark.parametrize("name", ["mlp_small_f32", "mlp_f32_ragged", "resnet_like_small", "resnet_like_odd",
+                                  "transformer_small", "deep_small", "rnn_small", "rnn_f32"])
+def test_backward_end_to_end(B, name):
+    """Own forward on each side, then Highway-BP at every k of the case, exact BP
+    and the parameter gradients."""
+    w = CASES[name]
+    inp, st, sv, p = _setup(B, w)
+    B.hbp_forward(p)
+    _check_backward(B, w, p, st, sv, inp, name)
+
+
+@pytest.mark.parametrize("name", ["mlp_f32_ragged", "resnet_like_small", "rnn_small", "rnn_chaotic_small"])
+def test_backward_shared_state(B, name):
+    """Both backward passes read the same (storage-rounded) forward state."""
+    w = CASES[name]
+    inp, st, sv, p = _setup(B, w)
+    sv_r = H.oracle_saved_rounded(w, sv)
+    H.upload_saved(p, w, sv_r)
+    _check_backward(B, w, p, st, sv_r, inp, name + "/shared")
+
+
+def test_k_beyond_L_is_exact_and_deterministic(B):
+    w = CASES["resnet_like_odd"]
+    inp, st, sv, p = _setup(B, w)
+    B.hbp_forward(p)
+    B.hbp_backward(p, w.L + 3)
+    torch.cuda.synchronize()
+    a = p.g.clone()
+    B.hbp_backward(p, w.L)
+    torch.cuda.synchronize()
+    assert torch.equal(a, p.g)
+    B.hbp_exact_backward(p)
+    torch.cuda.synchronize()
+    assert H.rel(H.to_np(a), H.to_np(p.g)) < 1e-2
+    # run-to-run determinism, including the split-K parameter gradients
+    B.hbp_backward(p, 2)
+    B.hbp_param_grads(p)
+    torch.cuda.synchronize()
+    g1, w1, w2 = p.g.clone(), p.dW1.clone(), p.dW2.clone()
+    p.g.zero_(); p.dW1.zero_(); p.dW2.zero_()
+    B.hbp_backward(p, 2)
+    B.hbp_param_grads(p)
+    torch.cuda.synchronize()
+    assert torch.equal(g1, p.g) and torch.equal(w1, p.dW1) and torch.equal(w2, p.dW2)
+
+
+@pytest.mark.parametrize("L,N", [(1, 1), (1, 9), (2, 1), (3, 64)])
+def test_degenerate_sizes(B, L, N):
+    w = synth.scaled(W["resnet_like"], name="tiny", L=L, N=N, d=64, d_ff=128, w2_scale=1.0, ks=(0, 1, 2))
+    inp, st, sv, p = _setup(B, w)
+    B.hbp_forward(p)
+    _check_backward(B, w, p, st, sv, inp, f"tiny L={L} N={N}")
+
+
+def test_error_codes_on_device_buffers(B):
+    w = CASES["resnet_like_odd"]
+    inp, st, sv, p = _setup(B, w)
+    with pytest.raises(B.HbpError) as ei:
+        B.hbp_backward(p, -1)
+    assert ei.value.status == 1
+    ws = p.workspace
+    p.workspace = ws[: ws.numel() // 2]
+    with pytest.raises(B.HbpError) as ei:
+        B.hbp_backward(p, 1)
+    assert ei.value.status == 3
+    p.workspace = ws
+    e = p.e
+    p.e = None
+    with pytest.raises(B.HbpError) as ei:
+        B.hbp_exact_backward(p)
+    assert ei.value.status == 4
+    p.e = e
+    B.hbp_forward(p)
+    B.hbp_backward(p, 1)
+    torch.cuda.synchronize()
