@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the Highway-BP backward pass on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--k ITER]
+
+One step = one pass of the whole hot path over one batch of synthetic input
+already resident in HBM: hbp_backward(k) (the residual-path-only estimate, then k
+iterations of {batched block VJP, residual-path scan}) followed by
+hbp_param_grads.  Prints ONE JSON line: backward tokens/s, the roofline of the
+dominant kernel class measured live with HIP events on the launch stream, the
+other classes' rooflines, throughput and gradient error at k = 1..4 against
+exact BP, and the CPU oracle timed on the host cores on a token sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X dense bf16
+PEAK_FP32_VECTOR_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def storage_bytes(w):
+    return 2 if w.dtype == "bf16" else 4
+
+
+def algorithmic_work(w, k):
+    """Flops / bytes per launch class for one step (multiply-add = 2 flops).
+
+    vjp1, vjp2: 2*rows*d*d_ff per launch over the blocks that launch covers
+    (iteration `it` recomputes blocks 0 .. L-it only).  dw: the token
+    contractions of hbp_param_grads.  scan: every state element is read once
+    per input stream and written once."""
+    s = storage_bytes(w)
+    L, N, d, dff = w.L, w.N, w.d, w.d_ff
+    per_block = 2.0 * N * d * dff
+    iters = min(k, L)
+    blocks = sum(L - it + 1 for it in range(1, iters + 1))
+    vjp1 = per_block * (blocks + L)        # + the one in hbp_param_grads
+    vjp2 = per_block * blocks
+    dw = 2.0 * per_block * L + (2.0 * N * L * dff * w.d_in if w.kind == "rnn" else 0.0)
+    S = float(L) * N * d
+    streams_in = 1 + (1 if w.norm == "rms" else 0) + (1 if w.loss_every_state else 0)
+    scan_iter = S * s * (streams_in + 1)
+    scan_init = S * s * (1 + (1 if w.loss_every_state else 0))
+    return {"vjp1": vjp1, "vjp2": vjp2, "dw": dw, "scan_bytes": scan_init + iters * scan_iter,
+            "scan_launches": 1 + iters}
+
+
+def gpu_errors(B, torch, p, ks):
+    """Relative L2 error and cosine of the k-iteration estimate against exact BP,
+    both from the GPU library, for states 0..L-1 and for all parameter gradients."""
+    B.hbp_exact_backward(p)
+    B.hbp_param_grads(p)
+    torch.cuda.synchronize()
+    G = p.g[:-1].float().clone()
+    PG = torch.cat([t.flatten() for t in (p.dW1, p.dW2, p.dU) if t is not None]).clone()
+    out = {}
+    for k in ks:
+        B.hbp_backward(p, k)
+        B.hbp_param_grads(p)
+        torch.cuda.synchronize()
+        g = p.g[:-1].float()
+        pg = torch.cat([t.flatten() for t in (p.dW1, p.dW2, p.dU) if t is not None])
+        out[str(k)] = {
+            "state_rel_l2": float((g - G).norm() / G.norm()),
+            "state_cos": float((g.flatten() @ G.flatten()) / (g.norm() * G.norm())),
+            "param_rel_l2": float((pg - PG).norm() / PG.norm()),
+            "param_cos": float((pg @ PG) / (pg.norm() * PG.norm())),
+        }
+    return out
+
+
+def time_steps(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def cpu_baseline(w, k, budget_tokens):
+    """The oracle as it stands on a token sample at the workload's full depth and
+    widths (cost per token is constant: tokens are independent)."""
+    from oracle import hbp_oracle as O
+    from paper_2501_17086_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    n = min(budget_tokens, w.N)
+    inp = synth.make_inputs(w, tokens=slice(0, n))
+    st = O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], U=inp["U"], eps=w.eps, L=w.L)
+    sv = O.forward(st, inp["x0"], inp["xin"])
+    t0 = time.perf_counter()
+    g = O.hbp_backward(st, sv, inp["e"], k)
+    O.param_grads(st, sv, g, inp["xin"])
+    dt = time.perf_counter() - t0
+    toks = n * (w.L if w.kind == "rnn" else 1)
+    return {"value": toks / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n} of {w.N} token rows at full L={w.L}, d={w.d}, d_ff={w.d_ff}; "
+                      f"hbp_backward(k={k}) + param_grads in {dt:.1f} s (forward untimed)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="resnet_like")
+    ap.add_argument("--k", type=int, default=2, help="Highway-BP iterations in the timed step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the k = 1..4 / exact table")
+    ap.add_argument("--cpu-tokens", type=int, default=0, help="token rows of the oracle sample (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (sharding is described in DESIGN.md)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2501_17086_amd import binding as B, synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    B.lib()   # fail loudly if the HIP library is not built
+
+    w = synth.WORKLOADS[args.workload]
+    k = args.k
+    inp = synth.make_inputs(w)
+    p = B.allocate(w, inp)
+    B.hbp_forward(p)            # support, untimed: fills the saved forward state
+    torch.cuda.synchronize()
+
+    def step():
+        B.hbp_backward(p, k)
+        B.hbp_param_grads(p)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.profile_enable(True)
+    B.profile_read()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    prof = B.profile_read()
+    B.profile_enable(False)
+
+    tokens = w.tokens
+    work = algorithmic_work(w, k)
+    ms = {c: prof[c][0] / args.steps for c in prof}
+    launches = {c: prof[c][1] // args.steps for c in prof}
+
+    def mfma_roof(cls):
+        t = ms[cls] * 1e-3
+        ach = work[cls] / t / 1e12 if t > 0 else 0.0
+        peak = PEAK_MFMA_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_VECTOR_TFLOPS
+        return {"bound": "mfma" if w.dtype == "bf16" else "alu", "achieved": ach, "peak": peak,
+                "unit": "TFLOP/s", "frac": ach / peak, "traffic": None, "kernel_class": cls,
+                "ms_per_step": ms[cls], "launches_per_step": launches[cls],
+                "avg_launch_ms": ms[cls] / max(launches[cls], 1)}
+
+    roofs = {c: mfma_roof(c) for c in ("vjp1", "vjp2", "dw")}
+    t_scan = ms["scan"] * 1e-3
+    ach = work["scan_bytes"] / t_scan / 1e9 if t_scan > 0 else 0.0
+    roofs["scan"] = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": ach / PEAK_HBM_GBS, "traffic": None, "kernel_class": "scan",
+                     "ms_per_step": ms["scan"], "launches_per_step": launches["scan"],
+                     "avg_launch_ms": ms["scan"] / max(launches["scan"], 1)}
+    dominant = max(("vjp1", "vjp2", "dw", "scan"), key=lambda c: ms[c])
+
+    out = {
+        "metric": "Highway-BP backward tokens/s (hbp_backward(k) + hbp_param_grads)",
+        "value": tokens / sec, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "k": k, "L": w.L, "tokens": tokens, "d": w.d, "d_ff": w.d_ff,
+                   "kind": w.kind, "norm": w.norm, "act": w.act},
+        "roofline": roofs[dominant],
+        "roofline_by_class": roofs,
+        "class_ms_per_step": ms,
+    }
+
+    if not args.no_sweep:
+        sweep = {}
+        for kk in (1, 2, 3, 4):
+            def f(kk=kk):
+                B.hbp_backward(p, kk)
+                B.hbp_param_grads(p)
+            t = time_steps(torch, f, max(3, args.steps // 2), 1)
+            sweep[str(kk)] = {"tokens_per_s": tokens / t, "ms": t * 1e3}
+
+        def fe():
+            B.hbp_exact_backward(p)
+            B.hbp_param_grads(p)
+        t = time_steps(torch, fe, max(3, args.steps // 2), 1)
+        sweep["exact"] = {"tokens_per_s": tokens / t, "ms": t * 1e3}
+        errs = gpu_errors(B, torch, p, (0, 1, 2, 3, 4))
+        for kk, v in errs.items():
+            sweep.setdefault(kk, {}).update(v)
+        out["per_k"] = sweep
+
+    if not args.no_cpu_baseline:
+        n = args.cpu_tokens or {"mlp_small_f32": 128, "resnet_like": 1024, "transformer_mlp": 192,
+                                "deep_large": 32, "gated_rnn": 2, "gated_rnn_contractive": 2}.get(w.name, 64)
+        out["cpu_baseline"] = cpu_baseline(w, k, n)
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -128,6 +128,24 @@ hbp_status hbp_param_grads(const hbp_desc* desc, hbp_buffers* bufs, void* stream
 
 const char* hbp_status_string(hbp_status s);
 
+/* Optional timing of the kernels the calls above enqueue, by class, with HIP
+ * events recorded on the caller's stream around each launch (host-side objects
+ * only; still no device allocation).  Off by default.  hbp_profile_read waits
+ * for the recorded events, adds the elapsed milliseconds and launch counts per
+ * class since the previous read into ms[HBP_PROF_CLASSES] and
+ * launches[HBP_PROF_CLASSES] (both HOST arrays), and forgets them. */
+enum {
+  HBP_PROF_VJP1 = 0,    /* da = (g W2) (.) act'      (step (i), first contraction)  */
+  HBP_PROF_VJP2 = 1,    /* dn = da W1                (step (i), second contraction) */
+  HBP_PROF_SCAN = 2,    /* residual-path scan        (step (ii), and w^0)           */
+  HBP_PROF_DW = 3,      /* parameter-gradient contractions over tokens              */
+  HBP_PROF_FORWARD = 4, /* forward support kernels                                  */
+  HBP_PROF_OTHER = 5,   /* copies, split-K reductions                               */
+  HBP_PROF_CLASSES = 6
+};
+hbp_status hbp_profile_enable(int on);
+hbp_status hbp_profile_read(double* ms, int64_t* launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -25,7 +25,8 @@ NORM = {"none": 0, "rms": 1}
 LAMBDA_ONE, LAMBDA_CHANNEL = 0, 1
 
 EXPORTS = ("hbp_workspace_size", "hbp_check", "hbp_forward", "hbp_backward", "hbp_exact_backward",
-           "hbp_param_grads", "hbp_status_string")
+           "hbp_param_grads", "hbp_profile_enable", "hbp_profile_read", "hbp_status_string")
+PROF_CLASSES = ("vjp1", "vjp2", "scan", "dw", "forward", "other")
 
 
 class hbp_desc(C.Structure):
@@ -65,6 +66,8 @@ def lib() -> C.CDLL:
         L.hbp_backward.argtypes = [C.POINTER(hbp_desc), C.c_int, C.POINTER(hbp_buffers), C.c_void_p]
         L.hbp_exact_backward.argtypes = [C.POINTER(hbp_desc), C.POINTER(hbp_buffers), C.c_void_p]
         L.hbp_param_grads.argtypes = [C.POINTER(hbp_desc), C.POINTER(hbp_buffers), C.c_void_p]
+        L.hbp_profile_enable.argtypes = [C.c_int]
+        L.hbp_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         L.hbp_status_string.argtypes = [C.c_int]
         L.hbp_status_string.restype = C.c_char_p
         for n in EXPORTS[:-1]:
@@ -160,6 +163,19 @@ def hbp_exact_backward(p: Problem, stream=None) -> None:
 def hbp_param_grads(p: Problem, stream=None) -> None:
     b = p.buffers()
     _call("hbp_param_grads", lib().hbp_param_grads(C.byref(p.desc), C.byref(b), _stream(stream)))
+
+
+def profile_enable(on: bool) -> None:
+    _call("hbp_profile_enable", lib().hbp_profile_enable(1 if on else 0))
+
+
+def profile_read() -> dict:
+    """{class: (milliseconds, launches)} since the previous read."""
+    n = len(PROF_CLASSES)
+    ms = (C.c_double * n)()
+    cnt = (C.c_int64 * n)()
+    _call("hbp_profile_read", lib().hbp_profile_read(ms, cnt))
+    return {PROF_CLASSES[i]: (ms[i], cnt[i]) for i in range(n)}
 
 
 def allocate(w, inputs, device="cuda:0", N: Optional[int] = None) -> Problem:

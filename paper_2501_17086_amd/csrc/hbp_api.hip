@@ -5,6 +5,9 @@
 #include "../../include/hbp.h"
 #include "hbp_common.h"
 
+#include <mutex>
+#include <vector>
+
 using namespace hbp;
 
 namespace {
@@ -116,7 +119,39 @@ hbp_status check_bufs(const hbp_desc* d, const hbp_buffers* b, int need) {
     if (_e != hipSuccess) return HBP_E_DEVICE; \
   } while (0)
 
-hbp_status run_gemm(const hbp_desc* d, const GemmArgs& ga, hipStream_t s) {
+// ---- optional per-kernel-class timing with HIP events (off by default) ----
+struct ProfRec { hipEvent_t a, b; int cls; };
+struct ProfState {
+  bool on = false;
+  std::vector<ProfRec> recs;      // events in flight since the last read
+  std::vector<hipEvent_t> pool;   // recycled events
+  std::mutex mu;
+};
+ProfState& prof() { static ProfState p; return p; }
+
+struct ProfScope {
+  hipStream_t s; hipEvent_t a = nullptr, b = nullptr; int cls; bool live = false;
+  ProfScope(int cls_, hipStream_t s_) : s(s_), cls(cls_) {
+    ProfState& p = prof();
+    if (!p.on) return;
+    std::lock_guard<std::mutex> lk(p.mu);
+    for (hipEvent_t* e : {&a, &b}) {
+      if (!p.pool.empty()) { *e = p.pool.back(); p.pool.pop_back(); }
+      else if (hipEventCreate(e) != hipSuccess) { *e = nullptr; return; }
+    }
+    live = hipEventRecord(a, s) == hipSuccess;
+  }
+  ~ProfScope() {
+    if (!live) return;
+    (void)hipEventRecord(b, s);
+    ProfState& p = prof();
+    std::lock_guard<std::mutex> lk(p.mu);
+    p.recs.push_back({a, b, cls});
+  }
+};
+
+hbp_status run_gemm(const hbp_desc* d, const GemmArgs& ga, hipStream_t s, int cls) {
+  ProfScope ps(cls, s);
   hipError_t err = hipSuccess;
   if (d->dtype == HBP_BF16 && launch_gemm_mfma(ga, s, &err)) {
     return err == hipSuccess ? HBP_OK : HBP_E_DEVICE;
@@ -163,7 +198,7 @@ hbp_status vjp_stage1(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
     ga.mode = EPI_STORE;
   }
   ga.aux_sb = d->N * d->d_ff;
-  return run_gemm(d, ga, s);
+  return run_gemm(d, ga, s, HBP_PROF_VJP1);
 }
 
 // dn[l] = da[l] . W1_l  (into the v buffer)
@@ -186,7 +221,7 @@ hbp_status vjp_stage2(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
   ga.a_sb = d->N * d->d_ff; ga.b_sb = d->d * d->d_ff; ga.c_sb = d->N * d->d;
   ga.split_k = 1;
   ga.mode = EPI_STORE;
-  return run_gemm(d, ga, s);
+  return run_gemm(d, ga, s, HBP_PROF_VJP2);
 }
 
 hbp_status scan_stage(const hbp_desc* d, const hbp_buffers* b, const Workspace& w, long l_lo, long l_hi,
@@ -201,6 +236,7 @@ hbp_status scan_stage(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
   sa.N = d->N; sa.d = d->d;
   sa.l_lo = l_lo; sa.l_hi = l_hi;
   sa.norm_rms = d->norm == HBP_NORM_RMS;
+  ProfScope ps(HBP_PROF_SCAN, s);
   HBP_TRY(launch_scan(d->dtype, sa, s));
   return HBP_OK;
 }
@@ -210,6 +246,7 @@ hbp_status seed_top(const hbp_desc* d, const hbp_buffers* b, hipStream_t s) {
   const size_t es = esize(d);
   const size_t row = (size_t)d->N * d->d * es;
   const void* src = d->loss_every_state ? at(b->e, (size_t)d->L * row) : b->e;
+  ProfScope ps(HBP_PROF_OTHER, s);
   HBP_TRY(hipMemcpyAsync(at(b->g, (size_t)d->L * row), src, row, hipMemcpyDeviceToDevice, s));
   return HBP_OK;
 }
@@ -229,8 +266,11 @@ hbp_status tn_gemm(const hbp_desc* d, const void* A, long lda, long a_sb, const 
   ga.mode = EPI_STORE;
   ga.c_is_f32 = 1;
   ga.C = split > 1 ? part : (void*)C;
-  HBP_RUN(run_gemm(d, ga, s));
-  if (split > 1) HBP_TRY(launch_splitk_reduce((const float*)part, C, batch * M * N, split, s));
+  HBP_RUN(run_gemm(d, ga, s, HBP_PROF_DW));
+  if (split > 1) {
+    ProfScope ps(HBP_PROF_OTHER, s);
+    HBP_TRY(launch_splitk_reduce((const float*)part, C, batch * M * N, split, s));
+  }
   return HBP_OK;
 }
 
@@ -248,6 +288,31 @@ const char* hbp_status_string(hbp_status s) {
     case HBP_E_DEVICE: return "HIP launch failed";
   }
   return "unknown status";
+}
+
+hbp_status hbp_profile_enable(int on) {
+  ProfState& p = prof();
+  std::lock_guard<std::mutex> lk(p.mu);
+  p.on = on != 0;
+  return HBP_OK;
+}
+
+hbp_status hbp_profile_read(double* ms, int64_t* launches) {
+  if (!ms || !launches) return HBP_E_NULL;
+  ProfState& p = prof();
+  std::lock_guard<std::mutex> lk(p.mu);
+  for (int c = 0; c < HBP_PROF_CLASSES; ++c) { ms[c] = 0.0; launches[c] = 0; }
+  hbp_status st = HBP_OK;
+  for (ProfRec& r : p.recs) {
+    float t = 0.f;
+    if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&t, r.a, r.b) != hipSuccess) st = HBP_E_DEVICE;
+    ms[r.cls] += t;
+    launches[r.cls] += 1;
+    p.pool.push_back(r.a);
+    p.pool.push_back(r.b);
+  }
+  p.recs.clear();
+  return st;
 }
 
 hbp_status hbp_workspace_size(const hbp_desc* desc, size_t* bytes) {
@@ -280,13 +345,14 @@ hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
     ga.b_sk = 1; ga.b_sn = d->d_in;
     ga.ldc = d->d_ff; ga.batch = 1; ga.split_k = 1;
     ga.mode = EPI_STORE; ga.c_is_f32 = 1;
-    HBP_RUN(run_gemm(d, ga, s));
+    HBP_RUN(run_gemm(d, ga, s, HBP_PROF_FORWARD));
   }
   for (long l = 0; l < d->L; ++l) {
     const size_t xo = (size_t)l * d->N * d->d * es;
     const size_t fo = (size_t)l * d->N * d->d_ff * es;
     const void* yl = at((const void*)b->x, xo);
     if (rms) {
+      ProfScope ps(HBP_PROF_FORWARD, s);
       HBP_TRY(launch_rmsnorm_fwd(d->dtype, at((const void*)b->x, xo), at(b->y, xo), b->rinv + l * d->N, d->N, d->d,
                                  d->eps, s));
       yl = at((const void*)b->y, xo);
@@ -304,7 +370,7 @@ hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
       else if (d->act == HBP_ACT_TANH) ga.mode = EPI_ACT_TANH;
       else ga.mode = EPI_STORE;
       if (d->kind == HBP_RNN) ga.addf = ux + l * d->N * d->d_ff;
-      HBP_RUN(run_gemm(d, ga, s));
+      HBP_RUN(run_gemm(d, ga, s, HBP_PROF_FORWARD));
     }
     {  // x_{l+1} = lambda (.) x_l + z W2^T
       GemmArgs ga{};
@@ -318,7 +384,7 @@ hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
       ga.mode = EPI_RESID;
       ga.aux = at((const void*)b->x, xo);
       ga.lambda = d->lambda_kind == HBP_LAMBDA_CHANNEL ? b->lambda + l * d->d : nullptr;
-      HBP_RUN(run_gemm(d, ga, s));
+      HBP_RUN(run_gemm(d, ga, s, HBP_PROF_FORWARD));
     }
   }
   return HBP_OK;
