@@ -48,10 +48,19 @@ typedef short short4v __attribute__((ext_vector_type(4)));
 typedef short short8v __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 256, BN = 128, BK = 32, NST = 3, NTHR = 256;
+constexpr int BM = 256, BK = 32;
 constexpr int A_BYTES = BM * BK * 2;            // 16 KB
-constexpr int B_BYTES = BN * BK * 2;            //  8 KB
-constexpr int STAGE_BYTES = A_BYTES + B_BYTES;  // 24 KB
+// WN = wave columns of the workgroup: 2 -> tile 256 x 128, 4 waves, 3 stages, two
+// workgroups per CU; 4 -> tile 256 x 256, 8 waves, 4 stages, one workgroup per CU.
+template <int WN> struct Cfg {
+  static constexpr int BN = 64 * WN;
+  static constexpr int NW = 2 * WN;                 // waves
+  static constexpr int NTHR = 64 * NW;
+  static constexpr int NST = WN == 2 ? 3 : 4;
+  static constexpr int B_BYTES = BN * BK * 2;
+  static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+  static constexpr int MIN_WG = WN == 2 ? 2 : 1;    // workgroups per CU
+};
 constexpr int EPI_LD = 64 + 4;                  // floats per staged row
 constexpr int EPI_WAVE = 32 * EPI_LD;           // floats per wave
 constexpr int GROUP_M = 8;                      // tile rows per block of the tile walk
@@ -71,9 +80,9 @@ __device__ __forceinline__ void wait_vm() {   // at most N vector-memory loads o
 }
 
 // Per-lane source description of one operand tile's copies (ROWS/64 per wave).
-template <bool KC, int ROWS>
+template <bool KC, int ROWS, int NW>
 struct TileSrc {
-  static constexpr int NI = ROWS / 64;          // copies per wave per slice
+  static constexpr int NI = ROWS / 16 / NW;     // copies per wave per slice
   static constexpr int CH = ROWS / 8;           // RC: 16-byte chunks per k row
   const bf16_t* p[NI];                          // pointer at slice 0 (may be out of range: guarded by ok/klim)
   bool ok[NI];                                  // the fixed coordinate is inside the matrix
@@ -84,17 +93,17 @@ struct TileSrc {
                                        int wave, int lane) {
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
-      const int j = wave + 4 * i;               // copy index within the tile: 1 KB each
+      const int j = wave + NW * i;              // copy index within the tile: 1 KB each
       if (KC) {
         const int r = 16 * j + (lane >> 2);
-        const int c = (lane & 3) ^ ((r >> 1) & 3);
+        const int c = (lane & 3) ^ ((r >> 2) & 3);
         ok[i] = row0 + r < rows_lim;
         kofs[i] = 8 * c;
         p[i] = base + (row0 + r) * ld + k_begin + 8 * c;
       } else {
         constexpr int KPI = 64 / CH;            // k rows per copy
         const int k = j * KPI + lane / CH;
-        const int c = (lane % CH) ^ (2 * (k & 3));
+        const int c = (lane % CH) ^ (4 * (k & 3));
         ok[i] = row0 + 8 * c < rows_lim;
         kofs[i] = k;
         p[i] = base + (k_begin + k) * ld + row0 + 8 * c;
@@ -108,7 +117,7 @@ struct TileSrc {
     for (int i = 0; i < NI; ++i) {
       const bool v = ok[i] && (k_begin + (long)t * BK + kofs[i] < k_end);
       const void* src = v ? (const void*)(p[i] + (long)t * step) : (const void*)(g_zero_chunks + lane);
-      dma16(src, lds_tile + (unsigned)(wave + 4 * i) * 1024u);
+      dma16(src, lds_tile + (unsigned)(wave + NW * i) * 1024u);
     }
   }
 };
@@ -119,14 +128,14 @@ __device__ __forceinline__ bf16x8 frag(const unsigned char* tile, int row0, int 
   if (KC) {
     const int r = row0 + (lane & 31);
     const int c = (kk >> 3) + (lane >> 5);
-    const uint4 v = *reinterpret_cast<const uint4*>(tile + r * 64 + ((c ^ ((r >> 1) & 3)) << 4));
+    const uint4 v = *reinterpret_cast<const uint4*>(tile + r * 64 + ((c ^ ((r >> 2) & 3)) << 4));
     return __builtin_bit_cast(bf16x8, v);
   } else {
     typedef __attribute__((address_space(3))) short4v* lds_p;
     const int s = lane & 15;
     const int e = row0 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
     const int k = kk + 8 * (lane >> 5) + (s >> 2);          // k & 3 == s >> 2 for both halves
-    const int sw = 2 * (s >> 2);
+    const int sw = 4 * (s >> 2);
     const unsigned char* p = tile + k * (ROWS * 2) + (((e >> 3) ^ sw) << 4) + (e & 7) * 2;
     const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p));
     const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_p)(p + 4 * (ROWS * 2)));
@@ -142,9 +151,12 @@ __device__ __forceinline__ float gelu_grad_f(float a) {
   return 0.5f * (1.0f + erff(a * 0.70710678118654752440f)) + a * __expf(-0.5f * a * a) * 0.39894228040143267794f;
 }
 
-template <bool A_KC, bool B_KC>
-__global__ __launch_bounds__(NTHR, 2) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n, long total,
-                                                            long per_xcd) {
+template <bool A_KC, bool B_KC, int WN>
+__global__ __launch_bounds__(Cfg<WN>::NTHR, Cfg<WN>::MIN_WG) void gemm_mfma_kernel(GemmArgs g, int tiles_m,
+                                                                                   int tiles_n, long total,
+                                                                                   long per_xcd) {
+  typedef Cfg<WN> C;
+  constexpr int BN = C::BN, NST = C::NST, STAGE_BYTES = C::STAGE_BYTES;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
   // ---- XCD-aware tile id, walking 8 x 8 blocks of tiles ----
@@ -163,7 +175,7 @@ __global__ __launch_bounds__(NTHR, 2) void gemm_mfma_kernel(GemmArgs g, int tile
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm0 = (wave >> 1) * 128, wn0 = (wave & 1) * 64;
+  const int wm0 = (wave / WN) * 128, wn0 = (wave % WN) * 64;
   const long m0 = (long)tm * BM, n0 = (long)tn * BN;
 
   const bf16_t* A = reinterpret_cast<const bf16_t*>(g.A) + batch * g.a_sb;
@@ -180,8 +192,8 @@ __global__ __launch_bounds__(NTHR, 2) void gemm_mfma_kernel(GemmArgs g, int tile
 
   const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
-  TileSrc<A_KC, BM> sa;
-  TileSrc<B_KC, BN> sb;
+  TileSrc<A_KC, BM, C::NW> sa;
+  TileSrc<B_KC, BN, C::NW> sb;
   sa.init(A, lda, m0, g.M, k_begin, wave, lane);
   sb.init(B, ldb, n0, g.N, k_begin, wave, lane);
 
@@ -193,7 +205,7 @@ __global__ __launch_bounds__(NTHR, 2) void gemm_mfma_kernel(GemmArgs g, int tile
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // prologue: two slices in flight
+  // prologue: NST-1 slices in flight
 #pragma unroll
   for (int s = 0; s < NST - 1; ++s)
     if (s < KT) {
@@ -201,33 +213,79 @@ __global__ __launch_bounds__(NTHR, 2) void gemm_mfma_kernel(GemmArgs g, int tile
       sb.issue(s, k_begin, k_end, lds0 + s * STAGE_BYTES + A_BYTES, wave, lane);
     }
 
-  constexpr int PER_SLICE = TileSrc<A_KC, BM>::NI + TileSrc<B_KC, BN>::NI;  // copies per wave per slice
+  constexpr int PER_SLICE = TileSrc<A_KC, BM, C::NW>::NI + TileSrc<B_KC, BN, C::NW>::NI;  // copies per wave per slice
+
+  // A slice is consumed in four groups of 2 x 2 MFMA blocks (k half, row half).
+  // The A fragments of group g+1 are read from LDS while the MFMAs of group g
+  // run, and the first fragments of slice kt+1 while the last group of slice kt
+  // runs, so the matrix cores do not wait for LDS.
+  auto load_b = [&](const unsigned char* bt, bf16x8 (&b)[2][2]) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) b[h][j] = frag<B_KC, BN>(bt, wn0 + 32 * j, 16 * h, lane);
+  };
+  auto load_a = [&](const unsigned char* at, int grp, bf16x8 (&a)[2]) {
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii) a[ii] = frag<A_KC, BM>(at, wm0 + 32 * ((grp & 1) * 2 + ii), 16 * (grp >> 1), lane);
+  };
+  auto mma = [&](int grp, const bf16x8 (&a)[2], const bf16x8 (&b)[2][2]) {
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int i = (grp & 1) * 2 + ii;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ii], b[grp >> 1][j], acc[i][j], 0, 0, 0);
+      }
+  };
+  // waits until at most n slices' worth of this wave's copies are outstanding
+  auto wait_slices = [&](int n) {
+    if (n >= 2) wait_vm<2 * PER_SLICE>();
+    else if (n == 1) wait_vm<PER_SLICE>();
+    else wait_vm<0>();
+  };
+
+  bf16x8 bcur[2][2], bnxt[2][2], a0[2], a1[2];
+  if (KT > 0) {
+    wait_slices((KT - 1 < NST - 2 ? KT - 1 : NST - 2));   // slice 0 has landed (this wave's part)
+    __syncthreads();                                      // ... and every other wave's
+    load_b(smem + A_BYTES, bcur);
+    load_a(smem, 0, a0);
+  }
   int st = 0;                                  // stage of slice kt
   for (int kt = 0; kt < KT; ++kt) {
-    // slice kt has landed once at most the copies of slice kt+1 are still outstanding
-    if (kt + 1 < KT) wait_vm<PER_SLICE>(); else wait_vm<0>();
-    __syncthreads();                           // ... for every wave; and everyone is done reading slice kt-1
-    if (kt + NST - 1 < KT) {
-      int sn = st + NST - 1; if (sn >= NST) sn -= NST;   // stage of slice kt-1: free now
-      sa.issue(kt + NST - 1, k_begin, k_end, lds0 + sn * STAGE_BYTES, wave, lane);
-      sb.issue(kt + NST - 1, k_begin, k_end, lds0 + sn * STAGE_BYTES + A_BYTES, wave, lane);
-    }
     const unsigned char* at = smem + st * STAGE_BYTES;
-    const unsigned char* bt = at + A_BYTES;
-#pragma unroll
-    for (int kk = 0; kk < BK; kk += 16) {
-      bf16x8 af[4], bfr[2];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) af[i] = frag<A_KC, BM>(at, wm0 + 32 * i, kk, lane);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) bfr[j] = frag<B_KC, BN>(bt, wn0 + 32 * j, kk, lane);
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    load_a(at, 1, a1);
+    mma(0, a0, bcur);
+    __builtin_amdgcn_sched_barrier(0);
+    load_a(at, 2, a0);
+    mma(1, a1, bcur);
+    __builtin_amdgcn_sched_barrier(0);
+    load_a(at, 3, a1);
+    mma(2, a0, bcur);
+    __builtin_amdgcn_sched_barrier(0);
+    int sn = st + 1; if (sn == NST) sn = 0;    // stage of slice kt+1
+    if (kt + 1 < KT) {
+      // slice kt+1 has landed once only the slices issued after it are outstanding
+      const int last = kt + NST - 2 < KT - 1 ? kt + NST - 2 : KT - 1;
+      wait_slices(last - (kt + 1));
+      __syncthreads();   // every wave's part of slice kt+1 is in LDS; everyone is done reading slice kt-1
+      if (kt + NST - 1 < KT) {
+        int sf = st + NST - 1; if (sf >= NST) sf -= NST;   // stage of slice kt-1: free now
+        sa.issue(kt + NST - 1, k_begin, k_end, lds0 + sf * STAGE_BYTES, wave, lane);
+        sb.issue(kt + NST - 1, k_begin, k_end, lds0 + sf * STAGE_BYTES + A_BYTES, wave, lane);
+      }
+      const unsigned char* an = smem + sn * STAGE_BYTES;
+      load_b(an + A_BYTES, bnxt);
+      load_a(an, 0, a0);
     }
-    if (++st == NST) st = 0;
+    mma(3, a1, bcur);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) bcur[h][j] = bnxt[h][j];
+    st = sn;
   }
   __syncthreads();   // all waves are done with the operand stages before they are reused below
 
@@ -346,13 +404,15 @@ __global__ __launch_bounds__(NTHR, 2) void gemm_mfma_kernel(GemmArgs g, int tile
   }
 }
 
-template <bool A_KC, bool B_KC>
+template <bool A_KC, bool B_KC, int WN>
 hipError_t launch_variant(const GemmArgs& g, hipStream_t s) {
-  constexpr size_t lds_main = (size_t)NST * STAGE_BYTES;
-  constexpr size_t lds_epi = (size_t)4 * EPI_WAVE * sizeof(float);
+  typedef Cfg<WN> C;
+  constexpr int BN = C::BN, NTHR = C::NTHR;
+  constexpr size_t lds_main = (size_t)C::NST * C::STAGE_BYTES;
+  constexpr size_t lds_epi = (size_t)C::NW * EPI_WAVE * sizeof(float);
   constexpr size_t lds_bytes = lds_main > lds_epi ? lds_main : lds_epi;
   static bool attr_set = false;
-  auto kern = gemm_mfma_kernel<A_KC, B_KC>;
+  auto kern = gemm_mfma_kernel<A_KC, B_KC, WN>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
@@ -385,9 +445,13 @@ bool launch_gemm_mfma(const GemmArgs& g, hipStream_t s, hipError_t* err) {
       !aligned16(g.addf) || !aligned16(g.lambda))
     return false;
   if (g.split_k > 1 && g.mode != EPI_STORE) return false;
-  if (a_kc && b_rc) *err = launch_variant<true, false>(g, s);
-  else if (a_rc && b_rc) *err = launch_variant<false, false>(g, s);
-  else if (a_kc && b_kc) *err = launch_variant<true, true>(g, s);
+  // Long contractions take the 256 x 256 tile (fewest bytes through L2 per
+  // flop); short ones, where the epilogue weighs as much as the main loop, the
+  // 256 x 128 tile with two workgroups per CU overlapping each other.
+  const bool wide = g.tile_hint ? g.tile_hint == 4 : (g.K / g.split_k >= 1024 && g.N > 128);
+  if (a_kc && b_rc) *err = wide ? launch_variant<true, false, 4>(g, s) : launch_variant<true, false, 2>(g, s);
+  else if (a_rc && b_rc) *err = wide ? launch_variant<false, false, 4>(g, s) : launch_variant<false, false, 2>(g, s);
+  else if (a_kc && b_kc) *err = wide ? launch_variant<true, true, 4>(g, s) : launch_variant<true, true, 2>(g, s);
   else return false;
   return true;
 }
