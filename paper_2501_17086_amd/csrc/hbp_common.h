@@ -83,7 +83,6 @@ struct GemmArgs {
   const float* addf; long addf_sb;    // fp32 [M,N], added to acc before the epilogue
   const float* lambda; long lambda_sb;  // fp32 [N]
   int c_is_f32;         // C stored as fp32 regardless of the storage type
-  int tile_hint;        // MFMA path: 0 = choose, 2 = 256x128 tile, 4 = 256x256 tile
 };
 
 // storage type: 0 = fp32, 1 = bf16
