@@ -206,7 +206,8 @@ enum FastEpi {
   FAST_STORE = 1,      // C(bf16) = acc
   FAST_STORE_F32 = 2,  // C(fp32) = acc, also the split-K partial sums
   FAST_MUL_AUX = 3,    // C(bf16) = acc * aux
-  FAST_MUL_1MZ2 = 4    // C(bf16) = acc * (1 - aux^2)
+  FAST_MUL_1MZ2 = 4,   // C(bf16) = acc * (1 - aux^2)
+  FAST_ADD_AUX = 5     // C(bf16) = acc + aux
 };
 template <int FAST> struct FastOps {   // vector-memory operations per wave of one fast epilogue
   static constexpr int value = FAST == FAST_STORE ? 16 : FAST == FAST_STORE_F32 ? 32 : FAST == FAST_NONE ? 0 : 32;
@@ -452,7 +453,7 @@ __global__ __launch_bounds__(NTHR, 1) void gemm_mfma_kernel(GemmArgs g, int tile
     const int le = launder(lane);
     const int er = le >> 3;
     const int ec = (le & 7) * 8;
-    constexpr bool HAS_AUX = FAST == FAST_MUL_AUX || FAST == FAST_MUL_1MZ2;
+    constexpr bool HAS_AUX = FAST == FAST_MUL_AUX || FAST == FAST_MUL_1MZ2 || FAST == FAST_ADD_AUX;
     const long off0 = (tc.m0 + wm0 + er) * g.ldc + tc.n0 + wn0 + ec;   // this lane's first element
     const bf16_t* aux = reinterpret_cast<const bf16_t*>(g.aux) + tc.batch * g.aux_sb + off0;
     const long cb = g.split_k > 1 ? ((long)tc.split * g.batch + tc.batch) * g.c_sb : tc.batch * g.c_sb;
@@ -501,6 +502,7 @@ __global__ __launch_bounds__(NTHR, 1) void gemm_mfma_kernel(GemmArgs g, int tile
             for (int x = 0; x < 4; ++x) {
               const float t0 = __uint_as_float(w4[x] << 16), t1 = __uint_as_float(w4[x] & 0xFFFF0000u);
               if (FAST == FAST_MUL_AUX) { v[2 * x] *= t0; v[2 * x + 1] *= t1; }
+              else if (FAST == FAST_ADD_AUX) { v[2 * x] += t0; v[2 * x + 1] += t1; }
               else { v[2 * x] *= (1.f - t0 * t0); v[2 * x + 1] *= (1.f - t1 * t1); }
             }
           }
@@ -650,6 +652,7 @@ bool launch_gemm_mfma(const GemmArgs& g, hipStream_t s, hipError_t* err) {
     if (plain && !g.c_is_f32 && g.split_k == 1) *err = launch_variant<true, false, false, FAST_STORE>(g, s);
     else if (g.mode == EPI_MUL_AUX && !g.addf && !g.c_is_f32) *err = launch_variant<true, false, false, FAST_MUL_AUX>(g, s);
     else if (g.mode == EPI_MUL_1MZ2 && !g.addf && !g.c_is_f32) *err = launch_variant<true, false, false, FAST_MUL_1MZ2>(g, s);
+    else if (g.mode == EPI_ADD_AUX && !g.addf && !g.c_is_f32) *err = launch_variant<true, false, false, FAST_ADD_AUX>(g, s);
     else *err = launch_variant<true, false, false, FAST_NONE>(g, s);
   } else if (a_rc && b_rc && !act) {     // parameter gradients
     if (plain && (g.c_is_f32 || g.split_k > 1)) *err = launch_variant<false, false, false, FAST_STORE_F32>(g, s);

@@ -17,7 +17,7 @@ inline size_t esize(const hbp_desc* d) { return d->dtype == HBP_F32 ? 4 : 2; }
 inline bool shared_w(const hbp_desc* d) { return d->kind == HBP_RNN; }
 
 struct Workspace {
-  size_t off_v, off_da, off_part, total;
+  size_t off_v, off_da, off_part, off_scan, total;
 };
 
 // split-K factor for a parameter-gradient GEMM with `tiles` output tiles and a
@@ -64,6 +64,7 @@ Workspace carve(const hbp_desc* d) {
     if (pu > part) part = pu;
   }
   w.off_part = o; o = align_up(o + part, 256);
+  w.off_scan = o; o = align_up(o + scan_chunk_ws_bytes(d->L, d->N, d->d, d->norm == HBP_NORM_RMS), 256);
   w.total = o;
   return w;
 }
@@ -169,6 +170,10 @@ hbp_status run_gemm(const hbp_desc* d, const GemmArgs& ga, hipStream_t s, int cl
 inline char* at(void* p, size_t bytes) { return reinterpret_cast<char*>(p) + bytes; }
 inline const char* at(const void* p, size_t bytes) { return reinterpret_cast<const char*>(p) + bytes; }
 
+// With a loss at every state and no norm between the block and the residual
+// path, e_l is added to v_l by the second contraction's epilogue.
+inline bool e_in_vjp(const hbp_desc* d) { return d->loss_every_state && d->norm == HBP_NORM_NONE; }
+
 // da[l] = (g[l+1] . W2_l) (.) act'(a_l) for blocks l_lo..l_hi-1
 hbp_status vjp_stage1(const hbp_desc* d, const hbp_buffers* b, const Workspace& w, long l_lo, long l_hi,
                       hipStream_t s) {
@@ -221,6 +226,11 @@ hbp_status vjp_stage2(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
   ga.a_sb = d->N * d->d_ff; ga.b_sb = d->d * d->d_ff; ga.c_sb = d->N * d->d;
   ga.split_k = 1;
   ga.mode = EPI_STORE;
+  if (e_in_vjp(d)) {   // v_l + e_l in the epilogue: the scan then reads one stream less
+    ga.mode = EPI_ADD_AUX;
+    ga.aux = at(b->e, (size_t)l_lo * d->N * d->d * es);
+    ga.aux_sb = d->N * d->d;
+  }
   return run_gemm(d, ga, s, HBP_PROF_VJP2);
 }
 
@@ -231,7 +241,9 @@ hbp_status scan_stage(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
   sa.dn = has_v ? at(b->workspace, w.off_v) : nullptr;
   sa.y = b->y;
   sa.rinv = b->rinv;
-  sa.e = d->loss_every_state ? b->e : nullptr;
+  sa.e = (d->loss_every_state && !(has_v && e_in_vjp(d))) ? b->e : nullptr;
+  sa.chunk_ws = scan_chunk_ws_bytes(d->L, d->N, d->d, d->norm == HBP_NORM_RMS)
+                    ? reinterpret_cast<float*>(at(b->workspace, w.off_scan)) : nullptr;
   sa.lambda = d->lambda_kind == HBP_LAMBDA_CHANNEL ? b->lambda : nullptr;
   sa.N = d->N; sa.d = d->d;
   sa.l_lo = l_lo; sa.l_hi = l_hi;

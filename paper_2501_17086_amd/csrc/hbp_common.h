@@ -109,8 +109,14 @@ struct ScanArgs {
   long N, d;
   long l_lo, l_hi;
   int norm_rms;
+  float* chunk_ws;      // scratch of scan_chunk_ws_bytes() for the chunked form (long chains), or NULL
 };
 hipError_t launch_scan(int dtype, const ScanArgs& a, hipStream_t s);
+// Long chains with few of them (the time axis of an RNN) are cut into chunks of
+// SCAN_CHUNK states scanned in parallel; bytes of fp32 scratch that form needs
+// (0 when the direct form is used).
+constexpr long SCAN_CHUNK = 64;
+size_t scan_chunk_ws_bytes(long L, long N, long d, int norm_rms);
 
 // y = x * rinv, rinv = 1/sqrt(mean(x^2)+eps) for `rows` rows of width d
 hipError_t launch_rmsnorm_fwd(int dtype, const void* x, void* y, float* rinv, long rows, long d, float eps,

@@ -160,9 +160,150 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const T* __restrict__ 
   }
 }
 
+// ---------------------------------------------------------------------------
+// Chunked form for long chains (T = thousands of states, only N*d chains): the
+// direct kernels above would leave most of the chip idle behind a sequential
+// walk.  The chain is cut into chunks of SCAN_CHUNK states.  With the linear
+// map of a chunk written  g_bottom = B + A (.) g_top  (A = product of lambda
+// over the chunk, B = the chunk scanned from a zero state), three passes do:
+//   reduce   every (chunk, row group, channel vector) in parallel: B
+//   combine  every chain, walking the chunks from the top: the state entering
+//            each chunk, cin_c = B_{c+1} + A_{c+1} (.) cin_{c+1}  (cin_top = g[l_hi])
+//   apply    every (chunk, ...) in parallel again: the recurrence from cin_c,
+//            writing g.
+// The same operator (A1,B1) o (A2,B2) = (A1 A2, B1 + A1 B2) composes chunks as
+// composes single states.  Each element is read twice and written once.
+// lambda is shared by the rows, so a thread walks ROWS rows of its channels at
+// once and reads each lambda row once for all of them.
+// ---------------------------------------------------------------------------
+constexpr int CH_ROWS = 4;
+
+template <typename T, bool APPLY>
+__global__ __launch_bounds__(256) void scan_chunk_kernel(ScanArgs a, long nchunks, long row_groups) {
+  const long vecs = a.d / 8;
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= nchunks * row_groups * vecs) return;
+  const long v = idx % vecs;
+  const long rg = (idx / vecs) % row_groups;
+  const long c = idx / (vecs * row_groups);
+  const long ch = v * 8;
+  const long layer = a.N * a.d;
+  const long l_bot = a.l_lo + c * SCAN_CHUNK;
+  const long l_top = l_bot + SCAN_CHUNK < a.l_hi ? l_bot + SCAN_CHUNK : a.l_hi;
+  T* g = reinterpret_cast<T*>(a.g);
+  const T* dn = reinterpret_cast<const T*>(a.dn);
+  const T* e = reinterpret_cast<const T*>(a.e);
+  float* B = a.chunk_ws;                                   // [nchunks][N][d]
+  float* cin = a.chunk_ws + nchunks * layer;               // [nchunks][N][d]
+
+  float carry[CH_ROWS][8];
+  long off[CH_ROWS];
+  bool on[CH_ROWS];
+#pragma unroll
+  for (int r = 0; r < CH_ROWS; ++r) {
+    const long row = rg * CH_ROWS + r;
+    on[r] = row < a.N;
+    off[r] = row * a.d + ch;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) carry[r][i] = 0.f;
+    if (APPLY && on[r]) load8(cin + c * layer + off[r], carry[r]);
+  }
+#pragma unroll 4
+  for (long l = l_top - 1; l >= l_bot; --l) {
+    float lam[8];
+    if (a.lambda) {
+      load8(a.lambda + l * a.d + ch, lam);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) lam[i] = 1.f;
+    }
+#pragma unroll
+    for (int r = 0; r < CH_ROWS; ++r) {
+      if (!on[r]) continue;
+      float b[8];
+      if (dn) {
+        load8(dn + l * layer + off[r], b);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) b[i] = 0.f;
+      }
+      if (e) {
+        float t[8];
+        load8(e + l * layer + off[r], t);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) b[i] += t[i];
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) carry[r][i] = fmaf(lam[i], carry[r][i], b[i]);
+      if (APPLY) store8(g + l * layer + off[r], carry[r]);
+    }
+  }
+  if (!APPLY) {
+#pragma unroll
+    for (int r = 0; r < CH_ROWS; ++r)
+      if (on[r]) store8(B + c * layer + off[r], carry[r]);
+  }
+}
+
+// A[c][ch] = product of lambda over chunk c (ones without lambda)
+__global__ __launch_bounds__(256) void scan_chunk_lambda_kernel(ScanArgs a, long nchunks, float* __restrict__ A) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= nchunks * a.d) return;
+  const long ch = idx % a.d, c = idx / a.d;
+  const long l_bot = a.l_lo + c * SCAN_CHUNK;
+  const long l_top = l_bot + SCAN_CHUNK < a.l_hi ? l_bot + SCAN_CHUNK : a.l_hi;
+  float p = 1.f;
+  if (a.lambda)
+    for (long l = l_top - 1; l >= l_bot; --l) p *= a.lambda[l * a.d + ch];
+  A[idx] = p;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void scan_chunk_combine_kernel(ScanArgs a, long nchunks, const float* __restrict__ A) {
+  const long layer = a.N * a.d;
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= layer / 8) return;
+  const long off = idx * 8;
+  const long ch = off % a.d;
+  const float* B = a.chunk_ws;
+  float* cin = a.chunk_ws + nchunks * layer;
+  float s[8];
+  load8(reinterpret_cast<const T*>(a.g) + a.l_hi * layer + off, s);
+  for (long c = nchunks - 1; c >= 0; --c) {
+    store8(cin + c * layer + off, s);
+    float b[8], p[8];
+    load8(B + c * layer + off, b);
+    load8(A + c * a.d + ch, p);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s[i] = fmaf(p[i], s[i], b[i]);
+  }
+}
+
+inline bool use_chunked(long L, long N, long d, int norm_rms) {
+  // long chains and too few of them to fill the chip with one thread per vector
+  return !norm_rms && L >= 4 * SCAN_CHUNK && N * d / 8 < 256L * 1024;
+}
+
+template <typename T>
+hipError_t launch_scan_chunked(const ScanArgs& a, hipStream_t s) {
+  const long L = a.l_hi - a.l_lo;
+  const long nchunks = (L + SCAN_CHUNK - 1) / SCAN_CHUNK;
+  const long row_groups = (a.N + CH_ROWS - 1) / CH_ROWS;
+  const long layer = a.N * a.d;
+  float* A = a.chunk_ws + 2 * nchunks * layer;
+  const long threads = nchunks * row_groups * (a.d / 8);
+  const dim3 block(256), grid((unsigned)((threads + 255) / 256));
+  hipLaunchKernelGGL(scan_chunk_lambda_kernel, dim3((unsigned)((nchunks * a.d + 255) / 256)), block, 0, s, a, nchunks, A);
+  hipLaunchKernelGGL((scan_chunk_kernel<T, false>), grid, block, 0, s, a, nchunks, row_groups);
+  hipLaunchKernelGGL(scan_chunk_combine_kernel<T>, dim3((unsigned)((layer / 8 + 255) / 256)), block, 0, s, a, nchunks, A);
+  hipLaunchKernelGGL((scan_chunk_kernel<T, true>), grid, block, 0, s, a, nchunks, row_groups);
+  return hipGetLastError();
+}
+
 template <typename T>
 hipError_t launch_scan_t(const ScanArgs& a, hipStream_t s) {
   if (a.l_hi <= a.l_lo) return hipSuccess;
+  if (a.chunk_ws && use_chunked(a.l_hi - a.l_lo, a.N, a.d, a.norm_rms && a.dn)) return launch_scan_chunked<T>(a, s);
   if (a.norm_rms && a.dn) {
     const int nch = (int)((a.d + 511) / 512);
     dim3 grid((unsigned)((a.N + 3) / 4)), block(256);
@@ -183,6 +324,12 @@ hipError_t launch_scan_t(const ScanArgs& a, hipStream_t s) {
 }
 
 }  // namespace
+
+size_t scan_chunk_ws_bytes(long L, long N, long d, int norm_rms) {
+  if (!use_chunked(L, N, d, norm_rms)) return 0;
+  const long nchunks = (L + SCAN_CHUNK - 1) / SCAN_CHUNK;
+  return (size_t)(2 * nchunks * N * d + nchunks * d) * sizeof(float);
+}
 
 hipError_t launch_scan(int dtype, const ScanArgs& a, hipStream_t s) {
   return dtype == 0 ? launch_scan_t<float>(a, s) : launch_scan_t<bf16_t>(a, s);

@@ -49,6 +49,11 @@ CASES = {
                               d_in=128, ks=(0, 1, 2, 4)),
     "rnn_f32": synth.scaled(W["gated_rnn_contractive"], name="rnn_f32", dtype="f32", L=19, N=3, d=64, d_ff=64,
                             d_in=40, ks=(0, 2, 19)),
+    # long chains, few of them: the chunked form of the scan (a ragged last chunk and row group)
+    "rnn_long": synth.scaled(W["gated_rnn_contractive"], name="rnn_long", L=300, N=6, d=128, d_ff=128,
+                             d_in=64, ks=(0, 1, 3)),
+    "mlp_f32_deep": synth.scaled(W["mlp_small_f32"], name="mlp_f32_deep", L=270, N=3, d=64, d_ff=64,
+                                 w2_scale=0.1, ks=(0, 2)),
     "rnn_chaotic_small": synth.scaled(W["gated_rnn"], name="rnn_chaotic_small", L=130, N=4, d=512, d_ff=512,
                                       d_in=256, ks=(1, 2, 4)),
 }
@@ -115,7 +120,8 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
 
 
 @pytest.mark.parametrize("name", ["mlp_small_f32", "mlp_f32_ragged", "resnet_like_small", "resnet_like_odd",
-                                  "transformer_small", "deep_small", "rnn_small", "rnn_f32"])
+                                  "transformer_small", "deep_small", "rnn_small", "rnn_f32", "rnn_long",
+                                  "mlp_f32_deep"])
 def test_backward_end_to_end(B, name):
     """Own forward on each side, then Highway-BP at every k of the case, exact BP
     and the parameter gradients."""
