@@ -50,7 +50,10 @@ def algorithmic_work(w, k):
     vjp2 = per_block * blocks
     dw = 2.0 * per_block * L + (2.0 * N * L * dff * w.d_in if w.kind == "rnn" else 0.0)
     S = float(L) * N * d
-    streams_in = 1 + (1 if w.norm == "rms" else 0) + (1 if w.loss_every_state else 0)
+    # per iteration the scan reads dn (+ y with a norm; + e only when a norm sits between
+    # the block and the residual path: otherwise e was added by the second contraction)
+    e_in_scan = w.loss_every_state and w.norm == "rms"
+    streams_in = 1 + (1 if w.norm == "rms" else 0) + (1 if e_in_scan else 0)
     scan_iter = S * s * (streams_in + 1)
     scan_init = S * s * (1 + (1 if w.loss_every_state else 0))
     return {"vjp1": vjp1, "vjp2": vjp2, "dw": dw, "scan_bytes": scan_init + iters * scan_iter,
@@ -222,7 +225,16 @@ def main():
                                 "deep_large": 32, "gated_rnn": 2, "gated_rnn_contractive": 2}.get(w.name, 64)
         out["cpu_baseline"] = cpu_baseline(w, k, n)
 
-    print(json.dumps(out))
+    def finite(o):   # JSON has no NaN/Infinity: overflowed error figures become null
+        if isinstance(o, float):
+            return o if np.isfinite(o) else None
+        if isinstance(o, dict):
+            return {k: finite(v) for k, v in o.items()}
+        if isinstance(o, (list, tuple)):
+            return [finite(v) for v in o]
+        return o
+
+    print(json.dumps(finite(out)))
 
 
 if __name__ == "__main__":

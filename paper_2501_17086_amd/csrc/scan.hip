@@ -173,89 +173,88 @@ __global__ __launch_bounds__(256) void rmsnorm_fwd_kernel(const T* __restrict__ 
 //            writing g.
 // The same operator (A1,B1) o (A2,B2) = (A1 A2, B1 + A1 B2) composes chunks as
 // composes single states.  Each element is read twice and written once.
-// lambda is shared by the rows, so a thread walks ROWS rows of its channels at
-// once and reads each lambda row once for all of them.
 // ---------------------------------------------------------------------------
-constexpr int CH_ROWS = 4;
+// A workgroup of 256 threads owns (chunk, 64 channels, 32 rows): thread = (row, 8
+// channels).  The chunk's lambda rows for those channels are shared by all rows,
+// so they are staged once in LDS (16 KB) instead of being re-read per row.
+constexpr int CH_ROWS = 32;
 
-template <typename T, bool APPLY>
-__global__ __launch_bounds__(256) void scan_chunk_kernel(ScanArgs a, long nchunks, long row_groups) {
-  const long vecs = a.d / 8;
-  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= nchunks * row_groups * vecs) return;
-  const long v = idx % vecs;
-  const long rg = (idx / vecs) % row_groups;
-  const long c = idx / (vecs * row_groups);
-  const long ch = v * 8;
+// HAS_DN / HAS_E are compile-time so that the unrolled loop has no branches
+// around its loads and several steps' loads are in flight at once.
+template <typename T, bool APPLY, bool HAS_DN, bool HAS_E>
+__global__ __launch_bounds__(256) void scan_chunk_kernel(ScanArgs a, long nchunks) {
+  __shared__ float lam_s[SCAN_CHUNK][64];
+  const int tid = threadIdx.x;
+  const long c = blockIdx.y;                 // neighbouring workgroups take neighbouring channel slabs
+  const long ch0 = (long)blockIdx.x * 64;
+  const long row = (long)blockIdx.z * CH_ROWS + (tid >> 3);
+  const long ch = ch0 + (tid & 7) * 8;
   const long layer = a.N * a.d;
   const long l_bot = a.l_lo + c * SCAN_CHUNK;
   const long l_top = l_bot + SCAN_CHUNK < a.l_hi ? l_bot + SCAN_CHUNK : a.l_hi;
-  T* g = reinterpret_cast<T*>(a.g);
-  const T* dn = reinterpret_cast<const T*>(a.dn);
-  const T* e = reinterpret_cast<const T*>(a.e);
+  const int steps = (int)(l_top - l_bot);
+  T* __restrict__ g = reinterpret_cast<T*>(a.g);
+  const T* __restrict__ dn = reinterpret_cast<const T*>(a.dn);
+  const T* __restrict__ e = reinterpret_cast<const T*>(a.e);
   float* B = a.chunk_ws;                                   // [nchunks][N][d]
   float* cin = a.chunk_ws + nchunks * layer;               // [nchunks][N][d]
 
-  float carry[CH_ROWS][8];
-  long off[CH_ROWS];
-  bool on[CH_ROWS];
-#pragma unroll
-  for (int r = 0; r < CH_ROWS; ++r) {
-    const long row = rg * CH_ROWS + r;
-    on[r] = row < a.N;
-    off[r] = row * a.d + ch;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) carry[r][i] = 0.f;
-    if (APPLY && on[r]) load8(cin + c * layer + off[r], carry[r]);
+  // stage lambda[l_bot .. l_top)[ch0 .. ch0+63] (ones where there is none)
+  for (int i = tid; i < steps * 16; i += 256) {
+    const int s = i >> 4, q = (i & 15) * 4;
+    float4 v = make_float4(1.f, 1.f, 1.f, 1.f);
+    if (a.lambda && ch0 + q < a.d) v = *reinterpret_cast<const float4*>(a.lambda + (l_bot + s) * a.d + ch0 + q);
+    *reinterpret_cast<float4*>(&lam_s[s][q]) = v;
   }
-#pragma unroll 4
-  for (long l = l_top - 1; l >= l_bot; --l) {
-    float lam[8];
-    if (a.lambda) {
-      load8(a.lambda + l * a.d + ch, lam);
-    } else {
+  __syncthreads();
+  if (!APPLY && blockIdx.z == 0 && tid < 64 && ch0 + tid < a.d) {   // A = product of lambda over the chunk
+    float p = 1.f;
+    for (int s = 0; s < steps; ++s) p *= lam_s[s][tid];
+    a.chunk_ws[2 * nchunks * layer + c * a.d + ch0 + tid] = p;
+  }
+  if (row >= a.N || ch >= a.d) return;
+
+  const long off = row * a.d + ch;
+  float carry[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) lam[i] = 1.f;
+  for (int i = 0; i < 8; ++i) carry[i] = 0.f;
+  if (APPLY) load8(cin + c * layer + off, carry);
+  // batches of 8 steps: all their loads are issued before the first value is used
+  constexpr int BATCH = 8;
+  for (int s0 = steps; s0 > 0; s0 -= BATCH) {
+    Raw8<T> rb[BATCH], re[BATCH];
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j) {
+      const int s = s0 - 1 - j;
+      if (s >= 0) {
+        if (HAS_DN) rb[j].load(dn + (l_bot + s) * layer + off);
+        if (HAS_E) re[j].load(e + (l_bot + s) * layer + off);
+      }
     }
 #pragma unroll
-    for (int r = 0; r < CH_ROWS; ++r) {
-      if (!on[r]) continue;
-      float b[8];
-      if (dn) {
-        load8(dn + l * layer + off[r], b);
+    for (int j = 0; j < BATCH; ++j) {
+      const int s = s0 - 1 - j;
+      if (s < 0) break;
+      float b[8], lam[8];
+      if (HAS_DN) {
+        rb[j].unpack(b);
       } else {
 #pragma unroll
         for (int i = 0; i < 8; ++i) b[i] = 0.f;
       }
-      if (e) {
+      if (HAS_E) {
         float t[8];
-        load8(e + l * layer + off[r], t);
+        re[j].unpack(t);
 #pragma unroll
         for (int i = 0; i < 8; ++i) b[i] += t[i];
       }
+      load8(&lam_s[s][(tid & 7) * 8], lam);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) carry[r][i] = fmaf(lam[i], carry[r][i], b[i]);
-      if (APPLY) store8(g + l * layer + off[r], carry[r]);
+      for (int i = 0; i < 8; ++i) carry[i] = fmaf(lam[i], carry[i], b[i]);
+      if (APPLY) store8(g + (l_bot + s) * layer + off, carry);
     }
   }
-  if (!APPLY) {
-#pragma unroll
-    for (int r = 0; r < CH_ROWS; ++r)
-      if (on[r]) store8(B + c * layer + off[r], carry[r]);
-  }
-}
-
-// A[c][ch] = product of lambda over chunk c (ones without lambda)
-__global__ __launch_bounds__(256) void scan_chunk_lambda_kernel(ScanArgs a, long nchunks, float* __restrict__ A) {
-  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= nchunks * a.d) return;
-  const long ch = idx % a.d, c = idx / a.d;
-  const long l_bot = a.l_lo + c * SCAN_CHUNK;
-  const long l_top = l_bot + SCAN_CHUNK < a.l_hi ? l_bot + SCAN_CHUNK : a.l_hi;
-  float p = 1.f;
-  if (a.lambda)
-    for (long l = l_top - 1; l >= l_bot; --l) p *= a.lambda[l * a.d + ch];
-  A[idx] = p;
+  if (!APPLY) store8(B + c * layer + off, carry);
 }
 
 template <typename T>
@@ -269,13 +268,25 @@ __global__ __launch_bounds__(256) void scan_chunk_combine_kernel(ScanArgs a, lon
   float* cin = a.chunk_ws + nchunks * layer;
   float s[8];
   load8(reinterpret_cast<const T*>(a.g) + a.l_hi * layer + off, s);
-  for (long c = nchunks - 1; c >= 0; --c) {
-    store8(cin + c * layer + off, s);
-    float b[8], p[8];
-    load8(B + c * layer + off, b);
-    load8(A + c * a.d + ch, p);
+  constexpr int BATCH = 8;
+  for (long c0 = nchunks; c0 > 0; c0 -= BATCH) {
+    Raw8<float> rb[BATCH], rp[BATCH];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) s[i] = fmaf(p[i], s[i], b[i]);
+    for (int j = 0; j < BATCH; ++j) {
+      const long c = c0 - 1 - j;
+      if (c >= 0) { rb[j].load(B + c * layer + off); rp[j].load(A + c * a.d + ch); }
+    }
+#pragma unroll
+    for (int j = 0; j < BATCH; ++j) {
+      const long c = c0 - 1 - j;
+      if (c < 0) break;
+      store8(cin + c * layer + off, s);
+      float b[8], p[8];
+      rb[j].unpack(b);
+      rp[j].unpack(p);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s[i] = fmaf(p[i], s[i], b[i]);
+    }
   }
 }
 
@@ -288,15 +299,24 @@ template <typename T>
 hipError_t launch_scan_chunked(const ScanArgs& a, hipStream_t s) {
   const long L = a.l_hi - a.l_lo;
   const long nchunks = (L + SCAN_CHUNK - 1) / SCAN_CHUNK;
-  const long row_groups = (a.N + CH_ROWS - 1) / CH_ROWS;
   const long layer = a.N * a.d;
   float* A = a.chunk_ws + 2 * nchunks * layer;
-  const long threads = nchunks * row_groups * (a.d / 8);
-  const dim3 block(256), grid((unsigned)((threads + 255) / 256));
-  hipLaunchKernelGGL(scan_chunk_lambda_kernel, dim3((unsigned)((nchunks * a.d + 255) / 256)), block, 0, s, a, nchunks, A);
-  hipLaunchKernelGGL((scan_chunk_kernel<T, false>), grid, block, 0, s, a, nchunks, row_groups);
+  const dim3 block(256);
+  const dim3 grid((unsigned)((a.d + 63) / 64), (unsigned)nchunks, (unsigned)((a.N + CH_ROWS - 1) / CH_ROWS));
+  const int var = (a.dn ? 1 : 0) | (a.e ? 2 : 0);
+  switch (var) {
+    case 1: hipLaunchKernelGGL((scan_chunk_kernel<T, false, true, false>), grid, block, 0, s, a, nchunks); break;
+    case 2: hipLaunchKernelGGL((scan_chunk_kernel<T, false, false, true>), grid, block, 0, s, a, nchunks); break;
+    case 3: hipLaunchKernelGGL((scan_chunk_kernel<T, false, true, true>), grid, block, 0, s, a, nchunks); break;
+    default: hipLaunchKernelGGL((scan_chunk_kernel<T, false, false, false>), grid, block, 0, s, a, nchunks); break;
+  }
   hipLaunchKernelGGL(scan_chunk_combine_kernel<T>, dim3((unsigned)((layer / 8 + 255) / 256)), block, 0, s, a, nchunks, A);
-  hipLaunchKernelGGL((scan_chunk_kernel<T, true>), grid, block, 0, s, a, nchunks, row_groups);
+  switch (var) {
+    case 1: hipLaunchKernelGGL((scan_chunk_kernel<T, true, true, false>), grid, block, 0, s, a, nchunks); break;
+    case 2: hipLaunchKernelGGL((scan_chunk_kernel<T, true, false, true>), grid, block, 0, s, a, nchunks); break;
+    case 3: hipLaunchKernelGGL((scan_chunk_kernel<T, true, true, true>), grid, block, 0, s, a, nchunks); break;
+    default: hipLaunchKernelGGL((scan_chunk_kernel<T, true, false, false>), grid, block, 0, s, a, nchunks); break;
+  }
   return hipGetLastError();
 }
 
