@@ -17,6 +17,7 @@ tokens; in the RNN lambda_t = sigmoid(N(3, 0.5^2)) is constant data.
 """
 from __future__ import annotations
 
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, replace
 from typing import Dict, Optional
 
@@ -125,11 +126,11 @@ def make_lambda(w: Workload) -> Optional[np.ndarray]:
     return (1.0 / (1.0 + np.exp(-a.astype(np.float64)))).astype(np.float32)
 
 
-def make_inputs(w: Workload, tokens: Optional[slice] = None) -> Dict[str, Optional[np.ndarray]]:
+def make_inputs(w: Workload, tokens=None) -> Dict[str, Optional[np.ndarray]]:
     """All tensors of a workload as fp32 numpy arrays holding storage-representable
-    values.  `tokens` restricts the token axis (rnn: the batch axis) to a slice;
-    the full tensors are drawn and then cut, so a subset sees the same values
-    as the full run.
+    values.  `tokens` restricts the token axis (rnn: the batch axis) to a slice
+    or an index array; the full tensors are drawn and then cut, so a subset sees
+    the same values as the full run.
 
     Keys: W1, W2 (mlp: [L,...]; rnn: shared), U (rnn), lam, x0 [N,d],
     xin [L,N,d_in] (rnn), e ([N,d], or [L+1,N,d] with e[0] = 0 when every state
@@ -140,8 +141,11 @@ def make_inputs(w: Workload, tokens: Optional[slice] = None) -> Dict[str, Option
     if w.kind == "mlp":
         W1 = np.empty((w.L, w.d_ff, w.d), np.float32)
         W2 = np.empty((w.L, w.d, w.d_ff), np.float32)
-        for l in range(w.L):
+
+        def fill(l):   # every block has its own generator key: order of evaluation is free
             W1[l], W2[l] = weights_block(w, l)
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            list(ex.map(fill, range(w.L)))
         out["U"] = None
         out["xin"] = None
     else:
