@@ -29,6 +29,11 @@ PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X dense bf16
 PEAK_FP32_VECTOR_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch (read + written) measured with rocprofv3's FETCH_SIZE and WRITE_SIZE counters, scaled by
+# what the same counters read for a plain 1 GiB copy (x2.00 and x1.00): profiles/bench_resnet_like_hbm_traffic.txt.
+# Only for the default workload; other workloads report null.
+MEASURED_TRAFFIC = {"resnet_like": {"vjp1": 3.209e9, "vjp2": 1.634e9, "dw": 1.478e9, "scan": 0.823e9}}
+
 
 def storage_bytes(w):
     return 2 if w.dtype == "bf16" else 4
@@ -129,6 +134,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the k = 1..4 / exact table")
     ap.add_argument("--cpu-tokens", type=int, default=0, help="token rows of the oracle sample (0 = auto)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run plain 1 GiB device copies and exit (reference for rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (sharding is described in DESIGN.md)",
@@ -141,6 +148,19 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     B.lib()   # fail loudly if the HIP library is not built
+
+    if args.copy_calibration:
+        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")      # 1 GiB
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 10
+        print(json.dumps({"copy_bytes_read": a.numel() * 4, "copy_bytes_written": a.numel() * 4, "copies": 10,
+                          "GBps_read_plus_write": 2 * a.numel() * 4 / dt / 1e9}))
+        return
 
     w = synth.WORKLOADS[args.workload]
     k = args.k
@@ -176,7 +196,8 @@ def main():
         ach = work[cls] / t / 1e12 if t > 0 else 0.0
         peak = PEAK_MFMA_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_VECTOR_TFLOPS
         return {"bound": "mfma" if w.dtype == "bf16" else "alu", "achieved": ach, "peak": peak,
-                "unit": "TFLOP/s", "frac": ach / peak, "traffic": None, "kernel_class": cls,
+                "unit": "TFLOP/s", "frac": ach / peak, "traffic": MEASURED_TRAFFIC.get(w.name, {}).get(cls),
+                "kernel_class": cls,
                 "ms_per_step": ms[cls], "launches_per_step": launches[cls],
                 "avg_launch_ms": ms[cls] / max(launches[cls], 1)}
 
@@ -184,7 +205,8 @@ def main():
     t_scan = ms["scan"] * 1e-3
     ach = work["scan_bytes"] / t_scan / 1e9 if t_scan > 0 else 0.0
     roofs["scan"] = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": ach / PEAK_HBM_GBS, "traffic": None, "kernel_class": "scan",
+                     "frac": ach / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC.get(w.name, {}).get("scan"),
+                     "kernel_class": "scan",
                      "ms_per_step": ms["scan"], "launches_per_step": launches["scan"],
                      "avg_launch_ms": ms["scan"] / max(launches["scan"], 1)}
     dominant = max(("vjp1", "vjp2", "dw", "scan"), key=lambda c: ms[c])
