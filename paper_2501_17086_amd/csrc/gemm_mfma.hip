@@ -1,21 +1,33 @@
 // bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16, fp32
 // accumulate) for the VJP and parameter-gradient contractions.
 //
-// Shape of the kernel
-//   workgroup   8 wavefronts (2 x 4), output tile 256 x 256, one workgroup per
-//               CU; a wavefront owns 128 x 64 = 4 x 2 MFMA blocks of 32 x 32 (128
-//               accumulator registers per lane).  The 256 x 256 tile is what
-//               keeps the L2 -> LDS stream (the measured limiter, ~14 TB/s over
-//               the chip) below the MFMA rate: 128 flop per byte copied.
+// Shape of the kernels
+//   workgroup   8 wavefronts, output tile 256 x 256, one workgroup per CU; a
+//               wavefront owns 128 x 64 = 4 x 2 MFMA blocks of 32 x 32 (128
+//               accumulator registers per lane).  The 256 x 256 tile keeps the
+//               global -> LDS stream, which is what bounds the kernel (measured:
+//               the copies alone take 0.6 of the time the MFMAs alone take),
+//               at 128 flop per byte copied.
 //   persistent  one workgroup per CU walks a list of tiles.  The K slices of all
 //               its tiles form one stream through a ring of 4 LDS stages, so the
 //               first slices of the next tile are already in flight while the
 //               current tile's epilogue runs: no per-tile fill latency.
+//   two phases  the wavefronts form two groups of four (one wavefront of each
+//               group per SIMD).  A wavefront alternates between a load phase
+//               (issue its share of the global -> LDS copy of the slice three
+//               ahead, read all fragments of the current slice from LDS, store
+//               a finished tile) and a compute phase (16 MFMAs back to back
+//               at raised priority), with a workgroup barrier after each
+//               phase.  The second group runs one barrier behind the first, so
+//               on every SIMD one wavefront multiplies while the other one
+//               loads: the LDS latency is paid once per slice, in bulk, and
+//               hidden behind the other group's MFMAs.  A wavefront issues at
+//               most one instruction every four cycles, so the load phase has to
+//               be short in instructions to fit under the 512 MFMA cycles of the
+//               other group: the lean kernel's is about 50.
 //   K pipeline  slices of 32 (32 KB per stage); a slice is copied global -> LDS
-//               directly (global_load_lds_dwordx4, no staging registers) up to
-//               three slices ahead of the one being multiplied; one barrier per
-//               slice.  Fragments of the next MFMA group are read from LDS
-//               while the current group's MFMAs run.
+//               directly (global_load_lds_dwordx4, no staging registers), issued
+//               from inline assembly so that the waits can be counted by hand.
 //   LDS layout  an operand tile sits in LDS in the orientation it has in memory:
 //                 KC  contraction index contiguous, [rows][32 k]: a lane's 8
 //                     k-values are one 16-byte ds_read;
@@ -31,24 +43,35 @@
 //   pairings    NN (A KC, B RC)  da = g W2, dn = da W1   (weights as stored)
 //               TN (A RC, B RC)  dW2 = g^T z, dW1 = da^T y, dU
 //               NT (A KC, B KC)  forward  a = y W1^T, out = z W2^T
-//   edges       chunks outside the matrix are copied from a zero-filled device
-//               array, rows/columns outside are not stored: any size whose
-//               contiguous dimensions are multiples of 8 is covered.
-//   epilogue    accumulators pass through 4 KB of wave-private LDS (16 rows at a
-//               time, XOR-swizzled) so that every global access (output and the
-//               fused element-wise operand) is a 16-byte row-contiguous access.
+//   accumulator the MFMAs are issued with the operands exchanged (B fragment
+//               first), which leaves a lane with one output row and groups of
+//               four consecutive output columns.
+//   two kernels lean: every tile inside the matrix, K a multiple of 32 per
+//               split, the hot epilogues.  Straight-line: its epilogues issue a
+//               known number of memory operations, so the copies stay counted
+//               across them.  bf16 tiles leave through 4 KB of wave-private LDS
+//               so that every global access covers whole 128-byte lines; fp32
+//               tiles (parameter gradients, one per 256+ slices) are stored
+//               from the registers, 16 bytes per lane.
+//               general: any size whose contiguous dimensions are multiples of
+//               8 and every epilogue; chunks outside the matrix are copied from
+//               a zero-filled device array, rows/columns outside are not
+//               stored, the pipeline drains after a tile's epilogue.
 //   tile order  workgroup ids are dealt round-robin to the 8 XCDs (one L2
 //               each): id % 8 selects a contiguous eighth of the tile list,
 //               the workgroups of an XCD take consecutive tiles of it, and the
 //               list walks 8 x 8 blocks of tiles, so the tiles an XCD works on
 //               at one time share operand panels.
 #include "hbp_common.h"
+#include <type_traits>
 
 namespace hbp {
 
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float float2v __attribute__((ext_vector_type(2)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef short short8v __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
@@ -57,9 +80,7 @@ constexpr int BM = 256, BN = 256, BK = 32, NST = 4, NW = 8, NTHR = 64 * NW;
 constexpr int A_BYTES = BM * BK * 2;            // 16 KB
 constexpr int B_BYTES = BN * BK * 2;            // 16 KB
 constexpr int STAGE_BYTES = A_BYTES + B_BYTES;  // 32 KB
-constexpr int RING_BYTES = NST * STAGE_BYTES;   // 128 KB
-constexpr int EPI_WAVE_BYTES = 16 * 64 * 4;     // 16 rows x 64 fp32 per wave
-constexpr int LDS_BYTES = RING_BYTES + NW * EPI_WAVE_BYTES;  // 160 KB: the whole CU
+constexpr int LDS_BYTES = NST * STAGE_BYTES;    // 128 KB
 constexpr int GROUP_M = 8;                      // tile rows per block of the tile walk
 constexpr int PER_SLICE = 4;                    // copies per wave per slice (2 for A, 2 for B)
 
@@ -67,34 +88,32 @@ __device__ uint4 g_zero_chunks[64];  // source of out-of-range chunks (zero-init
 
 // 16 bytes per lane, global -> LDS at lds_base + lane * 16.  lds_base is
 // wave-uniform.  The compiler does not see this write to LDS: callers order it
-// against LDS reads with wait_vm() + __syncthreads().
+// against LDS reads with a counted wait + a workgroup barrier.
 __device__ __forceinline__ void dma16(const void* gptr, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off\n"
                :: "v"(gptr), "s"(lds_base) : "memory");
 }
 // the same with a wave-uniform 64-bit base and a 32-bit unsigned byte offset per lane
-__device__ __forceinline__ void dma16_s(unsigned off, const void* sbase, unsigned lds_base) {
+__device__ __forceinline__ void dma16_s(unsigned off, const void* sbase_in, unsigned lds_base) {
+  // (the base is uniform by construction; say so where the register allocator has moved it to vector registers)
+  const unsigned long long b = reinterpret_cast<unsigned long long>(sbase_in);
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)b);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(b >> 32));
+  const unsigned long long u = (unsigned long long)lo | ((unsigned long long)hi << 32);
+  const void* sbase = reinterpret_cast<const void*>(u);
   asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n"
                :: "v"(off), "s"(sbase), "s"(lds_base) : "memory");
 }
+// at most N vector-memory operations outstanding (N <= 63), and no LDS operation
 template <int N>
-__device__ __forceinline__ void wait_vm() {   // at most N vector-memory operations outstanding
+__device__ __forceinline__ void wait_vm_lds() {
+  __builtin_amdgcn_s_waitcnt(0x0070 | (N & 15) | ((N >> 4) << 14));
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
-// at most n slices' worth of this wave's copies outstanding
-__device__ __forceinline__ void wait_slices(int n) {
-  if (n >= 2) wait_vm<2 * PER_SLICE>();
-  else if (n == 1) wait_vm<PER_SLICE>();
-  else wait_vm<0>();
-}
 
-// Hides a value's origin from the optimiser: addresses derived from a laundered
-// lane id are rebuilt where they are used instead of being hoisted out of the
-// persistent loop and kept (or spilled) across the MFMA blocks.
-__device__ __forceinline__ int launder(int v) {
-  asm volatile("" : "+v"(v));
-  return v;
-}
 // Byte offset of this lane's chunk of copy i (of 2) relative to the first
 // element of the tile's slice (the same for every slice and tile of a launch).
 template <bool KC>
@@ -116,8 +135,7 @@ __device__ __forceinline__ unsigned lane_src_offset(long ld, int i, int wave, in
 // contraction index.
 template <bool KC>
 __device__ __forceinline__ void issue_tile(const bf16_t* base, long ld, long rows_left, long k0, long k_end,
-                                           unsigned lds_tile, int wave, int lane_in) {
-  const int lane = launder(lane_in);
+                                           unsigned lds_tile, int wave, int lane) {
   const bf16_t* slice = KC ? base + k0 : base + k0 * ld;   // uniform
 #pragma unroll
   for (int i = 0; i < 256 / 16 / NW; ++i) {
@@ -168,6 +186,27 @@ __device__ __forceinline__ float gelu_grad_f(float a) {
   return 0.5f * (1.0f + erff(a * 0.70710678118654752440f)) + a * __expf(-0.5f * a * a) * 0.39894228040143267794f;
 }
 
+// 4 consecutive elements <-> 4 floats
+__device__ __forceinline__ unsigned pack2(float a, float b) {   // round to nearest even (v_cvt_pk_bf16_f32)
+  const float2v v = {a, b};
+  return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ void unpack4(uint2 r, float (&o)[4]) {
+  o[0] = __uint_as_float(r.x << 16); o[1] = __uint_as_float(r.x & 0xFFFF0000u);
+  o[2] = __uint_as_float(r.y << 16); o[3] = __uint_as_float(r.y & 0xFFFF0000u);
+}
+__device__ __forceinline__ void load4(const bf16_t* p, float (&o)[4]) { unpack4(*reinterpret_cast<const uint2*>(p), o); }
+__device__ __forceinline__ void load4(const float* p, float (&o)[4]) {
+  const float4 a = *reinterpret_cast<const float4*>(p);
+  o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+}
+__device__ __forceinline__ void store4(bf16_t* p, const float (&v)[4]) {
+  *reinterpret_cast<uint2*>(p) = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+}
+__device__ __forceinline__ void store4(float* p, const float (&v)[4]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+}
+
 // coordinates of one output tile and its share of the contraction
 struct TileCoord {
   long batch, m0, n0, k_begin, k_end;
@@ -195,32 +234,24 @@ __device__ __forceinline__ TileCoord decode_tile(const GemmArgs& g, int t, int t
   return c;
 }
 
-// Epilogue specialisations.  For tiles that lie fully inside the matrix the hot
-// epilogues are straight-line code: the number of vector-memory operations they
-// issue is then a constant, which (a) lets the compiler wait for the fused
-// operand with an exact count instead of draining the stores before it, and
-// (b) lets the K pipeline count its copies across the epilogue.  Everything
-// else (edge tiles, forward-pass epilogues) takes the general, guarded path.
+// Epilogues of the lean kernel
 enum FastEpi {
-  FAST_NONE = 0,       // general path only (ACT: with the activation epilogues)
   FAST_STORE = 1,      // C(bf16) = acc
   FAST_STORE_F32 = 2,  // C(fp32) = acc, also the split-K partial sums
   FAST_MUL_AUX = 3,    // C(bf16) = acc * aux
   FAST_MUL_1MZ2 = 4,   // C(bf16) = acc * (1 - aux^2)
   FAST_ADD_AUX = 5     // C(bf16) = acc + aux
 };
-template <int FAST> struct FastOps {   // vector-memory operations per wave of one fast epilogue
-  static constexpr int value = FAST == FAST_STORE ? 16 : FAST == FAST_STORE_F32 ? 32 : FAST == FAST_NONE ? 0 : 32;
-};
 
-template <bool A_KC, bool B_KC, bool ACT, int FAST>
+template <bool A_KC, bool B_KC, bool ACT>
 __global__ __launch_bounds__(NTHR, 1) void gemm_mfma_kernel(GemmArgs g, int tiles_m, int tiles_n, long total,
                                                             long per_xcd) {
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm0 = (wave >> 2) * 128, wn0 = (wave & 3) * 64;
+  const int grp = wave >> 2;           // phase group
+  const int wm0 = grp * 128, wn0 = (wave & 3) * 64;
   const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
 
   // tiles of this workgroup: t_first, t_first + t_stride, ... below t_end
@@ -235,7 +266,7 @@ __global__ __launch_bounds__(NTHR, 1) void gemm_mfma_kernel(GemmArgs g, int tile
 
   // ---- producer: the next slice of the stream to copy ----
   // All of its state is wave-uniform (scalar registers) and advanced
-  // incrementally; the only per-lane values are four 32-bit source offsets.
+  // incrementally; the only per-lane values are two 32-bit source offsets.
   const bf16_t* pa = nullptr;  // producer tile's first row of A / first column of B
   const bf16_t* pb = nullptr;
   const bf16_t* qa = nullptr;  // the same, at the next slice to copy
@@ -293,328 +324,510 @@ __global__ __launch_bounds__(NTHR, 1) void gemm_mfma_kernel(GemmArgs g, int tile
   };
 
   // ---- consumer ----
+  // acc[i][j]: lane l, element r  <->  output row wm0 + 32 i + l % 32,
+  //                                    column wn0 + 32 j + 8 (r / 4) + 4 (l / 32) + r % 4
   float16v acc[4][2];
-  auto zero_acc = [&]() {
+  bf16x8 fa[4][2], fb[2][2];
+  auto load_frags = [&](const unsigned char* st) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) fb[j][h] = frag<B_KC>(st + A_BYTES, wn0 + 32 * j, 16 * h, lane);
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) fa[i][h] = frag<A_KC>(st, wm0 + 32 * i, 16 * h, lane);
+  };
+  auto mma_slice = [&](bool first) {
+    if (first) {     // first slice of a tile: the accumulators start from zero
+      const float16v zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j][0], fa[i][0], zero, 0, 0, 0);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j][0], fa[i][0], acc[i][j], 0, 0, 0);
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-  };
-  // A slice is consumed in four groups of 2 x 2 MFMA blocks (k half, row half).
-  // The A fragments of group g+1 are read from LDS while the MFMAs of group g
-  // run, and the first fragments of the next slice while the last group runs.
-  auto load_b = [&](const unsigned char* bt, int h, bf16x8 (&b)[2], int ln) {   // k half h of the slice
-#pragma unroll
-    for (int j = 0; j < 2; ++j) b[j] = frag<B_KC>(bt, wn0 + 32 * j, 16 * h, ln);
-  };
-  auto load_a = [&](const unsigned char* at, int grp, bf16x8 (&a)[2], int ln) {
-#pragma unroll
-    for (int ii = 0; ii < 2; ++ii) a[ii] = frag<A_KC>(at, wm0 + 32 * ((grp & 1) * 2 + ii), 16 * (grp >> 1), ln);
-  };
-  auto mma = [&](int grp, const bf16x8 (&a)[2], const bf16x8 (&b)[2][2]) {
-#pragma unroll
-    for (int ii = 0; ii < 2; ++ii)
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int i = (grp & 1) * 2 + ii;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ii], b[grp >> 1][j], acc[i][j], 0, 0, 0);
-      }
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j][1], fa[i][1], acc[i][j], 0, 0, 0);
   };
 
-  // ---- epilogue of one tile (wave-private; no workgroup barrier inside) ----
-  float* stage = reinterpret_cast<float*>(smem + RING_BYTES + wave * EPI_WAVE_BYTES);
+  // ---- epilogue of one tile, general form: every access guarded, every mode ----
   auto epilogue = [&](const TileCoord& tc) {
-    // (addresses are rebuilt from the lane id per tile; see launder())
-    const int le = launder(lane);
-    const int er = le >> 3;         // row within a group of 8
-    const int ec = (le & 7) * 8;    // first of 8 columns
-    const long col = tc.n0 + wn0 + ec;
-    const bool col_ok = col < g.N;
+    const int rl = lane & 31, ch = (lane >> 5) * 4;
     const float* lam = g.lambda ? g.lambda + tc.batch * g.lambda_sb : nullptr;
-    const bool use_aux = g.split_k == 1 && (g.mode == EPI_MUL_AUX || g.mode == EPI_MUL_1MZ2 ||
-                                            g.mode == EPI_RESID || g.mode == EPI_ADD_AUX);
+    const bool use_aux = g.mode == EPI_MUL_AUX || g.mode == EPI_MUL_1MZ2 || g.mode == EPI_RESID ||
+                         g.mode == EPI_ADD_AUX;
     const bf16_t* aux = reinterpret_cast<const bf16_t*>(g.aux) + tc.batch * g.aux_sb;
-    uint4 auxv[2][4];
-    auto fetch_aux = [&](int i, uint4 (&dst)[4]) {   // the fused operand of 32 rows: 4 x 16 bytes per lane
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const long row = tc.m0 + wm0 + 32 * i + er + 8 * q;
-        if (use_aux && row < g.M && col_ok)
-          dst[q] = *reinterpret_cast<const uint4*>(aux + row * g.ldc + col);
-        else
-          dst[q] = make_uint4(0u, 0u, 0u, 0u);
-      }
-    };
-    fetch_aux(0, auxv[0]);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      if (i + 1 < 4) fetch_aux(i + 1, auxv[(i + 1) & 1]);
+      const long row = tc.m0 + wm0 + 32 * i + rl;
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {             // rows 16h .. 16h+15 of the 32: accumulator elements 8h .. 8h+7
+      for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int q = 0; q < 4; ++q) {
+          const long col = tc.n0 + wn0 + 32 * j + 8 * q + ch;
+          if (row >= g.M || col >= g.N) continue;
+          float v[4];
 #pragma unroll
-          for (int rr = 0; rr < 8; ++rr) {
-            const int r = 8 * h + rr;
-            const int lr = ((r >> 2) & 1) * 8 + (lane >> 5) * 4 + (r & 3);
-            const int c = j * 32 + (lane & 31);
-            const int sw = (lr & 1) | (((lr >> 2) & 1) << 3);
-            stage[lr * 64 + ((((c >> 2) ^ sw) << 2) | (c & 3))] = acc[i][j][r];
-          }
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int q2 = 0; q2 < 2; ++q2) {
-          const int lr = er + 8 * q2;
-          const int sw = (lr & 1) | (((lr >> 2) & 1) << 3);
-          const long row = tc.m0 + wm0 + 32 * i + 16 * h + lr;
-          float v[8];
-          {
-            const float4 lo = *reinterpret_cast<const float4*>(stage + lr * 64 + ((((ec >> 2)) ^ sw) << 2));
-            const float4 hi = *reinterpret_cast<const float4*>(stage + lr * 64 + ((((ec >> 2) + 1) ^ sw) << 2));
-            v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w;
-            v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
-          }
-          if (row >= g.M || !col_ok) continue;
+          for (int x = 0; x < 4; ++x) v[x] = acc[i][j][4 * q + x];
           const long off = row * g.ldc + col;
           if (g.split_k > 1) {
-            float* P = reinterpret_cast<float*>(g.C) + ((long)tc.split * g.batch + tc.batch) * g.c_sb + off;
-            store8(P, v);
+            store4(reinterpret_cast<float*>(g.C) + ((long)tc.split * g.batch + tc.batch) * g.c_sb + off, v);
             continue;
           }
           if (g.addf) {
-            float t8[8];
-            load8(g.addf + tc.batch * g.addf_sb + off, t8);
+            float t[4];
+            load4(g.addf + tc.batch * g.addf_sb + off, t);
 #pragma unroll
-            for (int x = 0; x < 8; ++x) v[x] += t8[x];
+            for (int x = 0; x < 4; ++x) v[x] += t[x];
           }
-          float t8[8];
-          {
-            const uint4 a4 = auxv[i & 1][2 * h + q2];
-            const unsigned int w4[4] = {a4.x, a4.y, a4.z, a4.w};
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-              t8[2 * x] = __uint_as_float(w4[x] << 16);
-              t8[2 * x + 1] = __uint_as_float(w4[x] & 0xFFFF0000u);
-            }
-          }
+          float t[4] = {0.f, 0.f, 0.f, 0.f};
+          if (use_aux) load4(aux + off, t);
           switch (g.mode) {
             case EPI_MUL_AUX:
 #pragma unroll
-              for (int x = 0; x < 8; ++x) v[x] *= t8[x];
+              for (int x = 0; x < 4; ++x) v[x] *= t[x];
               break;
             case EPI_MUL_1MZ2:
 #pragma unroll
-              for (int x = 0; x < 8; ++x) v[x] *= (1.f - t8[x] * t8[x]);
+              for (int x = 0; x < 4; ++x) v[x] *= (1.f - t[x] * t[x]);
               break;
-            case EPI_ACT_GELU: if (ACT) {
-              float d8[8];
+            case EPI_ACT_GELU:
+              if (ACT) {
+                float d[4];
 #pragma unroll
-              for (int x = 0; x < 8; ++x) { d8[x] = gelu_grad_f(v[x]); v[x] = gelu_f(v[x]); }
-              store8(reinterpret_cast<bf16_t*>(g.out2) + tc.batch * g.out2_sb + off, d8);
+                for (int x = 0; x < 4; ++x) { d[x] = gelu_grad_f(v[x]); v[x] = gelu_f(v[x]); }
+                store4(reinterpret_cast<bf16_t*>(g.out2) + tc.batch * g.out2_sb + off, d);
+              }
               break;
-            }
             case EPI_ACT_TANH:
               if (ACT) {
 #pragma unroll
-                for (int x = 0; x < 8; ++x) v[x] = tanhf(v[x]);
+                for (int x = 0; x < 4; ++x) v[x] = tanhf(v[x]);
               }
               break;
             case EPI_RESID:
               if (lam) {
-                float l8[8];
-                load8(lam + col, l8);
+                float l4[4];
+                load4(lam + col, l4);
 #pragma unroll
-                for (int x = 0; x < 8; ++x) v[x] = fmaf(l8[x], t8[x], v[x]);
+                for (int x = 0; x < 4; ++x) v[x] = fmaf(l4[x], t[x], v[x]);
               } else {
 #pragma unroll
-                for (int x = 0; x < 8; ++x) v[x] += t8[x];
+                for (int x = 0; x < 4; ++x) v[x] += t[x];
               }
               break;
             case EPI_ADD_AUX:
 #pragma unroll
-              for (int x = 0; x < 8; ++x) v[x] += t8[x];
+              for (int x = 0; x < 4; ++x) v[x] += t[x];
               break;
             default: break;
           }
           if (g.c_is_f32)
-            store8(reinterpret_cast<float*>(g.C) + tc.batch * g.c_sb + off, v);
+            store4(reinterpret_cast<float*>(g.C) + tc.batch * g.c_sb + off, v);
           else
-            store8(reinterpret_cast<bf16_t*>(g.C) + tc.batch * g.c_sb + off, v);
+            store4(reinterpret_cast<bf16_t*>(g.C) + tc.batch * g.c_sb + off, v);
         }
-        __builtin_amdgcn_wave_barrier();
-      }
-    }
-  };
-
-  // Straight-line epilogue for a tile fully inside the matrix (FAST != 0).
-  auto epilogue_fast = [&](const TileCoord& tc) {
-    const int le = launder(lane);
-    const int er = le >> 3;
-    const int ec = (le & 7) * 8;
-    constexpr bool HAS_AUX = FAST == FAST_MUL_AUX || FAST == FAST_MUL_1MZ2 || FAST == FAST_ADD_AUX;
-    const long off0 = (tc.m0 + wm0 + er) * g.ldc + tc.n0 + wn0 + ec;   // this lane's first element
-    const bf16_t* aux = reinterpret_cast<const bf16_t*>(g.aux) + tc.batch * g.aux_sb + off0;
-    const long cb = g.split_k > 1 ? ((long)tc.split * g.batch + tc.batch) * g.c_sb : tc.batch * g.c_sb;
-    float* cf = reinterpret_cast<float*>(g.C) + cb + off0;
-    bf16_t* ch = reinterpret_cast<bf16_t*>(g.C) + cb + off0;
-    uint4 auxv[2][4];
-    if (HAS_AUX) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) auxv[0][q] = *reinterpret_cast<const uint4*>(aux + (long)(8 * q) * g.ldc);
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (HAS_AUX && i + 1 < 4) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-          auxv[(i + 1) & 1][q] = *reinterpret_cast<const uint4*>(aux + (long)(32 * (i + 1) + 8 * q) * g.ldc);
-      }
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-          for (int rr = 0; rr < 8; ++rr) {
-            const int r = 8 * h + rr;
-            const int lr = ((r >> 2) & 1) * 8 + (lane >> 5) * 4 + (r & 3);
-            const int c = j * 32 + (lane & 31);
-            const int sw = (lr & 1) | (((lr >> 2) & 1) << 3);
-            stage[lr * 64 + ((((c >> 2) ^ sw) << 2) | (c & 3))] = acc[i][j][r];
-          }
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int q2 = 0; q2 < 2; ++q2) {
-          const int lr = er + 8 * q2;
-          const int sw = (lr & 1) | (((lr >> 2) & 1) << 3);
-          float v[8];
-          {
-            const float4 lo = *reinterpret_cast<const float4*>(stage + lr * 64 + ((((ec >> 2)) ^ sw) << 2));
-            const float4 hi = *reinterpret_cast<const float4*>(stage + lr * 64 + ((((ec >> 2) + 1) ^ sw) << 2));
-            v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w;
-            v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
-          }
-          if (HAS_AUX) {
-            const uint4 a4 = auxv[i & 1][2 * h + q2];
-            const unsigned int w4[4] = {a4.x, a4.y, a4.z, a4.w};
-#pragma unroll
-            for (int x = 0; x < 4; ++x) {
-              const float t0 = __uint_as_float(w4[x] << 16), t1 = __uint_as_float(w4[x] & 0xFFFF0000u);
-              if (FAST == FAST_MUL_AUX) { v[2 * x] *= t0; v[2 * x + 1] *= t1; }
-              else if (FAST == FAST_ADD_AUX) { v[2 * x] += t0; v[2 * x + 1] += t1; }
-              else { v[2 * x] *= (1.f - t0 * t0); v[2 * x + 1] *= (1.f - t1 * t1); }
-            }
-          }
-          const long ro = (long)(32 * i + 16 * h + 8 * q2) * g.ldc;
-          if (FAST == FAST_STORE_F32) store8(cf + ro, v); else store8(ch + ro, v);
-        }
-        __builtin_amdgcn_wave_barrier();
-      }
     }
   };
 
   // ---- the stream ----
-  // Ring use while slice c is multiplied: stage c%4 is read, slice c+1 has
-  // landed (or is landing), slice c+2 is in flight, and the stage of slice c-1
-  // is refilled with slice c+3.  The hand-over to slice c+1 (wait for its
-  // copies, barrier, issue the next copy) sits in the middle of slice c's MFMAs,
-  // whose operands are already in registers, so the matrix cores have work
-  // while the waves meet at the barrier.
+  // Barrier intervals ("ticks"): group 0 loads slice c in tick 2c and multiplies
+  // it in tick 2c+1; group 1 does the same one tick later.  Slice c+3 is issued
+  // in the load phase of slice c into the stage of slice c-1, which the last
+  // reader (group 1, tick 2c-1) has left.  Every wave waits for its own share
+  // of slice c+1 at the end of its load phase of slice c, two barriers or more
+  // before the first reader of slice c+1 starts.
 #pragma unroll 1
   for (int s = 0; s < NST - 1; ++s) produce();
   if (issued == 0) return;
-
-  bf16x8 bcur[2][2], a0[2], a1[2];
-  wait_slices(issued - 1);     // slice 0 has landed (this wave's part)
-  __syncthreads();             // ... and every other wave's
-  load_b(smem + A_BYTES, 0, bcur[0], lane);
-  load_a(smem, 0, a0, lane);
+  if (issued >= 3) wait_vm<2 * PER_SLICE>(); else if (issued == 2) wait_vm<PER_SLICE>(); else wait_vm<0>();
+  __builtin_amdgcn_s_barrier();            // slice 0 is in LDS
+  if (grp == 1) __builtin_amdgcn_s_barrier();   // group 1 runs one tick behind
 
   int ct = t_first - t_stride; // consumer tile (moved onto its first tile below)
-  TileCoord cc;
+  TileCoord cc, ec;
   cc.KT = 0;
   int ck = 0;                  // slice of the consumer tile being multiplied
   int c_stage = 0;             // its stage
   int consumed = 0;            // its index in the stream
-  int epi_ops = -1;            // >= 0: an epilogue issued that many operations after the copies in flight;
-                               // -2, -1: none pending (two hand-overs after an epilogue still see its operations)
-  int epi_age = 0;
+  bool epi_pending = false;    // tile ec is complete in the accumulators
+  int epi_age = 0;             // load phases whose wait still sees the last epilogue's operations
   while (true) {
+    // ---------------- load phase ----------------
+    if (epi_pending) {
+      epilogue(ec);
+      epi_age = 2;
+      epi_pending = false;
+    }
     if (ck == cc.KT) {         // first slice of the next tile (same walk as the producer's)
       do {
         ct += t_stride;
         cc = decode_tile(g, ct, tiles_m, tiles_n);
       } while (cc.KT == 0);
       ck = 0;
-      zero_acc();
     }
-    // The fragment addresses are rebuilt from the lane id in every slice rather
-    // than kept in registers across the loop (the accumulators need the space).
-    const int ln = lane;
-    const unsigned char* at = smem + c_stage * STAGE_BYTES;
-    load_b(at + A_BYTES, 1, bcur[1], ln);
-    load_a(at, 1, a1, ln);
-    mma(0, a0, bcur);
-    __builtin_amdgcn_sched_barrier(0);
-    load_a(at, 2, a0, ln);
-    mma(1, a1, bcur);
-    __builtin_amdgcn_sched_barrier(0);
+    produce();                 // slice consumed + 3, into the stage of slice consumed - 1
+    load_frags(smem + c_stage * STAGE_BYTES);
     const bool has_next = consumed + 1 < issued;   // the producer is always ahead while slices remain
-    if (has_next) {
-      // slice consumed+1 has landed once only the slices issued after it are outstanding
-      // (for two hand-overs after an epilogue its operations are younger than the
-      // copies waited for: they are counted if their number is known, else drained)
-      const int younger = issued - consumed - 2;
-      if (epi_age > 0) {
-        if (epi_ops < 0) wait_vm<0>();
-        else if (younger >= 1) wait_vm<PER_SLICE + FastOps<FAST>::value>();
-        else wait_vm<FastOps<FAST>::value>();
+    {
+      // this wave's share of slice consumed+1 has landed once only what was issued after it is outstanding
+      const int younger = has_next ? issued - consumed - 2 : 0;
+      if (epi_age > 0) {        // the epilogue's stores and loads are not counted: drain
+        wait_vm_lds<0>();
         --epi_age;
       } else {
-        wait_slices(younger);
+        if (younger >= 2) wait_vm_lds<2 * PER_SLICE>();
+        else if (younger == 1) wait_vm_lds<PER_SLICE>();
+        else wait_vm_lds<0>();
       }
-      __syncthreads();   // every wave's part of it is in LDS; everyone is done reading slice consumed-1
-      produce();         // into the stage of slice consumed-1
     }
     __builtin_amdgcn_sched_barrier(0);
-    const bool tile_done = ++ck == cc.KT;
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    // ---------------- compute phase ----------------
+    __builtin_amdgcn_s_setprio(1);
+    mma_slice(ck == 0);
+    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    if (++ck == cc.KT) { epi_pending = true; ec = cc; }
     if (++c_stage == NST) c_stage = 0;
-    const unsigned char* an = smem + c_stage * STAGE_BYTES;
-    const bool ahead = has_next && !tile_done;   // first fragments of the next slice under the last MFMAs
-    load_a(at, 3, a1, ln);
-    if (ahead) load_b(an + A_BYTES, 0, bcur[0], ln);
-    mma(2, a0, bcur);
-    __builtin_amdgcn_sched_barrier(0);
-    if (ahead) load_a(an, 0, a0, ln);
-    mma(3, a1, bcur);
-    __builtin_amdgcn_sched_barrier(0);
-    if (tile_done) {
-      if (FAST != FAST_NONE && cc.m0 + BM <= g.M && cc.n0 + BN <= g.N) {
-        epilogue_fast(cc);
-        epi_ops = FastOps<FAST>::value;
-      } else {
-        epilogue(cc);
-        epi_ops = -1;
-      }
-      epi_age = 2;
-      if (has_next) {
-        load_b(an + A_BYTES, 0, bcur[0], ln);
-        load_a(an, 0, a0, ln);
-      }
-    }
     if (!has_next) break;
     ++consumed;
   }
+  if (epi_pending) epilogue(ec);
+  if (grp == 0) __builtin_amdgcn_s_barrier();   // matches group 1's last barrier
 }
 
-template <bool A_KC, bool B_KC, bool ACT, int FAST>
-hipError_t launch_variant(const GemmArgs& g, hipStream_t s) {
+
+// Straight-line epilogue from the registers for a tile fully inside the matrix (fp32 output).
+template <int FAST>
+__device__ __forceinline__ void epilogue_fast_fn(const GemmArgs& g, const TileCoord& tc, const float16v (&acc)[4][2],
+                                                 int wm0, int wn0, int lane) {
+  constexpr bool HAS_AUX = FAST == FAST_MUL_AUX || FAST == FAST_MUL_1MZ2 || FAST == FAST_ADD_AUX;
+  const long off0 = (tc.m0 + wm0 + (lane & 31)) * g.ldc + tc.n0 + wn0 + 4 * (lane >> 5);   // this lane's first element
+  const bf16_t* aux = reinterpret_cast<const bf16_t*>(g.aux) + tc.batch * g.aux_sb + off0;
+  const long cb = g.split_k > 1 ? ((long)tc.split * g.batch + tc.batch) * g.c_sb : tc.batch * g.c_sb;
+  float* cf = reinterpret_cast<float*>(g.C) + cb + off0;
+  bf16_t* chp = reinterpret_cast<bf16_t*>(g.C) + cb + off0;
+  uint2 auxv[2][8];
+  if (HAS_AUX) {
+#pragma unroll
+    for (int jq = 0; jq < 8; ++jq) auxv[0][jq] = *reinterpret_cast<const uint2*>(aux + 8 * jq);
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    if (HAS_AUX && i + 1 < 4) {
+#pragma unroll
+      for (int jq = 0; jq < 8; ++jq)
+        auxv[(i + 1) & 1][jq] = *reinterpret_cast<const uint2*>(aux + (long)(32 * (i + 1)) * g.ldc + 8 * jq);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float v[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) v[x] = acc[i][j][4 * q + x];
+        if (HAS_AUX) {
+          float t[4];
+          unpack4(auxv[i & 1][4 * j + q], t);
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            if (FAST == FAST_MUL_AUX) v[x] *= t[x];
+            else if (FAST == FAST_ADD_AUX) v[x] += t[x];
+            else v[x] *= (1.f - t[x] * t[x]);
+          }
+        }
+        const long ro = (long)(32 * i) * g.ldc + 32 * j + 8 * q;
+        if (FAST == FAST_STORE_F32) store4(cf + ro, v); else store4(chp + ro, v);
+      }
+  }
+}
+
+// The lean form of the kernel, for launches in which every tile lies inside the
+// matrix and every tile's contraction range is a multiple of 4 slices: the LDS
+// stage of every step is then a compile-time constant (four steps are written
+// out), the copies need two scalar pointers that advance by a constant, and a
+// step is ~40 instructions next to its 16 MFMAs.  (A wavefront issues at most
+// one instruction every four cycles, so the instruction count of the load phase
+// is what decides whether it fits under the other group's 512 MFMA cycles.)
+template <int C>
+__device__ __forceinline__ void dma16_c(unsigned off, const void* sbase, unsigned lds_wave_base) {
+  asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n"
+               :: "v"(off), "s"(sbase), "s"(lds_wave_base), "n"(C) : "memory", "scc");
+}
+
+// Epilogue of a bf16 tile through 4 KB of wave-private LDS, 32 rows x 64 columns at a time: the
+// accumulators (and the fused operand) change between the MFMA layout (a lane owns one row and
+// groups of 4 columns) and a row layout (8 lanes cover the 128 bytes of a row), so that every
+// global access of a wave covers whole 128-byte lines: 8 rows per instruction.  The 16-byte chunk
+// k of row r sits at chunk k ^ (r/2 % 8) of the row (bank spread for both access shapes).
+// Lanes exchange data through LDS here without a fence: the accesses go through one base pointer with
+// run-time offsets, which the compiler must assume to overlap and therefore keeps in program order,
+// and the hardware executes a wave's LDS instructions in order.
+typedef unsigned uint4v __attribute__((ext_vector_type(4)));   // (a first-class vector: stays in registers)
+struct Quad16 { uint4v x0, x1, x2, x3; };   // 4 x 16 bytes per lane: 32 rows of the row layout
+template <int FAST>
+__device__ __forceinline__ void epilogue_staged_fn(const GemmArgs& g, const TileCoord& tc, const float16v (&acc)[4][2],
+                                                   int wm0, int wn0, int lane, unsigned char* stg) {
+  constexpr bool HAS_AUX = FAST == FAST_MUL_AUX || FAST == FAST_MUL_1MZ2 || FAST == FAST_ADD_AUX;
+  // row layout: this lane's row within a group of 8 rows, and its chunk of the row
+  const int rr = lane >> 3, rk = lane & 7;
+  // MFMA layout: this lane's row within the 32, half-chunk (4 columns) within a chunk
+  const int mr = lane & 31, mh = lane >> 5;
+  const long off_row = (tc.m0 + wm0 + rr) * g.ldc + tc.n0 + wn0 + 8 * rk;     // row layout, first row group
+  const bf16_t* aux = reinterpret_cast<const bf16_t*>(g.aux) + tc.batch * g.aux_sb + off_row;
+  bf16_t* cp = reinterpret_cast<bf16_t*>(g.C) + tc.batch * g.c_sb + off_row;
+  const long ld8 = 8 * g.ldc;
+  // staging addresses, row layout: rows rr, rr + 8, rr + 16, rr + 24
+  auto row_at = [&](int r) { return stg + r * 128 + ((rk ^ ((r >> 1) & 7)) << 4); };
+  unsigned char* const p0 = row_at(rr);
+  unsigned char* const p1 = row_at(rr + 8);
+  unsigned char* const p2 = row_at(rr + 16);
+  unsigned char* const p3 = row_at(rr + 24);
+  unsigned char* const m_base = stg + mr * 128 + 8 * mh;
+  const int m_sw = (mr >> 1) & 7;
+  auto fetch = [&](Quad16& q, int round) {
+    const bf16_t* a = aux + (long)(32 * round) * g.ldc;
+    q.x0 = *reinterpret_cast<const uint4v*>(a);
+    q.x1 = *reinterpret_cast<const uint4v*>(a + ld8);
+    q.x2 = *reinterpret_cast<const uint4v*>(a + 2 * ld8);
+    q.x3 = *reinterpret_cast<const uint4v*>(a + 3 * ld8);
+  };
+  auto round = [&](auto ic, const Quad16& q) {
+    constexpr int i = decltype(ic)::value;
+    uint2 auxm[8];
+    if (HAS_AUX) {
+      *reinterpret_cast<uint4v*>(p0) = q.x0;
+      *reinterpret_cast<uint4v*>(p1) = q.x1;
+      *reinterpret_cast<uint4v*>(p2) = q.x2;
+      *reinterpret_cast<uint4v*>(p3) = q.x3;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) auxm[k] = *reinterpret_cast<const uint2*>(m_base + ((k ^ m_sw) << 4));
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int qd = 0; qd < 4; ++qd) {
+        float v[4];
+#pragma unroll
+        for (int x = 0; x < 4; ++x) v[x] = acc[i][j][4 * qd + x];
+        if (HAS_AUX) {
+          float t[4];
+          unpack4(auxm[4 * j + qd], t);
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            if (FAST == FAST_MUL_AUX) v[x] *= t[x];
+            else if (FAST == FAST_ADD_AUX) v[x] += t[x];
+            else v[x] *= (1.f - t[x] * t[x]);
+          }
+        }
+        *reinterpret_cast<uint2*>(m_base + (((4 * j + qd) ^ m_sw) << 4)) = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+      }
+    const uint4v o0 = *reinterpret_cast<const uint4v*>(p0);
+    const uint4v o1 = *reinterpret_cast<const uint4v*>(p1);
+    const uint4v o2 = *reinterpret_cast<const uint4v*>(p2);
+    const uint4v o3 = *reinterpret_cast<const uint4v*>(p3);
+    bf16_t* c = cp + (long)(32 * i) * g.ldc;
+    *reinterpret_cast<uint4v*>(c) = o0;
+    *reinterpret_cast<uint4v*>(c + ld8) = o1;
+    *reinterpret_cast<uint4v*>(c + 2 * ld8) = o2;
+    *reinterpret_cast<uint4v*>(c + 3 * ld8) = o3;
+  };
+  Quad16 qa = {}, qb = {};
+  if (HAS_AUX) { fetch(qa, 0); fetch(qb, 1); }
+  round(std::integral_constant<int, 0>(), qa);
+  if (HAS_AUX) fetch(qa, 2);
+  round(std::integral_constant<int, 1>(), qb);
+  if (HAS_AUX) fetch(qb, 3);
+  round(std::integral_constant<int, 2>(), qa);
+  round(std::integral_constant<int, 3>(), qb);
+}
+template <int FAST> struct StagedOps {   // vector-memory operations per wave of one epilogue
+  static constexpr int value = FAST == FAST_STORE_F32 ? 32 : FAST == FAST_STORE ? 16 : 32;
+};
+
+constexpr int LEAN_NST = 4;                              // 4 x 32 KB, + 4 KB per wave for the epilogue
+constexpr int LEAN_LDS = LEAN_NST * STAGE_BYTES + NW * 4096;
+
+template <bool A_KC, bool B_KC, int FAST>
+__global__ __launch_bounds__(NTHR, 1) void gemm_mfma_lean_kernel(GemmArgs g, int tiles_m, int tiles_n, long total,
+                                                                 long per_xcd) {
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wave >> 2;
+  const int wm0 = grp * 128, wn0 = (wave & 3) * 64;
+  const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+  const unsigned lds_wave = lds0 + (unsigned)wave * 1024u;
+
+  const int xcd = blockIdx.x & 7;
+  const int t_stride = gridDim.x >> 3;
+  int t = xcd * (int)per_xcd + (blockIdx.x >> 3);
+  const int t_end = (xcd + 1) * per_xcd < total ? (xcd + 1) * (int)per_xcd : (int)total;
+  if (t >= t_end) return;
+
+  const long lda = A_KC ? g.a_sm : g.a_sk;
+  const long ldb = B_KC ? g.b_sn : g.b_sk;
+  const long step_a = (A_KC ? BK : BK * lda) * 2, step_b = (B_KC ? BK : BK * ldb) * 2;   // bytes per slice
+  // per-lane byte offsets of the wave's two copies per operand (the second is 128 rows / 16 k rows further)
+  const unsigned offA0 = lane_src_offset<A_KC>(lda, 0, wave, lane);
+  const unsigned offB0 = lane_src_offset<B_KC>(ldb, 0, wave, lane);
+  const unsigned offA1 = offA0 + (unsigned)((A_KC ? 128 : 16) * lda * 2);
+  const unsigned offB1 = offB0 + (unsigned)((B_KC ? 128 : 16) * ldb * 2);
+
+  // ---- producer (wave-uniform): first byte of the next slice to copy per operand, slices left in
+  // the tile it copies from, that tile's index, the stage the slice goes to ----
+  const unsigned char* qa;
+  const unsigned char* qb;
+  int p_left, pt = t;
+  bool p_more = true;
+  unsigned p_off = 0;      // byte offset of the producer's stage in the ring
+  auto aim = [&](const TileCoord& c) {
+    qa = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(g.A) + c.batch * g.a_sb +
+                                                (A_KC ? c.m0 * lda + c.k_begin : c.m0 + c.k_begin * lda));
+    qb = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(g.B) + c.batch * g.b_sb +
+                                                (B_KC ? c.n0 * ldb + c.k_begin : c.n0 + c.k_begin * ldb));
+    p_left = c.KT;
+  };
+  auto copy_slice = [&]() {
+    const unsigned dst = lds_wave + p_off;
+    dma16_c<0>(offA0, qa, dst);
+    dma16_c<NW * 1024>(offA1, qa, dst);
+    dma16_c<A_BYTES>(offB0, qb, dst);
+    dma16_c<A_BYTES + NW * 1024>(offB1, qb, dst);
+    qa += step_a;
+    qb += step_b;
+    p_off = p_off == (LEAN_NST - 1) * STAGE_BYTES ? 0u : p_off + STAGE_BYTES;
+    if (--p_left == 0) {
+      pt += t_stride;
+      if (pt < t_end) aim(decode_tile(g, pt, tiles_m, tiles_n));
+      else p_more = false;
+    }
+  };
+
+  float16v acc[4][2];
+  bf16x8 fa[4][2], fb[2][2];
+  unsigned c_off = 0;      // byte offset of the consumer's stage
+  int epi_recent = 0;      // waits that still see the last epilogue's operations
+  constexpr int E = StagedOps<FAST>::value;
+  constexpr int AHEAD = LEAN_NST - 1;                      // slices copied ahead of the one being multiplied
+  constexpr int W_PLAIN = (AHEAD - 1) * PER_SLICE;
+  constexpr int W_EPI = W_PLAIN + E > 63 ? 63 : W_PLAIN + E;
+
+  // One slice: load phase, barrier, compute phase, barrier.
+  // Barrier intervals ("ticks"): group 0 loads slice c in tick 2c and multiplies it in tick 2c+1;
+  // group 1 does the same one tick later.  Slice c+4 is issued in the load phase of slice c into
+  // the stage of slice c-1, which its last reader (group 1, tick 2c-1) has left.  Every wave waits
+  // for its own share of slice c+1 at the end of its load phase of slice c, a barrier or more
+  // before the first reader of slice c+1 starts.
+  auto step = [&](auto first_c) {
+    constexpr bool FIRST = decltype(first_c)::value;
+    const bool copying = p_more;
+    if (copying) copy_slice();
+    const unsigned char* st = smem + c_off;
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) fb[j][h] = frag<B_KC>(st + A_BYTES, wn0 + 32 * j, 16 * h, lane);
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) fa[i][h] = frag<A_KC>(st, wm0 + 32 * i, 16 * h, lane);
+    c_off = c_off == (LEAN_NST - 1) * STAGE_BYTES ? 0u : c_off + STAGE_BYTES;
+    // this wave's share of the next slice has landed once only what it issued for the slices after
+    // that one (and a recent epilogue's operations, which lie among them) is outstanding
+    if (!copying) wait_vm_lds<0>();
+    else if (epi_recent > 0) { wait_vm_lds<W_EPI>(); --epi_recent; }
+    else wait_vm_lds<W_PLAIN>();
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_setprio(1);
+    const float16v zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j][0], fa[i][0], FIRST ? zero : acc[i][j], 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j][1], fa[i][1], acc[i][j], 0, 0, 0);
+    __builtin_amdgcn_s_setprio(0);
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  TileCoord cc = decode_tile(g, t, tiles_m, tiles_n);
+  aim(cc);
+  int pro = 0;             // slices copied before the first step
+#pragma unroll 1
+  for (; pro < AHEAD && p_more; ++pro) copy_slice();
+  // slice 0 has landed once at most the pro - 1 slices after it are outstanding
+  if (pro >= 4) wait_vm<3 * PER_SLICE>(); else if (pro == 3) wait_vm<2 * PER_SLICE>();
+  else if (pro == 2) wait_vm<PER_SLICE>(); else wait_vm<0>();
+  __builtin_amdgcn_s_barrier();                 // slice 0 is in LDS
+  if (grp == 1) __builtin_amdgcn_s_barrier();   // group 1 runs one tick behind
+
+  while (true) {
+    step(std::true_type());
+#pragma unroll 1
+    for (int k = 1; k < cc.KT; ++k) step(std::false_type());
+    if (FAST == FAST_STORE_F32) epilogue_fast_fn<FAST>(g, cc, acc, wm0, wn0, lane);
+    else epilogue_staged_fn<FAST>(g, cc, acc, wm0, wn0, lane, smem + LEAN_NST * STAGE_BYTES + wave * 4096);
+    epi_recent = AHEAD - 1;
+    t += t_stride;
+    if (t >= t_end) break;
+    cc = decode_tile(g, t, tiles_m, tiles_n);
+  }
+  if (grp == 0) __builtin_amdgcn_s_barrier();   // matches group 1's last barrier
+}
+
+template <bool A_KC, bool B_KC, int FAST>
+hipError_t launch_lean(const GemmArgs& g, hipStream_t s) {
   static bool attr_set = false;
-  auto kern = gemm_mfma_kernel<A_KC, B_KC, ACT, FAST>;
+  auto kern = gemm_mfma_lean_kernel<A_KC, B_KC, FAST>;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LEAN_LDS);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int tiles_m = (int)(g.M / BM), tiles_n = (int)(g.N / BN);
+  const long total = (long)tiles_m * tiles_n * g.batch * g.split_k;
+  const long per_xcd = (total + 7) / 8;
+  const long wg_per_xcd = per_xcd < 32 ? per_xcd : 32;
+  const int lds = LEAN_LDS;
+  hipLaunchKernelGGL(kern, dim3((unsigned)(wg_per_xcd * 8)), dim3(NTHR), lds, s, g, tiles_m, tiles_n, total, per_xcd);
+  return hipGetLastError();
+}
+// every tile inside the matrix, every tile's share of K a whole number of slices
+inline bool lean_ok(const GemmArgs& g) {
+  return g.M % BM == 0 && g.N % BN == 0 && g.K % ((long)g.split_k * BK) == 0;
+}
+
+template <bool A_KC, bool B_KC, bool ACT>
+hipError_t launch_variant(const GemmArgs& g, hipStream_t s) {
+  static bool attr_set = false;
+  auto kern = gemm_mfma_kernel<A_KC, B_KC, ACT>;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES + 8192);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
@@ -644,21 +857,24 @@ bool launch_gemm_mfma(const GemmArgs& g, hipStream_t s, hipError_t* err) {
   if (!aligned16(g.A) || !aligned16(g.B) || !aligned16(g.C) || !aligned16(g.aux) || !aligned16(g.out2) ||
       !aligned16(g.addf) || !aligned16(g.lambda))
     return false;
+  if (lda > (1L << 22) || ldb > (1L << 22)) return false;   // per-lane source offsets are 32-bit
   if (g.split_k > 1 && g.mode != EPI_STORE) return false;
   if (g.M <= 0 || g.N <= 0 || g.K <= 0 || g.batch <= 0 || g.split_k <= 0) return false;
   const bool act = g.mode == EPI_ACT_GELU || g.mode == EPI_ACT_TANH;
   const bool plain = g.mode == EPI_STORE && !g.addf;
+  const bool lean = lean_ok(g);
+  const bool bf16_out = !g.addf && !g.c_is_f32 && g.split_k == 1;
   if (a_kc && b_rc && !act) {            // VJP contractions
-    if (plain && !g.c_is_f32 && g.split_k == 1) *err = launch_variant<true, false, false, FAST_STORE>(g, s);
-    else if (g.mode == EPI_MUL_AUX && !g.addf && !g.c_is_f32) *err = launch_variant<true, false, false, FAST_MUL_AUX>(g, s);
-    else if (g.mode == EPI_MUL_1MZ2 && !g.addf && !g.c_is_f32) *err = launch_variant<true, false, false, FAST_MUL_1MZ2>(g, s);
-    else if (g.mode == EPI_ADD_AUX && !g.addf && !g.c_is_f32) *err = launch_variant<true, false, false, FAST_ADD_AUX>(g, s);
-    else *err = launch_variant<true, false, false, FAST_NONE>(g, s);
+    if (lean && bf16_out && g.mode == EPI_STORE) *err = launch_lean<true, false, FAST_STORE>(g, s);
+    else if (lean && bf16_out && g.mode == EPI_MUL_AUX) *err = launch_lean<true, false, FAST_MUL_AUX>(g, s);
+    else if (lean && bf16_out && g.mode == EPI_MUL_1MZ2) *err = launch_lean<true, false, FAST_MUL_1MZ2>(g, s);
+    else if (lean && bf16_out && g.mode == EPI_ADD_AUX) *err = launch_lean<true, false, FAST_ADD_AUX>(g, s);
+    else *err = launch_variant<true, false, false>(g, s);
   } else if (a_rc && b_rc && !act) {     // parameter gradients
-    if (plain && (g.c_is_f32 || g.split_k > 1)) *err = launch_variant<false, false, false, FAST_STORE_F32>(g, s);
-    else *err = launch_variant<false, false, false, FAST_NONE>(g, s);
+    if (lean && plain && (g.c_is_f32 || g.split_k > 1)) *err = launch_lean<false, false, FAST_STORE_F32>(g, s);
+    else *err = launch_variant<false, false, false>(g, s);
   } else if (a_kc && b_kc) {             // forward
-    *err = act ? launch_variant<true, true, true, FAST_NONE>(g, s) : launch_variant<true, true, false, FAST_NONE>(g, s);
+    *err = act ? launch_variant<true, true, true>(g, s) : launch_variant<true, true, false>(g, s);
   } else {
     return false;
   }
