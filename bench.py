@@ -32,7 +32,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch (read + written) measured with rocprofv3's FETCH_SIZE and WRITE_SIZE counters, scaled by
 # what the same counters read for a plain 1 GiB copy (x2.00 and x1.00): profiles/bench_resnet_like_hbm_traffic.txt.
 # Only for the default workload; other workloads report null.
-MEASURED_TRAFFIC = {"resnet_like": {"vjp1": 3.209e9, "vjp2": 1.634e9, "dw": 1.478e9, "scan": 0.823e9}}
+MEASURED_TRAFFIC = {"resnet_like": {"vjp1": 2.939e9, "vjp2": 1.618e9, "dw": 1.479e9, "scan": 0.823e9}}
 
 
 def storage_bytes(w):
@@ -243,8 +243,9 @@ def main():
         out["per_k"] = sweep
 
     if not args.no_cpu_baseline:
-        n = args.cpu_tokens or {"mlp_small_f32": 128, "resnet_like": 1024, "transformer_mlp": 192,
-                                "deep_large": 32, "gated_rnn": 2, "gated_rnn_contractive": 2}.get(w.name, 64)
+        # about 10-20 s of oracle work on the GPU machine's host cores
+        n = args.cpu_tokens or {"mlp_small_f32": 128, "resnet_like": 8192, "transformer_mlp": 2048,
+                                "deep_large": 256, "gated_rnn": 16, "gated_rnn_contractive": 16}.get(w.name, 64)
         out["cpu_baseline"] = cpu_baseline(w, k, n)
 
     def finite(o):   # JSON has no NaN/Infinity: overflowed error figures become null

@@ -420,7 +420,15 @@ hbp_status hbp_backward(const hbp_desc* d, int k, hbp_buffers* b, void* stream) 
     // After it-2 iterations the states l+1 >= L-it+2 are already exact (and
     // bit-identical from then on), so v_l of blocks l >= L-it+1 left by the
     // previous iteration is still valid: recompute only the blocks below.
-    const long l_hi = d->L - it + 1;
+    long l_hi = d->L - it + 1;
+    if (d->kind == HBP_RNN) {
+      // One contraction covers all rows (l_hi * N): where re-doing a few of the final blocks keeps
+      // the row count a multiple of the 256-row GEMM tile, do that (same values, aligned kernel).
+      long step = 256;
+      for (long a = d->N, b2 = 256; b2 != 0;) { const long r = a % b2; a = b2; b2 = r; step = 256 / a; }
+      const long padded = (l_hi + step - 1) / step * step;
+      if (padded <= d->L) l_hi = padded;
+    }
     HBP_RUN(vjp_stage1(d, &bb, w, 0, l_hi, s));
     HBP_RUN(vjp_stage2(d, &bb, w, 0, l_hi, s));
     HBP_RUN(scan_stage(d, &bb, w, 0, d->L, true, s));
