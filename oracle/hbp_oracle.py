@@ -225,21 +225,32 @@ def cumsumprod_reverse(a: np.ndarray, lam_rows) -> np.ndarray:
 # Highway-BP, k iterations (Theorem 2, two-step form)
 # --------------------------------------------------------------------------
 def hbp_backward(st: Stack, saved: Dict[str, np.ndarray], e: np.ndarray, k: int,
-                 return_all: bool = False):
+                 return_all: bool = False, gamma: float = 0.0):
     """w^0 = CumSumProd(e, K);  repeat k times: v_l = w_{l+1} J_{l+1} for every
-    l from the current estimate, u = CumSumProd(v, K), w <- w^0 + u."""
+    l from the current estimate, u = CumSumProd(v, K), w <- w^0 + u.
+
+    gamma re-splits each layer between its block and its residual connection
+    (appendix, the decomposition with gamma used for pre-norm transformers,
+    written there for lambda = 1 and taken here for any diagonal coefficient):
+    the residual connection keeps (1 - gamma) lambda_l (.) x and the block gains
+    gamma lambda_l (.) x, i.e. K' = (1 - gamma) K and J' = J + gamma K.  The
+    function and its exact gradient are unchanged; the iterates are not.
+    gamma = 0 is the plain method, gamma = 1 the fixed-point iteration."""
     assert k >= 0
     N = saved["y"].shape[1]
     L = st.L
     ef = _e_full(st, e, N)
-    w0 = cumsumprod_reverse(ef, st.lam_row)
+    k_row = lambda l: (1.0 - gamma) * st.lam_row(l)
+    w0 = cumsumprod_reverse(ef, k_row)
     w = w0.copy()
     hist = [w0.copy()]
     for _ in range(k):
         v = np.zeros_like(w)                       # v_L = 0: no block above x_L
         for l in range(L):
             v[l] = block_vjp(st, l, saved, w[l + 1])
-        u = cumsumprod_reverse(v, st.lam_row)
+            if gamma != 0.0:
+                v[l] = v[l] + gamma * st.lam_row(l)[None, :] * w[l + 1]
+        u = cumsumprod_reverse(v, k_row)
         w = w0 + u
         hist.append(w.copy())
     return hist if return_all else w

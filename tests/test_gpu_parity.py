@@ -56,6 +56,12 @@ CASES = {
                                  w2_scale=0.1, ks=(0, 2)),
     "rnn_chaotic_small": synth.scaled(W["gated_rnn"], name="rnn_chaotic_small", L=130, N=4, d=512, d_ff=512,
                                       d_in=256, ks=(1, 2, 4)),
+    # every contraction on whole 256 x 256 tiles (the aligned GEMM kernel), several tiles per workgroup,
+    # contraction lengths of 8 and 16 slices; in the RNN the iterations' row counts are padded to the tile
+    "aligned_small": synth.scaled(W["resnet_like"], name="aligned_small", L=12, N=512, d=256, d_ff=512,
+                                  w2_scale=1 / np.sqrt(12.0), ks=(0, 1, 2, 5)),
+    "rnn_aligned": synth.scaled(W["gated_rnn_contractive"], name="rnn_aligned", L=64, N=8, d=256, d_ff=256,
+                                d_in=128, ks=(0, 1, 2, 3)),
 }
 
 
@@ -121,7 +127,7 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
 
 @pytest.mark.parametrize("name", ["mlp_small_f32", "mlp_f32_ragged", "resnet_like_small", "resnet_like_odd",
                                   "transformer_small", "deep_small", "rnn_small", "rnn_f32", "rnn_long",
-                                  "mlp_f32_deep"])
+                                  "mlp_f32_deep", "aligned_small", "rnn_aligned"])
 def test_backward_end_to_end(B, name):
     """Own forward on each side, then Highway-BP at every k of the case, exact BP
     and the parameter gradients."""

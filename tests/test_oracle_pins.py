@@ -294,6 +294,72 @@ def test_fixed_point_iteration_special_case():
                 assert np.all(w[i] == 0)
 
 
+# ---------------------------------------------------------------- P8b, P9b
+@pytest.mark.parametrize("gamma", [0.2, 0.8, 1.0])
+def test_gamma_iterates_by_path_enumeration(gamma):
+    """With gamma the layer is split into J' = J + gamma K and K' = (1 - gamma) K;
+    Theorem 2 applied to that pair: w_i^k sums, over end states j >= i and at most
+    k blocks taken through J', the products of J' (chosen) and K' (not)."""
+    st = small_mlp(L=5, d=3, dff=4)
+    N = 1
+    r = np.random.default_rng(11)
+    sv = O.forward(st, r.standard_normal((N, st.d)))
+    e = r.standard_normal((st.L + 1, N, st.d))
+    e[0] = 0
+    Js = _dense_block_jacobians(st, sv, 0)
+    Ks = [np.diag(st.lam[l]) for l in range(st.L)]
+    Jg = [Js[l] + gamma * Ks[l] for l in range(st.L)]
+    Kg = [(1.0 - gamma) * Ks[l] for l in range(st.L)]
+    L = st.L
+    for k in range(L + 1):
+        w = O.hbp_backward(st, sv, e, k, gamma=gamma)
+        for i in range(L + 1):
+            acc = np.zeros(st.d)
+            for j in range(i, L + 1):
+                layers = list(range(i, j))
+                for size in range(min(k, len(layers)) + 1):
+                    for chosen in itertools.combinations(layers, size):
+                        vec = e[j][0].copy()
+                        for l in reversed(layers):
+                            vec = vec @ (Jg[l] if l in chosen else Kg[l])
+                        acc += vec
+            np.testing.assert_allclose(w[i][0], acc, rtol=2e-6, atol=2e-8)
+    G = O.exact_backward(st, sv, e)
+    np.testing.assert_allclose(O.hbp_backward(st, sv, e, L, gamma=gamma), G, rtol=1e-10, atol=1e-12)
+
+
+def test_gamma_one_is_the_fixed_point_iteration():
+    """gamma = 1 leaves nothing on the residual path: the iterates are those of
+    k sweeps w_l <- e_l + w_{l+1} (J_l + K_l) through all layers at once, from
+    w = e (the fixed-point-iteration baseline), written here with dense matrices."""
+    st = small_mlp(L=6, d=4, dff=5)
+    r = np.random.default_rng(5)
+    sv = O.forward(st, r.standard_normal((1, st.d)))
+    e = r.standard_normal((st.L + 1, 1, st.d))
+    e[0] = 0
+    Js = _dense_block_jacobians(st, sv, 0)
+    T = [Js[l] + np.diag(st.lam[l]) for l in range(st.L)]
+    w = e[:, 0, :].copy()
+    for k in range(st.L + 2):
+        got = O.hbp_backward(st, sv, e, k, gamma=1.0)[:, 0, :]
+        np.testing.assert_allclose(got, w, rtol=2e-6, atol=2e-8)
+        nxt = e[:, 0, :].copy()
+        for l in range(st.L):
+            nxt[l] = e[l, 0] + w[l + 1] @ T[l]
+        w = nxt
+
+
+def test_gamma_zero_is_the_plain_method():
+    st = small_rnn()
+    r = np.random.default_rng(2)
+    xin = r.standard_normal((st.L, 2, st.U.shape[1]))
+    sv = O.forward(st, np.zeros((2, st.d)), xin)
+    e = r.standard_normal((st.L + 1, 2, st.d))
+    e[0] = 0
+    for k in (0, 1, 3):
+        assert np.array_equal(O.hbp_backward(st, sv, e, k), O.hbp_backward(st, sv, e, k, gamma=0.0))
+
+
 # ---------------------------------------------------------------- P9
 def test_gamma_reparametrisation_leaves_exact_gradient_unchanged():
     """Moving gamma*x from the residual connection into the block changes J and K
