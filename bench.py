@@ -65,7 +65,7 @@ def algorithmic_work(w, k):
             "scan_launches": 1 + iters}
 
 
-def gpu_errors(B, torch, p, ks):
+def gpu_errors(B, torch, p, ks, gamma=None):
     """Relative L2 error and cosine of the k-iteration estimate against exact BP,
     both from the GPU library, for states 0..L-1 and for all parameter gradients."""
     B.hbp_exact_backward(p)
@@ -75,7 +75,7 @@ def gpu_errors(B, torch, p, ks):
     PG = torch.cat([t.flatten() for t in (p.dW1, p.dW2, p.dU) if t is not None]).clone()
     out = {}
     for k in ks:
-        B.hbp_backward(p, k)
+        B.hbp_backward(p, k, gamma=gamma)
         B.hbp_param_grads(p)
         torch.cuda.synchronize()
         g = p.g[:-1].float()
@@ -241,6 +241,20 @@ def main():
         for kk, v in errs.items():
             sweep.setdefault(kk, {}).update(v)
         out["per_k"] = sweep
+        # the re-split iteration (gamma of the layer's residual connection counted with the block);
+        # gamma = 1 is the fixed-point-iteration baseline
+        if not (w.norm == "rms" and w.d > 2048):
+            gs = {}
+            for gm in (0.2, 0.5, 1.0):
+                def fg(gm=gm):
+                    B.hbp_backward(p, k, gamma=gm)
+                    B.hbp_param_grads(p)
+                t = time_steps(torch, fg, max(3, args.steps // 2), 1)
+                e = gpu_errors(B, torch, p, (1, 2, 3, 4), gamma=gm)
+                gs[str(gm)] = {"ms_at_k": t * 1e3, "k": k,
+                               "param_rel_l2": {kk: v["param_rel_l2"] for kk, v in e.items()},
+                               "state_rel_l2": {kk: v["state_rel_l2"] for kk, v in e.items()}}
+            out["per_gamma"] = gs
 
     if not args.no_cpu_baseline:
         # about 10-20 s of oracle work on the GPU machine's host cores

@@ -75,6 +75,11 @@ typedef struct {
   int64_t d;                 /* state width (RNN: hidden size) */
   int64_t d_ff;              /* inner width of a block (RNN: hidden size of the cell) */
   int64_t d_in;              /* RNN input width; 0 for HBP_MLP */
+  float gamma;               /* 0 <= gamma <= 1: share of the residual connection counted with the block in
+                              * hbp_backward (appendix, the decomposition with gamma): the iteration then runs on
+                              * K' = (1 - gamma) K and J' = J + gamma K.  0: the plain method; 1: fixed-point
+                              * iteration.  The exact gradient and the other calls do not depend on it. */
+  int32_t reserved;          /* 0 */
 } hbp_desc;
 
 typedef struct {
@@ -113,7 +118,8 @@ hbp_status hbp_check(const hbp_desc* desc, const hbp_buffers* bufs);
 hbp_status hbp_forward(const hbp_desc* desc, hbp_buffers* bufs, void* stream);
 
 /* g := w^k, the sum of all gradient paths through at most k block Jacobians
- * (Theorem 2).  k = 0 gives the residual-path-only estimate; k >= L is exact.
+ * (Theorem 2; with desc->gamma > 0, of the re-split pair J + gamma K and
+ * (1 - gamma) K).  k = 0 gives the residual-path-only estimate; k >= L is exact.
  * Reads W1, W2, lambda, y (or x), rinv, z, dphi, e; writes g and the workspace. */
 hbp_status hbp_backward(const hbp_desc* desc, int k, hbp_buffers* bufs, void* stream);
 

@@ -33,7 +33,7 @@ class hbp_desc(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("kind", C.c_int32), ("dtype", C.c_int32), ("act", C.c_int32),
                 ("norm", C.c_int32), ("lambda_kind", C.c_int32), ("loss_every_state", C.c_int32),
                 ("eps", C.c_float), ("L", C.c_int64), ("N", C.c_int64), ("d", C.c_int64), ("d_ff", C.c_int64),
-                ("d_in", C.c_int64)]
+                ("d_in", C.c_int64), ("gamma", C.c_float), ("reserved", C.c_int32)]
 
 
 class hbp_buffers(C.Structure):
@@ -81,10 +81,11 @@ def status_string(status: int) -> str:
 
 
 def make_desc(kind: str, dtype: str, act: str, norm: str, L: int, N: int, d: int, d_ff: int, d_in: int = 0,
-              lambda_channel: bool = False, loss_every_state: bool = False, eps: float = 1e-6) -> hbp_desc:
+              lambda_channel: bool = False, loss_every_state: bool = False, eps: float = 1e-6,
+              gamma: float = 0.0) -> hbp_desc:
     return hbp_desc(C.sizeof(hbp_desc), RNN if kind == "rnn" else MLP, BF16 if dtype == "bf16" else F32,
                     ACT[act], NORM[norm], LAMBDA_CHANNEL if lambda_channel else LAMBDA_ONE,
-                    1 if loss_every_state else 0, eps, L, N, d, d_ff, d_in)
+                    1 if loss_every_state else 0, eps, L, N, d, d_ff, d_in, gamma, 0)
 
 
 def workspace_size(desc: hbp_desc) -> int:
@@ -150,9 +151,14 @@ def hbp_forward(p: Problem, stream=None) -> None:
     _call("hbp_forward", lib().hbp_forward(C.byref(p.desc), C.byref(b), _stream(stream)))
 
 
-def hbp_backward(p: Problem, k: int, stream=None) -> None:
+def hbp_backward(p: Problem, k: int, stream=None, gamma: Optional[float] = None) -> None:
+    """gamma overrides the descriptor's for this call."""
     b = p.buffers()
-    _call("hbp_backward", lib().hbp_backward(C.byref(p.desc), int(k), C.byref(b), _stream(stream)))
+    desc = p.desc
+    if gamma is not None:
+        desc = hbp_desc.from_buffer_copy(p.desc)
+        desc.gamma = float(gamma)
+    _call("hbp_backward", lib().hbp_backward(C.byref(desc), int(k), C.byref(b), _stream(stream)))
 
 
 def hbp_exact_backward(p: Problem, stream=None) -> None:

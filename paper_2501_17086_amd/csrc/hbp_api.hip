@@ -84,6 +84,8 @@ hbp_status check_desc(const hbp_desc* d) {
   if (d->norm == HBP_NORM_RMS && !(d->eps >= 0.f)) return HBP_E_INVALID_ARG;
   if (d->d % 8 || d->d_ff % 8 || d->d_in % 8) return HBP_E_UNSUPPORTED;
   if (d->norm == HBP_NORM_RMS && d->d > 4096) return HBP_E_UNSUPPORTED;
+  if (!(d->gamma >= 0.f && d->gamma <= 1.f) || d->reserved != 0) return HBP_E_INVALID_ARG;
+  if (d->gamma != 0.f && d->norm == HBP_NORM_RMS && d->d > 2048) return HBP_E_UNSUPPORTED;
   if (d->L > (1 << 20) || d->N > (1L << 24) || d->d > (1 << 20) || d->d_ff > (1 << 20)) return HBP_E_UNSUPPORTED;
   return HBP_OK;
 }
@@ -234,9 +236,12 @@ hbp_status vjp_stage2(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
   return run_gemm(d, ga, s, HBP_PROF_VJP2);
 }
 
+// gamma: 0 for the exact recurrence; in the iterations of hbp_backward the descriptor's
 hbp_status scan_stage(const hbp_desc* d, const hbp_buffers* b, const Workspace& w, long l_lo, long l_hi,
-                      bool has_v, hipStream_t s) {
+                      bool has_v, hipStream_t s, float gamma = 0.f) {
   ScanArgs sa{};
+  sa.res_scale = 1.f - gamma;
+  sa.blk_gamma = has_v ? gamma : 0.f;   // w^0 has no block term: only the residual path is rescaled
   sa.g = b->g;
   sa.dn = has_v ? at(b->workspace, w.off_v) : nullptr;
   sa.y = b->y;
@@ -413,7 +418,7 @@ hbp_status hbp_backward(const hbp_desc* d, int k, hbp_buffers* b, void* stream) 
   if (d->norm == HBP_NORM_NONE) bb.y = bb.x;
   HBP_RUN(seed_top(d, &bb, s));
   // w^0: the residual path alone
-  HBP_RUN(scan_stage(d, &bb, w, 0, d->L, false, s));
+  HBP_RUN(scan_stage(d, &bb, w, 0, d->L, false, s, d->gamma));
   // More than L iterations change nothing (Theorem 2: exact for k >= L - i).
   const long iters = k > d->L ? d->L : k;
   for (long it = 1; it <= iters; ++it) {
@@ -431,7 +436,7 @@ hbp_status hbp_backward(const hbp_desc* d, int k, hbp_buffers* b, void* stream) 
     }
     HBP_RUN(vjp_stage1(d, &bb, w, 0, l_hi, s));
     HBP_RUN(vjp_stage2(d, &bb, w, 0, l_hi, s));
-    HBP_RUN(scan_stage(d, &bb, w, 0, d->L, true, s));
+    HBP_RUN(scan_stage(d, &bb, w, 0, d->L, true, s, d->gamma));
   }
   return HBP_OK;
 }

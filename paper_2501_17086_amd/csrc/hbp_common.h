@@ -123,8 +123,9 @@ hipError_t launch_splitk_reduce(const float* part, float* out, long n, int split
 // ---------------------------------------------------------------------------
 // residual-path scan:  for l = l_hi-1 .. l_lo:
 //   v_l = has_v ? (norm ? rmsnorm_bwd(dn_l; y_l, rinv_l) : dn_l) : 0
-//   g_l = (e_l) + v_l + lambda_l (.) g_{l+1}
-// g[l_hi] must already hold the incoming state gradient.
+//   g_l = (e_l) + v_l + res_gamma lambda_l (.) g_{l+1}^{old} + (1 - res_gamma') lambda_l (.) g_{l+1}
+// (written below as blk_gamma and res_scale).  g[l_hi] must already hold the
+// incoming state gradient; g^{old} is what g held before this scan.
 // ---------------------------------------------------------------------------
 struct ScanArgs {
   void* g;              // [L+1,N,d] storage
@@ -137,6 +138,8 @@ struct ScanArgs {
   long l_lo, l_hi;
   int norm_rms;
   float* chunk_ws;      // scratch of scan_chunk_ws_bytes() for the chunked form (long chains), or NULL
+  float res_scale;      // factor on lambda along the residual path (1 - gamma; 1 for the plain method)
+  float blk_gamma;      // gamma: adds gamma lambda_l (.) g_{l+1}^{old} to v_l (0: nothing read)
 };
 hipError_t launch_scan(int dtype, const ScanArgs& a, hipStream_t s);
 // Long chains with few of them (the time axis of an RNN) are cut into chunks of

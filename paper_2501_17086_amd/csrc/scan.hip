@@ -12,7 +12,9 @@ namespace {
 // One thread owns 8 consecutive channels of one token and walks down the
 // layers; the loads of the next layers do not depend on the carry, so the
 // unrolled loop keeps several of them in flight.
-template <typename T>
+// GAMMA: the re-split iteration, g_l = v_l + gamma lambda_l g_{l+1}^{old} + (1 - gamma) lambda_l g_{l+1};
+// the old g_l is read before it is overwritten and kept for the next step down.
+template <typename T, bool GAMMA>
 __global__ __launch_bounds__(256) void scan_vec_kernel(ScanArgs a) {
   const long vec_per_layer = a.N * a.d / 8;
   const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -24,8 +26,11 @@ __global__ __launch_bounds__(256) void scan_vec_kernel(ScanArgs a) {
   const T* dn = reinterpret_cast<const T*>(a.dn);
   const T* e = reinterpret_cast<const T*>(a.e);
 
-  float carry[8];
+  float carry[8], gold[8];
   load8(g + a.l_hi * layer + off, carry);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) gold[i] = carry[i];
+  const bool use_old = GAMMA && a.blk_gamma != 0.f;
 #pragma unroll 4
   for (long l = a.l_hi - 1; l >= a.l_lo; --l) {
     float v[8];
@@ -41,7 +46,26 @@ __global__ __launch_bounds__(256) void scan_vec_kernel(ScanArgs a) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) v[i] += t[i];
     }
-    if (a.lambda) {
+    float gl[8];
+    if (use_old) load8(g + l * layer + off, gl);     // the old g_l, for the step below
+    if (GAMMA) {
+      float lam[8];
+      if (a.lambda) {
+        load8(a.lambda + l * a.d + c0, lam);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) lam[i] = 1.f;
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (use_old) v[i] = fmaf(a.blk_gamma * lam[i], gold[i], v[i]);
+        carry[i] = fmaf(a.res_scale * lam[i], carry[i], v[i]);
+      }
+      if (use_old) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) gold[i] = gl[i];
+      }
+    } else if (a.lambda) {
       float lam[8];
       load8(a.lambda + l * a.d + c0, lam);
 #pragma unroll
@@ -62,7 +86,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 // One wavefront owns one token row (all d channels: NCH chunks of 512, 8 per
 // lane) so the row reduction of the norm's backward is a wave reduction.
-template <typename T, int NCH>
+template <typename T, int NCH, bool GAMMA>
 __global__ __launch_bounds__(256) void scan_rows_kernel(ScanArgs a) {
   const int lane = threadIdx.x & 63;
   const long row = (long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -77,6 +101,7 @@ __global__ __launch_bounds__(256) void scan_rows_kernel(ScanArgs a) {
   long off[NCH];
   bool on[NCH];
   float carry[NCH][8];
+  float gold[GAMMA ? NCH : 1][8];   // the old g_{l+1}
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
     long c = (long)j * 512 + lane * 8;
@@ -87,6 +112,10 @@ __global__ __launch_bounds__(256) void scan_rows_kernel(ScanArgs a) {
     } else {
 #pragma unroll
       for (int i = 0; i < 8; ++i) carry[j][i] = 0.f;
+    }
+    if (GAMMA) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) gold[GAMMA ? j : 0][i] = carry[j][i];
     }
   }
 
@@ -120,7 +149,22 @@ __global__ __launch_bounds__(256) void scan_rows_kernel(ScanArgs a) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) t[i] += ee[i];
       }
-      if (a.lambda) {
+      if (GAMMA) {
+        float lam[8], gl[8];
+        load8(g + l * layer + off[j], gl);             // the old g_l, for the step below
+        if (a.lambda) {
+          load8(a.lambda + l * a.d + (long)j * 512 + lane * 8, lam);
+        } else {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) lam[i] = 1.f;
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          t[i] = fmaf(a.blk_gamma * lam[i], gold[GAMMA ? j : 0][i], t[i]);
+          carry[j][i] = fmaf(a.res_scale * lam[i], carry[j][i], t[i]);
+          gold[GAMMA ? j : 0][i] = gl[i];
+        }
+      } else if (a.lambda) {
         float lam[8];
         load8(a.lambda + l * a.d + (long)j * 512 + lane * 8, lam);
 #pragma unroll
@@ -323,22 +367,34 @@ hipError_t launch_scan_chunked(const ScanArgs& a, hipStream_t s) {
 template <typename T>
 hipError_t launch_scan_t(const ScanArgs& a, hipStream_t s) {
   if (a.l_hi <= a.l_lo) return hipSuccess;
-  if (a.chunk_ws && use_chunked(a.l_hi - a.l_lo, a.N, a.d, a.norm_rms && a.dn)) return launch_scan_chunked<T>(a, s);
+  const bool gam = a.res_scale != 1.f || a.blk_gamma != 0.f;   // (the chunked form covers the plain recurrence only)
+  if (!gam && a.chunk_ws && use_chunked(a.l_hi - a.l_lo, a.N, a.d, a.norm_rms && a.dn)) return launch_scan_chunked<T>(a, s);
   if (a.norm_rms && a.dn) {
     const int nch = (int)((a.d + 511) / 512);
     dim3 grid((unsigned)((a.N + 3) / 4)), block(256);
+    if (gam) {
+      switch (nch) {
+        case 1: hipLaunchKernelGGL((scan_rows_kernel<T, 1, true>), grid, block, 0, s, a); break;
+        case 2: hipLaunchKernelGGL((scan_rows_kernel<T, 2, true>), grid, block, 0, s, a); break;
+        case 3: case 4: hipLaunchKernelGGL((scan_rows_kernel<T, 4, true>), grid, block, 0, s, a); break;
+        default: return hipErrorInvalidValue;   // (rejected by the caller: d > 2048)
+      }
+      return hipGetLastError();
+    }
     switch (nch) {
-      case 1: hipLaunchKernelGGL((scan_rows_kernel<T, 1>), grid, block, 0, s, a); break;
-      case 2: hipLaunchKernelGGL((scan_rows_kernel<T, 2>), grid, block, 0, s, a); break;
-      case 3: hipLaunchKernelGGL((scan_rows_kernel<T, 3>), grid, block, 0, s, a); break;
-      case 4: hipLaunchKernelGGL((scan_rows_kernel<T, 4>), grid, block, 0, s, a); break;
-      case 5: case 6: hipLaunchKernelGGL((scan_rows_kernel<T, 6>), grid, block, 0, s, a); break;
-      case 7: case 8: hipLaunchKernelGGL((scan_rows_kernel<T, 8>), grid, block, 0, s, a); break;
+      case 1: hipLaunchKernelGGL((scan_rows_kernel<T, 1, false>), grid, block, 0, s, a); break;
+      case 2: hipLaunchKernelGGL((scan_rows_kernel<T, 2, false>), grid, block, 0, s, a); break;
+      case 3: hipLaunchKernelGGL((scan_rows_kernel<T, 3, false>), grid, block, 0, s, a); break;
+      case 4: hipLaunchKernelGGL((scan_rows_kernel<T, 4, false>), grid, block, 0, s, a); break;
+      case 5: case 6: hipLaunchKernelGGL((scan_rows_kernel<T, 6, false>), grid, block, 0, s, a); break;
+      case 7: case 8: hipLaunchKernelGGL((scan_rows_kernel<T, 8, false>), grid, block, 0, s, a); break;
       default: return hipErrorInvalidValue;
     }
   } else {
     const long vecs = a.N * a.d / 8;
-    hipLaunchKernelGGL(scan_vec_kernel<T>, dim3((unsigned)((vecs + 255) / 256)), dim3(256), 0, s, a);
+    const dim3 grid((unsigned)((vecs + 255) / 256)), block(256);
+    if (gam) hipLaunchKernelGGL((scan_vec_kernel<T, true>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((scan_vec_kernel<T, false>), grid, block, 0, s, a);
   }
   return hipGetLastError();
 }

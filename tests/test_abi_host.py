@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layout_matches_header():
     # field order and sizes as in the header (LP64)
-    assert C.sizeof(B.hbp_desc) == 4 * 8 + 8 * 5
+    assert C.sizeof(B.hbp_desc) == 4 * 8 + 8 * 5 + 4 * 2
     assert C.sizeof(B.hbp_buffers) == 8 + 8 * 15 + 8 + 8
 
 
@@ -53,7 +53,7 @@ def test_workspace_size_scales():
 @pytest.mark.parametrize("field,value,status", [
     ("L", 0, 1), ("N", -1, 1), ("d", 0, 1), ("d", 60, 2), ("d_ff", 100, 2), ("kind", 7, 1), ("dtype", 3, 1),
     ("act", 5, 1), ("norm", 2, 1), ("lambda_kind", 9, 1), ("loss_every_state", 2, 1), ("struct_size", 12, 1),
-    ("d_in", 8, 1),
+    ("d_in", 8, 1), ("gamma", -0.1, 1), ("gamma", 1.5, 1), ("gamma", float("nan"), 1), ("reserved", 1, 1),
 ])
 def test_bad_descriptor_is_rejected(field, value, status):
     d = _desc()

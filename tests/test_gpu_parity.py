@@ -151,6 +151,51 @@ def test_backward_shared_state(B, name):
     _check_backward(B, w, p, st, sv_r, inp, name + "/shared", exact=name != "rnn_chaotic_small")
 
 
+@pytest.mark.parametrize("name,gamma", [("mlp_small_f32", 0.2), ("mlp_f32_ragged", 0.8), ("mlp_f32_ragged", 1.0),
+                                        ("resnet_like_small", 0.2), ("resnet_like_small", 1.0),
+                                        ("deep_small", 0.5), ("rnn_small", 0.3), ("rnn_f32", 1.0), ("rnn_long", 0.2),
+                                        ("aligned_small", 0.8)])
+def test_gamma_iterates(B, name, gamma):
+    """The iteration on the re-split pair (J + gamma K, (1 - gamma) K): every k of
+    the case against the oracle on a shared forward state; gamma = 1 is the
+    fixed-point-iteration baseline.  k >= L gives the exact gradient for any gamma."""
+    w = CASES[name]
+    inp, st, sv, p = _setup(B, w)
+    sv_r = H.oracle_saved_rounded(w, sv)
+    H.upload_saved(p, w, sv_r)
+    tol = H.TOL[w.dtype]
+    for k in w.ks:
+        B.hbp_backward(p, k, gamma=gamma)
+        B.hbp_param_grads(p)
+        torch.cuda.synchronize()
+        want = O.hbp_backward(st, sv_r, inp["e"], k, gamma=gamma)
+        err = H.rel(H.to_np(p.g), want)
+        assert err < tol, f"{name} gamma={gamma} k={k}: g rel L2 {err:.3e}"
+        for l in range(w.L + 1):
+            n = np.linalg.norm(want[l])
+            if n > 1e-30:   # (at gamma = 1 and a loss on the last state only, states below L - k are exactly 0)
+                el = H.rel(H.to_np(p.g[l]), want[l])
+                assert el < 2 * tol, f"{name} gamma={gamma} k={k} state {l}: {el:.3e}"
+            else:
+                assert float(p.g[l].abs().max()) == 0.0
+        pg = O.param_grads(st, sv_r, want, inp["xin"])
+        for nm, t in (("dW1", p.dW1), ("dW2", p.dW2), ("dU", p.dU)):
+            if t is not None:
+                assert H.rel(H.to_np(t), pg[nm]) < tol, f"{name} gamma={gamma} k={k}: {nm}"
+    if w.L <= 40:
+        B.hbp_backward(p, w.L, gamma=gamma)
+        torch.cuda.synchronize()
+        G = O.exact_backward(st, sv_r, inp["e"])
+        assert H.rel(H.to_np(p.g), G) < tol
+
+
+def test_gamma_needs_narrow_rows_with_rms(B):
+    d = B.make_desc("mlp", "bf16", "gelu", "rms", L=2, N=8, d=4096, d_ff=64, gamma=0.5)
+    assert B.workspace_size(B.make_desc("mlp", "bf16", "gelu", "rms", L=2, N=8, d=4096, d_ff=64)) > 0
+    n = __import__("ctypes").c_size_t(0)
+    assert B.lib().hbp_workspace_size(__import__("ctypes").byref(d), __import__("ctypes").byref(n)) == 2
+
+
 def test_k_beyond_L_is_exact_and_deterministic(B):
     w = CASES["resnet_like_odd"]
     inp, st, sv, p = _setup(B, w)
