@@ -225,9 +225,13 @@ constexpr int CH_ROWS = 32;
 
 // HAS_DN / HAS_E are compile-time so that the unrolled loop has no branches
 // around its loads and several steps' loads are in flight at once.
-template <typename T, bool APPLY, bool HAS_DN, bool HAS_E>
+// HAS_G: the re-split iteration's extra term gamma lambda_l (.) g_{l+1}^{old}.  A thread reads the old
+// g_l of its chunk before it overwrites it; the old state above the chunk belongs to another
+// workgroup's chunk, so the reduce pass (which writes nothing to g) saves it for the apply pass.
+template <typename T, bool APPLY, bool HAS_DN, bool HAS_E, bool HAS_G>
 __global__ __launch_bounds__(256) void scan_chunk_kernel(ScanArgs a, long nchunks) {
-  __shared__ float lam_s[SCAN_CHUNK][64];
+  __shared__ float lam_s[SCAN_CHUNK][64];                  // res_scale * lambda
+  __shared__ float glam_s[HAS_G ? SCAN_CHUNK : 1][64];     // blk_gamma * lambda
   const int tid = threadIdx.x;
   const long c = blockIdx.y;                 // neighbouring workgroups take neighbouring channel slabs
   const long ch0 = (long)blockIdx.x * 64;
@@ -242,13 +246,19 @@ __global__ __launch_bounds__(256) void scan_chunk_kernel(ScanArgs a, long nchunk
   const T* __restrict__ e = reinterpret_cast<const T*>(a.e);
   float* B = a.chunk_ws;                                   // [nchunks][N][d]
   float* cin = a.chunk_ws + nchunks * layer;               // [nchunks][N][d]
+  float* gtop = a.chunk_ws + 2 * nchunks * layer + nchunks * a.d;   // [nchunks][N][d]: old g above each chunk
 
-  // stage lambda[l_bot .. l_top)[ch0 .. ch0+63] (ones where there is none)
+  // stage lambda[l_bot .. l_top)[ch0 .. ch0+63] (ones where there is none), scaled
   for (int i = tid; i < steps * 16; i += 256) {
     const int s = i >> 4, q = (i & 15) * 4;
     float4 v = make_float4(1.f, 1.f, 1.f, 1.f);
     if (a.lambda && ch0 + q < a.d) v = *reinterpret_cast<const float4*>(a.lambda + (l_bot + s) * a.d + ch0 + q);
-    *reinterpret_cast<float4*>(&lam_s[s][q]) = v;
+    const float rs = a.res_scale;
+    *reinterpret_cast<float4*>(&lam_s[s][q]) = make_float4(rs * v.x, rs * v.y, rs * v.z, rs * v.w);
+    if (HAS_G) {
+      const float bg = a.blk_gamma;
+      *reinterpret_cast<float4*>(&glam_s[s][q]) = make_float4(bg * v.x, bg * v.y, bg * v.z, bg * v.w);
+    }
   }
   __syncthreads();
   if (!APPLY && blockIdx.z == 0 && tid < 64 && ch0 + tid < a.d) {   // A = product of lambda over the chunk
@@ -263,16 +273,26 @@ __global__ __launch_bounds__(256) void scan_chunk_kernel(ScanArgs a, long nchunk
 #pragma unroll
   for (int i = 0; i < 8; ++i) carry[i] = 0.f;
   if (APPLY) load8(cin + c * layer + off, carry);
+  float gold[8];            // the old g one state up
+  if (HAS_G) {
+    if (APPLY) {
+      load8(gtop + c * layer + off, gold);
+    } else {
+      load8(g + l_top * layer + off, gold);
+      store8(gtop + c * layer + off, gold);
+    }
+  }
   // batches of 8 steps: all their loads are issued before the first value is used
   constexpr int BATCH = 8;
   for (int s0 = steps; s0 > 0; s0 -= BATCH) {
-    Raw8<T> rb[BATCH], re[BATCH];
+    Raw8<T> rb[BATCH], re[BATCH], rg[HAS_G ? BATCH : 1];
 #pragma unroll
     for (int j = 0; j < BATCH; ++j) {
       const int s = s0 - 1 - j;
       if (s >= 0) {
         if (HAS_DN) rb[j].load(dn + (l_bot + s) * layer + off);
         if (HAS_E) re[j].load(e + (l_bot + s) * layer + off);
+        if (HAS_G) rg[HAS_G ? j : 0].load(g + (l_bot + s) * layer + off);   // old g_l: stored to only further down
       }
     }
 #pragma unroll
@@ -293,6 +313,13 @@ __global__ __launch_bounds__(256) void scan_chunk_kernel(ScanArgs a, long nchunk
         for (int i = 0; i < 8; ++i) b[i] += t[i];
       }
       load8(&lam_s[s][(tid & 7) * 8], lam);
+      if (HAS_G) {
+        float gl[8];
+        load8(&glam_s[HAS_G ? s : 0][(tid & 7) * 8], gl);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) b[i] = fmaf(gl[i], gold[i], b[i]);
+        rg[HAS_G ? j : 0].unpack(gold);
+      }
 #pragma unroll
       for (int i = 0; i < 8; ++i) carry[i] = fmaf(lam[i], carry[i], b[i]);
       if (APPLY) store8(g + (l_bot + s) * layer + off, carry);
@@ -339,6 +366,21 @@ inline bool use_chunked(long L, long N, long d, int norm_rms) {
   return !norm_rms && L >= 4 * SCAN_CHUNK && N * d / 8 < 256L * 1024;
 }
 
+template <typename T, bool APPLY>
+void launch_chunk_pass(const ScanArgs& a, long nchunks, dim3 grid, dim3 block, hipStream_t s) {
+  const int var = (a.dn ? 1 : 0) | (a.e ? 2 : 0) | (a.blk_gamma != 0.f ? 4 : 0);
+  switch (var) {
+    case 0: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, false, false, false>), grid, block, 0, s, a, nchunks); break;
+    case 1: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, true, false, false>), grid, block, 0, s, a, nchunks); break;
+    case 2: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, false, true, false>), grid, block, 0, s, a, nchunks); break;
+    case 3: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, true, true, false>), grid, block, 0, s, a, nchunks); break;
+    case 4: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, false, false, true>), grid, block, 0, s, a, nchunks); break;
+    case 5: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, true, false, true>), grid, block, 0, s, a, nchunks); break;
+    case 6: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, false, true, true>), grid, block, 0, s, a, nchunks); break;
+    default: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, true, true, true>), grid, block, 0, s, a, nchunks); break;
+  }
+}
+
 template <typename T>
 hipError_t launch_scan_chunked(const ScanArgs& a, hipStream_t s) {
   const long L = a.l_hi - a.l_lo;
@@ -347,28 +389,17 @@ hipError_t launch_scan_chunked(const ScanArgs& a, hipStream_t s) {
   float* A = a.chunk_ws + 2 * nchunks * layer;
   const dim3 block(256);
   const dim3 grid((unsigned)((a.d + 63) / 64), (unsigned)nchunks, (unsigned)((a.N + CH_ROWS - 1) / CH_ROWS));
-  const int var = (a.dn ? 1 : 0) | (a.e ? 2 : 0);
-  switch (var) {
-    case 1: hipLaunchKernelGGL((scan_chunk_kernel<T, false, true, false>), grid, block, 0, s, a, nchunks); break;
-    case 2: hipLaunchKernelGGL((scan_chunk_kernel<T, false, false, true>), grid, block, 0, s, a, nchunks); break;
-    case 3: hipLaunchKernelGGL((scan_chunk_kernel<T, false, true, true>), grid, block, 0, s, a, nchunks); break;
-    default: hipLaunchKernelGGL((scan_chunk_kernel<T, false, false, false>), grid, block, 0, s, a, nchunks); break;
-  }
+  launch_chunk_pass<T, false>(a, nchunks, grid, block, s);
   hipLaunchKernelGGL(scan_chunk_combine_kernel<T>, dim3((unsigned)((layer / 8 + 255) / 256)), block, 0, s, a, nchunks, A);
-  switch (var) {
-    case 1: hipLaunchKernelGGL((scan_chunk_kernel<T, true, true, false>), grid, block, 0, s, a, nchunks); break;
-    case 2: hipLaunchKernelGGL((scan_chunk_kernel<T, true, false, true>), grid, block, 0, s, a, nchunks); break;
-    case 3: hipLaunchKernelGGL((scan_chunk_kernel<T, true, true, true>), grid, block, 0, s, a, nchunks); break;
-    default: hipLaunchKernelGGL((scan_chunk_kernel<T, true, false, false>), grid, block, 0, s, a, nchunks); break;
-  }
+  launch_chunk_pass<T, true>(a, nchunks, grid, block, s);
   return hipGetLastError();
 }
 
 template <typename T>
 hipError_t launch_scan_t(const ScanArgs& a, hipStream_t s) {
   if (a.l_hi <= a.l_lo) return hipSuccess;
-  const bool gam = a.res_scale != 1.f || a.blk_gamma != 0.f;   // (the chunked form covers the plain recurrence only)
-  if (!gam && a.chunk_ws && use_chunked(a.l_hi - a.l_lo, a.N, a.d, a.norm_rms && a.dn)) return launch_scan_chunked<T>(a, s);
+  const bool gam = a.res_scale != 1.f || a.blk_gamma != 0.f;
+  if (a.chunk_ws && use_chunked(a.l_hi - a.l_lo, a.N, a.d, a.norm_rms && a.dn)) return launch_scan_chunked<T>(a, s);
   if (a.norm_rms && a.dn) {
     const int nch = (int)((a.d + 511) / 512);
     dim3 grid((unsigned)((a.N + 3) / 4)), block(256);
@@ -404,7 +435,7 @@ hipError_t launch_scan_t(const ScanArgs& a, hipStream_t s) {
 size_t scan_chunk_ws_bytes(long L, long N, long d, int norm_rms) {
   if (!use_chunked(L, N, d, norm_rms)) return 0;
   const long nchunks = (L + SCAN_CHUNK - 1) / SCAN_CHUNK;
-  return (size_t)(2 * nchunks * N * d + nchunks * d) * sizeof(float);
+  return (size_t)(3 * nchunks * N * d + nchunks * d) * sizeof(float);   // B, cin, old g above each chunk; A
 }
 
 hipError_t launch_scan(int dtype, const ScanArgs& a, hipStream_t s) {

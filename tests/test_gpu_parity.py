@@ -153,7 +153,7 @@ def test_backward_shared_state(B, name):
 
 @pytest.mark.parametrize("name,gamma", [("mlp_small_f32", 0.2), ("mlp_f32_ragged", 0.8), ("mlp_f32_ragged", 1.0),
                                         ("resnet_like_small", 0.2), ("resnet_like_small", 1.0),
-                                        ("deep_small", 0.5), ("rnn_small", 0.3), ("rnn_f32", 1.0), ("rnn_long", 0.2),
+                                        ("deep_small", 0.5), ("rnn_small", 0.3), ("rnn_f32", 1.0), ("rnn_long", 0.2), ("rnn_long", 1.0),
                                         ("aligned_small", 0.8)])
 def test_gamma_iterates(B, name, gamma):
     """The iteration on the re-split pair (J + gamma K, (1 - gamma) K): every k of
