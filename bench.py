@@ -68,24 +68,38 @@ def algorithmic_work(w, k):
 def gpu_errors(B, torch, p, ks, gamma=None):
     """Relative L2 error and cosine of the k-iteration estimate against exact BP,
     both from the GPU library, for states 0..L-1 and for all parameter gradients."""
+    def sums(a_list, b_list):   # (|a-b|^2, |a|^2, |b|^2, a.b) in fp64, one tensor slab at a time
+        acc = torch.zeros(4, dtype=torch.float64, device=a_list[0].device)
+        for a, b in zip(a_list, b_list):
+            a = a.reshape(-1).double()
+            b = b.reshape(-1).double()
+            acc += torch.stack([((a - b) ** 2).sum(), (a * a).sum(), (b * b).sum(), (a * b).sum()])
+        return [float(v) for v in acc]
+
+    def figures(est, ref):
+        d2, a2, b2, ab = sums(est, ref)
+        return (d2 / b2) ** 0.5, ab / (a2 * b2) ** 0.5
+
     B.hbp_exact_backward(p)
     B.hbp_param_grads(p)
     torch.cuda.synchronize()
-    G = p.g[:-1].float().clone()
-    PG = torch.cat([t.flatten() for t in (p.dW1, p.dW2, p.dU) if t is not None]).clone()
+    L = p.g.shape[0] - 1
+    G = p.g[:-1].clone()
+    PG = [t.clone() for t in (p.dW1, p.dW2, p.dU) if t is not None]
     out = {}
     for k in ks:
         B.hbp_backward(p, k, gamma=gamma)
         B.hbp_param_grads(p)
         torch.cuda.synchronize()
-        g = p.g[:-1].float()
-        pg = torch.cat([t.flatten() for t in (p.dW1, p.dW2, p.dU) if t is not None])
-        out[str(k)] = {
-            "state_rel_l2": float((g - G).norm() / G.norm()),
-            "state_cos": float((g.flatten() @ G.flatten()) / (g.norm() * G.norm())),
-            "param_rel_l2": float((pg - PG).norm() / PG.norm()),
-            "param_cos": float((pg @ PG) / (pg.norm() * PG.norm())),
-        }
+        s_rel, s_cos = figures([p.g[l] for l in range(L)], [G[l] for l in range(L)])
+        pg = [t for t in (p.dW1, p.dW2, p.dU) if t is not None]
+        if pg[0].dim() == 3:    # per-layer slabs
+            est = [t[l] for t in pg for l in range(t.shape[0])]
+            ref = [t[l] for t in PG for l in range(t.shape[0])]
+        else:
+            est, ref = pg, PG
+        p_rel, p_cos = figures(est, ref)
+        out[str(k)] = {"state_rel_l2": s_rel, "state_cos": s_cos, "param_rel_l2": p_rel, "param_cos": p_cos}
     return out
 
 
