@@ -601,10 +601,11 @@ __device__ __forceinline__ void epilogue_staged_fn(const GemmArgs& g, const Tile
   const int m_sw = (mr >> 1) & 7;
   auto fetch = [&](Quad16& q, int round) {
     const bf16_t* a = aux + (long)(32 * round) * g.ldc;
-    q.x0 = *reinterpret_cast<const uint4v*>(a);
-    q.x1 = *reinterpret_cast<const uint4v*>(a + ld8);
-    q.x2 = *reinterpret_cast<const uint4v*>(a + 2 * ld8);
-    q.x3 = *reinterpret_cast<const uint4v*>(a + 3 * ld8);
+    // (streamed once: non-temporal, so that it does not push the operand panels out of L2)
+    q.x0 = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(a));
+    q.x1 = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(a + ld8));
+    q.x2 = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(a + 2 * ld8));
+    q.x3 = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(a + 3 * ld8));
   };
   auto round = [&](auto ic, const Quad16& q) {
     constexpr int i = decltype(ic)::value;
@@ -641,10 +642,10 @@ __device__ __forceinline__ void epilogue_staged_fn(const GemmArgs& g, const Tile
     const uint4v o2 = *reinterpret_cast<const uint4v*>(p2);
     const uint4v o3 = *reinterpret_cast<const uint4v*>(p3);
     bf16_t* c = cp + (long)(32 * i) * g.ldc;
-    *reinterpret_cast<uint4v*>(c) = o0;
-    *reinterpret_cast<uint4v*>(c + ld8) = o1;
-    *reinterpret_cast<uint4v*>(c + 2 * ld8) = o2;
-    *reinterpret_cast<uint4v*>(c + 3 * ld8) = o3;
+    __builtin_nontemporal_store(o0, reinterpret_cast<uint4v*>(c));
+    __builtin_nontemporal_store(o1, reinterpret_cast<uint4v*>(c + ld8));
+    __builtin_nontemporal_store(o2, reinterpret_cast<uint4v*>(c + 2 * ld8));
+    __builtin_nontemporal_store(o3, reinterpret_cast<uint4v*>(c + 3 * ld8));
   };
   Quad16 qa = {}, qb = {};
   if (HAS_AUX) { fetch(qa, 0); fetch(qb, 1); }
