@@ -152,7 +152,7 @@ def main():
                     help="run plain 1 GiB device copies and exit (reference for rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (sharding is described in DESIGN.md)",
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives or sharding are built)",
               file=sys.stderr)
         sys.exit(2)
 
