@@ -57,7 +57,10 @@ class Stack:
                   l+1 and consumes xin[l]
     act    'gelu' (exact erf form) | 'tanh' | 'identity'
     norm   'none' | 'rms'  (no gain, eps inside the square root)
-    lam    None (lambda = 1) or [L, d]
+    lam    None (lambda = 1), [L, d] (one coefficient per block and channel,
+           shared by all tokens) or [L, N, d] (per token as well: a diagonal
+           K_l that depends on the data, given here as data, e.g. gates computed
+           from the input of a recurrent cell; Section "Layer decomposition")
     """
     kind: str
     act: str
@@ -101,9 +104,10 @@ class Stack:
         return self.W2[l] if self.kind == "mlp" else self.W2
 
     def lam_row(self, l: int) -> np.ndarray:
+        """Diagonal of K carrying state l+1 to state l, as [1, d] or [N, d]."""
         if self.lam is None:
-            return np.ones(self.d, dtype=F64)
-        return self.lam[l]
+            return np.ones((1, self.d), dtype=F64)
+        return np.atleast_2d(self.lam[l])
 
 
 # --------------------------------------------------------------------------
@@ -154,7 +158,7 @@ def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict
         a[l] = y[l] @ st.w1(l).T
         if st.kind == "rnn":
             a[l] += np.asarray(xin[l], dtype=F64) @ st.U.T
-        x[l + 1] = st.lam_row(l)[None, :] * x[l] + act_fn(st.act, a[l]) @ st.w2(l).T
+        x[l + 1] = st.lam_row(l) * x[l] + act_fn(st.act, a[l]) @ st.w2(l).T
     return {"x": x, "y": y, "rinv": rinv, "a": a,
             "z": act_fn(st.act, a), "dphi": act_grad(st.act, a)}
 
@@ -199,7 +203,7 @@ def exact_backward(st: Stack, saved: Dict[str, np.ndarray], e: np.ndarray) -> np
     G = np.zeros_like(ef)
     G[st.L] = ef[st.L]
     for l in range(st.L - 1, -1, -1):
-        G[l] = ef[l] + st.lam_row(l)[None, :] * G[l + 1] + block_vjp(st, l, saved, G[l + 1])
+        G[l] = ef[l] + st.lam_row(l) * G[l + 1] + block_vjp(st, l, saved, G[l + 1])
     return G
 
 
@@ -217,7 +221,7 @@ def cumsumprod_reverse(a: np.ndarray, lam_rows) -> np.ndarray:
     u = np.zeros_like(a)
     u[P - 1] = a[P - 1]
     for i in range(P - 2, -1, -1):
-        u[i] = a[i] + lam_rows(i)[None, :] * u[i + 1]
+        u[i] = a[i] + np.atleast_2d(lam_rows(i)) * u[i + 1]
     return u
 
 
@@ -249,7 +253,7 @@ def hbp_backward(st: Stack, saved: Dict[str, np.ndarray], e: np.ndarray, k: int,
         for l in range(L):
             v[l] = block_vjp(st, l, saved, w[l + 1])
             if gamma != 0.0:
-                v[l] = v[l] + gamma * st.lam_row(l)[None, :] * w[l + 1]
+                v[l] = v[l] + gamma * st.lam_row(l) * w[l + 1]
         u = cumsumprod_reverse(v, k_row)
         w = w0 + u
         hist.append(w.copy())

@@ -62,6 +62,12 @@ CASES = {
                                   w2_scale=1 / np.sqrt(12.0), ks=(0, 1, 2, 5)),
     "rnn_aligned": synth.scaled(W["gated_rnn_contractive"], name="rnn_aligned", L=64, N=8, d=256, d_ff=256,
                                 d_in=128, ks=(0, 1, 2, 3)),
+    # a loss on every state of a depth stack (e read by the scan behind the norm's backward), and without a norm
+    # (e added by the second contraction's epilogue)
+    "mlp_loss_all": synth.scaled(W["resnet_like"], name="mlp_loss_all", L=7, N=96, d=128, d_ff=256,
+                                 loss_every_state=True, w2_scale=1 / np.sqrt(7.0), ks=(0, 1, 3, 7)),
+    "mlp_loss_all_nonorm": synth.scaled(W["resnet_like"], name="mlp_loss_all_nonorm", norm="none", L=5, N=256, d=256,
+                                        d_ff=256, loss_every_state=True, w2_scale=0.3, ks=(0, 2, 5)),
 }
 
 
@@ -127,7 +133,8 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
 
 @pytest.mark.parametrize("name", ["mlp_small_f32", "mlp_f32_ragged", "resnet_like_small", "resnet_like_odd",
                                   "transformer_small", "deep_small", "rnn_small", "rnn_f32", "rnn_long",
-                                  "mlp_f32_deep", "aligned_small", "rnn_aligned"])
+                                  "mlp_f32_deep", "aligned_small", "rnn_aligned", "mlp_loss_all",
+                                  "mlp_loss_all_nonorm"])
 def test_backward_end_to_end(B, name):
     """Own forward on each side, then Highway-BP at every k of the case, exact BP
     and the parameter gradients."""

@@ -360,6 +360,88 @@ def test_gamma_zero_is_the_plain_method():
         assert np.array_equal(O.hbp_backward(st, sv, e, k), O.hbp_backward(st, sv, e, k, gamma=0.0))
 
 
+# ---------------------------------------------------------------- P10b: per-token diagonal K
+def _per_token(st, N, seed):
+    """The same stack with a coefficient per (block, token, channel)."""
+    r = np.random.default_rng(seed)
+    lam = r.uniform(0.4, 1.1, (st.L, N, st.d))
+    return O.Stack(st.kind, st.act, st.norm, st.W1, st.W2, lam=lam, U=st.U, eps=st.eps, L=st.L)
+
+
+@pytest.mark.parametrize("family", ["mlp", "rnn"])
+def test_per_token_coefficients_token_by_token(family):
+    """Tokens are independent: a stack with coefficients [L, N, d] gives, for token
+    n, what the per-channel stack built from lam[:, n, :] gives for that token alone
+    (forward state, exact gradient, every Highway-BP iterate, with and without gamma)."""
+    r = np.random.default_rng(21)
+    N = 3
+    if family == "rnn":
+        base = small_rnn(T=5, H=4, I=3)
+        xin = r.standard_normal((base.L, N, 3))
+        x0 = np.zeros((N, base.d))
+    else:
+        base = small_mlp(L=4, d=5, dff=6)
+        xin = None
+        x0 = r.standard_normal((N, base.d))
+    st = _per_token(base, N, 5)
+    e = r.standard_normal((st.L + 1, N, st.d))
+    e[0] = 0
+    sv = O.forward(st, x0, xin)
+    G = O.exact_backward(st, sv, e)
+    for n in range(N):
+        one = O.Stack(st.kind, st.act, st.norm, st.W1, st.W2, lam=st.lam[:, n, :], U=st.U, eps=st.eps, L=st.L)
+        xin1 = None if xin is None else xin[:, n:n + 1]
+        sv1 = O.forward(one, x0[n:n + 1], xin1)
+        np.testing.assert_allclose(sv["x"][:, n], sv1["x"][:, 0], rtol=1e-13, atol=1e-14)
+        np.testing.assert_allclose(G[:, n], O.exact_backward(one, sv1, e[:, n:n + 1])[:, 0], rtol=1e-12, atol=1e-14)
+        for k in (0, 1, 2, st.L):
+            for gamma in (0.0, 0.3):
+                w = O.hbp_backward(st, sv, e, k, gamma=gamma)
+                w1 = O.hbp_backward(one, sv1, e[:, n:n + 1], k, gamma=gamma)
+                np.testing.assert_allclose(w[:, n], w1[:, 0], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(O.hbp_backward(st, sv, e, st.L), G, rtol=1e-11, atol=1e-13)
+
+
+def test_per_token_coefficients_by_finite_differences():
+    """Exact gradient with per-token coefficients (held fixed as data) against central
+    differences of the loss in x_0 and in every weight; k = 0 is the per-token
+    cumulative product of the coefficients."""
+    r = np.random.default_rng(8)
+    N = 2
+    st = _per_token(small_mlp(L=3, d=4, dff=5), N, 9)
+    x0 = r.standard_normal((N, st.d))
+    c = r.standard_normal((st.L + 1, N, st.d))
+    sv = O.forward(st, x0)
+    G = O.exact_backward(st, sv, c)
+    pg = O.param_grads(st, sv, G)
+    h = 1e-6
+
+    def fd(arr):
+        out = np.zeros_like(arr)
+        it = np.nditer(arr, flags=["multi_index"])
+        for _ in it:
+            i = it.multi_index
+            old = arr[i]
+            arr[i] = old + h
+            lp = _loss(st, x0, None, c)
+            arr[i] = old - h
+            lm = _loss(st, x0, None, c)
+            arr[i] = old
+            out[i] = (lp - lm) / (2 * h)
+        return out
+
+    np.testing.assert_allclose(G[0], fd(x0), rtol=2e-6, atol=2e-8)
+    np.testing.assert_allclose(pg["dW1"], fd(st.W1), rtol=2e-6, atol=2e-8)
+    np.testing.assert_allclose(pg["dW2"], fd(st.W2), rtol=2e-6, atol=2e-8)
+    eL = r.standard_normal((N, st.d))
+    w0 = O.hbp_backward(st, sv, eL, 0)
+    for i in range(st.L + 1):
+        prod = np.ones((N, st.d))
+        for m in range(i, st.L):
+            prod = prod * st.lam[m]
+        np.testing.assert_allclose(w0[i], eL * prod, rtol=1e-13)
+
+
 # ---------------------------------------------------------------- P9
 def test_gamma_reparametrisation_leaves_exact_gradient_unchanged():
     """Moving gamma*x from the residual connection into the block changes J and K
