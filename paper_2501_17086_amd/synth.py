@@ -39,7 +39,7 @@ class Workload:
     d: int               # state width (rnn: hidden H)
     d_ff: int            # block inner width (rnn: H)
     d_in: int = 0        # rnn input width
-    lam: str = "one"     # 'one' | 'uniform' | 'sigmoid'
+    lam: str = "one"     # 'one' | 'uniform' | 'sigmoid' ([L,d]) | 'sigmoid_full' ([L,N,d]: per token as well)
     lam_lo: float = 1.0
     lam_hi: float = 1.0
     w1_std: float = 0.0  # 0 -> 1/sqrt(fan_in)
@@ -78,6 +78,9 @@ WORKLOADS: Dict[str, Workload] = {
 # specified is chaotic, so exact BPTT gradients overflow over 4096 steps.
 WORKLOADS["gated_rnn_contractive"] = replace(WORKLOADS["gated_rnn"], name="gated_rnn_contractive",
                                              rec_scale=0.25)
+# the same cell with a gate per (step, batch row, channel): a diagonal K that depends on the data
+WORKLOADS["gated_rnn_token_gates"] = replace(WORKLOADS["gated_rnn_contractive"], name="gated_rnn_token_gates",
+                                             lam="sigmoid_full")
 
 
 def scaled(w: Workload, **kw) -> Workload:
@@ -115,11 +118,19 @@ def weights_block(w: Workload, l: int):
     return storage_round(w, W1), storage_round(w, W2)
 
 
-def make_lambda(w: Workload) -> Optional[np.ndarray]:
-    """lambda [L,d] fp32, or None when lambda = 1."""
+def make_lambda(w: Workload, tokens=None) -> Optional[np.ndarray]:
+    """lambda [L,d] fp32, or None when lambda = 1; 'sigmoid_full': [L,N,d] in the
+    storage type (gates that depend on the token, e.g. computed from a cell's input)."""
     if w.lam == "one":
         return None
     g = _rng(w, _T_LAM)
+    if w.lam == "sigmoid_full":
+        sl = tokens if tokens is not None else slice(None)
+        out = np.empty((w.L, len(np.arange(w.N)[sl]), w.d), np.float32)
+        for l in range(w.L):   # drawn layer by layer in the full token range, then cut
+            a = g.standard_normal((w.N, w.d), dtype=np.float32) * np.float32(w.lam_hi) + np.float32(w.lam_lo)
+            out[l] = (1.0 / (1.0 + np.exp(-a.astype(np.float64)))).astype(np.float32)[sl]
+        return storage_round(w, out)
     if w.lam == "uniform":
         return g.uniform(w.lam_lo, w.lam_hi, (w.L, w.d)).astype(np.float32)
     a = g.standard_normal((w.L, w.d), dtype=np.float32) * np.float32(w.lam_hi) + np.float32(w.lam_lo)
@@ -153,7 +164,7 @@ def make_inputs(w: Workload, tokens=None) -> Dict[str, Optional[np.ndarray]]:
         out["U"] = storage_round(w, _normal(w, _T_U, 0, (w.d_ff, w.d_in), 1.0 / np.sqrt(w.d_in)))
         out["xin"] = storage_round(w, _normal(w, _T_XIN, 0, (w.L, w.N, w.d_in), 1.0)[:, sl])
     out["W1"], out["W2"] = W1, W2
-    out["lam"] = make_lambda(w)
+    out["lam"] = make_lambda(w, tokens)
     if w.kind == "rnn":
         out["x0"] = np.zeros((w.N, w.d), np.float32)[sl]
     else:
