@@ -58,9 +58,10 @@ def algorithmic_work(w, k):
     # per iteration the scan reads dn (+ y with a norm; + e only when a norm sits between
     # the block and the residual path: otherwise e was added by the second contraction)
     e_in_scan = w.loss_every_state and w.norm == "rms"
-    streams_in = 1 + (1 if w.norm == "rms" else 0) + (1 if e_in_scan else 0)
+    lam_tok = 1 if w.lam == "sigmoid_full" else 0      # coefficients per token: one more stream
+    streams_in = 1 + (1 if w.norm == "rms" else 0) + (1 if e_in_scan else 0) + lam_tok
     scan_iter = S * s * (streams_in + 1)
-    scan_init = S * s * (1 + (1 if w.loss_every_state else 0))
+    scan_init = S * s * (1 + (1 if w.loss_every_state else 0) + lam_tok)
     return {"vjp1": vjp1, "vjp2": vjp2, "dw": dw, "scan_bytes": scan_init + iters * scan_iter,
             "scan_launches": 1 + iters}
 
@@ -273,7 +274,8 @@ def main():
     if not args.no_cpu_baseline:
         # about 10-20 s of oracle work on the GPU machine's host cores
         n = args.cpu_tokens or {"mlp_small_f32": 128, "resnet_like": 8192, "transformer_mlp": 2048,
-                                "deep_large": 256, "gated_rnn": 16, "gated_rnn_contractive": 16}.get(w.name, 64)
+                                "deep_large": 256, "gated_rnn": 16, "gated_rnn_contractive": 16,
+                                "gated_rnn_token_gates": 16}.get(w.name, 64)
         out["cpu_baseline"] = cpu_baseline(w, k, n)
 
     def finite(o):   # JSON has no NaN/Infinity: overflowed error figures become null

@@ -58,8 +58,10 @@ typedef enum { HBP_MLP = 0, HBP_RNN = 1 } hbp_kind;
 typedef enum { HBP_ACT_GELU_ERF = 0, HBP_ACT_TANH = 1, HBP_ACT_IDENTITY = 2 } hbp_act;
 /* RMS: y = x / sqrt(mean_c(x^2) + eps), no gain. */
 typedef enum { HBP_NORM_NONE = 0, HBP_NORM_RMS = 1 } hbp_norm;
-/* ONE: lambda = 1 (buffers.lambda ignored). CHANNEL: fp32 [L, d], shared by all tokens. */
-typedef enum { HBP_LAMBDA_ONE = 0, HBP_LAMBDA_CHANNEL = 1 } hbp_lambda;
+/* ONE: lambda = 1 (buffers.lambda ignored). CHANNEL: fp32 [L, d], shared by all tokens.
+ * TOKEN: storage type S, [L, N, d]: a diagonal K_l that depends on the data (e.g. gates computed from
+ * a recurrent cell's input), given as data: the backward calls treat it as constant. */
+typedef enum { HBP_LAMBDA_ONE = 0, HBP_LAMBDA_CHANNEL = 1, HBP_LAMBDA_TOKEN = 2 } hbp_lambda;
 
 typedef struct {
   uint32_t struct_size;      /* = sizeof(hbp_desc) */
@@ -89,7 +91,7 @@ typedef struct {
   const void* W1;
   const void* W2;
   const void* U;
-  const float* lambda;       /* [L,d] fp32: row l carries state l+1 to state l */
+  const void* lambda;        /* CHANNEL: fp32 [L,d]; TOKEN: S [L,N,d].  Row (block) l carries state l+1 to state l */
   /* forward state: written by hbp_forward, read by the backward calls. */
   void* x;                   /* S [L+1,N,d]  states x_0..x_L (x[0] is the input) */
   void* y;                   /* S [L,N,d]    norm(x_l); unused (may be NULL) with HBP_NORM_NONE, where x is read */

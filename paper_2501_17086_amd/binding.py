@@ -22,7 +22,7 @@ F32, BF16 = 0, 1
 MLP, RNN = 0, 1
 ACT = {"gelu": 0, "tanh": 1, "identity": 2}
 NORM = {"none": 0, "rms": 1}
-LAMBDA_ONE, LAMBDA_CHANNEL = 0, 1
+LAMBDA_ONE, LAMBDA_CHANNEL, LAMBDA_TOKEN = 0, 1, 2
 
 EXPORTS = ("hbp_workspace_size", "hbp_check", "hbp_forward", "hbp_backward", "hbp_exact_backward",
            "hbp_param_grads", "hbp_profile_enable", "hbp_profile_read", "hbp_status_string")
@@ -82,9 +82,10 @@ def status_string(status: int) -> str:
 
 def make_desc(kind: str, dtype: str, act: str, norm: str, L: int, N: int, d: int, d_ff: int, d_in: int = 0,
               lambda_channel: bool = False, loss_every_state: bool = False, eps: float = 1e-6,
-              gamma: float = 0.0) -> hbp_desc:
+              gamma: float = 0.0, lambda_token: bool = False) -> hbp_desc:
     return hbp_desc(C.sizeof(hbp_desc), RNN if kind == "rnn" else MLP, BF16 if dtype == "bf16" else F32,
-                    ACT[act], NORM[norm], LAMBDA_CHANNEL if lambda_channel else LAMBDA_ONE,
+                    ACT[act], NORM[norm],
+                    LAMBDA_TOKEN if lambda_token else LAMBDA_CHANNEL if lambda_channel else LAMBDA_ONE,
                     1 if loss_every_state else 0, eps, L, N, d, d_ff, d_in, gamma, 0)
 
 
@@ -196,15 +197,18 @@ def allocate(w, inputs, device="cuda:0", N: Optional[int] = None) -> Problem:
     def up(a, dtype=dt):
         return None if a is None else torch.from_numpy(a).to(dev).to(dtype).contiguous()
 
+    lam = inputs["lam"]
+    per_token = lam is not None and lam.ndim == 3      # [L,N,d] in the storage type; [L,d] is fp32
     desc = make_desc(w.kind, w.dtype, w.act, w.norm, w.L, N, w.d, w.d_ff, w.d_in,
-                     lambda_channel=inputs["lam"] is not None, loss_every_state=w.loss_every_state, eps=w.eps)
+                     lambda_channel=lam is not None and not per_token, lambda_token=per_token,
+                     loss_every_state=w.loss_every_state, eps=w.eps)
     L, d, dff = w.L, w.d, w.d_ff
     x = torch.zeros((L + 1, N, d), dtype=dt, device=dev)
     x[0] = up(inputs["x0"])
     rms = w.norm == "rms"
     p = Problem(
         desc=desc, W1=up(inputs["W1"]), W2=up(inputs["W2"]), U=up(inputs["U"]),
-        lam=up(inputs["lam"], torch.float32), x=x,
+        lam=up(lam, dt if per_token else torch.float32), x=x,
         y=torch.zeros((L, N, d), dtype=dt, device=dev) if rms else None,
         rinv=torch.zeros((L, N), dtype=torch.float32, device=dev) if rms else None,
         z=torch.zeros((L, N, dff), dtype=dt, device=dev),

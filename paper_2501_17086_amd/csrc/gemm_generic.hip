@@ -114,7 +114,12 @@ __global__ __launch_bounds__(NT) void gemm_generic_kernel(GemmArgs g) {
           break;
         }
         case EPI_ACT_TANH: v = tanhf(v); break;
-        case EPI_RESID: { float l = lam ? lam[n] : 1.f; v = fmaf(l, Elem<T>::load(aux + off), v); break; }
+        case EPI_RESID: {
+          float l = lam ? lam[n] : 1.f;
+          if (g.lambda_mn) l = Elem<T>::load(reinterpret_cast<const T*>(g.lambda_mn) + batch * g.aux_sb + off);
+          v = fmaf(l, Elem<T>::load(aux + off), v);
+          break;
+        }
         case EPI_ADD_AUX: v += Elem<T>::load(aux + off); break;
         default: break;
       }

@@ -416,7 +416,12 @@ __global__ __launch_bounds__(NTHR, 1) void gemm_mfma_kernel(GemmArgs g, int tile
               }
               break;
             case EPI_RESID:
-              if (lam) {
+              if (g.lambda_mn) {
+                float l4[4];
+                load4(reinterpret_cast<const bf16_t*>(g.lambda_mn) + tc.batch * g.aux_sb + off, l4);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) v[x] = fmaf(l4[x], t[x], v[x]);
+              } else if (lam) {
                 float l4[4];
                 load4(lam + col, l4);
 #pragma unroll
@@ -856,7 +861,7 @@ bool launch_gemm_mfma(const GemmArgs& g, hipStream_t s, hipError_t* err) {
   if (lda % 8 || ldb % 8 || g.ldc % 8 || g.a_sb % 8 || g.b_sb % 8 || g.c_sb % 8) return false;
   if (g.aux_sb % 8 || g.out2_sb % 8 || g.addf_sb % 8 || g.lambda_sb % 8) return false;
   if (!aligned16(g.A) || !aligned16(g.B) || !aligned16(g.C) || !aligned16(g.aux) || !aligned16(g.out2) ||
-      !aligned16(g.addf) || !aligned16(g.lambda))
+      !aligned16(g.addf) || !aligned16(g.lambda) || !aligned16(g.lambda_mn))
     return false;
   if (lda > (1L << 22) || ldb > (1L << 22)) return false;   // per-lane source offsets are 32-bit
   if (g.split_k > 1 && g.mode != EPI_STORE) return false;

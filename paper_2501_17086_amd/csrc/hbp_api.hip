@@ -76,7 +76,7 @@ hbp_status check_desc(const hbp_desc* d) {
   if (d->dtype != HBP_F32 && d->dtype != HBP_BF16) return HBP_E_INVALID_ARG;
   if (d->act < HBP_ACT_GELU_ERF || d->act > HBP_ACT_IDENTITY) return HBP_E_INVALID_ARG;
   if (d->norm != HBP_NORM_NONE && d->norm != HBP_NORM_RMS) return HBP_E_INVALID_ARG;
-  if (d->lambda_kind != HBP_LAMBDA_ONE && d->lambda_kind != HBP_LAMBDA_CHANNEL) return HBP_E_INVALID_ARG;
+  if (d->lambda_kind < HBP_LAMBDA_ONE || d->lambda_kind > HBP_LAMBDA_TOKEN) return HBP_E_INVALID_ARG;
   if (d->loss_every_state != 0 && d->loss_every_state != 1) return HBP_E_INVALID_ARG;
   if (d->L <= 0 || d->N <= 0 || d->d <= 0 || d->d_ff <= 0 || d->d_in < 0) return HBP_E_INVALID_ARG;
   if (d->kind == HBP_RNN && d->d_in <= 0) return HBP_E_INVALID_ARG;
@@ -97,7 +97,7 @@ hbp_status check_bufs(const hbp_desc* d, const hbp_buffers* b, int need) {
   if (b->struct_size != sizeof(hbp_buffers)) return HBP_E_INVALID_ARG;
   if (!b->W1 || !b->W2) return HBP_E_NULL;
   if (d->kind == HBP_RNN && (need & (NEED_FWD | NEED_PG)) && (!b->U || !b->xin)) return HBP_E_NULL;
-  if (d->lambda_kind == HBP_LAMBDA_CHANNEL && !b->lambda) return HBP_E_NULL;
+  if (d->lambda_kind != HBP_LAMBDA_ONE && !b->lambda) return HBP_E_NULL;
   if (d->norm == HBP_NORM_RMS && (!b->y || !b->rinv)) return HBP_E_NULL;
   if (d->norm == HBP_NORM_NONE && !b->x) return HBP_E_NULL;
   if ((need & NEED_FWD) && !b->x) return HBP_E_NULL;
@@ -249,7 +249,8 @@ hbp_status scan_stage(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
   sa.e = (d->loss_every_state && !(has_v && e_in_vjp(d))) ? b->e : nullptr;
   sa.chunk_ws = scan_chunk_ws_bytes(d->L, d->N, d->d, d->norm == HBP_NORM_RMS)
                     ? reinterpret_cast<float*>(at(b->workspace, w.off_scan)) : nullptr;
-  sa.lambda = d->lambda_kind == HBP_LAMBDA_CHANNEL ? b->lambda : nullptr;
+  sa.lambda = d->lambda_kind == HBP_LAMBDA_CHANNEL ? reinterpret_cast<const float*>(b->lambda) : nullptr;
+  sa.lambda_tok = d->lambda_kind == HBP_LAMBDA_TOKEN ? b->lambda : nullptr;
   sa.N = d->N; sa.d = d->d;
   sa.l_lo = l_lo; sa.l_hi = l_hi;
   sa.norm_rms = d->norm == HBP_NORM_RMS;
@@ -400,7 +401,8 @@ hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
       ga.ldc = d->d; ga.batch = 1; ga.split_k = 1;
       ga.mode = EPI_RESID;
       ga.aux = at((const void*)b->x, xo);
-      ga.lambda = d->lambda_kind == HBP_LAMBDA_CHANNEL ? b->lambda + l * d->d : nullptr;
+      ga.lambda = d->lambda_kind == HBP_LAMBDA_CHANNEL ? reinterpret_cast<const float*>(b->lambda) + l * d->d : nullptr;
+      ga.lambda_mn = d->lambda_kind == HBP_LAMBDA_TOKEN ? at(b->lambda, xo) : nullptr;
       HBP_RUN(run_gemm(d, ga, s, HBP_PROF_FORWARD));
     }
   }

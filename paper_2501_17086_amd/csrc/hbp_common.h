@@ -109,6 +109,7 @@ struct GemmArgs {
   void* out2; long out2_sb;           // storage type
   const float* addf; long addf_sb;    // fp32 [M,N], added to acc before the epilogue
   const float* lambda; long lambda_sb;  // fp32 [N]
+  const void* lambda_mn;              // storage type [M,N] (row stride ldc, batch stride aux_sb): EPI_RESID per element
   int c_is_f32;         // C stored as fp32 regardless of the storage type
 };
 
@@ -134,6 +135,7 @@ struct ScanArgs {
   const float* rinv;    // [L,N]   (RMS only)
   const void* e;        // [L+1,N,d] storage or NULL
   const float* lambda;  // [L,d] or NULL
+  const void* lambda_tok;  // [L,N,d] storage, or NULL: coefficients per token (then lambda is NULL)
   long N, d;
   long l_lo, l_hi;
   int norm_rms;

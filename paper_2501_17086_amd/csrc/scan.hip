@@ -48,9 +48,11 @@ __global__ __launch_bounds__(256) void scan_vec_kernel(ScanArgs a) {
     }
     float gl[8];
     if (use_old) load8(g + l * layer + off, gl);     // the old g_l, for the step below
-    if (GAMMA) {
+    if (GAMMA || a.lambda_tok) {
       float lam[8];
-      if (a.lambda) {
+      if (a.lambda_tok) {
+        load8(reinterpret_cast<const T*>(a.lambda_tok) + l * layer + off, lam);
+      } else if (a.lambda) {
         load8(a.lambda + l * a.d + c0, lam);
       } else {
 #pragma unroll
@@ -152,7 +154,9 @@ __global__ __launch_bounds__(256) void scan_rows_kernel(ScanArgs a) {
       if (GAMMA) {
         float lam[8], gl[8];
         load8(g + l * layer + off[j], gl);             // the old g_l, for the step below
-        if (a.lambda) {
+        if (a.lambda_tok) {
+          load8(reinterpret_cast<const T*>(a.lambda_tok) + l * layer + off[j], lam);
+        } else if (a.lambda) {
           load8(a.lambda + l * a.d + (long)j * 512 + lane * 8, lam);
         } else {
 #pragma unroll
@@ -164,6 +168,11 @@ __global__ __launch_bounds__(256) void scan_rows_kernel(ScanArgs a) {
           carry[j][i] = fmaf(a.res_scale * lam[i], carry[j][i], t[i]);
           gold[GAMMA ? j : 0][i] = gl[i];
         }
+      } else if (a.lambda_tok) {
+        float lam[8];
+        load8(reinterpret_cast<const T*>(a.lambda_tok) + l * layer + off[j], lam);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) carry[j][i] = fmaf(lam[i], carry[j][i], t[i]);
       } else if (a.lambda) {
         float lam[8];
         load8(a.lambda + l * a.d + (long)j * 512 + lane * 8, lam);
@@ -228,7 +237,9 @@ constexpr int CH_ROWS = 32;
 // HAS_G: the re-split iteration's extra term gamma lambda_l (.) g_{l+1}^{old}.  A thread reads the old
 // g_l of its chunk before it overwrites it; the old state above the chunk belongs to another
 // workgroup's chunk, so the reduce pass (which writes nothing to g) saves it for the apply pass.
-template <typename T, bool APPLY, bool HAS_DN, bool HAS_E, bool HAS_G>
+// LTOK: coefficients per token ([L,N,d], read like the other streams) instead of per channel; the
+// chunk's product A is then per chain as well.
+template <typename T, bool APPLY, bool HAS_DN, bool HAS_E, bool HAS_G, bool LTOK>
 __global__ __launch_bounds__(256) void scan_chunk_kernel(ScanArgs a, long nchunks) {
   __shared__ float lam_s[SCAN_CHUNK][64];                  // res_scale * lambda
   __shared__ float glam_s[HAS_G ? SCAN_CHUNK : 1][64];     // blk_gamma * lambda
@@ -246,13 +257,15 @@ __global__ __launch_bounds__(256) void scan_chunk_kernel(ScanArgs a, long nchunk
   const T* __restrict__ e = reinterpret_cast<const T*>(a.e);
   float* B = a.chunk_ws;                                   // [nchunks][N][d]
   float* cin = a.chunk_ws + nchunks * layer;               // [nchunks][N][d]
-  float* gtop = a.chunk_ws + 2 * nchunks * layer + nchunks * a.d;   // [nchunks][N][d]: old g above each chunk
+  float* Aout = a.chunk_ws + 2 * nchunks * layer;          // [nchunks][d], or [nchunks][N][d] with LTOK
+  float* gtop = a.chunk_ws + 3 * nchunks * layer;          // [nchunks][N][d]: old g above each chunk
+  const T* __restrict__ ltok = reinterpret_cast<const T*>(a.lambda_tok);
 
   // stage lambda[l_bot .. l_top)[ch0 .. ch0+63] (ones where there is none), scaled
   for (int i = tid; i < steps * 16; i += 256) {
     const int s = i >> 4, q = (i & 15) * 4;
     float4 v = make_float4(1.f, 1.f, 1.f, 1.f);
-    if (a.lambda && ch0 + q < a.d) v = *reinterpret_cast<const float4*>(a.lambda + (l_bot + s) * a.d + ch0 + q);
+    if (!LTOK && a.lambda && ch0 + q < a.d) v = *reinterpret_cast<const float4*>(a.lambda + (l_bot + s) * a.d + ch0 + q);
     const float rs = a.res_scale;
     *reinterpret_cast<float4*>(&lam_s[s][q]) = make_float4(rs * v.x, rs * v.y, rs * v.z, rs * v.w);
     if (HAS_G) {
@@ -261,17 +274,17 @@ __global__ __launch_bounds__(256) void scan_chunk_kernel(ScanArgs a, long nchunk
     }
   }
   __syncthreads();
-  if (!APPLY && blockIdx.z == 0 && tid < 64 && ch0 + tid < a.d) {   // A = product of lambda over the chunk
+  if (!LTOK && !APPLY && blockIdx.z == 0 && tid < 64 && ch0 + tid < a.d) {   // A = product of lambda over the chunk
     float p = 1.f;
     for (int s = 0; s < steps; ++s) p *= lam_s[s][tid];
-    a.chunk_ws[2 * nchunks * layer + c * a.d + ch0 + tid] = p;
+    Aout[c * a.d + ch0 + tid] = p;
   }
   if (row >= a.N || ch >= a.d) return;
 
   const long off = row * a.d + ch;
-  float carry[8];
+  float carry[8], prod[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) carry[i] = 0.f;
+  for (int i = 0; i < 8; ++i) { carry[i] = 0.f; prod[i] = 1.f; }
   if (APPLY) load8(cin + c * layer + off, carry);
   float gold[8];            // the old g one state up
   if (HAS_G) {
@@ -285,7 +298,7 @@ __global__ __launch_bounds__(256) void scan_chunk_kernel(ScanArgs a, long nchunk
   // batches of 8 steps: all their loads are issued before the first value is used
   constexpr int BATCH = 8;
   for (int s0 = steps; s0 > 0; s0 -= BATCH) {
-    Raw8<T> rb[BATCH], re[BATCH], rg[HAS_G ? BATCH : 1];
+    Raw8<T> rb[BATCH], re[BATCH], rg[HAS_G ? BATCH : 1], rl[LTOK ? BATCH : 1];
 #pragma unroll
     for (int j = 0; j < BATCH; ++j) {
       const int s = s0 - 1 - j;
@@ -293,6 +306,7 @@ __global__ __launch_bounds__(256) void scan_chunk_kernel(ScanArgs a, long nchunk
         if (HAS_DN) rb[j].load(dn + (l_bot + s) * layer + off);
         if (HAS_E) re[j].load(e + (l_bot + s) * layer + off);
         if (HAS_G) rg[HAS_G ? j : 0].load(g + (l_bot + s) * layer + off);   // old g_l: stored to only further down
+        if (LTOK) rl[LTOK ? j : 0].load(ltok + (l_bot + s) * layer + off);
       }
     }
 #pragma unroll
@@ -312,10 +326,21 @@ __global__ __launch_bounds__(256) void scan_chunk_kernel(ScanArgs a, long nchunk
 #pragma unroll
         for (int i = 0; i < 8; ++i) b[i] += t[i];
       }
-      load8(&lam_s[s][(tid & 7) * 8], lam);
+      float gl[8];
+      if (LTOK) {
+        float raw[8];
+        rl[LTOK ? j : 0].unpack(raw);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { lam[i] = a.res_scale * raw[i]; gl[i] = a.blk_gamma * raw[i]; }
+        if (!APPLY) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) prod[i] *= lam[i];
+        }
+      } else {
+        load8(&lam_s[s][(tid & 7) * 8], lam);
+        if (HAS_G) load8(&glam_s[HAS_G ? s : 0][(tid & 7) * 8], gl);
+      }
       if (HAS_G) {
-        float gl[8];
-        load8(&glam_s[HAS_G ? s : 0][(tid & 7) * 8], gl);
 #pragma unroll
         for (int i = 0; i < 8; ++i) b[i] = fmaf(gl[i], gold[i], b[i]);
         rg[HAS_G ? j : 0].unpack(gold);
@@ -325,7 +350,10 @@ __global__ __launch_bounds__(256) void scan_chunk_kernel(ScanArgs a, long nchunk
       if (APPLY) store8(g + (l_bot + s) * layer + off, carry);
     }
   }
-  if (!APPLY) store8(B + c * layer + off, carry);
+  if (!APPLY) {
+    store8(B + c * layer + off, carry);
+    if (LTOK) store8(Aout + c * layer + off, prod);
+  }
 }
 
 template <typename T>
@@ -345,7 +373,7 @@ __global__ __launch_bounds__(256) void scan_chunk_combine_kernel(ScanArgs a, lon
 #pragma unroll
     for (int j = 0; j < BATCH; ++j) {
       const long c = c0 - 1 - j;
-      if (c >= 0) { rb[j].load(B + c * layer + off); rp[j].load(A + c * a.d + ch); }
+      if (c >= 0) { rb[j].load(B + c * layer + off); rp[j].load(a.lambda_tok ? A + c * layer + off : A + c * a.d + ch); }
     }
 #pragma unroll
     for (int j = 0; j < BATCH; ++j) {
@@ -366,18 +394,18 @@ inline bool use_chunked(long L, long N, long d, int norm_rms) {
   return !norm_rms && L >= 4 * SCAN_CHUNK && N * d / 8 < 256L * 1024;
 }
 
-template <typename T, bool APPLY>
+template <typename T, bool APPLY, bool LTOK>
 void launch_chunk_pass(const ScanArgs& a, long nchunks, dim3 grid, dim3 block, hipStream_t s) {
   const int var = (a.dn ? 1 : 0) | (a.e ? 2 : 0) | (a.blk_gamma != 0.f ? 4 : 0);
   switch (var) {
-    case 0: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, false, false, false>), grid, block, 0, s, a, nchunks); break;
-    case 1: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, true, false, false>), grid, block, 0, s, a, nchunks); break;
-    case 2: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, false, true, false>), grid, block, 0, s, a, nchunks); break;
-    case 3: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, true, true, false>), grid, block, 0, s, a, nchunks); break;
-    case 4: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, false, false, true>), grid, block, 0, s, a, nchunks); break;
-    case 5: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, true, false, true>), grid, block, 0, s, a, nchunks); break;
-    case 6: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, false, true, true>), grid, block, 0, s, a, nchunks); break;
-    default: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, true, true, true>), grid, block, 0, s, a, nchunks); break;
+    case 0: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, false, false, false, LTOK>), grid, block, 0, s, a, nchunks); break;
+    case 1: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, true, false, false, LTOK>), grid, block, 0, s, a, nchunks); break;
+    case 2: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, false, true, false, LTOK>), grid, block, 0, s, a, nchunks); break;
+    case 3: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, true, true, false, LTOK>), grid, block, 0, s, a, nchunks); break;
+    case 4: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, false, false, true, LTOK>), grid, block, 0, s, a, nchunks); break;
+    case 5: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, true, false, true, LTOK>), grid, block, 0, s, a, nchunks); break;
+    case 6: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, false, true, true, LTOK>), grid, block, 0, s, a, nchunks); break;
+    default: hipLaunchKernelGGL((scan_chunk_kernel<T, APPLY, true, true, true, LTOK>), grid, block, 0, s, a, nchunks); break;
   }
 }
 
@@ -389,9 +417,11 @@ hipError_t launch_scan_chunked(const ScanArgs& a, hipStream_t s) {
   float* A = a.chunk_ws + 2 * nchunks * layer;
   const dim3 block(256);
   const dim3 grid((unsigned)((a.d + 63) / 64), (unsigned)nchunks, (unsigned)((a.N + CH_ROWS - 1) / CH_ROWS));
-  launch_chunk_pass<T, false>(a, nchunks, grid, block, s);
+  if (a.lambda_tok) launch_chunk_pass<T, false, true>(a, nchunks, grid, block, s);
+  else launch_chunk_pass<T, false, false>(a, nchunks, grid, block, s);
   hipLaunchKernelGGL(scan_chunk_combine_kernel<T>, dim3((unsigned)((layer / 8 + 255) / 256)), block, 0, s, a, nchunks, A);
-  launch_chunk_pass<T, true>(a, nchunks, grid, block, s);
+  if (a.lambda_tok) launch_chunk_pass<T, true, true>(a, nchunks, grid, block, s);
+  else launch_chunk_pass<T, true, false>(a, nchunks, grid, block, s);
   return hipGetLastError();
 }
 
@@ -400,6 +430,7 @@ hipError_t launch_scan_t(const ScanArgs& a, hipStream_t s) {
   if (a.l_hi <= a.l_lo) return hipSuccess;
   const bool gam = a.res_scale != 1.f || a.blk_gamma != 0.f;
   if (a.chunk_ws && use_chunked(a.l_hi - a.l_lo, a.N, a.d, a.norm_rms && a.dn)) return launch_scan_chunked<T>(a, s);
+  (void)gam;
   if (a.norm_rms && a.dn) {
     const int nch = (int)((a.d + 511) / 512);
     dim3 grid((unsigned)((a.N + 3) / 4)), block(256);
@@ -435,7 +466,7 @@ hipError_t launch_scan_t(const ScanArgs& a, hipStream_t s) {
 size_t scan_chunk_ws_bytes(long L, long N, long d, int norm_rms) {
   if (!use_chunked(L, N, d, norm_rms)) return 0;
   const long nchunks = (L + SCAN_CHUNK - 1) / SCAN_CHUNK;
-  return (size_t)(3 * nchunks * N * d + nchunks * d) * sizeof(float);   // B, cin, old g above each chunk; A
+  return (size_t)(4 * nchunks * N * d) * sizeof(float);   // B, cin, A (per chain at most), old g above each chunk
 }
 
 hipError_t launch_scan(int dtype, const ScanArgs& a, hipStream_t s) {

@@ -64,6 +64,16 @@ CASES = {
                                 d_in=128, ks=(0, 1, 2, 3)),
     # a loss on every state of a depth stack (e read by the scan behind the norm's backward), and without a norm
     # (e added by the second contraction's epilogue)
+    # coefficients per (block, token, channel): direct scans (depth, RMS and none) and the chunked scan (time)
+    "rnn_token_gates": synth.scaled(W["gated_rnn_token_gates"], name="rnn_token_gates", L=40, N=9, d=128, d_ff=128,
+                                    d_in=64, ks=(0, 1, 2, 5)),
+    "rnn_token_gates_long": synth.scaled(W["gated_rnn_token_gates"], name="rnn_token_gates_long", L=330, N=5, d=128,
+                                         d_ff=128, d_in=64, ks=(0, 1, 3)),
+    "rnn_token_gates_f32": synth.scaled(W["gated_rnn_token_gates"], name="rnn_token_gates_f32", dtype="f32", L=21,
+                                        N=4, d=64, d_ff=64, d_in=24, ks=(0, 2, 21)),
+    "mlp_token_gates": synth.scaled(W["resnet_like"], name="mlp_token_gates", lam="sigmoid_full", lam_lo=2.0,
+                                    lam_hi=0.7, L=6, N=200, d=256, d_ff=512, w2_scale=1 / np.sqrt(6.0),
+                                    ks=(0, 1, 3, 6)),
     "mlp_loss_all": synth.scaled(W["resnet_like"], name="mlp_loss_all", L=7, N=96, d=128, d_ff=256,
                                  loss_every_state=True, w2_scale=1 / np.sqrt(7.0), ks=(0, 1, 3, 7)),
     "mlp_loss_all_nonorm": synth.scaled(W["resnet_like"], name="mlp_loss_all_nonorm", norm="none", L=5, N=256, d=256,
@@ -80,7 +90,8 @@ def _setup(B, w):
 
 
 @pytest.mark.parametrize("name", ["mlp_small_f32", "mlp_f32_ragged", "resnet_like_small", "resnet_like_odd",
-                                  "transformer_small", "deep_small", "rnn_small", "rnn_f32"])
+                                  "transformer_small", "deep_small", "rnn_small", "rnn_f32", "rnn_token_gates",
+                                  "rnn_token_gates_f32", "mlp_token_gates"])
 def test_forward_parity(B, name):
     w = CASES[name]
     inp, st, sv, p = _setup(B, w)
@@ -134,7 +145,8 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
 @pytest.mark.parametrize("name", ["mlp_small_f32", "mlp_f32_ragged", "resnet_like_small", "resnet_like_odd",
                                   "transformer_small", "deep_small", "rnn_small", "rnn_f32", "rnn_long",
                                   "mlp_f32_deep", "aligned_small", "rnn_aligned", "mlp_loss_all",
-                                  "mlp_loss_all_nonorm"])
+                                  "mlp_loss_all_nonorm", "rnn_token_gates", "rnn_token_gates_long",
+                                  "rnn_token_gates_f32", "mlp_token_gates"])
 def test_backward_end_to_end(B, name):
     """Own forward on each side, then Highway-BP at every k of the case, exact BP
     and the parameter gradients."""
@@ -161,7 +173,8 @@ def test_backward_shared_state(B, name):
 @pytest.mark.parametrize("name,gamma", [("mlp_small_f32", 0.2), ("mlp_f32_ragged", 0.8), ("mlp_f32_ragged", 1.0),
                                         ("resnet_like_small", 0.2), ("resnet_like_small", 1.0),
                                         ("deep_small", 0.5), ("rnn_small", 0.3), ("rnn_f32", 1.0), ("rnn_long", 0.2), ("rnn_long", 1.0),
-                                        ("aligned_small", 0.8)])
+                                        ("aligned_small", 0.8), ("rnn_token_gates", 0.4),
+                                        ("rnn_token_gates_long", 1.0), ("mlp_token_gates", 0.3)])
 def test_gamma_iterates(B, name, gamma):
     """The iteration on the re-split pair (J + gamma K, (1 - gamma) K): every k of
     the case against the oracle on a shared forward state; gamma = 1 is the
