@@ -32,7 +32,7 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch (read + written) measured with rocprofv3's FETCH_SIZE and WRITE_SIZE counters, scaled by
 # what the same counters read for a plain 1 GiB copy (x2.00 and x1.00): profiles/bench_resnet_like_hbm_traffic.txt.
 # Only for the default workload; other workloads report null.
-MEASURED_TRAFFIC = {"resnet_like": {"vjp1": 2.939e9, "vjp2": 1.618e9, "dw": 1.479e9, "scan": 0.823e9}}
+MEASURED_TRAFFIC = {"resnet_like": {"vjp1": 2.686e9, "vjp2": 1.602e9, "dw": 1.523e9, "scan": 0.823e9}}
 
 
 def storage_bytes(w):
