@@ -271,6 +271,21 @@ def main():
                                "state_rel_l2": {kk: v["state_rel_l2"] for kk, v in e.items()}}
             out["per_gamma"] = gs
 
+    if not args.no_sweep:
+        # the initial estimate w^0 by each form of the scan (the paper's Algorithm 1 among them)
+        abl = {}
+        S_bytes = float(w.L) * w.N * w.d * storage_bytes(w)
+        alg_bytes = S_bytes * (1 + (1 if w.loss_every_state else 0) + (1 if w.lam == "sigmoid_full" else 0))
+        for algo in ("auto", "sequential", "chunked", "hillis_steele"):
+            need = B.scan_workspace_size(p.desc, algo)
+            if need > 8 << 30:
+                continue
+            ws = torch.zeros(max(need, 16), dtype=torch.uint8, device=p.g.device)
+            t = time_steps(torch, lambda: B.hbp_initial_estimate(p, algo, workspace=ws), max(3, args.steps // 2), 1)
+            abl[algo] = {"ms": t * 1e3, "algorithmic_GBps": alg_bytes / t / 1e9, "workspace_MB": need / 1e6}
+            del ws
+        out["scan_forms_w0"] = abl
+
     if not args.no_cpu_baseline:
         # about 10-20 s of oracle work on the GPU machine's host cores
         n = args.cpu_tokens or {"mlp_small_f32": 128, "resnet_like": 8192, "transformer_mlp": 2048,

@@ -125,6 +125,18 @@ hbp_status hbp_forward(const hbp_desc* desc, hbp_buffers* bufs, void* stream);
  * Reads W1, W2, lambda, y (or x), rinv, z, dphi, e; writes g and the workspace. */
 hbp_status hbp_backward(const hbp_desc* desc, int k, hbp_buffers* bufs, void* stream);
 
+/* The initial estimate alone, g := w^0 = CumSumProd(e, K) (Theorem 2; K scaled by 1 - gamma), by a
+ * named form of the scan: what hbp_backward picks (AUTO), the sequential walk down the chain, the
+ * chunked reduce / combine / apply form, or the Hillis-Steele sweeps of the paper's Algorithm 1 (kept
+ * for comparison: O(L log L) elements moved).  Same result up to rounding order.  The workspace must
+ * hold hbp_scan_workspace_size(desc, algorithm) bytes (CHUNKED and HILLIS_STEELE need more than the
+ * backward calls; AUTO and SEQUENTIAL need hbp_workspace_size()).  Reads e, lambda; writes g. */
+typedef enum {
+  HBP_SCAN_AUTO = 0, HBP_SCAN_SEQUENTIAL = 1, HBP_SCAN_CHUNKED = 2, HBP_SCAN_HILLIS_STEELE = 3
+} hbp_scan_algorithm;
+hbp_status hbp_scan_workspace_size(const hbp_desc* desc, int algorithm, size_t* bytes);
+hbp_status hbp_initial_estimate(const hbp_desc* desc, int algorithm, hbp_buffers* bufs, void* stream);
+
 /* g := exact gradient by L sequential block steps,
  * G_l = e_l + lambda_l (.) G_{l+1} + G_{l+1} J_{l+1}. */
 hbp_status hbp_exact_backward(const hbp_desc* desc, hbp_buffers* bufs, void* stream);

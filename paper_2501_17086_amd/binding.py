@@ -25,6 +25,7 @@ NORM = {"none": 0, "rms": 1}
 LAMBDA_ONE, LAMBDA_CHANNEL, LAMBDA_TOKEN = 0, 1, 2
 
 EXPORTS = ("hbp_workspace_size", "hbp_check", "hbp_forward", "hbp_backward", "hbp_exact_backward",
+           "hbp_scan_workspace_size", "hbp_initial_estimate",
            "hbp_param_grads", "hbp_profile_enable", "hbp_profile_read", "hbp_status_string")
 PROF_CLASSES = ("vjp1", "vjp2", "scan", "dw", "forward", "other")
 
@@ -65,6 +66,8 @@ def lib() -> C.CDLL:
         L.hbp_forward.argtypes = [C.POINTER(hbp_desc), C.POINTER(hbp_buffers), C.c_void_p]
         L.hbp_backward.argtypes = [C.POINTER(hbp_desc), C.c_int, C.POINTER(hbp_buffers), C.c_void_p]
         L.hbp_exact_backward.argtypes = [C.POINTER(hbp_desc), C.POINTER(hbp_buffers), C.c_void_p]
+        L.hbp_scan_workspace_size.argtypes = [C.POINTER(hbp_desc), C.c_int, C.POINTER(C.c_size_t)]
+        L.hbp_initial_estimate.argtypes = [C.POINTER(hbp_desc), C.c_int, C.POINTER(hbp_buffers), C.c_void_p]
         L.hbp_param_grads.argtypes = [C.POINTER(hbp_desc), C.POINTER(hbp_buffers), C.c_void_p]
         L.hbp_profile_enable.argtypes = [C.c_int]
         L.hbp_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -160,6 +163,29 @@ def hbp_backward(p: Problem, k: int, stream=None, gamma: Optional[float] = None)
         desc = hbp_desc.from_buffer_copy(p.desc)
         desc.gamma = float(gamma)
     _call("hbp_backward", lib().hbp_backward(C.byref(desc), int(k), C.byref(b), _stream(stream)))
+
+
+SCAN_ALGORITHMS = {"auto": 0, "sequential": 1, "chunked": 2, "hillis_steele": 3}
+
+
+def scan_workspace_size(desc: hbp_desc, algorithm: str) -> int:
+    n = C.c_size_t(0)
+    _call("hbp_scan_workspace_size", lib().hbp_scan_workspace_size(C.byref(desc), SCAN_ALGORITHMS[algorithm], C.byref(n)))
+    return n.value
+
+
+def hbp_initial_estimate(p: Problem, algorithm: str = "auto", stream=None, workspace=None) -> None:
+    """g := w^0 by the named form of the scan; `workspace` (a uint8 tensor of
+    scan_workspace_size bytes) replaces the Problem's for this call."""
+    saved = p.workspace
+    if workspace is not None:
+        p.workspace = workspace
+    try:
+        b = p.buffers()
+    finally:
+        p.workspace = saved
+    _call("hbp_initial_estimate",
+          lib().hbp_initial_estimate(C.byref(p.desc), SCAN_ALGORITHMS[algorithm], C.byref(b), _stream(stream)))
 
 
 def hbp_exact_backward(p: Problem, stream=None) -> None:

@@ -238,8 +238,9 @@ hbp_status vjp_stage2(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
 
 // gamma: 0 for the exact recurrence; in the iterations of hbp_backward the descriptor's
 hbp_status scan_stage(const hbp_desc* d, const hbp_buffers* b, const Workspace& w, long l_lo, long l_hi,
-                      bool has_v, hipStream_t s, float gamma = 0.f) {
+                      bool has_v, hipStream_t s, float gamma = 0.f, int force = 0) {
   ScanArgs sa{};
+  sa.force = force;
   sa.res_scale = 1.f - gamma;
   sa.blk_gamma = has_v ? gamma : 0.f;   // w^0 has no block term: only the residual path is rescaled
   sa.g = b->g;
@@ -247,8 +248,8 @@ hbp_status scan_stage(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
   sa.y = b->y;
   sa.rinv = b->rinv;
   sa.e = (d->loss_every_state && !(has_v && e_in_vjp(d))) ? b->e : nullptr;
-  sa.chunk_ws = scan_chunk_ws_bytes(d->L, d->N, d->d, d->norm == HBP_NORM_RMS)
-                    ? reinterpret_cast<float*>(at(b->workspace, w.off_scan)) : nullptr;
+  sa.chunk_ws = (force == 2 || scan_chunk_ws_bytes(d->L, d->N, d->d, d->norm == HBP_NORM_RMS))
+                    ? reinterpret_cast<float*>(at(b->workspace, force == 2 ? 0 : w.off_scan)) : nullptr;
   sa.lambda = d->lambda_kind == HBP_LAMBDA_CHANNEL ? reinterpret_cast<const float*>(b->lambda) : nullptr;
   sa.lambda_tok = d->lambda_kind == HBP_LAMBDA_TOKEN ? b->lambda : nullptr;
   sa.N = d->N; sa.d = d->d;
@@ -441,6 +442,45 @@ hbp_status hbp_backward(const hbp_desc* d, int k, hbp_buffers* b, void* stream) 
     HBP_RUN(scan_stage(d, &bb, w, 0, d->L, true, s, d->gamma));
   }
   return HBP_OK;
+}
+
+hbp_status hbp_scan_workspace_size(const hbp_desc* d, int algorithm, size_t* bytes) {
+  if (!bytes) return HBP_E_NULL;
+  HBP_RUN(check_desc(d));
+  switch (algorithm) {
+    case HBP_SCAN_AUTO: case HBP_SCAN_SEQUENTIAL: *bytes = carve(d).total; break;
+    case HBP_SCAN_CHUNKED: *bytes = scan_chunk_ws_bytes_forced(d->L, d->N, d->d); break;
+    case HBP_SCAN_HILLIS_STEELE: *bytes = hs_ws_bytes(d->L, d->N, d->d, d->lambda_kind); break;
+    default: return HBP_E_INVALID_ARG;
+  }
+  return HBP_OK;
+}
+
+hbp_status hbp_initial_estimate(const hbp_desc* d, int algorithm, hbp_buffers* b, void* stream) {
+  size_t need = 0;
+  HBP_RUN(hbp_scan_workspace_size(d, algorithm, &need));
+  if (!b) return HBP_E_NULL;
+  if (b->struct_size != sizeof(hbp_buffers)) return HBP_E_INVALID_ARG;
+  if (!b->e || !b->g) return HBP_E_NULL;
+  if (d->lambda_kind != HBP_LAMBDA_ONE && !b->lambda) return HBP_E_NULL;
+  if (!b->workspace || b->workspace_bytes < need) return HBP_E_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  if (algorithm == HBP_SCAN_HILLIS_STEELE) {
+    HsArgs a{};
+    a.g = b->g; a.e = b->e; a.every_state = d->loss_every_state;
+    a.lambda = d->lambda_kind == HBP_LAMBDA_CHANNEL ? reinterpret_cast<const float*>(b->lambda) : nullptr;
+    a.lambda_tok = d->lambda_kind == HBP_LAMBDA_TOKEN ? b->lambda : nullptr;
+    a.res_scale = 1.f - d->gamma;
+    a.L = d->L; a.N = d->N; a.d = d->d;
+    a.ws = reinterpret_cast<float*>(b->workspace);
+    ProfScope ps(HBP_PROF_SCAN, s);
+    HBP_TRY(launch_scan_hillis_steele(d->dtype, a, s));
+    return HBP_OK;
+  }
+  const Workspace w = carve(d);
+  HBP_RUN(seed_top(d, b, s));
+  return scan_stage(d, b, w, 0, d->L, false, s, d->gamma,
+                    algorithm == HBP_SCAN_SEQUENTIAL ? 1 : algorithm == HBP_SCAN_CHUNKED ? 2 : 0);
 }
 
 hbp_status hbp_exact_backward(const hbp_desc* d, hbp_buffers* b, void* stream) {

@@ -140,6 +140,7 @@ struct ScanArgs {
   long l_lo, l_hi;
   int norm_rms;
   float* chunk_ws;      // scratch of scan_chunk_ws_bytes() for the chunked form (long chains), or NULL
+  int force;            // 0: the launcher picks the form; 1: the sequential form; 2: the chunked form (needs chunk_ws)
   float res_scale;      // factor on lambda along the residual path (1 - gamma; 1 for the plain method)
   float blk_gamma;      // gamma: adds gamma lambda_l (.) g_{l+1}^{old} to v_l (0: nothing read)
 };
@@ -149,6 +150,23 @@ hipError_t launch_scan(int dtype, const ScanArgs& a, hipStream_t s);
 // (0 when the direct form is used).
 constexpr long SCAN_CHUNK = 64;
 size_t scan_chunk_ws_bytes(long L, long N, long d, int norm_rms);
+size_t scan_chunk_ws_bytes_forced(long L, long N, long d);   // the same when the chunked form is asked for by name
+
+// The scan in the form of the paper's Algorithm 1 (Hillis-Steele): ceil(log2(L+1)) sweeps over all
+// positions, each adding the partner 2^s positions up, in fp32 scratch.  Kept for comparison: it
+// moves O(L log L) elements where the forms above move O(L).  u_i = a_i + lambda_i (.) u_{i+1}.
+struct HsArgs {
+  void* g;              // out [L+1,N,d] storage
+  const void* e;        // a: [L+1,N,d] storage (every_state) or [N,d] (a_L only, the rest 0)
+  int every_state;
+  const float* lambda;  // [L,d] or NULL
+  const void* lambda_tok;  // [L,N,d] storage or NULL
+  float res_scale;
+  long L, N, d;
+  float* ws;            // hs_ws_bytes()
+};
+size_t hs_ws_bytes(long L, long N, long d, int lambda_kind);   // 0 one, 1 channel, 2 token
+hipError_t launch_scan_hillis_steele(int dtype, const HsArgs& a, hipStream_t s);
 
 // y = x * rinv, rinv = 1/sqrt(mean(x^2)+eps) for `rows` rows of width d
 hipError_t launch_rmsnorm_fwd(int dtype, const void* x, void* y, float* rinv, long rows, long d, float eps,

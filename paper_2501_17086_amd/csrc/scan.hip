@@ -429,8 +429,12 @@ template <typename T>
 hipError_t launch_scan_t(const ScanArgs& a, hipStream_t s) {
   if (a.l_hi <= a.l_lo) return hipSuccess;
   const bool gam = a.res_scale != 1.f || a.blk_gamma != 0.f;
-  if (a.chunk_ws && use_chunked(a.l_hi - a.l_lo, a.N, a.d, a.norm_rms && a.dn)) return launch_scan_chunked<T>(a, s);
-  (void)gam;
+  const bool rms = a.norm_rms && a.dn;
+  if (a.force == 2) {
+    if (!a.chunk_ws || rms) return hipErrorInvalidValue;
+    return launch_scan_chunked<T>(a, s);
+  }
+  if (a.force == 0 && a.chunk_ws && use_chunked(a.l_hi - a.l_lo, a.N, a.d, rms)) return launch_scan_chunked<T>(a, s);
   if (a.norm_rms && a.dn) {
     const int nch = (int)((a.d + 511) / 512);
     dim3 grid((unsigned)((a.N + 3) / 4)), block(256);
@@ -461,7 +465,133 @@ hipError_t launch_scan_t(const ScanArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Algorithm 1 of the paper's appendix (with the multiplier of position i being the one that carries
+// i+1 to i): after sweep s, u_i holds the terms of positions i .. i + 2^(s+1) - 1 and P_i the
+// product of their multipliers.  Ping-pong buffers: a sweep reads one pair and writes the other.
+// ---------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void hs_init_kernel(HsArgs a, float* u, float* P) {
+  const long layer = a.N * a.d;
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;     // over (L+1) * layer / 8
+  if (idx >= (a.L + 1) * layer / 8) return;
+  const long off = idx * 8, i = off / layer, in_layer = off - i * layer;
+  float v[8];
+  const T* e = reinterpret_cast<const T*>(a.e);
+  if (a.every_state) load8(e + off, v);
+  else if (i == a.L) load8(e + in_layer, v);
+  else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = 0.f;
+  }
+  store8(u + off, v);
+  if (i < a.L) {
+    if (a.lambda_tok) {
+      float l[8];
+      load8(reinterpret_cast<const T*>(a.lambda_tok) + off, l);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) l[j] *= a.res_scale;
+      store8(P + off, l);
+    } else if (in_layer < a.d) {          // the first row of the layer writes the per-channel products
+      float l[8];
+      if (a.lambda) load8(a.lambda + i * a.d + in_layer, l);
+      else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) l[j] = 1.f;
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) l[j] *= a.res_scale;
+      store8(P + i * a.d + in_layer, l);
+    }
+  }
+}
+
+// u_out_i = u_in_i + P_in_i (.) u_in_{i+h}  (positions with a partner), else a copy;
+// P_out_i = P_in_i P_in_{i+h}  (the per-token form here, the per-channel form in hs_p_kernel)
+template <bool TOK>
+__global__ __launch_bounds__(256) void hs_sweep_kernel(HsArgs a, const float* __restrict__ ui, float* __restrict__ uo,
+                                                       const float* __restrict__ Pi, float* __restrict__ Po, long h) {
+  const long layer = a.N * a.d;
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (a.L + 1) * layer / 8) return;
+  const long off = idx * 8, i = off / layer, in_layer = off - i * layer;
+  float v[8];
+  load8(ui + off, v);
+  if (i + h <= a.L) {
+    float p[8], w[8];
+    load8(ui + off + h * layer, w);
+    load8(TOK ? Pi + off : Pi + i * a.d + in_layer % a.d, p);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = fmaf(p[j], w[j], v[j]);
+    if (TOK) {
+      if (i + h <= a.L - 1) {
+        float q[8];
+        load8(Pi + off + h * layer, q);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) p[j] *= q[j];
+      }
+      store8(Po + off, p);
+    }
+  } else if (TOK && i < a.L) {
+    float p[8];
+    load8(Pi + off, p);
+    store8(Po + off, p);
+  }
+  store8(uo + off, v);
+}
+__global__ __launch_bounds__(256) void hs_p_kernel(const float* __restrict__ Pi, float* __restrict__ Po, long L, long d,
+                                                   long h) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= L * d) return;
+  const long i = idx / d;
+  Po[idx] = i + h <= L - 1 ? Pi[idx] * Pi[idx + h * d] : Pi[idx];
+}
+template <typename T>
+__global__ __launch_bounds__(256) void hs_final_kernel(HsArgs a, const float* __restrict__ u) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (a.L + 1) * a.N * a.d / 8) return;
+  float v[8];
+  load8(u + idx * 8, v);
+  store8(reinterpret_cast<T*>(a.g) + idx * 8, v);
+}
+
+template <typename T>
+hipError_t launch_hs_t(const HsArgs& a, hipStream_t s) {
+  const long layer = a.N * a.d, states = (a.L + 1) * layer;
+  const bool tok = a.lambda_tok != nullptr;
+  const long psize = tok ? a.L * layer : a.L * a.d;
+  float* u[2] = {a.ws, a.ws + states};
+  float* P[2] = {a.ws + 2 * states, a.ws + 2 * states + psize};
+  const dim3 block(256), grid((unsigned)((states / 8 + 255) / 256));
+  hipLaunchKernelGGL(hs_init_kernel<T>, grid, block, 0, s, a, u[0], P[0]);
+  int cur = 0;
+  for (long h = 1; h <= a.L; h *= 2) {
+    if (tok) {
+      hipLaunchKernelGGL(hs_sweep_kernel<true>, grid, block, 0, s, a, u[cur], u[cur ^ 1], P[cur], P[cur ^ 1], h);
+    } else {
+      hipLaunchKernelGGL(hs_sweep_kernel<false>, grid, block, 0, s, a, u[cur], u[cur ^ 1], P[cur], P[cur ^ 1], h);
+      hipLaunchKernelGGL(hs_p_kernel, dim3((unsigned)((psize + 255) / 256)), block, 0, s, P[cur], P[cur ^ 1], a.L, a.d, h);
+    }
+    cur ^= 1;
+  }
+  hipLaunchKernelGGL(hs_final_kernel<T>, grid, block, 0, s, a, u[cur]);
+  return hipGetLastError();
+}
+
 }  // namespace
+
+size_t hs_ws_bytes(long L, long N, long d, int lambda_kind) {
+  const size_t states = (size_t)(L + 1) * N * d;
+  const size_t psize = lambda_kind == 2 ? (size_t)L * N * d : (size_t)L * d;
+  return (2 * states + 2 * psize) * sizeof(float);
+}
+hipError_t launch_scan_hillis_steele(int dtype, const HsArgs& a, hipStream_t s) {
+  return dtype == 0 ? launch_hs_t<float>(a, s) : launch_hs_t<bf16_t>(a, s);
+}
+size_t scan_chunk_ws_bytes_forced(long L, long N, long d) {
+  const long nchunks = (L + SCAN_CHUNK - 1) / SCAN_CHUNK;
+  return (size_t)(4 * nchunks * N * d) * sizeof(float);
+}
 
 size_t scan_chunk_ws_bytes(long L, long N, long d, int norm_rms) {
   if (!use_chunked(L, N, d, norm_rms)) return 0;

@@ -209,6 +209,25 @@ def test_gamma_iterates(B, name, gamma):
         assert H.rel(H.to_np(p.g), G) < tol
 
 
+@pytest.mark.parametrize("name", ["mlp_f32_ragged", "resnet_like_small", "rnn_small", "rnn_f32", "rnn_long",
+                                  "rnn_token_gates", "rnn_token_gates_long", "mlp_loss_all", "mlp_small_f32"])
+@pytest.mark.parametrize("algorithm", ["auto", "sequential", "chunked", "hillis_steele"])
+def test_initial_estimate_by_every_form_of_the_scan(B, name, algorithm):
+    """w^0 = CumSumProd(e, K): the sequential walk, the chunked form and the sweeps of the paper's
+    Algorithm 1 give the oracle's result (and so each other's) up to rounding order."""
+    w = CASES[name]
+    inp, st, sv, p = _setup(B, w)
+    ws = torch.zeros(max(B.scan_workspace_size(p.desc, algorithm), 16), dtype=torch.uint8, device=p.g.device)
+    p.g.fill_(float("nan"))
+    B.hbp_initial_estimate(p, algorithm, workspace=ws)
+    torch.cuda.synchronize()
+    want = O.hbp_backward(st, sv, inp["e"], 0)
+    assert H.rel(H.to_np(p.g), want) < H.TOL[w.dtype], f"{name} {algorithm}"
+    for l in range(w.L + 1):
+        if np.linalg.norm(want[l]) > 0:
+            assert H.rel(H.to_np(p.g[l]), want[l]) < 2 * H.TOL[w.dtype], f"{name} {algorithm} state {l}"
+
+
 def test_gamma_needs_narrow_rows_with_rms(B):
     d = B.make_desc("mlp", "bf16", "gelu", "rms", L=2, N=8, d=4096, d_ff=64, gamma=0.5)
     assert B.workspace_size(B.make_desc("mlp", "bf16", "gelu", "rms", L=2, N=8, d=4096, d_ff=64)) > 0
