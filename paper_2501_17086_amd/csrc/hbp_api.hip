@@ -17,7 +17,7 @@ inline size_t esize(const hbp_desc* d) { return d->dtype == HBP_F32 ? 4 : 2; }
 inline bool shared_w(const hbp_desc* d) { return d->kind == HBP_RNN; }
 
 struct Workspace {
-  size_t off_v, off_da, off_part, off_scan, total;
+  size_t off_v, off_da, off_part, off_scan, off_wt, total;
 };
 
 // split-K factor for a parameter-gradient GEMM with `tiles` output tiles and a
@@ -65,8 +65,16 @@ Workspace carve(const hbp_desc* d) {
   }
   w.off_part = o; o = align_up(o + part, 256);
   w.off_scan = o; o = align_up(o + scan_chunk_ws_bytes(d->L, d->N, d->d, d->norm == HBP_NORM_RMS), 256);
+  // transposed copies of the shared weights for step-by-step backpropagation through time
+  w.off_wt = o;
+  if (d->kind == HBP_RNN && d->dtype == HBP_BF16) o = align_up(o + 2 * (size_t)d->d * d->d_ff * es, 256);
   w.total = o;
   return w;
+}
+
+// One step of the recurrence at a time, few rows: the few-row kernel with transposed weights.
+inline bool step_skinny(const hbp_desc* d) {
+  return d->kind == HBP_RNN && d->dtype == HBP_BF16 && skinny_ok(d->N, d->d_ff, d->d) && skinny_ok(d->N, d->d, d->d_ff);
 }
 
 hbp_status check_desc(const hbp_desc* d) {
@@ -178,9 +186,23 @@ inline bool e_in_vjp(const hbp_desc* d) { return d->loss_every_state && d->norm 
 
 // da[l] = (g[l+1] . W2_l) (.) act'(a_l) for blocks l_lo..l_hi-1
 hbp_status vjp_stage1(const hbp_desc* d, const hbp_buffers* b, const Workspace& w, long l_lo, long l_hi,
-                      hipStream_t s) {
+                      hipStream_t s, bool skinny = false) {
   const size_t es = esize(d);
   const long nl = l_hi - l_lo;
+  if (skinny) {   // one step; W2^T [d_ff,d] sits first in the transposed-weight region
+    SkinnyArgs k{};
+    k.A = at(b->g, (size_t)(l_lo + 1) * d->N * d->d * es); k.lda = d->d;
+    k.Bt = at(b->workspace, w.off_wt); k.ldbt = d->d;
+    k.C = at(b->workspace, w.off_da + (size_t)l_lo * d->N * d->d_ff * es); k.ldc = d->d_ff;
+    k.M = d->N; k.N = d->d_ff; k.K = d->d;
+    k.ldaux = d->d_ff;
+    if (d->act == HBP_ACT_GELU_ERF) { k.mode = EPI_MUL_AUX; k.aux = at(b->dphi, (size_t)l_lo * d->N * d->d_ff * es); }
+    else if (d->act == HBP_ACT_TANH) { k.mode = EPI_MUL_1MZ2; k.aux = at(b->z, (size_t)l_lo * d->N * d->d_ff * es); }
+    else k.mode = EPI_STORE;
+    ProfScope ps(HBP_PROF_VJP1, s);
+    HBP_TRY(launch_gemm_skinny(k, s));
+    return HBP_OK;
+  }
   GemmArgs ga{};
   const bool sh = shared_w(d);
   ga.A = at(b->g, (size_t)(l_lo + 1) * d->N * d->d * es);
@@ -210,10 +232,29 @@ hbp_status vjp_stage1(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
 
 // dn[l] = da[l] . W1_l  (into the v buffer)
 hbp_status vjp_stage2(const hbp_desc* d, const hbp_buffers* b, const Workspace& w, long l_lo, long l_hi,
-                      hipStream_t s) {
+                      hipStream_t s, bool skinny = false, bool fuse_scan = false) {
   const size_t es = esize(d);
   const long nl = l_hi - l_lo;
   const bool sh = shared_w(d);
+  if (skinny) {   // W1^T [d,d_ff] follows W2^T
+    SkinnyArgs k{};
+    k.A = at(b->workspace, w.off_da + (size_t)l_lo * d->N * d->d_ff * es); k.lda = d->d_ff;
+    k.Bt = at(b->workspace, w.off_wt + (size_t)d->d * d->d_ff * es); k.ldbt = d->d_ff;
+    k.C = at(b->workspace, w.off_v + (size_t)l_lo * d->N * d->d * es); k.ldc = d->d;
+    k.M = d->N; k.N = d->d; k.K = d->d_ff;
+    k.mode = EPI_STORE;
+    if (e_in_vjp(d)) { k.mode = EPI_ADD_AUX; k.aux = at(b->e, (size_t)l_lo * d->N * d->d * es); k.ldaux = d->d; }
+    if (fuse_scan) {   // g_l = v_l (+ e_l) + lambda_l (.) g_{l+1} written straight into g
+      k.C = at(b->g, (size_t)l_lo * d->N * d->d * es);
+      k.next = at(b->g, (size_t)(l_lo + 1) * d->N * d->d * es);
+      k.mode = EPI_RESID;
+      if (d->lambda_kind == HBP_LAMBDA_CHANNEL) k.lambda = reinterpret_cast<const float*>(b->lambda) + l_lo * d->d;
+      if (d->lambda_kind == HBP_LAMBDA_TOKEN) k.lambda_mn = at(b->lambda, (size_t)l_lo * d->N * d->d * es);
+    }
+    ProfScope ps(HBP_PROF_VJP2, s);
+    HBP_TRY(launch_gemm_skinny(k, s));
+    return HBP_OK;
+  }
   GemmArgs ga{};
   ga.A = at(b->workspace, w.off_da + (size_t)l_lo * d->N * d->d_ff * es);
   ga.B = sh ? b->W1 : at(b->W1, (size_t)l_lo * d->d * d->d_ff * es);
@@ -356,6 +397,7 @@ hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
   const bool sh = shared_w(d);
   const bool rms = d->norm == HBP_NORM_RMS;
   float* ux = reinterpret_cast<float*>(at(b->workspace, w.off_da));
+  const bool skinny = step_skinny(d) && d->act != HBP_ACT_GELU_ERF;
   if (d->kind == HBP_RNN) {  // U . xin for every step at once
     GemmArgs ga{};
     ga.A = b->xin; ga.B = b->U; ga.C = ux;
@@ -375,6 +417,31 @@ hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
       HBP_TRY(launch_rmsnorm_fwd(d->dtype, at((const void*)b->x, xo), at(b->y, xo), b->rinv + l * d->N, d->N, d->d,
                                  d->eps, s));
       yl = at((const void*)b->y, xo);
+    }
+    if (skinny) {   // one step of the recurrence, few rows; the weights as stored are already K-contiguous
+      SkinnyArgs k{};
+      k.A = yl; k.lda = d->d;
+      k.Bt = b->W1; k.ldbt = d->d;
+      k.C = at(b->z, fo); k.ldc = d->d_ff;
+      k.M = d->N; k.N = d->d_ff; k.K = d->d;
+      k.mode = d->act == HBP_ACT_TANH ? EPI_ACT_TANH : EPI_STORE;
+      k.addf = ux + l * d->N * d->d_ff;
+      {
+        ProfScope ps(HBP_PROF_FORWARD, s);
+        HBP_TRY(launch_gemm_skinny(k, s));
+      }
+      SkinnyArgs r{};
+      r.A = at((const void*)b->z, fo); r.lda = d->d_ff;
+      r.Bt = b->W2; r.ldbt = d->d_ff;
+      r.C = at(b->x, xo + (size_t)d->N * d->d * es); r.ldc = d->d;
+      r.M = d->N; r.N = d->d; r.K = d->d_ff;
+      r.mode = EPI_RESID;
+      r.next = at((const void*)b->x, xo);
+      r.lambda = d->lambda_kind == HBP_LAMBDA_CHANNEL ? reinterpret_cast<const float*>(b->lambda) + l * d->d : nullptr;
+      r.lambda_mn = d->lambda_kind == HBP_LAMBDA_TOKEN ? at(b->lambda, xo) : nullptr;
+      ProfScope ps(HBP_PROF_FORWARD, s);
+      HBP_TRY(launch_gemm_skinny(r, s));
+      continue;
     }
     {  // a = y W1^T (+ U xin); z = act(a); dphi = act'(a)
       GemmArgs ga{};
@@ -491,10 +558,18 @@ hbp_status hbp_exact_backward(const hbp_desc* d, hbp_buffers* b, void* stream) {
   hbp_buffers bb = *b;
   if (d->norm == HBP_NORM_NONE) bb.y = bb.x;
   HBP_RUN(seed_top(d, &bb, s));
+  const bool skinny = step_skinny(d);
+  const bool fuse = skinny && d->norm == HBP_NORM_NONE;   // the step along the residual path in the same kernel
+  if (skinny) {
+    ProfScope ps(HBP_PROF_OTHER, s);
+    HBP_TRY(launch_transpose_bf16(bb.W2, at(bb.workspace, w.off_wt), (int)d->d, (int)d->d_ff, s));
+    HBP_TRY(launch_transpose_bf16(bb.W1, at(bb.workspace, w.off_wt + (size_t)d->d * d->d_ff * esize(d)), (int)d->d_ff,
+                                  (int)d->d, s));
+  }
   for (long l = d->L - 1; l >= 0; --l) {
-    HBP_RUN(vjp_stage1(d, &bb, w, l, l + 1, s));
-    HBP_RUN(vjp_stage2(d, &bb, w, l, l + 1, s));
-    HBP_RUN(scan_stage(d, &bb, w, l, l + 1, true, s));
+    HBP_RUN(vjp_stage1(d, &bb, w, l, l + 1, s, skinny));
+    HBP_RUN(vjp_stage2(d, &bb, w, l, l + 1, s, skinny, fuse));
+    if (!fuse) HBP_RUN(scan_stage(d, &bb, w, l, l + 1, true, s));
   }
   return HBP_OK;
 }

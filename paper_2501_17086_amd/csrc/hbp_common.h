@@ -118,6 +118,27 @@ hipError_t launch_gemm_generic(int dtype, const GemmArgs& g, hipStream_t s);
 // fast bf16 MFMA path; returns false when the shape/layout is not covered
 bool launch_gemm_mfma(const GemmArgs& g, hipStream_t s, hipError_t* err);
 
+// Few-row bf16 product with both operands K-contiguous: C[M,N] = epilogue(A[M,K] . Bt[N,K]^T).
+// Modes EPI_STORE, EPI_ACT_TANH, EPI_MUL_AUX, EPI_MUL_1MZ2, EPI_ADD_AUX; aux is bf16 [M,N] with row stride ldaux.
+// EPI_RESID here is the residual path's backward step, C = acc (+ aux) + lambda (.) next: next and
+// lambda_mn are bf16 [M,N] with C's row stride, lambda is fp32 [N]; neither lambda given means 1.
+struct SkinnyArgs {
+  const void* A; long lda;
+  const void* Bt; long ldbt;
+  void* C; long ldc;
+  long M, N, K;
+  int mode;
+  const void* aux; long ldaux;
+  const void* next;
+  const float* lambda;
+  const void* lambda_mn;
+  const float* addf;   // fp32 [M,N] with C's row stride, added to the product before the epilogue; or NULL
+};
+bool skinny_ok(long M, long N, long K);   // M <= 128, N % 32 == 0, K % 64 == 0
+hipError_t launch_gemm_skinny(const SkinnyArgs& a, hipStream_t s);
+// dst[cols,rows] = src[rows,cols]^T, 2-byte elements
+hipError_t launch_transpose_bf16(const void* src, void* dst, int rows, int cols, hipStream_t s);
+
 // out[i] = sum_s part[s][i], i < n
 hipError_t launch_splitk_reduce(const float* part, float* out, long n, int split, hipStream_t s);
 

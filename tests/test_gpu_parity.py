@@ -62,6 +62,12 @@ CASES = {
                                   w2_scale=1 / np.sqrt(12.0), ks=(0, 1, 2, 5)),
     "rnn_aligned": synth.scaled(W["gated_rnn_contractive"], name="rnn_aligned", L=64, N=8, d=256, d_ff=256,
                                 d_in=128, ks=(0, 1, 2, 3)),
+    # exact BPTT one step at a time: 40 batch rows (two 32-row blocks, the second ragged) with d != d_ff through the
+    # few-row kernel, and a width it does not take (96 is no multiple of 64)
+    "rnn_rows_40": synth.scaled(W["gated_rnn_contractive"], name="rnn_rows_40", L=20, N=40, d=192, d_ff=320,
+                                d_in=64, ks=(0, 2)),
+    "rnn_width_96": synth.scaled(W["gated_rnn_contractive"], name="rnn_width_96", L=12, N=7, d=96, d_ff=160,
+                                 d_in=32, ks=(0, 2)),
     # a loss on every state of a depth stack (e read by the scan behind the norm's backward), and without a norm
     # (e added by the second contraction's epilogue)
     # coefficients per (block, token, channel): direct scans (depth, RMS and none) and the chunked scan (time)
@@ -146,7 +152,7 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
                                   "transformer_small", "deep_small", "rnn_small", "rnn_f32", "rnn_long",
                                   "mlp_f32_deep", "aligned_small", "rnn_aligned", "mlp_loss_all",
                                   "mlp_loss_all_nonorm", "rnn_token_gates", "rnn_token_gates_long",
-                                  "rnn_token_gates_f32", "mlp_token_gates"])
+                                  "rnn_token_gates_f32", "mlp_token_gates", "rnn_rows_40", "rnn_width_96"])
 def test_backward_end_to_end(B, name):
     """Own forward on each side, then Highway-BP at every k of the case, exact BP
     and the parameter gradients."""
