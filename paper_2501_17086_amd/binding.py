@@ -60,6 +60,9 @@ def lib() -> C.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is not built; run `python -m paper_2501_17086_amd.build`")
+        # torch ships its own HIP runtime under the same soname: load it first, so that this library binds to the
+        # runtime that owns the tensors' memory and streams (two runtimes in one process do not share them)
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         L.hbp_workspace_size.argtypes = [C.POINTER(hbp_desc), C.POINTER(C.c_size_t)]
         L.hbp_check.argtypes = [C.POINTER(hbp_desc), C.POINTER(hbp_buffers)]
