@@ -11,7 +11,11 @@ and erf are the only library steps; no blocking, fusion or reordering):
   model      Section "Notations and assumptions": h_i = f_i(h_{i-1}),
              f_i(x) = r_i(x, g_i(x)), Jacobian J_i + K_i.  Here the residual
              function is r(x, z) = lam (.) x + z, so K = diag(lam), and the
-             block is  g(x) = W2 . act(W1 . norm(x) [+ U . xin]).
+             block is  g(x) = W2 . act(W1 . norm(x) [+ U . xin]).  With
+             post = 'relu' the residual function is the one of the original
+             ResNet in the table of layer decompositions, r(x, z) =
+             ReLU(lam (.) x + z): with m = 1[lam (.) x + z > 0],
+             K = dr/dx = diag(m (.) lam) and J = dr/dz . dg/dx = diag(m) . dg/dx.
   exact BP   Section "Backpropagation as a system of equations" and the first
              line of the proof of Theorem 1 (chain rule through J + K).
   Highway-BP Theorem 2 (w^0 and the recursion for w^{k+1}) in its two-step
@@ -57,6 +61,8 @@ class Stack:
                   l+1 and consumes xin[l]
     act    'gelu' (exact erf form) | 'tanh' | 'identity'
     norm   'none' | 'rms'  (no gain, eps inside the square root)
+    post   'none' | 'relu': what the residual function applies after the sum
+           (Section "Notations and assumptions": r need not be linear)
     lam    None (lambda = 1), [L, d] (one coefficient per block and channel,
            shared by all tokens) or [L, N, d] (per token as well: a diagonal
            K_l that depends on the data, given here as data, e.g. gates computed
@@ -71,8 +77,10 @@ class Stack:
     U: Optional[np.ndarray] = None
     eps: float = 1e-6
     L: int = 0
+    post: str = "none"
 
     def __post_init__(self):
+        assert self.post in ("none", "relu")
         assert self.kind in ("mlp", "rnn")
         assert self.act in ("gelu", "tanh", "identity")
         assert self.norm in ("none", "rms")
@@ -138,7 +146,8 @@ def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict
 
     Returns x[L+1,N,d] and the saved tensors y = norm(x_l) [L,N,d],
     rinv = 1/rms [L,N] (ones without a norm), a (pre-activation), z = act(a),
-    dphi = act'(a), all [L,N,d_ff].
+    dphi = act'(a), all [L,N,d_ff]; with post = 'relu' the sum goes through a
+    ReLU and mask[l] = 1 where the sum that made x_{l+1} was positive (all ones otherwise).
     """
     x0 = np.asarray(x0, dtype=F64)
     N, d = x0.shape
@@ -147,6 +156,7 @@ def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict
     y = np.zeros((L, N, d), F64)
     rinv = np.ones((L, N), F64)
     a = np.zeros((L, N, dff), F64)
+    mask = np.ones((L, N, d), F64)
     x[0] = x0
     for l in range(L):
         if st.norm == "rms":
@@ -159,7 +169,10 @@ def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict
         if st.kind == "rnn":
             a[l] += np.asarray(xin[l], dtype=F64) @ st.U.T
         x[l + 1] = st.lam_row(l) * x[l] + act_fn(st.act, a[l]) @ st.w2(l).T
-    return {"x": x, "y": y, "rinv": rinv, "a": a,
+        if st.post == "relu":
+            mask[l] = (x[l + 1] > 0.0).astype(F64)
+            x[l + 1] = np.maximum(x[l + 1], 0.0)
+    return {"x": x, "y": y, "rinv": rinv, "a": a, "mask": mask,
             "z": act_fn(st.act, a), "dphi": act_grad(st.act, a)}
 
 
@@ -180,6 +193,14 @@ def block_vjp(st: Stack, l: int, saved: Dict[str, np.ndarray], g_next: np.ndarra
         m = np.mean(dn * y, axis=1, keepdims=True)
         return (dn - y * m) * saved["rinv"][l][:, None]
     return dn
+
+
+def through_r(st: Stack, l: int, saved: Dict[str, np.ndarray], g_next: np.ndarray) -> np.ndarray:
+    """g_{l+1} . dr/d(sum): the gradient of state l+1 taken back through what the residual function applies after
+    the sum (the ReLU's mask, or nothing).  Both dr/dz and dr/dx = this . diag(lam) start from it."""
+    if st.post == "relu":
+        return saved["mask"][l] * g_next
+    return g_next
 
 
 def _e_full(st: Stack, e: np.ndarray, N: int) -> np.ndarray:
@@ -203,7 +224,8 @@ def exact_backward(st: Stack, saved: Dict[str, np.ndarray], e: np.ndarray) -> np
     G = np.zeros_like(ef)
     G[st.L] = ef[st.L]
     for l in range(st.L - 1, -1, -1):
-        G[l] = ef[l] + st.lam_row(l) * G[l + 1] + block_vjp(st, l, saved, G[l + 1])
+        gs = through_r(st, l, saved, G[l + 1])
+        G[l] = ef[l] + st.lam_row(l) * gs + block_vjp(st, l, saved, gs)
     return G
 
 
@@ -244,16 +266,18 @@ def hbp_backward(st: Stack, saved: Dict[str, np.ndarray], e: np.ndarray, k: int,
     N = saved["y"].shape[1]
     L = st.L
     ef = _e_full(st, e, N)
-    k_row = lambda l: (1.0 - gamma) * st.lam_row(l)
+    m_row = (lambda l: saved["mask"][l]) if st.post == "relu" else (lambda l: 1.0)
+    k_row = lambda l: (1.0 - gamma) * m_row(l) * st.lam_row(l)
     w0 = cumsumprod_reverse(ef, k_row)
     w = w0.copy()
     hist = [w0.copy()]
     for _ in range(k):
         v = np.zeros_like(w)                       # v_L = 0: no block above x_L
         for l in range(L):
-            v[l] = block_vjp(st, l, saved, w[l + 1])
+            ws = through_r(st, l, saved, w[l + 1])
+            v[l] = block_vjp(st, l, saved, ws)
             if gamma != 0.0:
-                v[l] = v[l] + gamma * st.lam_row(l) * w[l + 1]
+                v[l] = v[l] + gamma * st.lam_row(l) * ws
         u = cumsumprod_reverse(v, k_row)
         w = w0 + u
         hist.append(w.copy())
@@ -267,8 +291,10 @@ def param_grads(st: Stack, saved: Dict[str, np.ndarray], g: np.ndarray,
                 xin: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
     """dW2_l = sum_n g_{l+1}[n]^T z_l[n] ; dW1_l = sum_n da_l[n]^T y_l[n] ;
     dU = sum da^T xin, with da from the given g.  Shared weights (rnn) sum
-    over l as well."""
+    over l as well.  (With post = 'relu', g_{l+1} is first taken through the mask.)"""
     L = st.L
+    if st.post == "relu":
+        g = np.concatenate([g[:1]] + [through_r(st, l, saved, g[l + 1])[None] for l in range(L)], axis=0)
     if st.kind == "mlp":
         dW1 = np.zeros_like(st.W1)
         dW2 = np.zeros_like(st.W2)

@@ -537,3 +537,90 @@ def test_param_grads_use_the_given_estimate():
     # top block sees the exact gradient at any k; lower ones do not at k = 1
     np.testing.assert_allclose(p1["dW2"][-1], full["dW2"][-1], rtol=1e-11, atol=1e-13)
     assert O.rel_l2(p1["dW1"][0], full["dW1"][0]) > 1e-4
+
+
+# ---------------------------------------------------------------- P12: r(x, z) = ReLU(lam (.) x + z)
+def small_relu_mlp(L=4, d=6, dff=10, norm="rms", seed=5):
+    st = small_mlp(L=L, d=d, dff=dff, norm=norm, seed=seed)
+    st.post = "relu"
+    return st
+
+
+@pytest.mark.parametrize("norm", ["rms", "none"])
+def test_relu_after_the_sum_against_torch_autograd(norm):
+    """The original-ResNet residual function (table of layer decompositions): forward states, every
+    state gradient and every parameter gradient against torch's autograd of the same stack in fp64."""
+    r = np.random.default_rng(31)
+    N = 5
+    st = small_relu_mlp(L=5, d=8, dff=12, norm=norm)
+    x0 = r.standard_normal((N, st.d))
+    c = r.standard_normal((st.L + 1, N, st.d))
+    sv = O.forward(st, x0)
+    assert 0.1 < sv["mask"].mean() < 0.9            # both branches of the ReLU occur
+    assert np.all(sv["x"][1:] >= 0)
+    G = O.exact_backward(st, sv, c)
+    pg = O.param_grads(st, sv, G)
+
+    t = lambda a: torch.tensor(a, dtype=torch.float64, requires_grad=True)
+    W1, W2, lam = t(st.W1), t(st.W2), torch.tensor(st.lam)
+    xs = [t(x0)]
+    for l in range(st.L):
+        x = xs[-1]
+        y = x / torch.sqrt((x * x).mean(dim=1, keepdim=True) + st.eps) if norm == "rms" else x
+        nxt = torch.relu(lam[l] * x + torch.nn.functional.gelu(y @ W1[l].T) @ W2[l].T)
+        nxt.retain_grad()
+        xs.append(nxt)
+    loss = sum((torch.tensor(c[l]) * xs[l]).sum() for l in range(st.L + 1))
+    loss.backward()
+    for l in range(st.L + 1):
+        np.testing.assert_allclose(sv["x"][l], xs[l].detach().numpy(), rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(G[l], xs[l].grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(pg["dW1"], W1.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(pg["dW2"], W2.grad.numpy(), rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("gamma", [0.0, 0.3])
+def test_relu_after_the_sum_by_path_enumeration(gamma):
+    """Theorem 2 with K_l = diag(m_l lam_l) and J_l = diag(m_l) . (block Jacobian), m_l the ReLU's mask: every
+    iterate is the sum over paths with at most k block steps.  The block Jacobians come from central
+    differences of the block's forward map and the masks from the sign of the states."""
+    st = small_relu_mlp(L=5, d=3, dff=4, seed=8)
+    r = np.random.default_rng(4)
+    sv = O.forward(st, r.standard_normal((1, st.d)) + 0.5)
+    e = r.standard_normal((st.L + 1, 1, st.d))
+    Jb = _dense_block_jacobians(st, sv, 0)
+    L = st.L
+    Ms = [np.diag((sv["x"][l + 1][0] > 0).astype(float)) for l in range(L)]
+    assert 0 < sum(M.trace() for M in Ms) < L * st.d
+    Ks = [(1 - gamma) * Ms[l] @ np.diag(st.lam[l]) for l in range(L)]
+    Js = [Ms[l] @ Jb[l] + gamma * Ms[l] @ np.diag(st.lam[l]) for l in range(L)]
+    for k in range(L + 1):
+        w = O.hbp_backward(st, sv, e, k, gamma=gamma)
+        for i in range(L + 1):
+            acc = np.zeros(st.d)
+            for j in range(i, L + 1):
+                layers = list(range(i, j))
+                for size in range(min(k, len(layers)) + 1):
+                    for chosen in itertools.combinations(layers, size):
+                        vec = e[j][0].copy()
+                        for l in reversed(layers):
+                            vec = vec @ (Js[l] if l in chosen else Ks[l])
+                        acc += vec
+            np.testing.assert_allclose(w[i][0], acc, rtol=2e-6, atol=2e-8)
+    np.testing.assert_allclose(O.hbp_backward(st, sv, e, L, gamma=gamma), O.exact_backward(st, sv, e),
+                               rtol=1e-10, atol=1e-12)
+
+
+def test_relu_after_the_sum_finite_termination():
+    """Theorem 2's guarantee (exact for k >= L - i) holds with the non-linear residual function."""
+    st = small_relu_mlp(L=6, d=5, dff=7, seed=2)
+    r = np.random.default_rng(6)
+    sv = O.forward(st, r.standard_normal((3, st.d)))
+    e = r.standard_normal((3, st.d))
+    G = O.exact_backward(st, sv, e)
+    for k in range(st.L + 1):
+        w = O.hbp_backward(st, sv, e, k)
+        for i in range(st.L + 1):
+            if k >= st.L - i:
+                np.testing.assert_allclose(w[i], G[i], rtol=1e-11, atol=1e-13)
+    assert O.rel_l2(O.hbp_backward(st, sv, e, 1)[0], G[0]) > 1e-3
