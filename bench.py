@@ -60,8 +60,9 @@ def algorithmic_work(w, k):
     e_in_scan = w.loss_every_state and w.norm == "rms"
     lam_tok = 1 if w.lam == "sigmoid_full" else 0      # coefficients per token: one more stream
     streams_in = 1 + (1 if w.norm == "rms" else 0) + (1 if e_in_scan else 0) + lam_tok
-    scan_iter = S * s * (streams_in + 1)
-    scan_init = S * s * (1 + (1 if w.loss_every_state else 0) + lam_tok)
+    mask = S / 8.0 if w.post == "relu" else 0.0       # one bit per element per scan
+    scan_iter = S * s * (streams_in + 1) + mask
+    scan_init = S * s * (1 + (1 if w.loss_every_state else 0) + lam_tok) + mask
     return {"vjp1": vjp1, "vjp2": vjp2, "dw": dw, "scan_bytes": scan_init + iters * scan_iter,
             "scan_launches": 1 + iters}
 
@@ -127,7 +128,8 @@ def cpu_baseline(w, k, budget_tokens):
         threads = os.cpu_count() or 1
     n = min(budget_tokens, w.N)
     inp = synth.make_inputs(w, tokens=slice(0, n))
-    st = O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], U=inp["U"], eps=w.eps, L=w.L)
+    st = O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], U=inp["U"], eps=w.eps, L=w.L,
+                 post=w.post)
     sv = O.forward(st, inp["x0"], inp["xin"])
     t0 = time.perf_counter()
     g = O.hbp_backward(st, sv, inp["e"], k)
@@ -258,7 +260,7 @@ def main():
         out["per_k"] = sweep
         # the re-split iteration (gamma of the layer's residual connection counted with the block);
         # gamma = 1 is the fixed-point-iteration baseline
-        if not (w.norm == "rms" and w.d > 2048):
+        if not (w.norm == "rms" and w.d > 2048) and w.post == "none":
             gs = {}
             for gm in (0.2, 0.5, 1.0):
                 def fg(gm=gm):
@@ -276,7 +278,7 @@ def main():
         abl = {}
         S_bytes = float(w.L) * w.N * w.d * storage_bytes(w)
         alg_bytes = S_bytes * (1 + (1 if w.loss_every_state else 0) + (1 if w.lam == "sigmoid_full" else 0))
-        for algo in ("auto", "sequential", "chunked", "hillis_steele"):
+        for algo in ("auto", "sequential") + (("chunked", "hillis_steele") if w.post == "none" else ()):
             need = B.scan_workspace_size(p.desc, algo)
             if need > 8 << 30:
                 continue
@@ -288,7 +290,7 @@ def main():
 
     if not args.no_cpu_baseline:
         # about 10-20 s of oracle work on the GPU machine's host cores
-        n = args.cpu_tokens or {"mlp_small_f32": 128, "resnet_like": 8192, "transformer_mlp": 2048,
+        n = args.cpu_tokens or {"mlp_small_f32": 128, "resnet_like": 8192, "resnet_postact": 8192, "transformer_mlp": 2048,
                                 "deep_large": 256, "gated_rnn": 16, "gated_rnn_contractive": 16,
                                 "gated_rnn_token_gates": 16}.get(w.name, 64)
         out["cpu_baseline"] = cpu_baseline(w, k, n)

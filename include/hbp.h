@@ -62,6 +62,13 @@ typedef enum { HBP_NORM_NONE = 0, HBP_NORM_RMS = 1 } hbp_norm;
  * TOKEN: storage type S, [L, N, d]: a diagonal K_l that depends on the data (e.g. gates computed from
  * a recurrent cell's input), given as data: the backward calls treat it as constant. */
 typedef enum { HBP_LAMBDA_ONE = 0, HBP_LAMBDA_CHANNEL = 1, HBP_LAMBDA_TOKEN = 2 } hbp_lambda;
+/* What the residual function applies after the sum (Section "Notations and assumptions": r need not be
+ * linear; table of layer decompositions, the original ResNet's row): NONE: x_{l+1} = lambda_l (.) x_l + block_l(x_l).
+ * RELU: x_{l+1} = ReLU(lambda_l (.) x_l + block_l(x_l)); with m_l = 1[the sum > 0], K_l = diag(m_l lambda_l) and
+ * J_l = diag(m_l) . d block_l / dx.  The backward calls then keep every state gradient already taken through
+ * its ReLU: g[l] = m_{l-1} (.) dL/dx_l for l >= 1 (the gradient with respect to the sum that made x_l, which is
+ * what the block VJP and the parameter gradients start from), g[0] = dL/dx_0.  HBP_MLP with gamma = 0 only. */
+typedef enum { HBP_POST_NONE = 0, HBP_POST_RELU = 1 } hbp_post;
 
 typedef struct {
   uint32_t struct_size;      /* = sizeof(hbp_desc) */
@@ -81,7 +88,7 @@ typedef struct {
                               * hbp_backward (appendix, the decomposition with gamma): the iteration then runs on
                               * K' = (1 - gamma) K and J' = J + gamma K.  0: the plain method; 1: fixed-point
                               * iteration.  The exact gradient and the other calls do not depend on it. */
-  int32_t reserved;          /* 0 */
+  int32_t post;              /* hbp_post */
 } hbp_desc;
 
 typedef struct {
@@ -99,6 +106,9 @@ typedef struct {
   void* z;                   /* S [L,N,d_ff] act(a_l) */
   void* dphi;                /* S [L,N,d_ff] act'(a_l); unused with TANH (1 - z^2) and IDENTITY (1) */
   const void* xin;           /* S [L,N,d_in] RNN inputs; NULL for MLP */
+  uint8_t* mask;             /* [L,N,d/8] HBP_POST_RELU only (else unused, may be NULL): bit j of byte c of row
+                              * (l, n) is 1 where the sum that made x_{l+1}[n, 8c+j] was positive; written by
+                              * hbp_forward, read by the backward calls */
   /* loss gradients and results */
   const void* e;             /* S [N,d] or [L+1,N,d] (see loss_every_state) */
   void* g;                   /* S [L+1,N,d]  out: state-gradient estimates, g[L] = e_L */

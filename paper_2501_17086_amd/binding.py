@@ -22,6 +22,7 @@ F32, BF16 = 0, 1
 MLP, RNN = 0, 1
 ACT = {"gelu": 0, "tanh": 1, "identity": 2}
 NORM = {"none": 0, "rms": 1}
+POST = {"none": 0, "relu": 1}
 LAMBDA_ONE, LAMBDA_CHANNEL, LAMBDA_TOKEN = 0, 1, 2
 
 EXPORTS = ("hbp_workspace_size", "hbp_check", "hbp_forward", "hbp_backward", "hbp_exact_backward",
@@ -34,14 +35,15 @@ class hbp_desc(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("kind", C.c_int32), ("dtype", C.c_int32), ("act", C.c_int32),
                 ("norm", C.c_int32), ("lambda_kind", C.c_int32), ("loss_every_state", C.c_int32),
                 ("eps", C.c_float), ("L", C.c_int64), ("N", C.c_int64), ("d", C.c_int64), ("d_ff", C.c_int64),
-                ("d_in", C.c_int64), ("gamma", C.c_float), ("reserved", C.c_int32)]
+                ("d_in", C.c_int64), ("gamma", C.c_float), ("post", C.c_int32)]
 
 
 class hbp_buffers(C.Structure):
     _fields_ = [("struct_size", C.c_uint32),
                 ("W1", C.c_void_p), ("W2", C.c_void_p), ("U", C.c_void_p), ("lambda_", C.c_void_p),
                 ("x", C.c_void_p), ("y", C.c_void_p), ("rinv", C.c_void_p), ("z", C.c_void_p),
-                ("dphi", C.c_void_p), ("xin", C.c_void_p), ("e", C.c_void_p), ("g", C.c_void_p),
+                ("dphi", C.c_void_p), ("xin", C.c_void_p), ("mask", C.c_void_p), ("e", C.c_void_p),
+                ("g", C.c_void_p),
                 ("dW1", C.c_void_p), ("dW2", C.c_void_p), ("dU", C.c_void_p),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
 
@@ -88,11 +90,11 @@ def status_string(status: int) -> str:
 
 def make_desc(kind: str, dtype: str, act: str, norm: str, L: int, N: int, d: int, d_ff: int, d_in: int = 0,
               lambda_channel: bool = False, loss_every_state: bool = False, eps: float = 1e-6,
-              gamma: float = 0.0, lambda_token: bool = False) -> hbp_desc:
+              gamma: float = 0.0, lambda_token: bool = False, post: str = "none") -> hbp_desc:
     return hbp_desc(C.sizeof(hbp_desc), RNN if kind == "rnn" else MLP, BF16 if dtype == "bf16" else F32,
                     ACT[act], NORM[norm],
                     LAMBDA_TOKEN if lambda_token else LAMBDA_CHANNEL if lambda_channel else LAMBDA_ONE,
-                    1 if loss_every_state else 0, eps, L, N, d, d_ff, d_in, gamma, 0)
+                    1 if loss_every_state else 0, eps, L, N, d, d_ff, d_in, gamma, POST[post])
 
 
 def workspace_size(desc: hbp_desc) -> int:
@@ -121,6 +123,7 @@ class Problem:
     z: "object" = None
     dphi: "object" = None
     xin: "object" = None
+    mask: "object" = None
     e: "object" = None
     g: "object" = None
     dW1: "object" = None
@@ -132,7 +135,7 @@ class Problem:
         ws = self.workspace
         return hbp_buffers(C.sizeof(hbp_buffers), _ptr(self.W1), _ptr(self.W2), _ptr(self.U), _ptr(self.lam),
                            _ptr(self.x), _ptr(self.y), _ptr(self.rinv), _ptr(self.z), _ptr(self.dphi),
-                           _ptr(self.xin), _ptr(self.e), _ptr(self.g), _ptr(self.dW1), _ptr(self.dW2),
+                           _ptr(self.xin), _ptr(self.mask), _ptr(self.e), _ptr(self.g), _ptr(self.dW1), _ptr(self.dW2),
                            _ptr(self.dU), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size())
 
 
@@ -230,7 +233,7 @@ def allocate(w, inputs, device="cuda:0", N: Optional[int] = None) -> Problem:
     per_token = lam is not None and lam.ndim == 3      # [L,N,d] in the storage type; [L,d] is fp32
     desc = make_desc(w.kind, w.dtype, w.act, w.norm, w.L, N, w.d, w.d_ff, w.d_in,
                      lambda_channel=lam is not None and not per_token, lambda_token=per_token,
-                     loss_every_state=w.loss_every_state, eps=w.eps)
+                     loss_every_state=w.loss_every_state, eps=w.eps, post=getattr(w, "post", "none"))
     L, d, dff = w.L, w.d, w.d_ff
     x = torch.zeros((L + 1, N, d), dtype=dt, device=dev)
     x[0] = up(inputs["x0"])
@@ -243,6 +246,7 @@ def allocate(w, inputs, device="cuda:0", N: Optional[int] = None) -> Problem:
         z=torch.zeros((L, N, dff), dtype=dt, device=dev),
         dphi=torch.zeros((L, N, dff), dtype=dt, device=dev) if w.act == "gelu" else None,
         xin=up(inputs["xin"]), e=up(inputs["e"]),
+        mask=torch.zeros((L, N, d // 8), dtype=torch.uint8, device=dev) if getattr(w, "post", "none") == "relu" else None,
         g=torch.zeros((L + 1, N, d), dtype=dt, device=dev),
         dW1=torch.zeros(inputs["W1"].shape, dtype=torch.float32, device=dev),
         dW2=torch.zeros(inputs["W2"].shape, dtype=torch.float32, device=dev),

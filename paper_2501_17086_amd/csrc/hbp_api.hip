@@ -92,7 +92,9 @@ hbp_status check_desc(const hbp_desc* d) {
   if (d->norm == HBP_NORM_RMS && !(d->eps >= 0.f)) return HBP_E_INVALID_ARG;
   if (d->d % 8 || d->d_ff % 8 || d->d_in % 8) return HBP_E_UNSUPPORTED;
   if (d->norm == HBP_NORM_RMS && d->d > 4096) return HBP_E_UNSUPPORTED;
-  if (!(d->gamma >= 0.f && d->gamma <= 1.f) || d->reserved != 0) return HBP_E_INVALID_ARG;
+  if (!(d->gamma >= 0.f && d->gamma <= 1.f)) return HBP_E_INVALID_ARG;
+  if (d->post != HBP_POST_NONE && d->post != HBP_POST_RELU) return HBP_E_INVALID_ARG;
+  if (d->post == HBP_POST_RELU && (d->kind != HBP_MLP || d->gamma != 0.f)) return HBP_E_UNSUPPORTED;
   if (d->gamma != 0.f && d->norm == HBP_NORM_RMS && d->d > 2048) return HBP_E_UNSUPPORTED;
   if (d->L > (1 << 20) || d->N > (1L << 24) || d->d > (1 << 20) || d->d_ff > (1 << 20)) return HBP_E_UNSUPPORTED;
   return HBP_OK;
@@ -111,6 +113,7 @@ hbp_status check_bufs(const hbp_desc* d, const hbp_buffers* b, int need) {
   if ((need & NEED_FWD) && !b->x) return HBP_E_NULL;
   if (!b->z) return HBP_E_NULL;
   if (d->act == HBP_ACT_GELU_ERF && !b->dphi) return HBP_E_NULL;
+  if (d->post == HBP_POST_RELU && (need & (NEED_FWD | NEED_BWD)) && !b->mask) return HBP_E_NULL;
   if (need & (NEED_BWD | NEED_PG)) {
     if (!b->g) return HBP_E_NULL;
   }
@@ -296,6 +299,7 @@ hbp_status scan_stage(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
   sa.N = d->N; sa.d = d->d;
   sa.l_lo = l_lo; sa.l_hi = l_hi;
   sa.norm_rms = d->norm == HBP_NORM_RMS;
+  sa.mask = d->post == HBP_POST_RELU ? b->mask : nullptr;
   ProfScope ps(HBP_PROF_SCAN, s);
   HBP_TRY(launch_scan(d->dtype, sa, s));
   return HBP_OK;
@@ -308,6 +312,9 @@ hbp_status seed_top(const hbp_desc* d, const hbp_buffers* b, hipStream_t s) {
   const void* src = d->loss_every_state ? at(b->e, (size_t)d->L * row) : b->e;
   ProfScope ps(HBP_PROF_OTHER, s);
   HBP_TRY(hipMemcpyAsync(at(b->g, (size_t)d->L * row), src, row, hipMemcpyDeviceToDevice, s));
+  if (d->post == HBP_POST_RELU)   // g[L] is kept taken through the ReLU that made x_L, like every g[l >= 1]
+    HBP_TRY(launch_mask_apply(d->dtype, at(b->g, (size_t)d->L * row), b->mask + (size_t)(d->L - 1) * d->N * d->d / 8,
+                              d->N * d->d, s));
   return HBP_OK;
 }
 
@@ -473,6 +480,11 @@ hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
       ga.lambda_mn = d->lambda_kind == HBP_LAMBDA_TOKEN ? at(b->lambda, xo) : nullptr;
       HBP_RUN(run_gemm(d, ga, s, HBP_PROF_FORWARD));
     }
+    if (d->post == HBP_POST_RELU) {
+      ProfScope ps(HBP_PROF_FORWARD, s);
+      HBP_TRY(launch_relu_mask(d->dtype, at(b->x, xo + (size_t)d->N * d->d * es), b->mask + (size_t)l * d->N * d->d / 8,
+                               d->N * d->d, s));
+    }
   }
   return HBP_OK;
 }
@@ -514,6 +526,9 @@ hbp_status hbp_backward(const hbp_desc* d, int k, hbp_buffers* b, void* stream) 
 hbp_status hbp_scan_workspace_size(const hbp_desc* d, int algorithm, size_t* bytes) {
   if (!bytes) return HBP_E_NULL;
   HBP_RUN(check_desc(d));
+  // the ReLU's mask is applied by the direct forms only
+  if (d->post == HBP_POST_RELU && (algorithm == HBP_SCAN_CHUNKED || algorithm == HBP_SCAN_HILLIS_STEELE))
+    return HBP_E_UNSUPPORTED;
   switch (algorithm) {
     case HBP_SCAN_AUTO: case HBP_SCAN_SEQUENTIAL: *bytes = carve(d).total; break;
     case HBP_SCAN_CHUNKED: *bytes = scan_chunk_ws_bytes_forced(d->L, d->N, d->d); break;
@@ -531,6 +546,7 @@ hbp_status hbp_initial_estimate(const hbp_desc* d, int algorithm, hbp_buffers* b
   if (!b->e || !b->g) return HBP_E_NULL;
   if (d->lambda_kind != HBP_LAMBDA_ONE && !b->lambda) return HBP_E_NULL;
   if (!b->workspace || b->workspace_bytes < need) return HBP_E_WORKSPACE;
+  if (d->post == HBP_POST_RELU && !b->mask) return HBP_E_NULL;
   hipStream_t s = (hipStream_t)stream;
   if (algorithm == HBP_SCAN_HILLIS_STEELE) {
     HsArgs a{};

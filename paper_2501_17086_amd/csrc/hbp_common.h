@@ -164,6 +164,8 @@ struct ScanArgs {
   int force;            // 0: the launcher picks the form; 1: the sequential form; 2: the chunked form (needs chunk_ws)
   float res_scale;      // factor on lambda along the residual path (1 - gamma; 1 for the plain method)
   float blk_gamma;      // gamma: adds gamma lambda_l (.) g_{l+1}^{old} to v_l (0: nothing read)
+  const uint8_t* mask;  // [L,N,d/8] bits or NULL: g_l (l >= 1) is multiplied by the bits of row block l-1 (the ReLU
+                        // that made x_l) before it is stored and carried on; direct forms only, gamma = 0
 };
 hipError_t launch_scan(int dtype, const ScanArgs& a, hipStream_t s);
 // Long chains with few of them (the time axis of an RNN) are cut into chunks of
@@ -188,6 +190,10 @@ struct HsArgs {
 };
 size_t hs_ws_bytes(long L, long N, long d, int lambda_kind);   // 0 one, 1 channel, 2 token
 hipError_t launch_scan_hillis_steele(int dtype, const HsArgs& a, hipStream_t s);
+
+// x := max(x, 0) over n elements (n % 8 == 0), mask bit = 1 where x was positive; g := g (.) mask bits
+hipError_t launch_relu_mask(int dtype, void* x, uint8_t* mask, long n, hipStream_t s);
+hipError_t launch_mask_apply(int dtype, void* g, const uint8_t* mask, long n, hipStream_t s);
 
 // y = x * rinv, rinv = 1/sqrt(mean(x^2)+eps) for `rows` rows of width d
 hipError_t launch_rmsnorm_fwd(int dtype, const void* x, void* y, float* rinv, long rows, long d, float eps,

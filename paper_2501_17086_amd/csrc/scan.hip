@@ -76,6 +76,11 @@ __global__ __launch_bounds__(256) void scan_vec_kernel(ScanArgs a) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) carry[i] += v[i];
     }
+    if (a.mask && l > 0) {   // the ReLU that made x_l: g_l is kept already taken through it
+      const unsigned mb = a.mask[(l - 1) * vec_per_layer + idx];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) carry[i] = ((mb >> i) & 1u) ? carry[i] : 0.f;
+    }
     store8(g + l * layer + off, carry);
   }
 }
@@ -181,6 +186,11 @@ __global__ __launch_bounds__(256) void scan_rows_kernel(ScanArgs a) {
       } else {
 #pragma unroll
         for (int i = 0; i < 8; ++i) carry[j][i] += t[i];
+      }
+      if (a.mask && l > 0) {
+        const unsigned mb = a.mask[((l - 1) * layer + off[j]) >> 3];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) carry[j][i] = ((mb >> i) & 1u) ? carry[j][i] : 0.f;
       }
       store8(g + l * layer + off[j], carry[j]);
     }
@@ -431,10 +441,11 @@ hipError_t launch_scan_t(const ScanArgs& a, hipStream_t s) {
   const bool gam = a.res_scale != 1.f || a.blk_gamma != 0.f;
   const bool rms = a.norm_rms && a.dn;
   if (a.force == 2) {
-    if (!a.chunk_ws || rms) return hipErrorInvalidValue;
+    if (!a.chunk_ws || rms || a.mask) return hipErrorInvalidValue;
     return launch_scan_chunked<T>(a, s);
   }
-  if (a.force == 0 && a.chunk_ws && use_chunked(a.l_hi - a.l_lo, a.N, a.d, rms)) return launch_scan_chunked<T>(a, s);
+  if (a.force == 0 && !a.mask && a.chunk_ws && use_chunked(a.l_hi - a.l_lo, a.N, a.d, rms))
+    return launch_scan_chunked<T>(a, s);
   if (a.norm_rms && a.dn) {
     const int nch = (int)((a.d + 511) / 512);
     dim3 grid((unsigned)((a.N + 3) / 4)), block(256);
@@ -597,6 +608,52 @@ size_t scan_chunk_ws_bytes(long L, long N, long d, int norm_rms) {
   if (!use_chunked(L, N, d, norm_rms)) return 0;
   const long nchunks = (L + SCAN_CHUNK - 1) / SCAN_CHUNK;
   return (size_t)(4 * nchunks * N * d) * sizeof(float);   // B, cin, A (per chain at most), old g above each chunk
+}
+
+namespace {
+// x := max(x, 0) and one mask bit per element (1 where x was positive), 8 elements per thread
+template <typename T>
+__global__ __launch_bounds__(256) void relu_mask_kernel(T* __restrict__ x, uint8_t* __restrict__ mask, long nvec) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= nvec) return;
+  float v[8];
+  load8(x + i * 8, v);
+  unsigned mb = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    if (v[j] > 0.f) mb |= 1u << j; else v[j] = 0.f;
+  }
+  store8(x + i * 8, v);
+  mask[i] = (uint8_t)mb;
+}
+// g := g where the mask bit is 1, else 0
+template <typename T>
+__global__ __launch_bounds__(256) void mask_apply_kernel(T* __restrict__ g, const uint8_t* __restrict__ mask, long nvec) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= nvec) return;
+  float v[8];
+  load8(g + i * 8, v);
+  const unsigned mb = mask[i];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) v[j] = ((mb >> j) & 1u) ? v[j] : 0.f;
+  store8(g + i * 8, v);
+}
+}  // namespace
+
+hipError_t launch_relu_mask(int dtype, void* x, uint8_t* mask, long n, hipStream_t s) {
+  const long nvec = n / 8;
+  dim3 grid((unsigned)((nvec + 255) / 256)), block(256);
+  if (dtype == 0) hipLaunchKernelGGL(relu_mask_kernel<float>, grid, block, 0, s, (float*)x, mask, nvec);
+  else hipLaunchKernelGGL(relu_mask_kernel<bf16_t>, grid, block, 0, s, (bf16_t*)x, mask, nvec);
+  return hipGetLastError();
+}
+
+hipError_t launch_mask_apply(int dtype, void* g, const uint8_t* mask, long n, hipStream_t s) {
+  const long nvec = n / 8;
+  dim3 grid((unsigned)((nvec + 255) / 256)), block(256);
+  if (dtype == 0) hipLaunchKernelGGL(mask_apply_kernel<float>, grid, block, 0, s, (float*)g, mask, nvec);
+  else hipLaunchKernelGGL(mask_apply_kernel<bf16_t>, grid, block, 0, s, (bf16_t*)g, mask, nvec);
+  return hipGetLastError();
 }
 
 hipError_t launch_scan(int dtype, const ScanArgs& a, hipStream_t s) {

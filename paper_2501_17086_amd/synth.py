@@ -47,6 +47,7 @@ class Workload:
     w2_scale: float = 1.0
     rec_scale: float = 1.0   # extra factor on W_h and W_o (rnn variants)
     loss_every_state: bool = False
+    post: str = "none"   # 'none' | 'relu': what the residual function applies after the sum
     eps: float = 1e-6
     ks: tuple = (1, 2, 3, 4)
     seed: int = 0
@@ -69,6 +70,9 @@ WORKLOADS: Dict[str, Workload] = {
     # gated RNN along time, shared weights, a loss at every step
     "gated_rnn": Workload("gated_rnn", "rnn", "bf16", "tanh", "none", L=4096, N=32, d=1024, d_ff=1024,
                           d_in=1024, lam="sigmoid", lam_lo=3.0, lam_hi=0.5, loss_every_state=True),
+    # the same stack with the original ResNet's residual function: a ReLU after the sum
+    "resnet_postact": Workload("resnet_postact", "mlp", "bf16", "gelu", "rms", L=32, N=8192, d=512, d_ff=2048,
+                               lam="uniform", lam_lo=0.9, lam_hi=1.0, w2_scale=1.0 / np.sqrt(32.0), post="relu"),
     # large deep stack
     "deep_large": Workload("deep_large", "mlp", "bf16", "gelu", "rms", L=96, N=16384, d=2048, d_ff=8192,
                            lam="uniform", lam_lo=0.8, lam_hi=1.0, w1_std=0.02, w2_std=0.02,

@@ -12,7 +12,8 @@ TOL = {"f32": 1e-5, "bf16": 2e-2}   # relative L2, GPU vs oracle
 
 
 def oracle_stack(w: synth.Workload, inp) -> O.Stack:
-    return O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], U=inp["U"], eps=w.eps, L=w.L)
+    return O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], U=inp["U"], eps=w.eps, L=w.L,
+                   post=w.post)
 
 
 def to_np(t) -> np.ndarray:
@@ -47,6 +48,25 @@ def upload_saved(p, w: synth.Workload, sv_r):
     put(p.rinv, sv_r["rinv"])
     put(p.z, sv_r["z"])
     put(p.dphi, sv_r["dphi"])
+    if p.mask is not None:     # one bit per element, channel 8c+j in bit j of byte c
+        bits = np.packbits(sv_r["mask"].astype(np.uint8), axis=-1, bitorder="little")
+        p.mask.copy_(torch.from_numpy(bits).to(dev))
+
+
+def mask_bits(p) -> np.ndarray:
+    """The Problem's mask unpacked to [L,N,d] of 0/1."""
+    return np.unpackbits(p.mask.cpu().numpy(), axis=-1, bitorder="little").astype(np.float64)
+
+
+def as_kept(st: O.Stack, sv, G: np.ndarray) -> np.ndarray:
+    """State gradients in the form the library keeps them: with a ReLU after the sum, g[l >= 1] is the oracle's
+    gradient of state l taken through that ReLU (the oracle's own through_r); unchanged otherwise."""
+    if st.post != "relu":
+        return G
+    out = G.copy()
+    for l in range(st.L):
+        out[l + 1] = O.through_r(st, l, sv, G[l + 1])
+    return out
 
 
 def rel(a, b) -> float:

@@ -28,7 +28,7 @@ def test_library_exports_every_declared_symbol():
 def test_struct_layout_matches_header():
     # field order and sizes as in the header (LP64)
     assert C.sizeof(B.hbp_desc) == 4 * 8 + 8 * 5 + 4 * 2
-    assert C.sizeof(B.hbp_buffers) == 8 + 8 * 15 + 8 + 8
+    assert C.sizeof(B.hbp_buffers) == 8 + 8 * 16 + 8 + 8
 
 
 def _desc(**kw):
@@ -53,7 +53,7 @@ def test_workspace_size_scales():
 @pytest.mark.parametrize("field,value,status", [
     ("L", 0, 1), ("N", -1, 1), ("d", 0, 1), ("d", 60, 2), ("d_ff", 100, 2), ("kind", 7, 1), ("dtype", 3, 1),
     ("act", 5, 1), ("norm", 2, 1), ("lambda_kind", 9, 1), ("loss_every_state", 2, 1), ("struct_size", 12, 1),
-    ("d_in", 8, 1), ("gamma", -0.1, 1), ("gamma", 1.5, 1), ("gamma", float("nan"), 1), ("reserved", 1, 1),
+    ("d_in", 8, 1), ("gamma", -0.1, 1), ("gamma", 1.5, 1), ("gamma", float("nan"), 1), ("post", 2, 1), ("post", -1, 1),
 ])
 def test_bad_descriptor_is_rejected(field, value, status):
     d = _desc()
@@ -68,6 +68,18 @@ def test_rms_width_limit_and_rnn_needs_input_width():
     assert B.lib().hbp_workspace_size(C.byref(d), C.byref(n)) == 2
     d = _desc(kind="rnn", act="tanh", norm="none", d_in=0)
     assert B.lib().hbp_workspace_size(C.byref(d), C.byref(n)) == 1
+
+
+def test_relu_after_the_sum_is_for_depth_stacks_with_the_plain_split():
+    n = C.c_size_t(0)
+    assert B.lib().hbp_workspace_size(C.byref(_desc(post="relu")), C.byref(n)) == 0
+    assert B.lib().hbp_workspace_size(C.byref(_desc(post="relu", gamma=0.5)), C.byref(n)) == 2
+    d = _desc(kind="rnn", act="tanh", norm="none", d_in=64, post="relu")
+    assert B.lib().hbp_workspace_size(C.byref(d), C.byref(n)) == 2
+    for alg in (2, 3):
+        assert B.lib().hbp_scan_workspace_size(C.byref(_desc(post="relu")), alg, C.byref(n)) == 2
+        bufs = B.hbp_buffers(C.sizeof(B.hbp_buffers))
+        assert B.lib().hbp_initial_estimate(C.byref(_desc(post="relu")), alg, C.byref(bufs), None) == 2
 
 
 def test_null_pointers_and_workspace_are_checked_before_launch():

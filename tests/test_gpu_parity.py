@@ -68,6 +68,19 @@ CASES = {
                                 d_in=64, ks=(0, 2)),
     "rnn_width_96": synth.scaled(W["gated_rnn_contractive"], name="rnn_width_96", L=12, N=7, d=96, d_ff=160,
                                  d_in=32, ks=(0, 2)),
+    # a ReLU after the sum (the original ResNet's residual function): wave-per-row scan with the norm (one and two
+    # 512-channel chunks), thread-per-vector scan without, a chain long enough that the chunked form would be
+    # picked without the mask, and whole 256-row tiles
+    "postact_rms": synth.scaled(W["resnet_postact"], name="postact_rms", L=6, N=333, d=512, d_ff=1024,
+                                w2_scale=1 / np.sqrt(6.0), ks=(0, 1, 2, 6)),
+    "postact_wide": synth.scaled(W["resnet_postact"], name="postact_wide", L=4, N=130, d=1024, d_ff=512,
+                                 w2_scale=0.5, ks=(0, 1, 3)),
+    "postact_aligned": synth.scaled(W["resnet_postact"], name="postact_aligned", L=9, N=512, d=256, d_ff=512,
+                                    w2_scale=1 / 3.0, ks=(0, 2, 4)),
+    "postact_f32_none": synth.scaled(W["resnet_postact"], name="postact_f32_none", dtype="f32", norm="none", L=5,
+                                     N=203, d=72, d_ff=136, w2_scale=0.4, loss_every_state=True, ks=(0, 1, 2, 5)),
+    "postact_f32_deep": synth.scaled(W["resnet_postact"], name="postact_f32_deep", dtype="f32", norm="none", L=270,
+                                     N=3, d=64, d_ff=64, w2_scale=0.1, ks=(0, 2)),
     # a loss on every state of a depth stack (e read by the scan behind the norm's backward), and without a norm
     # (e added by the second contraction's epilogue)
     # coefficients per (block, token, channel): direct scans (depth, RMS and none) and the chunked scan (time)
@@ -122,11 +135,12 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
         B.hbp_param_grads(p)
         torch.cuda.synchronize()
         want = O.hbp_backward(st, sv_oracle, inp["e"], k)
-        err = H.rel(H.to_np(p.g), want)
+        kept = H.as_kept(st, sv_oracle, want)
+        err = H.rel(H.to_np(p.g), kept)
         assert err < tol, f"{tag} k={k}: g rel L2 {err:.3e}"
         # per-state check as well: an error confined to one state must not hide
         for l in range(w.L + 1):
-            el = H.rel(H.to_np(p.g[l]), want[l])
+            el = H.rel(H.to_np(p.g[l]), kept[l])
             assert el < 2 * tol, f"{tag} k={k} state {l}: {el:.3e}"
         pg = O.param_grads(st, sv_oracle, want, xin)
         for nm, t in (("dW1", p.dW1), ("dW2", p.dW2), ("dU", p.dU)):
@@ -140,7 +154,7 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
     B.hbp_param_grads(p)
     torch.cuda.synchronize()
     G = O.exact_backward(st, sv_oracle, inp["e"])
-    err = H.rel(H.to_np(p.g), G)
+    err = H.rel(H.to_np(p.g), H.as_kept(st, sv_oracle, G))
     assert err < tol, f"{tag} exact: g rel L2 {err:.3e}"
     pg = O.param_grads(st, sv_oracle, G, xin)
     for nm, t in (("dW1", p.dW1), ("dW2", p.dW2), ("dU", p.dU)):
@@ -152,7 +166,8 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
                                   "transformer_small", "deep_small", "rnn_small", "rnn_f32", "rnn_long",
                                   "mlp_f32_deep", "aligned_small", "rnn_aligned", "mlp_loss_all",
                                   "mlp_loss_all_nonorm", "rnn_token_gates", "rnn_token_gates_long",
-                                  "rnn_token_gates_f32", "mlp_token_gates", "rnn_rows_40", "rnn_width_96"])
+                                  "rnn_token_gates_f32", "mlp_token_gates", "rnn_rows_40", "rnn_width_96",
+                                  "postact_f32_none"])
 def test_backward_end_to_end(B, name):
     """Own forward on each side, then Highway-BP at every k of the case, exact BP
     and the parameter gradients."""
@@ -162,7 +177,28 @@ def test_backward_end_to_end(B, name):
     _check_backward(B, w, p, st, sv, inp, name)
 
 
-@pytest.mark.parametrize("name", ["mlp_f32_ragged", "resnet_like_small", "rnn_small", "rnn_chaotic_small"])
+@pytest.mark.parametrize("name", ["postact_rms", "postact_wide", "postact_f32_none", "postact_f32_deep"])
+def test_forward_with_relu_after_the_sum(B, name):
+    """States and the ReLU's mask.  A sum within rounding of zero may land on the other side in the
+    storage type: the masks may differ there and nowhere else."""
+    w = CASES[name]
+    inp, st, sv, p = _setup(B, w)
+    B.hbp_forward(p)
+    torch.cuda.synchronize()
+    tol = H.TOL[w.dtype]
+    assert H.rel(H.to_np(p.x), sv["x"]) < tol
+    assert float(H.to_np(p.x)[1:].min()) >= 0.0
+    got = H.mask_bits(p)
+    assert np.array_equal(got, (H.to_np(p.x)[1:] > 0).astype(np.float64))
+    differ = got != sv["mask"]
+    assert differ.mean() < (2e-2 if w.dtype == "bf16" else 1e-4)
+    scale = np.sqrt(np.mean(sv["x"][1:] ** 2))
+    assert np.all(np.abs(sv["x"][1:][differ]) < 10 * tol * scale)
+
+
+@pytest.mark.parametrize("name", ["mlp_f32_ragged", "resnet_like_small", "rnn_small", "rnn_chaotic_small",
+                                  "postact_rms", "postact_wide", "postact_aligned", "postact_f32_none",
+                                  "postact_f32_deep"])
 def test_backward_shared_state(B, name):
     """Both backward passes read the same (storage-rounded) forward state."""
     w = CASES[name]
@@ -232,6 +268,27 @@ def test_initial_estimate_by_every_form_of_the_scan(B, name, algorithm):
     for l in range(w.L + 1):
         if np.linalg.norm(want[l]) > 0:
             assert H.rel(H.to_np(p.g[l]), want[l]) < 2 * H.TOL[w.dtype], f"{name} {algorithm} state {l}"
+
+
+@pytest.mark.parametrize("name", ["postact_rms", "postact_f32_none", "postact_f32_deep"])
+@pytest.mark.parametrize("algorithm", ["auto", "sequential"])
+def test_initial_estimate_with_relu_after_the_sum(B, name, algorithm):
+    """w^0 along K_l = diag(mask_l lambda_l) on the oracle's forward state (its mask uploaded); the
+    chunked form and the sweeps are refused for this residual function."""
+    w = CASES[name]
+    inp, st, sv, p = _setup(B, w)
+    sv_r = H.oracle_saved_rounded(w, sv)
+    H.upload_saved(p, w, sv_r)
+    ws = torch.zeros(max(B.scan_workspace_size(p.desc, algorithm), 16), dtype=torch.uint8, device=p.g.device)
+    p.g.fill_(float("nan"))
+    B.hbp_initial_estimate(p, algorithm, workspace=ws)
+    torch.cuda.synchronize()
+    want = H.as_kept(st, sv_r, O.hbp_backward(st, sv_r, inp["e"], 0))
+    assert H.rel(H.to_np(p.g), want) < H.TOL[w.dtype], f"{name} {algorithm}"
+    for other in ("chunked", "hillis_steele"):
+        with pytest.raises(B.HbpError) as ei:
+            B.scan_workspace_size(p.desc, other)
+        assert ei.value.status == 2
 
 
 def test_gamma_needs_narrow_rows_with_rms(B):
