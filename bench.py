@@ -63,8 +63,26 @@ def algorithmic_work(w, k):
     mask = S / 8.0 if w.post == "relu" else 0.0       # one bit per element per scan
     scan_iter = S * s * (streams_in + 1) + mask
     scan_init = S * s * (1 + (1 if w.loss_every_state else 0) + lam_tok) + mask
+    # bytes the contractions must move: each operand read once, each result written once (weights once per
+    # launch when all steps share them).  They decide which roofline binds: at the published peaks the
+    # chip's balance is 2500 TFLOP/s / 8 TB/s = 312 flop per byte.
+    shared = w.kind == "rnn"
+    aux1 = 0.0 if w.act == "identity" else float(N) * dff * s            # act' (or z) read by the first epilogue
+    wbytes = float(d) * dff * s
+
+    def b1(nb):
+        return nb * (N * d * s + aux1 + N * dff * s) + (1 if shared else nb) * wbytes
+
+    def b2(nb):
+        e_aux = N * d * s if (w.loss_every_state and w.norm == "none") else 0.0
+        return nb * (N * dff * s + N * d * s + e_aux) + (1 if shared else nb) * wbytes
+    per_it = [L - it + 1 for it in range(1, iters + 1)]
+    vjp1_bytes = sum(b1(nb) for nb in per_it) + b1(L)
+    vjp2_bytes = sum(b2(nb) for nb in per_it)
+    dw_bytes = L * (2.0 * N * d * s + 2.0 * N * dff * s) + (1 if shared else L) * 2.0 * d * dff * 4 \
+        + ((L * N * (dff + w.d_in) * s + dff * w.d_in * 4.0) if shared else 0.0)
     return {"vjp1": vjp1, "vjp2": vjp2, "dw": dw, "scan_bytes": scan_init + iters * scan_iter,
-            "scan_launches": 1 + iters}
+            "scan_launches": 1 + iters, "vjp1_bytes": vjp1_bytes, "vjp2_bytes": vjp2_bytes, "dw_bytes": dw_bytes}
 
 
 def gpu_errors(B, torch, p, ks, gamma=None):
@@ -212,9 +230,15 @@ def main():
         t = ms[cls] * 1e-3
         ach = work[cls] / t / 1e12 if t > 0 else 0.0
         peak = PEAK_MFMA_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_VECTOR_TFLOPS
+        gbs = work[cls + "_bytes"] / t / 1e9 if t > 0 else 0.0
+        intensity = work[cls] / work[cls + "_bytes"]
         return {"bound": "mfma" if w.dtype == "bf16" else "alu", "achieved": ach, "peak": peak,
                 "unit": "TFLOP/s", "frac": ach / peak, "traffic": MEASURED_TRAFFIC.get(w.name, {}).get(cls),
                 "kernel_class": cls,
+                # the same launches against the other roofline: below peak / 8 TB/s flop per byte the
+                # memory roofline is the one that binds at the published peaks
+                "flop_per_byte": intensity, "hbm_GBps": gbs, "hbm_frac": gbs / PEAK_HBM_GBS,
+                "binding_at_peaks": "hbm" if intensity < peak * 1e3 / PEAK_HBM_GBS else "mfma",
                 "ms_per_step": ms[cls], "launches_per_step": launches[cls],
                 "avg_launch_ms": ms[cls] / max(launches[cls], 1)}
 
