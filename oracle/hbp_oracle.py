@@ -16,6 +16,10 @@ and erf are the only library steps; no blocking, fusion or reordering):
              ResNet in the table of layer decompositions, r(x, z) =
              ReLU(lam (.) x + z): with m = 1[lam (.) x + z > 0],
              K = dr/dx = diag(m (.) lam) and J = dr/dz . dg/dx = diag(m) . dg/dx.
+             kind = 'gated' is the GRU row of the same table, f(x) = a(x) (.) x + b(x)
+             with g = [a, b] and r(x, z) = z1 (.) x + z2, for the cell  u = sigmoid(W_u x + U_u xin),
+             c = tanh(W_c x + U_c xin),  a = 1 - u,  b = u (.) c  (a GRU without its reset gate):
+             K = dr/dx = diag(a), a function of the state, and J = diag(x) . da/dx + db/dx.
   exact BP   Section "Backpropagation as a system of equations" and the first
              line of the proof of Theorem 1 (chain rule through J + K).
   Highway-BP Theorem 2 (w^0 and the recursion for w^{k+1}) in its two-step
@@ -55,7 +59,10 @@ F64 = np.float64
 class Stack:
     """A residual stack.
 
-    kind   'mlp'  per-block weights W1[L,d_ff,d], W2[L,d,d_ff]
+    kind   'gated' one recurrent cell shared by all L (= T) steps, state width H:
+                  W1 = [W_u; W_c] [2H,H], U = [U_u; U_c] [2H,d_in], no W2, no lam
+                  (the coefficient of the residual path is the cell's own 1 - u)
+           'mlp'  per-block weights W1[L,d_ff,d], W2[L,d,d_ff]
            'rnn'  weights shared by all L (= T) blocks: W1 = W_h [d_ff,d],
                   W2 = W_o [d,d_ff], U [d_ff,d_in]; block l maps state l to
                   l+1 and consumes xin[l]
@@ -72,7 +79,7 @@ class Stack:
     act: str
     norm: str
     W1: np.ndarray
-    W2: np.ndarray
+    W2: Optional[np.ndarray]
     lam: Optional[np.ndarray] = None
     U: Optional[np.ndarray] = None
     eps: float = 1e-6
@@ -81,10 +88,15 @@ class Stack:
 
     def __post_init__(self):
         assert self.post in ("none", "relu")
-        assert self.kind in ("mlp", "rnn")
+        assert self.kind in ("mlp", "rnn", "gated")
         assert self.act in ("gelu", "tanh", "identity")
         assert self.norm in ("none", "rms")
         self.W1 = np.asarray(self.W1, dtype=F64)
+        if self.kind == "gated":
+            assert self.W2 is None and self.lam is None and self.norm == "none" and self.post == "none"
+            assert self.W1.ndim == 2 and self.W1.shape[0] == 2 * self.W1.shape[1] and self.L > 0
+            self.U = np.asarray(self.U, dtype=F64)
+            return
         self.W2 = np.asarray(self.W2, dtype=F64)
         if self.lam is not None:
             self.lam = np.asarray(self.lam, dtype=F64)
@@ -99,7 +111,7 @@ class Stack:
 
     @property
     def d(self) -> int:
-        return self.W2.shape[-2]
+        return self.W1.shape[-1] if self.kind == "gated" else self.W2.shape[-2]
 
     @property
     def d_ff(self) -> int:
@@ -151,6 +163,8 @@ def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict
     """
     x0 = np.asarray(x0, dtype=F64)
     N, d = x0.shape
+    if st.kind == "gated":
+        return _forward_gated(st, x0, xin)
     L, dff = st.L, st.d_ff
     x = np.zeros((L + 1, N, d), F64)
     y = np.zeros((L, N, d), F64)
@@ -176,11 +190,41 @@ def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict
             "z": act_fn(st.act, a), "dphi": act_grad(st.act, a)}
 
 
+def _forward_gated(st: Stack, x0: np.ndarray, xin: np.ndarray) -> Dict[str, np.ndarray]:
+    """x_{l+1} = (1 - u_l) (.) x_l + u_l (.) c_l,  u = sigmoid(W_u x + U_u xin),  c = tanh(W_c x + U_c xin).
+    Saved: x, u and c [L,N,H] (and y = x, rinv = 1, mask = 1 so that the shared code reads them)."""
+    N, H = x0.shape
+    L = st.L
+    x = np.zeros((L + 1, N, H), F64)
+    u = np.zeros((L, N, H), F64)
+    c = np.zeros((L, N, H), F64)
+    x[0] = x0
+    for l in range(L):
+        pre = x[l] @ st.W1.T + np.asarray(xin[l], dtype=F64) @ st.U.T
+        u[l] = 1.0 / (1.0 + np.exp(-pre[:, :H]))
+        c[l] = np.tanh(pre[:, H:])
+        x[l + 1] = (1.0 - u[l]) * x[l] + u[l] * c[l]
+    return {"x": x, "y": x[:-1], "rinv": np.ones((L, N), F64), "u": u, "c": c, "mask": np.ones((L, N, H), F64)}
+
+
+def k_diag(st: Stack, l: int, saved: Dict[str, np.ndarray]) -> np.ndarray:
+    """Diagonal of dr/dx for the layer that carries state l+1 to state l, before any mask: lam_l, or for the
+    gated cell its own coefficient a = 1 - u_l (per token)."""
+    if st.kind == "gated":
+        return 1.0 - saved["u"][l]
+    return st.lam_row(l)
+
+
 # --------------------------------------------------------------------------
 # step (i): vector-Jacobian product through one block,  v_l = g_{l+1} J_{l+1}
 # --------------------------------------------------------------------------
 def block_preact_grad(st: Stack, l: int, saved: Dict[str, np.ndarray], g_next: np.ndarray) -> np.ndarray:
-    """Gradient w.r.t. the pre-activation of block l: (g W2) (.) act'(a)."""
+    """Gradient w.r.t. the pre-activation of block l: (g W2) (.) act'(a).  Gated cell: with r = z1 (.) x + z2,
+    z1 = 1 - u, z2 = u (.) c:  dL/du = g (.) (c - x), dL/dc = g (.) u, taken through sigmoid' = u (1 - u) and
+    tanh' = 1 - c^2, side by side as [N, 2H]."""
+    if st.kind == "gated":
+        u, c, x = saved["u"][l], saved["c"][l], saved["x"][l]
+        return np.concatenate([g_next * (c - x) * u * (1.0 - u), g_next * u * (1.0 - c * c)], axis=1)
     return (g_next @ st.w2(l)) * saved["dphi"][l]
 
 
@@ -225,7 +269,7 @@ def exact_backward(st: Stack, saved: Dict[str, np.ndarray], e: np.ndarray) -> np
     G[st.L] = ef[st.L]
     for l in range(st.L - 1, -1, -1):
         gs = through_r(st, l, saved, G[l + 1])
-        G[l] = ef[l] + st.lam_row(l) * gs + block_vjp(st, l, saved, gs)
+        G[l] = ef[l] + k_diag(st, l, saved) * gs + block_vjp(st, l, saved, gs)
     return G
 
 
@@ -267,7 +311,7 @@ def hbp_backward(st: Stack, saved: Dict[str, np.ndarray], e: np.ndarray, k: int,
     L = st.L
     ef = _e_full(st, e, N)
     m_row = (lambda l: saved["mask"][l]) if st.post == "relu" else (lambda l: 1.0)
-    k_row = lambda l: (1.0 - gamma) * m_row(l) * st.lam_row(l)
+    k_row = lambda l: (1.0 - gamma) * m_row(l) * k_diag(st, l, saved)
     w0 = cumsumprod_reverse(ef, k_row)
     w = w0.copy()
     hist = [w0.copy()]
@@ -277,7 +321,7 @@ def hbp_backward(st: Stack, saved: Dict[str, np.ndarray], e: np.ndarray, k: int,
             ws = through_r(st, l, saved, w[l + 1])
             v[l] = block_vjp(st, l, saved, ws)
             if gamma != 0.0:
-                v[l] = v[l] + gamma * st.lam_row(l) * ws
+                v[l] = v[l] + gamma * k_diag(st, l, saved) * ws
         u = cumsumprod_reverse(v, k_row)
         w = w0 + u
         hist.append(w.copy())
@@ -303,6 +347,14 @@ def param_grads(st: Stack, saved: Dict[str, np.ndarray], g: np.ndarray,
             dW2[l] = g[l + 1].T @ saved["z"][l]
             dW1[l] = da.T @ saved["y"][l]
         return {"dW1": dW1, "dW2": dW2}
+    if st.kind == "gated":
+        dW1 = np.zeros_like(st.W1)
+        dU = np.zeros_like(st.U)
+        for l in range(L):
+            da = block_preact_grad(st, l, saved, g[l + 1])
+            dW1 += da.T @ saved["x"][l]
+            dU += da.T @ np.asarray(xin[l], dtype=F64)
+        return {"dW1": dW1, "dU": dU}
     dW1 = np.zeros_like(st.W1)
     dW2 = np.zeros_like(st.W2)
     dU = np.zeros_like(st.U)

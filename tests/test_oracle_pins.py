@@ -624,3 +624,110 @@ def test_relu_after_the_sum_finite_termination():
             if k >= st.L - i:
                 np.testing.assert_allclose(w[i], G[i], rtol=1e-11, atol=1e-13)
     assert O.rel_l2(O.hbp_backward(st, sv, e, 1)[0], G[0]) > 1e-3
+
+
+# ---------------------------------------------------------------- P13: the gated recurrent cell (GRU row of the table)
+def small_gated(T=5, H=6, I=4, seed=0):
+    r = np.random.default_rng(seed)
+    W = r.standard_normal((2 * H, H)) / math.sqrt(H)
+    U = r.standard_normal((2 * H, I)) / math.sqrt(I)
+    return O.Stack("gated", "tanh", "none", W, None, U=U, L=T)
+
+
+def test_gated_cell_against_torch_autograd():
+    """x' = (1 - u) x + u c with u = sigmoid(.), c = tanh(.): states, every state gradient and the gradients of
+    both weight matrices against torch's autograd of the same recurrence in fp64."""
+    r = np.random.default_rng(41)
+    N, I = 3, 5
+    st = small_gated(T=6, H=7, I=I)
+    H_ = st.d
+    xin = r.standard_normal((st.L, N, I))
+    x0 = r.standard_normal((N, H_)) * 0.5
+    c = r.standard_normal((st.L + 1, N, H_))
+    sv = O.forward(st, x0, xin)
+    G = O.exact_backward(st, sv, c)
+    pg = O.param_grads(st, sv, G, xin)
+    assert set(pg) == {"dW1", "dU"}
+
+    t = lambda a: torch.tensor(a, dtype=torch.float64, requires_grad=True)
+    W, U = t(st.W1), t(st.U)
+    xs = [t(x0)]
+    for l in range(st.L):
+        x = xs[-1]
+        pre = x @ W.T + torch.tensor(xin[l]) @ U.T
+        u, cc = torch.sigmoid(pre[:, :H_]), torch.tanh(pre[:, H_:])
+        nxt = (1 - u) * x + u * cc
+        nxt.retain_grad()
+        xs.append(nxt)
+    loss = sum((torch.tensor(c[l]) * xs[l]).sum() for l in range(st.L + 1))
+    loss.backward()
+    for l in range(st.L + 1):
+        np.testing.assert_allclose(sv["x"][l], xs[l].detach().numpy(), rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(G[l], xs[l].grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(pg["dW1"], W.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(pg["dU"], U.grad.numpy(), rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("gamma", [0.0, 0.4])
+def test_gated_cell_by_path_enumeration(gamma):
+    """Theorem 2 for r(x, z) = z1 (.) x + z2: K_l = diag(1 - u_l) (a function of the state) and J_l = the Jacobian
+    of h -> (1 - u(h)) (.) x_l + u(h) (.) c(h) with x_l held fixed, by central differences."""
+    st = small_gated(T=5, H=3, I=2, seed=3)
+    r = np.random.default_rng(9)
+    xin = r.standard_normal((st.L, 1, 2))
+    sv = O.forward(st, r.standard_normal((1, st.d)) * 0.5, xin)
+    e = r.standard_normal((st.L + 1, 1, st.d))
+    L, H_ = st.L, st.d
+
+    def jac(l):
+        x = sv["x"][l][0]
+
+        def via_g(h):
+            pre = st.W1 @ h + st.U @ xin[l][0]
+            u, c = 1 / (1 + np.exp(-pre[:H_])), np.tanh(pre[H_:])
+            return (1 - u) * x + u * c
+        J = np.zeros((H_, H_))
+        for i in range(H_):
+            hp, hm = x.copy(), x.copy()
+            hp[i] += 1e-6
+            hm[i] -= 1e-6
+            J[:, i] = (via_g(hp) - via_g(hm)) / 2e-6
+        return J
+    Kd = [np.diag(1 - sv["u"][l][0]) for l in range(L)]
+    Js = [jac(l) + gamma * Kd[l] for l in range(L)]
+    Ks = [(1 - gamma) * Kd[l] for l in range(L)]
+    for k in range(L + 1):
+        w = O.hbp_backward(st, sv, e, k, gamma=gamma)
+        for i in range(L + 1):
+            acc = np.zeros(H_)
+            for j in range(i, L + 1):
+                layers = list(range(i, j))
+                for size in range(min(k, len(layers)) + 1):
+                    for chosen in itertools.combinations(layers, size):
+                        vec = e[j][0].copy()
+                        for l in reversed(layers):
+                            vec = vec @ (Js[l] if l in chosen else Ks[l])
+                        acc += vec
+            np.testing.assert_allclose(w[i][0], acc, rtol=2e-6, atol=2e-8)
+    np.testing.assert_allclose(O.hbp_backward(st, sv, e, L, gamma=gamma), O.exact_backward(st, sv, e),
+                               rtol=1e-10, atol=1e-12)
+
+
+def test_gated_cell_k0_and_finite_termination():
+    """w^0 carries e_T down by the products of the cell's own 1 - u; exact once k >= T - i."""
+    st = small_gated(T=6, H=4, I=3, seed=5)
+    r = np.random.default_rng(2)
+    xin = r.standard_normal((st.L, 2, 3))
+    sv = O.forward(st, np.zeros((2, st.d)), xin)
+    e = r.standard_normal((2, st.d))
+    w0 = O.hbp_backward(st, sv, e, 0)
+    prod = np.ones_like(e)
+    for l in range(st.L - 1, -1, -1):
+        prod = prod * (1 - sv["u"][l])
+        np.testing.assert_allclose(w0[l], e * prod, rtol=1e-12)
+    G = O.exact_backward(st, sv, e)
+    for k in range(st.L + 1):
+        w = O.hbp_backward(st, sv, e, k)
+        for i in range(st.L + 1):
+            if k >= st.L - i:
+                np.testing.assert_allclose(w[i], G[i], rtol=1e-11, atol=1e-13)
