@@ -53,7 +53,11 @@ def algorithmic_work(w, k):
     blocks = sum(L - it + 1 for it in range(1, iters + 1))
     vjp1 = per_block * (blocks + L)        # + the one in hbp_param_grads
     vjp2 = per_block * blocks
-    dw = 2.0 * per_block * L + (2.0 * N * L * dff * w.d_in if w.kind == "rnn" else 0.0)
+    rec = w.kind in ("rnn", "gated")
+    dw = 2.0 * per_block * L + (2.0 * N * L * dff * w.d_in if rec else 0.0)
+    if w.kind == "gated":                  # no second weight: one parameter contraction less, and the first
+        dw -= per_block * L                # half of step (i) is elementwise (counted in bytes below)
+        vjp1 = 0.0
     S = float(L) * N * d
     # per iteration the scan reads dn (+ y with a norm; + e only when a norm sits between
     # the block and the residual path: otherwise e was added by the second contraction)
@@ -66,7 +70,7 @@ def algorithmic_work(w, k):
     # bytes the contractions must move: each operand read once, each result written once (weights once per
     # launch when all steps share them).  They decide which roofline binds: at the published peaks the
     # chip's balance is 2500 TFLOP/s / 8 TB/s = 312 flop per byte.
-    shared = w.kind == "rnn"
+    shared = rec
     aux1 = 0.0 if w.act == "identity" else float(N) * dff * s            # act' (or z) read by the first epilogue
     wbytes = float(d) * dff * s
 
@@ -77,9 +81,13 @@ def algorithmic_work(w, k):
         e_aux = N * d * s if (w.loss_every_state and w.norm == "none") else 0.0
         return nb * (N * dff * s + N * d * s + e_aux) + (1 if shared else nb) * wbytes
     per_it = [L - it + 1 for it in range(1, iters + 1)]
+    if w.kind == "gated":                  # reads g, x, [u | c]; writes da [N, 2H]
+        def b1(nb):
+            return nb * float(N) * (2 * d + 2 * dff) * s
     vjp1_bytes = sum(b1(nb) for nb in per_it) + b1(L)
     vjp2_bytes = sum(b2(nb) for nb in per_it)
-    dw_bytes = L * (2.0 * N * d * s + 2.0 * N * dff * s) + (1 if shared else L) * 2.0 * d * dff * 4 \
+    dw_bytes = L * ((1.0 if w.kind == "gated" else 2.0) * N * (d + dff) * s) \
+        + (1 if shared else L) * (1.0 if w.kind == "gated" else 2.0) * d * dff * 4 \
         + ((L * N * (dff + w.d_in) * s + dff * w.d_in * 4.0) if shared else 0.0)
     return {"vjp1": vjp1, "vjp2": vjp2, "dw": dw, "scan_bytes": scan_init + iters * scan_iter,
             "scan_launches": 1 + iters, "vjp1_bytes": vjp1_bytes, "vjp2_bytes": vjp2_bytes, "dw_bytes": dw_bytes}
@@ -146,14 +154,17 @@ def cpu_baseline(w, k, budget_tokens):
         threads = os.cpu_count() or 1
     n = min(budget_tokens, w.N)
     inp = synth.make_inputs(w, tokens=slice(0, n))
-    st = O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], U=inp["U"], eps=w.eps, L=w.L,
-                 post=w.post)
+    if w.kind == "gated":
+        st = O.Stack("gated", w.act, w.norm, inp["W1"], None, U=inp["U"], L=w.L)
+    else:
+        st = O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], U=inp["U"], eps=w.eps, L=w.L,
+                     post=w.post)
     sv = O.forward(st, inp["x0"], inp["xin"])
     t0 = time.perf_counter()
     g = O.hbp_backward(st, sv, inp["e"], k)
     O.param_grads(st, sv, g, inp["xin"])
     dt = time.perf_counter() - t0
-    toks = n * (w.L if w.kind == "rnn" else 1)
+    toks = n * (w.L if w.kind in ("rnn", "gated") else 1)
     return {"value": toks / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
             "sample": f"{n} of {w.N} token rows at full L={w.L}, d={w.d}, d_ff={w.d_ff}; "
                       f"hbp_backward(k={k}) + param_grads in {dt:.1f} s (forward untimed)"}
@@ -243,6 +254,13 @@ def main():
                 "avg_launch_ms": ms[cls] / max(launches[cls], 1)}
 
     roofs = {c: mfma_roof(c) for c in ("vjp1", "vjp2", "dw")}
+    if w.kind == "gated":                  # step (i)'s first half is elementwise there: memory roofline
+        t1 = ms["vjp1"] * 1e-3
+        a1 = work["vjp1_bytes"] / t1 / 1e9 if t1 > 0 else 0.0
+        roofs["vjp1"] = {"bound": "hbm", "achieved": a1, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                         "frac": a1 / PEAK_HBM_GBS, "traffic": None, "kernel_class": "vjp1",
+                         "ms_per_step": ms["vjp1"], "launches_per_step": launches["vjp1"],
+                         "avg_launch_ms": ms["vjp1"] / max(launches["vjp1"], 1)}
     t_scan = ms["scan"] * 1e-3
     ach = work["scan_bytes"] / t_scan / 1e9 if t_scan > 0 else 0.0
     roofs["scan"] = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -316,7 +334,7 @@ def main():
         # about 10-20 s of oracle work on the GPU machine's host cores
         n = args.cpu_tokens or {"mlp_small_f32": 128, "resnet_like": 8192, "resnet_postact": 8192, "transformer_mlp": 2048,
                                 "deep_large": 256, "gated_rnn": 16, "gated_rnn_contractive": 16,
-                                "gated_rnn_token_gates": 16}.get(w.name, 64)
+                                "gated_rnn_token_gates": 16, "gru_cell": 16}.get(w.name, 64)
         out["cpu_baseline"] = cpu_baseline(w, k, n)
 
     def finite(o):   # JSON has no NaN/Infinity: overflowed error figures become null

@@ -53,7 +53,14 @@ typedef enum {
 } hbp_status;
 
 typedef enum { HBP_F32 = 0, HBP_BF16 = 1 } hbp_dtype;
-typedef enum { HBP_MLP = 0, HBP_RNN = 1 } hbp_kind;
+/* HBP_GATED: a recurrent cell whose residual coefficient is a function of the state (the GRU row of the table
+ * of layer decompositions, f(x) = a(x) (.) x + b(x) with r(x, z) = z1 (.) x + z2):
+ *   u = sigmoid(W_u x + U_u xin), c = tanh(W_c x + U_c xin), x' = (1 - u) (.) x + u (.) c,
+ * so K = diag(1 - u) per token and the block VJP is [g (.) (c - x) u (1 - u) | g (.) u (1 - c^2)] . [W_u; W_c].
+ * Shapes: d = H, d_ff = 2H, W1 = [W_u; W_c] [2H,H], U = [U_u; U_c] [2H,d_in]; W2, dW2, dphi, y, rinv unused.
+ * z holds [u | c] as [L,N,2H].  lambda_kind must be HBP_LAMBDA_TOKEN: hbp_forward WRITES lambda = 1 - u there
+ * ([L,N,H], storage type) and the backward calls read it.  act = HBP_ACT_TANH, norm = HBP_NORM_NONE. */
+typedef enum { HBP_MLP = 0, HBP_RNN = 1, HBP_GATED = 2 } hbp_kind;
 /* GELU is the exact erf form a*Phi(a); IDENTITY makes blocks linear (tests). */
 typedef enum { HBP_ACT_GELU_ERF = 0, HBP_ACT_TANH = 1, HBP_ACT_IDENTITY = 2 } hbp_act;
 /* RMS: y = x / sqrt(mean_c(x^2) + eps), no gain. */
@@ -98,7 +105,8 @@ typedef struct {
   const void* W1;
   const void* W2;
   const void* U;
-  const void* lambda;        /* CHANNEL: fp32 [L,d]; TOKEN: S [L,N,d].  Row (block) l carries state l+1 to state l */
+  const void* lambda;        /* CHANNEL: fp32 [L,d]; TOKEN: S [L,N,d].  Row (block) l carries state l+1 to state l.
+                              * (HBP_GATED: written by hbp_forward through this pointer.) */
   /* forward state: written by hbp_forward, read by the backward calls. */
   void* x;                   /* S [L+1,N,d]  states x_0..x_L (x[0] is the input) */
   void* y;                   /* S [L,N,d]    norm(x_l); unused (may be NULL) with HBP_NORM_NONE, where x is read */

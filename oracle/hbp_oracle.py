@@ -192,7 +192,9 @@ def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict
 
 def _forward_gated(st: Stack, x0: np.ndarray, xin: np.ndarray) -> Dict[str, np.ndarray]:
     """x_{l+1} = (1 - u_l) (.) x_l + u_l (.) c_l,  u = sigmoid(W_u x + U_u xin),  c = tanh(W_c x + U_c xin).
-    Saved: x, u and c [L,N,H] (and y = x, rinv = 1, mask = 1 so that the shared code reads them)."""
+    Saved: x, u, c and a = 1 - u (the coefficient of the residual path, kept as its own tensor as the
+    layer decomposition has it: z1 = a(x)), all [L,N,H] (and y = x, rinv = 1, mask = 1 so that the
+    shared code reads them)."""
     N, H = x0.shape
     L = st.L
     x = np.zeros((L + 1, N, H), F64)
@@ -204,14 +206,15 @@ def _forward_gated(st: Stack, x0: np.ndarray, xin: np.ndarray) -> Dict[str, np.n
         u[l] = 1.0 / (1.0 + np.exp(-pre[:, :H]))
         c[l] = np.tanh(pre[:, H:])
         x[l + 1] = (1.0 - u[l]) * x[l] + u[l] * c[l]
-    return {"x": x, "y": x[:-1], "rinv": np.ones((L, N), F64), "u": u, "c": c, "mask": np.ones((L, N, H), F64)}
+    return {"x": x, "y": x[:-1], "rinv": np.ones((L, N), F64), "u": u, "c": c, "a": 1.0 - u,
+            "mask": np.ones((L, N, H), F64)}
 
 
 def k_diag(st: Stack, l: int, saved: Dict[str, np.ndarray]) -> np.ndarray:
     """Diagonal of dr/dx for the layer that carries state l+1 to state l, before any mask: lam_l, or for the
-    gated cell its own coefficient a = 1 - u_l (per token)."""
+    gated cell its own coefficient a_l = 1 - u_l (per token)."""
     if st.kind == "gated":
-        return 1.0 - saved["u"][l]
+        return saved["a"][l]
     return st.lam_row(l)
 
 

@@ -9,6 +9,8 @@ from __future__ import annotations
 
 import ctypes as C
 import os
+
+import numpy as np
 from dataclasses import dataclass
 from typing import Optional
 
@@ -19,7 +21,8 @@ HBP_OK = 0
 STATUS_NAMES = {0: "HBP_OK", 1: "HBP_E_INVALID_ARG", 2: "HBP_E_UNSUPPORTED", 3: "HBP_E_WORKSPACE",
                 4: "HBP_E_NULL", 5: "HBP_E_DEVICE"}
 F32, BF16 = 0, 1
-MLP, RNN = 0, 1
+MLP, RNN, GATED = 0, 1, 2
+KIND = {"mlp": MLP, "rnn": RNN, "gated": GATED}
 ACT = {"gelu": 0, "tanh": 1, "identity": 2}
 NORM = {"none": 0, "rms": 1}
 POST = {"none": 0, "relu": 1}
@@ -91,7 +94,7 @@ def status_string(status: int) -> str:
 def make_desc(kind: str, dtype: str, act: str, norm: str, L: int, N: int, d: int, d_ff: int, d_in: int = 0,
               lambda_channel: bool = False, loss_every_state: bool = False, eps: float = 1e-6,
               gamma: float = 0.0, lambda_token: bool = False, post: str = "none") -> hbp_desc:
-    return hbp_desc(C.sizeof(hbp_desc), RNN if kind == "rnn" else MLP, BF16 if dtype == "bf16" else F32,
+    return hbp_desc(C.sizeof(hbp_desc), KIND[kind], BF16 if dtype == "bf16" else F32,
                     ACT[act], NORM[norm],
                     LAMBDA_TOKEN if lambda_token else LAMBDA_CHANNEL if lambda_channel else LAMBDA_ONE,
                     1 if loss_every_state else 0, eps, L, N, d, d_ff, d_in, gamma, POST[post])
@@ -230,6 +233,8 @@ def allocate(w, inputs, device="cuda:0", N: Optional[int] = None) -> Problem:
         return None if a is None else torch.from_numpy(a).to(dev).to(dtype).contiguous()
 
     lam = inputs["lam"]
+    if w.kind == "gated":      # the cell's own 1 - u, written by hbp_forward: [L,N,d] in the storage type
+        lam = np.zeros((w.L, N, w.d), np.float32)
     per_token = lam is not None and lam.ndim == 3      # [L,N,d] in the storage type; [L,d] is fp32
     desc = make_desc(w.kind, w.dtype, w.act, w.norm, w.L, N, w.d, w.d_ff, w.d_in,
                      lambda_channel=lam is not None and not per_token, lambda_token=per_token,
@@ -249,7 +254,7 @@ def allocate(w, inputs, device="cuda:0", N: Optional[int] = None) -> Problem:
         mask=torch.zeros((L, N, d // 8), dtype=torch.uint8, device=dev) if getattr(w, "post", "none") == "relu" else None,
         g=torch.zeros((L + 1, N, d), dtype=dt, device=dev),
         dW1=torch.zeros(inputs["W1"].shape, dtype=torch.float32, device=dev),
-        dW2=torch.zeros(inputs["W2"].shape, dtype=torch.float32, device=dev),
+        dW2=None if inputs["W2"] is None else torch.zeros(inputs["W2"].shape, dtype=torch.float32, device=dev),
         dU=None if inputs["U"] is None else torch.zeros(inputs["U"].shape, dtype=torch.float32, device=dev),
     )
     p.workspace = torch.zeros(workspace_size(desc), dtype=torch.uint8, device=dev)

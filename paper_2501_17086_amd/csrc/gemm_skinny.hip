@@ -89,6 +89,11 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) v[j] += lm[j] * x[j];
   }
+  if (a.c_is_f32) {
+    *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.C) + (m0 + row) * a.ldc + n0 + c0) =
+        make_float4(v[0], v[1], v[2], v[3]);
+    return;
+  }
   uint2 o;
   o.x = (unsigned)f32_to_bf16(v[0]) | ((unsigned)f32_to_bf16(v[1]) << 16);
   o.y = (unsigned)f32_to_bf16(v[2]) | ((unsigned)f32_to_bf16(v[3]) << 16);
@@ -127,6 +132,7 @@ hipError_t launch_gemm_skinny(const SkinnyArgs& a, hipStream_t s) {
     return hipErrorInvalidValue;
   if (a.mode != EPI_STORE && a.mode != EPI_RESID && a.mode != EPI_ACT_TANH && !a.aux) return hipErrorInvalidValue;
   if (a.mode == EPI_RESID && !a.next) return hipErrorInvalidValue;
+  if (a.c_is_f32 && a.mode != EPI_STORE) return hipErrorInvalidValue;
   if ((a.lda % 8) || (a.ldbt % 8) || (a.ldc % 4) || (a.aux && (a.ldaux % 4))) return hipErrorInvalidValue;
   dim3 grid((unsigned)(a.N / 32), (unsigned)((a.M + 31) / 32));
   hipLaunchKernelGGL(gemm_skinny_kernel, grid, dim3(256), 0, s, a);

@@ -14,10 +14,11 @@ namespace {
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline size_t esize(const hbp_desc* d) { return d->dtype == HBP_F32 ? 4 : 2; }
-inline bool shared_w(const hbp_desc* d) { return d->kind == HBP_RNN; }
+inline bool recurrent(const hbp_desc* d) { return d->kind == HBP_RNN || d->kind == HBP_GATED; }
+inline bool shared_w(const hbp_desc* d) { return recurrent(d); }
 
 struct Workspace {
-  size_t off_v, off_da, off_part, off_scan, off_wt, total;
+  size_t off_v, off_da, off_part, off_scan, off_wt, off_pre, total;
 };
 
 // split-K factor for a parameter-gradient GEMM with `tiles` output tiles and a
@@ -43,7 +44,7 @@ Splits param_splits(const hbp_desc* d) {
   const long K = shared_w(d) ? d->L * d->N : d->N;
   s.s_w2 = pick_split(tiles_of(d->d, d->d_ff) * nb, K);
   s.s_w1 = s.s_w2;
-  if (d->kind == HBP_RNN) s.s_u = pick_split(tiles_of(d->d_ff, d->d_in), K);
+  if (recurrent(d)) s.s_u = pick_split(tiles_of(d->d_ff, d->d_in), K);
   return s;
 }
 
@@ -53,7 +54,7 @@ Workspace carve(const hbp_desc* d) {
   size_t o = 0;
   w.off_v = o;  o = align_up(o + (size_t)d->L * d->N * d->d * es, 256);
   // da [L,N,d_ff] in the storage type; the RNN forward also keeps U.xin here as fp32
-  size_t da_bytes = (size_t)d->L * d->N * d->d_ff * (d->kind == HBP_RNN ? 4 : es);
+  size_t da_bytes = (size_t)d->L * d->N * d->d_ff * (recurrent(d) ? 4 : es);
   w.off_da = o; o = align_up(o + da_bytes, 256);
   Splits sp = param_splits(d);
   const size_t nb = shared_w(d) ? 1 : (size_t)d->L;
@@ -67,27 +68,33 @@ Workspace carve(const hbp_desc* d) {
   w.off_scan = o; o = align_up(o + scan_chunk_ws_bytes(d->L, d->N, d->d, d->norm == HBP_NORM_RMS), 256);
   // transposed copies of the shared weights for step-by-step backpropagation through time
   w.off_wt = o;
-  if (d->kind == HBP_RNN && d->dtype == HBP_BF16) o = align_up(o + 2 * (size_t)d->d * d->d_ff * es, 256);
+  if (recurrent(d) && d->dtype == HBP_BF16) o = align_up(o + 2 * (size_t)d->d * d->d_ff * es, 256);
+  // one step's pre-activations of the gated cell, fp32 [N, 2H]
+  w.off_pre = o;
+  if (d->kind == HBP_GATED) o = align_up(o + (size_t)d->N * d->d_ff * 4, 256);
   w.total = o;
   return w;
 }
 
 // One step of the recurrence at a time, few rows: the few-row kernel with transposed weights.
 inline bool step_skinny(const hbp_desc* d) {
-  return d->kind == HBP_RNN && d->dtype == HBP_BF16 && skinny_ok(d->N, d->d_ff, d->d) && skinny_ok(d->N, d->d, d->d_ff);
+  return recurrent(d) && d->dtype == HBP_BF16 && skinny_ok(d->N, d->d_ff, d->d) && skinny_ok(d->N, d->d, d->d_ff);
 }
 
 hbp_status check_desc(const hbp_desc* d) {
   if (!d) return HBP_E_NULL;
   if (d->struct_size != sizeof(hbp_desc)) return HBP_E_INVALID_ARG;
-  if (d->kind != HBP_MLP && d->kind != HBP_RNN) return HBP_E_INVALID_ARG;
+  if (d->kind != HBP_MLP && d->kind != HBP_RNN && d->kind != HBP_GATED) return HBP_E_INVALID_ARG;
   if (d->dtype != HBP_F32 && d->dtype != HBP_BF16) return HBP_E_INVALID_ARG;
   if (d->act < HBP_ACT_GELU_ERF || d->act > HBP_ACT_IDENTITY) return HBP_E_INVALID_ARG;
   if (d->norm != HBP_NORM_NONE && d->norm != HBP_NORM_RMS) return HBP_E_INVALID_ARG;
   if (d->lambda_kind < HBP_LAMBDA_ONE || d->lambda_kind > HBP_LAMBDA_TOKEN) return HBP_E_INVALID_ARG;
   if (d->loss_every_state != 0 && d->loss_every_state != 1) return HBP_E_INVALID_ARG;
   if (d->L <= 0 || d->N <= 0 || d->d <= 0 || d->d_ff <= 0 || d->d_in < 0) return HBP_E_INVALID_ARG;
-  if (d->kind == HBP_RNN && d->d_in <= 0) return HBP_E_INVALID_ARG;
+  if (recurrent(d) && d->d_in <= 0) return HBP_E_INVALID_ARG;
+  if (d->kind == HBP_GATED && (d->act != HBP_ACT_TANH || d->norm != HBP_NORM_NONE || d->lambda_kind != HBP_LAMBDA_TOKEN ||
+                               d->d_ff != 2 * d->d))
+    return HBP_E_INVALID_ARG;
   if (d->kind == HBP_MLP && d->d_in != 0) return HBP_E_INVALID_ARG;
   if (d->norm == HBP_NORM_RMS && !(d->eps >= 0.f)) return HBP_E_INVALID_ARG;
   if (d->d % 8 || d->d_ff % 8 || d->d_in % 8) return HBP_E_UNSUPPORTED;
@@ -105,8 +112,8 @@ enum Need { NEED_FWD = 1, NEED_BWD = 2, NEED_PG = 4 };
 hbp_status check_bufs(const hbp_desc* d, const hbp_buffers* b, int need) {
   if (!b) return HBP_E_NULL;
   if (b->struct_size != sizeof(hbp_buffers)) return HBP_E_INVALID_ARG;
-  if (!b->W1 || !b->W2) return HBP_E_NULL;
-  if (d->kind == HBP_RNN && (need & (NEED_FWD | NEED_PG)) && (!b->U || !b->xin)) return HBP_E_NULL;
+  if (!b->W1 || (!b->W2 && d->kind != HBP_GATED)) return HBP_E_NULL;
+  if (recurrent(d) && (need & (NEED_FWD | NEED_PG)) && (!b->U || !b->xin)) return HBP_E_NULL;
   if (d->lambda_kind != HBP_LAMBDA_ONE && !b->lambda) return HBP_E_NULL;
   if (d->norm == HBP_NORM_RMS && (!b->y || !b->rinv)) return HBP_E_NULL;
   if (d->norm == HBP_NORM_NONE && !b->x) return HBP_E_NULL;
@@ -119,8 +126,8 @@ hbp_status check_bufs(const hbp_desc* d, const hbp_buffers* b, int need) {
   }
   if ((need & NEED_BWD) && !b->e) return HBP_E_NULL;
   if (need & NEED_PG) {
-    if (!b->dW1 || !b->dW2) return HBP_E_NULL;
-    if (d->kind == HBP_RNN && !b->dU) return HBP_E_NULL;
+    if (!b->dW1 || (!b->dW2 && d->kind != HBP_GATED)) return HBP_E_NULL;
+    if (recurrent(d) && !b->dU) return HBP_E_NULL;
   }
   Workspace w = carve(d);
   if (!b->workspace || b->workspace_bytes < w.total) return HBP_E_WORKSPACE;
@@ -192,6 +199,14 @@ hbp_status vjp_stage1(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
                       hipStream_t s, bool skinny = false) {
   const size_t es = esize(d);
   const long nl = l_hi - l_lo;
+  if (d->kind == HBP_GATED) {   // no first contraction: dL/du and dL/dc through sigmoid' and tanh', elementwise
+    ProfScope ps(HBP_PROF_VJP1, s);
+    HBP_TRY(launch_gated_vjp(d->dtype, at(b->g, (size_t)(l_lo + 1) * d->N * d->d * es),
+                             at((const void*)b->x, (size_t)l_lo * d->N * d->d * es),
+                             at((const void*)b->z, (size_t)l_lo * d->N * d->d_ff * es),
+                             at(b->workspace, w.off_da + (size_t)l_lo * d->N * d->d_ff * es), nl * d->N, d->d, s));
+    return HBP_OK;
+  }
   if (skinny) {   // one step; W2^T [d_ff,d] sits first in the transposed-weight region
     SkinnyArgs k{};
     k.A = at(b->g, (size_t)(l_lo + 1) * d->N * d->d * es); k.lda = d->d;
@@ -405,7 +420,7 @@ hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
   const bool rms = d->norm == HBP_NORM_RMS;
   float* ux = reinterpret_cast<float*>(at(b->workspace, w.off_da));
   const bool skinny = step_skinny(d) && d->act != HBP_ACT_GELU_ERF;
-  if (d->kind == HBP_RNN) {  // U . xin for every step at once
+  if (recurrent(d)) {  // U . xin for every step at once
     GemmArgs ga{};
     ga.A = b->xin; ga.B = b->U; ga.C = ux;
     ga.M = d->L * d->N; ga.N = d->d_ff; ga.K = d->d_in;
@@ -424,6 +439,35 @@ hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
       HBP_TRY(launch_rmsnorm_fwd(d->dtype, at((const void*)b->x, xo), at(b->y, xo), b->rinv + l * d->N, d->N, d->d,
                                  d->eps, s));
       yl = at((const void*)b->y, xo);
+    }
+    if (d->kind == HBP_GATED) {
+      // pre = x W1^T + U xin (fp32), then the cell elementwise: z[l] = [u | c], lambda[l] = 1 - u, x[l+1]
+      float* pre = reinterpret_cast<float*>(at(b->workspace, w.off_pre));
+      if (skinny) {
+        SkinnyArgs k{};
+        k.A = yl; k.lda = d->d;
+        k.Bt = b->W1; k.ldbt = d->d;
+        k.C = pre; k.ldc = d->d_ff; k.c_is_f32 = 1;
+        k.M = d->N; k.N = d->d_ff; k.K = d->d;
+        k.mode = EPI_STORE;
+        k.addf = ux + l * d->N * d->d_ff;
+        ProfScope ps(HBP_PROF_FORWARD, s);
+        HBP_TRY(launch_gemm_skinny(k, s));
+      } else {
+        GemmArgs ga{};
+        ga.A = yl; ga.B = b->W1; ga.C = pre;
+        ga.M = d->N; ga.N = d->d_ff; ga.K = d->d;
+        ga.a_sm = d->d; ga.a_sk = 1;
+        ga.b_sk = 1; ga.b_sn = d->d;
+        ga.ldc = d->d_ff; ga.batch = 1; ga.split_k = 1;
+        ga.mode = EPI_STORE; ga.c_is_f32 = 1;
+        ga.addf = ux + l * d->N * d->d_ff;
+        HBP_RUN(run_gemm(d, ga, s, HBP_PROF_FORWARD));
+      }
+      ProfScope ps(HBP_PROF_FORWARD, s);
+      HBP_TRY(launch_gated_fwd(d->dtype, pre, yl, at(b->z, fo), at(const_cast<void*>(b->lambda), xo),
+                               at(b->x, xo + (size_t)d->N * d->d * es), d->N, d->d, s));
+      continue;
     }
     if (skinny) {   // one step of the recurrence, few rows; the weights as stored are already K-contiguous
       SkinnyArgs k{};
@@ -508,7 +552,7 @@ hbp_status hbp_backward(const hbp_desc* d, int k, hbp_buffers* b, void* stream) 
     // bit-identical from then on), so v_l of blocks l >= L-it+1 left by the
     // previous iteration is still valid: recompute only the blocks below.
     long l_hi = d->L - it + 1;
-    if (d->kind == HBP_RNN) {
+    if (recurrent(d)) {
       // One contraction covers all rows (l_hi * N): where re-doing a few of the final blocks keeps
       // the row count a multiple of the 256-row GEMM tile, do that (same values, aligned kernel).
       long step = 256;
@@ -578,7 +622,8 @@ hbp_status hbp_exact_backward(const hbp_desc* d, hbp_buffers* b, void* stream) {
   const bool fuse = skinny && d->norm == HBP_NORM_NONE;   // the step along the residual path in the same kernel
   if (skinny) {
     ProfScope ps(HBP_PROF_OTHER, s);
-    HBP_TRY(launch_transpose_bf16(bb.W2, at(bb.workspace, w.off_wt), (int)d->d, (int)d->d_ff, s));
+    if (d->kind != HBP_GATED)
+      HBP_TRY(launch_transpose_bf16(bb.W2, at(bb.workspace, w.off_wt), (int)d->d, (int)d->d_ff, s));
     HBP_TRY(launch_transpose_bf16(bb.W1, at(bb.workspace, w.off_wt + (size_t)d->d * d->d_ff * esize(d)), (int)d->d_ff,
                                   (int)d->d, s));
   }
@@ -607,13 +652,14 @@ hbp_status hbp_param_grads(const hbp_desc* d, hbp_buffers* b, void* stream) {
   void* part = at(b->workspace, w.off_part);
   const void* g1 = at((const void*)bb.g, (size_t)d->N * d->d * es);
   const void* da = at((const void*)b->workspace, w.off_da);
-  // dW2[c,j] = sum_n g_{l+1}[n,c] z_l[n,j]
-  HBP_RUN(tn_gemm(d, g1, d->d, d->N * d->d, bb.z, d->d_ff, d->N * d->d_ff, bb.dW2, d->d, d->d_ff, K, nb, sp.s_w2,
-                  part, s));
+  // dW2[c,j] = sum_n g_{l+1}[n,c] z_l[n,j]   (the gated cell has no second weight)
+  if (d->kind != HBP_GATED)
+    HBP_RUN(tn_gemm(d, g1, d->d, d->N * d->d, bb.z, d->d_ff, d->N * d->d_ff, bb.dW2, d->d, d->d_ff, K, nb, sp.s_w2,
+                    part, s));
   // dW1[j,c] = sum_n da_l[n,j] y_l[n,c]
   HBP_RUN(tn_gemm(d, da, d->d_ff, d->N * d->d_ff, bb.y, d->d, d->N * d->d, bb.dW1, d->d_ff, d->d, K, nb, sp.s_w1,
                   part, s));
-  if (d->kind == HBP_RNN) {
+  if (recurrent(d)) {
     // dU[j,i] = sum da[n,j] xin[n,i]
     HBP_RUN(tn_gemm(d, da, d->d_ff, 0, bb.xin, d->d_in, 0, bb.dU, d->d_ff, d->d_in, K, 1, sp.s_u, part, s));
   }

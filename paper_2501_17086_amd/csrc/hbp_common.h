@@ -133,6 +133,7 @@ struct SkinnyArgs {
   const float* lambda;
   const void* lambda_mn;
   const float* addf;   // fp32 [M,N] with C's row stride, added to the product before the epilogue; or NULL
+  int c_is_f32;        // C stored as fp32 (EPI_STORE only)
 };
 bool skinny_ok(long M, long N, long K);   // M <= 128, N % 32 == 0, K % 64 == 0
 hipError_t launch_gemm_skinny(const SkinnyArgs& a, hipStream_t s);
@@ -194,6 +195,13 @@ hipError_t launch_scan_hillis_steele(int dtype, const HsArgs& a, hipStream_t s);
 // x := max(x, 0) over n elements (n % 8 == 0), mask bit = 1 where x was positive; g := g (.) mask bits
 hipError_t launch_relu_mask(int dtype, void* x, uint8_t* mask, long n, hipStream_t s);
 hipError_t launch_mask_apply(int dtype, void* g, const uint8_t* mask, long n, hipStream_t s);
+
+// The gated recurrent cell's elementwise parts (H % 8 == 0): one step forward from pre [N,2H] fp32, and step (i)
+// up to its contraction for `rows` token rows of consecutive blocks (g points at the gradient of block 0's NEXT state).
+hipError_t launch_gated_fwd(int dtype, const float* pre, const void* x, void* uc, void* a, void* xn, long N, long H,
+                            hipStream_t s);
+hipError_t launch_gated_vjp(int dtype, const void* g, const void* x, const void* uc, void* da, long rows, long H,
+                            hipStream_t s);
 
 // y = x * rinv, rinv = 1/sqrt(mean(x^2)+eps) for `rows` rows of width d
 hipError_t launch_rmsnorm_fwd(int dtype, const void* x, void* y, float* rinv, long rows, long d, float eps,

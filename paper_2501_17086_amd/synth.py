@@ -30,7 +30,7 @@ _T_W1, _T_W2, _T_U, _T_LAM, _T_X0, _T_XIN, _T_E = 1, 2, 3, 4, 5, 6, 7
 @dataclass(frozen=True)
 class Workload:
     name: str
-    kind: str            # 'mlp' | 'rnn'
+    kind: str            # 'mlp' | 'rnn' | 'gated' (recurrent cell x' = (1-u) x + u c; d_ff = 2 d)
     dtype: str           # 'f32' | 'bf16'   (storage; accumulation is fp32 on the GPU)
     act: str             # 'gelu' | 'tanh' | 'identity'
     norm: str            # 'none' | 'rms'
@@ -48,13 +48,14 @@ class Workload:
     rec_scale: float = 1.0   # extra factor on W_h and W_o (rnn variants)
     loss_every_state: bool = False
     post: str = "none"   # 'none' | 'relu': what the residual function applies after the sum
+    gate_bias: float = 0.0   # 'gated': constant added to the update gate's pre-activation (see make_inputs)
     eps: float = 1e-6
     ks: tuple = (1, 2, 3, 4)
     seed: int = 0
 
     @property
     def tokens(self) -> int:
-        return self.N * self.L if self.kind == "rnn" else self.N
+        return self.N * self.L if self.kind in ("rnn", "gated") else self.N
 
 
 WORKLOADS: Dict[str, Workload] = {
@@ -82,7 +83,11 @@ WORKLOADS: Dict[str, Workload] = {
 # specified is chaotic, so exact BPTT gradients overflow over 4096 steps.
 WORKLOADS["gated_rnn_contractive"] = replace(WORKLOADS["gated_rnn"], name="gated_rnn_contractive",
                                              rec_scale=0.25)
-# the same cell with a gate per (step, batch row, channel): a diagonal K that depends on the data
+# a recurrent cell whose residual coefficient is its own update gate (the GRU row of the paper's table of layer
+# decompositions): T = 4096, batch 32, H = 1024, gates biased towards closed (1 - u around 0.95)
+WORKLOADS["gru_cell"] = Workload("gru_cell", "gated", "bf16", "tanh", "none", L=4096, N=32, d=1024, d_ff=2048,
+                                 d_in=1024, loss_every_state=True, gate_bias=-3.0, rec_scale=0.5)
+# the contractive RNN with a gate per (step, batch row, channel): a diagonal K that depends on the data
 WORKLOADS["gated_rnn_token_gates"] = replace(WORKLOADS["gated_rnn_contractive"], name="gated_rnn_token_gates",
                                              lam="sigmoid_full")
 
@@ -114,7 +119,7 @@ def _normal(w: Workload, tid: int, idx: int, shape, std: float) -> np.ndarray:
 
 def weights_block(w: Workload, l: int):
     """(W1_l [d_ff,d], W2_l [d,d_ff]) for block l (rnn: l is ignored)."""
-    idx = 0 if w.kind == "rnn" else l
+    idx = 0 if w.kind in ("rnn", "gated") else l
     s1 = w.w1_std if w.w1_std > 0 else 1.0 / np.sqrt(w.d)
     s2 = (w.w2_std if w.w2_std > 0 else 1.0 / np.sqrt(w.d_ff)) * w.w2_scale
     W1 = _normal(w, _T_W1, idx, (w.d_ff, w.d), s1 * w.rec_scale)
@@ -168,8 +173,18 @@ def make_inputs(w: Workload, tokens=None) -> Dict[str, Optional[np.ndarray]]:
         out["U"] = storage_round(w, _normal(w, _T_U, 0, (w.d_ff, w.d_in), 1.0 / np.sqrt(w.d_in)))
         out["xin"] = storage_round(w, _normal(w, _T_XIN, 0, (w.L, w.N, w.d_in), 1.0)[:, sl])
     out["W1"], out["W2"] = W1, W2
+    if w.kind == "gated":
+        # W1 = [W_u; W_c].  The cell has no bias term: a constant update-gate bias (gates that are mostly closed,
+        # i.e. a long memory, as in a trained GRU) is realised through the input: channel 0 of xin is 1 and its
+        # column of U holds the bias for the gate rows and 0 for the candidate rows.
+        out["W2"] = None
+        H = w.d
+        out["xin"][..., 0] = 1.0
+        out["U"][:H, 0] = np.float32(w.gate_bias)
+        out["U"][H:, 0] = 0.0
+        out["U"] = storage_round(w, out["U"])
     out["lam"] = make_lambda(w, tokens)
-    if w.kind == "rnn":
+    if w.kind in ("rnn", "gated"):
         out["x0"] = np.zeros((w.N, w.d), np.float32)[sl]
     else:
         out["x0"] = storage_round(w, _normal(w, _T_X0, 0, (w.N, w.d), 1.0)[sl])

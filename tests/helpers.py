@@ -12,6 +12,8 @@ TOL = {"f32": 1e-5, "bf16": 2e-2}   # relative L2, GPU vs oracle
 
 
 def oracle_stack(w: synth.Workload, inp) -> O.Stack:
+    if w.kind == "gated":
+        return O.Stack("gated", w.act, w.norm, inp["W1"], None, U=inp["U"], L=w.L)
     return O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], U=inp["U"], eps=w.eps, L=w.L,
                    post=w.post)
 
@@ -25,6 +27,11 @@ def oracle_saved_rounded(w: synth.Workload, sv):
     arrays: the values a backward call reads from memory."""
     r = lambda a: synth.storage_round(w, a.astype(np.float32)).astype(np.float64)
     out = dict(sv)
+    if w.kind == "gated":      # x, the two gates and the residual coefficient, each stored on its own
+        for k in ("x", "u", "c", "a"):
+            out[k] = r(sv[k])
+        out["y"] = out["x"][:-1]
+        return out
     for k in ("x", "y", "z", "dphi"):
         out[k] = r(sv[k])
     out["rinv"] = sv["rinv"].astype(np.float32).astype(np.float64)
@@ -44,6 +51,10 @@ def upload_saved(p, w: synth.Workload, sv_r):
         if dst is not None:
             dst.copy_(torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev).to(dst.dtype))
     put(p.x, sv_r["x"])
+    if w.kind == "gated":      # z = [u | c] side by side, lambda = a
+        put(p.z, np.concatenate([sv_r["u"], sv_r["c"]], axis=-1))
+        put(p.lam, sv_r["a"])
+        return
     put(p.y, sv_r["y"])
     put(p.rinv, sv_r["rinv"])
     put(p.z, sv_r["z"])

@@ -82,6 +82,25 @@ def test_relu_after_the_sum_is_for_depth_stacks_with_the_plain_split():
         assert B.lib().hbp_initial_estimate(C.byref(_desc(post="relu")), alg, C.byref(bufs), None) == 2
 
 
+def test_gated_cell_descriptor_rules():
+    n = C.c_size_t(0)
+    ok = dict(kind="gated", act="tanh", norm="none", d=64, d_ff=128, d_in=32, lambda_token=True)
+    assert B.lib().hbp_workspace_size(C.byref(_desc(**ok)), C.byref(n)) == 0 and n.value > 0
+    for bad in (dict(d_ff=64), dict(act="gelu"), dict(norm="rms"), dict(lambda_token=False), dict(d_in=0),
+                dict(lambda_token=False, lambda_channel=True)):
+        assert B.lib().hbp_workspace_size(C.byref(_desc(**{**ok, **bad})), C.byref(n)) == 1, bad
+    assert B.lib().hbp_workspace_size(C.byref(_desc(**{**ok, "post": "relu"})), C.byref(n)) == 2
+    # W2 and dW2 are not part of the cell: NULL passes the pointer checks, a missing lambda does not
+    d = _desc(**ok)
+    bufs = B.hbp_buffers(C.sizeof(B.hbp_buffers))
+    for f in ("W1", "U", "xin", "x", "z", "e", "g", "dW1", "dU", "workspace"):
+        setattr(bufs, f, 256)
+    bufs.workspace_bytes = n.value
+    assert B.lib().hbp_check(C.byref(d), C.byref(bufs)) == 4
+    bufs.lambda_ = 256
+    assert B.lib().hbp_check(C.byref(d), C.byref(bufs)) == 0
+
+
 def test_null_pointers_and_workspace_are_checked_before_launch():
     d = _desc()
     bufs = B.hbp_buffers(C.sizeof(B.hbp_buffers))

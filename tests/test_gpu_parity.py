@@ -81,6 +81,18 @@ CASES = {
                                      N=203, d=72, d_ff=136, w2_scale=0.4, loss_every_state=True, ks=(0, 1, 2, 5)),
     "postact_f32_deep": synth.scaled(W["resnet_postact"], name="postact_f32_deep", dtype="f32", norm="none", L=270,
                                      N=3, d=64, d_ff=64, w2_scale=0.1, ks=(0, 2)),
+    # the gated recurrent cell (residual coefficient = the cell's own 1 - u): few-row kernels for the steps of exact
+    # BPTT and of the forward, fp32, a chain long enough for the chunked scan, a width the few-row kernel does not
+    # take, and row counts that are whole 256-row tiles
+    "gated_small": synth.scaled(W["gru_cell"], name="gated_small", L=37, N=5, d=128, d_ff=256, d_in=64,
+                                ks=(0, 1, 2, 5)),
+    "gated_f32": synth.scaled(W["gru_cell"], name="gated_f32", dtype="f32", L=19, N=3, d=64, d_ff=128, d_in=32,
+                              ks=(0, 1, 3, 19)),
+    "gated_long": synth.scaled(W["gru_cell"], name="gated_long", L=330, N=6, d=128, d_ff=256, d_in=64, ks=(0, 2)),
+    "gated_width_72": synth.scaled(W["gru_cell"], name="gated_width_72", L=12, N=7, d=72, d_ff=144, d_in=32,
+                                   ks=(0, 2)),
+    "gated_aligned": synth.scaled(W["gru_cell"], name="gated_aligned", L=64, N=8, d=256, d_ff=512, d_in=128,
+                                  ks=(0, 1, 2, 3)),
     # a loss on every state of a depth stack (e read by the scan behind the norm's backward), and without a norm
     # (e added by the second contraction's epilogue)
     # coefficients per (block, token, channel): direct scans (depth, RMS and none) and the chunked scan (time)
@@ -167,7 +179,8 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
                                   "mlp_f32_deep", "aligned_small", "rnn_aligned", "mlp_loss_all",
                                   "mlp_loss_all_nonorm", "rnn_token_gates", "rnn_token_gates_long",
                                   "rnn_token_gates_f32", "mlp_token_gates", "rnn_rows_40", "rnn_width_96",
-                                  "postact_f32_none"])
+                                  "postact_f32_none", "gated_small", "gated_f32", "gated_long", "gated_width_72",
+                                  "gated_aligned"])
 def test_backward_end_to_end(B, name):
     """Own forward on each side, then Highway-BP at every k of the case, exact BP
     and the parameter gradients."""
@@ -175,6 +188,19 @@ def test_backward_end_to_end(B, name):
     inp, st, sv, p = _setup(B, w)
     B.hbp_forward(p)
     _check_backward(B, w, p, st, sv, inp, name)
+
+
+@pytest.mark.parametrize("name", ["gated_small", "gated_f32", "gated_width_72", "gated_aligned"])
+def test_forward_of_the_gated_cell(B, name):
+    """States, both gates ([u | c] side by side) and the residual coefficient 1 - u that the forward writes."""
+    w = CASES[name]
+    inp, st, sv, p = _setup(B, w)
+    B.hbp_forward(p)
+    torch.cuda.synchronize()
+    tol = H.TOL[w.dtype]
+    assert H.rel(H.to_np(p.x), sv["x"]) < tol
+    assert H.rel(H.to_np(p.z), np.concatenate([sv["u"], sv["c"]], axis=-1)) < tol
+    assert H.rel(H.to_np(p.lam), sv["a"]) < tol
 
 
 @pytest.mark.parametrize("name", ["postact_rms", "postact_wide", "postact_f32_none", "postact_f32_deep"])
@@ -198,7 +224,7 @@ def test_forward_with_relu_after_the_sum(B, name):
 
 @pytest.mark.parametrize("name", ["mlp_f32_ragged", "resnet_like_small", "rnn_small", "rnn_chaotic_small",
                                   "postact_rms", "postact_wide", "postact_aligned", "postact_f32_none",
-                                  "postact_f32_deep"])
+                                  "postact_f32_deep", "gated_small", "gated_long"])
 def test_backward_shared_state(B, name):
     """Both backward passes read the same (storage-rounded) forward state."""
     w = CASES[name]
@@ -216,7 +242,8 @@ def test_backward_shared_state(B, name):
                                         ("resnet_like_small", 0.2), ("resnet_like_small", 1.0),
                                         ("deep_small", 0.5), ("rnn_small", 0.3), ("rnn_f32", 1.0), ("rnn_long", 0.2), ("rnn_long", 1.0),
                                         ("aligned_small", 0.8), ("rnn_token_gates", 0.4),
-                                        ("rnn_token_gates_long", 1.0), ("mlp_token_gates", 0.3)])
+                                        ("rnn_token_gates_long", 1.0), ("mlp_token_gates", 0.3),
+                                        ("gated_small", 0.3), ("gated_long", 1.0), ("gated_f32", 0.6)])
 def test_gamma_iterates(B, name, gamma):
     """The iteration on the re-split pair (J + gamma K, (1 - gamma) K): every k of
     the case against the oracle on a shared forward state; gamma = 1 is the

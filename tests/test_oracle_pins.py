@@ -693,6 +693,7 @@ def test_gated_cell_by_path_enumeration(gamma):
             hm[i] -= 1e-6
             J[:, i] = (via_g(hp) - via_g(hm)) / 2e-6
         return J
+    np.testing.assert_array_equal(sv["a"], 1 - sv["u"])
     Kd = [np.diag(1 - sv["u"][l][0]) for l in range(L)]
     Js = [jac(l) + gamma * Kd[l] for l in range(L)]
     Ks = [(1 - gamma) * Kd[l] for l in range(L)]
