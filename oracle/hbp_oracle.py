@@ -20,6 +20,11 @@ and erf are the only library steps; no blocking, fusion or reordering):
              with g = [a, b] and r(x, z) = z1 (.) x + z2, for the cell  u = sigmoid(W_u x + U_u xin),
              c = tanh(W_c x + U_c xin),  a = 1 - u,  b = u (.) c  (a GRU without its reset gate):
              K = dr/dx = diag(a), a function of the state, and J = diag(x) . da/dx + db/dx.
+             kind = 'lstm' is the LSTM row: the state is x = [c | h] (cell and hidden part),
+             f(x) = [a(x) (.) c + b(x), c3(x)] and r(x, z) = [z1 (.) c + z2, z3], for the standard cell
+             i, f, o = sigmoid(.), gg = tanh(.) of W h + U xin,  c' = f (.) c + i (.) gg,  h' = o (.) tanh(c'):
+             a = f, b = i (.) gg, c3 = o (.) tanh(f (.) c + i (.) gg).  K = dr/dx = diag([f | 0]): only the
+             cell part has a residual path; everything else, the dependence of h' on c included, is J.
   exact BP   Section "Backpropagation as a system of equations" and the first
              line of the proof of Theorem 1 (chain rule through J + K).
   Highway-BP Theorem 2 (w^0 and the recursion for w^{k+1}) in its two-step
@@ -59,7 +64,9 @@ F64 = np.float64
 class Stack:
     """A residual stack.
 
-    kind   'gated' one recurrent cell shared by all L (= T) steps, state width H:
+    kind   'lstm'  one LSTM cell shared by all L (= T) steps, state [c | h] of width 2H:
+                  W1 = [W_i; W_f; W_o; W_g] [4H,H] (acts on h), U likewise [4H,d_in], no W2, no lam
+           'gated' one recurrent cell shared by all L (= T) steps, state width H:
                   W1 = [W_u; W_c] [2H,H], U = [U_u; U_c] [2H,d_in], no W2, no lam
                   (the coefficient of the residual path is the cell's own 1 - u)
            'mlp'  per-block weights W1[L,d_ff,d], W2[L,d,d_ff]
@@ -88,13 +95,14 @@ class Stack:
 
     def __post_init__(self):
         assert self.post in ("none", "relu")
-        assert self.kind in ("mlp", "rnn", "gated")
+        assert self.kind in ("mlp", "rnn", "gated", "lstm")
         assert self.act in ("gelu", "tanh", "identity")
         assert self.norm in ("none", "rms")
         self.W1 = np.asarray(self.W1, dtype=F64)
-        if self.kind == "gated":
+        if self.kind in ("gated", "lstm"):
             assert self.W2 is None and self.lam is None and self.norm == "none" and self.post == "none"
-            assert self.W1.ndim == 2 and self.W1.shape[0] == 2 * self.W1.shape[1] and self.L > 0
+            assert self.W1.ndim == 2 and self.L > 0
+            assert self.W1.shape[0] == (2 if self.kind == "gated" else 4) * self.W1.shape[1]
             self.U = np.asarray(self.U, dtype=F64)
             return
         self.W2 = np.asarray(self.W2, dtype=F64)
@@ -111,7 +119,11 @@ class Stack:
 
     @property
     def d(self) -> int:
-        return self.W1.shape[-1] if self.kind == "gated" else self.W2.shape[-2]
+        if self.kind == "gated":
+            return self.W1.shape[-1]
+        if self.kind == "lstm":
+            return 2 * self.W1.shape[-1]
+        return self.W2.shape[-2]
 
     @property
     def d_ff(self) -> int:
@@ -165,6 +177,8 @@ def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict
     N, d = x0.shape
     if st.kind == "gated":
         return _forward_gated(st, x0, xin)
+    if st.kind == "lstm":
+        return _forward_lstm(st, x0, xin)
     L, dff = st.L, st.d_ff
     x = np.zeros((L + 1, N, d), F64)
     y = np.zeros((L, N, d), F64)
@@ -210,10 +224,38 @@ def _forward_gated(st: Stack, x0: np.ndarray, xin: np.ndarray) -> Dict[str, np.n
             "mask": np.ones((L, N, H), F64)}
 
 
+def _sigmoid(a: np.ndarray) -> np.ndarray:
+    return 1.0 / (1.0 + np.exp(-a))
+
+
+def _forward_lstm(st: Stack, x0: np.ndarray, xin: np.ndarray) -> Dict[str, np.ndarray]:
+    """x = [c | h];  [i, f, o, gg] = [sigmoid, sigmoid, sigmoid, tanh](W h + U xin);  c' = f (.) c + i (.) gg;
+    h' = o (.) tanh(c').  Saved: x [L+1,N,2H], gates = [i | f | o | gg] [L,N,4H], a = [f | 0] [L,N,2H] (the
+    diagonal of dr/dx: the hidden part has no residual path)."""
+    N, d = x0.shape
+    H = d // 2
+    L = st.L
+    x = np.zeros((L + 1, N, d), F64)
+    gates = np.zeros((L, N, 4 * H), F64)
+    a = np.zeros((L, N, d), F64)
+    x[0] = x0
+    for l in range(L):
+        c, h = x[l][:, :H], x[l][:, H:]
+        pre = h @ st.W1.T + np.asarray(xin[l], dtype=F64) @ st.U.T
+        i, f, o = _sigmoid(pre[:, :H]), _sigmoid(pre[:, H:2 * H]), _sigmoid(pre[:, 2 * H:3 * H])
+        gg = np.tanh(pre[:, 3 * H:])
+        cn = f * c + i * gg
+        x[l + 1] = np.concatenate([cn, o * np.tanh(cn)], axis=1)
+        gates[l] = np.concatenate([i, f, o, gg], axis=1)
+        a[l, :, :H] = f
+    return {"x": x, "y": x[:-1], "rinv": np.ones((L, N), F64), "gates": gates, "a": a,
+            "mask": np.ones((L, N, d), F64)}
+
+
 def k_diag(st: Stack, l: int, saved: Dict[str, np.ndarray]) -> np.ndarray:
     """Diagonal of dr/dx for the layer that carries state l+1 to state l, before any mask: lam_l, or for the
     gated cell its own coefficient a_l = 1 - u_l (per token)."""
-    if st.kind == "gated":
+    if st.kind in ("gated", "lstm"):
         return saved["a"][l]
     return st.lam_row(l)
 
@@ -228,11 +270,29 @@ def block_preact_grad(st: Stack, l: int, saved: Dict[str, np.ndarray], g_next: n
     if st.kind == "gated":
         u, c, x = saved["u"][l], saved["c"][l], saved["x"][l]
         return np.concatenate([g_next * (c - x) * u * (1.0 - u), g_next * u * (1.0 - c * c)], axis=1)
+    if st.kind == "lstm":
+        # g = [Gc | Gh] at the next state.  Everything that reaches c' : Gc and, through h' = o tanh(c'), Gh.
+        H = st.d // 2
+        Gc, Gh = g_next[:, :H], g_next[:, H:]
+        i, f, o, gg = (saved["gates"][l][:, j * H:(j + 1) * H] for j in range(4))
+        c = saved["x"][l][:, :H]
+        tc = np.tanh(saved["x"][l + 1][:, :H])
+        dct = Gc + Gh * o * (1.0 - tc * tc)
+        return np.concatenate([dct * gg * i * (1.0 - i), dct * c * f * (1.0 - f), Gh * tc * o * (1.0 - o),
+                               dct * i * (1.0 - gg * gg)], axis=1)
     return (g_next @ st.w2(l)) * saved["dphi"][l]
 
 
 def block_vjp(st: Stack, l: int, saved: Dict[str, np.ndarray], g_next: np.ndarray) -> np.ndarray:
     da = block_preact_grad(st, l, saved, g_next)
+    if st.kind == "lstm":
+        # J only: into h through the gates' weights; into c the part of d c'/d c = f that carries Gh (the part that
+        # carries Gc is K)
+        H = st.d // 2
+        Gh = g_next[:, H:]
+        f, o = saved["gates"][l][:, H:2 * H], saved["gates"][l][:, 2 * H:3 * H]
+        tc = np.tanh(saved["x"][l + 1][:, :H])
+        return np.concatenate([Gh * o * (1.0 - tc * tc) * f, da @ st.W1], axis=1)
     dn = da @ st.w1(l)
     if st.norm == "rms":
         # y = x / r, r = sqrt(mean(x^2) + eps):  dx = (dn - y * mean(dn (.) y)) / r
@@ -350,12 +410,13 @@ def param_grads(st: Stack, saved: Dict[str, np.ndarray], g: np.ndarray,
             dW2[l] = g[l + 1].T @ saved["z"][l]
             dW1[l] = da.T @ saved["y"][l]
         return {"dW1": dW1, "dW2": dW2}
-    if st.kind == "gated":
+    if st.kind in ("gated", "lstm"):
         dW1 = np.zeros_like(st.W1)
         dU = np.zeros_like(st.U)
+        H = st.W1.shape[1]
         for l in range(L):
             da = block_preact_grad(st, l, saved, g[l + 1])
-            dW1 += da.T @ saved["x"][l]
+            dW1 += da.T @ (saved["x"][l] if st.kind == "gated" else saved["x"][l][:, H:])
             dU += da.T @ np.asarray(xin[l], dtype=F64)
         return {"dW1": dW1, "dU": dU}
     dW1 = np.zeros_like(st.W1)

@@ -732,3 +732,114 @@ def test_gated_cell_k0_and_finite_termination():
         for i in range(st.L + 1):
             if k >= st.L - i:
                 np.testing.assert_allclose(w[i], G[i], rtol=1e-11, atol=1e-13)
+
+
+# ---------------------------------------------------------------- P14: the LSTM cell (LSTM row of the table)
+def small_lstm(T=5, H=4, I=3, seed=0):
+    r = np.random.default_rng(seed)
+    W = r.standard_normal((4 * H, H)) / math.sqrt(H)
+    U = r.standard_normal((4 * H, I)) / math.sqrt(I)
+    return O.Stack("lstm", "tanh", "none", W, None, U=U, L=T)
+
+
+def test_lstm_cell_against_torch_autograd():
+    """State [c | h], c' = f c + i g, h' = o tanh(c'): states, every state gradient (both parts) and the gradients
+    of both weight matrices against torch's autograd of the same recurrence in fp64."""
+    r = np.random.default_rng(51)
+    N, I = 3, 4
+    st = small_lstm(T=6, H=5, I=I)
+    H_ = st.d // 2
+    xin = r.standard_normal((st.L, N, I))
+    x0 = r.standard_normal((N, st.d)) * 0.5
+    c = r.standard_normal((st.L + 1, N, st.d))
+    sv = O.forward(st, x0, xin)
+    G = O.exact_backward(st, sv, c)
+    pg = O.param_grads(st, sv, G, xin)
+
+    t = lambda a: torch.tensor(a, dtype=torch.float64, requires_grad=True)
+    W, U = t(st.W1), t(st.U)
+    xs = [t(x0)]
+    for l in range(st.L):
+        x = xs[-1]
+        cc, h = x[:, :H_], x[:, H_:]
+        pre = h @ W.T + torch.tensor(xin[l]) @ U.T
+        i, f, o = (torch.sigmoid(pre[:, j * H_:(j + 1) * H_]) for j in range(3))
+        g = torch.tanh(pre[:, 3 * H_:])
+        cn = f * cc + i * g
+        nxt = torch.cat([cn, o * torch.tanh(cn)], dim=1)
+        nxt.retain_grad()
+        xs.append(nxt)
+    loss = sum((torch.tensor(c[l]) * xs[l]).sum() for l in range(st.L + 1))
+    loss.backward()
+    for l in range(st.L + 1):
+        np.testing.assert_allclose(sv["x"][l], xs[l].detach().numpy(), rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(G[l], xs[l].grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(pg["dW1"], W.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(pg["dU"], U.grad.numpy(), rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("gamma", [0.0, 0.5])
+def test_lstm_cell_by_path_enumeration(gamma):
+    """Theorem 2 with K_l = diag([f_l | 0]) and J_l = (Jacobian of the whole step) - K_l, the step's Jacobian by
+    central differences of the cell's forward map on [c | h]."""
+    st = small_lstm(T=4, H=2, I=2, seed=7)
+    r = np.random.default_rng(12)
+    xin = r.standard_normal((st.L, 1, 2))
+    sv = O.forward(st, r.standard_normal((1, st.d)) * 0.5, xin)
+    e = r.standard_normal((st.L + 1, 1, st.d))
+    L, d = st.L, st.d
+    H_ = d // 2
+
+    def step(x, l):
+        cc, h = x[:H_], x[H_:]
+        pre = st.W1 @ h + st.U @ xin[l][0]
+        sg = lambda a: 1 / (1 + np.exp(-a))
+        i, f, o, g = sg(pre[:H_]), sg(pre[H_:2 * H_]), sg(pre[2 * H_:3 * H_]), np.tanh(pre[3 * H_:])
+        cn = f * cc + i * g
+        return np.concatenate([cn, o * np.tanh(cn)])
+    Kd, Js = [], []
+    for l in range(L):
+        x = sv["x"][l][0]
+        F = np.zeros((d, d))
+        for i in range(d):
+            xp, xm = x.copy(), x.copy()
+            xp[i] += 1e-6
+            xm[i] -= 1e-6
+            F[:, i] = (step(xp, l) - step(xm, l)) / 2e-6
+        K = np.diag(np.concatenate([sv["gates"][l][0][H_:2 * H_], np.zeros(H_)]))
+        Kd.append(K)
+        Js.append(F - K)
+    np.testing.assert_array_equal(sv["a"][:, 0], np.stack([np.diag(K) for K in Kd]))
+    Jg = [Js[l] + gamma * Kd[l] for l in range(L)]
+    Kg = [(1 - gamma) * Kd[l] for l in range(L)]
+    for k in range(L + 1):
+        w = O.hbp_backward(st, sv, e, k, gamma=gamma)
+        for i in range(L + 1):
+            acc = np.zeros(d)
+            for j in range(i, L + 1):
+                layers = list(range(i, j))
+                for size in range(min(k, len(layers)) + 1):
+                    for chosen in itertools.combinations(layers, size):
+                        vec = e[j][0].copy()
+                        for l in reversed(layers):
+                            vec = vec @ (Jg[l] if l in chosen else Kg[l])
+                        acc += vec
+            np.testing.assert_allclose(w[i][0], acc, rtol=2e-6, atol=2e-8)
+    np.testing.assert_allclose(O.hbp_backward(st, sv, e, L, gamma=gamma), O.exact_backward(st, sv, e),
+                               rtol=1e-10, atol=1e-12)
+
+
+def test_lstm_cell_k0_follows_the_forget_gates_only():
+    """w^0: the cell part of e_T travels down through the products of the forget gates, the hidden part not at all."""
+    st = small_lstm(T=5, H=3, I=2, seed=9)
+    r = np.random.default_rng(3)
+    xin = r.standard_normal((st.L, 2, 2))
+    sv = O.forward(st, np.zeros((2, st.d)), xin)
+    e = r.standard_normal((2, st.d))
+    H_ = st.d // 2
+    w0 = O.hbp_backward(st, sv, e, 0)
+    prod = np.ones((2, H_))
+    for l in range(st.L - 1, -1, -1):
+        prod = prod * sv["gates"][l][:, H_:2 * H_]
+        np.testing.assert_allclose(w0[l][:, :H_], e[:, :H_] * prod, rtol=1e-12)
+        np.testing.assert_array_equal(w0[l][:, H_:], 0.0)
