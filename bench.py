@@ -53,16 +53,20 @@ def algorithmic_work(w, k):
     blocks = sum(L - it + 1 for it in range(1, iters + 1))
     vjp1 = per_block * (blocks + L)        # + the one in hbp_param_grads
     vjp2 = per_block * blocks
-    rec = w.kind in ("rnn", "gated")
+    rec = w.kind in ("rnn", "gated", "lstm")
     dw = 2.0 * per_block * L + (2.0 * N * L * dff * w.d_in if rec else 0.0)
-    if w.kind == "gated":                  # no second weight: one parameter contraction less, and the first
-        dw -= per_block * L                # half of step (i) is elementwise (counted in bytes below)
+    cellk = w.kind in ("gated", "lstm")
+    hw = d // 2 if w.kind == "lstm" else d             # width the cell's weights act on
+    if cellk:                              # no second weight: one parameter contraction (over the hidden part), and
+        per_block = 2.0 * N * hw * dff     # the first half of step (i) is elementwise (counted in bytes below)
+        dw = per_block * L + 2.0 * N * L * dff * w.d_in
         vjp1 = 0.0
+        vjp2 = per_block * blocks
     S = float(L) * N * d
     # per iteration the scan reads dn (+ y with a norm; + e only when a norm sits between
     # the block and the residual path: otherwise e was added by the second contraction)
     e_in_scan = w.loss_every_state and w.norm == "rms"
-    lam_tok = 1 if w.lam == "sigmoid_full" else 0      # coefficients per token: one more stream
+    lam_tok = 1 if (w.lam == "sigmoid_full" or w.kind in ("gated", "lstm")) else 0   # coefficients per token: one more stream
     streams_in = 1 + (1 if w.norm == "rms" else 0) + (1 if e_in_scan else 0) + lam_tok
     mask = S / 8.0 if w.post == "relu" else 0.0       # one bit per element per scan
     scan_iter = S * s * (streams_in + 1) + mask
@@ -84,10 +88,16 @@ def algorithmic_work(w, k):
     if w.kind == "gated":                  # reads g, x, [u | c]; writes da [N, 2H]
         def b1(nb):
             return nb * float(N) * (2 * d + 2 * dff) * s
+    if w.kind == "lstm":                   # reads g, c, c', the gates (+ e's cell half); writes da [N, 4H] and v's cell half
+        def b1(nb):
+            return nb * float(N) * (d + 2 * hw + 2 * dff + hw + (hw if w.loss_every_state else 0)) * s
+
+        def b2(nb):
+            return nb * float(N) * (dff + hw + (hw if w.loss_every_state else 0)) * s + hw * dff * s
     vjp1_bytes = sum(b1(nb) for nb in per_it) + b1(L)
     vjp2_bytes = sum(b2(nb) for nb in per_it)
-    dw_bytes = L * ((1.0 if w.kind == "gated" else 2.0) * N * (d + dff) * s) \
-        + (1 if shared else L) * (1.0 if w.kind == "gated" else 2.0) * d * dff * 4 \
+    dw_bytes = L * ((1.0 if cellk else 2.0) * N * (hw + dff) * s) \
+        + (1 if shared else L) * (1.0 if cellk else 2.0) * hw * dff * 4 \
         + ((L * N * (dff + w.d_in) * s + dff * w.d_in * 4.0) if shared else 0.0)
     return {"vjp1": vjp1, "vjp2": vjp2, "dw": dw, "scan_bytes": scan_init + iters * scan_iter,
             "scan_launches": 1 + iters, "vjp1_bytes": vjp1_bytes, "vjp2_bytes": vjp2_bytes, "dw_bytes": dw_bytes}
@@ -154,8 +164,8 @@ def cpu_baseline(w, k, budget_tokens):
         threads = os.cpu_count() or 1
     n = min(budget_tokens, w.N)
     inp = synth.make_inputs(w, tokens=slice(0, n))
-    if w.kind == "gated":
-        st = O.Stack("gated", w.act, w.norm, inp["W1"], None, U=inp["U"], L=w.L)
+    if w.kind in ("gated", "lstm"):
+        st = O.Stack(w.kind, w.act, w.norm, inp["W1"], None, U=inp["U"], L=w.L)
     else:
         st = O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], U=inp["U"], eps=w.eps, L=w.L,
                      post=w.post)
@@ -164,7 +174,7 @@ def cpu_baseline(w, k, budget_tokens):
     g = O.hbp_backward(st, sv, inp["e"], k)
     O.param_grads(st, sv, g, inp["xin"])
     dt = time.perf_counter() - t0
-    toks = n * (w.L if w.kind in ("rnn", "gated") else 1)
+    toks = n * (w.L if w.kind in ("rnn", "gated", "lstm") else 1)
     return {"value": toks / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
             "sample": f"{n} of {w.N} token rows at full L={w.L}, d={w.d}, d_ff={w.d_ff}; "
                       f"hbp_backward(k={k}) + param_grads in {dt:.1f} s (forward untimed)"}
@@ -254,7 +264,7 @@ def main():
                 "avg_launch_ms": ms[cls] / max(launches[cls], 1)}
 
     roofs = {c: mfma_roof(c) for c in ("vjp1", "vjp2", "dw")}
-    if w.kind == "gated":                  # step (i)'s first half is elementwise there: memory roofline
+    if w.kind in ("gated", "lstm"):        # step (i)'s first half is elementwise there: memory roofline
         t1 = ms["vjp1"] * 1e-3
         a1 = work["vjp1_bytes"] / t1 / 1e9 if t1 > 0 else 0.0
         roofs["vjp1"] = {"bound": "hbm", "achieved": a1, "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -319,7 +329,8 @@ def main():
         # the initial estimate w^0 by each form of the scan (the paper's Algorithm 1 among them)
         abl = {}
         S_bytes = float(w.L) * w.N * w.d * storage_bytes(w)
-        alg_bytes = S_bytes * (1 + (1 if w.loss_every_state else 0) + (1 if w.lam == "sigmoid_full" else 0))
+        alg_bytes = S_bytes * (1 + (1 if w.loss_every_state else 0)
+                               + (1 if (w.lam == "sigmoid_full" or w.kind in ("gated", "lstm")) else 0))
         for algo in ("auto", "sequential") + (("chunked", "hillis_steele") if w.post == "none" else ()):
             need = B.scan_workspace_size(p.desc, algo)
             if need > 8 << 30:
@@ -334,7 +345,7 @@ def main():
         # about 10-20 s of oracle work on the GPU machine's host cores
         n = args.cpu_tokens or {"mlp_small_f32": 128, "resnet_like": 8192, "resnet_postact": 8192, "transformer_mlp": 2048,
                                 "deep_large": 256, "gated_rnn": 16, "gated_rnn_contractive": 16,
-                                "gated_rnn_token_gates": 16, "gru_cell": 16}.get(w.name, 64)
+                                "gated_rnn_token_gates": 16, "gru_cell": 16, "lstm_cell": 8}.get(w.name, 64)
         out["cpu_baseline"] = cpu_baseline(w, k, n)
 
     def finite(o):   # JSON has no NaN/Infinity: overflowed error figures become null

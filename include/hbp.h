@@ -60,7 +60,13 @@ typedef enum { HBP_F32 = 0, HBP_BF16 = 1 } hbp_dtype;
  * Shapes: d = H, d_ff = 2H, W1 = [W_u; W_c] [2H,H], U = [U_u; U_c] [2H,d_in]; W2, dW2, dphi, y, rinv unused.
  * z holds [u | c] as [L,N,2H].  lambda_kind must be HBP_LAMBDA_TOKEN: hbp_forward WRITES lambda = 1 - u there
  * ([L,N,H], storage type) and the backward calls read it.  act = HBP_ACT_TANH, norm = HBP_NORM_NONE. */
-typedef enum { HBP_MLP = 0, HBP_RNN = 1, HBP_GATED = 2 } hbp_kind;
+/* HBP_LSTM: the LSTM row of the same table.  The state is x = [c | h] (cell and hidden part, d = 2H); with
+ * [i, f, o, gg] = [sigmoid, sigmoid, sigmoid, tanh](W h + U xin): c' = f (.) c + i (.) gg, h' = o (.) tanh(c').
+ * K = diag([f | 0]): only the cell part has a residual path; everything else, h' depending on c included, is J.
+ * Shapes: d = 2H, d_ff = 4H, W1 = [W_i; W_f; W_o; W_g] [4H,H] (acts on h), U likewise [4H,d_in]; z holds the
+ * gates [i | f | o | gg] as [L,N,4H]; lambda ([L,N,2H], HBP_LAMBDA_TOKEN) is WRITTEN by hbp_forward as [f | 0].
+ * dW1 is [4H,H].  Other rules as for HBP_GATED. */
+typedef enum { HBP_MLP = 0, HBP_RNN = 1, HBP_GATED = 2, HBP_LSTM = 3 } hbp_kind;
 /* GELU is the exact erf form a*Phi(a); IDENTITY makes blocks linear (tests). */
 typedef enum { HBP_ACT_GELU_ERF = 0, HBP_ACT_TANH = 1, HBP_ACT_IDENTITY = 2 } hbp_act;
 /* RMS: y = x / sqrt(mean_c(x^2) + eps), no gain. */
@@ -106,7 +112,7 @@ typedef struct {
   const void* W2;
   const void* U;
   const void* lambda;        /* CHANNEL: fp32 [L,d]; TOKEN: S [L,N,d].  Row (block) l carries state l+1 to state l.
-                              * (HBP_GATED: written by hbp_forward through this pointer.) */
+                              * (HBP_GATED, HBP_LSTM: written by hbp_forward through this pointer.) */
   /* forward state: written by hbp_forward, read by the backward calls. */
   void* x;                   /* S [L+1,N,d]  states x_0..x_L (x[0] is the input) */
   void* y;                   /* S [L,N,d]    norm(x_l); unused (may be NULL) with HBP_NORM_NONE, where x is read */

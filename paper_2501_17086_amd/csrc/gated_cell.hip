@@ -1,4 +1,4 @@
-// Elementwise kernels of the gated recurrent cell (the GRU row of the paper's table of layer
+// Elementwise kernels of the recurrent cells whose residual coefficient is a gate.  First the gated recurrent cell (the GRU row of the paper's table of layer
 // decompositions: f(x) = a(x) (.) x + b(x), r(x, z) = z1 (.) x + z2) for
 //   u = sigmoid(W_u x + U_u xin),  c = tanh(W_c x + U_c xin),  a = 1 - u,  b = u (.) c.
 // The two products with the weights are contractions (GEMM kernels); what is left of the cell is
@@ -60,7 +60,121 @@ __global__ __launch_bounds__(256) void gated_vjp_kernel(const T* __restrict__ g,
   store8(da + n * 2 * H + H + j, dc);
 }
 
+// ---------------------------------------------------------------------------
+// LSTM (the LSTM row of the same table): state x = [c | h] of width 2H, gates [i | f | o | gg] of width 4H from
+// W h + U xin;  c' = f c + i gg,  h' = o tanh(c').  K = diag([f | 0]).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float sigmoidf_(float a) { return 1.f / (1.f + expf(-a)); }
+
+// One step forward: pre [N,4H] fp32; writes gates [N,4H], a [N,2H] = [f | 0], xn [N,2H] = [c' | h'].
+template <typename T>
+__global__ __launch_bounds__(256) void lstm_fwd_kernel(const float* __restrict__ pre, const T* __restrict__ x,
+                                                       T* __restrict__ gates, T* __restrict__ a, T* __restrict__ xn,
+                                                       long N, long H) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long per_row = H / 8;
+  if (idx >= N * per_row) return;
+  const long n = idx / per_row, j = (idx % per_row) * 8;
+  float pi[8], pf[8], po[8], pg[8], c[8], i[8], f[8], o[8], gg[8], cn[8], hn[8], zero[8];
+  load8(pre + n * 4 * H + j, pi);
+  load8(pre + n * 4 * H + H + j, pf);
+  load8(pre + n * 4 * H + 2 * H + j, po);
+  load8(pre + n * 4 * H + 3 * H + j, pg);
+  load8(x + n * 2 * H + j, c);
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    i[q] = sigmoidf_(pi[q]);
+    f[q] = sigmoidf_(pf[q]);
+    o[q] = sigmoidf_(po[q]);
+    gg[q] = tanhf(pg[q]);
+    cn[q] = fmaf(f[q], c[q], i[q] * gg[q]);
+    hn[q] = o[q] * tanhf(cn[q]);
+    zero[q] = 0.f;
+  }
+  store8(gates + n * 4 * H + j, i);
+  store8(gates + n * 4 * H + H + j, f);
+  store8(gates + n * 4 * H + 2 * H + j, o);
+  store8(gates + n * 4 * H + 3 * H + j, gg);
+  store8(a + n * 2 * H + j, f);
+  store8(a + n * 2 * H + H + j, zero);
+  store8(xn + n * 2 * H + j, cn);
+  store8(xn + n * 2 * H + H + j, hn);
+}
+
+// Step (i) up to its contraction for `rows` token rows of consecutive blocks.  g = [Gc | Gh] is the gradient of each
+// row's NEXT state, x its current state (cell part read), xn its next state (c' read: tanh(c') is recomputed).
+//   dct = Gc + Gh o (1 - tanh^2 c')          everything that reaches c'
+//   da  = [dct gg i(1-i) | dct c f(1-f) | Gh tanh(c') o(1-o) | dct i (1-gg^2)]
+//   vc  = Gh o (1 - tanh^2 c') f (+ e_c)     J's part of d c'/d c (the part that carries Gc is K); cell half of v
+template <typename T>
+__global__ __launch_bounds__(256) void lstm_vjp_kernel(const T* __restrict__ g, const T* __restrict__ x,
+                                                       const T* __restrict__ xn, const T* __restrict__ gates,
+                                                       const T* __restrict__ e, T* __restrict__ da,
+                                                       T* __restrict__ v, long rows, long H) {
+  const long idx = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long per_row = H / 8;
+  if (idx >= rows * per_row) return;
+  const long n = idx / per_row, j = (idx % per_row) * 8;
+  float Gc[8], Gh[8], c[8], cn[8], i[8], f[8], o[8], gg[8], di[8], df[8], dO[8], dg[8], vc[8];
+  load8(g + n * 2 * H + j, Gc);
+  load8(g + n * 2 * H + H + j, Gh);
+  load8(x + n * 2 * H + j, c);
+  load8(xn + n * 2 * H + j, cn);
+  load8(gates + n * 4 * H + j, i);
+  load8(gates + n * 4 * H + H + j, f);
+  load8(gates + n * 4 * H + 2 * H + j, o);
+  load8(gates + n * 4 * H + 3 * H + j, gg);
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const float tc = tanhf(cn[q]);
+    const float through_h = Gh[q] * o[q] * (1.f - tc * tc);
+    const float dct = Gc[q] + through_h;
+    di[q] = dct * gg[q] * i[q] * (1.f - i[q]);
+    df[q] = dct * c[q] * f[q] * (1.f - f[q]);
+    dO[q] = Gh[q] * tc * o[q] * (1.f - o[q]);
+    dg[q] = dct * i[q] * (1.f - gg[q] * gg[q]);
+    vc[q] = through_h * f[q];
+  }
+  if (e) {
+    float ec[8];
+    load8(e + n * 2 * H + j, ec);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) vc[q] += ec[q];
+  }
+  store8(da + n * 4 * H + j, di);
+  store8(da + n * 4 * H + H + j, df);
+  store8(da + n * 4 * H + 2 * H + j, dO);
+  store8(da + n * 4 * H + 3 * H + j, dg);
+  store8(v + n * 2 * H + j, vc);
+}
+
 }  // namespace
+
+hipError_t launch_lstm_fwd(int dtype, const float* pre, const void* x, void* gates, void* a, void* xn, long N, long H,
+                           hipStream_t s) {
+  const long n = N * (H / 8);
+  dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  if (dtype == 0)
+    hipLaunchKernelGGL(lstm_fwd_kernel<float>, grid, block, 0, s, pre, (const float*)x, (float*)gates, (float*)a,
+                       (float*)xn, N, H);
+  else
+    hipLaunchKernelGGL(lstm_fwd_kernel<bf16_t>, grid, block, 0, s, pre, (const bf16_t*)x, (bf16_t*)gates, (bf16_t*)a,
+                       (bf16_t*)xn, N, H);
+  return hipGetLastError();
+}
+
+hipError_t launch_lstm_vjp(int dtype, const void* g, const void* x, const void* xn, const void* gates, const void* e,
+                           void* da, void* v, long rows, long H, hipStream_t s) {
+  const long n = rows * (H / 8);
+  dim3 grid((unsigned)((n + 255) / 256)), block(256);
+  if (dtype == 0)
+    hipLaunchKernelGGL(lstm_vjp_kernel<float>, grid, block, 0, s, (const float*)g, (const float*)x, (const float*)xn,
+                       (const float*)gates, (const float*)e, (float*)da, (float*)v, rows, H);
+  else
+    hipLaunchKernelGGL(lstm_vjp_kernel<bf16_t>, grid, block, 0, s, (const bf16_t*)g, (const bf16_t*)x,
+                       (const bf16_t*)xn, (const bf16_t*)gates, (const bf16_t*)e, (bf16_t*)da, (bf16_t*)v, rows, H);
+  return hipGetLastError();
+}
 
 hipError_t launch_gated_fwd(int dtype, const float* pre, const void* x, void* uc, void* a, void* xn, long N, long H,
                             hipStream_t s) {

@@ -14,7 +14,11 @@ namespace {
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline size_t esize(const hbp_desc* d) { return d->dtype == HBP_F32 ? 4 : 2; }
-inline bool recurrent(const hbp_desc* d) { return d->kind == HBP_RNN || d->kind == HBP_GATED; }
+inline bool cell(const hbp_desc* d) { return d->kind == HBP_GATED || d->kind == HBP_LSTM; }
+inline bool recurrent(const hbp_desc* d) { return d->kind == HBP_RNN || cell(d); }
+// A cell's weights act on the hidden part of the state: all of it (GATED), or the second half of [c | h] (LSTM).
+inline long hidden_w(const hbp_desc* d) { return d->kind == HBP_LSTM ? d->d / 2 : d->d; }
+inline long hidden_off(const hbp_desc* d) { return d->kind == HBP_LSTM ? d->d / 2 : 0; }
 inline bool shared_w(const hbp_desc* d) { return recurrent(d); }
 
 struct Workspace {
@@ -71,20 +75,21 @@ Workspace carve(const hbp_desc* d) {
   if (recurrent(d) && d->dtype == HBP_BF16) o = align_up(o + 2 * (size_t)d->d * d->d_ff * es, 256);
   // one step's pre-activations of the gated cell, fp32 [N, 2H]
   w.off_pre = o;
-  if (d->kind == HBP_GATED) o = align_up(o + (size_t)d->N * d->d_ff * 4, 256);
+  if (cell(d)) o = align_up(o + (size_t)d->N * d->d_ff * 4, 256);
   w.total = o;
   return w;
 }
 
 // One step of the recurrence at a time, few rows: the few-row kernel with transposed weights.
 inline bool step_skinny(const hbp_desc* d) {
-  return recurrent(d) && d->dtype == HBP_BF16 && skinny_ok(d->N, d->d_ff, d->d) && skinny_ok(d->N, d->d, d->d_ff);
+  return recurrent(d) && d->dtype == HBP_BF16 && skinny_ok(d->N, d->d_ff, hidden_w(d)) &&
+         skinny_ok(d->N, hidden_w(d), d->d_ff);
 }
 
 hbp_status check_desc(const hbp_desc* d) {
   if (!d) return HBP_E_NULL;
   if (d->struct_size != sizeof(hbp_desc)) return HBP_E_INVALID_ARG;
-  if (d->kind != HBP_MLP && d->kind != HBP_RNN && d->kind != HBP_GATED) return HBP_E_INVALID_ARG;
+  if (d->kind < HBP_MLP || d->kind > HBP_LSTM) return HBP_E_INVALID_ARG;
   if (d->dtype != HBP_F32 && d->dtype != HBP_BF16) return HBP_E_INVALID_ARG;
   if (d->act < HBP_ACT_GELU_ERF || d->act > HBP_ACT_IDENTITY) return HBP_E_INVALID_ARG;
   if (d->norm != HBP_NORM_NONE && d->norm != HBP_NORM_RMS) return HBP_E_INVALID_ARG;
@@ -92,9 +97,10 @@ hbp_status check_desc(const hbp_desc* d) {
   if (d->loss_every_state != 0 && d->loss_every_state != 1) return HBP_E_INVALID_ARG;
   if (d->L <= 0 || d->N <= 0 || d->d <= 0 || d->d_ff <= 0 || d->d_in < 0) return HBP_E_INVALID_ARG;
   if (recurrent(d) && d->d_in <= 0) return HBP_E_INVALID_ARG;
-  if (d->kind == HBP_GATED && (d->act != HBP_ACT_TANH || d->norm != HBP_NORM_NONE || d->lambda_kind != HBP_LAMBDA_TOKEN ||
-                               d->d_ff != 2 * d->d))
+  if (cell(d) && (d->act != HBP_ACT_TANH || d->norm != HBP_NORM_NONE || d->lambda_kind != HBP_LAMBDA_TOKEN ||
+                  d->d_ff != 2 * d->d))
     return HBP_E_INVALID_ARG;
+  if (d->kind == HBP_LSTM && d->d % 16) return HBP_E_UNSUPPORTED;   // both halves of [c | h] in 16-byte vectors
   if (d->kind == HBP_MLP && d->d_in != 0) return HBP_E_INVALID_ARG;
   if (d->norm == HBP_NORM_RMS && !(d->eps >= 0.f)) return HBP_E_INVALID_ARG;
   if (d->d % 8 || d->d_ff % 8 || d->d_in % 8) return HBP_E_UNSUPPORTED;
@@ -112,7 +118,7 @@ enum Need { NEED_FWD = 1, NEED_BWD = 2, NEED_PG = 4 };
 hbp_status check_bufs(const hbp_desc* d, const hbp_buffers* b, int need) {
   if (!b) return HBP_E_NULL;
   if (b->struct_size != sizeof(hbp_buffers)) return HBP_E_INVALID_ARG;
-  if (!b->W1 || (!b->W2 && d->kind != HBP_GATED)) return HBP_E_NULL;
+  if (!b->W1 || (!b->W2 && !cell(d))) return HBP_E_NULL;
   if (recurrent(d) && (need & (NEED_FWD | NEED_PG)) && (!b->U || !b->xin)) return HBP_E_NULL;
   if (d->lambda_kind != HBP_LAMBDA_ONE && !b->lambda) return HBP_E_NULL;
   if (d->norm == HBP_NORM_RMS && (!b->y || !b->rinv)) return HBP_E_NULL;
@@ -126,7 +132,7 @@ hbp_status check_bufs(const hbp_desc* d, const hbp_buffers* b, int need) {
   }
   if ((need & NEED_BWD) && !b->e) return HBP_E_NULL;
   if (need & NEED_PG) {
-    if (!b->dW1 || (!b->dW2 && d->kind != HBP_GATED)) return HBP_E_NULL;
+    if (!b->dW1 || (!b->dW2 && !cell(d))) return HBP_E_NULL;
     if (recurrent(d) && !b->dU) return HBP_E_NULL;
   }
   Workspace w = carve(d);
@@ -207,6 +213,17 @@ hbp_status vjp_stage1(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
                              at(b->workspace, w.off_da + (size_t)l_lo * d->N * d->d_ff * es), nl * d->N, d->d, s));
     return HBP_OK;
   }
+  if (d->kind == HBP_LSTM) {   // likewise; also writes the cell half of v (and adds e's cell half when the second
+    ProfScope ps(HBP_PROF_VJP1, s);   // contraction's epilogue adds the hidden half)
+    const size_t so = (size_t)l_lo * d->N * d->d * es;
+    HBP_TRY(launch_lstm_vjp(d->dtype, at(b->g, so + (size_t)d->N * d->d * es), at((const void*)b->x, so),
+                            at((const void*)b->x, so + (size_t)d->N * d->d * es),
+                            at((const void*)b->z, (size_t)l_lo * d->N * d->d_ff * es),
+                            e_in_vjp(d) ? at(b->e, so) : nullptr,
+                            at(b->workspace, w.off_da + (size_t)l_lo * d->N * d->d_ff * es),
+                            at(b->workspace, w.off_v + so), nl * d->N, d->d / 2, s));
+    return HBP_OK;
+  }
   if (skinny) {   // one step; W2^T [d_ff,d] sits first in the transposed-weight region
     SkinnyArgs k{};
     k.A = at(b->g, (size_t)(l_lo + 1) * d->N * d->d * es); k.lda = d->d;
@@ -254,14 +271,18 @@ hbp_status vjp_stage2(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
   const size_t es = esize(d);
   const long nl = l_hi - l_lo;
   const bool sh = shared_w(d);
-  if (skinny) {   // W1^T [d,d_ff] follows W2^T
+  // The product lands in the hidden part of v (all of it, except for the LSTM's [c | h]: there the cell half was
+  // written by the elementwise kernel and W1 is [d_ff, H]).
+  const long hw = hidden_w(d);
+  const size_t ho = (size_t)hidden_off(d) * es;
+  if (skinny) {   // W1^T [hw,d_ff] follows W2^T
     SkinnyArgs k{};
     k.A = at(b->workspace, w.off_da + (size_t)l_lo * d->N * d->d_ff * es); k.lda = d->d_ff;
     k.Bt = at(b->workspace, w.off_wt + (size_t)d->d * d->d_ff * es); k.ldbt = d->d_ff;
-    k.C = at(b->workspace, w.off_v + (size_t)l_lo * d->N * d->d * es); k.ldc = d->d;
-    k.M = d->N; k.N = d->d; k.K = d->d_ff;
+    k.C = at(b->workspace, w.off_v + (size_t)l_lo * d->N * d->d * es + ho); k.ldc = d->d;
+    k.M = d->N; k.N = hw; k.K = d->d_ff;
     k.mode = EPI_STORE;
-    if (e_in_vjp(d)) { k.mode = EPI_ADD_AUX; k.aux = at(b->e, (size_t)l_lo * d->N * d->d * es); k.ldaux = d->d; }
+    if (e_in_vjp(d)) { k.mode = EPI_ADD_AUX; k.aux = at(b->e, (size_t)l_lo * d->N * d->d * es + ho); k.ldaux = d->d; }
     if (fuse_scan) {   // g_l = v_l (+ e_l) + lambda_l (.) g_{l+1} written straight into g
       k.C = at(b->g, (size_t)l_lo * d->N * d->d * es);
       k.next = at(b->g, (size_t)(l_lo + 1) * d->N * d->d * es);
@@ -276,12 +297,12 @@ hbp_status vjp_stage2(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
   GemmArgs ga{};
   ga.A = at(b->workspace, w.off_da + (size_t)l_lo * d->N * d->d_ff * es);
   ga.B = sh ? b->W1 : at(b->W1, (size_t)l_lo * d->d * d->d_ff * es);
-  ga.C = at(b->workspace, w.off_v + (size_t)l_lo * d->N * d->d * es);
+  ga.C = at(b->workspace, w.off_v + (size_t)l_lo * d->N * d->d * es + ho);
   ga.M = sh ? nl * d->N : d->N;
-  ga.N = d->d;
+  ga.N = hw;
   ga.K = d->d_ff;
   ga.a_sm = d->d_ff; ga.a_sk = 1;
-  ga.b_sk = d->d; ga.b_sn = 1;
+  ga.b_sk = hw; ga.b_sn = 1;
   ga.ldc = d->d;
   ga.batch = sh ? 1 : nl;
   ga.a_sb = d->N * d->d_ff; ga.b_sb = d->d * d->d_ff; ga.c_sb = d->N * d->d;
@@ -289,7 +310,7 @@ hbp_status vjp_stage2(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
   ga.mode = EPI_STORE;
   if (e_in_vjp(d)) {   // v_l + e_l in the epilogue: the scan then reads one stream less
     ga.mode = EPI_ADD_AUX;
-    ga.aux = at(b->e, (size_t)l_lo * d->N * d->d * es);
+    ga.aux = at(b->e, (size_t)l_lo * d->N * d->d * es + ho);
     ga.aux_sb = d->N * d->d;
   }
   return run_gemm(d, ga, s, HBP_PROF_VJP2);
@@ -440,33 +461,40 @@ hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
                                  d->eps, s));
       yl = at((const void*)b->y, xo);
     }
-    if (d->kind == HBP_GATED) {
-      // pre = x W1^T + U xin (fp32), then the cell elementwise: z[l] = [u | c], lambda[l] = 1 - u, x[l+1]
+    if (cell(d)) {
+      // pre = h W1^T + U xin (fp32), then the cell elementwise: z[l] = the gates, lambda[l] = the residual
+      // coefficient, x[l+1]
       float* pre = reinterpret_cast<float*>(at(b->workspace, w.off_pre));
+      const long hw = hidden_w(d);
+      const void* hl = at(yl, (size_t)hidden_off(d) * es);
       if (skinny) {
         SkinnyArgs k{};
-        k.A = yl; k.lda = d->d;
-        k.Bt = b->W1; k.ldbt = d->d;
+        k.A = hl; k.lda = d->d;
+        k.Bt = b->W1; k.ldbt = hw;
         k.C = pre; k.ldc = d->d_ff; k.c_is_f32 = 1;
-        k.M = d->N; k.N = d->d_ff; k.K = d->d;
+        k.M = d->N; k.N = d->d_ff; k.K = hw;
         k.mode = EPI_STORE;
         k.addf = ux + l * d->N * d->d_ff;
         ProfScope ps(HBP_PROF_FORWARD, s);
         HBP_TRY(launch_gemm_skinny(k, s));
       } else {
         GemmArgs ga{};
-        ga.A = yl; ga.B = b->W1; ga.C = pre;
-        ga.M = d->N; ga.N = d->d_ff; ga.K = d->d;
+        ga.A = hl; ga.B = b->W1; ga.C = pre;
+        ga.M = d->N; ga.N = d->d_ff; ga.K = hw;
         ga.a_sm = d->d; ga.a_sk = 1;
-        ga.b_sk = 1; ga.b_sn = d->d;
+        ga.b_sk = 1; ga.b_sn = hw;
         ga.ldc = d->d_ff; ga.batch = 1; ga.split_k = 1;
         ga.mode = EPI_STORE; ga.c_is_f32 = 1;
         ga.addf = ux + l * d->N * d->d_ff;
         HBP_RUN(run_gemm(d, ga, s, HBP_PROF_FORWARD));
       }
       ProfScope ps(HBP_PROF_FORWARD, s);
-      HBP_TRY(launch_gated_fwd(d->dtype, pre, yl, at(b->z, fo), at(const_cast<void*>(b->lambda), xo),
-                               at(b->x, xo + (size_t)d->N * d->d * es), d->N, d->d, s));
+      if (d->kind == HBP_GATED)
+        HBP_TRY(launch_gated_fwd(d->dtype, pre, yl, at(b->z, fo), at(const_cast<void*>(b->lambda), xo),
+                                 at(b->x, xo + (size_t)d->N * d->d * es), d->N, d->d, s));
+      else
+        HBP_TRY(launch_lstm_fwd(d->dtype, pre, yl, at(b->z, fo), at(const_cast<void*>(b->lambda), xo),
+                                at(b->x, xo + (size_t)d->N * d->d * es), d->N, d->d / 2, s));
       continue;
     }
     if (skinny) {   // one step of the recurrence, few rows; the weights as stored are already K-contiguous
@@ -619,13 +647,14 @@ hbp_status hbp_exact_backward(const hbp_desc* d, hbp_buffers* b, void* stream) {
   if (d->norm == HBP_NORM_NONE) bb.y = bb.x;
   HBP_RUN(seed_top(d, &bb, s));
   const bool skinny = step_skinny(d);
-  const bool fuse = skinny && d->norm == HBP_NORM_NONE;   // the step along the residual path in the same kernel
+  // the step along the residual path in the same kernel (not for the LSTM, whose cell half is not a product)
+  const bool fuse = skinny && d->norm == HBP_NORM_NONE && d->kind != HBP_LSTM;
   if (skinny) {
     ProfScope ps(HBP_PROF_OTHER, s);
-    if (d->kind != HBP_GATED)
+    if (!cell(d))
       HBP_TRY(launch_transpose_bf16(bb.W2, at(bb.workspace, w.off_wt), (int)d->d, (int)d->d_ff, s));
     HBP_TRY(launch_transpose_bf16(bb.W1, at(bb.workspace, w.off_wt + (size_t)d->d * d->d_ff * esize(d)), (int)d->d_ff,
-                                  (int)d->d, s));
+                                  (int)hidden_w(d), s));
   }
   for (long l = d->L - 1; l >= 0; --l) {
     HBP_RUN(vjp_stage1(d, &bb, w, l, l + 1, s, skinny));
@@ -653,12 +682,12 @@ hbp_status hbp_param_grads(const hbp_desc* d, hbp_buffers* b, void* stream) {
   const void* g1 = at((const void*)bb.g, (size_t)d->N * d->d * es);
   const void* da = at((const void*)b->workspace, w.off_da);
   // dW2[c,j] = sum_n g_{l+1}[n,c] z_l[n,j]   (the gated cell has no second weight)
-  if (d->kind != HBP_GATED)
+  if (!cell(d))
     HBP_RUN(tn_gemm(d, g1, d->d, d->N * d->d, bb.z, d->d_ff, d->N * d->d_ff, bb.dW2, d->d, d->d_ff, K, nb, sp.s_w2,
                     part, s));
-  // dW1[j,c] = sum_n da_l[n,j] y_l[n,c]
-  HBP_RUN(tn_gemm(d, da, d->d_ff, d->N * d->d_ff, bb.y, d->d, d->N * d->d, bb.dW1, d->d_ff, d->d, K, nb, sp.s_w1,
-                  part, s));
+  // dW1[j,c] = sum_n da_l[n,j] y_l[n,c]   (a cell: over the hidden part of the state)
+  HBP_RUN(tn_gemm(d, da, d->d_ff, d->N * d->d_ff, at((const void*)bb.y, (size_t)hidden_off(d) * es), d->d,
+                  d->N * d->d, bb.dW1, d->d_ff, hidden_w(d), K, nb, sp.s_w1, part, s));
   if (recurrent(d)) {
     // dU[j,i] = sum da[n,j] xin[n,i]
     HBP_RUN(tn_gemm(d, da, d->d_ff, 0, bb.xin, d->d_in, 0, bb.dU, d->d_ff, d->d_in, K, 1, sp.s_u, part, s));

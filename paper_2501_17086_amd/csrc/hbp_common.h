@@ -203,6 +203,14 @@ hipError_t launch_gated_fwd(int dtype, const float* pre, const void* x, void* uc
 hipError_t launch_gated_vjp(int dtype, const void* g, const void* x, const void* uc, void* da, long rows, long H,
                             hipStream_t s);
 
+// The LSTM cell's elementwise parts (state [c | h] of width 2H, gates [i | f | o | gg] of width 4H, H % 8 == 0):
+// one step forward from pre [N,4H] fp32; step (i) up to its contraction for `rows` token rows (g: gradient of the
+// rows' next states, x / xn: current / next states, e: per-state loss gradients whose cell half is added to v, or NULL).
+hipError_t launch_lstm_fwd(int dtype, const float* pre, const void* x, void* gates, void* a, void* xn, long N, long H,
+                           hipStream_t s);
+hipError_t launch_lstm_vjp(int dtype, const void* g, const void* x, const void* xn, const void* gates, const void* e,
+                           void* da, void* v, long rows, long H, hipStream_t s);
+
 // y = x * rinv, rinv = 1/sqrt(mean(x^2)+eps) for `rows` rows of width d
 hipError_t launch_rmsnorm_fwd(int dtype, const void* x, void* y, float* rinv, long rows, long d, float eps,
                               hipStream_t s);

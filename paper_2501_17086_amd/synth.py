@@ -30,7 +30,8 @@ _T_W1, _T_W2, _T_U, _T_LAM, _T_X0, _T_XIN, _T_E = 1, 2, 3, 4, 5, 6, 7
 @dataclass(frozen=True)
 class Workload:
     name: str
-    kind: str            # 'mlp' | 'rnn' | 'gated' (recurrent cell x' = (1-u) x + u c; d_ff = 2 d)
+    kind: str            # 'mlp' | 'rnn' | 'gated' (recurrent cell x' = (1-u) x + u c; d_ff = 2 d) | 'lstm' (state
+                         # [c | h], d = 2H, d_ff = 4H)
     dtype: str           # 'f32' | 'bf16'   (storage; accumulation is fp32 on the GPU)
     act: str             # 'gelu' | 'tanh' | 'identity'
     norm: str            # 'none' | 'rms'
@@ -55,7 +56,7 @@ class Workload:
 
     @property
     def tokens(self) -> int:
-        return self.N * self.L if self.kind in ("rnn", "gated") else self.N
+        return self.N * self.L if self.kind in ("rnn", "gated", "lstm") else self.N
 
 
 WORKLOADS: Dict[str, Workload] = {
@@ -87,6 +88,9 @@ WORKLOADS["gated_rnn_contractive"] = replace(WORKLOADS["gated_rnn"], name="gated
 # decompositions): T = 4096, batch 32, H = 1024, gates biased towards closed (1 - u around 0.95)
 WORKLOADS["gru_cell"] = Workload("gru_cell", "gated", "bf16", "tanh", "none", L=4096, N=32, d=1024, d_ff=2048,
                                  d_in=1024, loss_every_state=True, gate_bias=-3.0, rec_scale=0.5)
+# an LSTM cell (the LSTM row of the same table): state [c | h] of 2 x 1024, forget gates around 0.95
+WORKLOADS["lstm_cell"] = Workload("lstm_cell", "lstm", "bf16", "tanh", "none", L=4096, N=32, d=2048, d_ff=4096,
+                                  d_in=1024, loss_every_state=True, gate_bias=3.0, rec_scale=0.5)
 # the contractive RNN with a gate per (step, batch row, channel): a diagonal K that depends on the data
 WORKLOADS["gated_rnn_token_gates"] = replace(WORKLOADS["gated_rnn_contractive"], name="gated_rnn_token_gates",
                                              lam="sigmoid_full")
@@ -119,7 +123,10 @@ def _normal(w: Workload, tid: int, idx: int, shape, std: float) -> np.ndarray:
 
 def weights_block(w: Workload, l: int):
     """(W1_l [d_ff,d], W2_l [d,d_ff]) for block l (rnn: l is ignored)."""
-    idx = 0 if w.kind in ("rnn", "gated") else l
+    idx = 0 if w.kind in ("rnn", "gated", "lstm") else l
+    if w.kind == "lstm":       # W1 = [W_i; W_f; W_o; W_g] acts on the hidden half of the state
+        H = w.d // 2
+        return storage_round(w, _normal(w, _T_W1, idx, (w.d_ff, H), w.rec_scale / np.sqrt(H))), None
     s1 = w.w1_std if w.w1_std > 0 else 1.0 / np.sqrt(w.d)
     s2 = (w.w2_std if w.w2_std > 0 else 1.0 / np.sqrt(w.d_ff)) * w.w2_scale
     W1 = _normal(w, _T_W1, idx, (w.d_ff, w.d), s1 * w.rec_scale)
@@ -183,8 +190,16 @@ def make_inputs(w: Workload, tokens=None) -> Dict[str, Optional[np.ndarray]]:
         out["U"][:H, 0] = np.float32(w.gate_bias)
         out["U"][H:, 0] = 0.0
         out["U"] = storage_round(w, out["U"])
+    if w.kind == "lstm":
+        # as for the gated cell: a constant forget-gate bias (gates mostly open: a long-lived cell state) through
+        # input channel 0, which is 1; rows H..2H of U are the forget gate's
+        H = w.d // 2
+        out["xin"][..., 0] = 1.0
+        out["U"][:, 0] = 0.0
+        out["U"][H:2 * H, 0] = np.float32(w.gate_bias)
+        out["U"] = storage_round(w, out["U"])
     out["lam"] = make_lambda(w, tokens)
-    if w.kind in ("rnn", "gated"):
+    if w.kind in ("rnn", "gated", "lstm"):
         out["x0"] = np.zeros((w.N, w.d), np.float32)[sl]
     else:
         out["x0"] = storage_round(w, _normal(w, _T_X0, 0, (w.N, w.d), 1.0)[sl])

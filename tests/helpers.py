@@ -12,8 +12,8 @@ TOL = {"f32": 1e-5, "bf16": 2e-2}   # relative L2, GPU vs oracle
 
 
 def oracle_stack(w: synth.Workload, inp) -> O.Stack:
-    if w.kind == "gated":
-        return O.Stack("gated", w.act, w.norm, inp["W1"], None, U=inp["U"], L=w.L)
+    if w.kind in ("gated", "lstm"):
+        return O.Stack(w.kind, w.act, w.norm, inp["W1"], None, U=inp["U"], L=w.L)
     return O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], U=inp["U"], eps=w.eps, L=w.L,
                    post=w.post)
 
@@ -29,6 +29,11 @@ def oracle_saved_rounded(w: synth.Workload, sv):
     out = dict(sv)
     if w.kind == "gated":      # x, the two gates and the residual coefficient, each stored on its own
         for k in ("x", "u", "c", "a"):
+            out[k] = r(sv[k])
+        out["y"] = out["x"][:-1]
+        return out
+    if w.kind == "lstm":
+        for k in ("x", "gates", "a"):
             out[k] = r(sv[k])
         out["y"] = out["x"][:-1]
         return out
@@ -53,6 +58,10 @@ def upload_saved(p, w: synth.Workload, sv_r):
     put(p.x, sv_r["x"])
     if w.kind == "gated":      # z = [u | c] side by side, lambda = a
         put(p.z, np.concatenate([sv_r["u"], sv_r["c"]], axis=-1))
+        put(p.lam, sv_r["a"])
+        return
+    if w.kind == "lstm":       # z = the four gates side by side, lambda = [f | 0]
+        put(p.z, sv_r["gates"])
         put(p.lam, sv_r["a"])
         return
     put(p.y, sv_r["y"])

@@ -101,6 +101,16 @@ def test_gated_cell_descriptor_rules():
     assert B.lib().hbp_check(C.byref(d), C.byref(bufs)) == 0
 
 
+def test_lstm_descriptor_rules():
+    n = C.c_size_t(0)
+    ok = dict(kind="lstm", act="tanh", norm="none", d=64, d_ff=128, d_in=32, lambda_token=True)
+    assert B.lib().hbp_workspace_size(C.byref(_desc(**ok)), C.byref(n)) == 0 and n.value > 0
+    assert B.lib().hbp_workspace_size(C.byref(_desc(**{**ok, "d_ff": 256})), C.byref(n)) == 1
+    assert B.lib().hbp_workspace_size(C.byref(_desc(**{**ok, "lambda_token": False})), C.byref(n)) == 1
+    # both halves of [c | h] must be whole 16-byte vectors
+    assert B.lib().hbp_workspace_size(C.byref(_desc(**{**ok, "d": 72, "d_ff": 144})), C.byref(n)) == 2
+
+
 def test_null_pointers_and_workspace_are_checked_before_launch():
     d = _desc()
     bufs = B.hbp_buffers(C.sizeof(B.hbp_buffers))

@@ -36,7 +36,7 @@ def _projection_check(p, w, tol):
     """dW2_l u == sum_n g_{l+1}[n] (z_l[n] . u) and dW1_l u == sum_n da-free form is not
     available, so dW1 is checked through y: u^T dW1_l == sum_n (u . da_l[n]) y_l[n] needs da;
     instead both are checked against torch contractions in fp64 on a few blocks."""
-    if w.kind == "gated":      # the cell has no second weight; dW1 and dU are compared element by element at the
+    if w.kind in ("gated", "lstm"):   # the cells have no second weight; dW1 and dU are compared element by element at the
         return                 # reduced sizes of test_gpu_parity
     g = torch.Generator(device="cpu").manual_seed(7)
     L = w.L
@@ -127,6 +127,11 @@ def test_gated_rnn_contractive_full(B):
 def test_gru_cell_full(B):
     # T = 4096 steps of the gated cell, each side on its own forward
     _run(B, W["gru_cell"], ks=(1, 3), rows_count=2, check_exact=True)
+
+
+@pytest.mark.timeout(300)
+def test_lstm_cell_full(B):
+    _run(B, W["lstm_cell"], ks=(1, 3), rows_count=2, check_exact=True)
 
 
 @pytest.mark.timeout(300)

@@ -93,6 +93,16 @@ CASES = {
                                    ks=(0, 2)),
     "gated_aligned": synth.scaled(W["gru_cell"], name="gated_aligned", L=64, N=8, d=256, d_ff=512, d_in=128,
                                   ks=(0, 1, 2, 3)),
+    # the LSTM cell (state [c | h]; the contraction's result lands in the hidden half of v with the full row stride)
+    "lstm_small": synth.scaled(W["lstm_cell"], name="lstm_small", L=37, N=5, d=128, d_ff=256, d_in=64,
+                               ks=(0, 1, 2, 5)),
+    "lstm_f32": synth.scaled(W["lstm_cell"], name="lstm_f32", dtype="f32", L=19, N=3, d=64, d_ff=128, d_in=32,
+                             ks=(0, 1, 3, 19)),
+    "lstm_long": synth.scaled(W["lstm_cell"], name="lstm_long", L=330, N=6, d=128, d_ff=256, d_in=64, ks=(0, 2)),
+    "lstm_width_80": synth.scaled(W["lstm_cell"], name="lstm_width_80", L=12, N=7, d=80, d_ff=160, d_in=32,
+                                  ks=(0, 2)),
+    "lstm_aligned": synth.scaled(W["lstm_cell"], name="lstm_aligned", L=64, N=8, d=512, d_ff=1024, d_in=128,
+                                 ks=(0, 1, 2, 3)),
     # a loss on every state of a depth stack (e read by the scan behind the norm's backward), and without a norm
     # (e added by the second contraction's epilogue)
     # coefficients per (block, token, channel): direct scans (depth, RMS and none) and the chunked scan (time)
@@ -180,7 +190,8 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
                                   "mlp_loss_all_nonorm", "rnn_token_gates", "rnn_token_gates_long",
                                   "rnn_token_gates_f32", "mlp_token_gates", "rnn_rows_40", "rnn_width_96",
                                   "postact_f32_none", "gated_small", "gated_f32", "gated_long", "gated_width_72",
-                                  "gated_aligned"])
+                                  "gated_aligned", "lstm_small", "lstm_f32", "lstm_long", "lstm_width_80",
+                                  "lstm_aligned"])
 def test_backward_end_to_end(B, name):
     """Own forward on each side, then Highway-BP at every k of the case, exact BP
     and the parameter gradients."""
@@ -201,6 +212,20 @@ def test_forward_of_the_gated_cell(B, name):
     assert H.rel(H.to_np(p.x), sv["x"]) < tol
     assert H.rel(H.to_np(p.z), np.concatenate([sv["u"], sv["c"]], axis=-1)) < tol
     assert H.rel(H.to_np(p.lam), sv["a"]) < tol
+
+
+@pytest.mark.parametrize("name", ["lstm_small", "lstm_f32", "lstm_width_80", "lstm_aligned"])
+def test_forward_of_the_lstm_cell(B, name):
+    """States [c | h], the four gates and the residual coefficient [f | 0] that the forward writes."""
+    w = CASES[name]
+    inp, st, sv, p = _setup(B, w)
+    B.hbp_forward(p)
+    torch.cuda.synchronize()
+    tol = H.TOL[w.dtype]
+    assert H.rel(H.to_np(p.x), sv["x"]) < tol
+    assert H.rel(H.to_np(p.z), sv["gates"]) < tol
+    assert H.rel(H.to_np(p.lam), sv["a"]) < tol
+    assert float(p.lam[..., w.d // 2:].abs().max()) == 0.0
 
 
 @pytest.mark.parametrize("name", ["postact_rms", "postact_wide", "postact_f32_none", "postact_f32_deep"])
@@ -224,7 +249,7 @@ def test_forward_with_relu_after_the_sum(B, name):
 
 @pytest.mark.parametrize("name", ["mlp_f32_ragged", "resnet_like_small", "rnn_small", "rnn_chaotic_small",
                                   "postact_rms", "postact_wide", "postact_aligned", "postact_f32_none",
-                                  "postact_f32_deep", "gated_small", "gated_long"])
+                                  "postact_f32_deep", "gated_small", "gated_long", "lstm_small", "lstm_long"])
 def test_backward_shared_state(B, name):
     """Both backward passes read the same (storage-rounded) forward state."""
     w = CASES[name]
@@ -243,7 +268,8 @@ def test_backward_shared_state(B, name):
                                         ("deep_small", 0.5), ("rnn_small", 0.3), ("rnn_f32", 1.0), ("rnn_long", 0.2), ("rnn_long", 1.0),
                                         ("aligned_small", 0.8), ("rnn_token_gates", 0.4),
                                         ("rnn_token_gates_long", 1.0), ("mlp_token_gates", 0.3),
-                                        ("gated_small", 0.3), ("gated_long", 1.0), ("gated_f32", 0.6)])
+                                        ("gated_small", 0.3), ("gated_long", 1.0), ("gated_f32", 0.6),
+                                        ("lstm_small", 0.3), ("lstm_long", 0.7)])
 def test_gamma_iterates(B, name, gamma):
     """The iteration on the re-split pair (J + gamma K, (1 - gamma) K): every k of
     the case against the oracle on a shared forward state; gamma = 1 is the
