@@ -871,6 +871,23 @@ bool launch_gemm_mfma(const GemmArgs& g, hipStream_t s, hipError_t* err) {
   const bool lean = lean_ok(g);
   const bool bf16_out = !g.addf && !g.c_is_f32 && g.split_k == 1;
   if (a_kc && b_rc && !act) {            // VJP contractions
+    // A row count that is no multiple of the tile (any number of tokens): the whole tiles go to the aligned
+    // kernel, the last rows to the general one in a second launch.  Rows are independent, both launches
+    // write disjoint rows of C.
+    const bool fast_mode = g.mode == EPI_STORE || g.mode == EPI_MUL_AUX || g.mode == EPI_MUL_1MZ2 || g.mode == EPI_ADD_AUX;
+    if (!lean && bf16_out && fast_mode && g.M > BM && g.M % BM != 0 && g.N % BN == 0 && g.K % BK == 0) {
+      GemmArgs head = g, tail = g;
+      head.M = g.M / BM * BM;
+      tail.M = g.M - head.M;
+      tail.A = reinterpret_cast<const bf16_t*>(g.A) + head.M * g.a_sm;
+      tail.C = reinterpret_cast<bf16_t*>(g.C) + head.M * g.ldc;
+      if (g.aux) tail.aux = reinterpret_cast<const bf16_t*>(g.aux) + head.M * g.ldc;
+      hipError_t e1 = hipSuccess;
+      launch_gemm_mfma(head, s, &e1);
+      if (e1 != hipSuccess) { *err = e1; return true; }
+      *err = launch_variant<true, false, false>(tail, s);
+      return true;
+    }
     if (lean && bf16_out && g.mode == EPI_STORE) *err = launch_lean<true, false, FAST_STORE>(g, s);
     else if (lean && bf16_out && g.mode == EPI_MUL_AUX) *err = launch_lean<true, false, FAST_MUL_AUX>(g, s);
     else if (lean && bf16_out && g.mode == EPI_MUL_1MZ2) *err = launch_lean<true, false, FAST_MUL_1MZ2>(g, s);

@@ -35,6 +35,11 @@ int pick_split(long tiles, long K) {
   if (want > cap) want = cap;
   if (want > 64) want = 64;
   if (want < 1) want = 1;
+  // the aligned kernel needs every share of the contraction to be a whole number of 32-row slices:
+  // take the largest such factor below the wanted one when there is one
+  if (K % 32 == 0)
+    for (long s = want; s >= 1; --s)
+      if ((K / 32) % s == 0) return (int)s;
   return (int)want;
 }
 

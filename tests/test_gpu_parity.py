@@ -103,6 +103,10 @@ CASES = {
                                   ks=(0, 2)),
     "lstm_aligned": synth.scaled(W["lstm_cell"], name="lstm_aligned", L=64, N=8, d=512, d_ff=1024, d_in=128,
                                  ks=(0, 1, 2, 3)),
+    # a token count that is no multiple of the 256-row tile: whole tiles on the aligned kernel, the last 88 rows on
+    # the general one (resnet_like_small and transformer_small take the same route with one whole tile)
+    "ragged_tokens": synth.scaled(W["resnet_like"], name="ragged_tokens", L=3, N=600, d=256, d_ff=512,
+                                  w2_scale=1 / np.sqrt(3.0), ks=(0, 1, 3)),
     # a loss on every state of a depth stack (e read by the scan behind the norm's backward), and without a norm
     # (e added by the second contraction's epilogue)
     # coefficients per (block, token, channel): direct scans (depth, RMS and none) and the chunked scan (time)
@@ -191,7 +195,7 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
                                   "rnn_token_gates_f32", "mlp_token_gates", "rnn_rows_40", "rnn_width_96",
                                   "postact_f32_none", "gated_small", "gated_f32", "gated_long", "gated_width_72",
                                   "gated_aligned", "lstm_small", "lstm_f32", "lstm_long", "lstm_width_80",
-                                  "lstm_aligned"])
+                                  "lstm_aligned", "ragged_tokens"])
 def test_backward_end_to_end(B, name):
     """Own forward on each side, then Highway-BP at every k of the case, exact BP
     and the parameter gradients."""
