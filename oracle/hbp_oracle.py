@@ -16,6 +16,12 @@ and erf are the only library steps; no blocking, fusion or reordering):
              ResNet in the table of layer decompositions, r(x, z) =
              ReLU(lam (.) x + z): with m = 1[lam (.) x + z > 0],
              K = dr/dx = diag(m (.) lam) and J = dr/dz . dg/dx = diag(m) . dg/dx.
+             post = 'rms' is the post-norm row of the table (f = Norm(x + Layer(x)) written as
+             a(x) (.) x + b(x) with r(x, z) = z1 (.) x + z2), for the RMS norm without gain: with
+             s = lam (.) x + g(x) and rho = 1/sqrt(mean(s^2) + eps):  a = lam rho (rho one number per token),
+             b = g(x) rho.  K = dr/dx = diag(lam rho), held as data like any z1; J = F - K with F the layer's
+             whole Jacobian, whose VJP is  G -> lam (.) P(G) + P(G) . dg/dx,  P(G) = rho (G - x' mean(G (.) x'))
+             the norm's backward at the new state x'.
              kind = 'gated' is the GRU row of the same table, f(x) = a(x) (.) x + b(x)
              with g = [a, b] and r(x, z) = z1 (.) x + z2, for the cell  u = sigmoid(W_u x + U_u xin),
              c = tanh(W_c x + U_c xin),  a = 1 - u,  b = u (.) c  (a GRU without its reset gate):
@@ -75,7 +81,7 @@ class Stack:
                   l+1 and consumes xin[l]
     act    'gelu' (exact erf form) | 'tanh' | 'identity'
     norm   'none' | 'rms'  (no gain, eps inside the square root)
-    post   'none' | 'relu': what the residual function applies after the sum
+    post   'none' | 'relu' | 'rms': what the residual function applies after the sum
            (Section "Notations and assumptions": r need not be linear)
     lam    None (lambda = 1), [L, d] (one coefficient per block and channel,
            shared by all tokens) or [L, N, d] (per token as well: a diagonal
@@ -94,7 +100,7 @@ class Stack:
     post: str = "none"
 
     def __post_init__(self):
-        assert self.post in ("none", "relu")
+        assert self.post in ("none", "relu", "rms")
         assert self.kind in ("mlp", "rnn", "gated", "lstm")
         assert self.act in ("gelu", "tanh", "identity")
         assert self.norm in ("none", "rms")
@@ -185,6 +191,7 @@ def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict
     rinv = np.ones((L, N), F64)
     a = np.zeros((L, N, dff), F64)
     mask = np.ones((L, N, d), F64)
+    rpost = np.ones((L, N), F64)
     x[0] = x0
     for l in range(L):
         if st.norm == "rms":
@@ -200,7 +207,10 @@ def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict
         if st.post == "relu":
             mask[l] = (x[l + 1] > 0.0).astype(F64)
             x[l + 1] = np.maximum(x[l + 1], 0.0)
-    return {"x": x, "y": y, "rinv": rinv, "a": a, "mask": mask,
+        if st.post == "rms":
+            rpost[l] = 1.0 / np.sqrt(np.mean(x[l + 1] * x[l + 1], axis=1) + st.eps)
+            x[l + 1] = x[l + 1] * rpost[l][:, None]
+    return {"x": x, "y": y, "rinv": rinv, "a": a, "mask": mask, "rpost": rpost,
             "z": act_fn(st.act, a), "dphi": act_grad(st.act, a)}
 
 
@@ -304,10 +314,34 @@ def block_vjp(st: Stack, l: int, saved: Dict[str, np.ndarray], g_next: np.ndarra
 
 def through_r(st: Stack, l: int, saved: Dict[str, np.ndarray], g_next: np.ndarray) -> np.ndarray:
     """g_{l+1} . dr/d(sum): the gradient of state l+1 taken back through what the residual function applies after
-    the sum (the ReLU's mask, or nothing).  Both dr/dz and dr/dx = this . diag(lam) start from it."""
+    the sum (the ReLU's mask, the norm's backward, or nothing): the gradient with respect to the sum, which is what
+    the block VJP and the parameter gradients start from."""
     if st.post == "relu":
         return saved["mask"][l] * g_next
+    if st.post == "rms":
+        xn = saved["x"][l + 1]
+        m = np.mean(g_next * xn, axis=1, keepdims=True)
+        return (g_next - xn * m) * saved["rpost"][l][:, None]
     return g_next
+
+
+def k_full(st: Stack, l: int, saved: Dict[str, np.ndarray]) -> np.ndarray:
+    """Diagonal of K_l = dr/dx for the layer between states l and l+1, as [1,d] or [N,d]."""
+    k = k_diag(st, l, saved)
+    if st.post == "relu":
+        return saved["mask"][l] * k
+    if st.post == "rms":
+        return saved["rpost"][l][:, None] * k
+    return k
+
+
+def j_vjp(st: Stack, l: int, saved: Dict[str, np.ndarray], g_next: np.ndarray) -> np.ndarray:
+    """g_{l+1} J_l with J_l = (the layer's whole Jacobian) - K_l."""
+    gs = through_r(st, l, saved, g_next)
+    v = block_vjp(st, l, saved, gs)
+    if st.post == "rms":     # what the sum's own lam (.) x contributes beyond K: lam (.) (P(G) - rho G)
+        v = v + k_diag(st, l, saved) * (gs - saved["rpost"][l][:, None] * g_next)
+    return v
 
 
 def _e_full(st: Stack, e: np.ndarray, N: int) -> np.ndarray:
@@ -331,8 +365,7 @@ def exact_backward(st: Stack, saved: Dict[str, np.ndarray], e: np.ndarray) -> np
     G = np.zeros_like(ef)
     G[st.L] = ef[st.L]
     for l in range(st.L - 1, -1, -1):
-        gs = through_r(st, l, saved, G[l + 1])
-        G[l] = ef[l] + k_diag(st, l, saved) * gs + block_vjp(st, l, saved, gs)
+        G[l] = ef[l] + k_full(st, l, saved) * G[l + 1] + j_vjp(st, l, saved, G[l + 1])
     return G
 
 
@@ -373,18 +406,16 @@ def hbp_backward(st: Stack, saved: Dict[str, np.ndarray], e: np.ndarray, k: int,
     N = saved["y"].shape[1]
     L = st.L
     ef = _e_full(st, e, N)
-    m_row = (lambda l: saved["mask"][l]) if st.post == "relu" else (lambda l: 1.0)
-    k_row = lambda l: (1.0 - gamma) * m_row(l) * k_diag(st, l, saved)
+    k_row = lambda l: (1.0 - gamma) * k_full(st, l, saved)
     w0 = cumsumprod_reverse(ef, k_row)
     w = w0.copy()
     hist = [w0.copy()]
     for _ in range(k):
         v = np.zeros_like(w)                       # v_L = 0: no block above x_L
         for l in range(L):
-            ws = through_r(st, l, saved, w[l + 1])
-            v[l] = block_vjp(st, l, saved, ws)
+            v[l] = j_vjp(st, l, saved, w[l + 1])
             if gamma != 0.0:
-                v[l] = v[l] + gamma * k_diag(st, l, saved) * ws
+                v[l] = v[l] + gamma * k_full(st, l, saved) * w[l + 1]
         u = cumsumprod_reverse(v, k_row)
         w = w0 + u
         hist.append(w.copy())
@@ -398,9 +429,9 @@ def param_grads(st: Stack, saved: Dict[str, np.ndarray], g: np.ndarray,
                 xin: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
     """dW2_l = sum_n g_{l+1}[n]^T z_l[n] ; dW1_l = sum_n da_l[n]^T y_l[n] ;
     dU = sum da^T xin, with da from the given g.  Shared weights (rnn) sum
-    over l as well.  (With post = 'relu', g_{l+1} is first taken through the mask.)"""
+    over l as well.  (With post = 'relu' or 'rms', g_{l+1} is first taken through it: through_r.)"""
     L = st.L
-    if st.post == "relu":
+    if st.post != "none":
         g = np.concatenate([g[:1]] + [through_r(st, l, saved, g[l + 1])[None] for l in range(L)], axis=0)
     if st.kind == "mlp":
         dW1 = np.zeros_like(st.W1)

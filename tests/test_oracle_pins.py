@@ -843,3 +843,104 @@ def test_lstm_cell_k0_follows_the_forget_gates_only():
         prod = prod * sv["gates"][l][:, H_:2 * H_]
         np.testing.assert_allclose(w0[l][:, :H_], e[:, :H_] * prod, rtol=1e-12)
         np.testing.assert_array_equal(w0[l][:, H_:], 0.0)
+
+
+# ---------------------------------------------------------------- P15: post-norm, x' = RMSnorm(lam (.) x + block(x))
+def small_postnorm_mlp(L=4, d=6, dff=10, seed=5):
+    st = small_mlp(L=L, d=d, dff=dff, norm="none", seed=seed)
+    st.post = "rms"
+    return st
+
+
+def test_post_norm_against_torch_autograd():
+    """The post-norm row of the table of layer decompositions (RMS norm without gain after the sum): forward
+    states, every state gradient and every parameter gradient against torch's autograd in fp64."""
+    r = np.random.default_rng(61)
+    N = 5
+    st = small_postnorm_mlp(L=5, d=8, dff=12)
+    x0 = r.standard_normal((N, st.d))
+    c = r.standard_normal((st.L + 1, N, st.d))
+    sv = O.forward(st, x0)
+    np.testing.assert_allclose(np.mean(sv["x"][1:] ** 2, axis=-1), 1.0, rtol=1e-5)
+    G = O.exact_backward(st, sv, c)
+    pg = O.param_grads(st, sv, G)
+
+    t = lambda a: torch.tensor(a, dtype=torch.float64, requires_grad=True)
+    W1, W2, lam = t(st.W1), t(st.W2), torch.tensor(st.lam)
+    xs = [t(x0)]
+    for l in range(st.L):
+        x = xs[-1]
+        s = lam[l] * x + torch.nn.functional.gelu(x @ W1[l].T) @ W2[l].T
+        nxt = s / torch.sqrt((s * s).mean(dim=1, keepdim=True) + st.eps)
+        nxt.retain_grad()
+        xs.append(nxt)
+    loss = sum((torch.tensor(c[l]) * xs[l]).sum() for l in range(st.L + 1))
+    loss.backward()
+    for l in range(st.L + 1):
+        np.testing.assert_allclose(sv["x"][l], xs[l].detach().numpy(), rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(G[l], xs[l].grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(pg["dW1"], W1.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(pg["dW2"], W2.grad.numpy(), rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("gamma", [0.0, 0.3])
+def test_post_norm_by_path_enumeration(gamma):
+    """Theorem 2 with K_l = diag(lam_l rho_l) (rho_l the token's 1/rms of the sum, held as data) and J_l = F_l - K_l,
+    F_l the whole layer's Jacobian by central differences of x -> RMSnorm(lam (.) x + block(x))."""
+    st = small_postnorm_mlp(L=5, d=3, dff=4, seed=8)
+    r = np.random.default_rng(4)
+    sv = O.forward(st, r.standard_normal((1, st.d)))
+    e = r.standard_normal((st.L + 1, 1, st.d))
+    L, d = st.L, st.d
+
+    def layer(x, l):
+        s = st.lam[l] * x + O.act_fn(st.act, st.W1[l] @ x) @ st.W2[l].T
+        return s / math.sqrt(np.mean(s * s) + st.eps)
+    Kd, Js = [], []
+    for l in range(L):
+        x = sv["x"][l][0]
+        F = np.zeros((d, d))
+        for i in range(d):
+            xp, xm = x.copy(), x.copy()
+            xp[i] += 1e-6
+            xm[i] -= 1e-6
+            F[:, i] = (layer(xp, l) - layer(xm, l)) / 2e-6
+        s = st.lam[l] * x + O.act_fn(st.act, st.W1[l] @ x) @ st.W2[l].T
+        K = np.diag(st.lam[l] / math.sqrt(np.mean(s * s) + st.eps))
+        Kd.append(K)
+        Js.append(F - K)
+    Jg = [Js[l] + gamma * Kd[l] for l in range(L)]
+    Kg = [(1 - gamma) * Kd[l] for l in range(L)]
+    for k in range(L + 1):
+        w = O.hbp_backward(st, sv, e, k, gamma=gamma)
+        for i in range(L + 1):
+            acc = np.zeros(d)
+            for j in range(i, L + 1):
+                layers = list(range(i, j))
+                for size in range(min(k, len(layers)) + 1):
+                    for chosen in itertools.combinations(layers, size):
+                        vec = e[j][0].copy()
+                        for l in reversed(layers):
+                            vec = vec @ (Jg[l] if l in chosen else Kg[l])
+                        acc += vec
+            np.testing.assert_allclose(w[i][0], acc, rtol=5e-6, atol=5e-8)
+    np.testing.assert_allclose(O.hbp_backward(st, sv, e, L, gamma=gamma), O.exact_backward(st, sv, e),
+                               rtol=1e-10, atol=1e-12)
+
+
+def test_post_norm_finite_termination_and_k0():
+    st = small_postnorm_mlp(L=6, d=5, dff=7, seed=2)
+    r = np.random.default_rng(6)
+    sv = O.forward(st, r.standard_normal((3, st.d)))
+    e = r.standard_normal((3, st.d))
+    G = O.exact_backward(st, sv, e)
+    w0 = O.hbp_backward(st, sv, e, 0)
+    prod = np.ones_like(e)
+    for l in range(st.L - 1, -1, -1):      # w^0: e_L times the products of lam rho
+        prod = prod * st.lam[l] * sv["rpost"][l][:, None]
+        np.testing.assert_allclose(w0[l], e * prod, rtol=1e-12)
+    for k in range(st.L + 1):
+        w = O.hbp_backward(st, sv, e, k)
+        for i in range(st.L + 1):
+            if k >= st.L - i:
+                np.testing.assert_allclose(w[i], G[i], rtol=1e-11, atol=1e-13)
