@@ -67,7 +67,7 @@ def algorithmic_work(w, k):
     # the block and the residual path: otherwise e was added by the second contraction)
     e_in_scan = w.loss_every_state and w.norm == "rms"
     lam_tok = 1 if (w.lam == "sigmoid_full" or w.kind in ("gated", "lstm")) else 0   # coefficients per token: one more stream
-    streams_in = 1 + (1 if w.norm == "rms" else 0) + (1 if e_in_scan else 0) + lam_tok
+    streams_in = 1 + (1 if (w.norm == "rms" or w.post == "rms") else 0) + (1 if e_in_scan else 0) + lam_tok
     mask = S / 8.0 if w.post == "relu" else 0.0       # one bit per element per scan
     scan_iter = S * s * (streams_in + 1) + mask
     scan_init = S * s * (1 + (1 if w.loss_every_state else 0) + lam_tok) + mask
@@ -312,7 +312,7 @@ def main():
         out["per_k"] = sweep
         # the re-split iteration (gamma of the layer's residual connection counted with the block);
         # gamma = 1 is the fixed-point-iteration baseline
-        if not (w.norm == "rms" and w.d > 2048) and w.post == "none":
+        if not ((w.norm == "rms" or w.post == "rms") and w.d > 2048) and w.post != "relu":
             gs = {}
             for gm in (0.2, 0.5, 1.0):
                 def fg(gm=gm):
@@ -343,7 +343,7 @@ def main():
 
     if not args.no_cpu_baseline:
         # about 10-20 s of oracle work on the GPU machine's host cores
-        n = args.cpu_tokens or {"mlp_small_f32": 128, "resnet_like": 8192, "resnet_postact": 8192, "transformer_mlp": 2048,
+        n = args.cpu_tokens or {"mlp_small_f32": 128, "resnet_like": 8192, "resnet_postact": 8192, "postnorm_mlp": 2048, "transformer_mlp": 2048,
                                 "deep_large": 256, "gated_rnn": 16, "gated_rnn_contractive": 16,
                                 "gated_rnn_token_gates": 16, "gru_cell": 16, "lstm_cell": 8}.get(w.name, 64)
         out["cpu_baseline"] = cpu_baseline(w, k, n)

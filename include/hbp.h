@@ -81,7 +81,14 @@ typedef enum { HBP_LAMBDA_ONE = 0, HBP_LAMBDA_CHANNEL = 1, HBP_LAMBDA_TOKEN = 2 
  * J_l = diag(m_l) . d block_l / dx.  The backward calls then keep every state gradient already taken through
  * its ReLU: g[l] = m_{l-1} (.) dL/dx_l for l >= 1 (the gradient with respect to the sum that made x_l, which is
  * what the block VJP and the parameter gradients start from), g[0] = dL/dx_0.  HBP_MLP with gamma = 0 only. */
-typedef enum { HBP_POST_NONE = 0, HBP_POST_RELU = 1 } hbp_post;
+typedef enum { HBP_POST_NONE = 0, HBP_POST_RELU = 1, HBP_POST_RMS = 2 } hbp_post;
+/* RMS: the post-norm row of the same table, x_{l+1} = RMSnorm(lambda_l (.) x_l + block_l(x_l)) (no gain; the block has
+ * no norm of its own: norm = HBP_NORM_NONE).  With rho_l = 1/rms of the sum (one number per token, written to rinv by
+ * hbp_forward): K_l = diag(lambda_l rho_l), J_l = the layer's Jacobian minus K_l.  As with RELU the backward calls
+ * keep g[l] (l >= 1) taken through the norm that made x_l: g[l] = rho_{l-1} (G_l - x_l mean(G_l (.) x_l)), the
+ * gradient with respect to the sum; g[0] = dL/dx_0.  HBP_MLP, lambda ONE or CHANNEL, d <= 4096 (2048 with gamma > 0).
+ * On deep post-norm stacks the plain split (gamma = 0) diverges with k, as the paper reports for transformers: use
+ * gamma around 0.5 .. 0.8. */
 
 typedef struct {
   uint32_t struct_size;      /* = sizeof(hbp_desc) */
@@ -116,7 +123,8 @@ typedef struct {
   /* forward state: written by hbp_forward, read by the backward calls. */
   void* x;                   /* S [L+1,N,d]  states x_0..x_L (x[0] is the input) */
   void* y;                   /* S [L,N,d]    norm(x_l); unused (may be NULL) with HBP_NORM_NONE, where x is read */
-  float* rinv;               /* [L,N]        1/sqrt(mean(x_l^2)+eps); unused with HBP_NORM_NONE */
+  float* rinv;               /* [L,N]        1/sqrt(mean(x_l^2)+eps); unused with HBP_NORM_NONE, except with
+                              *               HBP_POST_RMS, where it holds 1/rms of the sum that made x_{l+1} */
   void* z;                   /* S [L,N,d_ff] act(a_l) */
   void* dphi;                /* S [L,N,d_ff] act'(a_l); unused with TANH (1 - z^2) and IDENTITY (1) */
   const void* xin;           /* S [L,N,d_in] RNN inputs; NULL for MLP */

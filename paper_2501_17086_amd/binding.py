@@ -25,7 +25,7 @@ MLP, RNN, GATED, LSTM = 0, 1, 2, 3
 KIND = {"mlp": MLP, "rnn": RNN, "gated": GATED, "lstm": LSTM}
 ACT = {"gelu": 0, "tanh": 1, "identity": 2}
 NORM = {"none": 0, "rms": 1}
-POST = {"none": 0, "relu": 1}
+POST = {"none": 0, "relu": 1, "rms": 2}
 LAMBDA_ONE, LAMBDA_CHANNEL, LAMBDA_TOKEN = 0, 1, 2
 
 EXPORTS = ("hbp_workspace_size", "hbp_check", "hbp_forward", "hbp_backward", "hbp_exact_backward",
@@ -243,11 +243,12 @@ def allocate(w, inputs, device="cuda:0", N: Optional[int] = None) -> Problem:
     x = torch.zeros((L + 1, N, d), dtype=dt, device=dev)
     x[0] = up(inputs["x0"])
     rms = w.norm == "rms"
+    post = getattr(w, "post", "none")
     p = Problem(
         desc=desc, W1=up(inputs["W1"]), W2=up(inputs["W2"]), U=up(inputs["U"]),
         lam=up(lam, dt if per_token else torch.float32), x=x,
         y=torch.zeros((L, N, d), dtype=dt, device=dev) if rms else None,
-        rinv=torch.zeros((L, N), dtype=torch.float32, device=dev) if rms else None,
+        rinv=torch.zeros((L, N), dtype=torch.float32, device=dev) if (rms or post == "rms") else None,
         z=torch.zeros((L, N, dff), dtype=dt, device=dev),
         dphi=torch.zeros((L, N, dff), dtype=dt, device=dev) if w.act == "gelu" else None,
         xin=up(inputs["xin"]), e=up(inputs["e"]),

@@ -22,7 +22,7 @@ inline long hidden_off(const hbp_desc* d) { return d->kind == HBP_LSTM ? d->d / 
 inline bool shared_w(const hbp_desc* d) { return recurrent(d); }
 
 struct Workspace {
-  size_t off_v, off_da, off_part, off_scan, off_wt, off_pre, total;
+  size_t off_v, off_da, off_part, off_scan, off_wt, off_pre, off_m, total;
 };
 
 // split-K factor for a parameter-gradient GEMM with `tiles` output tiles and a
@@ -81,6 +81,9 @@ Workspace carve(const hbp_desc* d) {
   // one step's pre-activations of the gated cell, fp32 [N, 2H]
   w.off_pre = o;
   if (cell(d)) o = align_up(o + (size_t)d->N * d->d_ff * 4, 256);
+  // post-norm: mean(G (.) x) per (layer, token) of the previous and of the current estimate
+  w.off_m = o;
+  if (d->post == HBP_POST_RMS) o = align_up(o + 2 * (size_t)d->L * d->N * 4, 256);
   w.total = o;
   return w;
 }
@@ -111,8 +114,12 @@ hbp_status check_desc(const hbp_desc* d) {
   if (d->d % 8 || d->d_ff % 8 || d->d_in % 8) return HBP_E_UNSUPPORTED;
   if (d->norm == HBP_NORM_RMS && d->d > 4096) return HBP_E_UNSUPPORTED;
   if (!(d->gamma >= 0.f && d->gamma <= 1.f)) return HBP_E_INVALID_ARG;
-  if (d->post != HBP_POST_NONE && d->post != HBP_POST_RELU) return HBP_E_INVALID_ARG;
-  if (d->post == HBP_POST_RELU && (d->kind != HBP_MLP || d->gamma != 0.f)) return HBP_E_UNSUPPORTED;
+  if (d->post < HBP_POST_NONE || d->post > HBP_POST_RMS) return HBP_E_INVALID_ARG;
+  if (d->post != HBP_POST_NONE && d->kind != HBP_MLP) return HBP_E_UNSUPPORTED;
+  if (d->post == HBP_POST_RELU && d->gamma != 0.f) return HBP_E_UNSUPPORTED;
+  if (d->post == HBP_POST_RMS && (d->norm != HBP_NORM_NONE || d->lambda_kind == HBP_LAMBDA_TOKEN || d->d > 4096 ||
+                                  (d->gamma != 0.f && d->d > 2048)))
+    return HBP_E_UNSUPPORTED;
   if (d->gamma != 0.f && d->norm == HBP_NORM_RMS && d->d > 2048) return HBP_E_UNSUPPORTED;
   if (d->L > (1 << 20) || d->N > (1L << 24) || d->d > (1 << 20) || d->d_ff > (1 << 20)) return HBP_E_UNSUPPORTED;
   return HBP_OK;
@@ -132,6 +139,7 @@ hbp_status check_bufs(const hbp_desc* d, const hbp_buffers* b, int need) {
   if (!b->z) return HBP_E_NULL;
   if (d->act == HBP_ACT_GELU_ERF && !b->dphi) return HBP_E_NULL;
   if (d->post == HBP_POST_RELU && (need & (NEED_FWD | NEED_BWD)) && !b->mask) return HBP_E_NULL;
+  if (d->post == HBP_POST_RMS && (need & (NEED_FWD | NEED_BWD)) && !b->rinv) return HBP_E_NULL;
   if (need & (NEED_BWD | NEED_PG)) {
     if (!b->g) return HBP_E_NULL;
   }
@@ -323,7 +331,33 @@ hbp_status vjp_stage2(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
 
 // gamma: 0 for the exact recurrence; in the iterations of hbp_backward the descriptor's
 hbp_status scan_stage(const hbp_desc* d, const hbp_buffers* b, const Workspace& w, long l_lo, long l_hi,
-                      bool has_v, hipStream_t s, float gamma = 0.f, int force = 0) {
+                      bool has_v, hipStream_t s, float gamma = 0.f, int force = 0, int m_parity = 0,
+                      bool exact_step = false) {
+  if (d->post == HBP_POST_RMS) {
+    // the whole chain from the top (an iteration, or w^0), or one layer of exact backpropagation
+    const bool whole = !exact_step;
+    if (whole && (l_lo != 0 || l_hi != d->L)) return HBP_E_INVALID_ARG;
+    PostScanArgs pa{};
+    pa.g = b->g;
+    pa.dn = has_v ? at(b->workspace, w.off_v) : nullptr;
+    pa.e = (d->loss_every_state && !(has_v && e_in_vjp(d))) ? b->e : nullptr;
+    pa.e_top = d->loss_every_state ? at(b->e, (size_t)d->L * d->N * d->d * esize(d)) : b->e;
+    pa.x = b->x;
+    pa.lambda = d->lambda_kind == HBP_LAMBDA_CHANNEL ? reinterpret_cast<const float*>(b->lambda) : nullptr;
+    pa.rho = b->rinv;
+    float* m0 = reinterpret_cast<float*>(at(b->workspace, w.off_m));
+    float* m1 = m0 + d->L * d->N;
+    pa.m_old = m_parity ? m1 : m0;      // reads the set the previous scan wrote, writes the other
+    pa.m_new = m_parity ? m0 : m1;
+    pa.N = d->N; pa.d = d->d;
+    pa.l_lo = l_lo; pa.l_hi = l_hi;
+    pa.mode = whole ? 0 : 1;
+    pa.gamma = whole ? gamma : 0.f;
+    pa.blk_gamma = (whole && has_v) ? gamma : 0.f;   // w^0 has no block term: only the residual path is rescaled
+    ProfScope ps(HBP_PROF_SCAN, s);
+    HBP_TRY(launch_scan_post(d->dtype, pa, s));
+    return HBP_OK;
+  }
   ScanArgs sa{};
   sa.force = force;
   sa.res_scale = 1.f - gamma;
@@ -348,6 +382,7 @@ hbp_status scan_stage(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
 
 // g[L] := e_L
 hbp_status seed_top(const hbp_desc* d, const hbp_buffers* b, hipStream_t s) {
+  if (d->post == HBP_POST_RMS) return HBP_OK;   // the post-norm scan seeds g[L] itself (through the last norm)
   const size_t es = esize(d);
   const size_t row = (size_t)d->N * d->d * es;
   const void* src = d->loss_every_state ? at(b->e, (size_t)d->L * row) : b->e;
@@ -557,6 +592,11 @@ hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
       ga.lambda_mn = d->lambda_kind == HBP_LAMBDA_TOKEN ? at(b->lambda, xo) : nullptr;
       HBP_RUN(run_gemm(d, ga, s, HBP_PROF_FORWARD));
     }
+    if (d->post == HBP_POST_RMS) {
+      ProfScope ps(HBP_PROF_FORWARD, s);
+      HBP_TRY(launch_rmsnorm_inplace(d->dtype, at(b->x, xo + (size_t)d->N * d->d * es), b->rinv + l * d->N, d->N, d->d,
+                                     d->eps, s));
+    }
     if (d->post == HBP_POST_RELU) {
       ProfScope ps(HBP_PROF_FORWARD, s);
       HBP_TRY(launch_relu_mask(d->dtype, at(b->x, xo + (size_t)d->N * d->d * es), b->mask + (size_t)l * d->N * d->d / 8,
@@ -595,7 +635,7 @@ hbp_status hbp_backward(const hbp_desc* d, int k, hbp_buffers* b, void* stream) 
     }
     HBP_RUN(vjp_stage1(d, &bb, w, 0, l_hi, s));
     HBP_RUN(vjp_stage2(d, &bb, w, 0, l_hi, s));
-    HBP_RUN(scan_stage(d, &bb, w, 0, d->L, true, s, d->gamma));
+    HBP_RUN(scan_stage(d, &bb, w, 0, d->L, true, s, d->gamma, 0, (int)(it & 1)));
   }
   return HBP_OK;
 }
@@ -603,8 +643,8 @@ hbp_status hbp_backward(const hbp_desc* d, int k, hbp_buffers* b, void* stream) 
 hbp_status hbp_scan_workspace_size(const hbp_desc* d, int algorithm, size_t* bytes) {
   if (!bytes) return HBP_E_NULL;
   HBP_RUN(check_desc(d));
-  // the ReLU's mask is applied by the direct forms only
-  if (d->post == HBP_POST_RELU && (algorithm == HBP_SCAN_CHUNKED || algorithm == HBP_SCAN_HILLIS_STEELE))
+  // a ReLU's mask or a norm after the sum is applied by the direct forms only
+  if (d->post != HBP_POST_NONE && (algorithm == HBP_SCAN_CHUNKED || algorithm == HBP_SCAN_HILLIS_STEELE))
     return HBP_E_UNSUPPORTED;
   switch (algorithm) {
     case HBP_SCAN_AUTO: case HBP_SCAN_SEQUENTIAL: *bytes = carve(d).total; break;
@@ -624,6 +664,7 @@ hbp_status hbp_initial_estimate(const hbp_desc* d, int algorithm, hbp_buffers* b
   if (d->lambda_kind != HBP_LAMBDA_ONE && !b->lambda) return HBP_E_NULL;
   if (!b->workspace || b->workspace_bytes < need) return HBP_E_WORKSPACE;
   if (d->post == HBP_POST_RELU && !b->mask) return HBP_E_NULL;
+  if (d->post == HBP_POST_RMS && (!b->x || !b->rinv)) return HBP_E_NULL;
   hipStream_t s = (hipStream_t)stream;
   if (algorithm == HBP_SCAN_HILLIS_STEELE) {
     HsArgs a{};
@@ -651,6 +692,15 @@ hbp_status hbp_exact_backward(const hbp_desc* d, hbp_buffers* b, void* stream) {
   hbp_buffers bb = *b;
   if (d->norm == HBP_NORM_NONE) bb.y = bb.x;
   HBP_RUN(seed_top(d, &bb, s));
+  if (d->post == HBP_POST_RMS) {   // g[L] = e_L taken through the last norm
+    PostScanArgs pa{};
+    pa.g = bb.g; pa.x = bb.x; pa.rho = bb.rinv;
+    pa.e_top = d->loss_every_state ? at(bb.e, (size_t)d->L * d->N * d->d * esize(d)) : bb.e;
+    pa.m_new = reinterpret_cast<float*>(at(bb.workspace, w.off_m));
+    pa.N = d->N; pa.d = d->d; pa.l_lo = d->L; pa.l_hi = d->L; pa.mode = 2;
+    ProfScope ps(HBP_PROF_SCAN, s);
+    HBP_TRY(launch_scan_post(d->dtype, pa, s));
+  }
   const bool skinny = step_skinny(d);
   // the step along the residual path in the same kernel (not for the LSTM, whose cell half is not a product)
   const bool fuse = skinny && d->norm == HBP_NORM_NONE && d->kind != HBP_LSTM;
@@ -664,7 +714,7 @@ hbp_status hbp_exact_backward(const hbp_desc* d, hbp_buffers* b, void* stream) {
   for (long l = d->L - 1; l >= 0; --l) {
     HBP_RUN(vjp_stage1(d, &bb, w, l, l + 1, s, skinny));
     HBP_RUN(vjp_stage2(d, &bb, w, l, l + 1, s, skinny, fuse));
-    if (!fuse) HBP_RUN(scan_stage(d, &bb, w, l, l + 1, true, s));
+    if (!fuse) HBP_RUN(scan_stage(d, &bb, w, l, l + 1, true, s, 0.f, 0, 0, true));
   }
   return HBP_OK;
 }

@@ -192,6 +192,27 @@ struct HsArgs {
 size_t hs_ws_bytes(long L, long N, long d, int lambda_kind);   // 0 one, 1 channel, 2 token
 hipError_t launch_scan_hillis_steele(int dtype, const HsArgs& a, hipStream_t s);
 
+// The residual-path scan of a post-norm stack (x_{l+1} = RMSnorm(lambda_l (.) x_l + block_l(x_l))); g holds the
+// state gradients taken through the norm that made each state.  See scan_post_kernel.
+struct PostScanArgs {
+  void* g;              // [L+1,N,d] storage
+  const void* dn;       // [L,N,d] storage: block input gradients (with e_l already added when e is NULL), or NULL
+  const void* e;        // [L+1,N,d] storage or NULL: added per state
+  const void* e_top;    // [N,d] storage: e_L (modes 0 and 2)
+  const void* x;        // [L+1,N,d] storage: the (normalised) states
+  const float* lambda;  // [L,d] or NULL
+  const float* rho;     // [L,N]: 1/rms of the sums
+  const float* m_old;   // [L,N]: mean(G_{l+1} (.) x_{l+1}) of the previous estimate (mode 0 with dn)
+  float* m_new;         // [L,N]: the same of this one
+  long N, d;
+  long l_lo, l_hi;      // mode 0: layers l_hi-1 .. l_lo with l_hi = L; mode 1: the one layer l_lo (l_hi = l_lo + 1);
+  int mode;             // mode 2: l_hi = L, no layer
+  float gamma;          // mode 0: the residual path is scaled by 1 - gamma
+  float blk_gamma;      // mode 0: gamma lambda_l (.) g[l+1]^{old} is added to the block term (0: the old g is not read)
+};
+hipError_t launch_scan_post(int dtype, const PostScanArgs& a, hipStream_t s);
+hipError_t launch_rmsnorm_inplace(int dtype, void* x, float* rinv, long rows, long d, float eps, hipStream_t s);
+
 // x := max(x, 0) over n elements (n % 8 == 0), mask bit = 1 where x was positive; g := g (.) mask bits
 hipError_t launch_relu_mask(int dtype, void* x, uint8_t* mask, long n, hipStream_t s);
 hipError_t launch_mask_apply(int dtype, void* g, const uint8_t* mask, long n, hipStream_t s);

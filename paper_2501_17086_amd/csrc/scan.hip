@@ -611,6 +611,160 @@ size_t scan_chunk_ws_bytes(long L, long N, long d, int norm_rms) {
 }
 
 namespace {
+// ---------------------------------------------------------------------------
+// Post-norm stacks, x_{l+1} = RMSnorm(s_l), s_l = lambda_l (.) x_l + block_l(x_l), rho_l = 1/rms(s_l):
+// K_l = diag(lambda_l rho_l) and J_l = F_l - K_l (F_l the layer's Jacobian).  With the norm's backward
+// P_l(G) = rho_l (G - x_{l+1} mean(G (.) x_{l+1})), the gradient with respect to the sum, the block VJP
+// and the parameter gradients start from P_l(G_{l+1}); that is what g[l+1] holds (g[0] holds G_0).  With
+// m_l = mean(G_{l+1} (.) x_{l+1}):  G_{l+1} J_l = P(G) . dblock/dx - lambda_l rho_l x_{l+1} m_l, so one
+// iteration's scan is
+//   G_l = e_l + dn_l - lambda_l rho_l x_{l+1} m_l^{old} + lambda_l rho_l G_{l+1}      (G: fp32 carry)
+//   m_{l-1} = mean(G_l (.) x_l),  g[l] = rho_{l-1} (G_l - x_l m_{l-1})                (l >= 1)
+// One wavefront per token row (the means are wave reductions); x_l is read once and serves both the
+// projection of G_l and, one step further down, the correction term.
+// With the re-split by gamma (K' = (1 - gamma) K, J' = J + gamma K) the old G_{l+1} is needed as well; it is
+// recovered from what is stored, G = g/rho + x m, which turns the step into
+//   G_l = e_l + dn_l + gamma lambda_l g[l+1]^{old} + (1 - gamma) lambda_l rho_l (G_{l+1} - x_{l+1} m_l^{old})
+// (gamma = 1: the exact step applied to the old estimate, i.e. fixed-point iteration).  Without it the iteration
+// diverges on deep post-norm stacks: J holds the norm's rank-one term of size one per layer.
+// mode 0: the iteration's scan from the top (seeds g[L] from e_L, needs l_hi = L);
+// mode 1: one step of exact backpropagation for layer l_lo: G_l = e_l + dn_l + lambda_l (.) g[l+1];
+// mode 2: only g[L] = P_{L-1}(e_L).
+// ---------------------------------------------------------------------------
+template <typename T, int NCH, bool GAMMA>
+__global__ __launch_bounds__(256) void scan_post_kernel(PostScanArgs a) {
+  const int lane = threadIdx.x & 63;
+  const long row = (long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (row >= a.N) return;
+  const long layer = a.N * a.d;
+  T* g = reinterpret_cast<T*>(a.g);
+  const T* dn = reinterpret_cast<const T*>(a.dn);
+  const T* e = reinterpret_cast<const T*>(a.e);
+  const T* x = reinterpret_cast<const T*>(a.x);
+  const float inv_d = 1.0f / (float)a.d;
+  long off[NCH];
+  bool on[NCH];
+  float carry[NCH][8], xn[NCH][8];
+  float gold[GAMMA ? NCH : 1][8];    // the old g[l+1]
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const long c = (long)j * 512 + lane * 8;
+    on[j] = c < a.d;
+    off[j] = row * a.d + c;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) { carry[j][i] = 0.f; xn[j][i] = 0.f; gold[GAMMA ? j : 0][i] = 0.f; }
+  }
+  const float keep = 1.f - a.gamma;
+  // G (fp32, in `carry`) of state l, projected through the norm that made x_l and stored as g[l]
+  auto project_store = [&](long l) {
+    float dot = 0.f;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      if (on[j]) load8(x + l * layer + off[j], xn[j]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) dot = fmaf(carry[j][i], xn[j][i], dot);
+    }
+    const float m = wave_sum(dot) * inv_d;
+    const float rp = a.rho[(l - 1) * a.N + row];
+    if (lane == 0) a.m_new[(l - 1) * a.N + row] = m;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      if (!on[j]) continue;
+      float o[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] = rp * (carry[j][i] - xn[j][i] * m);
+      store8(g + l * layer + off[j], o);
+    }
+  };
+  if (a.mode != 1) {   // the top: G_L = e_L
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      if (!on[j]) continue;
+      load8(reinterpret_cast<const T*>(a.e_top) + off[j], carry[j]);
+      if (GAMMA) load8(g + a.l_hi * layer + off[j], gold[GAMMA ? j : 0]);
+    }
+    project_store(a.l_hi);
+    if (a.mode == 2) return;
+  }
+  for (long l = a.l_hi - 1; l >= a.l_lo; --l) {
+    const float rl = a.rho[l * a.N + row];
+    const float mo = (a.mode == 0 && dn) ? a.m_old[l * a.N + row] : 0.f;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      if (!on[j]) continue;
+      float t[8], lam[8];
+      if (dn) {
+        load8(dn + l * layer + off[j], t);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t[i] = 0.f;
+      }
+      if (e) {
+        float ee[8];
+        load8(e + l * layer + off[j], ee);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t[i] += ee[i];
+      }
+      if (a.lambda) {
+        load8(a.lambda + l * a.d + (long)j * 512 + lane * 8, lam);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) lam[i] = 1.f;
+      }
+      if (a.mode == 0 && GAMMA) {
+        float gl[8];
+        if (l >= 1) load8(g + l * layer + off[j], gl);     // the old g[l], for the step below
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          t[i] = fmaf(a.blk_gamma * lam[i], gold[GAMMA ? j : 0][i], t[i]);
+          carry[j][i] = fmaf(keep * lam[i] * rl, carry[j][i] - xn[j][i] * mo, t[i]);
+          gold[GAMMA ? j : 0][i] = gl[i];
+        }
+      } else if (a.mode == 0) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) carry[j][i] = fmaf(keep * lam[i] * rl, carry[j][i] - xn[j][i] * mo, t[i]);
+      } else {
+        float gn[8];
+        load8(g + (l + 1) * layer + off[j], gn);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) carry[j][i] = fmaf(lam[i], gn[i], t[i]);
+      }
+    }
+    if (l >= 1) {
+      project_store(l);
+    } else {
+#pragma unroll
+      for (int j = 0; j < NCH; ++j)
+        if (on[j]) store8(g + off[j], carry[j]);
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_inplace_kernel(T* x, float* rinv, long rows, long d, float eps) {
+  const int lane = threadIdx.x & 63;
+  const long row = (long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  T* xr = x + row * d;
+  float ss = 0.f;
+  for (long c = lane * 8; c < d; c += 512) {
+    float v[8];
+    load8(xr + c, v);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ss = fmaf(v[i], v[i], ss);
+  }
+  ss = wave_sum(ss);
+  const float r = 1.0f / sqrtf(ss / (float)d + eps);
+  if (lane == 0) rinv[row] = r;
+  for (long c = lane * 8; c < d; c += 512) {
+    float v[8];
+    load8(xr + c, v);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] *= r;
+    store8(xr + c, v);
+  }
+}
+
 // x := max(x, 0) and one mask bit per element (1 where x was positive), 8 elements per thread
 template <typename T>
 __global__ __launch_bounds__(256) void relu_mask_kernel(T* __restrict__ x, uint8_t* __restrict__ mask, long nvec) {
@@ -639,6 +793,41 @@ __global__ __launch_bounds__(256) void mask_apply_kernel(T* __restrict__ g, cons
   store8(g + i * 8, v);
 }
 }  // namespace
+
+template <typename T>
+hipError_t launch_scan_post_t(const PostScanArgs& a, hipStream_t s) {
+  const int nch = (int)((a.d + 511) / 512);
+  dim3 grid((unsigned)((a.N + 3) / 4)), block(256);
+  if (a.blk_gamma != 0.f && a.mode == 0) {
+    switch (nch) {
+      case 1: hipLaunchKernelGGL((scan_post_kernel<T, 1, true>), grid, block, 0, s, a); break;
+      case 2: hipLaunchKernelGGL((scan_post_kernel<T, 2, true>), grid, block, 0, s, a); break;
+      case 3: case 4: hipLaunchKernelGGL((scan_post_kernel<T, 4, true>), grid, block, 0, s, a); break;
+      default: return hipErrorInvalidValue;   // (rejected by the caller: d > 2048)
+    }
+    return hipGetLastError();
+  }
+  switch (nch) {
+    case 1: hipLaunchKernelGGL((scan_post_kernel<T, 1, false>), grid, block, 0, s, a); break;
+    case 2: hipLaunchKernelGGL((scan_post_kernel<T, 2, false>), grid, block, 0, s, a); break;
+    case 3: case 4: hipLaunchKernelGGL((scan_post_kernel<T, 4, false>), grid, block, 0, s, a); break;
+    case 5: case 6: case 7: case 8: hipLaunchKernelGGL((scan_post_kernel<T, 8, false>), grid, block, 0, s, a); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_scan_post(int dtype, const PostScanArgs& a, hipStream_t s) {
+  if (a.mode == 0 && a.l_hi <= a.l_lo) return hipErrorInvalidValue;
+  return dtype == 0 ? launch_scan_post_t<float>(a, s) : launch_scan_post_t<bf16_t>(a, s);
+}
+
+hipError_t launch_rmsnorm_inplace(int dtype, void* x, float* rinv, long rows, long d, float eps, hipStream_t s) {
+  dim3 grid((unsigned)((rows + 3) / 4)), block(256);
+  if (dtype == 0) hipLaunchKernelGGL(rmsnorm_inplace_kernel<float>, grid, block, 0, s, (float*)x, rinv, rows, d, eps);
+  else hipLaunchKernelGGL(rmsnorm_inplace_kernel<bf16_t>, grid, block, 0, s, (bf16_t*)x, rinv, rows, d, eps);
+  return hipGetLastError();
+}
 
 hipError_t launch_relu_mask(int dtype, void* x, uint8_t* mask, long n, hipStream_t s) {
   const long nvec = n / 8;

@@ -48,7 +48,7 @@ class Workload:
     w2_scale: float = 1.0
     rec_scale: float = 1.0   # extra factor on W_h and W_o (rnn variants)
     loss_every_state: bool = False
-    post: str = "none"   # 'none' | 'relu': what the residual function applies after the sum
+    post: str = "none"   # 'none' | 'relu' | 'rms': what the residual function applies after the sum
     gate_bias: float = 0.0   # 'gated': constant added to the update gate's pre-activation (see make_inputs)
     eps: float = 1e-6
     ks: tuple = (1, 2, 3, 4)
@@ -75,6 +75,9 @@ WORKLOADS: Dict[str, Workload] = {
     # the same stack with the original ResNet's residual function: a ReLU after the sum
     "resnet_postact": Workload("resnet_postact", "mlp", "bf16", "gelu", "rms", L=32, N=8192, d=512, d_ff=2048,
                                lam="uniform", lam_lo=0.9, lam_hi=1.0, w2_scale=1.0 / np.sqrt(32.0), post="relu"),
+    # a post-norm stack (the norm after the sum instead of inside the block), transformer widths
+    "postnorm_mlp": Workload("postnorm_mlp", "mlp", "bf16", "gelu", "none", L=24, N=8192, d=1024, d_ff=4096,
+                             w1_std=0.02, w2_std=0.02, post="rms"),
     # large deep stack
     "deep_large": Workload("deep_large", "mlp", "bf16", "gelu", "rms", L=96, N=16384, d=2048, d_ff=8192,
                            lam="uniform", lam_lo=0.8, lam_hi=1.0, w1_std=0.02, w2_std=0.02,

@@ -40,6 +40,8 @@ def oracle_saved_rounded(w: synth.Workload, sv):
     for k in ("x", "y", "z", "dphi"):
         out[k] = r(sv[k])
     out["rinv"] = sv["rinv"].astype(np.float32).astype(np.float64)
+    if "rpost" in sv:
+        out["rpost"] = sv["rpost"].astype(np.float32).astype(np.float64)
     if w.act == "tanh":        # the GPU derives act' from the stored z
         out["dphi"] = 1.0 - out["z"] ** 2
     if w.norm == "none":
@@ -65,7 +67,7 @@ def upload_saved(p, w: synth.Workload, sv_r):
         put(p.lam, sv_r["a"])
         return
     put(p.y, sv_r["y"])
-    put(p.rinv, sv_r["rinv"])
+    put(p.rinv, sv_r["rpost"] if w.post == "rms" else sv_r["rinv"])
     put(p.z, sv_r["z"])
     put(p.dphi, sv_r["dphi"])
     if p.mask is not None:     # one bit per element, channel 8c+j in bit j of byte c
@@ -79,9 +81,9 @@ def mask_bits(p) -> np.ndarray:
 
 
 def as_kept(st: O.Stack, sv, G: np.ndarray) -> np.ndarray:
-    """State gradients in the form the library keeps them: with a ReLU after the sum, g[l >= 1] is the oracle's
-    gradient of state l taken through that ReLU (the oracle's own through_r); unchanged otherwise."""
-    if st.post != "relu":
+    """State gradients in the form the library keeps them: with a ReLU or a norm after the sum, g[l >= 1] is the
+    oracle's gradient of state l taken through it (the oracle's own through_r); unchanged otherwise."""
+    if st.post == "none":
         return G
     out = G.copy()
     for l in range(st.L):

@@ -53,7 +53,7 @@ def test_workspace_size_scales():
 @pytest.mark.parametrize("field,value,status", [
     ("L", 0, 1), ("N", -1, 1), ("d", 0, 1), ("d", 60, 2), ("d_ff", 100, 2), ("kind", 7, 1), ("dtype", 3, 1),
     ("act", 5, 1), ("norm", 2, 1), ("lambda_kind", 9, 1), ("loss_every_state", 2, 1), ("struct_size", 12, 1),
-    ("d_in", 8, 1), ("gamma", -0.1, 1), ("gamma", 1.5, 1), ("gamma", float("nan"), 1), ("post", 2, 1), ("post", -1, 1),
+    ("d_in", 8, 1), ("gamma", -0.1, 1), ("gamma", 1.5, 1), ("gamma", float("nan"), 1), ("post", 3, 1), ("post", -1, 1),
 ])
 def test_bad_descriptor_is_rejected(field, value, status):
     d = _desc()
@@ -109,6 +109,18 @@ def test_lstm_descriptor_rules():
     assert B.lib().hbp_workspace_size(C.byref(_desc(**{**ok, "lambda_token": False})), C.byref(n)) == 1
     # both halves of [c | h] must be whole 16-byte vectors
     assert B.lib().hbp_workspace_size(C.byref(_desc(**{**ok, "d": 72, "d_ff": 144})), C.byref(n)) == 2
+
+
+def test_post_norm_descriptor_rules():
+    n = C.c_size_t(0)
+    ok = dict(norm="none", post="rms")
+    assert B.lib().hbp_workspace_size(C.byref(_desc(**ok)), C.byref(n)) == 0
+    assert B.lib().hbp_workspace_size(C.byref(_desc(**ok, gamma=0.5)), C.byref(n)) == 0
+    assert B.lib().hbp_workspace_size(C.byref(_desc(post="rms")), C.byref(n)) == 2          # a norm inside the block too
+    assert B.lib().hbp_workspace_size(C.byref(_desc(**ok, lambda_token=True)), C.byref(n)) == 2
+    assert B.lib().hbp_workspace_size(C.byref(_desc(**ok, d=4096 + 8)), C.byref(n)) == 2
+    assert B.lib().hbp_workspace_size(C.byref(_desc(**ok, d=4096, gamma=0.5)), C.byref(n)) == 2
+    assert B.lib().hbp_scan_workspace_size(C.byref(_desc(**ok)), 3, C.byref(n)) == 2
 
 
 def test_null_pointers_and_workspace_are_checked_before_launch():

@@ -73,7 +73,8 @@ def _run(B, w, ks, rows_count, shared_state=False, check_exact=True):
     if shared_state:
         # the oracle's forward state of the sampled rows, rounded to storage, replaces the library's
         sv = H.oracle_saved_rounded(w, sv)
-        for name, t in (("x", p.x), ("y", p.y), ("z", p.z), ("dphi", p.dphi), ("rinv", p.rinv)):
+        for name, t in (("x", p.x), ("y", p.y), ("z", p.z), ("dphi", p.dphi),
+                        ("rpost" if w.post == "rms" else "rinv", p.rinv)):
             if t is not None:
                 t[:, rows_t] = torch.from_numpy(sv[name].astype(np.float32)).to(t.device).to(t.dtype)
         if p.mask is not None:
@@ -111,6 +112,13 @@ def test_resnet_postact_full_shared_state(B):
     # forwards' masks differ in a fraction of a percent of the elements; the backward is compared on the oracle's
     # forward state (its mask included) for the sampled rows
     _run(B, W["resnet_postact"], ks=(1, 2, 4), rows_count=40, shared_state=True)
+
+
+@pytest.mark.timeout(300)
+def test_postnorm_mlp_full_shared_state(B):
+    # 24 post-norm layers: compared on the oracle's forward state for the sampled rows (the two forwards differ by
+    # storage rounding, which the iteration without gamma amplifies with k on such a stack)
+    _run(B, W["postnorm_mlp"], ks=(0, 1, 2), rows_count=16, shared_state=True)
 
 
 @pytest.mark.timeout(300)

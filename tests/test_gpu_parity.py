@@ -107,6 +107,17 @@ CASES = {
     # the general one (resnet_like_small and transformer_small take the same route with one whole tile)
     "ragged_tokens": synth.scaled(W["resnet_like"], name="ragged_tokens", L=3, N=600, d=256, d_ff=512,
                                   w2_scale=1 / np.sqrt(3.0), ks=(0, 1, 3)),
+    # post-norm stacks (RMS norm after the sum): one and two 512-channel chunks per row, fp32 without whole tiles and
+    # with a loss on every state, whole 256-row tiles
+    "postnorm_small": synth.scaled(W["postnorm_mlp"], name="postnorm_small", L=6, N=333, d=512, d_ff=1024,
+                                   ks=(0, 1, 2, 6)),
+    "postnorm_wide": synth.scaled(W["postnorm_mlp"], name="postnorm_wide", L=4, N=130, d=1024, d_ff=512,
+                                  lam="uniform", lam_lo=0.8, lam_hi=1.0, ks=(0, 1, 3)),
+    "postnorm_aligned": synth.scaled(W["postnorm_mlp"], name="postnorm_aligned", L=9, N=512, d=256, d_ff=512,
+                                     ks=(0, 2, 4)),
+    "postnorm_f32": synth.scaled(W["postnorm_mlp"], name="postnorm_f32", dtype="f32", L=5, N=203, d=72, d_ff=136,
+                                 w1_std=0.0, w2_std=0.0, lam="uniform", lam_lo=0.8, lam_hi=1.0,
+                                 loss_every_state=True, ks=(0, 1, 2, 5)),
     # a loss on every state of a depth stack (e read by the scan behind the norm's backward), and without a norm
     # (e added by the second contraction's epilogue)
     # coefficients per (block, token, channel): direct scans (depth, RMS and none) and the chunked scan (time)
@@ -195,7 +206,7 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
                                   "rnn_token_gates_f32", "mlp_token_gates", "rnn_rows_40", "rnn_width_96",
                                   "postact_f32_none", "gated_small", "gated_f32", "gated_long", "gated_width_72",
                                   "gated_aligned", "lstm_small", "lstm_f32", "lstm_long", "lstm_width_80",
-                                  "lstm_aligned", "ragged_tokens"])
+                                  "lstm_aligned", "ragged_tokens", "postnorm_f32", "postnorm_small"])
 def test_backward_end_to_end(B, name):
     """Own forward on each side, then Highway-BP at every k of the case, exact BP
     and the parameter gradients."""
@@ -232,6 +243,19 @@ def test_forward_of_the_lstm_cell(B, name):
     assert float(p.lam[..., w.d // 2:].abs().max()) == 0.0
 
 
+@pytest.mark.parametrize("name", ["postnorm_small", "postnorm_wide", "postnorm_f32"])
+def test_forward_of_a_post_norm_stack(B, name):
+    """Normalised states and the norm's 1/rms of each sum."""
+    w = CASES[name]
+    inp, st, sv, p = _setup(B, w)
+    B.hbp_forward(p)
+    torch.cuda.synchronize()
+    tol = H.TOL[w.dtype]
+    assert H.rel(H.to_np(p.x), sv["x"]) < tol
+    assert H.rel(H.to_np(p.rinv), sv["rpost"]) < tol
+    assert H.rel(H.to_np(p.z), sv["z"]) < tol
+
+
 @pytest.mark.parametrize("name", ["postact_rms", "postact_wide", "postact_f32_none", "postact_f32_deep"])
 def test_forward_with_relu_after_the_sum(B, name):
     """States and the ReLU's mask.  A sum within rounding of zero may land on the other side in the
@@ -253,7 +277,8 @@ def test_forward_with_relu_after_the_sum(B, name):
 
 @pytest.mark.parametrize("name", ["mlp_f32_ragged", "resnet_like_small", "rnn_small", "rnn_chaotic_small",
                                   "postact_rms", "postact_wide", "postact_aligned", "postact_f32_none",
-                                  "postact_f32_deep", "gated_small", "gated_long", "lstm_small", "lstm_long"])
+                                  "postact_f32_deep", "gated_small", "gated_long", "lstm_small", "lstm_long",
+                                  "postnorm_small", "postnorm_wide", "postnorm_aligned", "postnorm_f32"])
 def test_backward_shared_state(B, name):
     """Both backward passes read the same (storage-rounded) forward state."""
     w = CASES[name]
@@ -273,7 +298,9 @@ def test_backward_shared_state(B, name):
                                         ("aligned_small", 0.8), ("rnn_token_gates", 0.4),
                                         ("rnn_token_gates_long", 1.0), ("mlp_token_gates", 0.3),
                                         ("gated_small", 0.3), ("gated_long", 1.0), ("gated_f32", 0.6),
-                                        ("lstm_small", 0.3), ("lstm_long", 0.7)])
+                                        ("lstm_small", 0.3), ("lstm_long", 0.7),
+                                        ("postnorm_small", 0.5), ("postnorm_wide", 0.8), ("postnorm_f32", 1.0),
+                                        ("postnorm_aligned", 0.2)])
 def test_gamma_iterates(B, name, gamma):
     """The iteration on the re-split pair (J + gamma K, (1 - gamma) K): every k of
     the case against the oracle on a shared forward state; gamma = 1 is the
@@ -288,12 +315,13 @@ def test_gamma_iterates(B, name, gamma):
         B.hbp_param_grads(p)
         torch.cuda.synchronize()
         want = O.hbp_backward(st, sv_r, inp["e"], k, gamma=gamma)
-        err = H.rel(H.to_np(p.g), want)
+        kept = H.as_kept(st, sv_r, want)
+        err = H.rel(H.to_np(p.g), kept)
         assert err < tol, f"{name} gamma={gamma} k={k}: g rel L2 {err:.3e}"
         for l in range(w.L + 1):
-            n = np.linalg.norm(want[l])
+            n = np.linalg.norm(kept[l])
             if n > 1e-30:   # (at gamma = 1 and a loss on the last state only, states below L - k are exactly 0)
-                el = H.rel(H.to_np(p.g[l]), want[l])
+                el = H.rel(H.to_np(p.g[l]), kept[l])
                 assert el < 2 * tol, f"{name} gamma={gamma} k={k} state {l}: {el:.3e}"
             else:
                 assert float(p.g[l].abs().max()) == 0.0
@@ -305,7 +333,7 @@ def test_gamma_iterates(B, name, gamma):
         B.hbp_backward(p, w.L, gamma=gamma)
         torch.cuda.synchronize()
         G = O.exact_backward(st, sv_r, inp["e"])
-        assert H.rel(H.to_np(p.g), G) < tol
+        assert H.rel(H.to_np(p.g), H.as_kept(st, sv_r, G)) < tol
 
 
 @pytest.mark.parametrize("name", ["mlp_f32_ragged", "resnet_like_small", "rnn_small", "rnn_f32", "rnn_long",
@@ -327,7 +355,8 @@ def test_initial_estimate_by_every_form_of_the_scan(B, name, algorithm):
             assert H.rel(H.to_np(p.g[l]), want[l]) < 2 * H.TOL[w.dtype], f"{name} {algorithm} state {l}"
 
 
-@pytest.mark.parametrize("name", ["postact_rms", "postact_f32_none", "postact_f32_deep"])
+@pytest.mark.parametrize("name", ["postact_rms", "postact_f32_none", "postact_f32_deep", "postnorm_small",
+                                  "postnorm_f32"])
 @pytest.mark.parametrize("algorithm", ["auto", "sequential"])
 def test_initial_estimate_with_relu_after_the_sum(B, name, algorithm):
     """w^0 along K_l = diag(mask_l lambda_l) on the oracle's forward state (its mask uploaded); the
