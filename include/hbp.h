@@ -23,7 +23,9 @@
  *    the parameter gradients are always fp32.
  *  - The library never allocates or frees device memory and never
  *    synchronises: kernels are enqueued on `stream` (a hipStream_t passed as
- *    void*; NULL = the default stream) and the call returns at once.
+ *    void*; NULL = the default stream) and the call returns at once.  The
+ *    backward calls can therefore be recorded into a HIP graph by stream
+ *    capture and replayed (with timing by hbp_profile_enable off).
  *  - Inputs are read-only.  g, the workspace and the outputs must not alias
  *    the inputs or each other.
  *  - Errors are return codes, found before anything is launched: bad enum or

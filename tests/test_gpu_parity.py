@@ -438,3 +438,39 @@ def test_error_codes_on_device_buffers(B):
     B.hbp_forward(p)
     B.hbp_backward(p, 1)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name", ["aligned_small", "rnn_aligned", "gated_small", "postact_rms"])
+def test_calls_can_be_captured_in_a_graph_and_replayed(B, name):
+    """The backward calls allocate nothing and never synchronise, so a caller may record them into a HIP graph:
+    every replay, with eager work and synchronisations between them, gives the eager result bit for bit."""
+    w = CASES[name]
+    inp, st, sv, p = _setup(B, w)
+    B.hbp_forward(p)
+
+    def step():
+        B.hbp_backward(p, 2)
+        B.hbp_param_grads(p)
+    step()
+    torch.cuda.synchronize()
+    ref_g, ref_w = p.g.clone(), p.dW1.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):       # a first run on the capturing side, as torch's capture protocol asks
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    torch.cuda.synchronize()
+    for _ in range(3):
+        p.g.fill_(float("nan"))
+        p.dW1.fill_(float("nan"))
+        B.hbp_exact_backward(p)          # eager work between the replays
+        torch.cuda.synchronize()
+        p.g.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(p.g, ref_g)
+        assert torch.equal(p.dW1, ref_w)
