@@ -118,6 +118,14 @@ CASES = {
     "postnorm_f32": synth.scaled(W["postnorm_mlp"], name="postnorm_f32", dtype="f32", L=5, N=203, d=72, d_ff=136,
                                  w1_std=0.0, w2_std=0.0, lam="uniform", lam_lo=0.8, lam_hi=1.0,
                                  loss_every_state=True, ks=(0, 1, 2, 5)),
+    # the cells with a loss on the last state only (g[L] seeded by a copy, no e in the second contraction's epilogue
+    # or in the LSTM's elementwise kernel), and a ReLU stack with a norm and a loss on every state (e read by the scan)
+    "gated_last_loss": synth.scaled(W["gru_cell"], name="gated_last_loss", L=23, N=6, d=64, d_ff=128, d_in=32,
+                                    loss_every_state=False, ks=(0, 1, 3)),
+    "lstm_last_loss": synth.scaled(W["lstm_cell"], name="lstm_last_loss", L=23, N=6, d=128, d_ff=256, d_in=32,
+                                   loss_every_state=False, ks=(0, 1, 3)),
+    "postact_loss_all": synth.scaled(W["resnet_postact"], name="postact_loss_all", L=7, N=96, d=128, d_ff=256,
+                                     w2_scale=1 / np.sqrt(7.0), loss_every_state=True, ks=(0, 1, 2, 7)),
     # a loss on every state of a depth stack (e read by the scan behind the norm's backward), and without a norm
     # (e added by the second contraction's epilogue)
     # coefficients per (block, token, channel): direct scans (depth, RMS and none) and the chunked scan (time)
@@ -206,7 +214,8 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
                                   "rnn_token_gates_f32", "mlp_token_gates", "rnn_rows_40", "rnn_width_96",
                                   "postact_f32_none", "gated_small", "gated_f32", "gated_long", "gated_width_72",
                                   "gated_aligned", "lstm_small", "lstm_f32", "lstm_long", "lstm_width_80",
-                                  "lstm_aligned", "ragged_tokens", "postnorm_f32", "postnorm_small"])
+                                  "lstm_aligned", "ragged_tokens", "postnorm_f32", "postnorm_small",
+                                  "gated_last_loss", "lstm_last_loss"])
 def test_backward_end_to_end(B, name):
     """Own forward on each side, then Highway-BP at every k of the case, exact BP
     and the parameter gradients."""
@@ -278,7 +287,8 @@ def test_forward_with_relu_after_the_sum(B, name):
 @pytest.mark.parametrize("name", ["mlp_f32_ragged", "resnet_like_small", "rnn_small", "rnn_chaotic_small",
                                   "postact_rms", "postact_wide", "postact_aligned", "postact_f32_none",
                                   "postact_f32_deep", "gated_small", "gated_long", "lstm_small", "lstm_long",
-                                  "postnorm_small", "postnorm_wide", "postnorm_aligned", "postnorm_f32"])
+                                  "postnorm_small", "postnorm_wide", "postnorm_aligned", "postnorm_f32",
+                                  "postact_loss_all"])
 def test_backward_shared_state(B, name):
     """Both backward passes read the same (storage-rounded) forward state."""
     w = CASES[name]
