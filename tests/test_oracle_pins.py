@@ -944,3 +944,28 @@ def test_post_norm_finite_termination_and_k0():
         for i in range(st.L + 1):
             if k >= st.L - i:
                 np.testing.assert_allclose(w[i], G[i], rtol=1e-11, atol=1e-13)
+
+
+# ---------------------------------------------------------------- stored results of the oracle itself
+def test_oracle_reproduces_its_stored_results():
+    """tests/golden/oracle_small.txt (written by tests/golden/make_golden.py from the oracle alone): one tiny stack
+    per kind of layer; guards the oracle's arithmetic against accidental change."""
+    import importlib.util
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "make_golden.py"))
+    mg = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mg)
+    stored = {}
+    for line in open(os.path.join(here, "oracle_small.txt")):
+        if line.startswith("#"):
+            continue
+        parts = line.split()
+        stored[(parts[0], parts[1])] = np.array([float(t) for t in parts[2:]])
+    seen = 0
+    for name, (st, x0, xin, e) in mg.cases().items():
+        for q, v in mg.results(st, x0, xin, e).items():
+            np.testing.assert_allclose(np.asarray(v).ravel(), stored[(name, q)], rtol=1e-12, atol=1e-14,
+                                       err_msg=f"{name} {q}")
+            seen += 1
+    assert seen == len(stored) and seen >= 6 * 7
