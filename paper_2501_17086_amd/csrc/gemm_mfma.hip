@@ -871,22 +871,37 @@ bool launch_gemm_mfma(const GemmArgs& g, hipStream_t s, hipError_t* err) {
   const bool lean = lean_ok(g);
   const bool bf16_out = !g.addf && !g.c_is_f32 && g.split_k == 1;
   if (a_kc && b_rc && !act) {            // VJP contractions
-    // A row count that is no multiple of the tile (any number of tokens): the whole tiles go to the aligned
-    // kernel, the last rows to the general one in a second launch.  Rows are independent, both launches
-    // write disjoint rows of C.
+    // Row or column counts that are no multiple of the tile (any number of tokens, any width): the whole tiles go
+    // to the aligned kernel, the remaining columns and then the remaining rows to the general one in launches of
+    // their own.  The parts write disjoint blocks of C.
     const bool fast_mode = g.mode == EPI_STORE || g.mode == EPI_MUL_AUX || g.mode == EPI_MUL_1MZ2 || g.mode == EPI_ADD_AUX;
-    if (!lean && bf16_out && fast_mode && g.M > BM && g.M % BM != 0 && g.N % BN == 0 && g.K % BK == 0) {
-      GemmArgs head = g, tail = g;
-      head.M = g.M / BM * BM;
-      tail.M = g.M - head.M;
-      tail.A = reinterpret_cast<const bf16_t*>(g.A) + head.M * g.a_sm;
-      tail.C = reinterpret_cast<bf16_t*>(g.C) + head.M * g.ldc;
-      if (g.aux) tail.aux = reinterpret_cast<const bf16_t*>(g.aux) + head.M * g.ldc;
-      hipError_t e1 = hipSuccess;
-      launch_gemm_mfma(head, s, &e1);
-      if (e1 != hipSuccess) { *err = e1; return true; }
-      *err = launch_variant<true, false, false>(tail, s);
-      return true;
+    if (!lean && bf16_out && fast_mode && g.K % BK == 0) {
+      if (g.N > BN && g.N % BN != 0) {
+        GemmArgs head = g, tail = g;
+        head.N = g.N / BN * BN;
+        tail.N = g.N - head.N;
+        tail.B = reinterpret_cast<const bf16_t*>(g.B) + head.N;
+        tail.C = reinterpret_cast<bf16_t*>(g.C) + head.N;
+        if (g.aux) tail.aux = reinterpret_cast<const bf16_t*>(g.aux) + head.N;
+        hipError_t e1 = hipSuccess;
+        launch_gemm_mfma(head, s, &e1);
+        if (e1 != hipSuccess) { *err = e1; return true; }
+        *err = launch_variant<true, false, false>(tail, s);
+        return true;
+      }
+      if (g.M > BM && g.M % BM != 0 && g.N % BN == 0) {
+        GemmArgs head = g, tail = g;
+        head.M = g.M / BM * BM;
+        tail.M = g.M - head.M;
+        tail.A = reinterpret_cast<const bf16_t*>(g.A) + head.M * g.a_sm;
+        tail.C = reinterpret_cast<bf16_t*>(g.C) + head.M * g.ldc;
+        if (g.aux) tail.aux = reinterpret_cast<const bf16_t*>(g.aux) + head.M * g.ldc;
+        hipError_t e1 = hipSuccess;
+        launch_gemm_mfma(head, s, &e1);
+        if (e1 != hipSuccess) { *err = e1; return true; }
+        *err = launch_variant<true, false, false>(tail, s);
+        return true;
+      }
     }
     if (lean && bf16_out && g.mode == EPI_STORE) *err = launch_lean<true, false, FAST_STORE>(g, s);
     else if (lean && bf16_out && g.mode == EPI_MUL_AUX) *err = launch_lean<true, false, FAST_MUL_AUX>(g, s);
@@ -894,6 +909,30 @@ bool launch_gemm_mfma(const GemmArgs& g, hipStream_t s, hipError_t* err) {
     else if (lean && bf16_out && g.mode == EPI_ADD_AUX) *err = launch_lean<true, false, FAST_ADD_AUX>(g, s);
     else *err = launch_variant<true, false, false>(g, s);
   } else if (a_rc && b_rc && !act) {     // parameter gradients
+    // the same split for widths that are no multiple of the tile (fp32 result or split-K partial sums)
+    if (!lean && plain && (g.c_is_f32 || g.split_k > 1) && g.K % ((long)g.split_k * BK) == 0) {
+      const bool by_rows = g.M > BM && g.M % BM != 0;
+      const bool by_cols = !by_rows && g.N > BN && g.N % BN != 0 && g.M % BM == 0;
+      if (by_rows || by_cols) {
+        GemmArgs head = g, tail = g;
+        if (by_rows) {
+          head.M = g.M / BM * BM;
+          tail.M = g.M - head.M;
+          tail.A = reinterpret_cast<const bf16_t*>(g.A) + head.M;          // a_sm == 1
+          tail.C = reinterpret_cast<float*>(g.C) + head.M * g.ldc;
+        } else {
+          head.N = g.N / BN * BN;
+          tail.N = g.N - head.N;
+          tail.B = reinterpret_cast<const bf16_t*>(g.B) + head.N;          // b_sn == 1
+          tail.C = reinterpret_cast<float*>(g.C) + head.N;
+        }
+        hipError_t e1 = hipSuccess;
+        launch_gemm_mfma(head, s, &e1);
+        if (e1 != hipSuccess) { *err = e1; return true; }
+        *err = launch_variant<false, false, false>(tail, s);
+        return true;
+      }
+    }
     if (lean && plain && (g.c_is_f32 || g.split_k > 1)) *err = launch_lean<false, false, FAST_STORE_F32>(g, s);
     else *err = launch_variant<false, false, false>(g, s);
   } else if (a_kc && b_kc) {             // forward

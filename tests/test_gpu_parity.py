@@ -126,6 +126,10 @@ CASES = {
                                    loss_every_state=False, ks=(0, 1, 3)),
     "postact_loss_all": synth.scaled(W["resnet_postact"], name="postact_loss_all", L=7, N=96, d=128, d_ff=256,
                                      w2_scale=1 / np.sqrt(7.0), loss_every_state=True, ks=(0, 1, 2, 7)),
+    # widths that are no multiple of the 256-wide tile (320 = 256 + 64, 640 = 512 + 128) with 640 tokens: every
+    # contraction is split into a part on the aligned kernel and row / column remainders on the general one
+    "odd_widths": synth.scaled(W["resnet_like"], name="odd_widths", L=3, N=640, d=320, d_ff=640,
+                               w2_scale=1 / np.sqrt(3.0), ks=(0, 1, 3)),
     # a loss on every state of a depth stack (e read by the scan behind the norm's backward), and without a norm
     # (e added by the second contraction's epilogue)
     # coefficients per (block, token, channel): direct scans (depth, RMS and none) and the chunked scan (time)
@@ -215,7 +219,7 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
                                   "postact_f32_none", "gated_small", "gated_f32", "gated_long", "gated_width_72",
                                   "gated_aligned", "lstm_small", "lstm_f32", "lstm_long", "lstm_width_80",
                                   "lstm_aligned", "ragged_tokens", "postnorm_f32", "postnorm_small",
-                                  "gated_last_loss", "lstm_last_loss"])
+                                  "gated_last_loss", "lstm_last_loss", "odd_widths"])
 def test_backward_end_to_end(B, name):
     """Own forward on each side, then Highway-BP at every k of the case, exact BP
     and the parameter gradients."""
