@@ -150,3 +150,38 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(B, "LIB_PATH", "/nonexistent/libhbp.so")
     with pytest.raises(RuntimeError):
         B.lib()
+
+
+def test_header_compiles_as_c_and_links(tmp_path):
+    """include/hbp.h is plain C: a C99 program that fills the two structs positionally, asks for the workspace
+    size and has its NULL pointers reported, compiled with gcc against the built library."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "use_hbp.c"
+    src.write_text(r'''
+#include "hbp.h"
+#include <stdio.h>
+int main(void) {
+  hbp_desc d = { sizeof d, HBP_MLP, HBP_BF16, HBP_ACT_GELU_ERF, HBP_NORM_RMS, HBP_LAMBDA_CHANNEL, 0, 1e-6f,
+                 2, 8, 64, 128, 0, 0.f, HBP_POST_NONE };
+  size_t ws = 0;
+  if (hbp_workspace_size(&d, &ws) != HBP_OK || ws == 0) return 1;
+  hbp_buffers b = { sizeof b };
+  b.workspace_bytes = ws;
+  if (hbp_check(&d, &b) != HBP_E_NULL) return 2;
+  if (hbp_backward(&d, 1, &b, NULL) != HBP_E_NULL) return 3;      /* found before anything is launched */
+  printf("%s\n", hbp_status_string(HBP_E_NULL));
+  return 0;
+}
+''')
+    exe = tmp_path / "use_hbp"
+    libdir = os.path.join(root, "paper_2501_17086_amd")
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(root, "include"), str(src),
+                        "-L", libdir, "-lhbp", f"-Wl,-rpath,{libdir}", "-o", str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
+    assert "NULL" in r.stdout
