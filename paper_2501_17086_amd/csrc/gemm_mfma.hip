@@ -884,7 +884,7 @@ bool launch_gemm_mfma(const GemmArgs& g, hipStream_t s, hipError_t* err) {
         tail.C = reinterpret_cast<bf16_t*>(g.C) + head.N;
         if (g.aux) tail.aux = reinterpret_cast<const bf16_t*>(g.aux) + head.N;
         hipError_t e1 = hipSuccess;
-        launch_gemm_mfma(head, s, &e1);
+        if (!launch_gemm_mfma(head, s, &e1)) { *err = launch_variant<true, false, false>(g, s); return true; }
         if (e1 != hipSuccess) { *err = e1; return true; }
         *err = launch_variant<true, false, false>(tail, s);
         return true;
@@ -897,7 +897,7 @@ bool launch_gemm_mfma(const GemmArgs& g, hipStream_t s, hipError_t* err) {
         tail.C = reinterpret_cast<bf16_t*>(g.C) + head.M * g.ldc;
         if (g.aux) tail.aux = reinterpret_cast<const bf16_t*>(g.aux) + head.M * g.ldc;
         hipError_t e1 = hipSuccess;
-        launch_gemm_mfma(head, s, &e1);
+        if (!launch_gemm_mfma(head, s, &e1)) { *err = launch_variant<true, false, false>(g, s); return true; }
         if (e1 != hipSuccess) { *err = e1; return true; }
         *err = launch_variant<true, false, false>(tail, s);
         return true;
@@ -927,7 +927,7 @@ bool launch_gemm_mfma(const GemmArgs& g, hipStream_t s, hipError_t* err) {
           tail.C = reinterpret_cast<float*>(g.C) + head.N;
         }
         hipError_t e1 = hipSuccess;
-        launch_gemm_mfma(head, s, &e1);
+        if (!launch_gemm_mfma(head, s, &e1)) { *err = launch_variant<false, false, false>(g, s); return true; }
         if (e1 != hipSuccess) { *err = e1; return true; }
         *err = launch_variant<false, false, false>(tail, s);
         return true;
