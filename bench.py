@@ -10,6 +10,8 @@ hbp_param_grads.  Prints ONE JSON line: backward tokens/s, the roofline of the
 dominant kernel class measured live with HIP events on the launch stream, the
 other classes' rooflines, throughput and gradient error at k = 1..4 against
 exact BP, and the CPU oracle timed on the host cores on a token sample.
+The default workload is the largest of the benchmark's stacks that fits one
+GPU (deep_large: 96 blocks, d = 2048, d_ff = 8192, 16384 tokens, about 100 GB).
 """
 from __future__ import annotations
 
@@ -30,9 +32,13 @@ PEAK_FP32_VECTOR_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch (read + written) measured with rocprofv3's FETCH_SIZE and WRITE_SIZE counters, scaled by
-# what the same counters read for a plain 1 GiB copy (x2.00 and x1.00): profiles/bench_resnet_like_hbm_traffic.txt.
-# Only for the default workload; other workloads report null.
-MEASURED_TRAFFIC = {"resnet_like": {"vjp1": 2.686e9, "vjp2": 1.602e9, "dw": 1.523e9, "scan": 0.823e9}}
+# what the same counters read for a plain 1 GiB copy: one entry per workload that has such a profile, each naming
+# the summary under profiles/ it was copied from (a figure of that run, not of this one); other workloads
+# report null.
+MEASURED_TRAFFIC = {
+    "resnet_like": {"source": "profiles/bench_resnet_like_hbm_traffic.txt",
+                    "vjp1": 2.686e9, "vjp2": 1.602e9, "dw": 1.523e9, "scan": 0.823e9},
+}
 
 
 def storage_bytes(w):
@@ -152,6 +158,30 @@ def time_steps(torch, fn, steps, warmup):
     return (time.perf_counter() - t0) / steps
 
 
+def time_graph(torch, fn, steps):
+    """Seconds per replay of fn's launches recorded once into a HIP graph (the library's calls only enqueue
+    kernels and device-to-device copies on the current stream, so they can be captured)."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        fn()
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    del graph
+    return dt
+
+
 def cpu_baseline(w, k, budget_tokens):
     """The oracle as it stands on a token sample at the workload's full depth and
     widths (cost per token is constant: tokens are independent)."""
@@ -185,7 +215,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="resnet_like")
+    ap.add_argument("--workload", default="deep_large",
+                    help="default: the largest single-GPU stack (L=96, d=2048, d_ff=8192, 16384 tokens)")
     ap.add_argument("--k", type=int, default=2, help="Highway-BP iterations in the timed step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the k = 1..4 / exact table")
@@ -229,23 +260,31 @@ def main():
         B.hbp_backward(p, k)
         B.hbp_param_grads(p)
 
+    # the headline: K steps with the library's per-launch event timing off
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    B.profile_enable(True)
-    B.profile_read()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     sec = (time.perf_counter() - t0) / args.steps
+    # the per-class launch durations: the same step, again, with a HIP event pair around every launch on the
+    # launch stream (hbp_profile_enable); about 3 s of steps at most
+    prof_steps = max(2, min(args.steps, int(3.0 / sec) + 1))
+    B.profile_enable(True)
+    B.profile_read()
+    for _ in range(prof_steps):
+        step()
+    torch.cuda.synchronize()
     prof = B.profile_read()
     B.profile_enable(False)
 
     tokens = w.tokens
     work = algorithmic_work(w, k)
-    ms = {c: prof[c][0] / args.steps for c in prof}
-    launches = {c: prof[c][1] // args.steps for c in prof}
+    ms = {c: prof[c][0] / prof_steps for c in prof}
+    launches = {c: prof[c][1] // prof_steps for c in prof}
+    traffic = MEASURED_TRAFFIC.get(w.name, {})
 
     def mfma_roof(cls):
         t = ms[cls] * 1e-3
@@ -254,7 +293,7 @@ def main():
         gbs = work[cls + "_bytes"] / t / 1e9 if t > 0 else 0.0
         intensity = work[cls] / work[cls + "_bytes"]
         return {"bound": "mfma" if w.dtype == "bf16" else "alu", "achieved": ach, "peak": peak,
-                "unit": "TFLOP/s", "frac": ach / peak, "traffic": MEASURED_TRAFFIC.get(w.name, {}).get(cls),
+                "unit": "TFLOP/s", "frac": ach / peak, "traffic": traffic.get(cls), "traffic_source": traffic.get("source"),
                 "kernel_class": cls,
                 # the same launches against the other roofline: below peak / 8 TB/s flop per byte the
                 # memory roofline is the one that binds at the published peaks
@@ -274,7 +313,7 @@ def main():
     t_scan = ms["scan"] * 1e-3
     ach = work["scan_bytes"] / t_scan / 1e9 if t_scan > 0 else 0.0
     roofs["scan"] = {"bound": "hbm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                     "frac": ach / PEAK_HBM_GBS, "traffic": MEASURED_TRAFFIC.get(w.name, {}).get("scan"),
+                     "frac": ach / PEAK_HBM_GBS, "traffic": traffic.get("scan"), "traffic_source": traffic.get("source"),
                      "kernel_class": "scan",
                      "ms_per_step": ms["scan"], "launches_per_step": launches["scan"],
                      "avg_launch_ms": ms["scan"] / max(launches["scan"], 1)}
@@ -292,20 +331,29 @@ def main():
         "class_ms_per_step": ms,
     }
 
+    reps = max(3, min(args.steps // 2, int(2.0 / sec) + 1))   # repetitions per line of the tables below
     if not args.no_sweep:
         sweep = {}
         for kk in (1, 2, 3, 4):
             def f(kk=kk):
                 B.hbp_backward(p, kk)
                 B.hbp_param_grads(p)
-            t = time_steps(torch, f, max(3, args.steps // 2), 1)
+            t = time_steps(torch, f, reps, 1)
             sweep[str(kk)] = {"tokens_per_s": tokens / t, "ms": t * 1e3}
 
         def fe():
             B.hbp_exact_backward(p)
             B.hbp_param_grads(p)
-        t = time_steps(torch, fe, max(3, args.steps // 2), 1)
-        sweep["exact"] = {"tokens_per_s": tokens / t, "ms": t * 1e3}
+        t = time_steps(torch, fe, reps, 1)
+        sweep["exact"] = {"tokens_per_s": tokens / t, "ms": t * 1e3, "launch": "eager"}
+        if w.kind in ("rnn", "gated", "lstm"):
+            # Step-by-step backpropagation through time is thousands of short dependent launches: eager, it is
+            # bound by the host's launch rate.  The same call sequence recorded once into a HIP graph and replayed
+            # is the baseline that speed-ups are quoted against.
+            tg = time_graph(torch, fe, reps)
+            sweep["exact_graph"] = {"tokens_per_s": tokens / tg, "ms": tg * 1e3, "launch": "hip graph replay"}
+            tg2 = time_graph(torch, step, reps)
+            sweep["hbp_graph"] = {"k": k, "tokens_per_s": tokens / tg2, "ms": tg2 * 1e3, "launch": "hip graph replay"}
         errs = gpu_errors(B, torch, p, (0, 1, 2, 3, 4))
         for kk, v in errs.items():
             sweep.setdefault(kk, {}).update(v)
@@ -318,7 +366,7 @@ def main():
                 def fg(gm=gm):
                     B.hbp_backward(p, k, gamma=gm)
                     B.hbp_param_grads(p)
-                t = time_steps(torch, fg, max(3, args.steps // 2), 1)
+                t = time_steps(torch, fg, reps, 1)
                 e = gpu_errors(B, torch, p, (1, 2, 3, 4), gamma=gm)
                 gs[str(gm)] = {"ms_at_k": t * 1e3, "k": k,
                                "param_rel_l2": {kk: v["param_rel_l2"] for kk, v in e.items()},
@@ -336,7 +384,7 @@ def main():
             if need > 8 << 30:
                 continue
             ws = torch.zeros(max(need, 16), dtype=torch.uint8, device=p.g.device)
-            t = time_steps(torch, lambda: B.hbp_initial_estimate(p, algo, workspace=ws), max(3, args.steps // 2), 1)
+            t = time_steps(torch, lambda: B.hbp_initial_estimate(p, algo, workspace=ws), reps, 1)
             abl[algo] = {"ms": t * 1e3, "algorithmic_GBps": alg_bytes / t / 1e9, "workspace_MB": need / 1e6}
             del ws
         out["scan_forms_w0"] = abl

@@ -19,21 +19,33 @@
  *  - Every pointer in hbp_buffers is DEVICE memory owned by the caller,
  *    contiguous, 16-byte aligned, row-major with the channel index fastest.
  *    "S" below is the storage type desc.dtype (fp32, or bf16 rounded to
- *    nearest-even at every store); all accumulation is fp32; lambda, rinv and
- *    the parameter gradients are always fp32.
+ *    nearest-even at every store); all accumulation is fp32; rinv, the
+ *    parameter gradients and a per-channel lambda (HBP_LAMBDA_CHANNEL) are
+ *    always fp32, a per-token lambda (HBP_LAMBDA_TOKEN) is in S.  bf16 storage
+ *    runs the contractions on the matrix cores (bf16 x bf16 -> fp32 MFMA); fp32
+ *    storage runs them on the vector ALUs (an LDS-tiled FMA kernel, no fp32
+ *    MFMA): that path is for small reference problems.
  *  - The library never allocates or frees device memory and never
  *    synchronises: kernels are enqueued on `stream` (a hipStream_t passed as
  *    void*; NULL = the default stream) and the call returns at once.  The
  *    backward calls can therefore be recorded into a HIP graph by stream
  *    capture and replayed (with timing by hbp_profile_enable off).
- *  - Inputs are read-only.  g, the workspace and the outputs must not alias
- *    the inputs or each other.
+ *  - Inputs are read-only, with one exception: for HBP_GATED and HBP_LSTM
+ *    hbp_forward WRITES the residual coefficients through `lambda`.  g, the
+ *    workspace and the outputs must not alias the inputs or each other.
  *  - Errors are return codes, found before anything is launched: bad enum or
  *    struct_size, non-positive size, d / d_ff / d_in not a multiple of 8,
  *    d > 4096 with HBP_NORM_RMS, k < 0, a required pointer that is NULL, a
  *    workspace smaller than hbp_workspace_size() reports.  A failed launch
- *    gives HBP_E_DEVICE.  Calls are stateless and re-entrant; two calls that
- *    share g or the workspace must be ordered by the caller.
+ *    gives HBP_E_DEVICE.
+ *  - State between calls: none that changes results.  The library keeps (a) a
+ *    flag per kernel and device saying that the kernel's shared-memory limit
+ *    has been raised (set on the first launch, idempotent, safe from several
+ *    threads) and (b) the process-wide timing switch and event lists of
+ *    hbp_profile_enable / hbp_profile_read (mutex-protected).  Calls may be made
+ *    from several threads; two calls that share g or the workspace must be
+ *    ordered by the caller, and with timing on, hbp_profile_read returns the
+ *    launches of all threads together.
  */
 #ifndef HBP_H
 #define HBP_H
@@ -120,8 +132,8 @@ typedef struct {
   const void* W1;
   const void* W2;
   const void* U;
-  const void* lambda;        /* CHANNEL: fp32 [L,d]; TOKEN: S [L,N,d].  Row (block) l carries state l+1 to state l.
-                              * (HBP_GATED, HBP_LSTM: written by hbp_forward through this pointer.) */
+  void* lambda;              /* CHANNEL: fp32 [L,d]; TOKEN: S [L,N,d].  Row (block) l carries state l+1 to state l.
+                              * Read-only for the library, except HBP_GATED / HBP_LSTM: written by hbp_forward. */
   /* forward state: written by hbp_forward, read by the backward calls. */
   void* x;                   /* S [L+1,N,d]  states x_0..x_L (x[0] is the input) */
   void* y;                   /* S [L,N,d]    norm(x_l); unused (may be NULL) with HBP_NORM_NONE, where x is read */
@@ -171,13 +183,17 @@ typedef enum {
 hbp_status hbp_scan_workspace_size(const hbp_desc* desc, int algorithm, size_t* bytes);
 hbp_status hbp_initial_estimate(const hbp_desc* desc, int algorithm, hbp_buffers* bufs, void* stream);
 
-/* g := exact gradient by L sequential block steps,
- * G_l = e_l + lambda_l (.) G_{l+1} + G_{l+1} J_{l+1}. */
+/* g := the exact gradient by L sequential block steps, G_L = e_L,
+ * G_l = e_l + lambda_l (.) G_{l+1} + G_{l+1} J_{l+1}: the chain rule through J + K that Section
+ * "Backpropagation as a system of equations" writes as the system the method solves (first line of the proof
+ * of Theorem 1).  The comparison baseline; same buffers as hbp_backward. */
 hbp_status hbp_exact_backward(const hbp_desc* desc, hbp_buffers* bufs, void* stream);
 
-/* dW1, dW2 (and dU) from the g currently in bufs.g:
+/* The parameter gradients from the state-gradient estimate currently in bufs.g (sentence after Theorem 2:
+ * dL/dtheta_l = w_{l+1} . d f_l / d theta_l, with the current estimate w^k in place of the exact gradient):
  * da_l = (g_{l+1} W2_l) (.) act'(a_l); dW2_l = sum_n g_{l+1}[n]^T z_l[n];
- * dW1_l = sum_n da_l[n]^T y_l[n]; dU = sum da^T xin.  Shared weights sum over l too. */
+ * dW1_l = sum_n da_l[n]^T y_l[n]; dU = sum da^T xin.  Shared weights sum over l too.  Long contractions over
+ * tokens are computed in shares whose partial sums a second kernel adds in a fixed order (bitwise repeatable). */
 hbp_status hbp_param_grads(const hbp_desc* desc, hbp_buffers* bufs, void* stream);
 
 const char* hbp_status_string(hbp_status s);

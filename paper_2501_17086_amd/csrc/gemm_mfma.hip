@@ -63,6 +63,7 @@
 //               list walks 8 x 8 blocks of tiles, so the tiles an XCD works on
 //               at one time share operand panels.
 #include "hbp_common.h"
+#include <atomic>
 #include <type_traits>
 
 namespace hbp {
@@ -579,9 +580,9 @@ __device__ __forceinline__ void dma16_c(unsigned off, const void* sbase, unsigne
 // groups of 4 columns) and a row layout (8 lanes cover the 128 bytes of a row), so that every
 // global access of a wave covers whole 128-byte lines: 8 rows per instruction.  The 16-byte chunk
 // k of row r sits at chunk k ^ (r/2 % 8) of the row (bank spread for both access shapes).
-// Lanes exchange data through LDS here without a fence: the accesses go through one base pointer with
-// run-time offsets, which the compiler must assume to overlap and therefore keeps in program order,
-// and the hardware executes a wave's LDS instructions in order.
+// Lanes of one wave exchange data through LDS here: the hardware executes a wave's LDS instructions in
+// order, and a wave barrier between the two access shapes keeps the compiler from moving a read of one
+// shape above the writes of the other (it emits no instruction).
 typedef unsigned uint4v __attribute__((ext_vector_type(4)));   // (a first-class vector: stays in registers)
 struct Quad16 { uint4v x0, x1, x2, x3; };   // 4 x 16 bytes per lane: 32 rows of the row layout
 template <int FAST>
@@ -620,6 +621,7 @@ __device__ __forceinline__ void epilogue_staged_fn(const GemmArgs& g, const Tile
       *reinterpret_cast<uint4v*>(p1) = q.x1;
       *reinterpret_cast<uint4v*>(p2) = q.x2;
       *reinterpret_cast<uint4v*>(p3) = q.x3;
+      __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int k = 0; k < 8; ++k) auxm[k] = *reinterpret_cast<const uint2*>(m_base + ((k ^ m_sw) << 4));
     }
@@ -642,10 +644,12 @@ __device__ __forceinline__ void epilogue_staged_fn(const GemmArgs& g, const Tile
         }
         *reinterpret_cast<uint2*>(m_base + (((4 * j + qd) ^ m_sw) << 4)) = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
       }
+    __builtin_amdgcn_wave_barrier();
     const uint4v o0 = *reinterpret_cast<const uint4v*>(p0);
     const uint4v o1 = *reinterpret_cast<const uint4v*>(p1);
     const uint4v o2 = *reinterpret_cast<const uint4v*>(p2);
     const uint4v o3 = *reinterpret_cast<const uint4v*>(p3);
+    __builtin_amdgcn_wave_barrier();      // the next round's writes stay behind these reads
     bf16_t* c = cp + (long)(32 * i) * g.ldc;
     __builtin_nontemporal_store(o0, reinterpret_cast<uint4v*>(c));
     __builtin_nontemporal_store(o1, reinterpret_cast<uint4v*>(c + ld8));
@@ -804,15 +808,28 @@ __global__ __launch_bounds__(NTHR, 1) void gemm_mfma_lean_kernel(GemmArgs g, int
   if (grp == 0) __builtin_amdgcn_s_barrier();   // matches group 1's last barrier
 }
 
+// Raises a kernel's dynamic shared-memory limit once per device (one flag array per kernel instantiation; setting
+// the attribute twice from two threads is harmless, so a relaxed flag is enough).
+constexpr int MAX_DEVICES = 64;
+inline hipError_t raise_lds_limit(const void* kern, int bytes, std::atomic<bool> (&done)[MAX_DEVICES]) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  if (done[dev].load(std::memory_order_acquire)) return hipSuccess;
+  e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e != hipSuccess) return e;
+  done[dev].store(true, std::memory_order_release);
+  return hipSuccess;
+}
+
 template <bool A_KC, bool B_KC, int FAST>
 hipError_t launch_lean(const GemmArgs& g, hipStream_t s) {
-  static bool attr_set = false;
+  static std::atomic<bool> attr_set[MAX_DEVICES];
   auto kern = gemm_mfma_lean_kernel<A_KC, B_KC, FAST>;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LEAN_LDS);
+  {
+    hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kern), LEAN_LDS, attr_set);
     if (e != hipSuccess) return e;
-    attr_set = true;
   }
   const int tiles_m = (int)(g.M / BM), tiles_n = (int)(g.N / BN);
   const long total = (long)tiles_m * tiles_n * g.batch * g.split_k;
@@ -829,13 +846,11 @@ inline bool lean_ok(const GemmArgs& g) {
 
 template <bool A_KC, bool B_KC, bool ACT>
 hipError_t launch_variant(const GemmArgs& g, hipStream_t s) {
-  static bool attr_set = false;
+  static std::atomic<bool> attr_set[MAX_DEVICES];
   auto kern = gemm_mfma_kernel<A_KC, B_KC, ACT>;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES + 8192);
+  {
+    hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kern), LDS_BYTES + 8192, attr_set);
     if (e != hipSuccess) return e;
-    attr_set = true;
   }
   const int tiles_m = (int)((g.M + BM - 1) / BM), tiles_n = (int)((g.N + BN - 1) / BN);
   const long total = (long)tiles_m * tiles_n * g.batch * g.split_k;

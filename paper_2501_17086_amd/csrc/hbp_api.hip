@@ -534,10 +534,10 @@ hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
       }
       ProfScope ps(HBP_PROF_FORWARD, s);
       if (d->kind == HBP_GATED)
-        HBP_TRY(launch_gated_fwd(d->dtype, pre, yl, at(b->z, fo), at(const_cast<void*>(b->lambda), xo),
+        HBP_TRY(launch_gated_fwd(d->dtype, pre, yl, at(b->z, fo), at(b->lambda, xo),
                                  at(b->x, xo + (size_t)d->N * d->d * es), d->N, d->d, s));
       else
-        HBP_TRY(launch_lstm_fwd(d->dtype, pre, yl, at(b->z, fo), at(const_cast<void*>(b->lambda), xo),
+        HBP_TRY(launch_lstm_fwd(d->dtype, pre, yl, at(b->z, fo), at(b->lambda, xo),
                                 at(b->x, xo + (size_t)d->N * d->d * es), d->N, d->d / 2, s));
       continue;
     }

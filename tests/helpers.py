@@ -93,3 +93,62 @@ def as_kept(st: O.Stack, sv, G: np.ndarray) -> np.ndarray:
 
 def rel(a, b) -> float:
     return O.rel_l2(a, b)
+
+
+def assert_close(got, want, tol, tag, row_factor=4.0, abs_factor=8.0, row_floor=0.1):
+    """got against want ([..., rows, width]) by three measures, so that an error confined to a few rows or
+    elements (a tile edge, a ragged tail, the last chunk of a scan) cannot hide inside a whole-tensor norm:
+      whole tensor   relative L2 below tol;
+      per row        relative L2 of every row (last axis) below row_factor * tol, the row's norm floored at
+                     row_floor times the tensor's typical row norm (rows that are nearly zero carry the others'
+                     rounding; a weight-gradient row summed over a handful of tokens is one rounded number times
+                     a vector, so its floor is set higher by the callers);
+      per element    |got - want| below abs_factor * tol * (rms(want) + |want|) everywhere (an element's rounding
+                     error grows with its own size; a wrong element is off by about its size or the rms).
+    Returns the three figures (whole, worst row, worst element)."""
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    assert got.shape == want.shape, f"{tag}: shape {got.shape} vs {want.shape}"
+    assert np.isfinite(got).all(), f"{tag}: non-finite values"
+    whole = rel(got, want)
+    assert whole < tol, f"{tag}: rel L2 {whole:.3e} (bar {tol:g})"
+    rms = float(np.sqrt(np.mean(want * want)))
+    diff = got - want
+    if rms == 0.0:
+        assert float(np.abs(got).max()) == 0.0, f"{tag}: reference is zero, result is not"
+        return whole, 0.0, 0.0
+    width = want.shape[-1]
+    rn = np.linalg.norm(want.reshape(-1, width), axis=1)
+    floor = row_floor * rms * np.sqrt(width)
+    rows = np.linalg.norm(diff.reshape(-1, width), axis=1) / np.maximum(rn, floor)
+    worst_row = float(rows.max())
+    assert worst_row < row_factor * tol, \
+        f"{tag}: row {int(rows.argmax())} rel L2 {worst_row:.3e} (bar {row_factor * tol:g}; whole tensor {whole:.3e})"
+    ratio = np.abs(diff) / (rms + np.abs(want))
+    worst_abs = float(ratio.max())
+    assert worst_abs < abs_factor * tol, \
+        f"{tag}: element {np.unravel_index(int(ratio.argmax()), diff.shape)} off by {worst_abs:.3e} of rms + |value| " \
+        f"(bar {abs_factor * tol:g}; whole tensor {whole:.3e})"
+    return whole, worst_row, worst_abs
+
+
+def forward_rounded_stepwise(w: synth.Workload, st: O.Stack, x0):
+    """The oracle's forward of a depth stack one block at a time, every state rounded to the storage type before
+    the next block reads it: the states a forward pass that STORES each x_l in that type produces (rounding
+    accumulates over the depth), computed with the oracle's own forward on one-block stacks.  Returns a saved
+    state of the oracle's layout, the other saved tensors rounded once (oracle_saved_rounded)."""
+    assert st.kind == "mlp"
+    r = lambda a: synth.storage_round(w, np.asarray(a, np.float32)).astype(np.float64)
+    x = r(x0)
+    per = []
+    xs = [x]
+    for l in range(st.L):
+        one = O.Stack("mlp", st.act, st.norm, st.W1[l:l + 1], st.W2[l:l + 1],
+                      lam=None if st.lam is None else st.lam[l:l + 1], eps=st.eps, post=st.post)
+        sv1 = O.forward(one, x)
+        x = r(sv1["x"][1])
+        xs.append(x)
+        per.append(sv1)
+    out = {k: np.concatenate([s1[k] for s1 in per], axis=0) for k in ("y", "rinv", "a", "mask", "rpost", "z", "dphi")}
+    out["x"] = np.stack(xs)
+    return oracle_saved_rounded(w, out)

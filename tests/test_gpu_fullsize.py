@@ -2,8 +2,14 @@
 times: the library runs the whole workload; the oracle recomputes a sample of
 token rows (tokens are independent in every workload, so a row's result does
 not depend on the others) element by element; the parameter gradients, which
-sum over all tokens, are checked by random projections against a plain
-contraction of the library's own g and saved activations."""
+sum over all tokens, are checked (i) element by element against the oracle on
+runs with the token count cut to what the oracle finishes in seconds (full
+depth and widths, the contractions over tokens still split into shares), and
+(ii) at the full token count by random projections against a plain contraction
+of the library's own g and saved activations."""
+import json
+import os
+
 import numpy as np
 import pytest
 
@@ -32,29 +38,61 @@ def _sample_rows(n, count, seed):
     return rows
 
 
-def _projection_check(p, w, tol):
-    """dW2_l u == sum_n g_{l+1}[n] (z_l[n] . u) and dW1_l u == sum_n da-free form is not
-    available, so dW1 is checked through y: u^T dW1_l == sum_n (u . da_l[n]) y_l[n] needs da;
-    instead both are checked against torch contractions in fp64 on a few blocks."""
-    if w.kind in ("gated", "lstm"):   # the cells have no second weight; dW1 and dU are compared element by element at the
-        return                 # reduced sizes of test_gpu_parity
-    g = torch.Generator(device="cpu").manual_seed(7)
+def _projection_check(p, w, inp, tol):
+    """Every parameter gradient of hbp_param_grads (they sum over all tokens, so no token sample can check them)
+    against a plain contraction of the library's own g and saved state with a random vector u:
+        dW2_l u = sum_n g_{l+1}[n] (z_l[n] . u)        dW1_l u = sum_n da_l[n] (y_l[n] . u)
+        dU u    = sum_{l,n} da_l[n] (xin_l[n] . u)
+    in fp64.  da is recomputed here from g: for the two-matrix blocks as (g_{l+1} W2_l) (.) act' with torch's
+    matmul; for the cells by the oracle's block_preact_grad, step by step.  Per-block weights: three blocks;
+    shared weights: the one sum over all steps."""
+    gen = torch.Generator(device="cpu").manual_seed(7)
+    dev = p.g.device
     L = w.L
-    blocks = sorted({0, L // 2, L - 1}) if w.kind == "mlp" else [0]
-    for l in blocks:
-        if w.kind == "mlp":
-            gl, zl = p.g[l + 1].double(), p.z[l].double()
-            u = torch.randn(w.d_ff, generator=g, dtype=torch.float64).to(gl.device)
-            want = gl.T @ (zl @ u)
-            got = p.dW2[l].double() @ u
-        else:
-            gl = p.g[1:].reshape(-1, w.d).double()
-            zl = p.z.reshape(-1, w.d_ff).double()
-            u = torch.randn(w.d_ff, generator=g, dtype=torch.float64).to(gl.device)
-            want = gl.T @ (zl @ u)
-            got = p.dW2.double() @ u
+
+    def check(name, dW, left, right):
+        """dW [r, c] u  against  left^T (right u), u random in R^c."""
+        u = torch.randn(dW.shape[1], generator=gen, dtype=torch.float64).to(dev)
+        got, want = dW.double() @ u, left.T @ (right @ u)
         err = float((got - want).norm() / want.norm())
-        assert err < tol, f"dW2 projection, block {l}: {err:.3e}"
+        assert err < tol, f"{w.name}: {name} projection {err:.3e}"
+
+    if w.kind == "mlp":
+        for l in sorted({0, L // 2, L - 1}):
+            gl, zl = p.g[l + 1].double(), p.z[l].double()
+            yl = (p.y if p.y is not None else p.x)[l].double()
+            dphi = p.dphi[l].double() if p.dphi is not None else 1.0 - zl * zl
+            da = (gl @ p.W2[l].double()) * dphi
+            check(f"dW2[{l}]", p.dW2[l], gl, zl)
+            check(f"dW1[{l}]", p.dW1[l], da, yl)
+        return
+    g1 = p.g[1:].reshape(-1, w.d).double()
+    xin = p.xin.reshape(-1, w.d_in).double()
+    if w.kind == "rnn":
+        z = p.z.reshape(-1, w.d_ff).double()
+        y = p.x[:-1].reshape(-1, w.d).double()
+        da = (g1 @ p.W2.double()) * (1.0 - z * z)
+        check("dW2", p.dW2, g1, z)
+    else:
+        # the cells: da of every step from the oracle's own definition, on the library's g and saved state
+        st = H.oracle_stack(w, inp)
+        Hh = w.d if w.kind == "gated" else w.d // 2
+        zz = H.to_np(p.z)
+        saved = {"x": H.to_np(p.x), "u": zz[..., :Hh], "c": zz[..., Hh:], "gates": zz}
+        gg = H.to_np(p.g)
+        da_np = np.stack([O.block_preact_grad(st, l, saved, gg[l + 1]) for l in range(L)])
+        da = torch.from_numpy(da_np.reshape(-1, w.d_ff)).to(dev)
+        y = p.x[:-1][..., w.d - Hh:].reshape(-1, Hh).double()      # the part of the state the weights act on
+    check("dW1", p.dW1, da, y)
+    check("dU", p.dU, da, xin)
+
+
+def _subset(w, inp, rows):
+    sub = {k: (v[rows] if k in ("x0",) else v[:, rows] if k in ("xin",) else v) for k, v in inp.items()
+           if v is not None}
+    sub["e"] = inp["e"][:, rows] if w.loss_every_state else inp["e"][rows]
+    sub.setdefault("U", None); sub.setdefault("xin", None); sub.setdefault("lam", inp["lam"])
+    return sub
 
 
 def _run(B, w, ks, rows_count, shared_state=False, check_exact=True):
@@ -63,10 +101,7 @@ def _run(B, w, ks, rows_count, shared_state=False, check_exact=True):
     B.hbp_forward(p)
     torch.cuda.synchronize()
     rows = _sample_rows(w.N, rows_count, 3)
-    sub = {k: (v[rows] if k in ("x0",) else v[:, rows] if k in ("xin",) else v) for k, v in inp.items()
-           if v is not None}
-    sub["e"] = inp["e"][:, rows] if w.loss_every_state else inp["e"][rows]
-    sub.setdefault("U", None); sub.setdefault("xin", None); sub.setdefault("lam", inp["lam"])
+    sub = _subset(w, inp, rows)
     st = H.oracle_stack(w, sub)
     sv = O.forward(st, sub["x0"], sub["xin"])
     rows_t = torch.from_numpy(rows).to(p.x.device)
@@ -87,18 +122,60 @@ def _run(B, w, ks, rows_count, shared_state=False, check_exact=True):
         torch.cuda.synchronize()
         want = H.as_kept(st, sv, O.hbp_backward(st, sv, sub["e"], k))
         got = H.to_np(p.g[:, rows_t])
-        err = H.rel(got, want)
-        assert err < tol, f"{w.name} k={k}: g rel L2 on {len(rows)} sampled rows {err:.3e}"
-        assert np.isfinite(got).all()
-        _projection_check(p, w, 5e-3)
+        H.assert_close(got, want, tol, f"{w.name} k={k}: g on {len(rows)} sampled rows")
+        _projection_check(p, w, inp, 5e-3)
     if check_exact:
         B.hbp_exact_backward(p)
         torch.cuda.synchronize()
         want = H.as_kept(st, sv, O.exact_backward(st, sv, sub["e"]))
-        err = H.rel(H.to_np(p.g[:, rows_t]), want)
-        assert err < tol, f"{w.name} exact: g rel L2 on sampled rows {err:.3e}"
+        H.assert_close(H.to_np(p.g[:, rows_t]), want, tol, f"{w.name} exact: g on sampled rows")
     del p
     torch.cuda.empty_cache()
+
+
+def _run_cut(B, w, ks):
+    """The workload at full depth and widths with its token count cut: the library against the oracle on EVERY
+    element of every state gradient and parameter gradient."""
+    inp = synth.make_inputs(w)
+    st = H.oracle_stack(w, inp)
+    sv = O.forward(st, inp["x0"], inp["xin"])
+    p = B.allocate(w, inp)
+    B.hbp_forward(p)
+    tol = H.TOL[w.dtype]
+    for k in ks:
+        B.hbp_backward(p, k)
+        B.hbp_param_grads(p)
+        torch.cuda.synchronize()
+        want = O.hbp_backward(st, sv, inp["e"], k)
+        H.assert_close(H.to_np(p.g), want, tol, f"{w.name} k={k}: g")
+        pg = O.param_grads(st, sv, want, inp["xin"])
+        for nm, t in (("dW1", p.dW1), ("dW2", p.dW2), ("dU", p.dU)):
+            if t is not None:
+                H.assert_close(H.to_np(t), pg[nm], tol, f"{w.name} k={k}: {nm}", row_floor=0.5)
+    del p
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(300)
+def test_resnet_like_cut_to_2048_tokens_every_element(B):
+    # 32 blocks at d = 512, d_ff = 2048; 2048 tokens: the contractions over tokens run in one share
+    _run_cut(B, synth.scaled(W["resnet_like"], name="resnet_like_2048", N=2048), ks=(2,))
+
+
+@pytest.mark.timeout(300)
+def test_gated_rnn_contractive_cut_to_2_rows_every_element(B):
+    # T = 4096 steps, 2 batch rows: 8192 rows per contraction over tokens, in 4 shares (split-K); chunked scan
+    _run_cut(B, synth.scaled(W["gated_rnn_contractive"], name="gated_rnn_2rows", N=2), ks=(2,))
+
+
+@pytest.mark.timeout(300)
+def test_gru_cell_cut_to_2_rows_every_element(B):
+    _run_cut(B, synth.scaled(W["gru_cell"], name="gru_cell_2rows", N=2), ks=(2,))
+
+
+@pytest.mark.timeout(300)
+def test_lstm_cell_cut_to_2_rows_every_element(B):
+    _run_cut(B, synth.scaled(W["lstm_cell"], name="lstm_cell_2rows", N=2), ks=(2,))
 
 
 @pytest.mark.timeout(300)
@@ -148,10 +225,85 @@ def test_gated_rnn_chaotic_full_shared_state(B):
     _run(B, W["gated_rnn"], ks=(1, 2, 4), rows_count=2, shared_state=True, check_exact=False)
 
 
-@pytest.mark.timeout(900)
+def _library_state(p, w, rows_t):
+    """The forward state hbp_forward left in device memory, for the sampled rows, as the oracle's `saved`."""
+    g = lambda t: H.to_np(t[:, rows_t])
+    L = w.L
+    n = len(rows_t)
+    return {"x": g(p.x), "y": g(p.y), "z": g(p.z), "dphi": g(p.dphi), "rinv": g(p.rinv),
+            "mask": np.ones((L, n, w.d)), "rpost": np.ones((L, n))}
+
+
+@pytest.mark.timeout(1100)
 def test_deep_large_full(B):
-    # 96 blocks of bf16 storage: the two forward passes alone differ by 1e-2 in x at the top
-    # of the stack, which the ill-conditioned block Jacobians (shrinking x under RMS norm)
-    # amplify to the size of the bar.  The backward path is therefore compared on one
-    # forward state (the oracle's, rounded to storage), as for the chaotic RNN.
-    _run(B, W["deep_large"], ks=(1, 3), rows_count=6, shared_state=True)
+    """The largest stack (96 blocks, d = 2048, d_ff = 8192, 16384 tokens), on 6 sampled token rows, three ways:
+      own state     the oracle's backward run from the forward state hbp_forward itself left in memory: the
+                    backward kernels on exactly the inputs bench.py gives them (bar: 2e-2);
+      shared state  the oracle's own forward state, rounded to storage, uploaded for the sampled rows (bar: 2e-2);
+      end to end    each side on its own forward from x_0 (bar 2e-2 at k = 1).  A forward pass that stores every
+                    state in bf16 accumulates that rounding over 96 blocks (x_96 differs from the fp64 forward's
+                    by 1e-2), and the ill-conditioned block Jacobians amplify it: at k = 3 the ORACLE's backward
+                    on its own forward run with every state rounded to storage (block by block) differs from the
+                    oracle's backward on its fp64 forward by about the bar itself.  That is asserted here, beside
+                    a looser bar of 3e-2 for the library at k = 3.
+    The forward state itself (x, y, z, act', 1/rms) is held to the bar too.  Figures go to gpurun_out/."""
+    w = W["deep_large"]
+    tol = H.TOL[w.dtype]
+    inp = synth.make_inputs(w)
+    p = B.allocate(w, inp)
+    B.hbp_forward(p)
+    torch.cuda.synchronize()
+    rows = _sample_rows(w.N, 4, 3)
+    rows_t = torch.from_numpy(rows).to(p.x.device)
+    sub = _subset(w, inp, rows)
+    st = H.oracle_stack(w, sub)
+    sv_fp64 = O.forward(st, sub["x0"], None)
+    sv_round = H.oracle_saved_rounded(w, sv_fp64)
+    sv_step = H.forward_rounded_stepwise(w, st, sub["x0"])
+    sv_lib = _library_state(p, w, rows_t)
+    fig = {"rows": [int(r) for r in rows]}
+    # forward state: library against oracle
+    for nm in ("x", "y", "z", "dphi", "rinv"):
+        fig["forward_" + nm] = H.rel(sv_lib[nm], sv_fp64[nm])
+        assert fig["forward_" + nm] < tol, f"deep_large forward {nm}: {fig['forward_' + nm]:.3e}"
+    for k in (1, 3):
+        B.hbp_backward(p, k)
+        B.hbp_param_grads(p)
+        torch.cuda.synchronize()
+        got = H.to_np(p.g[:, rows_t])
+        want_lib = O.hbp_backward(st, sv_lib, sub["e"], k)
+        want_fp64 = O.hbp_backward(st, sv_fp64, sub["e"], k)
+        want_round = O.hbp_backward(st, sv_round, sub["e"], k)
+        want_step = O.hbp_backward(st, sv_step, sub["e"], k)
+        H.assert_close(got, want_lib, tol, f"deep_large k={k}, own state: g on sampled rows")
+        fig[f"k{k}_own_state"] = H.rel(got, want_lib)
+        fig[f"k{k}_end_to_end"] = H.rel(got, want_fp64)
+        fig[f"k{k}_oracle_state_rounded_once_vs_fp64_state"] = H.rel(want_round, want_fp64)
+        fig[f"k{k}_oracle_state_rounded_every_block_vs_fp64_state"] = H.rel(want_step, want_fp64)
+        _projection_check(p, w, inp, 5e-3)
+    assert fig["k1_end_to_end"] < tol, f"deep_large k=1 end to end {fig['k1_end_to_end']:.3e}"
+    assert fig["k3_end_to_end"] < 1.5 * tol, f"deep_large k=3 end to end {fig['k3_end_to_end']:.3e}"
+    # the oracle alone, on a forward whose states are rounded to storage block by block, moves by the same order
+    fig["forward_x_oracle_rounded_every_block"] = H.rel(sv_step["x"], sv_fp64["x"])
+    assert fig["k3_oracle_state_rounded_every_block_vs_fp64_state"] > 0.5 * fig["k3_end_to_end"], fig
+    # shared state
+    for name, t in (("x", p.x), ("y", p.y), ("z", p.z), ("dphi", p.dphi), ("rinv", p.rinv)):
+        t[:, rows_t] = torch.from_numpy(sv_round[name].astype(np.float32)).to(t.device).to(t.dtype)
+    for k in (1, 3):
+        B.hbp_backward(p, k)
+        torch.cuda.synchronize()
+        want = O.hbp_backward(st, sv_round, sub["e"], k)
+        H.assert_close(H.to_np(p.g[:, rows_t]), want, tol, f"deep_large k={k}, shared state: g on sampled rows")
+        fig[f"k{k}_shared_state"] = H.rel(H.to_np(p.g[:, rows_t]), want)
+    B.hbp_exact_backward(p)
+    torch.cuda.synchronize()
+    want = O.exact_backward(st, sv_round, sub["e"])
+    H.assert_close(H.to_np(p.g[:, rows_t]), want, tol, "deep_large exact, shared state: g on sampled rows")
+    fig["exact_shared_state"] = H.rel(H.to_np(p.g[:, rows_t]), want)
+    print("deep_large parity figures:", json.dumps(fig))
+    out = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(out):
+        with open(os.path.join(out, "deep_large_parity.json"), "w") as f:
+            json.dump(fig, f, indent=1)
+    del p
+    torch.cuda.empty_cache()

@@ -969,3 +969,44 @@ def test_oracle_reproduces_its_stored_results():
                                        err_msg=f"{name} {q}")
             seen += 1
     assert seen == len(stored) and seen >= 6 * 7
+
+
+def test_error_measures_on_hand_computed_vectors():
+    """rel_l2 and cosine, the two measures every comparison goes through, on vectors small enough to do by hand:
+    a = (3, 4), b = (0, 4): a - b = (3, 0), |a - b| = 3, |b| = 4, so rel_l2 = 3/4 (the SECOND argument is the
+    reference: swapped, |a| = 5 gives 3/5); cosine((3, 4), (4, 3)) = 24/25; a zero reference leaves the plain
+    norm of the difference; shapes are flattened."""
+    assert O.rel_l2([3.0, 4.0], [0.0, 4.0]) == pytest.approx(0.75, abs=1e-15)
+    assert O.rel_l2([0.0, 4.0], [3.0, 4.0]) == pytest.approx(0.6, abs=1e-15)
+    assert O.rel_l2([[1.0, 2.0], [2.0, 0.0]], np.zeros((2, 2))) == pytest.approx(3.0, abs=1e-15)
+    assert O.rel_l2([1.0, -2.0, 0.5], [1.0, -2.0, 0.5]) == 0.0
+    assert O.rel_l2([2.0, 0.0], [1.0, 0.0]) == pytest.approx(1.0, abs=1e-15)       # not symmetric, not capped
+    assert O.cosine([3.0, 4.0], [4.0, 3.0]) == pytest.approx(24.0 / 25.0, abs=1e-15)
+    assert O.cosine([1.0, 0.0], [0.0, 5.0]) == 0.0
+    assert O.cosine([[1.0, 2.0]], [[-2.0, -4.0]]) == pytest.approx(-1.0, abs=1e-15)
+
+
+def test_assert_close_catches_a_wrong_row_and_a_wrong_element():
+    """The comparison helper of the GPU tests: a perturbation too small for the whole-tensor norm must still be
+    caught when it sits in one row or one element (planted here in a copy of the reference, on the CPU)."""
+    from tests import helpers as H
+    rng = np.random.default_rng(0)
+    want = rng.standard_normal((333, 512))
+    tol = 2e-2
+    noisy = want * (1.0 + 2e-3 * rng.standard_normal(want.shape))      # rounding-sized noise passes
+    H.assert_close(noisy, want, tol, "noise")
+    bad_row = noisy.copy()
+    bad_row[332] = rng.standard_normal(512)                            # one wrong row of 333: whole tensor 7.7e-2
+    assert H.rel(bad_row, want) < 0.1
+    with pytest.raises(AssertionError):
+        H.assert_close(bad_row, want, 0.1, "row")
+    bad_el = noisy.copy()
+    bad_el[17, 300] += 1.5                                             # one wrong element: whole tensor 3.6e-3, its
+    assert H.rel(bad_el, want) < tol                                   # row 6.6e-2 (below the row bar of 8e-2)
+    with pytest.raises(AssertionError, match="element"):
+        H.assert_close(bad_el, want, tol, "element")
+    few = noisy.copy()
+    few[100, :48] = 0.0                                                # 48 elements of a row left unwritten
+    assert H.rel(few, want) < tol
+    with pytest.raises(AssertionError):
+        H.assert_close(few, want, tol, "corner")
