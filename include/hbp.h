@@ -183,6 +183,18 @@ typedef enum {
 hbp_status hbp_scan_workspace_size(const hbp_desc* desc, int algorithm, size_t* bytes);
 hbp_status hbp_initial_estimate(const hbp_desc* desc, int algorithm, hbp_buffers* bufs, void* stream);
 
+/* For callers that cannot allocate device memory or bring a workspace (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): hbp_initial_estimate(desc, HBP_SCAN_CHUNKED, ...) with the chunked
+ * scan's scratch in a fixed array inside the library instead of bufs->workspace (which is ignored and may be NULL).
+ * Same kernels, same result bit for bit.  Calls no hipMalloc / hipFree or any allocating routine.  Limit:
+ * 16 * ceil(L / 64) * N * d bytes of scratch must fit HBP_STATIC_SCRATCH_BYTES (32 MiB: T = 4096 steps of 32 x 1024
+ * chains just fit); larger problems return HBP_E_WORKSPACE, a residual function with a ReLU or norm after the sum
+ * HBP_E_UNSUPPORTED.  Every GPU the library runs on holds one such array until the process ends, and every call on
+ * a GPU shares it: it keeps the previous call's contents (each call writes what it reads, nothing needs clearing),
+ * and two calls that overlap on one GPU (different streams or threads) race on it: the caller must order them. */
+#define HBP_STATIC_SCRATCH_BYTES (32u << 20)
+hbp_status hbp_initial_estimate_static(const hbp_desc* desc, hbp_buffers* bufs, void* stream);
+
 /* g := the exact gradient by L sequential block steps, G_L = e_L,
  * G_l = e_l + lambda_l (.) G_{l+1} + G_{l+1} J_{l+1}: the chain rule through J + K that Section
  * "Backpropagation as a system of equations" writes as the system the method solves (first line of the proof

@@ -29,7 +29,7 @@ POST = {"none": 0, "relu": 1, "rms": 2}
 LAMBDA_ONE, LAMBDA_CHANNEL, LAMBDA_TOKEN = 0, 1, 2
 
 EXPORTS = ("hbp_workspace_size", "hbp_check", "hbp_forward", "hbp_backward", "hbp_exact_backward",
-           "hbp_scan_workspace_size", "hbp_initial_estimate",
+           "hbp_scan_workspace_size", "hbp_initial_estimate", "hbp_initial_estimate_static",
            "hbp_param_grads", "hbp_profile_enable", "hbp_profile_read", "hbp_status_string")
 PROF_CLASSES = ("vjp1", "vjp2", "scan", "dw", "forward", "other")
 
@@ -76,6 +76,7 @@ def lib() -> C.CDLL:
         L.hbp_exact_backward.argtypes = [C.POINTER(hbp_desc), C.POINTER(hbp_buffers), C.c_void_p]
         L.hbp_scan_workspace_size.argtypes = [C.POINTER(hbp_desc), C.c_int, C.POINTER(C.c_size_t)]
         L.hbp_initial_estimate.argtypes = [C.POINTER(hbp_desc), C.c_int, C.POINTER(hbp_buffers), C.c_void_p]
+        L.hbp_initial_estimate_static.argtypes = [C.POINTER(hbp_desc), C.POINTER(hbp_buffers), C.c_void_p]
         L.hbp_param_grads.argtypes = [C.POINTER(hbp_desc), C.POINTER(hbp_buffers), C.c_void_p]
         L.hbp_profile_enable.argtypes = [C.c_int]
         L.hbp_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
@@ -195,6 +196,21 @@ def hbp_initial_estimate(p: Problem, algorithm: str = "auto", stream=None, works
         p.workspace = saved
     _call("hbp_initial_estimate",
           lib().hbp_initial_estimate(C.byref(p.desc), SCAN_ALGORITHMS[algorithm], C.byref(b), _stream(stream)))
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def hbp_initial_estimate_static(p: Problem, stream=None) -> None:
+    """g := w^0 by the chunked scan with the library's own fixed scratch: no workspace, no allocation."""
+    saved = p.workspace
+    p.workspace = None
+    try:
+        b = p.buffers()
+    finally:
+        p.workspace = saved
+    _call("hbp_initial_estimate_static",
+          lib().hbp_initial_estimate_static(C.byref(p.desc), C.byref(b), _stream(stream)))
 
 
 def hbp_exact_backward(p: Problem, stream=None) -> None:

@@ -10,6 +10,13 @@
 
 using namespace hbp;
 
+// Scratch of hbp_initial_estimate_static, the entry point that allocates nothing and takes no workspace: the
+// chunked scan's per-chunk partial results (B, the state entering each chunk, the products A, the old state above
+// each chunk) live here instead of in a caller's workspace.  One copy per GPU the library's code object is loaded
+// on, held until the process ends.  In host code the name below is a stand-in, not a device address: host code
+// uses the pointer hipGetSymbolAddress returns for the current device (static_scratch()).
+static __device__ __align__(256) unsigned char scratch[HBP_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -686,6 +693,56 @@ hbp_status hbp_initial_estimate(const hbp_desc* d, int algorithm, hbp_buffers* b
   HBP_RUN(seed_top(d, b, s));
   return scan_stage(d, b, w, 0, d->L, false, s, d->gamma,
                     algorithm == HBP_SCAN_SEQUENTIAL ? 1 : algorithm == HBP_SCAN_CHUNKED ? 2 : 0);
+}
+
+namespace {
+// The device address of `scratch` on the current device, looked up once per device.
+hbp_status static_scratch(float** out) {
+  constexpr int MAX_DEV = 64;
+  static std::mutex mu;
+  static void* ptr[MAX_DEV] = {};
+  int dev = 0;
+  HBP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_DEV) return HBP_E_DEVICE;
+  std::lock_guard<std::mutex> lk(mu);
+  if (!ptr[dev]) {
+    void* q = nullptr;
+    HBP_TRY(hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)));
+    if (!q) return HBP_E_DEVICE;
+    ptr[dev] = q;
+  }
+  *out = reinterpret_cast<float*>(ptr[dev]);
+  return HBP_OK;
+}
+}  // namespace
+
+hbp_status hbp_initial_estimate_static(const hbp_desc* d, hbp_buffers* b, void* stream) {
+  HBP_RUN(check_desc(d));
+  if (d->post != HBP_POST_NONE) return HBP_E_UNSUPPORTED;   // as for HBP_SCAN_CHUNKED
+  if (scan_chunk_ws_bytes_forced(d->L, d->N, d->d) > (size_t)HBP_STATIC_SCRATCH_BYTES) return HBP_E_WORKSPACE;
+  if (!b) return HBP_E_NULL;
+  if (b->struct_size != sizeof(hbp_buffers)) return HBP_E_INVALID_ARG;
+  if (!b->e || !b->g) return HBP_E_NULL;
+  if (d->lambda_kind != HBP_LAMBDA_ONE && !b->lambda) return HBP_E_NULL;
+  hipStream_t s = (hipStream_t)stream;
+  float* ws = nullptr;
+  HBP_RUN(static_scratch(&ws));
+  HBP_RUN(seed_top(d, b, s));
+  // Every part of the scratch the passes read is written earlier in the same call (the reduce pass writes B, A and
+  // the old state above each chunk, the combine pass the state entering each chunk): nothing has to start at zero.
+  ScanArgs sa{};
+  sa.force = 2;
+  sa.res_scale = 1.f - d->gamma;
+  sa.g = b->g;
+  sa.e = d->loss_every_state ? b->e : nullptr;
+  sa.chunk_ws = ws;
+  sa.lambda = d->lambda_kind == HBP_LAMBDA_CHANNEL ? reinterpret_cast<const float*>(b->lambda) : nullptr;
+  sa.lambda_tok = d->lambda_kind == HBP_LAMBDA_TOKEN ? b->lambda : nullptr;
+  sa.N = d->N; sa.d = d->d;
+  sa.l_lo = 0; sa.l_hi = d->L;
+  ProfScope ps(HBP_PROF_SCAN, s);
+  HBP_TRY(launch_scan(d->dtype, sa, s));
+  return HBP_OK;
 }
 
 hbp_status hbp_exact_backward(const hbp_desc* d, hbp_buffers* b, void* stream) {
