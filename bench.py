@@ -379,9 +379,16 @@ def main():
         S_bytes = float(w.L) * w.N * w.d * storage_bytes(w)
         alg_bytes = S_bytes * (1 + (1 if w.loss_every_state else 0)
                                + (1 if (w.lam == "sigmoid_full" or w.kind in ("gated", "lstm")) else 0))
-        for algo in ("auto", "sequential") + (("chunked", "hillis_steele") if w.post == "none" else ()):
+        algos = ("auto", "sequential")
+        if w.post == "none":
+            algos += ("chunked",) + (("single_pass",) if w.dtype == "bf16" else ()) + ("hillis_steele",)
+        for algo in algos:
             need = B.scan_workspace_size(p.desc, algo)
-            if need > 8 << 30:
+            if algo in ("auto", "sequential"):       # these run in the workspace of the backward calls
+                t = time_steps(torch, lambda: B.hbp_initial_estimate(p, algo), reps, 1)
+                abl[algo] = {"ms": t * 1e3, "algorithmic_GBps": alg_bytes / t / 1e9, "workspace_MB": need / 1e6}
+                continue
+            if need > 16 << 30:
                 continue
             ws = torch.zeros(max(need, 16), dtype=torch.uint8, device=p.g.device)
             t = time_steps(torch, lambda: B.hbp_initial_estimate(p, algo, workspace=ws), reps, 1)

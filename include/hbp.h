@@ -173,12 +173,15 @@ hbp_status hbp_backward(const hbp_desc* desc, int k, hbp_buffers* bufs, void* st
 
 /* The initial estimate alone, g := w^0 = CumSumProd(e, K) (Theorem 2; K scaled by 1 - gamma), by a
  * named form of the scan: what hbp_backward picks (AUTO), the sequential walk down the chain, the
- * chunked reduce / combine / apply form, or the Hillis-Steele sweeps of the paper's Algorithm 1 (kept
- * for comparison: O(L log L) elements moved).  Same result up to rounding order.  The workspace must
+ * chunked reduce / combine / apply form (every element read twice), the single-pass form (chunks that
+ * hand their state down the chain through a chained look-back: every element read once; bf16 storage
+ * only), or the Hillis-Steele sweeps of the paper's Algorithm 1 (kept for comparison: O(L log L)
+ * elements moved).  Same result up to rounding order; each form is bitwise repeatable.  The workspace must
  * hold hbp_scan_workspace_size(desc, algorithm) bytes (CHUNKED and HILLIS_STEELE need more than the
  * backward calls; AUTO and SEQUENTIAL need hbp_workspace_size()).  Reads e, lambda; writes g. */
 typedef enum {
-  HBP_SCAN_AUTO = 0, HBP_SCAN_SEQUENTIAL = 1, HBP_SCAN_CHUNKED = 2, HBP_SCAN_HILLIS_STEELE = 3
+  HBP_SCAN_AUTO = 0, HBP_SCAN_SEQUENTIAL = 1, HBP_SCAN_CHUNKED = 2, HBP_SCAN_HILLIS_STEELE = 3,
+  HBP_SCAN_SINGLE_PASS = 4
 } hbp_scan_algorithm;
 hbp_status hbp_scan_workspace_size(const hbp_desc* desc, int algorithm, size_t* bytes);
 hbp_status hbp_initial_estimate(const hbp_desc* desc, int algorithm, hbp_buffers* bufs, void* stream);

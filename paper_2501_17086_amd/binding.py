@@ -175,7 +175,7 @@ def hbp_backward(p: Problem, k: int, stream=None, gamma: Optional[float] = None)
     _call("hbp_backward", lib().hbp_backward(C.byref(desc), int(k), C.byref(b), _stream(stream)))
 
 
-SCAN_ALGORITHMS = {"auto": 0, "sequential": 1, "chunked": 2, "hillis_steele": 3}
+SCAN_ALGORITHMS = {"auto": 0, "sequential": 1, "chunked": 2, "hillis_steele": 3, "single_pass": 4}
 
 
 def scan_workspace_size(desc: hbp_desc, algorithm: str) -> int:

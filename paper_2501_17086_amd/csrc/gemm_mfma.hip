@@ -950,8 +950,12 @@ bool launch_gemm_mfma(const GemmArgs& g, hipStream_t s, hipError_t* err) {
     }
     if (lean && plain && (g.c_is_f32 || g.split_k > 1)) *err = launch_lean<false, false, FAST_STORE_F32>(g, s);
     else *err = launch_variant<false, false, false>(g, s);
-  } else if (a_kc && b_kc) {             // forward
-    *err = act ? launch_variant<true, true, true>(g, s) : launch_variant<true, true, false>(g, s);
+  } else if (a_kc && b_kc) {             // forward; VJP contractions against transposed weights
+    if (lean && bf16_out && g.mode == EPI_STORE) *err = launch_lean<true, true, FAST_STORE>(g, s);
+    else if (lean && bf16_out && g.mode == EPI_MUL_AUX) *err = launch_lean<true, true, FAST_MUL_AUX>(g, s);
+    else if (lean && bf16_out && g.mode == EPI_MUL_1MZ2) *err = launch_lean<true, true, FAST_MUL_1MZ2>(g, s);
+    else if (lean && bf16_out && g.mode == EPI_ADD_AUX) *err = launch_lean<true, true, FAST_ADD_AUX>(g, s);
+    else *err = act ? launch_variant<true, true, true>(g, s) : launch_variant<true, true, false>(g, s);
   } else {
     return false;
   }

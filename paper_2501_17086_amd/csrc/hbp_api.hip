@@ -378,8 +378,8 @@ hbp_status scan_stage(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
   sa.y = b->y;
   sa.rinv = b->rinv;
   sa.e = (d->loss_every_state && !(has_v && e_in_vjp(d))) ? b->e : nullptr;
-  sa.chunk_ws = (force == 2 || scan_chunk_ws_bytes(d->L, d->N, d->d, d->norm == HBP_NORM_RMS))
-                    ? reinterpret_cast<float*>(at(b->workspace, force == 2 ? 0 : w.off_scan)) : nullptr;
+  sa.chunk_ws = (force >= 2 || scan_chunk_ws_bytes(d->L, d->N, d->d, d->norm == HBP_NORM_RMS))
+                    ? reinterpret_cast<float*>(at(b->workspace, force >= 2 ? 0 : w.off_scan)) : nullptr;
   sa.lambda = d->lambda_kind == HBP_LAMBDA_CHANNEL ? reinterpret_cast<const float*>(b->lambda) : nullptr;
   sa.lambda_tok = d->lambda_kind == HBP_LAMBDA_TOKEN ? b->lambda : nullptr;
   sa.N = d->N; sa.d = d->d;
@@ -655,11 +655,14 @@ hbp_status hbp_scan_workspace_size(const hbp_desc* d, int algorithm, size_t* byt
   if (!bytes) return HBP_E_NULL;
   HBP_RUN(check_desc(d));
   // a ReLU's mask or a norm after the sum is applied by the direct forms only
-  if (d->post != HBP_POST_NONE && (algorithm == HBP_SCAN_CHUNKED || algorithm == HBP_SCAN_HILLIS_STEELE))
+  if (d->post != HBP_POST_NONE && (algorithm == HBP_SCAN_CHUNKED || algorithm == HBP_SCAN_HILLIS_STEELE ||
+                                   algorithm == HBP_SCAN_SINGLE_PASS))
     return HBP_E_UNSUPPORTED;
+  if (algorithm == HBP_SCAN_SINGLE_PASS && d->dtype != HBP_BF16) return HBP_E_UNSUPPORTED;
   switch (algorithm) {
     case HBP_SCAN_AUTO: case HBP_SCAN_SEQUENTIAL: *bytes = carve(d).total; break;
     case HBP_SCAN_CHUNKED: *bytes = scan_chunk_ws_bytes_forced(d->L, d->N, d->d); break;
+    case HBP_SCAN_SINGLE_PASS: *bytes = scan_sp_ws_bytes(d->L, d->N, d->d, d->lambda_kind == HBP_LAMBDA_TOKEN); break;
     case HBP_SCAN_HILLIS_STEELE: *bytes = hs_ws_bytes(d->L, d->N, d->d, d->lambda_kind); break;
     default: return HBP_E_INVALID_ARG;
   }
@@ -692,7 +695,8 @@ hbp_status hbp_initial_estimate(const hbp_desc* d, int algorithm, hbp_buffers* b
   const Workspace w = carve(d);
   HBP_RUN(seed_top(d, b, s));
   return scan_stage(d, b, w, 0, d->L, false, s, d->gamma,
-                    algorithm == HBP_SCAN_SEQUENTIAL ? 1 : algorithm == HBP_SCAN_CHUNKED ? 2 : 0);
+                    algorithm == HBP_SCAN_SEQUENTIAL ? 1 : algorithm == HBP_SCAN_CHUNKED ? 2 :
+                    algorithm == HBP_SCAN_SINGLE_PASS ? 3 : 0);
 }
 
 namespace {

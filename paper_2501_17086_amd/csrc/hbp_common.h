@@ -17,6 +17,14 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f) {
   return (bf16_t)(u >> 16);
 }
 
+// two floats -> two bf16 in one word, round to nearest even (one v_cvt_pk_bf16_f32)
+__device__ __forceinline__ unsigned int pack_bf16x2(float a, float b) {
+  typedef float f2_t __attribute__((ext_vector_type(2)));
+  typedef __bf16 b2_t __attribute__((ext_vector_type(2)));
+  const f2_t v = {a, b};
+  return __builtin_bit_cast(unsigned int, __builtin_convertvector(v, b2_t));
+}
+
 template <typename T> struct Elem;
 template <> struct Elem<float> {
   static __device__ __forceinline__ float load(const float* p) { return *p; }
@@ -46,13 +54,27 @@ __device__ __forceinline__ void load8(const float* p, float (&o)[8]) {
 __device__ __forceinline__ void store8(bf16_t* p, const float (&v)[8]) {
   unsigned int w[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
-    w[i] = (unsigned int)f32_to_bf16(v[2 * i]) | ((unsigned int)f32_to_bf16(v[2 * i + 1]) << 16);
+  for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
   *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
 }
 __device__ __forceinline__ void store8(float* p, const float (&v)[8]) {
   *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
   *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+
+// store8 with a non-temporal hint
+__device__ __forceinline__ void store8_nt(bf16_t* p, const float (&v)[8]) {
+  typedef unsigned u4 __attribute__((ext_vector_type(4)));
+  u4 w;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) w[i] = pack_bf16x2(v[2 * i], v[2 * i + 1]);
+  __builtin_nontemporal_store(w, reinterpret_cast<u4*>(p));
+}
+__device__ __forceinline__ void store8_nt(float* p, const float (&v)[8]) {
+  typedef float f4 __attribute__((ext_vector_type(4)));
+  const f4 a = {v[0], v[1], v[2], v[3]}, b = {v[4], v[5], v[6], v[7]};
+  __builtin_nontemporal_store(a, reinterpret_cast<f4*>(p));
+  __builtin_nontemporal_store(b, reinterpret_cast<f4*>(p + 4));
 }
 
 // 8 consecutive elements as loaded, unpacked later: lets a kernel issue a batch
@@ -61,6 +83,12 @@ template <typename T> struct Raw8;
 template <> struct Raw8<bf16_t> {
   uint4 v;
   __device__ __forceinline__ void load(const bf16_t* p) { v = *reinterpret_cast<const uint4*>(p); }
+  // streamed once: non-temporal (does not displace what other kernels keep in the caches)
+  __device__ __forceinline__ void load_nt(const bf16_t* p) {
+    typedef unsigned u4 __attribute__((ext_vector_type(4)));
+    const u4 t = __builtin_nontemporal_load(reinterpret_cast<const u4*>(p));
+    v = make_uint4(t.x, t.y, t.z, t.w);
+  }
   __device__ __forceinline__ void unpack(float (&o)[8]) const {
     const unsigned int w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -75,6 +103,13 @@ template <> struct Raw8<float> {
   __device__ __forceinline__ void load(const float* p) {
     a = *reinterpret_cast<const float4*>(p);
     b = *reinterpret_cast<const float4*>(p + 4);
+  }
+  __device__ __forceinline__ void load_nt(const float* p) {
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const f4 t = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p));
+    const f4 u = __builtin_nontemporal_load(reinterpret_cast<const f4*>(p + 4));
+    a = make_float4(t.x, t.y, t.z, t.w);
+    b = make_float4(u.x, u.y, u.z, u.w);
   }
   __device__ __forceinline__ void unpack(float (&o)[8]) const {
     o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
@@ -162,7 +197,8 @@ struct ScanArgs {
   long l_lo, l_hi;
   int norm_rms;
   float* chunk_ws;      // scratch of scan_chunk_ws_bytes() for the chunked form (long chains), or NULL
-  int force;            // 0: the launcher picks the form; 1: the sequential form; 2: the chunked form (needs chunk_ws)
+  int force;            // 0: the launcher picks the form; 1: the sequential form; 2: the chunked three-pass form;
+                        // 3: the single-pass form (2 and 3 need chunk_ws; 3: bf16, one value stream, no old-estimate term)
   float res_scale;      // factor on lambda along the residual path (1 - gamma; 1 for the plain method)
   float blk_gamma;      // gamma: adds gamma lambda_l (.) g_{l+1}^{old} to v_l (0: nothing read)
   const uint8_t* mask;  // [L,N,d/8] bits or NULL: g_l (l >= 1) is multiplied by the bits of row block l-1 (the ReLU
@@ -175,6 +211,7 @@ hipError_t launch_scan(int dtype, const ScanArgs& a, hipStream_t s);
 constexpr long SCAN_CHUNK = 64;
 size_t scan_chunk_ws_bytes(long L, long N, long d, int norm_rms);
 size_t scan_chunk_ws_bytes_forced(long L, long N, long d);   // the same when the chunked form is asked for by name
+size_t scan_sp_ws_bytes(long L, long N, long d, int lambda_tok);   // scratch of the single-pass form (force = 3)
 
 // The scan in the form of the paper's Algorithm 1 (Hillis-Steele): ceil(log2(L+1)) sweeps over all
 // positions, each adding the partner 2^s positions up, in fp32 scratch.  Kept for comparison: it

@@ -4,6 +4,8 @@
 // (v_l = (dn_l - y_l * mean(dn_l (.) y_l)) * rinv_l), so dn is read once and v
 // never goes to memory.  HBM-bound: every element is read once and written once.
 #include "hbp_common.h"
+#include <atomic>
+#include <type_traits>
 
 namespace hbp {
 
@@ -194,6 +196,117 @@ __global__ __launch_bounds__(256) void scan_rows_kernel(ScanArgs a) {
       }
       store8(g + l * layer + off[j], carry[j]);
     }
+  }
+}
+
+// Sum over the 64 lanes of a wave, the same value in every lane: four rotations inside each row of 16 lanes
+// (DPP row_ror 8, 4, 2, 1: no LDS round trip), then the four row totals through scalar registers.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+  v += dpp_f<0x128>(v);
+  v += dpp_f<0x124>(v);
+  v += dpp_f<0x122>(v);
+  v += dpp_f<0x121>(v);
+  const int b = __builtin_bit_cast(int, v);
+  const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 0));
+  const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 16));
+  const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 32));
+  const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(b, 48));
+  return (r0 + r1) + (r2 + r3);
+}
+
+// The wave-per-row scan for rows of exactly NCH * 512 channels with the plain recurrence (no re-split, no
+// mask, coefficients per channel or 1), written as a software pipeline: the loads of layer l - 1 (block input
+// gradient, normalised input, coefficients, 1/rms; all as raw 16-byte vectors) are issued before the values of
+// layer l are touched, without a branch between them, so that a wave always has two layers' loads in flight
+// (the layer index is clamped at the bottom instead of guarded: the last stage is loaded twice).
+template <typename T, int NCH, bool HAS_E, bool HAS_LAM>
+__global__ __launch_bounds__(256) void scan_rows_pipe_kernel(ScanArgs a) {
+  const int lane = threadIdx.x & 63;
+  const long row = (long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (row >= a.N) return;
+  const long layer = a.N * a.d;
+  T* __restrict__ g = reinterpret_cast<T*>(a.g);
+  const T* __restrict__ dn = reinterpret_cast<const T*>(a.dn);
+  const T* __restrict__ y = reinterpret_cast<const T*>(a.y);
+  const T* __restrict__ e = reinterpret_cast<const T*>(a.e);
+  const float inv_d = 1.0f / (float)a.d;
+  const long off = row * a.d + lane * 8;          // chunk j: + 512 j
+  const long loff = lane * 8;
+
+  struct Stage {
+    Raw8<T> v[NCH], y[NCH], e[HAS_E ? NCH : 1];
+    Raw8<float> lam[HAS_LAM ? NCH : 1];
+    float rinv;
+  };
+  auto issue = [&](Stage& st, long l) {
+    const long base = l * layer + off;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      if (NCH == 1) {     // narrow rows: measured faster with the streamed operands read non-temporally (+13 %);
+        st.v[j].load_nt(dn + base + 512 * j);          // wider rows: measured slower (-3 %)
+        st.y[j].load_nt(y + base + 512 * j);
+        if (HAS_E) st.e[HAS_E ? j : 0].load_nt(e + base + 512 * j);
+      } else {
+        st.v[j].load(dn + base + 512 * j);
+        st.y[j].load(y + base + 512 * j);
+        if (HAS_E) st.e[HAS_E ? j : 0].load(e + base + 512 * j);
+      }
+      if (HAS_LAM) st.lam[HAS_LAM ? j : 0].load(a.lambda + l * a.d + loff + 512 * j);
+    }
+    st.rinv = a.rinv[l * a.N + row];
+  };
+  float carry[NCH][8];
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) load8(g + a.l_hi * layer + off + 512 * j, carry[j]);
+  auto consume = [&](const Stage& st, long l) {
+    float v[NCH][8], yy[NCH][8];
+    float dot = 0.f;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      st.v[j].unpack(v[j]);
+      st.y[j].unpack(yy[j]);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) dot = fmaf(v[j][i], yy[j][i], dot);
+    }
+    const float m = wave_sum_dpp(dot) * inv_d;
+    const float r = st.rinv;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      float t[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t[i] = (v[j][i] - yy[j][i] * m) * r;
+      if (HAS_E) {
+        float ee[8];
+        st.e[HAS_E ? j : 0].unpack(ee);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t[i] += ee[i];
+      }
+      if (HAS_LAM) {
+        float lam[8];
+        st.lam[HAS_LAM ? j : 0].unpack(lam);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) carry[j][i] = fmaf(lam[i], carry[j][i], t[i]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) carry[j][i] += t[i];
+      }
+      store8(g + l * layer + off + 512 * j, carry[j]);
+    }
+  };
+  Stage s0, s1;
+  long l = a.l_hi - 1;
+  issue(s0, l);
+  while (true) {
+    issue(s1, l - 1 > a.l_lo ? l - 1 : a.l_lo);
+    consume(s0, l);
+    if (--l < a.l_lo) break;
+    issue(s0, l - 1 > a.l_lo ? l - 1 : a.l_lo);
+    consume(s1, l);
+    if (--l < a.l_lo) break;
   }
 }
 
@@ -399,6 +512,257 @@ __global__ __launch_bounds__(256) void scan_chunk_combine_kernel(ScanArgs a, lon
   }
 }
 
+// ---------------------------------------------------------------------------
+// Single-pass form for long chains (bf16 storage, plain recurrence): every element is read once and written once.
+// A workgroup owns (chunk of SP_STEPS states, 4 token rows, 128 channels); a wave owns one row and a lane 2
+// channels, and keeps its chunk's raw values in registers (one 4-byte load per state: a wave reads 256
+// contiguous bytes).  It
+//   1. scans the chunk from a zero state: the chunk's map is  g_bottom = B + A (.) g_top;
+//   2. publishes (A, B) for the chunks below it (flag 1);
+//   3. finds the state entering the chunk: it looks at the chunks above (64 flags at a time, one per lane of the
+//      first wave) for the nearest one that has published the state X leaving it (flag 2), then applies the maps of
+//      the chunks in between to X one after the other (chained decoupled look-back).  Only maps applied to a state, never maps composed with maps: whichever
+//      chunk the walk starts from, the same operations produce the same bits, so runs are bitwise repeatable;
+//   4. publishes its own X = B + A (.) (state entering) (flag 2) and then runs the recurrence from the entering
+//      state over the registers, storing g.
+// Chunks are handed out from the top of the chain down by a ticket counter in the order the workgroups start, so
+// a workgroup only ever waits for workgroups that are already running: the waits end.  They are bounded all the
+// same: after SP_SPIN_LIMIT polls a workgroup gives up and carries NaN on, so that a broken run is loud and
+// every kernel exits.  Aggregates cross the chip through device-scope (write-through / L2-coherent) accesses:
+// the writers wait for their stores to be acknowledged before the flag is raised.
+// ---------------------------------------------------------------------------
+constexpr int SP_STEPS = 128;         // states per chunk (64 with per-token coefficients: two raw streams)
+constexpr int SP_SPIN_LIMIT = 1 << 22;
+
+struct SpScratch {
+  float* A;        // [nchunks][N][d]   product of the coefficients over the chunk, per chain
+  float* B;        // [nchunks][N][d]   the chunk scanned from a zero state
+  float* X;        // [nchunks][N][d]   state leaving the chunk at its bottom
+  int* flags;      // [nchunks][slabs]  0: nothing, 1: (A, B) published, 2: X published (chunk 0 = top)
+  int* ticket;     // next unit
+};
+
+// two floats (8-byte aligned) as one device-scope access
+__device__ __forceinline__ void st_dev2(float* p, float v0, float v1) {
+  const unsigned long long u = (unsigned long long)__float_as_uint(v0) | ((unsigned long long)__float_as_uint(v1) << 32);
+  __hip_atomic_store(reinterpret_cast<unsigned long long*>(p), u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void ld_dev2(const float* p, float& v0, float& v1) {
+  const unsigned long long u =
+      __hip_atomic_load(reinterpret_cast<const unsigned long long*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  v0 = __uint_as_float((unsigned)u); v1 = __uint_as_float((unsigned)(u >> 32));
+}
+
+__global__ void scan_sp_init_kernel(int* flags, long n) {   // flags and the ticket (the word after them)
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) flags[i] = 0;
+}
+
+// 4 bytes at a wave-uniform 64-bit base plus a per-lane 32-bit byte offset, issued from inline assembly in the
+// scalar-base address form (the compiler otherwise builds a 64-bit per-lane address for every state of the chunk
+// ahead of time: two registers per pending load).  The compiler does not count this load: callers wait for it.
+__device__ __forceinline__ unsigned ld_u32_s(const char* sbase, unsigned lane_off) {
+  unsigned r;
+  asm volatile("global_load_dword %0, %1, %2" : "=v"(r) : "v"(lane_off), "s"(sbase));
+  return r;
+}
+
+typedef float float2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float2v ld_f2_s(const char* sbase, unsigned lane_off) {
+  float2v r;
+  asm volatile("global_load_dwordx2 %0, %1, %2" : "=v"(r) : "v"(lane_off), "s"(sbase));
+  return r;
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {   // at most N vector-memory operations outstanding (N <= 63)
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+  asm volatile("" ::: "memory");
+}
+
+// The compiler does not know that the registers written by the loads above arrive later: after the wait, every
+// such register passes through an empty asm statement (ordered after the wait, like every volatile asm), so
+// that no use of it can be scheduled ahead of the wait.
+__device__ __forceinline__ void landed(unsigned& r) { asm volatile("" : "+v"(r)); }
+__device__ __forceinline__ void landed(float2v& r) { asm volatile("" : "+v"(r)); }
+
+// Every chunk has exactly STEPS states (the launcher gives the chain's remainder to the sequential kernel).
+// A workgroup is 4 waves = 4 token rows x 128 channels (a lane owns 2 channels).
+// LAMK: 0 coefficients 1; 1 per channel (fp32 [L,d]): the chunk's STEPS x 128 coefficients, shared by the four rows,
+// are staged once in LDS (64 KB), scaled; 2 per token: a second raw stream in registers.
+constexpr int SP_ROWS = 4, SP_CH = 128;
+template <int STEPS, bool HAS_SRC, int LAMK>
+__global__ __launch_bounds__(256) void scan_sp_kernel(ScanArgs a, SpScratch sp, int nchunks, int slabs_ch, int slabs) {
+  constexpr bool LTOK = LAMK == 2;
+  extern __shared__ __attribute__((aligned(16))) float lam_s[];     // [STEPS][SP_CH] with LAMK == 1
+  __shared__ int sh_unit, sh_start;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  if (tid == 0) sh_unit = atomicAdd(sp.ticket, 1);
+  __syncthreads();
+  const int unit = __builtin_amdgcn_readfirstlane(sh_unit);
+  const int ct = unit / slabs;               // chunk, counted from the top of the chain
+  const int slab = unit - ct * slabs;
+  if (ct >= nchunks) return;                 // (the grid has exactly nchunks * slabs workgroups)
+  const int rg = slab / slabs_ch;
+  const int ch0 = (slab - rg * slabs_ch) * SP_CH;
+  const int row = rg * SP_ROWS + wave;
+  const int ch = ch0 + lane * 2;
+  const bool valid = row < (int)a.N && ch < (int)a.d;
+  const long layer = a.N * a.d;
+  const long layer_b = layer * 2;                                     // bytes per state
+  const long l_bot = a.l_hi - (long)(ct + 1) * STEPS;                 // chunk: states l_bot .. l_bot + STEPS - 1
+  const unsigned voff = valid ? ((unsigned)row * (unsigned)a.d + (unsigned)ch) * 2u : 0u;   // lanes outside read element 0
+  const char* gsrc = reinterpret_cast<const char*>(HAS_SRC ? (a.dn ? a.dn : a.e) : a.g) + l_bot * layer_b;
+  const char* gtok = reinterpret_cast<const char*>(LTOK ? a.lambda_tok : a.g) + l_bot * layer_b;
+  char* gout = reinterpret_cast<char*>(a.g) + l_bot * layer_b;
+  const float rs = a.res_scale;
+
+  // 1. the chunk's raw values ...
+  unsigned raw[HAS_SRC ? STEPS : 1], rawl[LTOK ? STEPS : 1];
+  {
+    const char* p = gsrc;
+    const char* q = gtok;
+#pragma unroll
+    for (int s = 0; s < STEPS; ++s) {
+      if (HAS_SRC) { raw[HAS_SRC ? s : 0] = ld_u32_s(p, voff); p += layer_b; }
+      if (LTOK) { rawl[LTOK ? s : 0] = ld_u32_s(q, voff); q += layer_b; }
+    }
+  }
+  // ... and its coefficients into LDS (ones past the width), 4 channels per thread and pass
+  if (LAMK == 1) {
+    const float* lg = a.lambda + l_bot * a.d + ch0;
+#pragma unroll 4
+    for (int i = tid; i < STEPS * (SP_CH / 4); i += 256) {
+      const int st = i / (SP_CH / 4), q = (i % (SP_CH / 4)) * 4;
+      float4 v = make_float4(1.f, 1.f, 1.f, 1.f);
+      if (ch0 + q < (int)a.d) v = *reinterpret_cast<const float4*>(lg + (long)st * a.d + q);
+      *reinterpret_cast<float4*>(lam_s + st * SP_CH + q) = make_float4(rs * v.x, rs * v.y, rs * v.z, rs * v.w);
+    }
+  }
+  wait_vmcnt<0>();
+#pragma unroll
+  for (int s = 0; s < STEPS; ++s) {
+    if (HAS_SRC) landed(raw[HAS_SRC ? s : 0]);
+    if (LTOK) landed(rawl[LTOK ? s : 0]);
+  }
+  if (LAMK == 1) __syncthreads();
+  const float* lmine = lam_s + lane * 2;
+  auto coeff = [&](int s, float& l0, float& l1) {
+    if (LTOK) {
+      const unsigned r = rawl[LTOK ? s : 0];
+      l0 = rs * __uint_as_float(r << 16); l1 = rs * __uint_as_float(r & 0xFFFF0000u);
+    } else if (LAMK == 1) {
+      const float2 t = *reinterpret_cast<const float2*>(lmine + s * SP_CH);
+      l0 = t.x; l1 = t.y;
+    } else { l0 = rs; l1 = rs; }
+  };
+  auto value = [&](int s, float& v0, float& v1) {
+    if (HAS_SRC) {
+      const unsigned r = raw[HAS_SRC ? s : 0];
+      v0 = __uint_as_float(r << 16); v1 = __uint_as_float(r & 0xFFFF0000u);
+    } else { v0 = 0.f; v1 = 0.f; }
+  };
+  // 2. the chunk's map
+  float B0 = 0.f, B1 = 0.f, A0 = 1.f, A1 = 1.f;
+#pragma unroll
+  for (int s = STEPS - 1; s >= 0; --s) {
+    float l0, l1, v0, v1;
+    coeff(s, l0, l1);
+    value(s, v0, v1);
+    B0 = fmaf(l0, B0, v0); B1 = fmaf(l1, B1, v1);
+    A0 *= l0; A1 *= l1;
+  }
+  const long agg = (long)ct * layer + (voff >> 1);
+  float S0, S1;
+  if (ct == 0) {                    // the top chunk: the state above it is g[l_hi]
+    const unsigned r = *reinterpret_cast<const unsigned*>(reinterpret_cast<const char*>(a.g) + a.l_hi * layer_b + voff);
+    S0 = __uint_as_float(r << 16); S1 = __uint_as_float(r & 0xFFFF0000u);
+  } else {
+    if (valid) { st_dev2(sp.A + agg, A0, A1); st_dev2(sp.B + agg, B0, B1); }
+    wait_vmcnt<0>();
+    __syncthreads();
+    if (tid < 64) {
+      if (tid == 0)
+        __hip_atomic_store(sp.flags + (long)ct * slabs + slab, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      // 3. look back: the 64 lanes of the first wave read the flags of 64 chunks above at once; the walk ends at
+      // the nearest chunk that shows 2 once every chunk between it and this one shows 1
+      int base = ct - 1, start = -1, spins = 0;
+      while (true) {
+        const int j = base - tid;
+        int f = 3;                                     // above the top of the chain: nothing to wait for
+        if (j >= 0) f = __hip_atomic_load(sp.flags + (long)j * slabs + slab, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long has2 = __ballot(f == 2), has0 = __ballot(f == 0);
+        if (has2) {
+          const int first = __builtin_ctzll(has2);     // nearest chunk with its leaving state published
+          if ((has0 & ((1ull << first) - 1ull)) == 0) { start = base - first; break; }
+        } else if (has0 == 0) {                        // 64 maps, no state yet: further up (chunk 0 shows 2 in the end)
+          base -= 64;
+          continue;
+        }
+        if (++spins > SP_SPIN_LIMIT) break;
+        __builtin_amdgcn_s_sleep(4);
+      }
+      if (tid == 0) sh_start = start;
+    }
+    __syncthreads();
+    const int start = __builtin_amdgcn_readfirstlane(sh_start);
+    if (start < 0) {
+      S0 = S1 = __builtin_nanf("");
+    } else {
+      const long vo = voff >> 1;
+      ld_dev2(sp.X + (long)start * layer + vo, S0, S1);
+      // the maps of the chunks in between, applied one after the other; four chunks' loads at a time (indices past
+      // the last one are clamped and their maps replaced by the identity)
+      for (int j0 = start + 1; j0 < ct; j0 += 4) {
+        float a0[4], a1[4], b0[4], b1[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int j = j0 + i < ct ? j0 + i : ct - 1;
+          ld_dev2(sp.A + (long)j * layer + vo, a0[i], a1[i]);
+          ld_dev2(sp.B + (long)j * layer + vo, b0[i], b1[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bool on = j0 + i < ct;
+          S0 = fmaf(on ? a0[i] : 1.f, S0, on ? b0[i] : 0.f);
+          S1 = fmaf(on ? a1[i] : 1.f, S1, on ? b1[i] : 0.f);
+        }
+      }
+    }
+  }
+  // 4. the state leaving this chunk, for the chunks below
+  if (ct + 1 < nchunks) {
+    if (valid) st_dev2(sp.X + agg, fmaf(A0, S0, B0), fmaf(A1, S1, B1));
+    wait_vmcnt<0>();
+    __syncthreads();
+    if (tid == 0)
+      __hip_atomic_store(sp.flags + (long)ct * slabs + slab, 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  // the recurrence from the entering state.  The raw values are unpacked again and the coefficients read from LDS
+  // again (an empty asm makes them new values to the compiler: kept from the first loop they would hold two
+  // more registers per state)
+  wait_vmcnt<0>();
+  asm volatile("" ::: "memory");
+#pragma unroll
+  for (int s = 0; s < STEPS; ++s) {
+    if (HAS_SRC) landed(raw[HAS_SRC ? s : 0]);
+    if (LTOK) landed(rawl[LTOK ? s : 0]);
+  }
+  {
+    char* p = gout + (STEPS - 1) * layer_b;
+#pragma unroll
+    for (int s = STEPS - 1; s >= 0; --s) {
+      float l0, l1, v0, v1;
+      coeff(s, l0, l1);
+      value(s, v0, v1);
+      S0 = fmaf(l0, S0, v0); S1 = fmaf(l1, S1, v1);
+      const unsigned o = pack_bf16x2(S0, S1);
+      if (valid) asm volatile("global_store_dword %0, %1, %2" :: "v"(voff), "v"(o), "s"(p) : "memory");
+      p -= layer_b;
+    }
+  }
+}
+
 inline bool use_chunked(long L, long N, long d, int norm_rms) {
   // long chains and too few of them to fill the chip with one thread per vector
   return !norm_rms && L >= 4 * SCAN_CHUNK && N * d / 8 < 256L * 1024;
@@ -435,17 +799,100 @@ hipError_t launch_scan_chunked(const ScanArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+inline int sp_steps(bool ltok) { return ltok ? SP_STEPS / 2 : SP_STEPS; }
+inline long sp_slabs(long N, long d) { return ((N + SP_ROWS - 1) / SP_ROWS) * ((d + SP_CH - 1) / SP_CH); }
+
+// the single-pass form covers: bf16 storage, no extra term from the old estimate (blk_gamma = 0), one value stream
+inline bool sp_covers(int dtype, const ScanArgs& a) {
+  return dtype == 1 && a.blk_gamma == 0.f && !a.mask && !(a.dn && a.e) && !(a.norm_rms && a.dn) && a.d % 2 == 0 &&
+         a.d % 8 == 0 && a.N * a.d <= (1L << 30);     // per-lane byte offsets inside a state are 32-bit
+}
+
+hipError_t launch_scan_sp(const ScanArgs& a, hipStream_t s) {
+  const bool ltok = a.lambda_tok != nullptr;
+  const int steps = sp_steps(ltok);
+  const long L = a.l_hi - a.l_lo;
+  const long layer = a.N * a.d;
+  // whole chunks only: the top L % steps states go to the sequential kernel first (it leaves g[l_hi - rem], the
+  // state the chunked part starts from)
+  const long rem = L % steps;
+  ScanArgs top = a;
+  top.l_lo = a.l_hi - rem;
+  ScanArgs rest = a;
+  rest.l_hi = a.l_hi - rem;
+  if (rem) {
+    const long vecs = layer / 8;
+    const dim3 vgrid((unsigned)((vecs + 255) / 256)), vblock(256);
+    if (a.res_scale != 1.f) hipLaunchKernelGGL((scan_vec_kernel<bf16_t, true>), vgrid, vblock, 0, s, top);
+    else hipLaunchKernelGGL((scan_vec_kernel<bf16_t, false>), vgrid, vblock, 0, s, top);
+  }
+  const int nch = (int)(L / steps);
+  if (nch == 0) return hipGetLastError();
+  const long slabs = sp_slabs(a.N, a.d);
+  if (slabs * nch > (1L << 30)) return hipErrorInvalidValue;
+  SpScratch sp;
+  sp.A = a.chunk_ws;
+  sp.B = sp.A + (long)nch * layer;
+  sp.X = sp.B + (long)nch * layer;
+  sp.flags = reinterpret_cast<int*>(sp.X + (long)nch * layer);
+  sp.ticket = sp.flags + (long)nch * slabs;
+  const long nflags = (long)nch * slabs + 1;
+  hipLaunchKernelGGL(scan_sp_init_kernel, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, s, sp.flags, nflags);
+  const dim3 grid((unsigned)(nch * slabs)), block(256);
+  const int slabs_ch = (int)((a.d + SP_CH - 1) / SP_CH);
+  constexpr int lam_lds = SP_STEPS * SP_CH * (int)sizeof(float);
+  {   // the per-channel variants' 64 KB of dynamic LDS: raise the limit once per device
+    static std::atomic<bool> done[2][64];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    for (int v = 0; v < 2; ++v) {
+      if (done[v][dev].load(std::memory_order_acquire)) continue;
+      const void* k = v ? reinterpret_cast<const void*>(scan_sp_kernel<SP_STEPS, true, 1>)
+                        : reinterpret_cast<const void*>(scan_sp_kernel<SP_STEPS, false, 1>);
+      e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lam_lds);
+      if (e != hipSuccess) return e;
+      done[v][dev].store(true, std::memory_order_release);
+    }
+  }
+  const bool src = a.dn || a.e;
+#define HBP_SP(STEPS_, SRC_, LAMK_)                                                                       \
+  hipLaunchKernelGGL((scan_sp_kernel<STEPS_, SRC_, LAMK_>), grid, block, (LAMK_) == 1 ? lam_lds : 0, s, rest, sp, nch, \
+                     slabs_ch, (int)slabs)
+  if (ltok) {
+    if (src) HBP_SP(SP_STEPS / 2, true, 2); else HBP_SP(SP_STEPS / 2, false, 2);
+  } else if (a.lambda) {
+    if (src) HBP_SP(SP_STEPS, true, 1); else HBP_SP(SP_STEPS, false, 1);
+  } else {
+    if (src) HBP_SP(SP_STEPS, true, 0); else HBP_SP(SP_STEPS, false, 0);
+  }
+#undef HBP_SP
+  return hipGetLastError();
+}
+
 template <typename T>
 hipError_t launch_scan_t(const ScanArgs& a, hipStream_t s) {
   if (a.l_hi <= a.l_lo) return hipSuccess;
   const bool gam = a.res_scale != 1.f || a.blk_gamma != 0.f;
   const bool rms = a.norm_rms && a.dn;
+  constexpr int dtype = std::is_same<T, float>::value ? 0 : 1;
+  if (a.force == 3) {
+    if (!a.chunk_ws || !sp_covers(dtype, a)) return hipErrorInvalidValue;
+    return launch_scan_sp(a, s);
+  }
   if (a.force == 2) {
     if (!a.chunk_ws || rms || a.mask) return hipErrorInvalidValue;
     return launch_scan_chunked<T>(a, s);
   }
-  if (a.force == 0 && !a.mask && a.chunk_ws && use_chunked(a.l_hi - a.l_lo, a.N, a.d, rms))
+  if (a.force == 0 && !a.mask && a.chunk_ws && use_chunked(a.l_hi - a.l_lo, a.N, a.d, rms)) {
+    // (the scratch of the three-pass form, which the callers size the workspace for, holds the single-pass form's)
+    if (sp_covers(dtype, a) &&
+        scan_sp_ws_bytes(a.l_hi - a.l_lo, a.N, a.d, a.lambda_tok != nullptr) <=
+            scan_chunk_ws_bytes_forced(a.l_hi - a.l_lo, a.N, a.d))
+      return launch_scan_sp(a, s);
     return launch_scan_chunked<T>(a, s);
+  }
   if (a.norm_rms && a.dn) {
     const int nch = (int)((a.d + 511) / 512);
     dim3 grid((unsigned)((a.N + 3) / 4)), block(256);
@@ -456,6 +903,23 @@ hipError_t launch_scan_t(const ScanArgs& a, hipStream_t s) {
         case 3: case 4: hipLaunchKernelGGL((scan_rows_kernel<T, 4, true>), grid, block, 0, s, a); break;
         default: return hipErrorInvalidValue;   // (rejected by the caller: d > 2048)
       }
+      return hipGetLastError();
+    }
+    if (a.d % 512 == 0 && nch <= 4 && !a.mask && !a.lambda_tok) {    // whole 512-channel chunks: the pipelined form
+#define HBP_ROWS_PIPE(N_)                                                                                          \
+      do {                                                                                                         \
+        if (a.e && a.lambda) hipLaunchKernelGGL((scan_rows_pipe_kernel<T, N_, true, true>), grid, block, 0, s, a);      \
+        else if (a.e) hipLaunchKernelGGL((scan_rows_pipe_kernel<T, N_, true, false>), grid, block, 0, s, a);            \
+        else if (a.lambda) hipLaunchKernelGGL((scan_rows_pipe_kernel<T, N_, false, true>), grid, block, 0, s, a);       \
+        else hipLaunchKernelGGL((scan_rows_pipe_kernel<T, N_, false, false>), grid, block, 0, s, a);                    \
+      } while (0)
+      switch (nch) {
+        case 1: HBP_ROWS_PIPE(1); break;
+        case 2: HBP_ROWS_PIPE(2); break;
+        case 3: HBP_ROWS_PIPE(3); break;
+        default: HBP_ROWS_PIPE(4); break;
+      }
+#undef HBP_ROWS_PIPE
       return hipGetLastError();
     }
     switch (nch) {
@@ -598,6 +1062,12 @@ size_t hs_ws_bytes(long L, long N, long d, int lambda_kind) {
 }
 hipError_t launch_scan_hillis_steele(int dtype, const HsArgs& a, hipStream_t s) {
   return dtype == 0 ? launch_hs_t<float>(a, s) : launch_hs_t<bf16_t>(a, s);
+}
+size_t scan_sp_ws_bytes(long L, long N, long d, int lambda_tok) {
+  const long steps = lambda_tok ? SP_STEPS / 2 : SP_STEPS;
+  const long nch = (L + steps - 1) / steps;
+  const long slabs = ((N + 3) / 4) * ((d + 127) / 128);
+  return (size_t)(3 * nch * N * d) * sizeof(float) + (size_t)(nch * slabs + 1) * sizeof(int);
 }
 size_t scan_chunk_ws_bytes_forced(long L, long N, long d) {
   const long nchunks = (L + SCAN_CHUNK - 1) / SCAN_CHUNK;

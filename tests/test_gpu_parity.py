@@ -364,12 +364,18 @@ def test_gamma_iterates(B, name, gamma):
 
 @pytest.mark.parametrize("name", ["mlp_f32_ragged", "resnet_like_small", "rnn_small", "rnn_f32", "rnn_long",
                                   "rnn_token_gates", "rnn_token_gates_long", "mlp_loss_all", "mlp_small_f32"])
-@pytest.mark.parametrize("algorithm", ["auto", "sequential", "chunked", "hillis_steele"])
+@pytest.mark.parametrize("algorithm", ["auto", "sequential", "chunked", "single_pass", "hillis_steele"])
 def test_initial_estimate_by_every_form_of_the_scan(B, name, algorithm):
-    """w^0 = CumSumProd(e, K): the sequential walk, the chunked form and the sweeps of the paper's
-    Algorithm 1 give the oracle's result (and so each other's) up to rounding order."""
+    """w^0 = CumSumProd(e, K): the sequential walk, the chunked three-pass form, the single-pass form with its
+    chained look-back and the sweeps of the paper's Algorithm 1 give the oracle's result (and so each other's)
+    up to rounding order."""
     w = CASES[name]
     inp, st, sv, p = _setup(B, w)
+    if algorithm == "single_pass" and w.dtype != "bf16":      # bf16 storage only
+        with pytest.raises(B.HbpError) as ei:
+            B.scan_workspace_size(p.desc, algorithm)
+        assert ei.value.status == 2
+        return
     ws = torch.zeros(max(B.scan_workspace_size(p.desc, algorithm), 16), dtype=torch.uint8, device=p.g.device)
     p.g.fill_(float("nan"))
     B.hbp_initial_estimate(p, algorithm, workspace=ws)
@@ -397,7 +403,7 @@ def test_initial_estimate_with_relu_after_the_sum(B, name, algorithm):
     torch.cuda.synchronize()
     want = H.as_kept(st, sv_r, O.hbp_backward(st, sv_r, inp["e"], 0))
     assert H.rel(H.to_np(p.g), want) < H.TOL[w.dtype], f"{name} {algorithm}"
-    for other in ("chunked", "hillis_steele"):
+    for other in ("chunked", "hillis_steele", "single_pass"):
         with pytest.raises(B.HbpError) as ei:
             B.scan_workspace_size(p.desc, other)
         assert ei.value.status == 2
