@@ -501,3 +501,64 @@ def cosine(a: np.ndarray, b: np.ndarray) -> float:
     a = np.asarray(a, F64).ravel()
     b = np.asarray(b, F64).ravel()
     return float(a @ b / (np.linalg.norm(a) * np.linalg.norm(b)))
+
+
+# --------------------------------------------------------------------------
+# a training step around the backward pass (Section "Discussion and conclusion": the number of iterations can be
+# raised during training, ending with exact backpropagation; appendix "Training scheme": SGD with momentum and
+# weight decay for the ResNets, AdamW with gradient clipping for the transformers and RNNs)
+# --------------------------------------------------------------------------
+def mse_loss_and_grad(x_states: np.ndarray, target: np.ndarray, every_state: bool):
+    """The stand-in training loss: half the squared distance of the states to targets, averaged over tokens.
+    every_state: states 1..L each have a target (target [L+1,N,d], row 0 unused); else only x_L (target [N,d]).
+    Returns (loss, e) with e = dL/dx in the layout the backward pass takes ([L+1,N,d] with e[0] = 0, or [N,d])."""
+    x = np.asarray(x_states, F64)
+    t = np.asarray(target, F64)
+    N = x.shape[1]
+    if every_state:
+        diff = x - t
+        diff[0] = 0.0
+        return 0.5 * float(np.sum(diff * diff)) / N, diff / N
+    diff = x[-1] - t
+    return 0.5 * float(np.sum(diff * diff)) / N, diff / N
+
+
+def clip_scale(grads, max_norm: float) -> float:
+    """Factor that brings the global L2 norm of all gradients down to max_norm (1 when it is below, or when
+    max_norm <= 0: no clipping): min(1, max_norm / (norm + 1e-6))."""
+    if max_norm <= 0.0:
+        return 1.0
+    tot = math.sqrt(sum(float(np.sum(np.asarray(g, F64) ** 2)) for g in grads))
+    return min(1.0, max_norm / (tot + 1e-6))
+
+
+def sgd_momentum_step(w, g, buf, lr: float, momentum: float, weight_decay: float, scale: float = 1.0):
+    """SGD with momentum and L2 weight decay, in the form the ResNet recipe uses:
+    g' = scale g + weight_decay w;  buf <- momentum buf + g';  w <- w - lr buf.  Returns (w, buf)."""
+    w = np.asarray(w, F64)
+    gp = scale * np.asarray(g, F64) + weight_decay * w
+    buf = momentum * np.asarray(buf, F64) + gp
+    return w - lr * buf, buf
+
+
+def adamw_step(w, g, m, v, step: int, lr: float, beta1: float, beta2: float, eps: float, weight_decay: float,
+               scale: float = 1.0):
+    """AdamW (weight decay decoupled from the gradient), step counted from 1:
+    w <- w (1 - lr wd);  m <- b1 m + (1 - b1) g;  v <- b2 v + (1 - b2) g^2;
+    w <- w - lr (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps).  Returns (w, m, v)."""
+    w = np.asarray(w, F64) * (1.0 - lr * weight_decay)
+    g = scale * np.asarray(g, F64)
+    m = beta1 * np.asarray(m, F64) + (1.0 - beta1) * g
+    v = beta2 * np.asarray(v, F64) + (1.0 - beta2) * g * g
+    mhat = m / (1.0 - beta1 ** step)
+    vhat = v / (1.0 - beta2 ** step)
+    return w - lr * mhat / (np.sqrt(vhat) + eps), m, v
+
+
+def lr_schedule(step: int, total: int, base_lr: float, warmup: int) -> float:
+    """Linear warm-up over `warmup` steps, then a cosine from base_lr down to a tenth of it at step `total`
+    (appendix "Training scheme").  step counts from 0."""
+    if warmup > 0 and step < warmup:
+        return base_lr * (step + 1) / warmup
+    p = min(1.0, (step - warmup) / max(1, total - warmup))
+    return base_lr * (0.1 + 0.9 * 0.5 * (1.0 + math.cos(math.pi * p)))

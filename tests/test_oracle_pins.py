@@ -1010,3 +1010,96 @@ def test_assert_close_catches_a_wrong_row_and_a_wrong_element():
     assert H.rel(few, want) < tol
     with pytest.raises(AssertionError):
         H.assert_close(few, want, tol, "corner")
+
+
+def test_optimizer_steps_against_torch_optim():
+    """The oracle's SGD-with-momentum and AdamW steps against torch.optim (an independent implementation) over
+    several steps in fp64, and a one-step closed form done by hand."""
+    rng = np.random.default_rng(3)
+    w0 = rng.standard_normal((5, 7))
+    grads = [rng.standard_normal((5, 7)) for _ in range(4)]
+    # SGD: lr 0.1, momentum 0.9, weight decay 1e-2
+    p = torch.nn.Parameter(torch.tensor(w0, dtype=torch.float64))
+    opt = torch.optim.SGD([p], lr=0.1, momentum=0.9, weight_decay=1e-2)
+    w, buf = w0.copy(), np.zeros_like(w0)
+    for g in grads:
+        p.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        w, buf = O.sgd_momentum_step(w, g, buf, 0.1, 0.9, 1e-2)
+        assert np.allclose(w, p.detach().numpy(), rtol=1e-13, atol=1e-13)
+    # AdamW: lr 1e-2, betas (0.9, 0.98), eps 1e-8, weight decay 0.1
+    p = torch.nn.Parameter(torch.tensor(w0, dtype=torch.float64))
+    opt = torch.optim.AdamW([p], lr=1e-2, betas=(0.9, 0.98), eps=1e-8, weight_decay=0.1)
+    w, m, v = w0.copy(), np.zeros_like(w0), np.zeros_like(w0)
+    for t, g in enumerate(grads, start=1):
+        p.grad = torch.tensor(g, dtype=torch.float64)
+        opt.step()
+        w, m, v = O.adamw_step(w, g, m, v, t, 1e-2, 0.9, 0.98, 1e-8, 0.1)
+        assert np.allclose(w, p.detach().numpy(), rtol=1e-12, atol=1e-12)
+    # by hand: one AdamW step from zero moments moves every weight by lr sign(g) (up to eps) after the decay
+    w1, _, _ = O.adamw_step(np.array([2.0]), np.array([0.5]), np.zeros(1), np.zeros(1), 1, 0.1, 0.9, 0.999, 0.0, 0.5)
+    assert w1[0] == pytest.approx(2.0 * (1 - 0.05) - 0.1, abs=1e-12)
+    # by hand: SGD, first step, no momentum history: w - lr (g + wd w)
+    w1, b1 = O.sgd_momentum_step(np.array([2.0]), np.array([0.5]), np.zeros(1), 0.1, 0.9, 0.25)
+    assert w1[0] == pytest.approx(2.0 - 0.1 * (0.5 + 0.5), abs=1e-15) and b1[0] == pytest.approx(1.0)
+
+
+def test_clip_scale_and_schedule_and_loss():
+    """Gradient clipping against torch's clip_grad_norm_, the learning-rate schedule at its fixed points, and the
+    stand-in loss against autograd."""
+    rng = np.random.default_rng(4)
+    gs = [rng.standard_normal((3, 4)), rng.standard_normal(6)]
+    ps = [torch.nn.Parameter(torch.zeros(3, 4, dtype=torch.float64)), torch.nn.Parameter(torch.zeros(6, dtype=torch.float64))]
+    for p, g in zip(ps, gs):
+        p.grad = torch.tensor(g)
+    torch.nn.utils.clip_grad_norm_(ps, 1.0)
+    s = O.clip_scale(gs, 1.0)
+    for p, g in zip(ps, gs):
+        assert np.allclose(p.grad.numpy(), s * g, rtol=1e-12)
+    assert O.clip_scale(gs, 0.0) == 1.0 and O.clip_scale([np.array([0.3, 0.4])], 1.0) == 1.0
+    assert O.clip_scale([np.array([3.0, 4.0])], 1.0) == pytest.approx(1.0 / (5.0 + 1e-6))
+    # schedule: warm-up reaches the base rate, the cosine ends at a tenth of it, half-way it is 0.55 of it
+    assert O.lr_schedule(0, 100, 1.0, 10) == pytest.approx(0.1)
+    assert O.lr_schedule(9, 100, 1.0, 10) == pytest.approx(1.0)
+    assert O.lr_schedule(10, 100, 1.0, 10) == pytest.approx(1.0)
+    assert O.lr_schedule(55, 100, 1.0, 10) == pytest.approx(0.55)
+    assert O.lr_schedule(100, 100, 1.0, 10) == pytest.approx(0.1)
+    # loss: e is the gradient of the loss w.r.t. the states
+    x = rng.standard_normal((4, 3, 5)); t = rng.standard_normal((4, 3, 5))
+    for every in (True, False):
+        xt = torch.tensor(x, requires_grad=True)
+        if every:
+            loss = 0.5 * ((xt[1:] - torch.tensor(t[1:])) ** 2).sum() / 3
+        else:
+            loss = 0.5 * ((xt[-1] - torch.tensor(t[-1])) ** 2).sum() / 3
+        loss.backward()
+        val, e = O.mse_loss_and_grad(x, t if every else t[-1], every)
+        assert val == pytest.approx(float(loss.detach()), rel=1e-13)
+        want = xt.grad.numpy() if every else xt.grad.numpy()[-1]
+        assert np.allclose(e, want, rtol=1e-13, atol=1e-15)
+
+
+def test_training_with_few_iterations_then_exact_reduces_the_loss():
+    """The conclusion's recipe on a tiny stack, all in the oracle: SGD on the stand-in loss with gradients from
+    Highway-BP at k = 1, then k = 2, then exact backpropagation; the loss goes down in every phase, and a step
+    with k >= L equals a step with exact backpropagation."""
+    rng = np.random.default_rng(5)
+    L, N, d, dff = 4, 16, 6, 12
+    W1 = rng.standard_normal((L, dff, d)) / np.sqrt(d)
+    W2 = rng.standard_normal((L, d, dff)) / np.sqrt(dff) * 0.5
+    x0 = rng.standard_normal((N, d)); target = rng.standard_normal((N, d)) * 0.1
+    b1, b2 = np.zeros_like(W1), np.zeros_like(W2)
+    losses = []
+    for step in range(30):
+        st = O.Stack("mlp", "gelu", "rms", W1, W2)
+        sv = O.forward(st, x0)
+        loss, e = O.mse_loss_and_grad(sv["x"], target, False)
+        losses.append(loss)
+        k = 1 if step < 10 else 2 if step < 20 else None
+        g = O.exact_backward(st, sv, e) if k is None else O.hbp_backward(st, sv, e, k)
+        if step == 29:
+            assert np.allclose(O.hbp_backward(st, sv, e, L), O.exact_backward(st, sv, e), rtol=1e-12, atol=1e-14)
+        pg = O.param_grads(st, sv, g)
+        W1, b1 = O.sgd_momentum_step(W1, pg["dW1"], b1, 0.05, 0.9, 0.0)
+        W2, b2 = O.sgd_momentum_step(W2, pg["dW2"], b2, 0.05, 0.9, 0.0)
+    assert losses[10] < losses[0] and losses[20] < losses[10] and losses[29] < losses[20]
