@@ -396,6 +396,28 @@ def main():
             del ws
         out["scan_forms_w0"] = abl
 
+    if not args.no_sweep:
+        # The whole training step (conclusion of the paper: few iterations early, exact backpropagation at the end;
+        # cost model T_forward + (k / L) T_backward + O(k log L)): forward, stand-in loss, backward, parameter
+        # gradients, optimizer update (AdamW with clipping, fp32 master weights).  Run last: it moves the weights.
+        st_o = B.allocate_optim(p, adamw=True)
+        tgt = torch.zeros_like(p.e)
+        opt = B.make_optim("adamw", lr=1e-4, beta1=0.9, beta2=0.98, eps=1e-8, weight_decay=0.1, clip_norm=1.0, step=1)
+        tr = {"optimizer": "adamw, clip 1.0, fp32 master weights"}
+        tr["forward_ms"] = time_steps(torch, lambda: B.hbp_forward(p), reps, 1) * 1e3
+        tr["loss_ms"] = time_steps(torch, lambda: B.hbp_loss_mse(p, tgt, st_o), reps, 1) * 1e3
+        B.hbp_backward(p, k)
+        B.hbp_param_grads(p)
+        tr["optimizer_ms"] = time_steps(torch, lambda: B.hbp_optimizer_step(p, opt, st_o), reps, 1) * 1e3
+        steps_ms = {}
+        for kk in (1, 2, 3, -1):
+            t = time_steps(torch, lambda kk=kk: B.hbp_train_step(p, kk, tgt, opt, st_o), reps, 1)
+            steps_ms["exact" if kk < 0 else str(kk)] = {"ms": t * 1e3, "tokens_per_s": tokens / t}
+        tr["train_step"] = steps_ms
+        tr["loss_after"] = float(st_o.loss)
+        out["training_step"] = tr
+        del st_o, tgt
+
     if not args.no_cpu_baseline:
         # about 10-20 s of oracle work on the GPU machine's host cores
         n = args.cpu_tokens or {"mlp_small_f32": 128, "resnet_like": 8192, "resnet_postact": 8192, "postnorm_mlp": 2048, "transformer_mlp": 2048,

@@ -211,6 +211,56 @@ hbp_status hbp_exact_backward(const hbp_desc* desc, hbp_buffers* bufs, void* str
  * tokens are computed in shares whose partial sums a second kernel adds in a fixed order (bitwise repeatable). */
 hbp_status hbp_param_grads(const hbp_desc* desc, hbp_buffers* bufs, void* stream);
 
+/* ---- the training step around the backward pass --------------------------------------------------------------
+ * Section "Discussion and conclusion": the number of iterations is a knob that can be turned during training (few
+ * iterations early, more later, exact backpropagation at the end); Section "Approximating backpropagation": a step
+ * costs T_forward + (k / L) T_backward + O(k log L).  The calls below complete hbp_forward, hbp_backward /
+ * hbp_exact_backward and hbp_param_grads into such a step: a stand-in loss, gradient clipping and the two
+ * optimizers of the appendix "Training scheme" (SGD with momentum and weight decay; AdamW).  The schedule of k and
+ * of the learning rate is the caller's loop. */
+typedef enum { HBP_OPT_SGD = 0, HBP_OPT_ADAMW = 1 } hbp_opt_kind;
+typedef struct {
+  uint32_t struct_size;      /* = sizeof(hbp_optim) */
+  int32_t kind;              /* hbp_opt_kind */
+  float lr;
+  float beta1;               /* SGD: the momentum; AdamW: beta1 */
+  float beta2;               /* AdamW */
+  float eps;                 /* AdamW */
+  float weight_decay;        /* SGD: added to the gradient (L2); AdamW: decoupled */
+  float clip_norm;           /* > 0: gradients scaled by min(1, clip_norm / (global L2 norm + 1e-6)); 0: off */
+  int64_t step;              /* AdamW: number of this update, counted from 1 */
+} hbp_optim;
+typedef struct {
+  uint32_t struct_size;      /* = sizeof(hbp_optim_state) */
+  /* DEVICE, fp32, shapes of W1 / W2 / U (entries for weights the kind does not have are ignored).
+   * master*: fp32 copies of the weights, updated and then rounded into W1 / W2 / U; may be NULL: the weights are
+   * then kept in the storage type alone.  m*: momentum buffer (SGD) or first moment (AdamW); v*: second moment
+   * (AdamW only).  The caller zeroes m and v before the first step and fills master with the weights. */
+  float* master1; float* master2; float* masterU;
+  float* m1; float* m2; float* mU;
+  float* v1; float* v2; float* vU;
+  float* scratch;            /* DEVICE, hbp_train_scratch_size() bytes: partial sums of the reductions */
+  size_t scratch_bytes;
+} hbp_optim_state;
+
+hbp_status hbp_train_scratch_size(size_t* bytes);
+
+/* The stand-in loss L = 1/(2N) sum |x - target|^2 over the last state (loss_every_state = 0: target [N,d]) or over
+ * states 1..L (loss_every_state = 1: target [L+1,N,d], row 0 unused), N = desc->N: writes e_out = dL/dx in the
+ * layout hbp_backward reads as bufs->e ([N,d] or [L+1,N,d] with e[0] = 0) and the loss value to loss_out[0] (DEVICE
+ * float).  Reads bufs->x; scratch as in hbp_optim_state. */
+hbp_status hbp_loss_mse(const hbp_desc* desc, const hbp_buffers* bufs, const void* target, void* e_out, float* loss_out,
+                        float* scratch, size_t scratch_bytes, void* stream);
+
+/* One optimizer update of W1, W2 (and U) from dW1, dW2 (and dU) in bufs. */
+hbp_status hbp_optimizer_step(const hbp_desc* desc, hbp_buffers* bufs, const hbp_optim* opt, hbp_optim_state* state,
+                              void* stream);
+
+/* One training step: hbp_forward, hbp_loss_mse (writes bufs->e, which must be writable here), hbp_backward(k) or,
+ * with k < 0, hbp_exact_backward, hbp_param_grads, hbp_optimizer_step. */
+hbp_status hbp_train_step(const hbp_desc* desc, int k, hbp_buffers* bufs, const void* target, float* loss_out,
+                          const hbp_optim* opt, hbp_optim_state* state, void* stream);
+
 const char* hbp_status_string(hbp_status s);
 
 /* Optional timing of the kernels the calls above enqueue, by class, with HIP

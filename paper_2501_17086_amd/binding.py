@@ -30,7 +30,8 @@ LAMBDA_ONE, LAMBDA_CHANNEL, LAMBDA_TOKEN = 0, 1, 2
 
 EXPORTS = ("hbp_workspace_size", "hbp_check", "hbp_forward", "hbp_backward", "hbp_exact_backward",
            "hbp_scan_workspace_size", "hbp_initial_estimate", "hbp_initial_estimate_static",
-           "hbp_param_grads", "hbp_profile_enable", "hbp_profile_read", "hbp_status_string")
+           "hbp_param_grads", "hbp_train_scratch_size", "hbp_loss_mse", "hbp_optimizer_step", "hbp_train_step",
+           "hbp_profile_enable", "hbp_profile_read", "hbp_status_string")
 PROF_CLASSES = ("vjp1", "vjp2", "scan", "dw", "forward", "other")
 
 
@@ -49,6 +50,23 @@ class hbp_buffers(C.Structure):
                 ("g", C.c_void_p),
                 ("dW1", C.c_void_p), ("dW2", C.c_void_p), ("dU", C.c_void_p),
                 ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+
+
+OPT_SGD, OPT_ADAMW = 0, 1
+
+
+class hbp_optim(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("kind", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float),
+                ("beta2", C.c_float), ("eps", C.c_float), ("weight_decay", C.c_float), ("clip_norm", C.c_float),
+                ("step", C.c_int64)]
+
+
+class hbp_optim_state(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32),
+                ("master1", C.c_void_p), ("master2", C.c_void_p), ("masterU", C.c_void_p),
+                ("m1", C.c_void_p), ("m2", C.c_void_p), ("mU", C.c_void_p),
+                ("v1", C.c_void_p), ("v2", C.c_void_p), ("vU", C.c_void_p),
+                ("scratch", C.c_void_p), ("scratch_bytes", C.c_size_t)]
 
 
 class HbpError(RuntimeError):
@@ -78,6 +96,13 @@ def lib() -> C.CDLL:
         L.hbp_initial_estimate.argtypes = [C.POINTER(hbp_desc), C.c_int, C.POINTER(hbp_buffers), C.c_void_p]
         L.hbp_initial_estimate_static.argtypes = [C.POINTER(hbp_desc), C.POINTER(hbp_buffers), C.c_void_p]
         L.hbp_param_grads.argtypes = [C.POINTER(hbp_desc), C.POINTER(hbp_buffers), C.c_void_p]
+        L.hbp_train_scratch_size.argtypes = [C.POINTER(C.c_size_t)]
+        L.hbp_loss_mse.argtypes = [C.POINTER(hbp_desc), C.POINTER(hbp_buffers), C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_void_p, C.c_size_t, C.c_void_p]
+        L.hbp_optimizer_step.argtypes = [C.POINTER(hbp_desc), C.POINTER(hbp_buffers), C.POINTER(hbp_optim),
+                                         C.POINTER(hbp_optim_state), C.c_void_p]
+        L.hbp_train_step.argtypes = [C.POINTER(hbp_desc), C.c_int, C.POINTER(hbp_buffers), C.c_void_p, C.c_void_p,
+                                     C.POINTER(hbp_optim), C.POINTER(hbp_optim_state), C.c_void_p]
         L.hbp_profile_enable.argtypes = [C.c_int]
         L.hbp_profile_read.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         L.hbp_status_string.argtypes = [C.c_int]
@@ -221,6 +246,66 @@ def hbp_exact_backward(p: Problem, stream=None) -> None:
 def hbp_param_grads(p: Problem, stream=None) -> None:
     b = p.buffers()
     _call("hbp_param_grads", lib().hbp_param_grads(C.byref(p.desc), C.byref(b), _stream(stream)))
+
+
+def train_scratch_size() -> int:
+    n = C.c_size_t(0)
+    _call("hbp_train_scratch_size", lib().hbp_train_scratch_size(C.byref(n)))
+    return n.value
+
+
+def make_optim(kind: str, lr: float, beta1: float = 0.9, beta2: float = 0.999, eps: float = 1e-8,
+               weight_decay: float = 0.0, clip_norm: float = 0.0, step: int = 1) -> hbp_optim:
+    return hbp_optim(C.sizeof(hbp_optim), OPT_ADAMW if kind == "adamw" else OPT_SGD, lr, beta1, beta2, eps,
+                     weight_decay, clip_norm, step)
+
+
+@dataclass
+class OptimState:
+    """Device tensors of the optimizer: fp32 master copies of the weights (optional), moments, reduction scratch."""
+    master: tuple
+    m: tuple
+    v: tuple
+    scratch: "object"
+    loss: "object"        # device float: the last loss value
+
+    def struct(self) -> hbp_optim_state:
+        return hbp_optim_state(C.sizeof(hbp_optim_state), *[_ptr(t) for t in self.master], *[_ptr(t) for t in self.m],
+                               *[_ptr(t) for t in self.v], _ptr(self.scratch),
+                               self.scratch.numel() * self.scratch.element_size())
+
+
+def allocate_optim(p: Problem, adamw: bool, master: bool = True) -> OptimState:
+    import torch
+    ws = (p.W1, p.W2, p.U)
+    f = lambda w: None if w is None else torch.zeros(w.shape, dtype=torch.float32, device=w.device)
+    return OptimState(master=tuple((None if (w is None or not master) else w.float().clone()) for w in ws),
+                      m=tuple(f(w) for w in ws), v=tuple((f(w) if adamw else None) for w in ws),
+                      scratch=torch.zeros(train_scratch_size() // 4, dtype=torch.float32, device=p.W1.device),
+                      loss=torch.zeros(1, dtype=torch.float32, device=p.W1.device))
+
+
+def hbp_loss_mse(p: Problem, target, st: OptimState, stream=None) -> None:
+    """Writes p.e (the loss gradient) and st.loss from p.x and `target`."""
+    b = p.buffers()
+    _call("hbp_loss_mse", lib().hbp_loss_mse(C.byref(p.desc), C.byref(b), target.data_ptr(), p.e.data_ptr(),
+                                             st.loss.data_ptr(), st.scratch.data_ptr(),
+                                             st.scratch.numel() * 4, _stream(stream)))
+
+
+def hbp_optimizer_step(p: Problem, opt: hbp_optim, st: OptimState, stream=None) -> None:
+    b = p.buffers()
+    s = st.struct()
+    _call("hbp_optimizer_step", lib().hbp_optimizer_step(C.byref(p.desc), C.byref(b), C.byref(opt), C.byref(s),
+                                                         _stream(stream)))
+
+
+def hbp_train_step(p: Problem, k: int, target, opt: hbp_optim, st: OptimState, stream=None) -> None:
+    """forward, loss, hbp_backward(k) (k < 0: exact backpropagation), parameter gradients, optimizer update."""
+    b = p.buffers()
+    s = st.struct()
+    _call("hbp_train_step", lib().hbp_train_step(C.byref(p.desc), int(k), C.byref(b), target.data_ptr(),
+                                                 st.loss.data_ptr(), C.byref(opt), C.byref(s), _stream(stream)))
 
 
 def profile_enable(on: bool) -> None:

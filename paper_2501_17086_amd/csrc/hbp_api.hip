@@ -5,6 +5,7 @@
 #include "../../include/hbp.h"
 #include "hbp_common.h"
 
+#include <cmath>
 #include <mutex>
 #include <vector>
 
@@ -813,6 +814,102 @@ hbp_status hbp_param_grads(const hbp_desc* d, hbp_buffers* b, void* stream) {
     HBP_RUN(tn_gemm(d, da, d->d_ff, 0, bb.xin, d->d_in, 0, bb.dU, d->d_ff, d->d_in, K, 1, sp.s_u, part, s));
   }
   return HBP_OK;
+}
+
+namespace {
+struct ParamSizes { long n1, n2, nu; };
+ParamSizes param_sizes(const hbp_desc* d) {
+  const long nb = shared_w(d) ? 1 : d->L;
+  ParamSizes p{};
+  p.n1 = nb * d->d_ff * hidden_w(d);
+  p.n2 = cell(d) ? 0 : nb * d->d * d->d_ff;
+  p.nu = recurrent(d) ? d->d_ff * d->d_in : 0;
+  return p;
+}
+}  // namespace
+
+hbp_status hbp_train_scratch_size(size_t* bytes) {
+  if (!bytes) return HBP_E_NULL;
+  *bytes = train_scratch_floats() * sizeof(float);
+  return HBP_OK;
+}
+
+hbp_status hbp_loss_mse(const hbp_desc* d, const hbp_buffers* b, const void* target, void* e_out, float* loss_out,
+                        float* scratch, size_t scratch_bytes, void* stream) {
+  HBP_RUN(check_desc(d));
+  if (!b) return HBP_E_NULL;
+  if (b->struct_size != sizeof(hbp_buffers)) return HBP_E_INVALID_ARG;
+  if (!b->x || !target || !e_out || !loss_out) return HBP_E_NULL;
+  if (!scratch || scratch_bytes < train_scratch_floats() * sizeof(float)) return HBP_E_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  const size_t es = esize(d);
+  const long layer = d->N * d->d;
+  const float inv_n = 1.0f / (float)d->N;
+  ProfScope ps(HBP_PROF_OTHER, s);
+  if (d->loss_every_state) {      // states 1..L; e[0] = 0
+    HBP_TRY(launch_zero(d->dtype, e_out, layer, s));
+    HBP_TRY(launch_mse_loss_grad(d->dtype, at((const void*)b->x, (size_t)layer * es), at(target, (size_t)layer * es),
+                                 at(e_out, (size_t)layer * es), d->L * layer, inv_n, scratch, loss_out, s));
+  } else {
+    HBP_TRY(launch_mse_loss_grad(d->dtype, at((const void*)b->x, (size_t)d->L * layer * es), target, e_out, layer, inv_n,
+                                 scratch, loss_out, s));
+  }
+  return HBP_OK;
+}
+
+hbp_status hbp_optimizer_step(const hbp_desc* d, hbp_buffers* b, const hbp_optim* o, hbp_optim_state* st, void* stream) {
+  HBP_RUN(check_desc(d));
+  if (!b || !o || !st) return HBP_E_NULL;
+  if (b->struct_size != sizeof(hbp_buffers) || o->struct_size != sizeof(hbp_optim) ||
+      st->struct_size != sizeof(hbp_optim_state))
+    return HBP_E_INVALID_ARG;
+  if (o->kind != HBP_OPT_SGD && o->kind != HBP_OPT_ADAMW) return HBP_E_INVALID_ARG;
+  const bool adamw = o->kind == HBP_OPT_ADAMW;
+  if (!(o->lr >= 0.f) || !(o->beta1 >= 0.f && o->beta1 < 1.f) || !(o->weight_decay >= 0.f) || !(o->clip_norm >= 0.f))
+    return HBP_E_INVALID_ARG;
+  if (adamw && (!(o->beta2 >= 0.f && o->beta2 < 1.f) || !(o->eps >= 0.f) || o->step < 1)) return HBP_E_INVALID_ARG;
+  const ParamSizes ps = param_sizes(d);
+  struct T3 { void* w; float* master; const float* g; float* m; float* v; long n; };
+  T3 t[3] = {{const_cast<void*>(b->W1), st->master1, b->dW1, st->m1, st->v1, ps.n1},
+             {const_cast<void*>(b->W2), st->master2, b->dW2, st->m2, st->v2, ps.n2},
+             {const_cast<void*>(b->U), st->masterU, b->dU, st->mU, st->vU, ps.nu}};
+  for (const T3& x : t) {
+    if (x.n == 0) continue;
+    if (!x.w || !x.g || !x.m || (adamw && !x.v)) return HBP_E_NULL;
+  }
+  if (o->clip_norm > 0.f && (!st->scratch || st->scratch_bytes < train_scratch_floats() * sizeof(float)))
+    return HBP_E_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  ProfScope pscope(HBP_PROF_OTHER, s);
+  const float* clip = nullptr;
+  if (o->clip_norm > 0.f) {
+    const float* gs[3]; long ns[3]; int cnt = 0;
+    for (const T3& x : t) if (x.n) { gs[cnt] = x.g; ns[cnt] = x.n; ++cnt; }
+    float* factor = st->scratch + train_scratch_floats() - 8;
+    HBP_TRY(launch_clip_factor(gs, ns, cnt, o->clip_norm, st->scratch, factor, s));
+    clip = factor;
+  }
+  OptimArgs a{};
+  a.lr = o->lr; a.beta1 = o->beta1; a.beta2 = o->beta2; a.eps = o->eps; a.weight_decay = o->weight_decay;
+  if (adamw) {
+    a.inv_bias1 = (float)(1.0 / (1.0 - pow((double)o->beta1, (double)o->step)));
+    a.inv_bias2 = (float)(1.0 / (1.0 - pow((double)o->beta2, (double)o->step)));
+  }
+  for (const T3& x : t)
+    if (x.n) HBP_TRY(launch_optim(d->dtype, adamw ? 1 : 0, x.w, x.master, x.g, x.m, x.v, x.n, clip, a, s));
+  return HBP_OK;
+}
+
+hbp_status hbp_train_step(const hbp_desc* d, int k, hbp_buffers* b, const void* target, float* loss_out,
+                          const hbp_optim* o, hbp_optim_state* st, void* stream) {
+  if (!b || !st) return HBP_E_NULL;
+  if (st->struct_size != sizeof(hbp_optim_state)) return HBP_E_INVALID_ARG;
+  HBP_RUN(hbp_forward(d, b, stream));
+  HBP_RUN(hbp_loss_mse(d, b, target, const_cast<void*>(b->e), loss_out, st->scratch, st->scratch_bytes, stream));
+  if (k < 0) HBP_RUN(hbp_exact_backward(d, b, stream));
+  else HBP_RUN(hbp_backward(d, k, b, stream));
+  HBP_RUN(hbp_param_grads(d, b, stream));
+  return hbp_optimizer_step(d, b, o, st, stream);
 }
 
 }  // extern "C"

@@ -269,6 +269,23 @@ hipError_t launch_lstm_fwd(int dtype, const float* pre, const void* x, void* gat
 hipError_t launch_lstm_vjp(int dtype, const void* g, const void* x, const void* xn, const void* gates, const void* e,
                            void* da, void* v, long rows, long H, hipStream_t s);
 
+// ---------------------------------------------------------------------------
+// the training step around the backward pass (train.hip)
+// ---------------------------------------------------------------------------
+struct OptimArgs {
+  float lr, beta1 /* SGD: momentum */, beta2, eps, weight_decay;
+  float inv_bias1, inv_bias2;     // AdamW: 1 / (1 - beta^step)
+};
+size_t train_scratch_floats();    // floats of scratch the reductions below need
+// e = (x - target) * inv_n over n elements (n % 8 == 0), loss[0] = 0.5 * inv_n * sum (x - target)^2
+hipError_t launch_mse_loss_grad(int dtype, const void* x, const void* target, void* e, long n, float inv_n,
+                                float* scratch, float* loss, hipStream_t s);
+hipError_t launch_zero(int dtype, void* p, long n, hipStream_t s);   // n % 8 == 0
+hipError_t launch_clip_factor(const float* const* grads, const long* sizes, int count, float max_norm, float* scratch,
+                              float* factor, hipStream_t s);
+hipError_t launch_optim(int dtype, int adamw, void* w, float* master, const float* g, float* m, float* v, long n,
+                        const float* clip, const OptimArgs& o, hipStream_t s);
+
 // y = x * rinv, rinv = 1/sqrt(mean(x^2)+eps) for `rows` rows of width d
 hipError_t launch_rmsnorm_fwd(int dtype, const void* x, void* y, float* rinv, long rows, long d, float eps,
                               hipStream_t s);

@@ -29,6 +29,8 @@ def test_struct_layout_matches_header():
     # field order and sizes as in the header (LP64)
     assert C.sizeof(B.hbp_desc) == 4 * 8 + 8 * 5 + 4 * 2
     assert C.sizeof(B.hbp_buffers) == 8 + 8 * 16 + 8 + 8
+    assert C.sizeof(B.hbp_optim) == 4 * 8 + 8
+    assert C.sizeof(B.hbp_optim_state) == 8 + 8 * 9 + 8 + 8
 
 
 def _desc(**kw):
