@@ -26,6 +26,9 @@ and erf are the only library steps; no blocking, fusion or reordering):
              with g = [a, b] and r(x, z) = z1 (.) x + z2, for the cell  u = sigmoid(W_u x + U_u xin),
              c = tanh(W_c x + U_c xin),  a = 1 - u,  b = u (.) c  (a GRU without its reset gate):
              K = dr/dx = diag(a), a function of the state, and J = diag(x) . da/dx + db/dx.
+             kind = 'gru' is the same row for the standard cell with its reset gate:  z = sigmoid(W_z x + U_z xin),
+             r = sigmoid(W_r x + U_r xin),  n = tanh(W_n (r (.) x) + U_n xin),  a = 1 - z,  b = z (.) n  (the
+             candidate sees the state through the reset gate: two dependent products per step).  K = diag(1 - z).
              kind = 'lstm' is the LSTM row: the state is x = [c | h] (cell and hidden part),
              f(x) = [a(x) (.) c + b(x), c3(x)] and r(x, z) = [z1 (.) c + z2, z3], for the standard cell
              i, f, o = sigmoid(.), gg = tanh(.) of W h + U xin,  c' = f (.) c + i (.) gg,  h' = o (.) tanh(c'):
@@ -70,7 +73,9 @@ F64 = np.float64
 class Stack:
     """A residual stack.
 
-    kind   'lstm'  one LSTM cell shared by all L (= T) steps, state [c | h] of width 2H:
+    kind   'gru'   one standard GRU cell shared by all L (= T) steps, state width H:
+                  W1 = [W_z; W_r; W_n] [3H,H], U = [U_z; U_r; U_n] [3H,d_in], no W2, no lam
+           'lstm'  one LSTM cell shared by all L (= T) steps, state [c | h] of width 2H:
                   W1 = [W_i; W_f; W_o; W_g] [4H,H] (acts on h), U likewise [4H,d_in], no W2, no lam
            'gated' one recurrent cell shared by all L (= T) steps, state width H:
                   W1 = [W_u; W_c] [2H,H], U = [U_u; U_c] [2H,d_in], no W2, no lam
@@ -101,14 +106,14 @@ class Stack:
 
     def __post_init__(self):
         assert self.post in ("none", "relu", "rms")
-        assert self.kind in ("mlp", "rnn", "gated", "lstm")
+        assert self.kind in ("mlp", "rnn", "gated", "lstm", "gru")
         assert self.act in ("gelu", "tanh", "identity")
         assert self.norm in ("none", "rms")
         self.W1 = np.asarray(self.W1, dtype=F64)
-        if self.kind in ("gated", "lstm"):
+        if self.kind in ("gated", "lstm", "gru"):
             assert self.W2 is None and self.lam is None and self.norm == "none" and self.post == "none"
             assert self.W1.ndim == 2 and self.L > 0
-            assert self.W1.shape[0] == (2 if self.kind == "gated" else 4) * self.W1.shape[1]
+            assert self.W1.shape[0] == {"gated": 2, "gru": 3, "lstm": 4}[self.kind] * self.W1.shape[1]
             self.U = np.asarray(self.U, dtype=F64)
             return
         self.W2 = np.asarray(self.W2, dtype=F64)
@@ -125,7 +130,7 @@ class Stack:
 
     @property
     def d(self) -> int:
-        if self.kind == "gated":
+        if self.kind in ("gated", "gru"):
             return self.W1.shape[-1]
         if self.kind == "lstm":
             return 2 * self.W1.shape[-1]
@@ -185,6 +190,8 @@ def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict
         return _forward_gated(st, x0, xin)
     if st.kind == "lstm":
         return _forward_lstm(st, x0, xin)
+    if st.kind == "gru":
+        return _forward_gru(st, x0, xin)
     L, dff = st.L, st.d_ff
     x = np.zeros((L + 1, N, d), F64)
     y = np.zeros((L, N, d), F64)
@@ -238,6 +245,27 @@ def _sigmoid(a: np.ndarray) -> np.ndarray:
     return 1.0 / (1.0 + np.exp(-a))
 
 
+def _forward_gru(st: Stack, x0: np.ndarray, xin: np.ndarray) -> Dict[str, np.ndarray]:
+    """The standard GRU: z = sigmoid(W_z x + U_z xin), r = sigmoid(W_r x + U_r xin),
+    n = tanh(W_n (r (.) x) + U_n xin), x' = (1 - z) (.) x + z (.) n.  Saved: x, the gates zrn = [z | r | n]
+    [L,N,3H] and a = 1 - z (the coefficient of the residual path)."""
+    N, H = x0.shape
+    L = st.L
+    Wz, Wr, Wn = st.W1[:H], st.W1[H:2 * H], st.W1[2 * H:]
+    x = np.zeros((L + 1, N, H), F64)
+    zrn = np.zeros((L, N, 3 * H), F64)
+    x[0] = x0
+    for l in range(L):
+        ux = np.asarray(xin[l], dtype=F64) @ st.U.T
+        z = _sigmoid(x[l] @ Wz.T + ux[:, :H])
+        r = _sigmoid(x[l] @ Wr.T + ux[:, H:2 * H])
+        n = np.tanh((r * x[l]) @ Wn.T + ux[:, 2 * H:])
+        x[l + 1] = (1.0 - z) * x[l] + z * n
+        zrn[l] = np.concatenate([z, r, n], axis=1)
+    return {"x": x, "y": x[:-1], "rinv": np.ones((L, N), F64), "zrn": zrn, "a": 1.0 - zrn[:, :, :H],
+            "mask": np.ones((L, N, H), F64)}
+
+
 def _forward_lstm(st: Stack, x0: np.ndarray, xin: np.ndarray) -> Dict[str, np.ndarray]:
     """x = [c | h];  [i, f, o, gg] = [sigmoid, sigmoid, sigmoid, tanh](W h + U xin);  c' = f (.) c + i (.) gg;
     h' = o (.) tanh(c').  Saved: x [L+1,N,2H], gates = [i | f | o | gg] [L,N,4H], a = [f | 0] [L,N,2H] (the
@@ -265,7 +293,7 @@ def _forward_lstm(st: Stack, x0: np.ndarray, xin: np.ndarray) -> Dict[str, np.nd
 def k_diag(st: Stack, l: int, saved: Dict[str, np.ndarray]) -> np.ndarray:
     """Diagonal of dr/dx for the layer that carries state l+1 to state l, before any mask: lam_l, or for the
     gated cell its own coefficient a_l = 1 - u_l (per token)."""
-    if st.kind in ("gated", "lstm"):
+    if st.kind in ("gated", "lstm", "gru"):
         return saved["a"][l]
     return st.lam_row(l)
 
@@ -280,6 +308,17 @@ def block_preact_grad(st: Stack, l: int, saved: Dict[str, np.ndarray], g_next: n
     if st.kind == "gated":
         u, c, x = saved["u"][l], saved["c"][l], saved["x"][l]
         return np.concatenate([g_next * (c - x) * u * (1.0 - u), g_next * u * (1.0 - c * c)], axis=1)
+    if st.kind == "gru":
+        # dL/dz = g (.) (n - x), dL/dn = g (.) z, through sigmoid' and tanh'; the reset gate receives what comes back
+        # from the candidate's product through r (.) x:  d(r (.) x) = dn_pre W_n,  dL/dr = d(r (.) x) (.) x
+        H = st.d
+        z, r, n = (saved["zrn"][l][:, j * H:(j + 1) * H] for j in range(3))
+        x = saved["x"][l]
+        dn = g_next * z * (1.0 - n * n)
+        dz = g_next * (n - x) * z * (1.0 - z)
+        drx = dn @ st.W1[2 * H:]
+        dr = drx * x * r * (1.0 - r)
+        return np.concatenate([dz, dr, dn], axis=1)
     if st.kind == "lstm":
         # g = [Gc | Gh] at the next state.  Everything that reaches c' : Gc and, through h' = o tanh(c'), Gh.
         H = st.d // 2
@@ -303,6 +342,11 @@ def block_vjp(st: Stack, l: int, saved: Dict[str, np.ndarray], g_next: np.ndarra
         f, o = saved["gates"][l][:, H:2 * H], saved["gates"][l][:, 2 * H:3 * H]
         tc = np.tanh(saved["x"][l + 1][:, :H])
         return np.concatenate([Gh * o * (1.0 - tc * tc) * f, da @ st.W1], axis=1)
+    if st.kind == "gru":
+        # into the state: through the two gates' weights, and through r (.) x directly (scaled by r)
+        H = st.d
+        r = saved["zrn"][l][:, H:2 * H]
+        return da[:, :2 * H] @ st.W1[:2 * H] + (da[:, 2 * H:] @ st.W1[2 * H:]) * r
     dn = da @ st.w1(l)
     if st.norm == "rms":
         # y = x / r, r = sqrt(mean(x^2) + eps):  dx = (dn - y * mean(dn (.) y)) / r
@@ -448,6 +492,17 @@ def param_grads(st: Stack, saved: Dict[str, np.ndarray], g: np.ndarray,
         for l in range(L):
             da = block_preact_grad(st, l, saved, g[l + 1])
             dW1 += da.T @ (saved["x"][l] if st.kind == "gated" else saved["x"][l][:, H:])
+            dU += da.T @ np.asarray(xin[l], dtype=F64)
+        return {"dW1": dW1, "dU": dU}
+    if st.kind == "gru":      # the candidate's weights see r (.) x, the gates' weights x
+        dW1 = np.zeros_like(st.W1)
+        dU = np.zeros_like(st.U)
+        H = st.d
+        for l in range(L):
+            da = block_preact_grad(st, l, saved, g[l + 1])
+            x, r = saved["x"][l], saved["zrn"][l][:, H:2 * H]
+            dW1[:2 * H] += da[:, :2 * H].T @ x
+            dW1[2 * H:] += da[:, 2 * H:].T @ (r * x)
             dU += da.T @ np.asarray(xin[l], dtype=F64)
         return {"dW1": dW1, "dU": dU}
     dW1 = np.zeros_like(st.W1)

@@ -734,6 +734,133 @@ def test_gated_cell_k0_and_finite_termination():
                 np.testing.assert_allclose(w[i], G[i], rtol=1e-11, atol=1e-13)
 
 
+# ---------------------------------------------------------------- the standard GRU (reset gate included)
+def small_gru(T=5, H=6, I=4, seed=0):
+    r = np.random.default_rng(seed)
+    W = r.standard_normal((3 * H, H)) / math.sqrt(H)
+    U = r.standard_normal((3 * H, I)) / math.sqrt(I)
+    return O.Stack("gru", "tanh", "none", W, None, U=U, L=T)
+
+
+def test_gru_cell_against_torch_autograd_and_torch_grucell_form():
+    """The standard GRU: states, every state gradient and both weight gradients against torch's autograd of the
+    same recurrence written out in fp64."""
+    r = np.random.default_rng(43)
+    N, I = 3, 5
+    st = small_gru(T=6, H=7, I=I)
+    H_ = st.d
+    xin = r.standard_normal((st.L, N, I))
+    x0 = r.standard_normal((N, H_)) * 0.5
+    c = r.standard_normal((st.L + 1, N, H_))
+    sv = O.forward(st, x0, xin)
+    G = O.exact_backward(st, sv, c)
+    pg = O.param_grads(st, sv, G, xin)
+    t = lambda a: torch.tensor(a, dtype=torch.float64, requires_grad=True)
+    W, U = t(st.W1), t(st.U)
+    xs = [t(x0)]
+    for l in range(st.L):
+        x = xs[-1]
+        ux = torch.tensor(xin[l]) @ U.T
+        z = torch.sigmoid(x @ W[:H_].T + ux[:, :H_])
+        rr = torch.sigmoid(x @ W[H_:2 * H_].T + ux[:, H_:2 * H_])
+        n = torch.tanh((rr * x) @ W[2 * H_:].T + ux[:, 2 * H_:])
+        nxt = (1 - z) * x + z * n
+        nxt.retain_grad()
+        xs.append(nxt)
+    loss = sum((torch.tensor(c[l]) * xs[l]).sum() for l in range(st.L + 1))
+    loss.backward()
+    for l in range(st.L + 1):
+        np.testing.assert_allclose(sv["x"][l], xs[l].detach().numpy(), rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(G[l], xs[l].grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(pg["dW1"], W.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(pg["dU"], U.grad.numpy(), rtol=1e-10, atol=1e-12)
+    # with the reset gate held open (its rows of W and U zero, a large constant input) the cell is the gated cell
+    H2 = 4
+    g2 = small_gated(T=4, H=H2, I=3, seed=8)
+    W3 = np.concatenate([g2.W1[:H2], np.zeros((H2, H2)), g2.W1[H2:]])
+    U3 = np.concatenate([g2.U[:H2], np.zeros((H2, 3)), g2.U[H2:]])
+    U3 = np.concatenate([U3, np.concatenate([np.zeros(H2), np.full(H2, 40.0), np.zeros(H2)])[:, None]], axis=1)
+    gr = O.Stack("gru", "tanh", "none", W3, None, U=U3, L=4)
+    xin2 = r.standard_normal((4, 2, 3))
+    x02 = r.standard_normal((2, H2)) * 0.5
+    sv_a = O.forward(g2, x02, xin2)
+    sv_b = O.forward(gr, x02, np.concatenate([xin2, np.ones((4, 2, 1))], axis=-1))
+    np.testing.assert_allclose(sv_b["x"], sv_a["x"], rtol=1e-12, atol=1e-13)
+    e2 = r.standard_normal((5, 2, H2))
+    for k in (0, 1, 2, 4):
+        np.testing.assert_allclose(O.hbp_backward(gr, sv_b, e2, k), O.hbp_backward(g2, sv_a, e2, k), rtol=1e-10, atol=1e-12)
+
+
+@pytest.mark.parametrize("gamma", [0.0, 0.4])
+def test_gru_cell_by_path_enumeration(gamma):
+    """Theorem 2 with K_l = diag(1 - z_l) and J_l = the Jacobian of h -> (1 - z(h)) (.) x_l + z(h) (.) n(h) with x_l
+    held fixed in the residual term, by central differences."""
+    st = small_gru(T=5, H=3, I=2, seed=3)
+    r = np.random.default_rng(9)
+    xin = r.standard_normal((st.L, 1, 2))
+    sv = O.forward(st, r.standard_normal((1, st.d)) * 0.5, xin)
+    e = r.standard_normal((st.L + 1, 1, st.d))
+    L, H_ = st.L, st.d
+
+    def jac(l):
+        x = sv["x"][l][0]
+
+        def via_g(h):
+            ux = st.U @ xin[l][0]
+            z = 1 / (1 + np.exp(-(st.W1[:H_] @ h + ux[:H_])))
+            rr = 1 / (1 + np.exp(-(st.W1[H_:2 * H_] @ h + ux[H_:2 * H_])))
+            n = np.tanh(st.W1[2 * H_:] @ (rr * h) + ux[2 * H_:])
+            return (1 - z) * x + z * n
+        J = np.zeros((H_, H_))
+        for i in range(H_):
+            hp, hm = x.copy(), x.copy()
+            hp[i] += 1e-6
+            hm[i] -= 1e-6
+            J[:, i] = (via_g(hp) - via_g(hm)) / 2e-6
+        return J
+    Kd = [np.diag(1 - sv["zrn"][l][0][:H_]) for l in range(L)]
+    Js = [jac(l) + gamma * Kd[l] for l in range(L)]
+    Ks = [(1 - gamma) * Kd[l] for l in range(L)]
+    for k in range(L + 1):
+        w = O.hbp_backward(st, sv, e, k, gamma=gamma)
+        for i in range(L + 1):
+            acc = np.zeros(H_)
+            for j in range(i, L + 1):
+                layers = list(range(i, j))
+                for size in range(min(k, len(layers)) + 1):
+                    for chosen in itertools.combinations(layers, size):
+                        vec = e[j][0].copy()
+                        for l in reversed(layers):
+                            vec = vec @ (Js[l] if l in chosen else Ks[l])
+                        acc += vec
+            np.testing.assert_allclose(w[i][0], acc, rtol=2e-6, atol=2e-8)
+    np.testing.assert_allclose(O.hbp_backward(st, sv, e, L, gamma=gamma), O.exact_backward(st, sv, e),
+                               rtol=1e-10, atol=1e-12)
+
+
+def test_gru_cell_parameter_gradients_by_finite_differences():
+    """Every entry of W1 = [W_z; W_r; W_n] and of U by central differences of a scalar loss."""
+    st = small_gru(T=4, H=3, I=2, seed=6)
+    r = np.random.default_rng(12)
+    xin = r.standard_normal((st.L, 2, 2))
+    x0 = r.standard_normal((2, st.d)) * 0.5
+    c = r.standard_normal((st.L + 1, 2, st.d))
+
+    def loss(W, U):
+        s2 = O.Stack("gru", "tanh", "none", W, None, U=U, L=st.L)
+        return float(np.sum(c * O.forward(s2, x0, xin)["x"]))
+    sv = O.forward(st, x0, xin)
+    pg = O.param_grads(st, sv, O.exact_backward(st, sv, c), xin)
+    for name, M in (("dW1", st.W1), ("dU", st.U)):
+        num = np.zeros_like(M)
+        for idx in np.ndindex(M.shape):
+            Mp, Mm = M.copy(), M.copy()
+            Mp[idx] += 1e-6
+            Mm[idx] -= 1e-6
+            num[idx] = ((loss(Mp, st.U) - loss(Mm, st.U)) if name == "dW1" else (loss(st.W1, Mp) - loss(st.W1, Mm))) / 2e-6
+        np.testing.assert_allclose(pg[name], num, rtol=2e-6, atol=2e-8)
+
+
 # ---------------------------------------------------------------- P14: the LSTM cell (LSTM row of the table)
 def small_lstm(T=5, H=4, I=3, seed=0):
     r = np.random.default_rng(seed)
