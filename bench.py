@@ -59,9 +59,9 @@ def algorithmic_work(w, k):
     blocks = sum(L - it + 1 for it in range(1, iters + 1))
     vjp1 = per_block * (blocks + L)        # + the one in hbp_param_grads
     vjp2 = per_block * blocks
-    rec = w.kind in ("rnn", "gated", "lstm")
+    rec = w.kind in ("rnn", "gated", "lstm", "gru")
     dw = 2.0 * per_block * L + (2.0 * N * L * dff * w.d_in if rec else 0.0)
-    cellk = w.kind in ("gated", "lstm")
+    cellk = w.kind in ("gated", "lstm", "gru")
     hw = d // 2 if w.kind == "lstm" else d             # width the cell's weights act on
     if cellk:                              # no second weight: one parameter contraction (over the hidden part), and
         per_block = 2.0 * N * hw * dff     # the first half of step (i) is elementwise (counted in bytes below)
@@ -72,7 +72,7 @@ def algorithmic_work(w, k):
     # per iteration the scan reads dn (+ y with a norm; + e only when a norm sits between
     # the block and the residual path: otherwise e was added by the second contraction)
     e_in_scan = w.loss_every_state and w.norm == "rms"
-    lam_tok = 1 if (w.lam == "sigmoid_full" or w.kind in ("gated", "lstm")) else 0   # coefficients per token: one more stream
+    lam_tok = 1 if (w.lam == "sigmoid_full" or w.kind in ("gated", "lstm", "gru")) else 0   # coefficients per token: one more stream
     streams_in = 1 + (1 if (w.norm == "rms" or w.post == "rms") else 0) + (1 if e_in_scan else 0) + lam_tok
     mask = S / 8.0 if w.post == "relu" else 0.0       # one bit per element per scan
     scan_iter = S * s * (streams_in + 1) + mask
@@ -94,6 +94,9 @@ def algorithmic_work(w, k):
     if w.kind == "gated":                  # reads g, x, [u | c]; writes da [N, 2H]
         def b1(nb):
             return nb * float(N) * (2 * d + 2 * dff) * s
+    if w.kind == "gru":                    # elementwise: g, x, [z | r | n] in, da [N,3H] out, tmp in and out; + the H x H product
+        def b1(nb):
+            return nb * float(N) * (2 * d + 2 * dff + 2 * d) * s
     if w.kind == "lstm":                   # reads g, c, c', the gates (+ e's cell half); writes da [N, 4H] and v's cell half
         def b1(nb):
             return nb * float(N) * (d + 2 * hw + 2 * dff + hw + (hw if w.loss_every_state else 0)) * s
@@ -194,7 +197,7 @@ def cpu_baseline(w, k, budget_tokens):
         threads = os.cpu_count() or 1
     n = min(budget_tokens, w.N)
     inp = synth.make_inputs(w, tokens=slice(0, n))
-    if w.kind in ("gated", "lstm"):
+    if w.kind in ("gated", "lstm", "gru"):
         st = O.Stack(w.kind, w.act, w.norm, inp["W1"], None, U=inp["U"], L=w.L)
     else:
         st = O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], U=inp["U"], eps=w.eps, L=w.L,
@@ -204,7 +207,7 @@ def cpu_baseline(w, k, budget_tokens):
     g = O.hbp_backward(st, sv, inp["e"], k)
     O.param_grads(st, sv, g, inp["xin"])
     dt = time.perf_counter() - t0
-    toks = n * (w.L if w.kind in ("rnn", "gated", "lstm") else 1)
+    toks = n * (w.L if w.kind in ("rnn", "gated", "lstm", "gru") else 1)
     return {"value": toks / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
             "sample": f"{n} of {w.N} token rows at full L={w.L}, d={w.d}, d_ff={w.d_ff}; "
                       f"hbp_backward(k={k}) + param_grads in {dt:.1f} s (forward untimed)"}
@@ -303,7 +306,7 @@ def main():
                 "avg_launch_ms": ms[cls] / max(launches[cls], 1)}
 
     roofs = {c: mfma_roof(c) for c in ("vjp1", "vjp2", "dw")}
-    if w.kind in ("gated", "lstm"):        # step (i)'s first half is elementwise there: memory roofline
+    if w.kind in ("gated", "lstm", "gru"):   # step (i)'s first half is elementwise there (GRU: plus an H x H product): memory roofline
         t1 = ms["vjp1"] * 1e-3
         a1 = work["vjp1_bytes"] / t1 / 1e9 if t1 > 0 else 0.0
         roofs["vjp1"] = {"bound": "hbm", "achieved": a1, "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -346,7 +349,7 @@ def main():
             B.hbp_param_grads(p)
         t = time_steps(torch, fe, reps, 1)
         sweep["exact"] = {"tokens_per_s": tokens / t, "ms": t * 1e3, "launch": "eager"}
-        if w.kind in ("rnn", "gated", "lstm"):
+        if w.kind in ("rnn", "gated", "lstm", "gru"):
             # Step-by-step backpropagation through time is thousands of short dependent launches: eager, it is
             # bound by the host's launch rate.  The same call sequence recorded once into a HIP graph and replayed
             # is the baseline that speed-ups are quoted against.
@@ -378,7 +381,7 @@ def main():
         abl = {}
         S_bytes = float(w.L) * w.N * w.d * storage_bytes(w)
         alg_bytes = S_bytes * (1 + (1 if w.loss_every_state else 0)
-                               + (1 if (w.lam == "sigmoid_full" or w.kind in ("gated", "lstm")) else 0))
+                               + (1 if (w.lam == "sigmoid_full" or w.kind in ("gated", "lstm", "gru")) else 0))
         algos = ("auto", "sequential")
         if w.post == "none":
             algos += ("chunked",) + (("single_pass",) if w.dtype == "bf16" else ()) + ("hillis_steele",)
@@ -422,7 +425,7 @@ def main():
         # about 10-20 s of oracle work on the GPU machine's host cores
         n = args.cpu_tokens or {"mlp_small_f32": 128, "resnet_like": 8192, "resnet_postact": 8192, "postnorm_mlp": 2048, "transformer_mlp": 2048,
                                 "deep_large": 256, "gated_rnn": 16, "gated_rnn_contractive": 16,
-                                "gated_rnn_token_gates": 16, "gru_cell": 16, "lstm_cell": 8}.get(w.name, 64)
+                                "gated_rnn_token_gates": 16, "gru_cell": 16, "gru_std_cell": 12, "lstm_cell": 8}.get(w.name, 64)
         out["cpu_baseline"] = cpu_baseline(w, k, n)
 
     def finite(o):   # JSON has no NaN/Infinity: overflowed error figures become null

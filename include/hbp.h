@@ -80,7 +80,13 @@ typedef enum { HBP_F32 = 0, HBP_BF16 = 1 } hbp_dtype;
  * Shapes: d = 2H, d_ff = 4H, W1 = [W_i; W_f; W_o; W_g] [4H,H] (acts on h), U likewise [4H,d_in]; z holds the
  * gates [i | f | o | gg] as [L,N,4H]; lambda ([L,N,2H], HBP_LAMBDA_TOKEN) is WRITTEN by hbp_forward as [f | 0].
  * dW1 is [4H,H].  Other rules as for HBP_GATED. */
-typedef enum { HBP_MLP = 0, HBP_RNN = 1, HBP_GATED = 2, HBP_LSTM = 3 } hbp_kind;
+/* HBP_GRU: the standard GRU, reset gate included (the GRU row of the table; the cell of the paper's RNN experiments):
+ *   z = sigmoid(W_z x + U_z xin), r = sigmoid(W_r x + U_r xin), n = tanh(W_n (r (.) x) + U_n xin), x' = (1 - z) (.) x + z (.) n.
+ * K = diag(1 - z); the block VJP is elementwise -> product with W_n -> elementwise -> product with [W_z; W_r].
+ * Shapes: d = H, d_ff = 3H, W1 = [W_z; W_r; W_n] [3H,H], U [3H,d_in]; z holds [z | r | n] as [L,N,3H]; lambda
+ * ([L,N,H], HBP_LAMBDA_TOKEN) is WRITTEN by hbp_forward as 1 - z.  Other rules as for HBP_GATED (which is this cell with the
+ * reset gate held open). */
+typedef enum { HBP_MLP = 0, HBP_RNN = 1, HBP_GATED = 2, HBP_LSTM = 3, HBP_GRU = 4 } hbp_kind;
 /* GELU is the exact erf form a*Phi(a); IDENTITY makes blocks linear (tests). */
 typedef enum { HBP_ACT_GELU_ERF = 0, HBP_ACT_TANH = 1, HBP_ACT_IDENTITY = 2 } hbp_act;
 /* RMS: y = x / sqrt(mean_c(x^2) + eps), no gain. */

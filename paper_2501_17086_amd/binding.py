@@ -21,8 +21,8 @@ HBP_OK = 0
 STATUS_NAMES = {0: "HBP_OK", 1: "HBP_E_INVALID_ARG", 2: "HBP_E_UNSUPPORTED", 3: "HBP_E_WORKSPACE",
                 4: "HBP_E_NULL", 5: "HBP_E_DEVICE"}
 F32, BF16 = 0, 1
-MLP, RNN, GATED, LSTM = 0, 1, 2, 3
-KIND = {"mlp": MLP, "rnn": RNN, "gated": GATED, "lstm": LSTM}
+MLP, RNN, GATED, LSTM, GRU = 0, 1, 2, 3, 4
+KIND = {"mlp": MLP, "rnn": RNN, "gated": GATED, "lstm": LSTM, "gru": GRU}
 ACT = {"gelu": 0, "tanh": 1, "identity": 2}
 NORM = {"none": 0, "rms": 1}
 POST = {"none": 0, "relu": 1, "rms": 2}
@@ -334,7 +334,7 @@ def allocate(w, inputs, device="cuda:0", N: Optional[int] = None) -> Problem:
         return None if a is None else torch.from_numpy(a).to(dev).to(dtype).contiguous()
 
     lam = inputs["lam"]
-    if w.kind in ("gated", "lstm"):   # the cell's own residual coefficient, written by hbp_forward: [L,N,d], storage type
+    if w.kind in ("gated", "lstm", "gru"):   # the cell's own residual coefficient, written by hbp_forward: [L,N,d], storage type
         lam = np.zeros((w.L, N, w.d), np.float32)
     per_token = lam is not None and lam.ndim == 3      # [L,N,d] in the storage type; [L,d] is fp32
     desc = make_desc(w.kind, w.dtype, w.act, w.norm, w.L, N, w.d, w.d_ff, w.d_in,

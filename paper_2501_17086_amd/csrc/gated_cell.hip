@@ -148,6 +148,114 @@ __global__ __launch_bounds__(256) void lstm_vjp_kernel(const T* __restrict__ g, 
   store8(v + n * 2 * H + j, vc);
 }
 
+// ---------------------------------------------------------------------------
+// The standard GRU (reset gate included): z = sigmoid(W_z x + U_z xin), r = sigmoid(W_r x + U_r xin),
+// n = tanh(W_n (r (.) x) + U_n xin), x' = (1 - z) x + z n.  The candidate's product depends on the reset gate, so a
+// step forward is two products with an elementwise kernel after each, and step (i) of the backward pass is
+// elementwise -> product with W_n -> elementwise -> product with [W_z; W_r].  Gates are kept as zrn = [z | r | n] [.,3H].
+// ---------------------------------------------------------------------------
+// forward, first half: pre [N,3H] fp32 (first 2H columns valid): z, r into zrn; rx [N,H] = r (.) x
+template <typename T>
+__global__ __launch_bounds__(256) void gru_fwd1_kernel(const float* __restrict__ pre, const T* __restrict__ x,
+                                                       T* __restrict__ zrn, T* __restrict__ rx, long N, long H) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long per_row = H / 8;
+  if (i >= N * per_row) return;
+  const long n = i / per_row, j = (i % per_row) * 8;
+  float pz[8], pr[8], xv[8], z[8], r[8], o[8];
+  load8(pre + n * 3 * H + j, pz);
+  load8(pre + n * 3 * H + H + j, pr);
+  load8(x + n * H + j, xv);
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    z[q] = sigmoidf_(pz[q]);
+    r[q] = sigmoidf_(pr[q]);
+    o[q] = r[q] * xv[q];
+  }
+  store8(zrn + n * 3 * H + j, z);
+  store8(zrn + n * 3 * H + H + j, r);
+  store8(rx + n * H + j, o);
+}
+// forward, second half: pre's last H columns = W_n (r (.) x) + U_n xin: n into zrn, a = 1 - z, xn = a x + z n
+template <typename T>
+__global__ __launch_bounds__(256) void gru_fwd2_kernel(const float* __restrict__ pre, const T* __restrict__ x,
+                                                       T* __restrict__ zrn, T* __restrict__ a, T* __restrict__ xn,
+                                                       long N, long H) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long per_row = H / 8;
+  if (i >= N * per_row) return;
+  const long n = i / per_row, j = (i % per_row) * 8;
+  float pn[8], xv[8], z[8], nn[8], av[8], o[8];
+  load8(pre + n * 3 * H + 2 * H + j, pn);
+  load8(x + n * H + j, xv);
+  load8(zrn + n * 3 * H + j, z);
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    nn[q] = tanhf(pn[q]);
+    av[q] = 1.f - z[q];
+    o[q] = fmaf(av[q], xv[q], z[q] * nn[q]);
+  }
+  store8(zrn + n * 3 * H + 2 * H + j, nn);
+  store8(a + n * H + j, av);
+  store8(xn + n * H + j, o);
+}
+// step (i), first elementwise part, for `rows` token rows: da [rows,3H]: columns 0..H = dL/dz through sigmoid',
+// columns 2H..3H = dL/dn through tanh' (columns H..2H are written by the second part)
+template <typename T>
+__global__ __launch_bounds__(256) void gru_vjp1_kernel(const T* __restrict__ g, const T* __restrict__ x,
+                                                       const T* __restrict__ zrn, T* __restrict__ da, long rows, long H) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long per_row = H / 8;
+  if (i >= rows * per_row) return;
+  const long n = i / per_row, j = (i % per_row) * 8;
+  float gv[8], xv[8], z[8], nn[8], dz[8], dn[8];
+  load8(g + n * H + j, gv);
+  load8(x + n * H + j, xv);
+  load8(zrn + n * 3 * H + j, z);
+  load8(zrn + n * 3 * H + 2 * H + j, nn);
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    dz[q] = gv[q] * (nn[q] - xv[q]) * z[q] * (1.f - z[q]);
+    dn[q] = gv[q] * z[q] * (1.f - nn[q] * nn[q]);
+  }
+  store8(da + n * 3 * H + j, dz);
+  store8(da + n * 3 * H + 2 * H + j, dn);
+}
+// step (i), second elementwise part: drx [rows,H] = dn W_n arrives; da's columns H..2H = drx (.) x (.) r (1 - r);
+// drx is overwritten by the state's direct share drx (.) r (+ e); rx (or NULL) = r (.) x for the parameter gradients
+template <typename T>
+__global__ __launch_bounds__(256) void gru_vjp2_kernel(T* __restrict__ drx, const T* __restrict__ x,
+                                                       const T* __restrict__ zrn, const T* __restrict__ e,
+                                                       T* __restrict__ da, T* __restrict__ rx, long rows, long H) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long per_row = H / 8;
+  if (i >= rows * per_row) return;
+  const long n = i / per_row, j = (i % per_row) * 8;
+  float dv[8], xv[8], r[8], dr[8], o[8];
+  load8(drx + n * H + j, dv);
+  load8(x + n * H + j, xv);
+  load8(zrn + n * 3 * H + H + j, r);
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    dr[q] = dv[q] * xv[q] * r[q] * (1.f - r[q]);
+    o[q] = dv[q] * r[q];
+  }
+  if (e) {
+    float ev[8];
+    load8(e + n * H + j, ev);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) o[q] += ev[q];
+  }
+  store8(da + n * 3 * H + H + j, dr);
+  store8(drx + n * H + j, o);
+  if (rx) {
+    float rxv[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) rxv[q] = r[q] * xv[q];
+    store8(rx + n * H + j, rxv);
+  }
+}
+
 }  // namespace
 
 hipError_t launch_lstm_fwd(int dtype, const float* pre, const void* x, void* gates, void* a, void* xn, long N, long H,
@@ -201,5 +309,37 @@ hipError_t launch_gated_vjp(int dtype, const void* g, const void* x, const void*
                        (const bf16_t*)uc, (bf16_t*)da, rows, H);
   return hipGetLastError();
 }
+
+#define HBP_GRU_LAUNCH(KERNEL, ROWS, ...)                                                                  \
+  do {                                                                                                      \
+    const long n_ = (ROWS) * (H / 8);                                                                       \
+    dim3 grid((unsigned)((n_ + 255) / 256)), block(256);                                                    \
+    hipLaunchKernelGGL(KERNEL<T>, grid, block, 0, s, __VA_ARGS__);                                          \
+  } while (0)
+
+hipError_t launch_gru_fwd1(int dtype, const float* pre, const void* x, void* zrn, void* rx, long N, long H, hipStream_t s) {
+  if (dtype == 0) { typedef float T; HBP_GRU_LAUNCH(gru_fwd1_kernel, N, pre, (const T*)x, (T*)zrn, (T*)rx, N, H); }
+  else { typedef bf16_t T; HBP_GRU_LAUNCH(gru_fwd1_kernel, N, pre, (const T*)x, (T*)zrn, (T*)rx, N, H); }
+  return hipGetLastError();
+}
+hipError_t launch_gru_fwd2(int dtype, const float* pre, const void* x, void* zrn, void* a, void* xn, long N, long H,
+                           hipStream_t s) {
+  if (dtype == 0) { typedef float T; HBP_GRU_LAUNCH(gru_fwd2_kernel, N, pre, (const T*)x, (T*)zrn, (T*)a, (T*)xn, N, H); }
+  else { typedef bf16_t T; HBP_GRU_LAUNCH(gru_fwd2_kernel, N, pre, (const T*)x, (T*)zrn, (T*)a, (T*)xn, N, H); }
+  return hipGetLastError();
+}
+hipError_t launch_gru_vjp1(int dtype, const void* g, const void* x, const void* zrn, void* da, long rows, long H,
+                           hipStream_t s) {
+  if (dtype == 0) { typedef float T; HBP_GRU_LAUNCH(gru_vjp1_kernel, rows, (const T*)g, (const T*)x, (const T*)zrn, (T*)da, rows, H); }
+  else { typedef bf16_t T; HBP_GRU_LAUNCH(gru_vjp1_kernel, rows, (const T*)g, (const T*)x, (const T*)zrn, (T*)da, rows, H); }
+  return hipGetLastError();
+}
+hipError_t launch_gru_vjp2(int dtype, void* drx, const void* x, const void* zrn, const void* e, void* da, void* rx,
+                           long rows, long H, hipStream_t s) {
+  if (dtype == 0) { typedef float T; HBP_GRU_LAUNCH(gru_vjp2_kernel, rows, (T*)drx, (const T*)x, (const T*)zrn, (const T*)e, (T*)da, (T*)rx, rows, H); }
+  else { typedef bf16_t T; HBP_GRU_LAUNCH(gru_vjp2_kernel, rows, (T*)drx, (const T*)x, (const T*)zrn, (const T*)e, (T*)da, (T*)rx, rows, H); }
+  return hipGetLastError();
+}
+#undef HBP_GRU_LAUNCH
 
 }  // namespace hbp

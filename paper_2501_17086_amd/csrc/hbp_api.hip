@@ -22,7 +22,8 @@ namespace {
 
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline size_t esize(const hbp_desc* d) { return d->dtype == HBP_F32 ? 4 : 2; }
-inline bool cell(const hbp_desc* d) { return d->kind == HBP_GATED || d->kind == HBP_LSTM; }
+inline bool cell(const hbp_desc* d) { return d->kind == HBP_GATED || d->kind == HBP_LSTM || d->kind == HBP_GRU; }
+inline bool gru(const hbp_desc* d) { return d->kind == HBP_GRU; }
 inline bool recurrent(const hbp_desc* d) { return d->kind == HBP_RNN || cell(d); }
 // A cell's weights act on the hidden part of the state: all of it (GATED), or the second half of [c | h] (LSTM).
 inline long hidden_w(const hbp_desc* d) { return d->kind == HBP_LSTM ? d->d / 2 : d->d; }
@@ -30,7 +31,7 @@ inline long hidden_off(const hbp_desc* d) { return d->kind == HBP_LSTM ? d->d / 
 inline bool shared_w(const hbp_desc* d) { return recurrent(d); }
 
 struct Workspace {
-  size_t off_v, off_da, off_part, off_scan, off_wt, off_pre, off_m, total;
+  size_t off_v, off_da, off_part, off_scan, off_wt, off_pre, off_m, off_tmp, total;
 };
 
 // split-K factor for a parameter-gradient GEMM with `tiles` output tiles and a
@@ -96,12 +97,16 @@ Workspace carve(const hbp_desc* d) {
   // post-norm: mean(G (.) x) per (layer, token) of the previous and of the current estimate
   w.off_m = o;
   if (d->post == HBP_POST_RMS) o = align_up(o + 2 * (size_t)d->L * d->N * 4, 256);
+  // the standard GRU: what comes back through the candidate's product, [L,N,H] in the storage type
+  w.off_tmp = o;
+  if (gru(d)) o = align_up(o + (size_t)d->L * d->N * d->d * es, 256);
   w.total = o;
   return w;
 }
 
 // One step of the recurrence at a time, few rows: the few-row kernel with transposed weights.
 inline bool step_skinny(const hbp_desc* d) {
+  if (gru(d)) return d->dtype == HBP_BF16 && skinny_ok(d->N, d->d, d->d);   // products H x H and H x 2H, 2H x H
   return recurrent(d) && d->dtype == HBP_BF16 && skinny_ok(d->N, d->d_ff, hidden_w(d)) &&
          skinny_ok(d->N, hidden_w(d), d->d_ff);
 }
@@ -109,7 +114,7 @@ inline bool step_skinny(const hbp_desc* d) {
 hbp_status check_desc(const hbp_desc* d) {
   if (!d) return HBP_E_NULL;
   if (d->struct_size != sizeof(hbp_desc)) return HBP_E_INVALID_ARG;
-  if (d->kind < HBP_MLP || d->kind > HBP_LSTM) return HBP_E_INVALID_ARG;
+  if (d->kind < HBP_MLP || d->kind > HBP_GRU) return HBP_E_INVALID_ARG;
   if (d->dtype != HBP_F32 && d->dtype != HBP_BF16) return HBP_E_INVALID_ARG;
   if (d->act < HBP_ACT_GELU_ERF || d->act > HBP_ACT_IDENTITY) return HBP_E_INVALID_ARG;
   if (d->norm != HBP_NORM_NONE && d->norm != HBP_NORM_RMS) return HBP_E_INVALID_ARG;
@@ -118,7 +123,7 @@ hbp_status check_desc(const hbp_desc* d) {
   if (d->L <= 0 || d->N <= 0 || d->d <= 0 || d->d_ff <= 0 || d->d_in < 0) return HBP_E_INVALID_ARG;
   if (recurrent(d) && d->d_in <= 0) return HBP_E_INVALID_ARG;
   if (cell(d) && (d->act != HBP_ACT_TANH || d->norm != HBP_NORM_NONE || d->lambda_kind != HBP_LAMBDA_TOKEN ||
-                  d->d_ff != 2 * d->d))
+                  d->d_ff != (gru(d) ? 3 : 2) * d->d))
     return HBP_E_INVALID_ARG;
   if (d->kind == HBP_LSTM && d->d % 16) return HBP_E_UNSUPPORTED;   // both halves of [c | h] in 16-byte vectors
   if (d->kind == HBP_MLP && d->d_in != 0) return HBP_E_INVALID_ARG;
@@ -227,9 +232,45 @@ inline bool e_in_vjp(const hbp_desc* d) { return d->loss_every_state && d->norm 
 
 // da[l] = (g[l+1] . W2_l) (.) act'(a_l) for blocks l_lo..l_hi-1
 hbp_status vjp_stage1(const hbp_desc* d, const hbp_buffers* b, const Workspace& w, long l_lo, long l_hi,
-                      hipStream_t s, bool skinny = false) {
+                      hipStream_t s, bool skinny = false, void* rx_out = nullptr) {
   const size_t es = esize(d);
   const long nl = l_hi - l_lo;
+  if (gru(d)) {
+    // dL/dz and dL/dn elementwise; what comes back through the candidate's product, tmp = dn W_n; then dL/dr and the
+    // state's direct share tmp (.) r (+ e), which the second contraction's epilogue adds to its product
+    const long H = d->d, rows = nl * d->N;
+    const size_t so = (size_t)l_lo * d->N * H * es, fo = (size_t)l_lo * d->N * d->d_ff * es;
+    void* da = at(b->workspace, w.off_da + fo);
+    void* tmp = at(b->workspace, w.off_tmp + so);
+    ProfScope ps(HBP_PROF_VJP1, s);
+    HBP_TRY(launch_gru_vjp1(d->dtype, at(b->g, so + (size_t)d->N * H * es), at((const void*)b->x, so),
+                            at((const void*)b->z, fo), da, rows, H, s));
+    if (skinny) {     // W_n^T [H,H] sits after [W_z; W_r]^T [H,2H] in the transposed-weight region
+      SkinnyArgs k{};
+      k.A = at((const void*)da, (size_t)2 * H * es); k.lda = d->d_ff;
+      k.Bt = at(b->workspace, w.off_wt + (size_t)2 * H * H * es); k.ldbt = H;
+      k.C = tmp; k.ldc = H;
+      k.M = rows; k.N = H; k.K = H;
+      k.mode = EPI_STORE;
+      HBP_TRY(launch_gemm_skinny(k, s));
+    } else {
+      GemmArgs ga{};
+      ga.A = at((const void*)da, (size_t)2 * H * es);
+      ga.B = at(b->W1, (size_t)2 * H * H * es);
+      ga.C = tmp;
+      ga.M = rows; ga.N = H; ga.K = H;
+      ga.a_sm = d->d_ff; ga.a_sk = 1;
+      ga.b_sk = H; ga.b_sn = 1;
+      ga.ldc = H; ga.batch = 1; ga.split_k = 1;
+      ga.mode = EPI_STORE;
+      hipError_t err = hipSuccess;
+      if (!(d->dtype == HBP_BF16 && launch_gemm_mfma(ga, s, &err))) err = launch_gemm_generic(d->dtype, ga, s);
+      if (err != hipSuccess) return HBP_E_DEVICE;
+    }
+    HBP_TRY(launch_gru_vjp2(d->dtype, tmp, at((const void*)b->x, so), at((const void*)b->z, fo),
+                            e_in_vjp(d) ? at(b->e, so) : nullptr, da, rx_out, rows, H, s));
+    return HBP_OK;
+  }
   if (d->kind == HBP_GATED) {   // no first contraction: dL/du and dL/dc through sigmoid' and tanh', elementwise
     ProfScope ps(HBP_PROF_VJP1, s);
     HBP_TRY(launch_gated_vjp(d->dtype, at(b->g, (size_t)(l_lo + 1) * d->N * d->d * es),
@@ -300,14 +341,19 @@ hbp_status vjp_stage2(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
   // written by the elementwise kernel and W1 is [d_ff, H]).
   const long hw = hidden_w(d);
   const size_t ho = (size_t)hidden_off(d) * es;
-  if (skinny) {   // W1^T [hw,d_ff] follows W2^T
+  // the standard GRU: the product runs over the two gates' 2H columns of da against [W_z; W_r], and the state's
+  // direct share (with e already in it) comes in from the buffer the first stage left
+  const long kk = gru(d) ? 2 * d->d : d->d_ff;
+  const void* gru_aux = gru(d) ? at((const void*)b->workspace, w.off_tmp + (size_t)l_lo * d->N * d->d * es) : nullptr;
+  if (skinny) {   // W1^T [hw,d_ff] follows W2^T (GRU: [W_z; W_r]^T [H,2H] comes first)
     SkinnyArgs k{};
     k.A = at(b->workspace, w.off_da + (size_t)l_lo * d->N * d->d_ff * es); k.lda = d->d_ff;
-    k.Bt = at(b->workspace, w.off_wt + (size_t)d->d * d->d_ff * es); k.ldbt = d->d_ff;
+    k.Bt = at(b->workspace, w.off_wt + (gru(d) ? 0 : (size_t)d->d * d->d_ff * es)); k.ldbt = kk;
     k.C = at(b->workspace, w.off_v + (size_t)l_lo * d->N * d->d * es + ho); k.ldc = d->d;
-    k.M = d->N; k.N = hw; k.K = d->d_ff;
+    k.M = d->N; k.N = hw; k.K = kk;
     k.mode = EPI_STORE;
-    if (e_in_vjp(d)) { k.mode = EPI_ADD_AUX; k.aux = at(b->e, (size_t)l_lo * d->N * d->d * es + ho); k.ldaux = d->d; }
+    if (gru(d)) { k.mode = EPI_ADD_AUX; k.aux = gru_aux; k.ldaux = d->d; }
+    else if (e_in_vjp(d)) { k.mode = EPI_ADD_AUX; k.aux = at(b->e, (size_t)l_lo * d->N * d->d * es + ho); k.ldaux = d->d; }
     if (fuse_scan) {   // g_l = v_l (+ e_l) + lambda_l (.) g_{l+1} written straight into g
       k.C = at(b->g, (size_t)l_lo * d->N * d->d * es);
       k.next = at(b->g, (size_t)(l_lo + 1) * d->N * d->d * es);
@@ -325,7 +371,7 @@ hbp_status vjp_stage2(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
   ga.C = at(b->workspace, w.off_v + (size_t)l_lo * d->N * d->d * es + ho);
   ga.M = sh ? nl * d->N : d->N;
   ga.N = hw;
-  ga.K = d->d_ff;
+  ga.K = kk;
   ga.a_sm = d->d_ff; ga.a_sk = 1;
   ga.b_sk = hw; ga.b_sn = 1;
   ga.ldc = d->d;
@@ -333,7 +379,11 @@ hbp_status vjp_stage2(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
   ga.a_sb = d->N * d->d_ff; ga.b_sb = d->d * d->d_ff; ga.c_sb = d->N * d->d;
   ga.split_k = 1;
   ga.mode = EPI_STORE;
-  if (e_in_vjp(d)) {   // v_l + e_l in the epilogue: the scan then reads one stream less
+  if (gru(d)) {
+    ga.mode = EPI_ADD_AUX;
+    ga.aux = gru_aux;
+    ga.aux_sb = d->N * d->d;
+  } else if (e_in_vjp(d)) {   // v_l + e_l in the epilogue: the scan then reads one stream less
     ga.mode = EPI_ADD_AUX;
     ga.aux = at(b->e, (size_t)l_lo * d->N * d->d * es + ho);
     ga.aux_sb = d->N * d->d;
@@ -512,6 +562,47 @@ hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
       HBP_TRY(launch_rmsnorm_fwd(d->dtype, at((const void*)b->x, xo), at(b->y, xo), b->rinv + l * d->N, d->N, d->d,
                                  d->eps, s));
       yl = at((const void*)b->y, xo);
+    }
+    if (gru(d)) {
+      // two dependent products per step: the gates z, r from x; then the candidate from r (.) x
+      float* pre = reinterpret_cast<float*>(at(b->workspace, w.off_pre));
+      void* rx = at(b->workspace, w.off_tmp);
+      const long H = d->d;
+      const float* uxl = ux + l * d->N * d->d_ff;
+      auto product = [&](const void* A, long n_out, long col0) -> hbp_status {   // pre[:, col0 .. col0 + n_out) = A W^T + ux
+        const void* Wp = at(b->W1, (size_t)col0 * H * es);
+        if (skinny) {
+          SkinnyArgs k{};
+          k.A = A; k.lda = H;
+          k.Bt = Wp; k.ldbt = H;
+          k.C = pre + col0; k.ldc = d->d_ff; k.c_is_f32 = 1;
+          k.M = d->N; k.N = n_out; k.K = H;
+          k.mode = EPI_STORE;
+          k.addf = uxl + col0;
+          ProfScope ps(HBP_PROF_FORWARD, s);
+          HBP_TRY(launch_gemm_skinny(k, s));
+          return HBP_OK;
+        }
+        GemmArgs ga{};
+        ga.A = A; ga.B = Wp; ga.C = pre + col0;
+        ga.M = d->N; ga.N = n_out; ga.K = H;
+        ga.a_sm = H; ga.a_sk = 1;
+        ga.b_sk = 1; ga.b_sn = H;
+        ga.ldc = d->d_ff; ga.batch = 1; ga.split_k = 1;
+        ga.mode = EPI_STORE; ga.c_is_f32 = 1;
+        ga.addf = uxl + col0;
+        return run_gemm(d, ga, s, HBP_PROF_FORWARD);
+      };
+      HBP_RUN(product(yl, 2 * H, 0));
+      {
+        ProfScope ps(HBP_PROF_FORWARD, s);
+        HBP_TRY(launch_gru_fwd1(d->dtype, pre, yl, at(b->z, fo), rx, d->N, H, s));
+      }
+      HBP_RUN(product(rx, H, 2 * H));
+      ProfScope ps(HBP_PROF_FORWARD, s);
+      HBP_TRY(launch_gru_fwd2(d->dtype, pre, yl, at(b->z, fo), at(b->lambda, xo), at(b->x, xo + (size_t)d->N * H * es),
+                              d->N, H, s));
+      continue;
     }
     if (cell(d)) {
       // pre = h W1^T + U xin (fp32), then the cell elementwise: z[l] = the gates, lambda[l] = the residual
@@ -770,7 +861,13 @@ hbp_status hbp_exact_backward(const hbp_desc* d, hbp_buffers* b, void* stream) {
   const bool skinny = step_skinny(d);
   // the step along the residual path in the same kernel (not for the LSTM, whose cell half is not a product)
   const bool fuse = skinny && d->norm == HBP_NORM_NONE && d->kind != HBP_LSTM;
-  if (skinny) {
+  if (skinny && gru(d)) {   // [W_z; W_r]^T [H,2H], then W_n^T [H,H]
+    ProfScope ps(HBP_PROF_OTHER, s);
+    const long H = d->d;
+    HBP_TRY(launch_transpose_bf16(bb.W1, at(bb.workspace, w.off_wt), (int)(2 * H), (int)H, s));
+    HBP_TRY(launch_transpose_bf16(at(bb.W1, (size_t)2 * H * H * esize(d)),
+                                  at(bb.workspace, w.off_wt + (size_t)2 * H * H * esize(d)), (int)H, (int)H, s));
+  } else if (skinny) {
     ProfScope ps(HBP_PROF_OTHER, s);
     if (!cell(d))
       HBP_TRY(launch_transpose_bf16(bb.W2, at(bb.workspace, w.off_wt), (int)d->d, (int)d->d_ff, s));
@@ -795,8 +892,8 @@ hbp_status hbp_param_grads(const hbp_desc* d, hbp_buffers* b, void* stream) {
   hbp_buffers bb = *b;
   if (d->norm == HBP_NORM_NONE) bb.y = bb.x;
   const Splits sp = param_splits(d);
-  // da from the final estimate
-  HBP_RUN(vjp_stage1(d, &bb, w, 0, d->L, s));
+  // da from the final estimate (the standard GRU also leaves r (.) x, the candidate weights' operand, in the v buffer)
+  HBP_RUN(vjp_stage1(d, &bb, w, 0, d->L, s, false, gru(d) ? at(b->workspace, w.off_v) : nullptr));
   const long K = sh ? d->L * d->N : d->N;
   const long nb = sh ? 1 : d->L;
   void* part = at(b->workspace, w.off_part);
@@ -807,6 +904,12 @@ hbp_status hbp_param_grads(const hbp_desc* d, hbp_buffers* b, void* stream) {
     HBP_RUN(tn_gemm(d, g1, d->d, d->N * d->d, bb.z, d->d_ff, d->N * d->d_ff, bb.dW2, d->d, d->d_ff, K, nb, sp.s_w2,
                     part, s));
   // dW1[j,c] = sum_n da_l[n,j] y_l[n,c]   (a cell: over the hidden part of the state)
+  if (gru(d)) {      // rows of the two gates against x, rows of the candidate against r (.) x
+    const long H = d->d;
+    HBP_RUN(tn_gemm(d, da, d->d_ff, 0, bb.y, H, 0, bb.dW1, 2 * H, H, K, 1, sp.s_w1, part, s));
+    HBP_RUN(tn_gemm(d, at(da, (size_t)2 * H * es), d->d_ff, 0, at((const void*)b->workspace, w.off_v), H, 0,
+                    bb.dW1 + 2 * H * H, H, H, K, 1, sp.s_w1, part, s));
+  } else
   HBP_RUN(tn_gemm(d, da, d->d_ff, d->N * d->d_ff, at((const void*)bb.y, (size_t)hidden_off(d) * es), d->d,
                   d->N * d->d, bb.dW1, d->d_ff, hidden_w(d), K, nb, sp.s_w1, part, s));
   if (recurrent(d)) {

@@ -261,6 +261,16 @@ hipError_t launch_gated_fwd(int dtype, const float* pre, const void* x, void* uc
 hipError_t launch_gated_vjp(int dtype, const void* g, const void* x, const void* uc, void* da, long rows, long H,
                             hipStream_t s);
 
+// The standard GRU's elementwise parts (gates kept as zrn = [z | r | n] [.,3H]; H % 8 == 0): the two halves of a step
+// forward (pre [N,3H] fp32), and of step (i) for `rows` token rows (see gated_cell.hip).
+hipError_t launch_gru_fwd1(int dtype, const float* pre, const void* x, void* zrn, void* rx, long N, long H, hipStream_t s);
+hipError_t launch_gru_fwd2(int dtype, const float* pre, const void* x, void* zrn, void* a, void* xn, long N, long H,
+                           hipStream_t s);
+hipError_t launch_gru_vjp1(int dtype, const void* g, const void* x, const void* zrn, void* da, long rows, long H,
+                           hipStream_t s);
+hipError_t launch_gru_vjp2(int dtype, void* drx, const void* x, const void* zrn, const void* e, void* da, void* rx,
+                           long rows, long H, hipStream_t s);
+
 // The LSTM cell's elementwise parts (state [c | h] of width 2H, gates [i | f | o | gg] of width 4H, H % 8 == 0):
 // one step forward from pre [N,4H] fp32; step (i) up to its contraction for `rows` token rows (g: gradient of the
 // rows' next states, x / xn: current / next states, e: per-state loss gradients whose cell half is added to v, or NULL).

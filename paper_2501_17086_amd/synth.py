@@ -31,7 +31,7 @@ _T_W1, _T_W2, _T_U, _T_LAM, _T_X0, _T_XIN, _T_E = 1, 2, 3, 4, 5, 6, 7
 class Workload:
     name: str
     kind: str            # 'mlp' | 'rnn' | 'gated' (recurrent cell x' = (1-u) x + u c; d_ff = 2 d) | 'lstm' (state
-                         # [c | h], d = 2H, d_ff = 4H)
+                         # [c | h], d = 2H, d_ff = 4H) | 'gru' (the standard GRU, gates [z | r | n]; d_ff = 3 d)
     dtype: str           # 'f32' | 'bf16'   (storage; accumulation is fp32 on the GPU)
     act: str             # 'gelu' | 'tanh' | 'identity'
     norm: str            # 'none' | 'rms'
@@ -56,7 +56,7 @@ class Workload:
 
     @property
     def tokens(self) -> int:
-        return self.N * self.L if self.kind in ("rnn", "gated", "lstm") else self.N
+        return self.N * self.L if self.kind in ("rnn", "gated", "lstm", "gru") else self.N
 
 
 WORKLOADS: Dict[str, Workload] = {
@@ -91,6 +91,9 @@ WORKLOADS["gated_rnn_contractive"] = replace(WORKLOADS["gated_rnn"], name="gated
 # decompositions): T = 4096, batch 32, H = 1024, gates biased towards closed (1 - u around 0.95)
 WORKLOADS["gru_cell"] = Workload("gru_cell", "gated", "bf16", "tanh", "none", L=4096, N=32, d=1024, d_ff=2048,
                                  d_in=1024, loss_every_state=True, gate_bias=-3.0, rec_scale=0.5)
+# the standard GRU (reset gate included), the cell of the paper's GRU experiments, at the same sizes
+WORKLOADS["gru_std_cell"] = Workload("gru_std_cell", "gru", "bf16", "tanh", "none", L=4096, N=32, d=1024, d_ff=3072,
+                                     d_in=1024, loss_every_state=True, gate_bias=-3.0, rec_scale=0.5)
 # an LSTM cell (the LSTM row of the same table): state [c | h] of 2 x 1024, forget gates around 0.95
 WORKLOADS["lstm_cell"] = Workload("lstm_cell", "lstm", "bf16", "tanh", "none", L=4096, N=32, d=2048, d_ff=4096,
                                   d_in=1024, loss_every_state=True, gate_bias=3.0, rec_scale=0.5)
@@ -126,7 +129,7 @@ def _normal(w: Workload, tid: int, idx: int, shape, std: float) -> np.ndarray:
 
 def weights_block(w: Workload, l: int):
     """(W1_l [d_ff,d], W2_l [d,d_ff]) for block l (rnn: l is ignored)."""
-    idx = 0 if w.kind in ("rnn", "gated", "lstm") else l
+    idx = 0 if w.kind in ("rnn", "gated", "lstm", "gru") else l
     if w.kind == "lstm":       # W1 = [W_i; W_f; W_o; W_g] acts on the hidden half of the state
         H = w.d // 2
         return storage_round(w, _normal(w, _T_W1, idx, (w.d_ff, H), w.rec_scale / np.sqrt(H))), None
@@ -183,6 +186,14 @@ def make_inputs(w: Workload, tokens=None) -> Dict[str, Optional[np.ndarray]]:
         out["U"] = storage_round(w, _normal(w, _T_U, 0, (w.d_ff, w.d_in), 1.0 / np.sqrt(w.d_in)))
         out["xin"] = storage_round(w, _normal(w, _T_XIN, 0, (w.L, w.N, w.d_in), 1.0)[:, sl])
     out["W1"], out["W2"] = W1, W2
+    if w.kind == "gru":
+        # W1 = [W_z; W_r; W_n]; as for the gated cell below, a constant bias of the update gate z through input channel 0
+        out["W2"] = None
+        H = w.d
+        out["xin"][..., 0] = 1.0
+        out["U"][:H, 0] = np.float32(w.gate_bias)
+        out["U"][H:, 0] = 0.0
+        out["U"] = storage_round(w, out["U"])
     if w.kind == "gated":
         # W1 = [W_u; W_c].  The cell has no bias term: a constant update-gate bias (gates that are mostly closed,
         # i.e. a long memory, as in a trained GRU) is realised through the input: channel 0 of xin is 1 and its
@@ -202,7 +213,7 @@ def make_inputs(w: Workload, tokens=None) -> Dict[str, Optional[np.ndarray]]:
         out["U"][H:2 * H, 0] = np.float32(w.gate_bias)
         out["U"] = storage_round(w, out["U"])
     out["lam"] = make_lambda(w, tokens)
-    if w.kind in ("rnn", "gated", "lstm"):
+    if w.kind in ("rnn", "gated", "lstm", "gru"):
         out["x0"] = np.zeros((w.N, w.d), np.float32)[sl]
     else:
         out["x0"] = storage_round(w, _normal(w, _T_X0, 0, (w.N, w.d), 1.0)[sl])

@@ -12,7 +12,7 @@ TOL = {"f32": 1e-5, "bf16": 2e-2}   # relative L2, GPU vs oracle
 
 
 def oracle_stack(w: synth.Workload, inp) -> O.Stack:
-    if w.kind in ("gated", "lstm"):
+    if w.kind in ("gated", "lstm", "gru"):
         return O.Stack(w.kind, w.act, w.norm, inp["W1"], None, U=inp["U"], L=w.L)
     return O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], U=inp["U"], eps=w.eps, L=w.L,
                    post=w.post)
@@ -34,6 +34,11 @@ def oracle_saved_rounded(w: synth.Workload, sv):
         return out
     if w.kind == "lstm":
         for k in ("x", "gates", "a"):
+            out[k] = r(sv[k])
+        out["y"] = out["x"][:-1]
+        return out
+    if w.kind == "gru":
+        for k in ("x", "zrn", "a"):
             out[k] = r(sv[k])
         out["y"] = out["x"][:-1]
         return out
@@ -64,6 +69,10 @@ def upload_saved(p, w: synth.Workload, sv_r):
         return
     if w.kind == "lstm":       # z = the four gates side by side, lambda = [f | 0]
         put(p.z, sv_r["gates"])
+        put(p.lam, sv_r["a"])
+        return
+    if w.kind == "gru":        # z = [z | r | n], lambda = 1 - z
+        put(p.z, sv_r["zrn"])
         put(p.lam, sv_r["a"])
         return
     put(p.y, sv_r["y"])

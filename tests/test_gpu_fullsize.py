@@ -76,14 +76,19 @@ def _projection_check(p, w, inp, tol):
     else:
         # the cells: da of every step from the oracle's own definition, on the library's g and saved state
         st = H.oracle_stack(w, inp)
-        Hh = w.d if w.kind == "gated" else w.d // 2
+        Hh = w.d // 2 if w.kind == "lstm" else w.d
         zz = H.to_np(p.z)
-        saved = {"x": H.to_np(p.x), "u": zz[..., :Hh], "c": zz[..., Hh:], "gates": zz}
+        saved = {"x": H.to_np(p.x), "u": zz[..., :Hh], "c": zz[..., Hh:], "gates": zz, "zrn": zz}
         gg = H.to_np(p.g)
         da_np = np.stack([O.block_preact_grad(st, l, saved, gg[l + 1]) for l in range(L)])
         da = torch.from_numpy(da_np.reshape(-1, w.d_ff)).to(dev)
         y = p.x[:-1][..., w.d - Hh:].reshape(-1, Hh).double()      # the part of the state the weights act on
-    check("dW1", p.dW1, da, y)
+    if w.kind == "gru":     # the gates' rows see x, the candidate's rows r (.) x
+        r = p.z[..., Hh:2 * Hh].reshape(-1, Hh).double()
+        check("dW1[z, r]", p.dW1[:2 * Hh], da[:, :2 * Hh], y)
+        check("dW1[n]", p.dW1[2 * Hh:], da[:, 2 * Hh:], r * y)
+    else:
+        check("dW1", p.dW1, da, y)
     check("dU", p.dU, da, xin)
 
 
@@ -174,6 +179,11 @@ def test_gru_cell_cut_to_2_rows_every_element(B):
 
 
 @pytest.mark.timeout(300)
+def test_gru_std_cell_cut_to_2_rows_every_element(B):
+    _run_cut(B, synth.scaled(W["gru_std_cell"], name="gru_std_cell_2rows", N=2), ks=(2,))
+
+
+@pytest.mark.timeout(300)
 def test_lstm_cell_cut_to_2_rows_every_element(B):
     _run_cut(B, synth.scaled(W["lstm_cell"], name="lstm_cell_2rows", N=2), ks=(2,))
 
@@ -212,6 +222,12 @@ def test_gated_rnn_contractive_full(B):
 def test_gru_cell_full(B):
     # T = 4096 steps of the gated cell, each side on its own forward
     _run(B, W["gru_cell"], ks=(1, 3), rows_count=2, check_exact=True)
+
+
+@pytest.mark.timeout(300)
+def test_gru_std_cell_full(B):
+    # the standard GRU (reset gate included) at T = 4096, batch 32, H = 1024
+    _run(B, W["gru_std_cell"], ks=(1, 3), rows_count=2, check_exact=True)
 
 
 @pytest.mark.timeout(300)

@@ -93,6 +93,22 @@ CASES = {
                                    ks=(0, 2)),
     "gated_aligned": synth.scaled(W["gru_cell"], name="gated_aligned", L=64, N=8, d=256, d_ff=512, d_in=128,
                                   ks=(0, 1, 2, 3)),
+    # the standard GRU (reset gate: two dependent products per step and per VJP): few-row kernels, fp32, a long chain
+    # (single-pass scan + remainder), a width the few-row kernel does not take, whole 256-row tiles, a loss on the
+    # last state only, contractions over tokens in several shares
+    "gru_small": synth.scaled(W["gru_std_cell"], name="gru_small", L=37, N=5, d=128, d_ff=384, d_in=64,
+                              ks=(0, 1, 2, 5)),
+    "gru_f32": synth.scaled(W["gru_std_cell"], name="gru_f32", dtype="f32", L=19, N=3, d=64, d_ff=192, d_in=32,
+                            ks=(0, 1, 3, 19)),
+    "gru_long": synth.scaled(W["gru_std_cell"], name="gru_long", L=330, N=6, d=128, d_ff=384, d_in=64, ks=(0, 2)),
+    "gru_width_72": synth.scaled(W["gru_std_cell"], name="gru_width_72", L=12, N=7, d=72, d_ff=216, d_in=32,
+                                 ks=(0, 2)),
+    "gru_aligned": synth.scaled(W["gru_std_cell"], name="gru_aligned", L=64, N=8, d=256, d_ff=768, d_in=128,
+                                ks=(0, 1, 2, 3)),
+    "gru_last_loss": synth.scaled(W["gru_std_cell"], name="gru_last_loss", L=23, N=6, d=64, d_ff=192, d_in=32,
+                                  loss_every_state=False, ks=(0, 1, 3)),
+    "gru_splitk": synth.scaled(W["gru_std_cell"], name="gru_splitk", L=128, N=64, d=256, d_ff=768, d_in=128,
+                               ks=(0, 2)),
     # the LSTM cell (state [c | h]; the contraction's result lands in the hidden half of v with the full row stride)
     "lstm_small": synth.scaled(W["lstm_cell"], name="lstm_small", L=37, N=5, d=128, d_ff=256, d_in=64,
                                ks=(0, 1, 2, 5)),
@@ -163,7 +179,9 @@ CASES = {
     "lstm_splitk": synth.scaled(W["lstm_cell"], name="lstm_splitk", L=128, N=64, d=512, d_ff=1024, d_in=128,
                                 ks=(0, 2)),
 }
-SPLITK_CASES = ["mlp_splitk", "mlp_splitk_odd", "rnn_splitk", "rnn_splitk_odd", "gated_splitk", "lstm_splitk"]
+SPLITK_CASES = ["mlp_splitk", "mlp_splitk_odd", "rnn_splitk", "rnn_splitk_odd", "gated_splitk", "lstm_splitk",
+                "gru_splitk"]
+GRU_CASES = ["gru_small", "gru_f32", "gru_long", "gru_width_72", "gru_aligned", "gru_last_loss"]
 
 
 def _setup(B, w):
@@ -231,7 +249,7 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
                                   "postact_f32_none", "gated_small", "gated_f32", "gated_long", "gated_width_72",
                                   "gated_aligned", "lstm_small", "lstm_f32", "lstm_long", "lstm_width_80",
                                   "lstm_aligned", "ragged_tokens", "postnorm_f32", "postnorm_small",
-                                  "gated_last_loss", "lstm_last_loss", "odd_widths"] + SPLITK_CASES)
+                                  "gated_last_loss", "lstm_last_loss", "odd_widths"] + SPLITK_CASES + GRU_CASES)
 def test_backward_end_to_end(B, name):
     """Own forward on each side, then Highway-BP at every k of the case, exact BP
     and the parameter gradients."""
@@ -251,6 +269,19 @@ def test_forward_of_the_gated_cell(B, name):
     tol = H.TOL[w.dtype]
     assert H.rel(H.to_np(p.x), sv["x"]) < tol
     assert H.rel(H.to_np(p.z), np.concatenate([sv["u"], sv["c"]], axis=-1)) < tol
+    assert H.rel(H.to_np(p.lam), sv["a"]) < tol
+
+
+@pytest.mark.parametrize("name", ["gru_small", "gru_f32", "gru_width_72", "gru_aligned"])
+def test_forward_of_the_standard_gru(B, name):
+    """States, the three gates [z | r | n] and the residual coefficient 1 - z that the forward writes."""
+    w = CASES[name]
+    inp, st, sv, p = _setup(B, w)
+    B.hbp_forward(p)
+    torch.cuda.synchronize()
+    tol = H.TOL[w.dtype]
+    assert H.rel(H.to_np(p.x), sv["x"]) < tol
+    assert H.rel(H.to_np(p.z), sv["zrn"]) < tol
     assert H.rel(H.to_np(p.lam), sv["a"]) < tol
 
 
@@ -304,7 +335,7 @@ def test_forward_with_relu_after_the_sum(B, name):
                                   "postact_rms", "postact_wide", "postact_aligned", "postact_f32_none",
                                   "postact_f32_deep", "gated_small", "gated_long", "lstm_small", "lstm_long",
                                   "postnorm_small", "postnorm_wide", "postnorm_aligned", "postnorm_f32",
-                                  "postact_loss_all"])
+                                  "postact_loss_all", "gru_small", "gru_long"])
 def test_backward_shared_state(B, name):
     """Both backward passes read the same (storage-rounded) forward state."""
     w = CASES[name]
@@ -324,7 +355,7 @@ def test_backward_shared_state(B, name):
                                         ("aligned_small", 0.8), ("rnn_token_gates", 0.4),
                                         ("rnn_token_gates_long", 1.0), ("mlp_token_gates", 0.3),
                                         ("gated_small", 0.3), ("gated_long", 1.0), ("gated_f32", 0.6),
-                                        ("lstm_small", 0.3), ("lstm_long", 0.7),
+                                        ("lstm_small", 0.3), ("lstm_long", 0.7), ("gru_small", 0.3), ("gru_long", 1.0),
                                         ("postnorm_small", 0.5), ("postnorm_wide", 0.8), ("postnorm_f32", 1.0),
                                         ("postnorm_aligned", 0.2)])
 def test_gamma_iterates(B, name, gamma):
