@@ -36,8 +36,18 @@ PEAK_HBM_GBS = 8000.0
 # the summary under profiles/ it was copied from (a figure of that run, not of this one); other workloads
 # report null.
 MEASURED_TRAFFIC = {
+    "deep_large": {"source": "profiles/bench_deep_large_hbm_traffic.txt",
+                   "vjp1": 1.323e11, "vjp2": 8.408e10, "dw": 3.064e11, "scan": 1.543e10},
+    "transformer_mlp": {"source": "profiles/bench_transformer_mlp_hbm_traffic.txt",
+                        "vjp1": 2.247e10, "vjp2": 1.116e10, "dw": 2.335e10, "scan": 3.815e9},
     "resnet_like": {"source": "profiles/bench_resnet_like_hbm_traffic.txt",
-                    "vjp1": 2.686e9, "vjp2": 1.602e9, "dw": 1.523e9, "scan": 0.823e9},
+                    "vjp1": 2.692e9, "vjp2": 1.591e9, "dw": 1.483e9, "scan": 6.481e8},
+    "postnorm_mlp": {"source": "profiles/bench_postnorm_mlp_hbm_traffic.txt",
+                     "vjp1": 5.650e9, "vjp2": 2.760e9, "dw": 2.824e9, "scan": 1.120e9},
+    "gated_rnn": {"source": "profiles/bench_gated_rnn_hbm_traffic.txt",
+                  "vjp1": 9.441e8, "vjp2": 9.397e8, "dw": 6.041e8, "scan": 6.381e8},
+    "lstm_cell": {"source": "profiles/bench_lstm_cell_hbm_traffic.txt",
+                  "vjp1": 3.491e9, "vjp2": 2.150e9, "dw": 2.029e9, "scan": 1.702e9},
 }
 
 
@@ -332,6 +342,8 @@ def main():
         "roofline": roofs[dominant],
         "roofline_by_class": roofs,
         "class_ms_per_step": ms,
+        # steps run before the tables below: warm-up, timed, and the ones with per-launch events
+        "steps_run": {"warmup": args.warmup, "timed": args.steps, "per_launch_events": prof_steps},
     }
 
     reps = max(3, min(args.steps // 2, int(2.0 / sec) + 1))   # repetitions per line of the tables below
