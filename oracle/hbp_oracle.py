@@ -34,6 +34,12 @@ and erf are the only library steps; no blocking, fusion or reordering):
              i, f, o = sigmoid(.), gg = tanh(.) of W h + U xin,  c' = f (.) c + i (.) gg,  h' = o (.) tanh(c'):
              a = f, b = i (.) gg, c3 = o (.) tanh(f (.) c + i (.) gg).  K = dr/dx = diag([f | 0]): only the
              cell part has a residual path; everything else, the dependence of h' on c included, is J.
+             kind = 'transformer' is the pre-norm transformer of the appendix (GPT-2 paragraph), every layer split into
+             its two sub-layers, so that L = 2 x layers: block l even is multi-head self-attention on the normed state,
+             [q | k | v] = norm(x) Wqkv^T, per sequence and head softmax(q k^T / sqrt(dh)) v (keys after the query
+             masked out when causal), heads side by side, times Wo^T; block l odd is the two-matrix MLP.  The residual
+             function is r(x, z) = lam (.) x + z as for 'mlp' (the decomposition with gamma applies as for any kind);
+             a token's block output now depends on the other tokens of its sequence, so J couples the rows of a state.
   exact BP   Section "Backpropagation as a system of equations" and the first
              line of the proof of Theorem 1 (chain rule through J + K).
   Highway-BP Theorem 2 (w^0 and the recursion for w^{k+1}) in its two-step
@@ -81,6 +87,9 @@ class Stack:
                   W1 = [W_u; W_c] [2H,H], U = [U_u; U_c] [2H,d_in], no W2, no lam
                   (the coefficient of the residual path is the cell's own 1 - u)
            'mlp'  per-block weights W1[L,d_ff,d], W2[L,d,d_ff]
+           'transformer'  L = 2 x layers alternating sub-blocks: l even self-attention with Wqkv[L/2,3d,d] (rows
+                  [W_q; W_k; W_v], head h in columns h dh .. (h+1) dh of each third) and Wo[L/2,d,d]; l odd the MLP with
+                  W1[L/2,d_ff,d], W2[L/2,d,d_ff].  Tokens are B sequences of T: row n = b T + t.
            'rnn'  weights shared by all L (= T) blocks: W1 = W_h [d_ff,d],
                   W2 = W_o [d,d_ff], U [d_ff,d_in]; block l maps state l to
                   l+1 and consumes xin[l]
@@ -103,10 +112,15 @@ class Stack:
     eps: float = 1e-6
     L: int = 0
     post: str = "none"
+    Wqkv: Optional[np.ndarray] = None
+    Wo: Optional[np.ndarray] = None
+    T: int = 0               # sequence length of the attention sub-blocks
+    heads: int = 0
+    causal: bool = True
 
     def __post_init__(self):
         assert self.post in ("none", "relu", "rms")
-        assert self.kind in ("mlp", "rnn", "gated", "lstm", "gru")
+        assert self.kind in ("mlp", "rnn", "gated", "lstm", "gru", "transformer")
         assert self.act in ("gelu", "tanh", "identity")
         assert self.norm in ("none", "rms")
         self.W1 = np.asarray(self.W1, dtype=F64)
@@ -124,6 +138,14 @@ class Stack:
         if self.kind == "mlp":
             assert self.W1.ndim == 3 and self.W2.ndim == 3
             self.L = self.W1.shape[0]
+        elif self.kind == "transformer":
+            assert self.W1.ndim == 3 and self.W2.ndim == 3 and self.post == "none"
+            self.Wqkv = np.asarray(self.Wqkv, dtype=F64)
+            self.Wo = np.asarray(self.Wo, dtype=F64)
+            assert self.Wqkv.shape == (self.W1.shape[0], 3 * self.W2.shape[1], self.W2.shape[1])
+            assert self.Wo.shape == (self.W1.shape[0], self.W2.shape[1], self.W2.shape[1])
+            assert self.T > 0 and self.heads > 0 and self.W2.shape[1] % self.heads == 0
+            self.L = 2 * self.W1.shape[0]
         else:
             assert self.W1.ndim == 2 and self.W2.ndim == 2
             assert self.L > 0, "rnn stacks need L (= T) given"
@@ -140,10 +162,19 @@ class Stack:
     def d_ff(self) -> int:
         return self.W1.shape[-2]
 
+    def is_attn(self, l: int) -> bool:
+        return self.kind == "transformer" and l % 2 == 0
+
     def w1(self, l: int) -> np.ndarray:
+        """The matrix a block applies to its (normed) input: W1, or Wqkv for an attention sub-block."""
+        if self.kind == "transformer":
+            return self.Wqkv[l // 2] if l % 2 == 0 else self.W1[l // 2]
         return self.W1[l] if self.kind == "mlp" else self.W1
 
     def w2(self, l: int) -> np.ndarray:
+        """The matrix that maps a block's inner result back to the state: W2, or Wo for an attention sub-block."""
+        if self.kind == "transformer":
+            return self.Wo[l // 2] if l % 2 == 0 else self.W2[l // 2]
         return self.W2[l] if self.kind == "mlp" else self.W2
 
     def lam_row(self, l: int) -> np.ndarray:
@@ -174,6 +205,54 @@ def act_grad(name: str, a: np.ndarray) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
+# multi-head self-attention on [q | k | v] rows (the attention sub-block between its two matrices)
+# --------------------------------------------------------------------------
+def _heads(st: Stack, m: np.ndarray) -> np.ndarray:
+    """[B T, heads dh] -> [B, heads, T, dh]"""
+    B = m.shape[0] // st.T
+    return m.reshape(B, st.T, st.heads, -1).transpose(0, 2, 1, 3)
+
+
+def _merge(m: np.ndarray) -> np.ndarray:
+    """[B, heads, T, dh] -> [B T, heads dh]"""
+    B, Hn, T, dh = m.shape
+    return m.transpose(0, 2, 1, 3).reshape(B * T, Hn * dh)
+
+
+def attn_probs(st: Stack, q: np.ndarray, k: np.ndarray) -> np.ndarray:
+    """softmax over the keys of q k^T / sqrt(dh), [B, heads, T, T]; causal: a query sees keys up to its own position."""
+    dh = q.shape[-1]
+    s = q @ k.transpose(0, 1, 3, 2) / math.sqrt(dh)
+    if st.causal:
+        s = np.where(np.tril(np.ones((st.T, st.T), dtype=bool)), s, -np.inf)
+    p = np.exp(s - s.max(axis=-1, keepdims=True))
+    return p / p.sum(axis=-1, keepdims=True)
+
+
+def attention(st: Stack, qkv: np.ndarray) -> np.ndarray:
+    """o = softmax(q k^T / sqrt(dh)) v per sequence and head; qkv [N,3d] -> o [N,d]."""
+    d = qkv.shape[1] // 3
+    q, k, v = (_heads(st, qkv[:, j * d:(j + 1) * d]) for j in range(3))
+    return _merge(attn_probs(st, q, k) @ v)
+
+
+def attention_vjp(st: Stack, qkv: np.ndarray, do: np.ndarray) -> np.ndarray:
+    """Gradient w.r.t. [q | k | v] given the gradient do of o:  dv = P^T do,  dP = do v^T,
+    dS = P (.) (dP - rowsum(dP (.) P)),  dq = dS k / sqrt(dh),  dk = dS^T q / sqrt(dh)."""
+    d = qkv.shape[1] // 3
+    q, k, v = (_heads(st, qkv[:, j * d:(j + 1) * d]) for j in range(3))
+    doh = _heads(st, do)
+    P = attn_probs(st, q, k)
+    dv = P.transpose(0, 1, 3, 2) @ doh
+    dP = doh @ v.transpose(0, 1, 3, 2)
+    dS = P * (dP - np.sum(dP * P, axis=-1, keepdims=True))
+    sc = 1.0 / math.sqrt(q.shape[-1])
+    dq = dS @ k * sc
+    dk = dS.transpose(0, 1, 3, 2) @ q * sc
+    return np.concatenate([_merge(dq), _merge(dk), _merge(dv)], axis=1)
+
+
+# --------------------------------------------------------------------------
 # forward: produces the states and what the backward pass needs
 # --------------------------------------------------------------------------
 def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict[str, np.ndarray]:
@@ -183,6 +262,8 @@ def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict
     rinv = 1/rms [L,N] (ones without a norm), a (pre-activation), z = act(a),
     dphi = act'(a), all [L,N,d_ff]; with post = 'relu' the sum goes through a
     ReLU and mask[l] = 1 where the sum that made x_{l+1} was positive (all ones otherwise).
+    kind = 'transformer' also returns qkv [L,N,3d] and o [L,N,d] (attention output before Wo); rows of a, z, dphi
+    belonging to attention sub-blocks and rows of qkv, o belonging to MLP sub-blocks are zero.
     """
     x0 = np.asarray(x0, dtype=F64)
     N, d = x0.shape
@@ -199,6 +280,9 @@ def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict
     a = np.zeros((L, N, dff), F64)
     mask = np.ones((L, N, d), F64)
     rpost = np.ones((L, N), F64)
+    tr = st.kind == "transformer"
+    qkv = np.zeros((L, N, 3 * d), F64) if tr else None
+    o = np.zeros((L, N, d), F64) if tr else None
     x[0] = x0
     for l in range(L):
         if st.norm == "rms":
@@ -207,6 +291,11 @@ def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict
             y[l] = x[l] / r[:, None]
         else:
             y[l] = x[l]
+        if st.is_attn(l):
+            qkv[l] = y[l] @ st.w1(l).T
+            o[l] = attention(st, qkv[l])
+            x[l + 1] = st.lam_row(l) * x[l] + o[l] @ st.w2(l).T
+            continue
         a[l] = y[l] @ st.w1(l).T
         if st.kind == "rnn":
             a[l] += np.asarray(xin[l], dtype=F64) @ st.U.T
@@ -217,8 +306,14 @@ def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict
         if st.post == "rms":
             rpost[l] = 1.0 / np.sqrt(np.mean(x[l + 1] * x[l + 1], axis=1) + st.eps)
             x[l + 1] = x[l + 1] * rpost[l][:, None]
-    return {"x": x, "y": y, "rinv": rinv, "a": a, "mask": mask, "rpost": rpost,
-            "z": act_fn(st.act, a), "dphi": act_grad(st.act, a)}
+    out = {"x": x, "y": y, "rinv": rinv, "a": a, "mask": mask, "rpost": rpost,
+           "z": act_fn(st.act, a), "dphi": act_grad(st.act, a)}
+    if tr:
+        out["qkv"], out["o"] = qkv, o
+        for l in range(0, L, 2):      # no MLP in these blocks
+            out["z"][l] = 0.0
+            out["dphi"][l] = 0.0
+    return out
 
 
 def _forward_gated(st: Stack, x0: np.ndarray, xin: np.ndarray) -> Dict[str, np.ndarray]:
@@ -329,6 +424,8 @@ def block_preact_grad(st: Stack, l: int, saved: Dict[str, np.ndarray], g_next: n
         dct = Gc + Gh * o * (1.0 - tc * tc)
         return np.concatenate([dct * gg * i * (1.0 - i), dct * c * f * (1.0 - f), Gh * tc * o * (1.0 - o),
                                dct * i * (1.0 - gg * gg)], axis=1)
+    if st.is_attn(l):      # the gradient of [q | k | v]: back through Wo, then through the attention
+        return attention_vjp(st, saved["qkv"][l], g_next @ st.w2(l))
     return (g_next @ st.w2(l)) * saved["dphi"][l]
 
 
@@ -485,6 +582,18 @@ def param_grads(st: Stack, saved: Dict[str, np.ndarray], g: np.ndarray,
             dW2[l] = g[l + 1].T @ saved["z"][l]
             dW1[l] = da.T @ saved["y"][l]
         return {"dW1": dW1, "dW2": dW2}
+    if st.kind == "transformer":
+        out = {"dW1": np.zeros_like(st.W1), "dW2": np.zeros_like(st.W2), "dWqkv": np.zeros_like(st.Wqkv),
+               "dWo": np.zeros_like(st.Wo)}
+        for l in range(L):
+            da = block_preact_grad(st, l, saved, g[l + 1])
+            if st.is_attn(l):
+                out["dWo"][l // 2] = g[l + 1].T @ saved["o"][l]
+                out["dWqkv"][l // 2] = da.T @ saved["y"][l]
+            else:
+                out["dW2"][l // 2] = g[l + 1].T @ saved["z"][l]
+                out["dW1"][l // 2] = da.T @ saved["y"][l]
+        return out
     if st.kind in ("gated", "lstm"):
         dW1 = np.zeros_like(st.W1)
         dU = np.zeros_like(st.U)

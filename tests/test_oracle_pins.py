@@ -861,6 +861,173 @@ def test_gru_cell_parameter_gradients_by_finite_differences():
         np.testing.assert_allclose(pg[name], num, rtol=2e-6, atol=2e-8)
 
 
+# ---------------------------------------------------------------- attention sub-blocks (appendix, GPT-2 paragraph)
+def small_transformer(layers=2, d=8, dff=12, T=4, heads=2, causal=True, norm="rms", lam="rand", seed=0):
+    r = np.random.default_rng(seed)
+    W1 = r.standard_normal((layers, dff, d)) / math.sqrt(d)
+    W2 = r.standard_normal((layers, d, dff)) / math.sqrt(dff)
+    Wqkv = r.standard_normal((layers, 3 * d, d)) / math.sqrt(d) * 1.5
+    Wo = r.standard_normal((layers, d, d)) / math.sqrt(d)
+    lm = None if lam == "one" else r.uniform(0.5, 1.1, (2 * layers, d))
+    return O.Stack("transformer", "gelu", norm, W1, W2, lam=lm, Wqkv=Wqkv, Wo=Wo, T=T, heads=heads, causal=causal)
+
+
+@pytest.mark.parametrize("causal,norm", [(True, "rms"), (False, "rms"), (True, "none")])
+def test_transformer_stack_against_torch_autograd(causal, norm):
+    """The alternating attention / MLP stack written with torch fp64 ops, the attention itself by torch's own
+    scaled_dot_product_attention, differentiated by autograd: states, state gradients, all four weight gradients."""
+    r = np.random.default_rng(31)
+    B, T, heads = 3, 5, 2
+    st = small_transformer(layers=2, d=8, dff=12, T=T, heads=heads, causal=causal, norm=norm)
+    d = st.d
+    x0 = r.standard_normal((B * T, d))
+    c = r.standard_normal((st.L + 1, B * T, d))
+    sv = O.forward(st, x0)
+    G = O.exact_backward(st, sv, c)
+    pg = O.param_grads(st, sv, G)
+    t = lambda a: torch.tensor(a, dtype=torch.float64, requires_grad=True)
+    W1, W2, Wqkv, Wo, lam = t(st.W1), t(st.W2), t(st.Wqkv), t(st.Wo), torch.tensor(st.lam)
+    xs = [t(x0)]
+    for l in range(st.L):
+        x = xs[-1]
+        y = x / torch.sqrt((x * x).mean(dim=1, keepdim=True) + st.eps) if norm == "rms" else x
+        if l % 2 == 0:
+            qkv = (y @ Wqkv[l // 2].T).reshape(B, T, 3, heads, d // heads).permute(2, 0, 3, 1, 4)
+            o = torch.nn.functional.scaled_dot_product_attention(qkv[0], qkv[1], qkv[2], is_causal=causal)
+            nxt = lam[l] * x + o.permute(0, 2, 1, 3).reshape(B * T, d) @ Wo[l // 2].T
+        else:
+            nxt = lam[l] * x + torch.nn.functional.gelu(y @ W1[l // 2].T) @ W2[l // 2].T
+        nxt.retain_grad()
+        xs.append(nxt)
+    loss = sum((torch.tensor(c[l]) * xs[l]).sum() for l in range(st.L + 1))
+    loss.backward()
+    for l in range(st.L + 1):
+        np.testing.assert_allclose(sv["x"][l], xs[l].detach().numpy(), rtol=1e-11, atol=1e-12)
+        np.testing.assert_allclose(G[l], xs[l].grad.numpy(), rtol=1e-9, atol=1e-11)
+    for name, w in (("dW1", W1), ("dW2", W2), ("dWqkv", Wqkv), ("dWo", Wo)):
+        np.testing.assert_allclose(pg[name], w.grad.numpy(), rtol=1e-9, atol=1e-11)
+
+
+@pytest.mark.parametrize("gamma", [0.0, 0.2])
+def test_transformer_stack_by_path_enumeration(gamma):
+    """Theorem 2 for one sequence taken as a single state vector of T d entries: K_l = diag(lam_l) repeated per token,
+    J_l = the Jacobian of the whole sub-block (attention couples the tokens), by central differences."""
+    st = small_transformer(layers=2, d=4, dff=5, T=3, heads=2, seed=4)
+    r = np.random.default_rng(17)
+    T, d, L = st.T, st.d, st.L
+    x0 = r.standard_normal((T, d))
+    sv = O.forward(st, x0)
+    e = r.standard_normal((L + 1, T, d))
+
+    def block(xflat, l):
+        x = xflat.reshape(T, d)
+        y = x / np.sqrt(np.mean(x * x, axis=1, keepdims=True) + st.eps)
+        if l % 2 == 0:
+            qkv = y @ st.Wqkv[l // 2].T
+            out = np.zeros((T, d))
+            dh = d // st.heads
+            for h in range(st.heads):
+                q, k, v = (qkv[:, j * d + h * dh: j * d + (h + 1) * dh] for j in range(3))
+                for i in range(T):          # one query at a time, its own softmax over the keys it may see
+                    sc = np.array([q[i] @ k[j] / math.sqrt(dh) for j in range(i + 1)])
+                    pr = np.exp(sc) / np.exp(sc).sum()
+                    out[i, h * dh:(h + 1) * dh] = sum(pr[j] * v[j] for j in range(i + 1))
+            return (out @ st.Wo[l // 2].T).ravel()
+        a = y @ st.W1[l // 2].T
+        return ((0.5 * a * (1 + np.vectorize(math.erf)(a / math.sqrt(2)))) @ st.W2[l // 2].T).ravel()
+
+    def jac(l):
+        xf = sv["x"][l].ravel()
+        J = np.zeros((T * d, T * d))
+        for i in range(T * d):
+            hp, hm = xf.copy(), xf.copy()
+            hp[i] += 1e-6
+            hm[i] -= 1e-6
+            J[:, i] = (block(hp, l) - block(hm, l)) / 2e-6
+        return J
+    # the forward state the oracle produced is the one this independent block function produces
+    for l in range(L):
+        np.testing.assert_allclose(sv["x"][l + 1].ravel(), np.tile(st.lam[l], T) * sv["x"][l].ravel() + block(sv["x"][l].ravel(), l),
+                                   rtol=1e-12, atol=1e-13)
+    Kd = [np.diag(np.tile(st.lam[l], T)) for l in range(L)]
+    Js = [jac(l) + gamma * Kd[l] for l in range(L)]
+    Ks = [(1 - gamma) * Kd[l] for l in range(L)]
+    for k in range(L + 1):
+        w = O.hbp_backward(st, sv, e, k, gamma=gamma)
+        for i in range(L + 1):
+            acc = np.zeros(T * d)
+            for j in range(i, L + 1):
+                layers = list(range(i, j))
+                for size in range(min(k, len(layers)) + 1):
+                    for chosen in itertools.combinations(layers, size):
+                        vec = e[j].ravel().copy()
+                        for l in reversed(layers):
+                            vec = vec @ (Js[l] if l in chosen else Ks[l])
+                        acc += vec
+            np.testing.assert_allclose(w[i].ravel(), acc, rtol=5e-6, atol=5e-8)
+    np.testing.assert_allclose(O.hbp_backward(st, sv, e, L, gamma=gamma), O.exact_backward(st, sv, e), rtol=1e-10, atol=1e-12)
+
+
+def test_transformer_parameter_gradients_by_finite_differences():
+    """Every entry of Wqkv, Wo, W1, W2 by central differences of a scalar loss (two sequences, non-causal as well)."""
+    for causal in (True, False):
+        st = small_transformer(layers=2, d=4, dff=5, T=3, heads=2, causal=causal, seed=9)
+        r = np.random.default_rng(5)
+        x0 = r.standard_normal((2 * st.T, st.d))
+        c = r.standard_normal((st.L + 1, 2 * st.T, st.d))
+        sv = O.forward(st, x0)
+        pg = O.param_grads(st, sv, O.exact_backward(st, sv, c))
+
+        def loss(**kw):
+            a = dict(W1=st.W1, W2=st.W2, Wqkv=st.Wqkv, Wo=st.Wo)
+            a.update(kw)
+            s2 = O.Stack("transformer", "gelu", "rms", a["W1"], a["W2"], lam=st.lam, Wqkv=a["Wqkv"], Wo=a["Wo"], T=st.T,
+                         heads=st.heads, causal=causal)
+            return float(np.sum(c * O.forward(s2, x0)["x"]))
+        for name in ("W1", "W2", "Wqkv", "Wo"):
+            M = getattr(st, name)
+            num = np.zeros_like(M)
+            for idx in np.ndindex(M.shape):
+                Mp, Mm = M.copy(), M.copy()
+                Mp[idx] += 1e-6
+                Mm[idx] -= 1e-6
+                num[idx] = (loss(**{name: Mp}) - loss(**{name: Mm})) / 2e-6
+            np.testing.assert_allclose(pg["d" + name], num, rtol=5e-6, atol=5e-8)
+
+
+def test_attention_special_cases():
+    """What the attention must reduce to: with one token per sequence the softmax is 1 and o = v; with zero query
+    weights every visible key weighs the same, so o is the running mean of v (causal) or its mean (not causal); and with
+    a causal mask the gradient of a loss on token t reaches no later token."""
+    r = np.random.default_rng(3)
+    d, heads = 8, 2
+    st1 = small_transformer(layers=1, d=d, T=1, heads=heads, lam="one", norm="none")
+    qkv = r.standard_normal((5, 3 * d))
+    np.testing.assert_allclose(O.attention(st1, qkv), qkv[:, 2 * d:], rtol=0, atol=1e-15)
+    dqkv = O.attention_vjp(st1, qkv, np.ones((5, d)))
+    np.testing.assert_allclose(dqkv, np.concatenate([np.zeros((5, 2 * d)), np.ones((5, d))], axis=1), atol=1e-15)
+    T = 6
+    for causal in (True, False):
+        st = small_transformer(layers=1, d=d, T=T, heads=heads, causal=causal)
+        qkv = r.standard_normal((2 * T, 3 * d))
+        qkv[:, :d] = 0.0
+        v = qkv[:, 2 * d:].reshape(2, T, d)
+        want = np.cumsum(v, axis=1) / np.arange(1, T + 1)[None, :, None] if causal else np.repeat(v.mean(axis=1, keepdims=True), T, axis=1)
+        np.testing.assert_allclose(O.attention(st, qkv), want.reshape(2 * T, d), rtol=1e-13, atol=1e-14)
+    st = small_transformer(layers=2, d=d, T=T, heads=heads, causal=True)
+    sv = O.forward(st, r.standard_normal((T, d)))
+    e = np.zeros((st.L + 1, T, d))
+    e[st.L, 2] = r.standard_normal(d)
+    for k in (1, 2, st.L):
+        w = O.hbp_backward(st, sv, e, k)
+        assert np.all(w[:, 3:] == 0.0) and np.abs(w[0, :3]).min() > 0.0
+    # rows of the probabilities sum to one and respect the mask
+    q, k_ = (O._heads(st, sv["qkv"][0][:, j * d:(j + 1) * d]) for j in range(2))
+    P = O.attn_probs(st, q, k_)
+    np.testing.assert_allclose(P.sum(-1), 1.0, rtol=1e-14)
+    assert np.all(P[..., np.triu_indices(T, 1)[0], np.triu_indices(T, 1)[1]] == 0.0)
+
+
 # ---------------------------------------------------------------- P14: the LSTM cell (LSTM row of the table)
 def small_lstm(T=5, H=4, I=3, seed=0):
     r = np.random.default_rng(seed)
