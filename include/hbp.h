@@ -11,7 +11,8 @@
  *        residual path                                    ("Parallel computation", step 2)
  * then the parameter gradients dL/dtheta_l = g_{l+1} . d block_l / d theta_l
  * (sentence after Theorem 2), and exact sequential backpropagation for
- * comparison.  kind = HBP_MLP: one weight pair per block, states along depth.
+ * comparison.  kind = HBP_MLP: one weight pair per block, states along depth
+ * (HBP_TRANSFORMER: attention and MLP sub-blocks in turn).
  * kind = HBP_RNN: one weight set shared by all L = T blocks, states along time,
  * block l maps state l to state l+1 and consumes xin[l].
  *
@@ -86,7 +87,19 @@ typedef enum { HBP_F32 = 0, HBP_BF16 = 1 } hbp_dtype;
  * Shapes: d = H, d_ff = 3H, W1 = [W_z; W_r; W_n] [3H,H], U [3H,d_in]; z holds [z | r | n] as [L,N,3H]; lambda
  * ([L,N,H], HBP_LAMBDA_TOKEN) is WRITTEN by hbp_forward as 1 - z.  Other rules as for HBP_GATED (which is this cell with the
  * reset gate held open). */
-typedef enum { HBP_MLP = 0, HBP_RNN = 1, HBP_GATED = 2, HBP_LSTM = 3, HBP_GRU = 4 } hbp_kind;
+/* HBP_TRANSFORMER: the pre-norm transformer of the appendix (GPT-2 paragraph), every layer split into its self-attention
+ * and feed-forward sub-layers, so that L = 2 x layers (L even).  Block l even: multi-head self-attention on the normed
+ * state, [q | k | v] = norm(x_l) Wqkv_j^T (j = l/2), per sequence and head softmax(q k^T / sqrt(dh)) v (causal = 1: a
+ * query sees keys up to its own position), heads side by side, times Wo_j^T.  Block l odd: the MLP of HBP_MLP with
+ * W1_j, W2_j.  The N tokens are N / seq_len sequences of seq_len consecutive rows; head h is columns h dh .. (h+1) dh
+ * (dh = d / heads) of each third of a [q | k | v] row.  The block Jacobian of an attention sub-block couples the rows of
+ * a sequence; K stays diag(lambda), so steps (ii) and w^0 are unchanged, and gamma applies as for HBP_MLP (the paper
+ * uses gamma = 0.2 on this stack).  Shapes: W1 [L/2,d_ff,d], W2 [L/2,d,d_ff], Wqkv [L/2,3d,d], Wo [L/2,d,d]; z, dphi
+ * [L/2,N,d_ff]; qkv [L/2,N,3d], attn_o [L/2,N,d] (the attention's output before Wo) and lse [L/2, N heads] are
+ * written by hbp_forward and read by the backward calls; x, y, rinv, lambda, e, g are per state / block as for
+ * HBP_MLP.  post = HBP_POST_NONE, d_in = 0; dh a multiple of 8 (bf16 with dh = 64 runs on the matrix cores, any other
+ * case on plain kernels that need seq_len <= 8192). */
+typedef enum { HBP_MLP = 0, HBP_RNN = 1, HBP_GATED = 2, HBP_LSTM = 3, HBP_GRU = 4, HBP_TRANSFORMER = 5 } hbp_kind;
 /* GELU is the exact erf form a*Phi(a); IDENTITY makes blocks linear (tests). */
 typedef enum { HBP_ACT_GELU_ERF = 0, HBP_ACT_TANH = 1, HBP_ACT_IDENTITY = 2 } hbp_act;
 /* RMS: y = x / sqrt(mean_c(x^2) + eps), no gain. */
@@ -129,6 +142,10 @@ typedef struct {
                               * K' = (1 - gamma) K and J' = J + gamma K.  0: the plain method; 1: fixed-point
                               * iteration.  The exact gradient and the other calls do not depend on it. */
   int32_t post;              /* hbp_post */
+  /* HBP_TRANSFORMER only (ignored otherwise) */
+  int32_t heads;             /* attention heads; d % heads == 0 */
+  int32_t causal;            /* 1: keys after the query are masked out; 0: every query sees the whole sequence */
+  int64_t seq_len;           /* rows per sequence; N % seq_len == 0 */
 } hbp_desc;
 
 typedef struct {
@@ -159,6 +176,15 @@ typedef struct {
   float* dU;                 /* out, fp32, shape of U (RNN) */
   void* workspace;
   size_t workspace_bytes;
+  /* HBP_TRANSFORMER only (ignored otherwise, may be NULL) */
+  const void* Wqkv;          /* S [L/2,3d,d]  rows [W_q; W_k; W_v] */
+  const void* Wo;            /* S [L/2,d,d] */
+  void* qkv;                 /* S [L/2,N,3d]  forward state */
+  void* attn_o;              /* S [L/2,N,d]   forward state: attention output before Wo */
+  float* lse;                /* [L/2, N heads] forward state: per (sequence, head, position) the base-2 logarithm of
+                              * sum_j exp2(s_j log2 e), s the scaled scores the query sees */
+  float* dWqkv;              /* out, fp32, shape of Wqkv */
+  float* dWo;                /* out, fp32, shape of Wo */
 } hbp_buffers;
 
 /* Bytes of workspace that any of the calls below may need for this problem. */
@@ -247,6 +273,10 @@ typedef struct {
   float* v1; float* v2; float* vU;
   float* scratch;            /* DEVICE, hbp_train_scratch_size() bytes: partial sums of the reductions */
   size_t scratch_bytes;
+  /* HBP_TRANSFORMER only: the same for Wqkv and Wo */
+  float* masterQ; float* masterO;
+  float* mQ; float* mO;
+  float* vQ; float* vO;
 } hbp_optim_state;
 
 hbp_status hbp_train_scratch_size(size_t* bytes);
@@ -258,7 +288,7 @@ hbp_status hbp_train_scratch_size(size_t* bytes);
 hbp_status hbp_loss_mse(const hbp_desc* desc, const hbp_buffers* bufs, const void* target, void* e_out, float* loss_out,
                         float* scratch, size_t scratch_bytes, void* stream);
 
-/* One optimizer update of W1, W2 (and U) from dW1, dW2 (and dU) in bufs. */
+/* One optimizer update of W1, W2 (and U; Wqkv, Wo) from dW1, dW2 (and dU; dWqkv, dWo) in bufs. */
 hbp_status hbp_optimizer_step(const hbp_desc* desc, hbp_buffers* bufs, const hbp_optim* opt, hbp_optim_state* state,
                               void* stream);
 
@@ -282,7 +312,8 @@ enum {
   HBP_PROF_DW = 3,      /* parameter-gradient contractions over tokens              */
   HBP_PROF_FORWARD = 4, /* forward support kernels                                  */
   HBP_PROF_OTHER = 5,   /* copies, split-K reductions                               */
-  HBP_PROF_CLASSES = 6
+  HBP_PROF_ATTN = 6,    /* attention between its two matrices, forward and backward  */
+  HBP_PROF_CLASSES = 7
 };
 hbp_status hbp_profile_enable(int on);
 hbp_status hbp_profile_read(double* ms, int64_t* launches);

@@ -21,8 +21,8 @@ HBP_OK = 0
 STATUS_NAMES = {0: "HBP_OK", 1: "HBP_E_INVALID_ARG", 2: "HBP_E_UNSUPPORTED", 3: "HBP_E_WORKSPACE",
                 4: "HBP_E_NULL", 5: "HBP_E_DEVICE"}
 F32, BF16 = 0, 1
-MLP, RNN, GATED, LSTM, GRU = 0, 1, 2, 3, 4
-KIND = {"mlp": MLP, "rnn": RNN, "gated": GATED, "lstm": LSTM, "gru": GRU}
+MLP, RNN, GATED, LSTM, GRU, TRANSFORMER = 0, 1, 2, 3, 4, 5
+KIND = {"mlp": MLP, "rnn": RNN, "gated": GATED, "lstm": LSTM, "gru": GRU, "transformer": TRANSFORMER}
 ACT = {"gelu": 0, "tanh": 1, "identity": 2}
 NORM = {"none": 0, "rms": 1}
 POST = {"none": 0, "relu": 1, "rms": 2}
@@ -32,14 +32,15 @@ EXPORTS = ("hbp_workspace_size", "hbp_check", "hbp_forward", "hbp_backward", "hb
            "hbp_scan_workspace_size", "hbp_initial_estimate", "hbp_initial_estimate_static",
            "hbp_param_grads", "hbp_train_scratch_size", "hbp_loss_mse", "hbp_optimizer_step", "hbp_train_step",
            "hbp_profile_enable", "hbp_profile_read", "hbp_status_string")
-PROF_CLASSES = ("vjp1", "vjp2", "scan", "dw", "forward", "other")
+PROF_CLASSES = ("vjp1", "vjp2", "scan", "dw", "forward", "other", "attn")
 
 
 class hbp_desc(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("kind", C.c_int32), ("dtype", C.c_int32), ("act", C.c_int32),
                 ("norm", C.c_int32), ("lambda_kind", C.c_int32), ("loss_every_state", C.c_int32),
                 ("eps", C.c_float), ("L", C.c_int64), ("N", C.c_int64), ("d", C.c_int64), ("d_ff", C.c_int64),
-                ("d_in", C.c_int64), ("gamma", C.c_float), ("post", C.c_int32)]
+                ("d_in", C.c_int64), ("gamma", C.c_float), ("post", C.c_int32),
+                ("heads", C.c_int32), ("causal", C.c_int32), ("seq_len", C.c_int64)]
 
 
 class hbp_buffers(C.Structure):
@@ -49,7 +50,9 @@ class hbp_buffers(C.Structure):
                 ("dphi", C.c_void_p), ("xin", C.c_void_p), ("mask", C.c_void_p), ("e", C.c_void_p),
                 ("g", C.c_void_p),
                 ("dW1", C.c_void_p), ("dW2", C.c_void_p), ("dU", C.c_void_p),
-                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+                ("Wqkv", C.c_void_p), ("Wo", C.c_void_p), ("qkv", C.c_void_p), ("attn_o", C.c_void_p),
+                ("lse", C.c_void_p), ("dWqkv", C.c_void_p), ("dWo", C.c_void_p)]
 
 
 OPT_SGD, OPT_ADAMW = 0, 1
@@ -66,7 +69,9 @@ class hbp_optim_state(C.Structure):
                 ("master1", C.c_void_p), ("master2", C.c_void_p), ("masterU", C.c_void_p),
                 ("m1", C.c_void_p), ("m2", C.c_void_p), ("mU", C.c_void_p),
                 ("v1", C.c_void_p), ("v2", C.c_void_p), ("vU", C.c_void_p),
-                ("scratch", C.c_void_p), ("scratch_bytes", C.c_size_t)]
+                ("scratch", C.c_void_p), ("scratch_bytes", C.c_size_t),
+                ("masterQ", C.c_void_p), ("masterO", C.c_void_p), ("mQ", C.c_void_p), ("mO", C.c_void_p),
+                ("vQ", C.c_void_p), ("vO", C.c_void_p)]
 
 
 class HbpError(RuntimeError):
@@ -119,11 +124,13 @@ def status_string(status: int) -> str:
 
 def make_desc(kind: str, dtype: str, act: str, norm: str, L: int, N: int, d: int, d_ff: int, d_in: int = 0,
               lambda_channel: bool = False, loss_every_state: bool = False, eps: float = 1e-6,
-              gamma: float = 0.0, lambda_token: bool = False, post: str = "none") -> hbp_desc:
+              gamma: float = 0.0, lambda_token: bool = False, post: str = "none", heads: int = 0,
+              causal: bool = True, seq_len: int = 0) -> hbp_desc:
     return hbp_desc(C.sizeof(hbp_desc), KIND[kind], BF16 if dtype == "bf16" else F32,
                     ACT[act], NORM[norm],
                     LAMBDA_TOKEN if lambda_token else LAMBDA_CHANNEL if lambda_channel else LAMBDA_ONE,
-                    1 if loss_every_state else 0, eps, L, N, d, d_ff, d_in, gamma, POST[post])
+                    1 if loss_every_state else 0, eps, L, N, d, d_ff, d_in, gamma, POST[post], heads,
+                    1 if causal else 0, seq_len)
 
 
 def workspace_size(desc: hbp_desc) -> int:
@@ -159,13 +166,22 @@ class Problem:
     dW2: "object" = None
     dU: "object" = None
     workspace: "object" = None
+    Wqkv: "object" = None
+    Wo: "object" = None
+    qkv: "object" = None
+    attn_o: "object" = None
+    lse: "object" = None
+    dWqkv: "object" = None
+    dWo: "object" = None
 
     def buffers(self) -> hbp_buffers:
         ws = self.workspace
         return hbp_buffers(C.sizeof(hbp_buffers), _ptr(self.W1), _ptr(self.W2), _ptr(self.U), _ptr(self.lam),
                            _ptr(self.x), _ptr(self.y), _ptr(self.rinv), _ptr(self.z), _ptr(self.dphi),
                            _ptr(self.xin), _ptr(self.mask), _ptr(self.e), _ptr(self.g), _ptr(self.dW1), _ptr(self.dW2),
-                           _ptr(self.dU), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size())
+                           _ptr(self.dU), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+                           _ptr(self.Wqkv), _ptr(self.Wo), _ptr(self.qkv), _ptr(self.attn_o), _ptr(self.lse),
+                           _ptr(self.dWqkv), _ptr(self.dWo))
 
 
 def _stream(stream) -> Optional[int]:
@@ -270,14 +286,17 @@ class OptimState:
     loss: "object"        # device float: the last loss value
 
     def struct(self) -> hbp_optim_state:
-        return hbp_optim_state(C.sizeof(hbp_optim_state), *[_ptr(t) for t in self.master], *[_ptr(t) for t in self.m],
-                               *[_ptr(t) for t in self.v], _ptr(self.scratch),
-                               self.scratch.numel() * self.scratch.element_size())
+        three = lambda ts: [_ptr(t) for t in ts[:3]]
+        two = lambda ts: [_ptr(t) for t in (tuple(ts[3:]) + (None, None))[:2]]
+        qo = [x for pair in zip(two(self.master), two(self.m), two(self.v)) for x in pair]   # masterQ, mQ, vQ, masterO, ...
+        return hbp_optim_state(C.sizeof(hbp_optim_state), *three(self.master), *three(self.m), *three(self.v),
+                               _ptr(self.scratch), self.scratch.numel() * self.scratch.element_size(),
+                               qo[0], qo[3], qo[1], qo[4], qo[2], qo[5])
 
 
 def allocate_optim(p: Problem, adamw: bool, master: bool = True) -> OptimState:
     import torch
-    ws = (p.W1, p.W2, p.U)
+    ws = (p.W1, p.W2, p.U, p.Wqkv, p.Wo)
     f = lambda w: None if w is None else torch.zeros(w.shape, dtype=torch.float32, device=w.device)
     return OptimState(master=tuple((None if (w is None or not master) else w.float().clone()) for w in ws),
                       m=tuple(f(w) for w in ws), v=tuple((f(w) if adamw else None) for w in ws),
@@ -339,8 +358,11 @@ def allocate(w, inputs, device="cuda:0", N: Optional[int] = None) -> Problem:
     per_token = lam is not None and lam.ndim == 3      # [L,N,d] in the storage type; [L,d] is fp32
     desc = make_desc(w.kind, w.dtype, w.act, w.norm, w.L, N, w.d, w.d_ff, w.d_in,
                      lambda_channel=lam is not None and not per_token, lambda_token=per_token,
-                     loss_every_state=w.loss_every_state, eps=w.eps, post=getattr(w, "post", "none"))
+                     loss_every_state=w.loss_every_state, eps=w.eps, post=getattr(w, "post", "none"),
+                     heads=getattr(w, "heads", 0), causal=getattr(w, "causal", True), seq_len=getattr(w, "seq_len", 0))
     L, d, dff = w.L, w.d, w.d_ff
+    tfm = w.kind == "transformer"
+    Li = L // 2 if tfm else L        # rows of the inner state: one per MLP block
     x = torch.zeros((L + 1, N, d), dtype=dt, device=dev)
     x[0] = up(inputs["x0"])
     rms = w.norm == "rms"
@@ -350,8 +372,8 @@ def allocate(w, inputs, device="cuda:0", N: Optional[int] = None) -> Problem:
         lam=up(lam, dt if per_token else torch.float32), x=x,
         y=torch.zeros((L, N, d), dtype=dt, device=dev) if rms else None,
         rinv=torch.zeros((L, N), dtype=torch.float32, device=dev) if (rms or post == "rms") else None,
-        z=torch.zeros((L, N, dff), dtype=dt, device=dev),
-        dphi=torch.zeros((L, N, dff), dtype=dt, device=dev) if w.act == "gelu" else None,
+        z=torch.zeros((Li, N, dff), dtype=dt, device=dev),
+        dphi=torch.zeros((Li, N, dff), dtype=dt, device=dev) if w.act == "gelu" else None,
         xin=up(inputs["xin"]), e=up(inputs["e"]),
         mask=torch.zeros((L, N, d // 8), dtype=torch.uint8, device=dev) if getattr(w, "post", "none") == "relu" else None,
         g=torch.zeros((L + 1, N, d), dtype=dt, device=dev),
@@ -359,5 +381,12 @@ def allocate(w, inputs, device="cuda:0", N: Optional[int] = None) -> Problem:
         dW2=None if inputs["W2"] is None else torch.zeros(inputs["W2"].shape, dtype=torch.float32, device=dev),
         dU=None if inputs["U"] is None else torch.zeros(inputs["U"].shape, dtype=torch.float32, device=dev),
     )
+    if tfm:
+        p.Wqkv, p.Wo = up(inputs["Wqkv"]), up(inputs["Wo"])
+        p.qkv = torch.zeros((Li, N, 3 * d), dtype=dt, device=dev)
+        p.attn_o = torch.zeros((Li, N, d), dtype=dt, device=dev)
+        p.lse = torch.zeros((Li, N * w.heads), dtype=torch.float32, device=dev)
+        p.dWqkv = torch.zeros(inputs["Wqkv"].shape, dtype=torch.float32, device=dev)
+        p.dWo = torch.zeros(inputs["Wo"].shape, dtype=torch.float32, device=dev)
     p.workspace = torch.zeros(workspace_size(desc), dtype=torch.uint8, device=dev)
     return p

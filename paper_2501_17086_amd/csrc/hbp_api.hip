@@ -29,9 +29,12 @@ inline bool recurrent(const hbp_desc* d) { return d->kind == HBP_RNN || cell(d);
 inline long hidden_w(const hbp_desc* d) { return d->kind == HBP_LSTM ? d->d / 2 : d->d; }
 inline long hidden_off(const hbp_desc* d) { return d->kind == HBP_LSTM ? d->d / 2 : 0; }
 inline bool shared_w(const hbp_desc* d) { return recurrent(d); }
+// The alternating attention / MLP stack: weight sets and inner-state rows are counted per layer (L / 2).
+inline bool tfm(const hbp_desc* d) { return d->kind == HBP_TRANSFORMER; }
+inline long head_w(const hbp_desc* d) { return d->d / d->heads; }
 
 struct Workspace {
-  size_t off_v, off_da, off_part, off_scan, off_wt, off_pre, off_m, off_tmp, total;
+  size_t off_v, off_da, off_part, off_scan, off_wt, off_pre, off_m, off_tmp, off_dqkv, off_dsum, total;
 };
 
 // split-K factor for a parameter-gradient GEMM with `tiles` output tiles and a
@@ -58,10 +61,17 @@ int pick_split(long tiles, long K) {
 
 long tiles_of(long M, long N) { return ((M + 255) / 256) * ((N + 255) / 256); }
 
-struct Splits { int s_w2, s_w1, s_u; };
+struct Splits { int s_w2, s_w1, s_u, s_qkv, s_o; };
 
 Splits param_splits(const hbp_desc* d) {
-  Splits s{1, 1, 1};
+  Splits s{1, 1, 1, 1, 1};
+  if (tfm(d)) {
+    const long nb = d->L / 2;
+    s.s_w2 = s.s_w1 = pick_split(tiles_of(d->d, d->d_ff) * nb, d->N);
+    s.s_qkv = pick_split(tiles_of(3 * d->d, d->d) * nb, d->N);
+    s.s_o = pick_split(tiles_of(d->d, d->d) * nb, d->N);
+    return s;
+  }
   const long nb = shared_w(d) ? 1 : d->L;
   const long K = shared_w(d) ? d->L * d->N : d->N;
   s.s_w2 = pick_split(tiles_of(d->d, d->d_ff) * nb, K);
@@ -76,12 +86,16 @@ Workspace carve(const hbp_desc* d) {
   size_t o = 0;
   w.off_v = o;  o = align_up(o + (size_t)d->L * d->N * d->d * es, 256);
   // da [L,N,d_ff] in the storage type; the RNN forward also keeps U.xin here as fp32
-  size_t da_bytes = (size_t)d->L * d->N * d->d_ff * (recurrent(d) ? 4 : es);
+  size_t da_bytes = (size_t)(tfm(d) ? d->L / 2 : d->L) * d->N * d->d_ff * (recurrent(d) ? 4 : es);
   w.off_da = o; o = align_up(o + da_bytes, 256);
   Splits sp = param_splits(d);
-  const size_t nb = shared_w(d) ? 1 : (size_t)d->L;
+  const size_t nb = shared_w(d) ? 1 : tfm(d) ? (size_t)d->L / 2 : (size_t)d->L;
   size_t part = 0;
   if (sp.s_w2 > 1) part = (size_t)sp.s_w2 * nb * d->d * d->d_ff * 4;
+  if (tfm(d)) {
+    if (sp.s_qkv > 1 && (size_t)sp.s_qkv * nb * 3 * d->d * d->d * 4 > part) part = (size_t)sp.s_qkv * nb * 3 * d->d * d->d * 4;
+    if (sp.s_o > 1 && (size_t)sp.s_o * nb * d->d * d->d * 4 > part) part = (size_t)sp.s_o * nb * d->d * d->d * 4;
+  }
   if (sp.s_u > 1) {
     size_t pu = (size_t)sp.s_u * d->d_ff * d->d_in * 4;
     if (pu > part) part = pu;
@@ -100,6 +114,12 @@ Workspace carve(const hbp_desc* d) {
   // the standard GRU: what comes back through the candidate's product, [L,N,H] in the storage type
   w.off_tmp = o;
   if (gru(d)) o = align_up(o + (size_t)d->L * d->N * d->d * es, 256);
+  // the attention sub-blocks: the gradient of the attention's output (in tmp), of [q | k | v], and rowsum(do (.) o)
+  if (tfm(d)) o = align_up(o + (size_t)(d->L / 2) * d->N * d->d * es, 256);
+  w.off_dqkv = o;
+  if (tfm(d)) o = align_up(o + (size_t)(d->L / 2) * d->N * 3 * d->d * es, 256);
+  w.off_dsum = o;
+  if (tfm(d)) o = align_up(o + (size_t)(d->L / 2) * d->N * d->heads * 4, 256);
   w.total = o;
   return w;
 }
@@ -114,7 +134,7 @@ inline bool step_skinny(const hbp_desc* d) {
 hbp_status check_desc(const hbp_desc* d) {
   if (!d) return HBP_E_NULL;
   if (d->struct_size != sizeof(hbp_desc)) return HBP_E_INVALID_ARG;
-  if (d->kind < HBP_MLP || d->kind > HBP_GRU) return HBP_E_INVALID_ARG;
+  if (d->kind < HBP_MLP || d->kind > HBP_TRANSFORMER) return HBP_E_INVALID_ARG;
   if (d->dtype != HBP_F32 && d->dtype != HBP_BF16) return HBP_E_INVALID_ARG;
   if (d->act < HBP_ACT_GELU_ERF || d->act > HBP_ACT_IDENTITY) return HBP_E_INVALID_ARG;
   if (d->norm != HBP_NORM_NONE && d->norm != HBP_NORM_RMS) return HBP_E_INVALID_ARG;
@@ -126,7 +146,13 @@ hbp_status check_desc(const hbp_desc* d) {
                   d->d_ff != (gru(d) ? 3 : 2) * d->d))
     return HBP_E_INVALID_ARG;
   if (d->kind == HBP_LSTM && d->d % 16) return HBP_E_UNSUPPORTED;   // both halves of [c | h] in 16-byte vectors
-  if (d->kind == HBP_MLP && d->d_in != 0) return HBP_E_INVALID_ARG;
+  if ((d->kind == HBP_MLP || tfm(d)) && d->d_in != 0) return HBP_E_INVALID_ARG;
+  if (tfm(d)) {
+    if (d->L % 2 || d->heads <= 0 || d->seq_len <= 0 || (d->causal != 0 && d->causal != 1)) return HBP_E_INVALID_ARG;
+    if (d->N % d->seq_len || d->d % d->heads) return HBP_E_INVALID_ARG;
+    if (d->post != HBP_POST_NONE || head_w(d) % 8) return HBP_E_UNSUPPORTED;
+    if (!attn_supported(d->dtype, d->seq_len, (int)head_w(d))) return HBP_E_UNSUPPORTED;
+  }
   if (d->norm == HBP_NORM_RMS && !(d->eps >= 0.f)) return HBP_E_INVALID_ARG;
   if (d->d % 8 || d->d_ff % 8 || d->d_in % 8) return HBP_E_UNSUPPORTED;
   if (d->norm == HBP_NORM_RMS && d->d > 4096) return HBP_E_UNSUPPORTED;
@@ -154,6 +180,8 @@ hbp_status check_bufs(const hbp_desc* d, const hbp_buffers* b, int need) {
   if (d->norm == HBP_NORM_NONE && !b->x) return HBP_E_NULL;
   if ((need & NEED_FWD) && !b->x) return HBP_E_NULL;
   if (!b->z) return HBP_E_NULL;
+  if (tfm(d) && (!b->Wqkv || !b->Wo || !b->qkv || !b->attn_o || !b->lse)) return HBP_E_NULL;
+  if (tfm(d) && (need & NEED_PG) && (!b->dWqkv || !b->dWo)) return HBP_E_NULL;
   if (d->act == HBP_ACT_GELU_ERF && !b->dphi) return HBP_E_NULL;
   if (d->post == HBP_POST_RELU && (need & (NEED_FWD | NEED_BWD)) && !b->mask) return HBP_E_NULL;
   if (d->post == HBP_POST_RMS && (need & (NEED_FWD | NEED_BWD)) && !b->rinv) return HBP_E_NULL;
@@ -230,9 +258,110 @@ inline const char* at(const void* p, size_t bytes) { return reinterpret_cast<con
 // path, e_l is added to v_l by the second contraction's epilogue.
 inline bool e_in_vjp(const hbp_desc* d) { return d->loss_every_state && d->norm == HBP_NORM_NONE; }
 
+// ---- the alternating attention / MLP stack: step (i) for blocks l_lo..l_hi-1, each kind of sub-block batched over
+// its own blocks (attention: even l = 2j; MLP: odd l = 2j+1; state-shaped arrays then have a batch stride of two
+// states, inner arrays and weights of one layer) ----
+AttnArgs attn_args(const hbp_desc* d, const hbp_buffers* b, const Workspace& w, long j_lo, long j_hi) {
+  const size_t es = esize(d);
+  const long N = d->N, D = d->d;
+  AttnArgs a{};
+  a.qkv = at((const void*)b->qkv, (size_t)j_lo * N * 3 * D * es);
+  a.o = at(b->attn_o, (size_t)j_lo * N * D * es);
+  a.lse = b->lse + j_lo * N * d->heads;
+  a.dout = at((const void*)b->workspace, w.off_tmp + (size_t)j_lo * N * D * es);
+  a.dqkv = at(b->workspace, w.off_dqkv + (size_t)j_lo * N * 3 * D * es);
+  a.dsum = reinterpret_cast<float*>(at(b->workspace, w.off_dsum)) + j_lo * N * d->heads;
+  a.seqs = (j_hi - j_lo) * (N / d->seq_len);
+  a.T = d->seq_len;
+  a.heads = d->heads;
+  a.dh = (int)head_w(d);
+  a.causal = d->causal;
+  a.scale = 1.0f / sqrtf((float)head_w(d));
+  return a;
+}
+
+// first half: da_j = (g[2j+2] W2_j) (.) act' for the MLP sub-blocks; do_j = g[2j+1] Wo_j and, through the attention,
+// the gradient of [q | k | v] for the attention sub-blocks
+hbp_status tfm_stage1(const hbp_desc* d, const hbp_buffers* b, const Workspace& w, long l_lo, long l_hi, hipStream_t s) {
+  const size_t es = esize(d);
+  const long N = d->N, D = d->d, F = d->d_ff;
+  const long ja_lo = (l_lo + 1) / 2, ja_hi = (l_hi + 1) / 2;
+  const long jm_lo = l_lo / 2, jm_hi = l_hi / 2;
+  if (jm_hi > jm_lo) {
+    GemmArgs ga{};
+    ga.A = at(b->g, (size_t)(2 * jm_lo + 2) * N * D * es);
+    ga.B = at(b->W2, (size_t)jm_lo * D * F * es);
+    ga.C = at(b->workspace, w.off_da + (size_t)jm_lo * N * F * es);
+    ga.M = N; ga.N = F; ga.K = D;
+    ga.a_sm = D; ga.a_sk = 1;
+    ga.b_sk = F; ga.b_sn = 1;
+    ga.ldc = F;
+    ga.batch = jm_hi - jm_lo;
+    ga.a_sb = 2 * N * D; ga.b_sb = D * F; ga.c_sb = N * F;
+    ga.split_k = 1;
+    if (d->act == HBP_ACT_GELU_ERF) { ga.mode = EPI_MUL_AUX; ga.aux = at(b->dphi, (size_t)jm_lo * N * F * es); }
+    else if (d->act == HBP_ACT_TANH) { ga.mode = EPI_MUL_1MZ2; ga.aux = at(b->z, (size_t)jm_lo * N * F * es); }
+    else ga.mode = EPI_STORE;
+    ga.aux_sb = N * F;
+    HBP_RUN(run_gemm(d, ga, s, HBP_PROF_VJP1));
+  }
+  if (ja_hi > ja_lo) {
+    GemmArgs ga{};
+    ga.A = at(b->g, (size_t)(2 * ja_lo + 1) * N * D * es);
+    ga.B = at(b->Wo, (size_t)ja_lo * D * D * es);
+    ga.C = at(b->workspace, w.off_tmp + (size_t)ja_lo * N * D * es);
+    ga.M = N; ga.N = D; ga.K = D;
+    ga.a_sm = D; ga.a_sk = 1;
+    ga.b_sk = D; ga.b_sn = 1;
+    ga.ldc = D;
+    ga.batch = ja_hi - ja_lo;
+    ga.a_sb = 2 * N * D; ga.b_sb = D * D; ga.c_sb = N * D;
+    ga.split_k = 1;
+    ga.mode = EPI_STORE;
+    HBP_RUN(run_gemm(d, ga, s, HBP_PROF_VJP1));
+    ProfScope ps(HBP_PROF_ATTN, s);
+    HBP_TRY(launch_attn_bwd(d->dtype, attn_args(d, b, w, ja_lo, ja_hi), s));
+  }
+  return HBP_OK;
+}
+
+// second half: dn = da_j W1_j into v[2j+1], dn = dqkv_j Wqkv_j into v[2j] (+ e where the scan has no norm to apply first)
+hbp_status tfm_stage2(const hbp_desc* d, const hbp_buffers* b, const Workspace& w, long l_lo, long l_hi, hipStream_t s) {
+  const size_t es = esize(d);
+  const long N = d->N, D = d->d, F = d->d_ff;
+  const long ja_lo = (l_lo + 1) / 2, ja_hi = (l_hi + 1) / 2;
+  const long jm_lo = l_lo / 2, jm_hi = l_hi / 2;
+  for (int attn = 0; attn < 2; ++attn) {
+    const long j_lo = attn ? ja_lo : jm_lo, j_hi = attn ? ja_hi : jm_hi;
+    if (j_hi <= j_lo) continue;
+    const long l0 = attn ? 2 * j_lo : 2 * j_lo + 1;        // first block of this kind in the range
+    const long kk = attn ? 3 * D : F;
+    GemmArgs ga{};
+    ga.A = attn ? at(b->workspace, w.off_dqkv + (size_t)j_lo * N * kk * es) : at(b->workspace, w.off_da + (size_t)j_lo * N * kk * es);
+    ga.B = attn ? at(b->Wqkv, (size_t)j_lo * kk * D * es) : at(b->W1, (size_t)j_lo * kk * D * es);
+    ga.C = at(b->workspace, w.off_v + (size_t)l0 * N * D * es);
+    ga.M = N; ga.N = D; ga.K = kk;
+    ga.a_sm = kk; ga.a_sk = 1;
+    ga.b_sk = D; ga.b_sn = 1;
+    ga.ldc = D;
+    ga.batch = j_hi - j_lo;
+    ga.a_sb = N * kk; ga.b_sb = kk * D; ga.c_sb = 2 * N * D;
+    ga.split_k = 1;
+    ga.mode = EPI_STORE;
+    if (e_in_vjp(d)) {
+      ga.mode = EPI_ADD_AUX;
+      ga.aux = at(b->e, (size_t)l0 * N * D * es);
+      ga.aux_sb = 2 * N * D;
+    }
+    HBP_RUN(run_gemm(d, ga, s, HBP_PROF_VJP2));
+  }
+  return HBP_OK;
+}
+
 // da[l] = (g[l+1] . W2_l) (.) act'(a_l) for blocks l_lo..l_hi-1
 hbp_status vjp_stage1(const hbp_desc* d, const hbp_buffers* b, const Workspace& w, long l_lo, long l_hi,
                       hipStream_t s, bool skinny = false, void* rx_out = nullptr) {
+  if (tfm(d)) return tfm_stage1(d, b, w, l_lo, l_hi, s);
   const size_t es = esize(d);
   const long nl = l_hi - l_lo;
   if (gru(d)) {
@@ -334,6 +463,7 @@ hbp_status vjp_stage1(const hbp_desc* d, const hbp_buffers* b, const Workspace& 
 // dn[l] = da[l] . W1_l  (into the v buffer)
 hbp_status vjp_stage2(const hbp_desc* d, const hbp_buffers* b, const Workspace& w, long l_lo, long l_hi,
                       hipStream_t s, bool skinny = false, bool fuse_scan = false) {
+  if (tfm(d)) return tfm_stage2(d, b, w, l_lo, l_hi, s);
   const size_t es = esize(d);
   const long nl = l_hi - l_lo;
   const bool sh = shared_w(d);
@@ -554,14 +684,48 @@ hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
     HBP_RUN(run_gemm(d, ga, s, HBP_PROF_FORWARD));
   }
   for (long l = 0; l < d->L; ++l) {
+    const long wl = tfm(d) ? l / 2 : l;          // weight set and inner-state row of this block
     const size_t xo = (size_t)l * d->N * d->d * es;
-    const size_t fo = (size_t)l * d->N * d->d_ff * es;
+    const size_t fo = (size_t)wl * d->N * d->d_ff * es;
     const void* yl = at((const void*)b->x, xo);
     if (rms) {
       ProfScope ps(HBP_PROF_FORWARD, s);
       HBP_TRY(launch_rmsnorm_fwd(d->dtype, at((const void*)b->x, xo), at(b->y, xo), b->rinv + l * d->N, d->N, d->d,
                                  d->eps, s));
       yl = at((const void*)b->y, xo);
+    }
+    if (tfm(d) && l % 2 == 0) {     // attention sub-block: [q | k | v] = y Wqkv^T, attention, x_{l+1} = lambda (.) x_l + o Wo^T
+      const long N = d->N, D = d->d;
+      {
+        GemmArgs ga{};
+        ga.A = yl;
+        ga.B = at(b->Wqkv, (size_t)wl * 3 * D * D * es);
+        ga.C = at(b->qkv, (size_t)wl * N * 3 * D * es);
+        ga.M = N; ga.N = 3 * D; ga.K = D;
+        ga.a_sm = D; ga.a_sk = 1;
+        ga.b_sk = 1; ga.b_sn = D;
+        ga.ldc = 3 * D; ga.batch = 1; ga.split_k = 1;
+        ga.mode = EPI_STORE;
+        HBP_RUN(run_gemm(d, ga, s, HBP_PROF_FORWARD));
+      }
+      {
+        ProfScope ps(HBP_PROF_ATTN, s);
+        HBP_TRY(launch_attn_fwd(d->dtype, attn_args(d, b, w, wl, wl + 1), s));
+      }
+      GemmArgs ga{};
+      ga.A = at((const void*)b->attn_o, (size_t)wl * N * D * es);
+      ga.B = at(b->Wo, (size_t)wl * D * D * es);
+      ga.C = at(b->x, xo + (size_t)N * D * es);
+      ga.M = N; ga.N = D; ga.K = D;
+      ga.a_sm = D; ga.a_sk = 1;
+      ga.b_sk = 1; ga.b_sn = D;
+      ga.ldc = D; ga.batch = 1; ga.split_k = 1;
+      ga.mode = EPI_RESID;
+      ga.aux = at((const void*)b->x, xo);
+      ga.lambda = d->lambda_kind == HBP_LAMBDA_CHANNEL ? reinterpret_cast<const float*>(b->lambda) + l * D : nullptr;
+      ga.lambda_mn = d->lambda_kind == HBP_LAMBDA_TOKEN ? at(b->lambda, xo) : nullptr;
+      HBP_RUN(run_gemm(d, ga, s, HBP_PROF_FORWARD));
+      continue;
     }
     if (gru(d)) {
       // two dependent products per step: the gates z, r from x; then the candidate from r (.) x
@@ -668,7 +832,7 @@ hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
     {  // a = y W1^T (+ U xin); z = act(a); dphi = act'(a)
       GemmArgs ga{};
       ga.A = yl;
-      ga.B = sh ? b->W1 : at(b->W1, (size_t)l * d->d * d->d_ff * es);
+      ga.B = sh ? b->W1 : at(b->W1, (size_t)wl * d->d * d->d_ff * es);
       ga.C = at(b->z, fo);
       ga.M = d->N; ga.N = d->d_ff; ga.K = d->d;
       ga.a_sm = d->d; ga.a_sk = 1;
@@ -683,7 +847,7 @@ hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
     {  // x_{l+1} = lambda (.) x_l + z W2^T
       GemmArgs ga{};
       ga.A = at((const void*)b->z, fo);
-      ga.B = sh ? b->W2 : at(b->W2, (size_t)l * d->d * d->d_ff * es);
+      ga.B = sh ? b->W2 : at(b->W2, (size_t)wl * d->d * d->d_ff * es);
       ga.C = at(b->x, xo + (size_t)d->N * d->d * es);
       ga.M = d->N; ga.N = d->d; ga.K = d->d_ff;
       ga.a_sm = d->d_ff; ga.a_sk = 1;
@@ -899,6 +1063,19 @@ hbp_status hbp_param_grads(const hbp_desc* d, hbp_buffers* b, void* stream) {
   void* part = at(b->workspace, w.off_part);
   const void* g1 = at((const void*)bb.g, (size_t)d->N * d->d * es);
   const void* da = at((const void*)b->workspace, w.off_da);
+  if (tfm(d)) {
+    // MLP sub-blocks (odd l = 2j+1): dW2_j = g[2j+2]^T z_j, dW1_j = da_j^T y[2j+1]; attention sub-blocks (even l = 2j):
+    // dWo_j = g[2j+1]^T o_j, dWqkv_j = dqkv_j^T y[2j]
+    const long N = d->N, D = d->d, F = d->d_ff, Lh = d->L / 2;
+    const void* g2 = at((const void*)bb.g, (size_t)2 * N * D * es);
+    const void* y1 = at((const void*)bb.y, (size_t)N * D * es);
+    HBP_RUN(tn_gemm(d, g2, D, 2 * N * D, bb.z, F, N * F, bb.dW2, D, F, N, Lh, sp.s_w2, part, s));
+    HBP_RUN(tn_gemm(d, da, F, N * F, y1, D, 2 * N * D, bb.dW1, F, D, N, Lh, sp.s_w1, part, s));
+    HBP_RUN(tn_gemm(d, g1, D, 2 * N * D, bb.attn_o, D, N * D, bb.dWo, D, D, N, Lh, sp.s_o, part, s));
+    HBP_RUN(tn_gemm(d, at((const void*)b->workspace, w.off_dqkv), 3 * D, 3 * N * D, bb.y, D, 2 * N * D, bb.dWqkv, 3 * D, D,
+                    N, Lh, sp.s_qkv, part, s));
+    return HBP_OK;
+  }
   // dW2[c,j] = sum_n g_{l+1}[n,c] z_l[n,j]   (the gated cell has no second weight)
   if (!cell(d))
     HBP_RUN(tn_gemm(d, g1, d->d, d->N * d->d, bb.z, d->d_ff, d->N * d->d_ff, bb.dW2, d->d, d->d_ff, K, nb, sp.s_w2,
@@ -920,10 +1097,12 @@ hbp_status hbp_param_grads(const hbp_desc* d, hbp_buffers* b, void* stream) {
 }
 
 namespace {
-struct ParamSizes { long n1, n2, nu; };
+struct ParamSizes { long n1, n2, nu, nq, no; };
 ParamSizes param_sizes(const hbp_desc* d) {
-  const long nb = shared_w(d) ? 1 : d->L;
+  const long nb = shared_w(d) ? 1 : tfm(d) ? d->L / 2 : d->L;
   ParamSizes p{};
+  p.nq = tfm(d) ? nb * 3 * d->d * d->d : 0;
+  p.no = tfm(d) ? nb * d->d * d->d : 0;
   p.n1 = nb * d->d_ff * hidden_w(d);
   p.n2 = cell(d) ? 0 : nb * d->d * d->d_ff;
   p.nu = recurrent(d) ? d->d_ff * d->d_in : 0;
@@ -973,9 +1152,11 @@ hbp_status hbp_optimizer_step(const hbp_desc* d, hbp_buffers* b, const hbp_optim
   if (adamw && (!(o->beta2 >= 0.f && o->beta2 < 1.f) || !(o->eps >= 0.f) || o->step < 1)) return HBP_E_INVALID_ARG;
   const ParamSizes ps = param_sizes(d);
   struct T3 { void* w; float* master; const float* g; float* m; float* v; long n; };
-  T3 t[3] = {{const_cast<void*>(b->W1), st->master1, b->dW1, st->m1, st->v1, ps.n1},
+  T3 t[5] = {{const_cast<void*>(b->W1), st->master1, b->dW1, st->m1, st->v1, ps.n1},
              {const_cast<void*>(b->W2), st->master2, b->dW2, st->m2, st->v2, ps.n2},
-             {const_cast<void*>(b->U), st->masterU, b->dU, st->mU, st->vU, ps.nu}};
+             {const_cast<void*>(b->U), st->masterU, b->dU, st->mU, st->vU, ps.nu},
+             {const_cast<void*>(b->Wqkv), st->masterQ, b->dWqkv, st->mQ, st->vQ, ps.nq},
+             {const_cast<void*>(b->Wo), st->masterO, b->dWo, st->mO, st->vO, ps.no}};
   for (const T3& x : t) {
     if (x.n == 0) continue;
     if (!x.w || !x.g || !x.m || (adamw && !x.v)) return HBP_E_NULL;
@@ -986,7 +1167,7 @@ hbp_status hbp_optimizer_step(const hbp_desc* d, hbp_buffers* b, const hbp_optim
   ProfScope pscope(HBP_PROF_OTHER, s);
   const float* clip = nullptr;
   if (o->clip_norm > 0.f) {
-    const float* gs[3]; long ns[3]; int cnt = 0;
+    const float* gs[5]; long ns[5]; int cnt = 0;
     for (const T3& x : t) if (x.n) { gs[cnt] = x.g; ns[cnt] = x.n; ++cnt; }
     float* factor = st->scratch + train_scratch_floats() - 8;
     HBP_TRY(launch_clip_factor(gs, ns, cnt, o->clip_norm, st->scratch, factor, s));

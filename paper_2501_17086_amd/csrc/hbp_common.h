@@ -153,6 +153,23 @@ hipError_t launch_gemm_generic(int dtype, const GemmArgs& g, hipStream_t s);
 // fast bf16 MFMA path; returns false when the shape/layout is not covered
 bool launch_gemm_mfma(const GemmArgs& g, hipStream_t s, hipError_t* err);
 
+// Multi-head self-attention on rows [q | k | v] (3 d wide, head h in columns h dh .. of each third), `seqs` sequences of
+// T consecutive rows each; o and dout are d wide.  lse and dsum hold one float per (sequence, head, position).
+struct AttnArgs {
+  const void* qkv;      // storage type [seqs * T, 3 d]
+  void* o;              // forward: out; backward: in   [seqs * T, d]
+  float* lse;           // forward: out; backward: in   log2 of each row's sum of exp2(s log2 e)
+  const void* dout;     // backward: gradient of o      [seqs * T, d]
+  void* dqkv;           // backward: out                [seqs * T, 3 d]
+  float* dsum;          // backward: scratch            sum_c dout (.) o per row and head
+  long seqs, T;
+  int heads, dh, causal;
+  float scale;          // 1 / sqrt(dh)
+};
+bool attn_supported(int dtype, long T, int dh);
+hipError_t launch_attn_fwd(int dtype, const AttnArgs& a, hipStream_t s);
+hipError_t launch_attn_bwd(int dtype, const AttnArgs& a, hipStream_t s);
+
 // Few-row bf16 product with both operands K-contiguous: C[M,N] = epilogue(A[M,K] . Bt[N,K]^T).
 // Modes EPI_STORE, EPI_ACT_TANH, EPI_MUL_AUX, EPI_MUL_1MZ2, EPI_ADD_AUX; aux is bf16 [M,N] with row stride ldaux.
 // EPI_RESID here is the residual path's backward step, C = acc (+ aux) + lambda (.) next: next and

@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256) void optim_kernel(T* __restrict__ w, float* __
 
 }  // namespace
 
-size_t train_scratch_floats() { return 4 * RED_BLOCKS + 16; }
+size_t train_scratch_floats() { return 6 * RED_BLOCKS + 16; }
 
 template <typename T>
 hipError_t launch_mse_t(const void* x, const void* target, void* e, long n, float inv_n, float* partial, float* loss,
@@ -176,7 +176,7 @@ hipError_t launch_zero(int dtype, void* p, long n, hipStream_t s) {
   return hipGetLastError();
 }
 
-// factor[0] = min(1, max_norm / (global L2 norm of the given gradients + 1e-6)); up to 3 tensors
+// factor[0] = min(1, max_norm / (global L2 norm of the given gradients + 1e-6)); up to 5 tensors
 hipError_t launch_clip_factor(const float* const* grads, const long* sizes, int count, float max_norm, float* scratch,
                               float* factor, hipStream_t s) {
   for (int t = 0; t < count; ++t)

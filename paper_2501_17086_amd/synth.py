@@ -24,7 +24,7 @@ from typing import Dict, Optional
 import numpy as np
 
 # tensor ids for the Philox key
-_T_W1, _T_W2, _T_U, _T_LAM, _T_X0, _T_XIN, _T_E = 1, 2, 3, 4, 5, 6, 7
+_T_W1, _T_W2, _T_U, _T_LAM, _T_X0, _T_XIN, _T_E, _T_WQKV, _T_WO = 1, 2, 3, 4, 5, 6, 7, 8, 9
 
 
 @dataclass(frozen=True)
@@ -32,6 +32,8 @@ class Workload:
     name: str
     kind: str            # 'mlp' | 'rnn' | 'gated' (recurrent cell x' = (1-u) x + u c; d_ff = 2 d) | 'lstm' (state
                          # [c | h], d = 2H, d_ff = 4H) | 'gru' (the standard GRU, gates [z | r | n]; d_ff = 3 d)
+                         # | 'transformer' (L = 2 x layers: attention sub-blocks at even l, MLP sub-blocks at odd l;
+                         # the N tokens are N / seq_len sequences of seq_len consecutive rows)
     dtype: str           # 'f32' | 'bf16'   (storage; accumulation is fp32 on the GPU)
     act: str             # 'gelu' | 'tanh' | 'identity'
     norm: str            # 'none' | 'rms'
@@ -53,6 +55,10 @@ class Workload:
     eps: float = 1e-6
     ks: tuple = (1, 2, 3, 4)
     seed: int = 0
+    heads: int = 0       # 'transformer': attention heads, sequence length, causal mask
+    seq_len: int = 0
+    causal: bool = True
+    gamma: float = 0.0   # the share of the residual connection counted with the block that the workload is run with
 
     @property
     def tokens(self) -> int:
@@ -83,6 +89,15 @@ WORKLOADS: Dict[str, Workload] = {
                            lam="uniform", lam_lo=0.8, lam_hi=1.0, w1_std=0.02, w2_std=0.02,
                            w2_scale=1.0 / np.sqrt(192.0), ks=(1, 2, 3)),
 }
+# The paper's GPT-2 configuration (appendix, hyperparameter table: 12 layers, hidden 256, context 256, batch 128;
+# every layer split into attention and feed-forward sub-layers, L = 24; run with gamma = 0.2), with RMS norm and no
+# biases, and a larger stack of the same kind (24 layers of width 1024, 16 sequences of 1024 tokens).
+WORKLOADS["gpt2_paper"] = Workload("gpt2_paper", "transformer", "bf16", "gelu", "rms", L=24, N=128 * 256, d=256,
+                                   d_ff=1024, w1_std=0.02, w2_std=0.02, w2_scale=1.0 / np.sqrt(24.0), heads=4,
+                                   seq_len=256, causal=True, gamma=0.2, ks=(1, 2, 3))
+WORKLOADS["transformer_attn"] = Workload("transformer_attn", "transformer", "bf16", "gelu", "rms", L=48, N=16 * 1024,
+                                         d=1024, d_ff=4096, w1_std=0.02, w2_std=0.02, w2_scale=1.0 / np.sqrt(48.0),
+                                         heads=16, seq_len=1024, causal=True, gamma=0.2, ks=(1, 2, 3))
 # contractive variant of the RNN (recurrent weights x 0.25): the stack as
 # specified is chaotic, so exact BPTT gradients overflow over 4096 steps.
 WORKLOADS["gated_rnn_contractive"] = replace(WORKLOADS["gated_rnn"], name="gated_rnn_contractive",
@@ -140,6 +155,14 @@ def weights_block(w: Workload, l: int):
     return storage_round(w, W1), storage_round(w, W2)
 
 
+def attention_weights_block(w: Workload, j: int):
+    """(Wqkv_j [3d,d], Wo_j [d,d]) of layer j of a 'transformer' stack; Wo scaled like W2."""
+    s1 = w.w1_std if w.w1_std > 0 else 1.0 / np.sqrt(w.d)
+    s2 = (w.w2_std if w.w2_std > 0 else 1.0 / np.sqrt(w.d)) * w.w2_scale
+    return (storage_round(w, _normal(w, _T_WQKV, j, (3 * w.d, w.d), s1)),
+            storage_round(w, _normal(w, _T_WO, j, (w.d, w.d), s2)))
+
+
 def make_lambda(w: Workload, tokens=None) -> Optional[np.ndarray]:
     """lambda [L,d] fp32, or None when lambda = 1; 'sigmoid_full': [L,N,d] in the
     storage type (gates that depend on the token, e.g. computed from a cell's input)."""
@@ -171,14 +194,20 @@ def make_inputs(w: Workload, tokens=None) -> Dict[str, Optional[np.ndarray]]:
     """
     sl = tokens if tokens is not None else slice(None)
     out: Dict[str, Optional[np.ndarray]] = {}
-    if w.kind == "mlp":
-        W1 = np.empty((w.L, w.d_ff, w.d), np.float32)
-        W2 = np.empty((w.L, w.d, w.d_ff), np.float32)
+    if w.kind in ("mlp", "transformer"):
+        nb = w.L // 2 if w.kind == "transformer" else w.L
+        W1 = np.empty((nb, w.d_ff, w.d), np.float32)
+        W2 = np.empty((nb, w.d, w.d_ff), np.float32)
+        if w.kind == "transformer":
+            out["Wqkv"] = np.empty((nb, 3 * w.d, w.d), np.float32)
+            out["Wo"] = np.empty((nb, w.d, w.d), np.float32)
 
         def fill(l):   # every block has its own generator key: order of evaluation is free
             W1[l], W2[l] = weights_block(w, l)
+            if w.kind == "transformer":
+                out["Wqkv"][l], out["Wo"][l] = attention_weights_block(w, l)
         with ThreadPoolExecutor(max_workers=8) as ex:
-            list(ex.map(fill, range(w.L)))
+            list(ex.map(fill, range(nb)))
         out["U"] = None
         out["xin"] = None
     else:

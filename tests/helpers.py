@@ -14,8 +14,23 @@ TOL = {"f32": 1e-5, "bf16": 2e-2}   # relative L2, GPU vs oracle
 def oracle_stack(w: synth.Workload, inp) -> O.Stack:
     if w.kind in ("gated", "lstm", "gru"):
         return O.Stack(w.kind, w.act, w.norm, inp["W1"], None, U=inp["U"], L=w.L)
+    if w.kind == "transformer":
+        return O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], eps=w.eps, Wqkv=inp["Wqkv"],
+                       Wo=inp["Wo"], T=w.seq_len, heads=w.heads, causal=w.causal)
     return O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], U=inp["U"], eps=w.eps, L=w.L,
                    post=w.post)
+
+
+def attn_row_stats(st: O.Stack, qkv: np.ndarray) -> np.ndarray:
+    """What the library keeps of an attention sub-block's probabilities: per (sequence, head, position) the base-2
+    logarithm of sum_j exp2(s_j log2 e) over the keys the query sees, s = q k^T / sqrt(dh); qkv [N,3d] -> [N heads]."""
+    d = qkv.shape[1] // 3
+    q, k = (O._heads(st, qkv[:, j * d:(j + 1) * d]) for j in range(2))
+    s = q @ k.transpose(0, 1, 3, 2) / np.sqrt(q.shape[-1])
+    if st.causal:
+        s = np.where(np.tril(np.ones((st.T, st.T), dtype=bool)), s, -np.inf)
+    m = s.max(axis=-1)
+    return ((m + np.log(np.exp(s - m[..., None]).sum(axis=-1))) / np.log(2.0)).reshape(-1)
 
 
 def to_np(t) -> np.ndarray:
@@ -42,7 +57,7 @@ def oracle_saved_rounded(w: synth.Workload, sv):
             out[k] = r(sv[k])
         out["y"] = out["x"][:-1]
         return out
-    for k in ("x", "y", "z", "dphi"):
+    for k in ("x", "y", "z", "dphi") + (("qkv", "o") if w.kind == "transformer" else ()):
         out[k] = r(sv[k])
     out["rinv"] = sv["rinv"].astype(np.float32).astype(np.float64)
     if "rpost" in sv:
@@ -77,6 +92,14 @@ def upload_saved(p, w: synth.Workload, sv_r):
         return
     put(p.y, sv_r["y"])
     put(p.rinv, sv_r["rpost"] if w.post == "rms" else sv_r["rinv"])
+    if w.kind == "transformer":   # inner state of the MLP sub-blocks (odd l) and of the attention sub-blocks (even l)
+        put(p.z, sv_r["z"][1::2])
+        put(p.dphi, sv_r["dphi"][1::2])
+        put(p.qkv, sv_r["qkv"][0::2])
+        put(p.attn_o, sv_r["o"][0::2])
+        st = sv_r["_stack"]
+        put(p.lse, np.stack([attn_row_stats(st, sv_r["qkv"][l]) for l in range(0, w.L, 2)]))
+        return
     put(p.z, sv_r["z"])
     put(p.dphi, sv_r["dphi"])
     if p.mask is not None:     # one bit per element, channel 8c+j in bit j of byte c

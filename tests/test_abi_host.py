@@ -27,10 +27,10 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layout_matches_header():
     # field order and sizes as in the header (LP64)
-    assert C.sizeof(B.hbp_desc) == 4 * 8 + 8 * 5 + 4 * 2
-    assert C.sizeof(B.hbp_buffers) == 8 + 8 * 16 + 8 + 8
+    assert C.sizeof(B.hbp_desc) == 4 * 8 + 8 * 5 + 4 * 2 + 4 * 2 + 8
+    assert C.sizeof(B.hbp_buffers) == 8 + 8 * 16 + 8 + 8 + 8 * 7
     assert C.sizeof(B.hbp_optim) == 4 * 8 + 8
-    assert C.sizeof(B.hbp_optim_state) == 8 + 8 * 9 + 8 + 8
+    assert C.sizeof(B.hbp_optim_state) == 8 + 8 * 9 + 8 + 8 + 8 * 6
 
 
 def _desc(**kw):
@@ -100,6 +100,30 @@ def test_gated_cell_descriptor_rules():
     bufs.workspace_bytes = n.value
     assert B.lib().hbp_check(C.byref(d), C.byref(bufs)) == 4
     bufs.lambda_ = 256
+    assert B.lib().hbp_check(C.byref(d), C.byref(bufs)) == 0
+
+
+def test_transformer_descriptor_rules():
+    n = C.c_size_t(0)
+    ok = dict(kind="transformer", L=4, N=64, d=128, d_ff=256, heads=2, seq_len=32)
+    assert B.lib().hbp_workspace_size(C.byref(_desc(**ok)), C.byref(n)) == 0 and n.value > 0
+    for bad in (dict(L=3), dict(heads=0), dict(seq_len=0), dict(seq_len=48), dict(heads=3), dict(d_in=8)):
+        assert B.lib().hbp_workspace_size(C.byref(_desc(**{**ok, **bad})), C.byref(n)) == 1, bad
+    # heads must be whole 16-byte vectors; a ReLU or norm after the sum is not built for this kind; the plain
+    # kernels (fp32, or heads other than 64 wide) hold a row of scores in LDS
+    for bad in (dict(d=96, heads=8), dict(post="relu"), dict(dtype="f32", N=16384, seq_len=16384),
+                dict(heads=4, N=16384, seq_len=16384)):
+        assert B.lib().hbp_workspace_size(C.byref(_desc(**{**ok, **bad})), C.byref(n)) == 2, bad
+    assert B.lib().hbp_workspace_size(C.byref(_desc(**{**ok, "N": 16384, "seq_len": 16384})), C.byref(n)) == 0
+    # the attention's weights and saved state are required pointers
+    d = _desc(**ok)
+    B.lib().hbp_workspace_size(C.byref(d), C.byref(n))
+    bufs = B.hbp_buffers(C.sizeof(B.hbp_buffers))
+    for f in ("W1", "W2", "x", "y", "rinv", "z", "dphi", "e", "g", "workspace", "Wqkv", "Wo", "qkv", "attn_o"):
+        setattr(bufs, f, 256)
+    bufs.workspace_bytes = n.value
+    assert B.lib().hbp_check(C.byref(d), C.byref(bufs)) == 4
+    bufs.lse = 256
     assert B.lib().hbp_check(C.byref(d), C.byref(bufs)) == 0
 
 

@@ -109,6 +109,28 @@ CASES = {
                                   loss_every_state=False, ks=(0, 1, 3)),
     "gru_splitk": synth.scaled(W["gru_std_cell"], name="gru_splitk", L=128, N=64, d=256, d_ff=768, d_in=128,
                                ks=(0, 2)),
+    # attention sub-blocks (L = 2 x layers): fp32 with narrow heads (plain kernels), causal and not; bf16 with 64-wide
+    # heads (matrix-core kernels) on a sequence length with a ragged last tile of 32, not causal on three tiles, 32-wide
+    # heads in bf16 (plain kernels), whole 256-row GEMM tiles with several tiles of queries per sequence, a loss at
+    # every state without a norm (e added by the second contraction), contractions over tokens in several shares
+    "tfm_f32": synth.scaled(W["gpt2_paper"], name="tfm_f32", dtype="f32", L=4, N=30, seq_len=10, d=32, heads=2,
+                            d_ff=64, w1_std=0.0, w2_std=0.0, w2_scale=0.7, lam="uniform", lam_lo=0.8, lam_hi=1.0,
+                            ks=(0, 1, 2, 4)),
+    "tfm_f32_bidir": synth.scaled(W["gpt2_paper"], name="tfm_f32_bidir", dtype="f32", L=6, N=21, seq_len=7, d=48,
+                                  heads=3, d_ff=40, w1_std=0.0, w2_std=0.0, w2_scale=0.7, causal=False, ks=(0, 2, 6)),
+    "tfm_small": synth.scaled(W["gpt2_paper"], name="tfm_small", L=6, N=120, seq_len=40, d=128, heads=2, d_ff=256,
+                              w1_std=0.0, w2_std=0.0, w2_scale=0.6, ks=(0, 1, 2, 6)),
+    "tfm_bidir": synth.scaled(W["gpt2_paper"], name="tfm_bidir", L=4, N=140, seq_len=70, d=128, heads=2, d_ff=128,
+                              w1_std=0.0, w2_std=0.0, w2_scale=0.6, causal=False, ks=(0, 1, 3)),
+    "tfm_heads_32": synth.scaled(W["gpt2_paper"], name="tfm_heads_32", L=4, N=66, seq_len=33, d=64, heads=2, d_ff=128,
+                                 w1_std=0.0, w2_std=0.0, w2_scale=0.6, ks=(0, 2)),
+    "tfm_aligned": synth.scaled(W["gpt2_paper"], name="tfm_aligned", L=4, N=1024, seq_len=256, d=256, heads=4,
+                                d_ff=512, w1_std=0.0, w2_std=0.0, w2_scale=0.6, ks=(0, 1, 2, 3)),
+    "tfm_loss_all": synth.scaled(W["gpt2_paper"], name="tfm_loss_all", L=4, N=96, seq_len=48, d=128, heads=2,
+                                 d_ff=256, norm="none", w2_scale=0.5, loss_every_state=True, lam="uniform",
+                                 lam_lo=0.8, lam_hi=1.0, ks=(0, 1, 3)),
+    "tfm_splitk": synth.scaled(W["gpt2_paper"], name="tfm_splitk", L=2, N=8192, seq_len=128, d=128, heads=2,
+                               d_ff=256, w1_std=0.0, w2_std=0.0, w2_scale=0.6, ks=(0, 2)),
     # the LSTM cell (state [c | h]; the contraction's result lands in the hidden half of v with the full row stride)
     "lstm_small": synth.scaled(W["lstm_cell"], name="lstm_small", L=37, N=5, d=128, d_ff=256, d_in=64,
                                ks=(0, 1, 2, 5)),
@@ -180,7 +202,9 @@ CASES = {
                                 ks=(0, 2)),
 }
 SPLITK_CASES = ["mlp_splitk", "mlp_splitk_odd", "rnn_splitk", "rnn_splitk_odd", "gated_splitk", "lstm_splitk",
-                "gru_splitk"]
+                "gru_splitk"]       # (tfm_splitk is listed with the transformer cases)
+TFM_CASES = ["tfm_f32", "tfm_f32_bidir", "tfm_small", "tfm_bidir", "tfm_heads_32", "tfm_aligned", "tfm_loss_all",
+             "tfm_splitk"]
 GRU_CASES = ["gru_small", "gru_f32", "gru_long", "gru_width_72", "gru_aligned", "gru_last_loss"]
 
 
@@ -224,7 +248,7 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
         for l in range(w.L + 1):     # per state: an error confined to one state, row or element must not hide
             H.assert_close(got[l], kept[l], 2 * tol, f"{tag} {label} state {l}", row_factor=2.0, abs_factor=4.0)
         pg = O.param_grads(st, sv_oracle, want_g, xin)
-        for nm, t in (("dW1", p.dW1), ("dW2", p.dW2), ("dU", p.dU)):
+        for nm, t in (("dW1", p.dW1), ("dW2", p.dW2), ("dU", p.dU), ("dWqkv", p.dWqkv), ("dWo", p.dWo)):
             if t is not None:
                 H.assert_close(H.to_np(t), pg[nm], tol, f"{tag} {label}: {nm}", row_floor=0.5)
 
@@ -249,7 +273,8 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
                                   "postact_f32_none", "gated_small", "gated_f32", "gated_long", "gated_width_72",
                                   "gated_aligned", "lstm_small", "lstm_f32", "lstm_long", "lstm_width_80",
                                   "lstm_aligned", "ragged_tokens", "postnorm_f32", "postnorm_small",
-                                  "gated_last_loss", "lstm_last_loss", "odd_widths"] + SPLITK_CASES + GRU_CASES)
+                                  "gated_last_loss", "lstm_last_loss", "odd_widths"] + SPLITK_CASES + GRU_CASES
+                         + TFM_CASES)
 def test_backward_end_to_end(B, name):
     """Own forward on each side, then Highway-BP at every k of the case, exact BP
     and the parameter gradients."""
@@ -257,6 +282,23 @@ def test_backward_end_to_end(B, name):
     inp, st, sv, p = _setup(B, w)
     B.hbp_forward(p)
     _check_backward(B, w, p, st, sv, inp, name)
+
+
+@pytest.mark.parametrize("name", TFM_CASES)
+def test_forward_of_the_transformer_stack(B, name):
+    """States, the MLP sub-blocks' inner state, [q | k | v], the attention's output and its row statistics."""
+    w = CASES[name]
+    inp, st, sv, p = _setup(B, w)
+    B.hbp_forward(p)
+    torch.cuda.synchronize()
+    tol = H.TOL[w.dtype]
+    for l in range(w.L + 1):
+        H.assert_close(H.to_np(p.x)[l], sv["x"][l], tol, f"{name} x[{l}]")
+    H.assert_close(H.to_np(p.z), sv["z"][1::2], tol, f"{name} z")
+    H.assert_close(H.to_np(p.qkv), sv["qkv"][0::2], tol, f"{name} qkv")
+    H.assert_close(H.to_np(p.attn_o), sv["o"][0::2], tol, f"{name} attention output")
+    want = np.stack([H.attn_row_stats(st, sv["qkv"][l]) for l in range(0, w.L, 2)])
+    assert np.abs(H.to_np(p.lse) - want).max() < (1e-4 if w.dtype == "f32" else 0.05)
 
 
 @pytest.mark.parametrize("name", ["gated_small", "gated_f32", "gated_width_72", "gated_aligned"])
@@ -335,12 +377,14 @@ def test_forward_with_relu_after_the_sum(B, name):
                                   "postact_rms", "postact_wide", "postact_aligned", "postact_f32_none",
                                   "postact_f32_deep", "gated_small", "gated_long", "lstm_small", "lstm_long",
                                   "postnorm_small", "postnorm_wide", "postnorm_aligned", "postnorm_f32",
-                                  "postact_loss_all", "gru_small", "gru_long"])
+                                  "postact_loss_all", "gru_small", "gru_long", "tfm_f32", "tfm_small", "tfm_bidir",
+                                  "tfm_heads_32"])
 def test_backward_shared_state(B, name):
     """Both backward passes read the same (storage-rounded) forward state."""
     w = CASES[name]
     inp, st, sv, p = _setup(B, w)
     sv_r = H.oracle_saved_rounded(w, sv)
+    sv_r["_stack"] = st
     H.upload_saved(p, w, sv_r)
     # Exact BPTT through the chaotic RNN amplifies storage rounding exponentially
     # with the number of steps (gradient norms grow by orders of magnitude), so
@@ -356,6 +400,7 @@ def test_backward_shared_state(B, name):
                                         ("rnn_token_gates_long", 1.0), ("mlp_token_gates", 0.3),
                                         ("gated_small", 0.3), ("gated_long", 1.0), ("gated_f32", 0.6),
                                         ("lstm_small", 0.3), ("lstm_long", 0.7), ("gru_small", 0.3), ("gru_long", 1.0),
+                                        ("tfm_f32", 0.2), ("tfm_small", 0.2), ("tfm_small", 1.0),
                                         ("postnorm_small", 0.5), ("postnorm_wide", 0.8), ("postnorm_f32", 1.0),
                                         ("postnorm_aligned", 0.2)])
 def test_gamma_iterates(B, name, gamma):
@@ -365,6 +410,7 @@ def test_gamma_iterates(B, name, gamma):
     w = CASES[name]
     inp, st, sv, p = _setup(B, w)
     sv_r = H.oracle_saved_rounded(w, sv)
+    sv_r["_stack"] = st
     H.upload_saved(p, w, sv_r)
     tol = H.TOL[w.dtype]
     for k in w.ks:
@@ -383,7 +429,7 @@ def test_gamma_iterates(B, name, gamma):
             else:
                 assert float(p.g[l].abs().max()) == 0.0
         pg = O.param_grads(st, sv_r, want, inp["xin"])
-        for nm, t in (("dW1", p.dW1), ("dW2", p.dW2), ("dU", p.dU)):
+        for nm, t in (("dW1", p.dW1), ("dW2", p.dW2), ("dU", p.dU), ("dWqkv", p.dWqkv), ("dWo", p.dWo)):
             if t is not None:
                 assert H.rel(H.to_np(t), pg[nm]) < tol, f"{name} gamma={gamma} k={k}: {nm}"
     if w.L <= 40:
