@@ -62,6 +62,8 @@ def algorithmic_work(w, k):
     (iteration `it` recomputes blocks 0 .. L-it only).  dw: the token
     contractions of hbp_param_grads.  scan: every state element is read once
     per input stream and written once."""
+    if w.kind == "transformer":
+        return transformer_work(w, k)
     s = storage_bytes(w)
     L, N, d, dff = w.L, w.N, w.d, w.d_ff
     per_block = 2.0 * N * d * dff
@@ -122,6 +124,42 @@ def algorithmic_work(w, k):
             "scan_launches": 1 + iters, "vjp1_bytes": vjp1_bytes, "vjp2_bytes": vjp2_bytes, "dw_bytes": dw_bytes}
 
 
+def transformer_work(w, k):
+    """The same figures for the alternating attention / MLP stack (L = 2 x layers).  An attention sub-block's step (i)
+    is: do = g Wo (class vjp1), the attention's own backward (class attn: the five products S, dP, dV, dQ, dK of
+    2 T^2 dh flops each per sequence and head, half of that under a causal mask; it reads q, k, v, do, o and writes
+    dq, dk, dv), dn = [dq | dk | dv] Wqkv (class vjp2).  An iteration covers blocks 0 .. L-it."""
+    s = storage_bytes(w)
+    L, N, d, dff, T = w.L, w.N, w.d, w.d_ff, w.seq_len
+    iters = min(k, L)
+    his = [L - it + 1 for it in range(1, iters + 1)]
+    n_attn = [(h + 1) // 2 for h in his]          # even l below l_hi
+    n_mlp = [h // 2 for h in his]
+    Lh = L // 2
+    mlp_f, wo_f, qkv_f = 2.0 * N * d * dff, 2.0 * N * d * d, 2.0 * N * 3 * d * d
+    attn_f = 5 * 2.0 * T * T * (d // w.heads) * (N // T) * w.heads * (0.5 if w.causal else 1.0)
+    e_aux = N * d * s if (w.loss_every_state and w.norm == "none") else 0.0
+    aux1 = 0.0 if w.act == "identity" else float(N) * dff * s
+    b1m = lambda nb: nb * (N * d * s + aux1 + N * dff * s + d * dff * s)
+    b1a = lambda nb: nb * (2.0 * N * d * s + d * d * s)
+    b2m = lambda nb: nb * (N * dff * s + N * d * s + e_aux + d * dff * s)
+    b2a = lambda nb: nb * (N * 3 * d * s + N * d * s + e_aux + 3 * d * d * s)
+    S = float(L) * N * d
+    streams_in = 1 + (1 if w.norm == "rms" else 0) + (1 if (w.loss_every_state and w.norm == "rms") else 0)
+    return {
+        "vjp1": mlp_f * (sum(n_mlp) + Lh) + wo_f * (sum(n_attn) + Lh),
+        "vjp2": mlp_f * sum(n_mlp) + qkv_f * sum(n_attn),
+        "attn": attn_f * (sum(n_attn) + Lh),
+        "dw": Lh * (2 * mlp_f + wo_f + qkv_f),
+        "vjp1_bytes": sum(b1m(a) for a in n_mlp) + b1m(Lh) + sum(b1a(a) for a in n_attn) + b1a(Lh),
+        "vjp2_bytes": sum(b2m(a) for a in n_mlp) + sum(b2a(a) for a in n_attn),
+        "attn_bytes": (sum(n_attn) + Lh) * 8.0 * N * d * s,
+        "dw_bytes": Lh * (2.0 * N * (d + dff) * s + 2 * d * dff * 4.0 + 2.0 * N * d * s + 4.0 * N * d * s + 4 * d * d * 4.0),
+        "scan_bytes": S * s * (1 + (1 if w.loss_every_state else 0)) + iters * S * s * (streams_in + 1),
+        "scan_launches": 1 + iters,
+    }
+
+
 def gpu_errors(B, torch, p, ks, gamma=None):
     """Relative L2 error and cosine of the k-iteration estimate against exact BP,
     both from the GPU library, for states 0..L-1 and for all parameter gradients."""
@@ -142,14 +180,14 @@ def gpu_errors(B, torch, p, ks, gamma=None):
     torch.cuda.synchronize()
     L = p.g.shape[0] - 1
     G = p.g[:-1].clone()
-    PG = [t.clone() for t in (p.dW1, p.dW2, p.dU) if t is not None]
+    PG = [t.clone() for t in (p.dW1, p.dW2, p.dU, p.dWqkv, p.dWo) if t is not None]
     out = {}
     for k in ks:
         B.hbp_backward(p, k, gamma=gamma)
         B.hbp_param_grads(p)
         torch.cuda.synchronize()
         s_rel, s_cos = figures([p.g[l] for l in range(L)], [G[l] for l in range(L)])
-        pg = [t for t in (p.dW1, p.dW2, p.dU) if t is not None]
+        pg = [t for t in (p.dW1, p.dW2, p.dU, p.dWqkv, p.dWo) if t is not None]
         if pg[0].dim() == 3:    # per-layer slabs
             est = [t[l] for t in pg for l in range(t.shape[0])]
             ref = [t[l] for t in PG for l in range(t.shape[0])]
@@ -207,14 +245,17 @@ def cpu_baseline(w, k, budget_tokens):
         threads = os.cpu_count() or 1
     n = min(budget_tokens, w.N)
     inp = synth.make_inputs(w, tokens=slice(0, n))
-    if w.kind in ("gated", "lstm", "gru"):
+    if w.kind == "transformer":      # n is a whole number of sequences
+        st = O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], eps=w.eps, Wqkv=inp["Wqkv"],
+                     Wo=inp["Wo"], T=w.seq_len, heads=w.heads, causal=w.causal)
+    elif w.kind in ("gated", "lstm", "gru"):
         st = O.Stack(w.kind, w.act, w.norm, inp["W1"], None, U=inp["U"], L=w.L)
     else:
         st = O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], U=inp["U"], eps=w.eps, L=w.L,
                      post=w.post)
     sv = O.forward(st, inp["x0"], inp["xin"])
     t0 = time.perf_counter()
-    g = O.hbp_backward(st, sv, inp["e"], k)
+    g = O.hbp_backward(st, sv, inp["e"], k, gamma=w.gamma)
     O.param_grads(st, sv, g, inp["xin"])
     dt = time.perf_counter() - t0
     toks = n * (w.L if w.kind in ("rnn", "gated", "lstm", "gru") else 1)
@@ -315,7 +356,7 @@ def main():
                 "ms_per_step": ms[cls], "launches_per_step": launches[cls],
                 "avg_launch_ms": ms[cls] / max(launches[cls], 1)}
 
-    roofs = {c: mfma_roof(c) for c in ("vjp1", "vjp2", "dw")}
+    roofs = {c: mfma_roof(c) for c in ("vjp1", "vjp2", "dw") + (("attn",) if w.kind == "transformer" else ())}
     if w.kind in ("gated", "lstm", "gru"):   # step (i)'s first half is elementwise there (GRU: plus an H x H product): memory roofline
         t1 = ms["vjp1"] * 1e-3
         a1 = work["vjp1_bytes"] / t1 / 1e9 if t1 > 0 else 0.0
@@ -330,7 +371,7 @@ def main():
                      "kernel_class": "scan",
                      "ms_per_step": ms["scan"], "launches_per_step": launches["scan"],
                      "avg_launch_ms": ms["scan"] / max(launches["scan"], 1)}
-    dominant = max(("vjp1", "vjp2", "dw", "scan"), key=lambda c: ms[c])
+    dominant = max([c for c in ("vjp1", "vjp2", "dw", "scan", "attn") if c in roofs], key=lambda c: ms[c])
 
     out = {
         "metric": "Highway-BP backward tokens/s (hbp_backward(k) + hbp_param_grads)",
@@ -338,7 +379,8 @@ def main():
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "k": k, "L": w.L, "tokens": tokens, "d": w.d, "d_ff": w.d_ff,
-                   "kind": w.kind, "norm": w.norm, "act": w.act},
+                   "kind": w.kind, "norm": w.norm, "act": w.act, "gamma": w.gamma,
+                   **({"seq_len": w.seq_len, "heads": w.heads, "causal": w.causal} if w.kind == "transformer" else {})},
         "roofline": roofs[dominant],
         "roofline_by_class": roofs,
         "class_ms_per_step": ms,
@@ -437,7 +479,8 @@ def main():
         # about 10-20 s of oracle work on the GPU machine's host cores
         n = args.cpu_tokens or {"mlp_small_f32": 128, "resnet_like": 8192, "resnet_postact": 8192, "postnorm_mlp": 2048, "transformer_mlp": 2048,
                                 "deep_large": 256, "gated_rnn": 16, "gated_rnn_contractive": 16,
-                                "gated_rnn_token_gates": 16, "gru_cell": 16, "gru_std_cell": 12, "lstm_cell": 8}.get(w.name, 64)
+                                "gated_rnn_token_gates": 16, "gru_cell": 16, "gru_std_cell": 12, "lstm_cell": 8,
+                                "gpt2_paper": 16 * 256, "transformer_attn": 1024}.get(w.name, 64)
         out["cpu_baseline"] = cpu_baseline(w, k, n)
 
     def finite(o):   # JSON has no NaN/Infinity: overflowed error figures become null

@@ -359,7 +359,8 @@ def allocate(w, inputs, device="cuda:0", N: Optional[int] = None) -> Problem:
     desc = make_desc(w.kind, w.dtype, w.act, w.norm, w.L, N, w.d, w.d_ff, w.d_in,
                      lambda_channel=lam is not None and not per_token, lambda_token=per_token,
                      loss_every_state=w.loss_every_state, eps=w.eps, post=getattr(w, "post", "none"),
-                     heads=getattr(w, "heads", 0), causal=getattr(w, "causal", True), seq_len=getattr(w, "seq_len", 0))
+                     heads=getattr(w, "heads", 0), causal=getattr(w, "causal", True), seq_len=getattr(w, "seq_len", 0),
+                     gamma=getattr(w, "gamma", 0.0))
     L, d, dff = w.L, w.d, w.d_ff
     tfm = w.kind == "transformer"
     Li = L // 2 if tfm else L        # rows of the inner state: one per MLP block

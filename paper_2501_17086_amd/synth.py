@@ -91,12 +91,12 @@ WORKLOADS: Dict[str, Workload] = {
 }
 # The paper's GPT-2 configuration (appendix, hyperparameter table: 12 layers, hidden 256, context 256, batch 128;
 # every layer split into attention and feed-forward sub-layers, L = 24; run with gamma = 0.2), with RMS norm and no
-# biases, and a larger stack of the same kind (24 layers of width 1024, 16 sequences of 1024 tokens).
+# biases, and a larger stack of the same kind (12 layers of width 1024, 16 heads, 16 sequences of 1024 tokens).
 WORKLOADS["gpt2_paper"] = Workload("gpt2_paper", "transformer", "bf16", "gelu", "rms", L=24, N=128 * 256, d=256,
                                    d_ff=1024, w1_std=0.02, w2_std=0.02, w2_scale=1.0 / np.sqrt(24.0), heads=4,
                                    seq_len=256, causal=True, gamma=0.2, ks=(1, 2, 3))
-WORKLOADS["transformer_attn"] = Workload("transformer_attn", "transformer", "bf16", "gelu", "rms", L=48, N=16 * 1024,
-                                         d=1024, d_ff=4096, w1_std=0.02, w2_std=0.02, w2_scale=1.0 / np.sqrt(48.0),
+WORKLOADS["transformer_attn"] = Workload("transformer_attn", "transformer", "bf16", "gelu", "rms", L=24, N=16 * 1024,
+                                         d=1024, d_ff=4096, w1_std=0.02, w2_std=0.02, w2_scale=1.0 / np.sqrt(24.0),
                                          heads=16, seq_len=1024, causal=True, gamma=0.2, ks=(1, 2, 3))
 # contractive variant of the RNN (recurrent weights x 0.25): the stack as
 # specified is chaotic, so exact BPTT gradients overflow over 4096 steps.

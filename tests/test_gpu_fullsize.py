@@ -32,8 +32,12 @@ def B():
     return binding
 
 
-def _sample_rows(n, count, seed):
+def _sample_rows(n, count, seed, seq_len=0):
+    """Token rows the oracle recomputes; with seq_len > 0 whole sequences (attention couples a sequence's tokens)."""
     r = np.random.default_rng(seed)
+    if seq_len:
+        seqs = np.unique(np.concatenate([[n // seq_len - 1], r.integers(0, n // seq_len, size=count)]))
+        return (seqs[:, None] * seq_len + np.arange(seq_len)[None, :]).reshape(-1)
     rows = np.unique(np.concatenate([[0, n - 1], r.integers(0, n, size=count)]))
     return rows
 
@@ -57,6 +61,23 @@ def _projection_check(p, w, inp, tol):
         err = float((got - want).norm() / want.norm())
         assert err < tol, f"{w.name}: {name} projection {err:.3e}"
 
+    if w.kind == "transformer":
+        # three layers; the gradient of [q | k | v] by torch's autograd through torch's own attention, in fp64, on the
+        # library's saved q, k, v and its do = g Wo
+        Bn, T, Hn, d = w.N // w.seq_len, w.seq_len, w.heads, w.d
+        for j in sorted({0, L // 4, L // 2 - 1}):
+            gm, zl, ym = p.g[2 * j + 2].double(), p.z[j].double(), p.y[2 * j + 1].double()
+            da = (gm @ p.W2[j].double()) * p.dphi[j].double()
+            check(f"dW2[{j}]", p.dW2[j], gm, zl)
+            check(f"dW1[{j}]", p.dW1[j], da, ym)
+            ga, ya = p.g[2 * j + 1].double(), p.y[2 * j].double()
+            check(f"dWo[{j}]", p.dWo[j], ga, p.attn_o[j].double())
+            qkv = p.qkv[j].double().reshape(Bn, T, 3, Hn, d // Hn).permute(2, 0, 3, 1, 4).clone().requires_grad_(True)
+            o = torch.nn.functional.scaled_dot_product_attention(qkv[0], qkv[1], qkv[2], is_causal=w.causal)
+            o.backward((ga @ p.Wo[j].double()).reshape(Bn, T, Hn, d // Hn).permute(0, 2, 1, 3))
+            dqkv = qkv.grad.permute(1, 3, 0, 2, 4).reshape(Bn * T, 3 * d)
+            check(f"dWqkv[{j}]", p.dWqkv[j], dqkv, ya)
+        return
     if w.kind == "mlp":
         for l in sorted({0, L // 2, L - 1}):
             gl, zl = p.g[l + 1].double(), p.z[l].double()
@@ -105,7 +126,7 @@ def _run(B, w, ks, rows_count, shared_state=False, check_exact=True):
     p = B.allocate(w, inp)
     B.hbp_forward(p)
     torch.cuda.synchronize()
-    rows = _sample_rows(w.N, rows_count, 3)
+    rows = _sample_rows(w.N, rows_count, 3, w.seq_len if w.kind == "transformer" else 0)
     sub = _subset(w, inp, rows)
     st = H.oracle_stack(w, sub)
     sv = O.forward(st, sub["x0"], sub["xin"])
@@ -125,7 +146,7 @@ def _run(B, w, ks, rows_count, shared_state=False, check_exact=True):
         B.hbp_backward(p, k)
         B.hbp_param_grads(p)
         torch.cuda.synchronize()
-        want = H.as_kept(st, sv, O.hbp_backward(st, sv, sub["e"], k))
+        want = H.as_kept(st, sv, O.hbp_backward(st, sv, sub["e"], k, gamma=w.gamma))
         got = H.to_np(p.g[:, rows_t])
         H.assert_close(got, want, tol, f"{w.name} k={k}: g on {len(rows)} sampled rows")
         _projection_check(p, w, inp, 5e-3)
@@ -151,10 +172,10 @@ def _run_cut(B, w, ks):
         B.hbp_backward(p, k)
         B.hbp_param_grads(p)
         torch.cuda.synchronize()
-        want = O.hbp_backward(st, sv, inp["e"], k)
+        want = O.hbp_backward(st, sv, inp["e"], k, gamma=w.gamma)
         H.assert_close(H.to_np(p.g), want, tol, f"{w.name} k={k}: g")
         pg = O.param_grads(st, sv, want, inp["xin"])
-        for nm, t in (("dW1", p.dW1), ("dW2", p.dW2), ("dU", p.dU)):
+        for nm, t in (("dW1", p.dW1), ("dW2", p.dW2), ("dU", p.dU), ("dWqkv", p.dWqkv), ("dWo", p.dWo)):
             if t is not None:
                 H.assert_close(H.to_np(t), pg[nm], tol, f"{w.name} k={k}: {nm}", row_floor=0.5)
     del p
@@ -186,6 +207,25 @@ def test_gru_std_cell_cut_to_2_rows_every_element(B):
 @pytest.mark.timeout(300)
 def test_lstm_cell_cut_to_2_rows_every_element(B):
     _run_cut(B, synth.scaled(W["lstm_cell"], name="lstm_cell_2rows", N=2), ks=(2,))
+
+
+@pytest.mark.timeout(300)
+def test_gpt2_paper_cut_to_8_sequences_every_element(B):
+    # 12 layers = 24 sub-blocks at width 256, 4 heads, context 256, gamma = 0.2; 8 of the 128 sequences
+    _run_cut(B, synth.scaled(W["gpt2_paper"], name="gpt2_paper_8seq", N=8 * 256), ks=(1, 3))
+
+
+@pytest.mark.timeout(300)
+def test_gpt2_paper_full(B):
+    # the paper's GPT-2 configuration whole (128 sequences of 256 tokens); the oracle recomputes the last sequence and
+    # three others
+    _run(B, W["gpt2_paper"], ks=(1, 3), rows_count=3)
+
+
+@pytest.mark.timeout(300)
+def test_transformer_attn_full(B):
+    # 12 layers = 24 sub-blocks at width 1024, 16 heads, 16 sequences of 1024 tokens; the oracle recomputes the last one
+    _run(B, W["transformer_attn"], ks=(1,), rows_count=0, check_exact=False)
 
 
 @pytest.mark.timeout(300)

@@ -256,7 +256,7 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
         B.hbp_backward(p, k)
         B.hbp_param_grads(p)
         torch.cuda.synchronize()
-        compare(f"k={k}", O.hbp_backward(st, sv_oracle, inp["e"], k))
+        compare(f"k={k}", O.hbp_backward(st, sv_oracle, inp["e"], k, gamma=w.gamma))   # the workload's own split
     if not exact:
         return
     B.hbp_exact_backward(p)
