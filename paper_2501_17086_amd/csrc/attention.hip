@@ -18,6 +18,8 @@
 // Everything else (fp32 storage, other head widths) takes plain one-wavefront-per-query (per-key) kernels.
 #include "hbp_common.h"
 
+#include <type_traits>
+
 namespace hbp {
 
 namespace {
@@ -169,6 +171,7 @@ __device__ __forceinline__ float16v mfma(bf16x8 x, bf16x8 y, float16v acc) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(x, y, acc, 0, 0, 0);
 }
 __device__ __forceinline__ int tile_row_of(int r, int hh) { return 8 * (r >> 2) + 4 * hh + (r & 3); }
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }   // v_exp_f32: exp2(-inf) = 0
 
 // A wavefront's LDS tile: 32 rows x 64 bf16 (128-byte rows), 16-byte chunk c of row r at chunk c ^ ((r >> 1) & 7).
 __device__ __forceinline__ int swz(int r) { return (r >> 1) & 7; }
@@ -181,15 +184,30 @@ __device__ __forceinline__ void lds_handover() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// rows r0 .. r0+31 (rows at or past rmax read row rmax-1) x 64 columns from memory into the tile
-__device__ __forceinline__ void tile_to_lds(const bf16_t* base, long ld, int r0, int rmax, unsigned char* tile, int lane) {
+// Addresses: a wavefront-uniform pointer to row 0 of the 32-row tile plus one 32-bit byte offset per lane, which is
+// the same for every whole tile (LaneOffsets, computed once); a tile that runs past the last row re-reads that row
+// instead (CLAMP: rows_left < 32 rows are there).
+struct LaneOffsets {
+  unsigned frag;       // fragment loads: row l % 32, 16 bytes at column 8 (l / 32)  (+ 32 bytes per step kk)
+  unsigned tile;       // tile loads: row l / 8 (+ 8 rows per load), 16-byte chunk l % 8
+  unsigned ldb;        // row stride in bytes
+};
+__device__ __forceinline__ LaneOffsets lane_offsets(unsigned ldb, int lane) {
+  LaneOffsets o;
+  o.ldb = ldb;
+  o.frag = (unsigned)(lane & 31) * ldb + (unsigned)(lane >> 5) * 16u;
+  o.tile = (unsigned)(lane >> 3) * ldb + (unsigned)(lane & 7) * 16u;
+  return o;
+}
+template <bool CLAMP>
+__device__ __forceinline__ void tile_to_lds(const unsigned char* base, const LaneOffsets& lo, int rows_left,
+                                            unsigned char* tile, int lane) {
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
-    const int id = lane + 64 * u;
-    const int r = id >> 3, ch = id & 7;
-    int rr = r0 + r;
-    rr = rr < rmax ? rr : rmax - 1;
-    const uint4 v = *reinterpret_cast<const uint4*>(base + (long)rr * ld + 8 * ch);
+    const int r = (lane >> 3) + 8 * u, ch = lane & 7;
+    unsigned off = lo.tile + (unsigned)(8 * u) * lo.ldb;
+    if (CLAMP) off = (unsigned)(r < rows_left ? r : rows_left - 1) * lo.ldb + (unsigned)ch * 16u;
+    const uint4 v = *reinterpret_cast<const uint4*>(base + off);
     *reinterpret_cast<uint4*>(tile + r * 128 + ((ch ^ swz(r)) << 4)) = v;
   }
   lds_handover();
@@ -200,10 +218,15 @@ __device__ __forceinline__ bf16x8 frag_cols_lds(const unsigned char* tile, int k
   return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(tile + r * 128 + ((ch ^ swz(r)) << 4)));
 }
 // the same straight from memory
-__device__ __forceinline__ bf16x8 frag_cols_mem(const bf16_t* base, long ld, int r0, int rmax, int kk, int lane) {
-  int rr = r0 + (lane & 31);
-  rr = rr < rmax ? rr : rmax - 1;
-  return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + (long)rr * ld + 16 * kk + 8 * (lane >> 5)));
+template <bool CLAMP>
+__device__ __forceinline__ bf16x8 frag_cols_mem(const unsigned char* base, const LaneOffsets& lo, int rows_left, int kk,
+                                                int lane) {
+  unsigned off = lo.frag;
+  if (CLAMP) {
+    const int r = lane & 31;
+    off = (unsigned)(r < rows_left ? r : rows_left - 1) * lo.ldb + (unsigned)(lane >> 5) * 16u;
+  }
+  return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(base + off + 32u * kk));
 }
 // operand fragment with the contraction along the tile's ROWS, in the order the accumulator of the first product
 // holds them: lane holds column 32 m + l % 32; its element i of step t is tile row 16 t + 8 (i/4) + 4 (l/32) + i%4
@@ -237,69 +260,93 @@ __device__ __forceinline__ void store_row(bf16_t* row, const float16v& a0, const
     store4b(row + 32 + 8 * g + 4 * hh, a1[4 * g] * f, a1[4 * g + 1] * f, a1[4 * g + 2] * f, a1[4 * g + 3] * f);
   }
 }
+__device__ __forceinline__ float dot8(bf16x8 a, bf16x8 b) {
+  const uint4 x = __builtin_bit_cast(uint4, a), y = __builtin_bit_cast(uint4, b);
+  const unsigned xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+  float acc = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    acc = fmaf(__uint_as_float(xs[i] << 16), __uint_as_float(ys[i] << 16), acc);
+    acc = fmaf(__uint_as_float(xs[i] & 0xFFFF0000u), __uint_as_float(ys[i] & 0xFFFF0000u), acc);
+  }
+  return acc;
+}
 
 constexpr int AT_WAVES = 4;    // wavefronts (tiles) per workgroup
 
-struct HeadPtrs {
-  const bf16_t* q; const bf16_t* k; const bf16_t* v;   // row t of the head at + t * ld
-  long ld, d, tok0; int h;
+// One (sequence, head): wavefront-uniform byte pointers to row 0 of q, k, v (row stride 6 d bytes) and of the
+// d-wide arrays (row stride 2 d bytes), all at the head's 64 columns.
+struct Head {
+  const unsigned char* q; const unsigned char* k; const unsigned char* v;
+  long wide_off;         // byte offset of row 0 of the head in a [tokens, d] array
+  long tok0, d, ld;
+  unsigned h;
 };
-__device__ __forceinline__ HeadPtrs head_ptrs(const AttnArgs& a, long p) {
-  HeadPtrs hp;
-  hp.h = (int)(p % a.heads);
-  const long seq = p / a.heads;
-  hp.d = (long)a.heads * 64;
-  hp.ld = 3 * hp.d;
-  hp.tok0 = seq * a.T;
-  hp.q = reinterpret_cast<const bf16_t*>(a.qkv) + hp.tok0 * hp.ld + (long)hp.h * 64;
-  hp.k = hp.q + hp.d;
-  hp.v = hp.k + hp.d;
-  return hp;
+__device__ __forceinline__ Head head_of(const AttnArgs& a, unsigned p) {
+  Head hd;
+  const unsigned heads = (unsigned)a.heads;
+  hd.h = p % heads;
+  const unsigned seq = p / heads;
+  hd.d = (long)heads * 64;
+  hd.ld = 3 * hd.d;
+  hd.tok0 = (long)seq * a.T;
+  hd.q = reinterpret_cast<const unsigned char*>(a.qkv) + (hd.tok0 * hd.ld + (long)hd.h * 64) * 2;
+  hd.k = hd.q + hd.d * 2;
+  hd.v = hd.k + hd.d * 2;
+  hd.wide_off = (hd.tok0 * hd.d + (long)hd.h * 64) * 2;
+  return hd;
 }
 
 template <bool CAUSAL>
 __global__ __launch_bounds__(64 * AT_WAVES) void attn_fwd_mfma_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[AT_WAVES][4096];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hh = lane >> 5;
-  const int T = (int)a.T, nt = (T + 31) / 32;
+  const int lane = threadIdx.x & 63, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int T = (int)a.T, nt = (T + 31) >> 5;
   const int qt = nt - 1 - ((int)blockIdx.y * AT_WAVES + wave);     // long rows first
   if (qt < 0) return;
-  const long p = blockIdx.x;
-  const HeadPtrs hp = head_ptrs(a, p);
+  const unsigned p = blockIdx.x;
+  const Head hd = head_of(a, p);
+  const LaneOffsets lo = lane_offsets((unsigned)(hd.ld * 2), lane);
   unsigned char* tile = smem[wave];
   const int q0 = 32 * qt, qi = q0 + (lane & 31);
   const float c = a.scale * LOG2E;
   bf16x8 fq[4];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) fq[kk] = frag_cols_mem(hp.q, hp.ld, q0, T, kk, lane);
+  for (int kk = 0; kk < 4; ++kk) fq[kk] = frag_cols_mem<true>(hd.q + (long)q0 * lo.ldb, lo, T - q0, kk, lane);
   float16v o0, o1;
 #pragma unroll
   for (int r = 0; r < 16; ++r) { o0[r] = 0.f; o1[r] = 0.f; }
   float m = -INFINITY, l = 0.f;
   const int nkt = CAUSAL ? qt + 1 : nt;
-  for (int kt = 0; kt < nkt; ++kt) {
+  // one tile of 32 keys; MASKED: the tile on the diagonal (causal) or the one that runs past the last key
+  auto step = [&](int kt, auto masked_c) __attribute__((always_inline)) {
+    constexpr bool MASKED = decltype(masked_c)::value;
     const int k0 = 32 * kt;
-    tile_to_lds(hp.v, hp.ld, k0, T, tile, lane);
+    const unsigned char* kb = hd.k + (long)k0 * lo.ldb;
+    tile_to_lds<MASKED>(kb + hd.d * 2, lo, T - k0, tile, lane);
     float16v s;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) s = mfma(frag_cols_mem(hp.k, hp.ld, k0, T, kk, lane), fq[kk], s);
+    for (int kk = 0; kk < 4; ++kk) s = mfma(frag_cols_mem<MASKED>(kb, lo, T - k0, kk, lane), fq[kk], s);
     float sv[16];
     float tmax = -INFINITY;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int kj = k0 + tile_row_of(r, hh);
-      const bool ok = kj < T && (!CAUSAL || kj <= qi);
-      sv[r] = ok ? s[r] * c : -INFINITY;
+      sv[r] = s[r] * c;
+      if (MASKED) {
+        const int kj = k0 + tile_row_of(r, hh);
+        if (!(CAUSAL ? kj <= qi : kj < T)) sv[r] = -INFINITY;
+      }
       tmax = fmaxf(tmax, sv[r]);
     }
     tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
     const float mn = fmaxf(m, tmax);          // finite: every tile has a key its queries may see
-    const float alpha = exp2f(m - mn);
+    const float alpha = fast_exp2(m - mn);
     float ps = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { sv[r] = exp2f(sv[r] - mn); ps += sv[r]; }
+    for (int r = 0; r < 16; ++r) { sv[r] = fast_exp2(sv[r] - mn); ps += sv[r]; }
     ps += __shfl_xor(ps, 32, 64);
     l = l * alpha + ps;
     m = mn;
@@ -311,78 +358,75 @@ __global__ __launch_bounds__(64 * AT_WAVES) void attn_fwd_mfma_kernel(AttnArgs a
     o1 = mfma(frag_rows_lds(tile, 1, 0, lane), p0, o1);
     o1 = mfma(frag_rows_lds(tile, 1, 1, lane), p1, o1);
     lds_handover();
-  }
+  };
+  const int n_plain = CAUSAL ? nkt - 1 : (T & 31 ? nkt - 1 : nkt);
+  for (int kt = 0; kt < n_plain; ++kt) step(kt, std::false_type());
+  if (n_plain < nkt) step(nkt - 1, std::true_type());
   if (qi < T) {
-    store_row(reinterpret_cast<bf16_t*>(a.o) + (hp.tok0 + qi) * hp.d + (long)hp.h * 64, o0, o1, 1.f / l, hh);
-    if (hh == 0) a.lse[p * a.T + qi] = m + log2f(l);
+    store_row(reinterpret_cast<bf16_t*>(reinterpret_cast<unsigned char*>(a.o) + hd.wide_off) + (long)qi * hd.d, o0, o1,
+              1.f / l, hh);
+    if (hh == 0) a.lse[(long)p * a.T + qi] = m + log2f(l);
   }
 }
 
-// D[p][t] = sum_c do[t][c] o[t][c] over the head's 64 columns: one thread per (token, head)
-__global__ __launch_bounds__(256) void attn_dsum_kernel(AttnArgs a, long total) {
-  const long i = (long)blockIdx.x * 256 + threadIdx.x;    // token * heads + head
-  if (i >= total) return;
-  const int h = (int)(i % a.heads);
-  const long tok = i / a.heads;
-  const long d = (long)a.heads * 64;
-  const bf16_t* x = reinterpret_cast<const bf16_t*>(a.dout) + tok * d + (long)h * 64;
-  const bf16_t* y = reinterpret_cast<const bf16_t*>(a.o) + tok * d + (long)h * 64;
-  float acc = 0.f;
-#pragma unroll
-  for (int u = 0; u < 8; ++u) {
-    float xa[8], ya[8];
-    load8(x + 8 * u, xa);
-    load8(y + 8 * u, ya);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc = fmaf(xa[j], ya[j], acc);
-  }
-  const long seq = tok / a.T;
-  a.dsum[(seq * a.heads + h) * a.T + tok % a.T] = acc;
-}
-
+// dq of a tile of 32 queries; also leaves D = rowsum(do (.) o) of its queries for the dk/dv kernel
 template <bool CAUSAL>
 __global__ __launch_bounds__(64 * AT_WAVES) void attn_bwd_q_mfma_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[AT_WAVES][4096];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hh = lane >> 5;
-  const int T = (int)a.T, nt = (T + 31) / 32;
+  const int lane = threadIdx.x & 63, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int T = (int)a.T, nt = (T + 31) >> 5;
   const int qt = nt - 1 - ((int)blockIdx.y * AT_WAVES + wave);
   if (qt < 0) return;
-  const long p = blockIdx.x;
-  const HeadPtrs hp = head_ptrs(a, p);
-  const bf16_t* dob = reinterpret_cast<const bf16_t*>(a.dout) + hp.tok0 * hp.d + (long)hp.h * 64;
+  const unsigned p = blockIdx.x;
+  const Head hd = head_of(a, p);
+  const LaneOffsets lo = lane_offsets((unsigned)(hd.ld * 2), lane);
+  const LaneOffsets lw = lane_offsets((unsigned)(hd.d * 2), lane);
   unsigned char* tile = smem[wave];
   const int q0 = 32 * qt, qi = q0 + (lane & 31);
   const int qc = qi < T ? qi : T - 1;
   const float c = a.scale * LOG2E;
-  const float L2 = a.lse[p * a.T + qc], D = a.dsum[p * a.T + qc];
+  const float L2 = a.lse[(long)p * a.T + qc];
   bf16x8 fq[4], fdo[4];
+  float D = 0.f;
+  {
+    const unsigned char* dob = reinterpret_cast<const unsigned char*>(a.dout) + hd.wide_off + (long)q0 * lw.ldb;
+    const unsigned char* ob = reinterpret_cast<const unsigned char*>(a.o) + hd.wide_off + (long)q0 * lw.ldb;
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    fq[kk] = frag_cols_mem(hp.q, hp.ld, q0, T, kk, lane);
-    fdo[kk] = frag_cols_mem(dob, hp.d, q0, T, kk, lane);
+    for (int kk = 0; kk < 4; ++kk) {
+      fq[kk] = frag_cols_mem<true>(hd.q + (long)q0 * lo.ldb, lo, T - q0, kk, lane);
+      fdo[kk] = frag_cols_mem<true>(dob, lw, T - q0, kk, lane);
+      D += dot8(fdo[kk], frag_cols_mem<true>(ob, lw, T - q0, kk, lane));
+    }
+    D += __shfl_xor(D, 32, 64);
+    if (hh == 0 && qi < T) a.dsum[(long)p * a.T + qi] = D;
   }
   float16v dq0, dq1;
 #pragma unroll
   for (int r = 0; r < 16; ++r) { dq0[r] = 0.f; dq1[r] = 0.f; }
   const int nkt = CAUSAL ? qt + 1 : nt;
-  for (int kt = 0; kt < nkt; ++kt) {
+  auto step = [&](int kt, auto masked_c) __attribute__((always_inline)) {
+    constexpr bool MASKED = decltype(masked_c)::value;
     const int k0 = 32 * kt;
-    tile_to_lds(hp.k, hp.ld, k0, T, tile, lane);
+    const unsigned char* kb = hd.k + (long)k0 * lo.ldb;
+    tile_to_lds<MASKED>(kb, lo, T - k0, tile, lane);
     float16v s, dp;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+    for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = -D; }      // dp comes out as dP - D
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       s = mfma(frag_cols_lds(tile, kk, lane), fq[kk], s);
-      dp = mfma(frag_cols_mem(hp.v, hp.ld, k0, T, kk, lane), fdo[kk], dp);
+      dp = mfma(frag_cols_mem<MASKED>(kb + hd.d * 2, lo, T - k0, kk, lane), fdo[kk], dp);
     }
     float ds[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int kj = k0 + tile_row_of(r, hh);
-      const bool ok = kj < T && (!CAUSAL || kj <= qi);
-      const float pr = ok ? exp2f(s[r] * c - L2) : 0.f;
-      ds[r] = pr * (dp[r] - D);
+      float pr = fast_exp2(fmaf(s[r], c, -L2));
+      if (MASKED) {
+        const int kj = k0 + tile_row_of(r, hh);
+        if (!(CAUSAL ? kj <= qi : kj < T)) pr = 0.f;
+      }
+      ds[r] = pr * dp[r];
     }
     const bf16x8 d0 = pack8(ds), d1 = pack8(ds + 8);
     dq0 = mfma(frag_rows_lds(tile, 0, 0, lane), d0, dq0);
@@ -390,43 +434,66 @@ __global__ __launch_bounds__(64 * AT_WAVES) void attn_bwd_q_mfma_kernel(AttnArgs
     dq1 = mfma(frag_rows_lds(tile, 1, 0, lane), d0, dq1);
     dq1 = mfma(frag_rows_lds(tile, 1, 1, lane), d1, dq1);
     lds_handover();
-  }
+  };
+  const int n_plain = CAUSAL ? nkt - 1 : (T & 31 ? nkt - 1 : nkt);
+  for (int kt = 0; kt < n_plain; ++kt) step(kt, std::false_type());
+  if (n_plain < nkt) step(nkt - 1, std::true_type());
   if (qi < T)
-    store_row(reinterpret_cast<bf16_t*>(a.dqkv) + (hp.tok0 + qi) * hp.ld + (long)hp.h * 64, dq0, dq1, a.scale, hh);
+    store_row(reinterpret_cast<bf16_t*>(reinterpret_cast<unsigned char*>(a.dqkv) + (hd.q - reinterpret_cast<const unsigned char*>(a.qkv))) +
+                  (long)qi * hd.ld, dq0, dq1, a.scale, hh);
 }
 
+// dk, dv of a tile of 32 keys (after the dq kernel: reads D)
 template <bool CAUSAL>
 __global__ __launch_bounds__(64 * AT_WAVES) void attn_bwd_kv_mfma_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(16))) unsigned char smem[AT_WAVES][2][4096];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, hh = lane >> 5;
-  const int T = (int)a.T, nt = (T + 31) / 32;
+  __shared__ __attribute__((aligned(16))) float stats[AT_WAVES][64];
+  const int lane = threadIdx.x & 63, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int T = (int)a.T, nt = (T + 31) >> 5;
   const int kt = (int)blockIdx.y * AT_WAVES + wave;                // causal: early keys see the most queries
   if (kt >= nt) return;
-  const long p = blockIdx.x;
-  const HeadPtrs hp = head_ptrs(a, p);
-  const bf16_t* dob = reinterpret_cast<const bf16_t*>(a.dout) + hp.tok0 * hp.d + (long)hp.h * 64;
+  const unsigned p = blockIdx.x;
+  const Head hd = head_of(a, p);
+  const LaneOffsets lo = lane_offsets((unsigned)(hd.ld * 2), lane);
+  const LaneOffsets lw = lane_offsets((unsigned)(hd.d * 2), lane);
+  const unsigned char* dob = reinterpret_cast<const unsigned char*>(a.dout) + hd.wide_off;
   unsigned char* tq = smem[wave][0];
   unsigned char* td = smem[wave][1];
+  float* st = stats[wave];
   const int k0 = 32 * kt, kj = k0 + (lane & 31);
   const float c = a.scale * LOG2E;
-  const float* lse = a.lse + p * a.T;
-  const float* dsum = a.dsum + p * a.T;
+  // lanes 0..31 fetch the row statistic of query l of each tile, lanes 32..63 its D
+  const float* stat_src = (hh == 0 ? a.lse : a.dsum) + (long)p * a.T;
+  const float ninv_c = -1.0f / c;
   bf16x8 fk[4], fv[4];
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) {
-    fk[kk] = frag_cols_mem(hp.k, hp.ld, k0, T, kk, lane);
-    fv[kk] = frag_cols_mem(hp.v, hp.ld, k0, T, kk, lane);
+    fk[kk] = frag_cols_mem<true>(hd.k + (long)k0 * lo.ldb, lo, T - k0, kk, lane);
+    fv[kk] = frag_cols_mem<true>(hd.v + (long)k0 * lo.ldb, lo, T - k0, kk, lane);
   }
   float16v dk0, dk1, dv0, dv1;
 #pragma unroll
   for (int r = 0; r < 16; ++r) { dk0[r] = 0.f; dk1[r] = 0.f; dv0[r] = 0.f; dv1[r] = 0.f; }
-  for (int qt = CAUSAL ? kt : 0; qt < nt; ++qt) {
+  // one tile of 32 queries; MASKED: the tile on the diagonal (causal) or the one that runs past the last query
+  auto step = [&](int qt, auto masked_c) __attribute__((always_inline)) {
+    constexpr bool MASKED = decltype(masked_c)::value;
     const int q0 = 32 * qt;
-    tile_to_lds(hp.q, hp.ld, q0, T, tq, lane);
-    tile_to_lds(dob, hp.d, q0, T, td, lane);
+    {
+      const int r = lane & 31;
+      st[lane] = stat_src[q0 + ((!MASKED || r < T - q0) ? r : T - 1 - q0)];
+    }
+    tile_to_lds<MASKED>(hd.q + (long)q0 * lo.ldb, lo, T - q0, tq, lane);
+    tile_to_lds<MASKED>(dob + (long)q0 * lw.ldb, lw, T - q0, td, lane);
     float16v s, dp;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+    for (int g = 0; g < 4; ++g) {       // the statistics of the lane's 16 queries: rows 8 g + 4 hh .. + 3
+      const float4 a4 = *reinterpret_cast<const float4*>(st + 8 * g + 4 * hh);
+      const float4 d4 = *reinterpret_cast<const float4*>(st + 32 + 8 * g + 4 * hh);
+      // the products start from -L2 / c and -D: they come out as (s c - L2) / c and dP - D
+      s[4 * g] = a4.x * ninv_c; s[4 * g + 1] = a4.y * ninv_c; s[4 * g + 2] = a4.z * ninv_c; s[4 * g + 3] = a4.w * ninv_c;
+      dp[4 * g] = -d4.x; dp[4 * g + 1] = -d4.y; dp[4 * g + 2] = -d4.z; dp[4 * g + 3] = -d4.w;
+    }
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
       s = mfma(frag_cols_lds(tq, kk, lane), fk[kk], s);
@@ -435,11 +502,12 @@ __global__ __launch_bounds__(64 * AT_WAVES) void attn_bwd_kv_mfma_kernel(AttnArg
     float pr[16], ds[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const int qi = q0 + tile_row_of(r, hh);
-      const int qc = qi < T ? qi : T - 1;
-      const bool ok = qi < T && kj < T && (!CAUSAL || kj <= qi);
-      pr[r] = ok ? exp2f(s[r] * c - lse[qc]) : 0.f;
-      ds[r] = pr[r] * (dp[r] - dsum[qc]);
+      pr[r] = fast_exp2(s[r] * c);
+      if (MASKED) {
+        const int qi = q0 + tile_row_of(r, hh);
+        if (!(qi < T && (!CAUSAL || kj <= qi))) pr[r] = 0.f;
+      }
+      ds[r] = pr[r] * dp[r];
     }
     const bf16x8 p0 = pack8(pr), p1 = pack8(pr + 8), d0 = pack8(ds), d1 = pack8(ds + 8);
     dv0 = mfma(frag_rows_lds(td, 0, 0, lane), p0, dv0);
@@ -451,11 +519,21 @@ __global__ __launch_bounds__(64 * AT_WAVES) void attn_bwd_kv_mfma_kernel(AttnArg
     dk1 = mfma(frag_rows_lds(tq, 1, 0, lane), d0, dk1);
     dk1 = mfma(frag_rows_lds(tq, 1, 1, lane), d1, dk1);
     lds_handover();
+  };
+  const bool ragged = (T & 31) != 0;
+  int qt = CAUSAL ? kt : 0;
+  if (CAUSAL) {                                  // the diagonal tile first
+    step(qt, std::true_type());
+    ++qt;
   }
+  const int n_plain = ragged ? nt - 1 : nt;
+  for (; qt < n_plain; ++qt) step(qt, std::false_type());
+  if (qt < nt) step(qt, std::true_type());       // the ragged last tile (unless it was the diagonal one)
   if (kj < T) {
-    bf16_t* row = reinterpret_cast<bf16_t*>(a.dqkv) + (hp.tok0 + kj) * hp.ld + hp.d + (long)hp.h * 64;
+    bf16_t* row = reinterpret_cast<bf16_t*>(reinterpret_cast<unsigned char*>(a.dqkv) + (hd.k - reinterpret_cast<const unsigned char*>(a.qkv))) +
+                  (long)kj * hd.ld;
     store_row(row, dk0, dk1, a.scale, hh);
-    store_row(row + hp.d, dv0, dv1, 1.f, hh);
+    store_row(row + hd.d, dv0, dv1, 1.f, hh);
   }
 }
 
@@ -487,8 +565,6 @@ hipError_t launch_attn_fwd(int dtype, const AttnArgs& a, hipStream_t s) {
 hipError_t launch_attn_bwd(int dtype, const AttnArgs& a, hipStream_t s) {
   const long P = a.seqs * a.heads;
   if (use_mfma(dtype, a)) {
-    const long total = a.seqs * a.T * a.heads;
-    hipLaunchKernelGGL(attn_dsum_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a, total);
     const dim3 grid((unsigned)P, (unsigned)(((a.T + 31) / 32 + AT_WAVES - 1) / AT_WAVES)), block(64 * AT_WAVES);
     if (a.causal) {
       hipLaunchKernelGGL(attn_bwd_q_mfma_kernel<true>, grid, block, 0, s, a);
