@@ -4,15 +4,18 @@
 // dk = dS^T q / sqrt(dh).  P is never stored: the forward keeps one number per (head, query), the base-2 logarithm of
 // the row's sum of exp2(s log2 e), and the backward kernels rebuild P tile by tile from q and k.
 //
-// bf16 storage with dh = 64 runs on the matrix cores (v_mfma_f32_32x32x16_bf16), one wavefront per tile of 32 queries
-// (forward, dq) or 32 keys (dk, dv), no communication between wavefronts:
+// bf16 storage with dh = 64 runs on the matrix cores (v_mfma_f32_32x32x16_bf16).  A workgroup of four wavefronts owns
+// four tiles of 32 queries (forward, dq) or 32 keys (dk, dv), one per wavefront, and streams the other side's tiles
+// through a ring of LDS buffers that all four read:
 //   - the MFMA is issued so that a lane owns one query (dk/dv kernel: one key) and its 16 accumulator registers run
-//     over 16 of the tile's 32 keys (queries): row statistics, the running rescale of the output and the factor
-//     dP - D are per-lane scalars;
+//     over 16 of the streamed tile's 32 keys (queries): row statistics, the running rescale of the output and the
+//     factor dP - D are per-lane scalars (D and the row statistic enter as the accumulators' start values);
 //   - the scores of a lane, rounded to bf16, are fed back as the second product's operand straight from the
 //     registers: the contraction index of an MFMA is a dummy, so it is enough that the other operand is fetched
-//     in the same (permuted) order of keys, which the transposing LDS read ds_read_b64_tr_b16 does from the v, k, q
-//     or do tile staged once per step in the wavefront's own 4 KB of LDS;
+//     in the same (permuted) order of keys, which the transposing LDS read ds_read_b64_tr_b16 does from the tile;
+//   - tiles reach LDS by direct copies (global_load_lds_dwordx4, no staging registers) issued three steps ahead, each
+//     wavefront copying a quarter of every tile; the loop holds no other global load, so a counted s_waitcnt tells a
+//     wavefront that its share of the next tile has landed, and one barrier per step completes the hand-over;
 //   - dq on one side and dk, dv on the other are two kernels that each rebuild S: seven products instead of five,
 //     no atomics, results bitwise repeatable.
 // Everything else (fp32 storage, other head widths) takes plain one-wavefront-per-query (per-key) kernels.
@@ -199,18 +202,84 @@ __device__ __forceinline__ LaneOffsets lane_offsets(unsigned ldb, int lane) {
   o.tile = (unsigned)(lane >> 3) * ldb + (unsigned)(lane & 7) * 16u;
   return o;
 }
-template <bool CLAMP>
-__device__ __forceinline__ void tile_to_lds(const unsigned char* base, const LaneOffsets& lo, int rows_left,
-                                            unsigned char* tile, int lane) {
+// Tiles reach LDS by direct copies (global_load_lds_dwordx4: 16 bytes per lane from memory to lds_base + 16 lane,
+// no staging registers), issued one step ahead into the other of two buffers.  A copy instruction fills 8 rows of
+// the tile; the chunk swizzle is applied on the memory side: LDS position (row r, slot c) receives chunk c ^ swz(r)
+// of the row.  The compiler sees neither the LDS write nor when it lands: copies_landed() comes before the reads.
+struct CopyOffsets { unsigned o[4]; };
+__device__ __forceinline__ CopyOffsets copy_offsets(unsigned ldb, int lane) {
+  CopyOffsets c;
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
-    const int r = (lane >> 3) + 8 * u, ch = lane & 7;
-    unsigned off = lo.tile + (unsigned)(8 * u) * lo.ldb;
-    if (CLAMP) off = (unsigned)(r < rows_left ? r : rows_left - 1) * lo.ldb + (unsigned)ch * 16u;
-    const uint4 v = *reinterpret_cast<const uint4*>(base + off);
-    *reinterpret_cast<uint4*>(tile + r * 128 + ((ch ^ swz(r)) << 4)) = v;
+    const int r = 8 * u + (lane >> 3);
+    c.o[u] = (unsigned)r * ldb + (unsigned)(((lane & 7) ^ swz(r)) << 4);
   }
-  lds_handover();
+  return c;
+}
+__device__ __forceinline__ void copy16_to_lds(unsigned off, const void* sbase_in, unsigned lds_base) {
+  // (the base is uniform by construction; say so where the register allocator has moved it to vector registers)
+  const unsigned long long b = reinterpret_cast<unsigned long long>(sbase_in);
+  const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)b);
+  const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(b >> 32));
+  const void* sbase = reinterpret_cast<const void*>((unsigned long long)lo | ((unsigned long long)hi << 32));
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1\n"
+               :: "v"(off), "s"(sbase), "s"(lds_base) : "memory");
+}
+// 4 bytes per lane from a per-lane address to lds_base + 4 lane
+__device__ __forceinline__ void copy4_to_lds(const void* gptr, unsigned lds_base) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off\n" :: "v"(gptr), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ void copies_landed() {
+  __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0)
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+}
+// 32 rows x 128 bytes from `base` (row 0 of the tile, wave-uniform) to the tile at LDS address lds_tile; CLAMP: only
+// rows_left < 32 rows exist, the others repeat the last one
+template <bool CLAMP>
+__device__ __forceinline__ void copy_tile(const unsigned char* base, const CopyOffsets& co, unsigned ldb, int rows_left,
+                                          unsigned lds_tile, int lane) {
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    unsigned off = co.o[u];
+    if (CLAMP) {
+      const int r = 8 * u + (lane >> 3);
+      off = (unsigned)(r < rows_left ? r : rows_left - 1) * ldb + (unsigned)(((lane & 7) ^ swz(r)) << 4);
+    }
+    copy16_to_lds(off, base, lds_tile + 1024u * u);
+  }
+}
+// this lane's byte offset into a tile for the quarter copy of wavefront w (row 8 w + l / 8, chunk (l % 8) ^ swz(row))
+__device__ __forceinline__ unsigned quarter_offset(unsigned ldb, int w, int lane) {
+  const int r = 8 * w + (lane >> 3);
+  return (unsigned)r * ldb + (unsigned)(((lane & 7) ^ swz(r)) << 4);
+}
+// One wavefront's quarter of a tile copy (rows 8 w .. 8 w + 7): the four wavefronts of a workgroup fill a tile together.
+template <bool CLAMP>
+__device__ __forceinline__ void copy_tile_quarter(const unsigned char* base, unsigned own_off, unsigned ldb, int rows_left,
+                                                  unsigned lds_tile, int w, int lane) {
+  unsigned off = own_off;
+  if (CLAMP) {
+    const int r = 8 * w + (lane >> 3);
+    off = (unsigned)(r < rows_left ? r : rows_left - 1) * ldb + (unsigned)(((lane & 7) ^ swz(r)) << 4);
+  }
+  copy16_to_lds(off, base, lds_tile + 1024u * (unsigned)w);
+}
+// at most N of this wavefront's copies still in flight (they land in issue order)
+template <int N>
+__device__ __forceinline__ void copies_in_flight() {
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+// every wavefront of the workgroup has passed its wait: the tile is complete, and the buffer of the step before is free
+__device__ __forceinline__ void workgroup_handover() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("" ::: "memory");
+}
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+  return (unsigned)(uintptr_t)(__attribute__((address_space(3))) const unsigned char*)p;
 }
 // operand fragment with the contraction along the tile's columns (step kk of 16 columns): lane holds row l % 32
 __device__ __forceinline__ bf16x8 frag_cols_lds(const unsigned char* tile, int kk, int lane) {
@@ -272,7 +341,8 @@ __device__ __forceinline__ float dot8(bf16x8 a, bf16x8 b) {
   return acc;
 }
 
-constexpr int AT_WAVES = 4;    // wavefronts (tiles) per workgroup
+constexpr int AT_WAVES = 4;    // wavefronts per workgroup: 4 tiles of 32 queries (dk/dv kernel: keys) that share the streamed tiles
+constexpr int AT_NST = 4;      // stages of the ring of streamed tile pairs (8 KB each): copies run AT_NST - 1 steps ahead
 
 // One (sequence, head): wavefront-uniform byte pointers to row 0 of q, k, v (row stride 6 d bytes) and of the
 // d-wide arrays (row stride 2 d bytes), all at the head's 64 columns.
@@ -297,39 +367,64 @@ __device__ __forceinline__ Head head_of(const AttnArgs& a, unsigned p) {
   return hd;
 }
 
+// The three kernels share one shape.  A workgroup of four wavefronts owns four consecutive tiles of 32 queries
+// (dk/dv kernel: keys), one per wavefront, and streams the tiles of the other side through a ring of AT_NST buffer
+// pairs that all four read: at step t each wavefront waits for its own quarter of pair t, the workgroup meets at a
+// barrier (pair t complete; everyone done with pair t-1), the quarter copies of pair t + AT_NST - 1 go out into the
+// buffer just freed, and the wavefront computes on pair t (or skips it when the causal mask hides the whole tile from
+// its rows).  No global load is issued inside the loop other than these copies, so the counted wait is exact.
+
 template <bool CAUSAL>
-__global__ __launch_bounds__(64 * AT_WAVES) void attn_fwd_mfma_kernel(AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) unsigned char smem[AT_WAVES][4096];
+__global__ __launch_bounds__(64 * AT_WAVES, 2) void attn_fwd_mfma_kernel(AttnArgs a) {
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[AT_NST][2][4096];   // [stage][k | v]
   const int lane = threadIdx.x & 63, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int T = (int)a.T, nt = (T + 31) >> 5;
-  const int qt = nt - 1 - ((int)blockIdx.y * AT_WAVES + wave);     // long rows first
-  if (qt < 0) return;
+  const int nblk = (nt + AT_WAVES - 1) / AT_WAVES;
+  const int blk = nblk - 1 - (int)blockIdx.y;                      // long rows first
+  const int qt = AT_WAVES * blk + wave;
+  const bool live = qt < nt;                                       // a ragged workgroup's spare wavefronts only copy
   const unsigned p = blockIdx.x;
   const Head hd = head_of(a, p);
   const LaneOffsets lo = lane_offsets((unsigned)(hd.ld * 2), lane);
-  unsigned char* tile = smem[wave];
+  const unsigned lds0 = lds_address(smem);
+  const bool ragged = (T & 31) != 0;
   const int q0 = 32 * qt, qi = q0 + (lane & 31);
   const float c = a.scale * LOG2E;
+  const int last_q = AT_WAVES * blk + AT_WAVES - 1 < nt - 1 ? AT_WAVES * blk + AT_WAVES - 1 : nt - 1;
+  const int nkt = CAUSAL ? last_q + 1 : nt;                        // key tiles the workgroup streams
+  const int own_nkt = CAUSAL ? qt + 1 : nt;                        // ... and those this wavefront's rows see
+  const unsigned own = quarter_offset(lo.ldb, wave, lane);
+  auto issue = [&](int kt) __attribute__((always_inline)) {        // this wavefront's quarters of the k and v tiles of key tile kt
+    const unsigned char* kb = hd.k + (long)(32 * kt) * lo.ldb;
+    const unsigned dst = lds0 + (unsigned)(kt % AT_NST) * 8192u;
+    if (ragged && kt == nt - 1) {
+      copy_tile_quarter<true>(kb, own, lo.ldb, T - 32 * kt, dst, wave, lane);
+      copy_tile_quarter<true>(kb + hd.d * 2, own, lo.ldb, T - 32 * kt, dst + 4096u, wave, lane);
+    } else {
+      copy_tile_quarter<false>(kb, own, lo.ldb, 32, dst, wave, lane);
+      copy_tile_quarter<false>(kb + hd.d * 2, own, lo.ldb, 32, dst + 4096u, wave, lane);
+    }
+  };
   bf16x8 fq[4];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) fq[kk] = frag_cols_mem<true>(hd.q + (long)q0 * lo.ldb, lo, T - q0, kk, lane);
+  for (int kk = 0; kk < 4; ++kk) fq[kk] = frag_cols_mem<true>(hd.q + (long)(live ? q0 : 0) * lo.ldb, lo, live ? T - q0 : 1, kk, lane);
+  for (int kt = 0; kt < AT_NST - 1 && kt < nkt; ++kt) issue(kt);
   float16v o0, o1;
 #pragma unroll
   for (int r = 0; r < 16; ++r) { o0[r] = 0.f; o1[r] = 0.f; }
   float m = -INFINITY, l = 0.f;
-  const int nkt = CAUSAL ? qt + 1 : nt;
   // one tile of 32 keys; MASKED: the tile on the diagonal (causal) or the one that runs past the last key
   auto step = [&](int kt, auto masked_c) __attribute__((always_inline)) {
     constexpr bool MASKED = decltype(masked_c)::value;
     const int k0 = 32 * kt;
-    const unsigned char* kb = hd.k + (long)k0 * lo.ldb;
-    tile_to_lds<MASKED>(kb + hd.d * 2, lo, T - k0, tile, lane);
+    const unsigned char* tk = smem[kt % AT_NST][0];
+    const unsigned char* tv = smem[kt % AT_NST][1];
     float16v s;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) s = mfma(frag_cols_mem<MASKED>(kb, lo, T - k0, kk, lane), fq[kk], s);
+    for (int kk = 0; kk < 4; ++kk) s = mfma(frag_cols_lds(tk, kk, lane), fq[kk], s);
     float sv[16];
     float tmax = -INFINITY;
 #pragma unroll
@@ -353,39 +448,67 @@ __global__ __launch_bounds__(64 * AT_WAVES) void attn_fwd_mfma_kernel(AttnArgs a
 #pragma unroll
     for (int r = 0; r < 16; ++r) { o0[r] *= alpha; o1[r] *= alpha; }
     const bf16x8 p0 = pack8(sv), p1 = pack8(sv + 8);
-    o0 = mfma(frag_rows_lds(tile, 0, 0, lane), p0, o0);
-    o0 = mfma(frag_rows_lds(tile, 0, 1, lane), p1, o0);
-    o1 = mfma(frag_rows_lds(tile, 1, 0, lane), p0, o1);
-    o1 = mfma(frag_rows_lds(tile, 1, 1, lane), p1, o1);
-    lds_handover();
+    o0 = mfma(frag_rows_lds(tv, 0, 0, lane), p0, o0);
+    o0 = mfma(frag_rows_lds(tv, 0, 1, lane), p1, o0);
+    o1 = mfma(frag_rows_lds(tv, 1, 0, lane), p0, o1);
+    o1 = mfma(frag_rows_lds(tv, 1, 1, lane), p1, o1);
   };
-  const int n_plain = CAUSAL ? nkt - 1 : (T & 31 ? nkt - 1 : nkt);
-  for (int kt = 0; kt < n_plain; ++kt) step(kt, std::false_type());
-  if (n_plain < nkt) step(nkt - 1, std::true_type());
-  if (qi < T) {
+  // tile kt complete and visible to the workgroup, the buffer of tile kt - 1 free and refilled
+  auto advance = [&](int kt) __attribute__((always_inline)) {
+    if (kt + AT_NST - 2 < nkt) copies_in_flight<2 * (AT_NST - 2)>();
+    else copies_in_flight<0>();
+    workgroup_handover();
+    if (kt + AT_NST - 1 < nkt) issue(kt + AT_NST - 1);
+  };
+  // whole tiles, then the masked one, then (causal) the tiles the workgroup streams for its later rows only
+  const int n_own = live ? own_nkt : 0;
+  const int n_plain = CAUSAL ? n_own - 1 : (ragged ? n_own - 1 : n_own);
+  int kt = 0;
+  for (; kt < n_plain; ++kt) { advance(kt); step(kt, std::false_type()); }
+  if (kt < n_own) { advance(kt); step(kt, std::true_type()); ++kt; }
+  for (; kt < nkt; ++kt) advance(kt);
+  if (live && qi < T) {
     store_row(reinterpret_cast<bf16_t*>(reinterpret_cast<unsigned char*>(a.o) + hd.wide_off) + (long)qi * hd.d, o0, o1,
               1.f / l, hh);
     if (hh == 0) a.lse[(long)p * a.T + qi] = m + log2f(l);
   }
 }
 
-// dq of a tile of 32 queries; also leaves D = rowsum(do (.) o) of its queries for the dk/dv kernel
+// dq of four tiles of 32 queries; also leaves D = rowsum(do (.) o) of their queries for the dk/dv kernel
 template <bool CAUSAL>
-__global__ __launch_bounds__(64 * AT_WAVES) void attn_bwd_q_mfma_kernel(AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) unsigned char smem[AT_WAVES][4096];
+__global__ __launch_bounds__(64 * AT_WAVES, 2) void attn_bwd_q_mfma_kernel(AttnArgs a) {
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[AT_NST][2][4096];   // [stage][k | v]
   const int lane = threadIdx.x & 63, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int T = (int)a.T, nt = (T + 31) >> 5;
-  const int qt = nt - 1 - ((int)blockIdx.y * AT_WAVES + wave);
-  if (qt < 0) return;
+  const int nblk = (nt + AT_WAVES - 1) / AT_WAVES;
+  const int blk = nblk - 1 - (int)blockIdx.y;
+  const int qt = AT_WAVES * blk + wave;
+  const bool live = qt < nt;
   const unsigned p = blockIdx.x;
   const Head hd = head_of(a, p);
   const LaneOffsets lo = lane_offsets((unsigned)(hd.ld * 2), lane);
   const LaneOffsets lw = lane_offsets((unsigned)(hd.d * 2), lane);
-  unsigned char* tile = smem[wave];
-  const int q0 = 32 * qt, qi = q0 + (lane & 31);
+  const unsigned lds0 = lds_address(smem);
+  const bool ragged = (T & 31) != 0;
+  const int q0 = live ? 32 * qt : 0, qi = 32 * qt + (lane & 31);
   const int qc = qi < T ? qi : T - 1;
   const float c = a.scale * LOG2E;
+  const int last_q = AT_WAVES * blk + AT_WAVES - 1 < nt - 1 ? AT_WAVES * blk + AT_WAVES - 1 : nt - 1;
+  const int nkt = CAUSAL ? last_q + 1 : nt;
+  const int own_nkt = CAUSAL ? qt + 1 : nt;
+  const unsigned own = quarter_offset(lo.ldb, wave, lane);
+  auto issue = [&](int kt) __attribute__((always_inline)) {
+    const unsigned char* kb = hd.k + (long)(32 * kt) * lo.ldb;
+    const unsigned dst = lds0 + (unsigned)(kt % AT_NST) * 8192u;
+    if (ragged && kt == nt - 1) {
+      copy_tile_quarter<true>(kb, own, lo.ldb, T - 32 * kt, dst, wave, lane);
+      copy_tile_quarter<true>(kb + hd.d * 2, own, lo.ldb, T - 32 * kt, dst + 4096u, wave, lane);
+    } else {
+      copy_tile_quarter<false>(kb, own, lo.ldb, 32, dst, wave, lane);
+      copy_tile_quarter<false>(kb + hd.d * 2, own, lo.ldb, 32, dst + 4096u, wave, lane);
+    }
+  };
   const float L2 = a.lse[(long)p * a.T + qc];
   bf16x8 fq[4], fdo[4];
   float D = 0.f;
@@ -399,24 +522,24 @@ __global__ __launch_bounds__(64 * AT_WAVES) void attn_bwd_q_mfma_kernel(AttnArgs
       D += dot8(fdo[kk], frag_cols_mem<true>(ob, lw, T - q0, kk, lane));
     }
     D += __shfl_xor(D, 32, 64);
-    if (hh == 0 && qi < T) a.dsum[(long)p * a.T + qi] = D;
+    if (live && hh == 0 && qi < T) a.dsum[(long)p * a.T + qi] = D;
   }
+  for (int kt = 0; kt < AT_NST - 1 && kt < nkt; ++kt) issue(kt);
   float16v dq0, dq1;
 #pragma unroll
   for (int r = 0; r < 16; ++r) { dq0[r] = 0.f; dq1[r] = 0.f; }
-  const int nkt = CAUSAL ? qt + 1 : nt;
   auto step = [&](int kt, auto masked_c) __attribute__((always_inline)) {
     constexpr bool MASKED = decltype(masked_c)::value;
     const int k0 = 32 * kt;
-    const unsigned char* kb = hd.k + (long)k0 * lo.ldb;
-    tile_to_lds<MASKED>(kb, lo, T - k0, tile, lane);
+    const unsigned char* tk = smem[kt % AT_NST][0];
+    const unsigned char* tv = smem[kt % AT_NST][1];
     float16v s, dp;
 #pragma unroll
     for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = -D; }      // dp comes out as dP - D
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      s = mfma(frag_cols_lds(tile, kk, lane), fq[kk], s);
-      dp = mfma(frag_cols_mem<MASKED>(kb + hd.d * 2, lo, T - k0, kk, lane), fdo[kk], dp);
+      s = mfma(frag_cols_lds(tk, kk, lane), fq[kk], s);
+      dp = mfma(frag_cols_lds(tv, kk, lane), fdo[kk], dp);
     }
     float ds[16];
 #pragma unroll
@@ -429,62 +552,91 @@ __global__ __launch_bounds__(64 * AT_WAVES) void attn_bwd_q_mfma_kernel(AttnArgs
       ds[r] = pr * dp[r];
     }
     const bf16x8 d0 = pack8(ds), d1 = pack8(ds + 8);
-    dq0 = mfma(frag_rows_lds(tile, 0, 0, lane), d0, dq0);
-    dq0 = mfma(frag_rows_lds(tile, 0, 1, lane), d1, dq0);
-    dq1 = mfma(frag_rows_lds(tile, 1, 0, lane), d0, dq1);
-    dq1 = mfma(frag_rows_lds(tile, 1, 1, lane), d1, dq1);
-    lds_handover();
+    dq0 = mfma(frag_rows_lds(tk, 0, 0, lane), d0, dq0);
+    dq0 = mfma(frag_rows_lds(tk, 0, 1, lane), d1, dq0);
+    dq1 = mfma(frag_rows_lds(tk, 1, 0, lane), d0, dq1);
+    dq1 = mfma(frag_rows_lds(tk, 1, 1, lane), d1, dq1);
   };
-  const int n_plain = CAUSAL ? nkt - 1 : (T & 31 ? nkt - 1 : nkt);
-  for (int kt = 0; kt < n_plain; ++kt) step(kt, std::false_type());
-  if (n_plain < nkt) step(nkt - 1, std::true_type());
-  if (qi < T)
+  // tile kt complete and visible to the workgroup, the buffer of tile kt - 1 free and refilled
+  auto advance = [&](int kt) __attribute__((always_inline)) {
+    if (kt + AT_NST - 2 < nkt) copies_in_flight<2 * (AT_NST - 2)>();
+    else copies_in_flight<0>();
+    workgroup_handover();
+    if (kt + AT_NST - 1 < nkt) issue(kt + AT_NST - 1);
+  };
+  // whole tiles, then the masked one, then (causal) the tiles the workgroup streams for its later rows only
+  const int n_own = live ? own_nkt : 0;
+  const int n_plain = CAUSAL ? n_own - 1 : (ragged ? n_own - 1 : n_own);
+  int kt = 0;
+  for (; kt < n_plain; ++kt) { advance(kt); step(kt, std::false_type()); }
+  if (kt < n_own) { advance(kt); step(kt, std::true_type()); ++kt; }
+  for (; kt < nkt; ++kt) advance(kt);
+  if (live && qi < T)
     store_row(reinterpret_cast<bf16_t*>(reinterpret_cast<unsigned char*>(a.dqkv) + (hd.q - reinterpret_cast<const unsigned char*>(a.qkv))) +
                   (long)qi * hd.ld, dq0, dq1, a.scale, hh);
 }
 
-// dk, dv of a tile of 32 keys (after the dq kernel: reads D)
+// dk, dv of four tiles of 32 keys (after the dq kernel: reads D)
 template <bool CAUSAL>
-__global__ __launch_bounds__(64 * AT_WAVES) void attn_bwd_kv_mfma_kernel(AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) unsigned char smem[AT_WAVES][2][4096];
-  __shared__ __attribute__((aligned(16))) float stats[AT_WAVES][64];
+__global__ __launch_bounds__(64 * AT_WAVES, 2) void attn_bwd_kv_mfma_kernel(AttnArgs a) {
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[AT_NST][2][4096];   // [stage][q | do]
+  __shared__ __attribute__((aligned(1024))) unsigned char own[AT_WAVES][2][4096];   // [wave][k | v]: the wavefront's own keys
+  __shared__ __attribute__((aligned(256))) float stats[AT_WAVES][AT_NST][64];       // [wave][stage][L2 | D] (a copy per wavefront)
   const int lane = threadIdx.x & 63, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int T = (int)a.T, nt = (T + 31) >> 5;
-  const int kt = (int)blockIdx.y * AT_WAVES + wave;                // causal: early keys see the most queries
-  if (kt >= nt) return;
+  const int blk = (int)blockIdx.y;                                 // causal: early keys see the most queries
+  const int kt = AT_WAVES * blk + wave;
+  const bool live = kt < nt;
   const unsigned p = blockIdx.x;
   const Head hd = head_of(a, p);
   const LaneOffsets lo = lane_offsets((unsigned)(hd.ld * 2), lane);
-  const LaneOffsets lw = lane_offsets((unsigned)(hd.d * 2), lane);
+  const unsigned ldw = (unsigned)(hd.d * 2);
   const unsigned char* dob = reinterpret_cast<const unsigned char*>(a.dout) + hd.wide_off;
-  unsigned char* tq = smem[wave][0];
-  unsigned char* td = smem[wave][1];
-  float* st = stats[wave];
-  const int k0 = 32 * kt, kj = k0 + (lane & 31);
+  const unsigned lds0 = lds_address(smem), lds_s = lds_address(stats[wave]);
+  const bool ragged = (T & 31) != 0;
+  const int k0 = live ? 32 * kt : 0, kj = 32 * kt + (lane & 31);
   const float c = a.scale * LOG2E;
+  const float ninv_c = -1.0f / c;
   // lanes 0..31 fetch the row statistic of query l of each tile, lanes 32..63 its D
   const float* stat_src = (hh == 0 ? a.lse : a.dsum) + (long)p * a.T;
-  const float ninv_c = -1.0f / c;
-  bf16x8 fk[4], fv[4];
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    fk[kk] = frag_cols_mem<true>(hd.k + (long)k0 * lo.ldb, lo, T - k0, kk, lane);
-    fv[kk] = frag_cols_mem<true>(hd.v + (long)k0 * lo.ldb, lo, T - k0, kk, lane);
+  const int q_first = CAUSAL ? AT_WAVES * blk : 0;                 // query tiles the workgroup streams: q_first .. nt - 1
+  const int own_first = CAUSAL ? kt : 0;                           // ... and the first one this wavefront's keys are seen by
+  const unsigned own_q = quarter_offset(lo.ldb, wave, lane), own_d = quarter_offset(ldw, wave, lane);
+  auto issue = [&](int qt) __attribute__((always_inline)) {       // quarters of the q and do tiles, and the statistics, of query tile qt
+    const int q0 = 32 * qt, b = qt % AT_NST;
+    const unsigned dst = lds0 + (unsigned)b * 8192u;
+    int r = lane & 31;
+    if (ragged && qt == nt - 1) {
+      copy_tile_quarter<true>(hd.q + (long)q0 * lo.ldb, own_q, lo.ldb, T - q0, dst, wave, lane);
+      copy_tile_quarter<true>(dob + (long)q0 * ldw, own_d, ldw, T - q0, dst + 4096u, wave, lane);
+      r = r < T - q0 ? r : T - 1 - q0;
+    } else {
+      copy_tile_quarter<false>(hd.q + (long)q0 * lo.ldb, own_q, lo.ldb, 32, dst, wave, lane);
+      copy_tile_quarter<false>(dob + (long)q0 * ldw, own_d, ldw, 32, dst + 4096u, wave, lane);
+    }
+    copy4_to_lds(stat_src + q0 + r, lds_s + (unsigned)b * 256u);
+  };
+  {   // the wavefront's own k and v tiles stay in LDS for the whole loop (copied before the ring's first tiles, so they
+      // have landed when the first of those has)
+    const CopyOffsets co = copy_offsets(lo.ldb, lane);
+    const unsigned dst = lds_address(own[wave]);
+    copy_tile<true>(hd.k + (long)k0 * lo.ldb, co, lo.ldb, T - k0, dst, lane);
+    copy_tile<true>(hd.v + (long)k0 * lo.ldb, co, lo.ldb, T - k0, dst + 4096u, lane);
   }
+  const unsigned char* ok = own[wave][0];
+  const unsigned char* ov = own[wave][1];
+  for (int qt = q_first; qt < q_first + AT_NST - 1 && qt < nt; ++qt) issue(qt);
   float16v dk0, dk1, dv0, dv1;
 #pragma unroll
   for (int r = 0; r < 16; ++r) { dk0[r] = 0.f; dk1[r] = 0.f; dv0[r] = 0.f; dv1[r] = 0.f; }
   // one tile of 32 queries; MASKED: the tile on the diagonal (causal) or the one that runs past the last query
   auto step = [&](int qt, auto masked_c) __attribute__((always_inline)) {
     constexpr bool MASKED = decltype(masked_c)::value;
-    const int q0 = 32 * qt;
-    {
-      const int r = lane & 31;
-      st[lane] = stat_src[q0 + ((!MASKED || r < T - q0) ? r : T - 1 - q0)];
-    }
-    tile_to_lds<MASKED>(hd.q + (long)q0 * lo.ldb, lo, T - q0, tq, lane);
-    tile_to_lds<MASKED>(dob + (long)q0 * lw.ldb, lw, T - q0, td, lane);
+    const int q0 = 32 * qt, b = qt % AT_NST;
+    const unsigned char* tq = smem[b][0];
+    const unsigned char* td = smem[b][1];
+    const float* st = stats[wave][b];
     float16v s, dp;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {       // the statistics of the lane's 16 queries: rows 8 g + 4 hh .. + 3
@@ -496,9 +648,10 @@ __global__ __launch_bounds__(64 * AT_WAVES) void attn_bwd_kv_mfma_kernel(AttnArg
     }
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      s = mfma(frag_cols_lds(tq, kk, lane), fk[kk], s);
-      dp = mfma(frag_cols_lds(td, kk, lane), fv[kk], dp);
+      s = mfma(frag_cols_lds(tq, kk, lane), frag_cols_lds(ok, kk, lane), s);
+      dp = mfma(frag_cols_lds(td, kk, lane), frag_cols_lds(ov, kk, lane), dp);
     }
+    __builtin_amdgcn_sched_barrier(0);   // (keeps the second products' operand reads below: fewer live registers)
     float pr[16], ds[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -510,6 +663,7 @@ __global__ __launch_bounds__(64 * AT_WAVES) void attn_bwd_kv_mfma_kernel(AttnArg
       ds[r] = pr[r] * dp[r];
     }
     const bf16x8 p0 = pack8(pr), p1 = pack8(pr + 8), d0 = pack8(ds), d1 = pack8(ds + 8);
+    __builtin_amdgcn_sched_barrier(0);
     dv0 = mfma(frag_rows_lds(td, 0, 0, lane), p0, dv0);
     dv0 = mfma(frag_rows_lds(td, 0, 1, lane), p1, dv0);
     dv1 = mfma(frag_rows_lds(td, 1, 0, lane), p0, dv1);
@@ -518,18 +672,22 @@ __global__ __launch_bounds__(64 * AT_WAVES) void attn_bwd_kv_mfma_kernel(AttnArg
     dk0 = mfma(frag_rows_lds(tq, 0, 1, lane), d1, dk0);
     dk1 = mfma(frag_rows_lds(tq, 1, 0, lane), d0, dk1);
     dk1 = mfma(frag_rows_lds(tq, 1, 1, lane), d1, dk1);
-    lds_handover();
   };
-  const bool ragged = (T & 31) != 0;
-  int qt = CAUSAL ? kt : 0;
-  if (CAUSAL) {                                  // the diagonal tile first
-    step(qt, std::true_type());
-    ++qt;
-  }
-  const int n_plain = ragged ? nt - 1 : nt;
-  for (; qt < n_plain; ++qt) step(qt, std::false_type());
-  if (qt < nt) step(qt, std::true_type());       // the ragged last tile (unless it was the diagonal one)
-  if (kj < T) {
+  auto advance = [&](int qt) __attribute__((always_inline)) {
+    if (qt + AT_NST - 2 < nt) copies_in_flight<3 * (AT_NST - 2)>();
+    else copies_in_flight<0>();
+    workgroup_handover();
+    if (qt + AT_NST - 1 < nt) issue(qt + AT_NST - 1);
+  };
+  // (causal) the tiles streamed for the workgroup's earlier keys only, the tile on the diagonal, whole tiles, a ragged last one
+  int qt = q_first;
+  const int first = live ? own_first : nt;
+  for (; qt < first; ++qt) advance(qt);
+  if (CAUSAL && qt < nt) { advance(qt); step(qt, std::true_type()); ++qt; }
+  const int plain_end = ragged ? nt - 1 : nt;
+  for (; qt < plain_end; ++qt) { advance(qt); step(qt, std::false_type()); }
+  if (qt < nt) { advance(qt); step(qt, std::true_type()); }
+  if (live && kj < T) {
     bf16_t* row = reinterpret_cast<bf16_t*>(reinterpret_cast<unsigned char*>(a.dqkv) + (hd.k - reinterpret_cast<const unsigned char*>(a.qkv))) +
                   (long)kj * hd.ld;
     store_row(row, dk0, dk1, a.scale, hh);
