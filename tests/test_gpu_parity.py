@@ -519,7 +519,7 @@ def test_k_beyond_L_is_exact_and_deterministic(B):
     assert torch.equal(g1, p.g) and torch.equal(w1, p.dW1) and torch.equal(w2, p.dW2)
 
 
-@pytest.mark.parametrize("name", SPLITK_CASES + ["rnn_long", "rnn_token_gates_long", "gated_long"])
+@pytest.mark.parametrize("name", SPLITK_CASES + ["rnn_long", "rnn_token_gates_long", "gated_long", "tfm_splitk", "tfm_small"])
 def test_split_parameter_gradients_are_deterministic(B, name):
     """Two runs from scratch give the same bits: the shares of a split contraction are added in a fixed order by
     a second kernel (no atomics), and the chunked scan combines its chunks in a fixed order."""
@@ -528,13 +528,13 @@ def test_split_parameter_gradients_are_deterministic(B, name):
     B.hbp_forward(p)
     outs = []
     for _ in range(2):
-        for t in (p.g, p.dW1, p.dW2, p.dU, p.workspace):
+        for t in (p.g, p.dW1, p.dW2, p.dU, p.dWqkv, p.dWo, p.workspace):
             if t is not None:
                 t.fill_(0)
         B.hbp_backward(p, 2)
         B.hbp_param_grads(p)
         torch.cuda.synchronize()
-        outs.append([t.clone() for t in (p.g, p.dW1, p.dW2, p.dU) if t is not None])
+        outs.append([t.clone() for t in (p.g, p.dW1, p.dW2, p.dU, p.dWqkv, p.dWo) if t is not None])
     for a, b in zip(*outs):
         assert torch.equal(a, b)
 
@@ -570,7 +570,7 @@ def test_error_codes_on_device_buffers(B):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("name", ["aligned_small", "rnn_aligned", "gated_small", "postact_rms"])
+@pytest.mark.parametrize("name", ["aligned_small", "rnn_aligned", "gated_small", "postact_rms", "tfm_aligned"])
 def test_calls_can_be_captured_in_a_graph_and_replayed(B, name):
     """The backward calls allocate nothing and never synchronise, so a caller may record them into a HIP graph:
     every replay, with eager work and synchronisations between them, gives the eager result bit for bit."""

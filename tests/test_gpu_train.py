@@ -15,6 +15,8 @@ W = synth.WORKLOADS
 SMALL_F32 = synth.scaled(W["mlp_small_f32"], name="train_f32", L=4, N=64, d=64, d_ff=128, norm="rms", lam="uniform",
                          lam_lo=0.9, lam_hi=1.0)
 SMALL_BF16 = synth.scaled(W["resnet_like"], name="train_bf16", L=4, N=256, d=256, d_ff=512, w2_scale=0.5)
+TFM_F32 = synth.scaled(W["gpt2_paper"], name="train_tfm_f32", dtype="f32", L=4, N=48, seq_len=12, d=32, heads=2, d_ff=64,
+                       w1_std=0.0, w2_std=0.0, w2_scale=0.7, gamma=0.2)
 RNN_F32 = synth.scaled(W["gated_rnn_contractive"], name="train_rnn_f32", dtype="f32", L=12, N=4, d=64, d_ff=64, d_in=32)
 
 
@@ -86,7 +88,8 @@ def test_optimizer_steps(B, kind, master):
 
 def _oracle_train(w, inp, tgt, ks, kind, hp):
     """The same loop in the oracle (fp64).  Returns the losses and the final weights."""
-    names = ["W1", "W2", "U"]
+    names = ["W1", "W2", "U", "Wqkv", "Wo"]
+    inp = {**{n: None for n in names}, **inp}
     Ws = {n: (None if inp[n] is None else inp[n].astype(np.float64)) for n in names}
     m = {n: (None if Ws[n] is None else np.zeros_like(Ws[n])) for n in names}
     v = {n: (None if Ws[n] is None else np.zeros_like(Ws[n])) for n in names}
@@ -97,7 +100,7 @@ def _oracle_train(w, inp, tgt, ks, kind, hp):
         sv = O.forward(st, inp["x0"], inp["xin"])
         loss, e = O.mse_loss_and_grad(sv["x"], tgt, w.loss_every_state)
         losses.append(loss)
-        g = O.exact_backward(st, sv, e) if k < 0 else O.hbp_backward(st, sv, e, k)
+        g = O.exact_backward(st, sv, e) if k < 0 else O.hbp_backward(st, sv, e, k, gamma=w.gamma)
         pg = O.param_grads(st, sv, g, inp["xin"])
         have = [n for n in names if Ws[n] is not None]
         sc = O.clip_scale([pg["d" + n] for n in have], hp["clip_norm"])
@@ -110,8 +113,8 @@ def _oracle_train(w, inp, tgt, ks, kind, hp):
     return losses, Ws
 
 
-@pytest.mark.parametrize("w,kind", [(SMALL_F32, "sgd"), (SMALL_F32, "adamw"), (RNN_F32, "adamw")],
-                         ids=["mlp_sgd", "mlp_adamw", "rnn_adamw"])
+@pytest.mark.parametrize("w,kind", [(SMALL_F32, "sgd"), (SMALL_F32, "adamw"), (RNN_F32, "adamw"), (TFM_F32, "adamw")],
+                         ids=["mlp_sgd", "mlp_adamw", "rnn_adamw", "transformer_adamw"])
 def test_training_steps_under_a_schedule_of_iterations(B, w, kind):
     """Nine whole steps (forward, loss, backward, parameter gradients, update) with k = 1, 1, 1, 2, 2, 2, then exact
     backpropagation three times: losses and final weights against the same loop in the oracle (fp32 storage)."""
@@ -131,7 +134,7 @@ def test_training_steps_under_a_schedule_of_iterations(B, w, kind):
         losses.append(float(os_.loss))
     assert np.allclose(losses, want_losses, rtol=2e-4), (losses, want_losses)
     assert losses[-1] < losses[0]
-    for n, t in (("W1", p.W1), ("W2", p.W2), ("U", p.U)):
+    for n, t in (("W1", p.W1), ("W2", p.W2), ("U", p.U), ("Wqkv", p.Wqkv), ("Wo", p.Wo)):
         if t is not None:
             # the update itself (what training moved), not the weights it is small against
             H.assert_close(H.to_np(t) - inp[n], want_W[n] - inp[n], 2e-3, f"{w.name} {kind}: change of {n}", row_floor=0.5)
