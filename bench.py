@@ -279,6 +279,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true", help="skip the k = 1..4 / exact table")
     ap.add_argument("--cpu-tokens", type=int, default=0, help="token rows of the oracle sample (0 = auto)")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="time torch.matmul (the vendor library) on random bf16 operands of the workload's three "
+                         "contraction shapes and layouts, one block at a time, and exit: what the same hardware gives "
+                         "a tuned library on these shapes (a reference for the roofline fractions, not a target)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run plain 1 GiB device copies and exit (reference for rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -309,6 +313,26 @@ def main():
 
     w = synth.WORKLOADS[args.workload]
     k = args.k
+    if args.vendor_gemm:
+        # per block: vjp1  da[N,d_ff] = g[N,d] W2[d,d_ff]; vjp2  dn[N,d] = da[N,d_ff] W1[d_ff,d]; dw  dW2[d,d_ff] = g^T[d,N] z[N,d_ff]
+        # (operands as the backward pass holds them: weights untransposed, the token contraction over rows)
+        gen = torch.Generator(device="cuda:0").manual_seed(1)
+        rnd = lambda *shape: torch.randn(*shape, generator=gen, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
+        N, d, dff = w.N * (w.L if w.kind in ("rnn", "gated", "lstm", "gru") else 1), w.d, w.d_ff
+        N = min(N, 32768)
+        g_, da_, z_, W1_, W2_ = rnd(N, d), rnd(N, dff), rnd(N, dff), rnd(dff, d), rnd(d, dff)
+        res = {}
+        for name, fn, flops in (("vjp1", lambda: g_ @ W2_, 2.0 * N * d * dff), ("vjp2", lambda: da_ @ W1_, 2.0 * N * d * dff),
+                                ("dw", lambda: g_.t() @ z_, 2.0 * N * d * dff),
+                                ("square_8192_nt", None, 0.0)):
+            if fn is None:
+                a_, b_ = rnd(8192, 8192), rnd(8192, 8192)
+                fn, flops = (lambda: a_ @ b_.t()), 2.0 * 8192 ** 3
+            t = time_steps(torch, fn, 20, 5)
+            res[name] = {"ms": t * 1e3, "TFLOP/s": flops / t / 1e12, "frac_of_2500": flops / t / 1e12 / PEAK_MFMA_BF16_TFLOPS}
+        print(json.dumps({"vendor_gemm": "torch.matmul, bf16, randn operands", "workload": w.name, "rows": N, "d": d,
+                          "d_ff": dff, "results": res}))
+        return
     inp = synth.make_inputs(w)
     p = B.allocate(w, inp)
     B.hbp_forward(p)            # support, untimed: fills the saved forward state
