@@ -241,7 +241,9 @@ enum FastEpi {
   FAST_STORE_F32 = 2,  // C(fp32) = acc, also the split-K partial sums
   FAST_MUL_AUX = 3,    // C(bf16) = acc * aux
   FAST_MUL_1MZ2 = 4,   // C(bf16) = acc * (1 - aux^2)
-  FAST_ADD_AUX = 5     // C(bf16) = acc + aux
+  FAST_ADD_AUX = 5,    // C(bf16) = acc + aux
+  FAST_RESID = 6,      // C(bf16) = acc + lambda[n] * aux   (forward: x_{l+1}; lambda NULL = 1)
+  FAST_ACT_GELU = 7    // C(bf16) = gelu(acc), out2(bf16) = gelu'(acc)   (forward: z and act')
 };
 
 template <bool A_KC, bool B_KC, bool ACT>
@@ -588,7 +590,8 @@ struct Quad16 { uint4v x0, x1, x2, x3; };   // 4 x 16 bytes per lane: 32 rows of
 template <int FAST>
 __device__ __forceinline__ void epilogue_staged_fn(const GemmArgs& g, const TileCoord& tc, const float16v (&acc)[4][2],
                                                    int wm0, int wn0, int lane, unsigned char* stg) {
-  constexpr bool HAS_AUX = FAST == FAST_MUL_AUX || FAST == FAST_MUL_1MZ2 || FAST == FAST_ADD_AUX;
+  constexpr bool HAS_AUX = FAST == FAST_MUL_AUX || FAST == FAST_MUL_1MZ2 || FAST == FAST_ADD_AUX || FAST == FAST_RESID;
+  constexpr bool TWO_OUT = FAST == FAST_ACT_GELU;
   // row layout: this lane's row within a group of 8 rows, and its chunk of the row
   const int rr = lane >> 3, rk = lane & 7;
   // MFMA layout: this lane's row within the 32, half-chunk (4 columns) within a chunk
@@ -596,7 +599,22 @@ __device__ __forceinline__ void epilogue_staged_fn(const GemmArgs& g, const Tile
   const long off_row = (tc.m0 + wm0 + rr) * g.ldc + tc.n0 + wn0 + 8 * rk;     // row layout, first row group
   const bf16_t* aux = reinterpret_cast<const bf16_t*>(g.aux) + tc.batch * g.aux_sb + off_row;
   bf16_t* cp = reinterpret_cast<bf16_t*>(g.C) + tc.batch * g.c_sb + off_row;
+  bf16_t* cp2 = TWO_OUT ? reinterpret_cast<bf16_t*>(g.out2) + tc.batch * g.out2_sb + off_row : nullptr;
   const long ld8 = 8 * g.ldc;
+  // FAST_RESID: the coefficients of this lane's columns in the MFMA layout (chunk k: columns 8 k + 4 mh .. + 3)
+  float lam[8][4];
+  if (FAST == FAST_RESID) {
+    const float* lp = g.lambda ? g.lambda + tc.batch * g.lambda_sb + tc.n0 + wn0 + 4 * mh : nullptr;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      if (lp) {
+        const float4 t = *reinterpret_cast<const float4*>(lp + 8 * k);
+        lam[k][0] = t.x; lam[k][1] = t.y; lam[k][2] = t.z; lam[k][3] = t.w;
+      } else {
+        lam[k][0] = lam[k][1] = lam[k][2] = lam[k][3] = 1.f;
+      }
+    }
+  }
   // staging addresses, row layout: rows rr, rr + 8, rr + 16, rr + 24
   auto row_at = [&](int r) { return stg + r * 128 + ((rk ^ ((r >> 1) & 7)) << 4); };
   unsigned char* const p0 = row_at(rr);
@@ -613,9 +631,23 @@ __device__ __forceinline__ void epilogue_staged_fn(const GemmArgs& g, const Tile
     q.x2 = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(a + 2 * ld8));
     q.x3 = __builtin_nontemporal_load(reinterpret_cast<const uint4v*>(a + 3 * ld8));
   };
+  // 32 rows x 64 columns now in the staging tile (MFMA layout written): read as rows, store whole lines
+  auto flush = [&](bf16_t* c) {
+    __builtin_amdgcn_wave_barrier();
+    const uint4v o0 = *reinterpret_cast<const uint4v*>(p0);
+    const uint4v o1 = *reinterpret_cast<const uint4v*>(p1);
+    const uint4v o2 = *reinterpret_cast<const uint4v*>(p2);
+    const uint4v o3 = *reinterpret_cast<const uint4v*>(p3);
+    __builtin_amdgcn_wave_barrier();      // the next round's writes stay behind these reads
+    __builtin_nontemporal_store(o0, reinterpret_cast<uint4v*>(c));
+    __builtin_nontemporal_store(o1, reinterpret_cast<uint4v*>(c + ld8));
+    __builtin_nontemporal_store(o2, reinterpret_cast<uint4v*>(c + 2 * ld8));
+    __builtin_nontemporal_store(o3, reinterpret_cast<uint4v*>(c + 3 * ld8));
+  };
   auto round = [&](auto ic, const Quad16& q) {
     constexpr int i = decltype(ic)::value;
     uint2 auxm[8];
+    uint2 second[8];        // TWO_OUT: the second output's values, packed, until the first has left the staging tile
     if (HAS_AUX) {
       *reinterpret_cast<uint4v*>(p0) = q.x0;
       *reinterpret_cast<uint4v*>(p1) = q.x1;
@@ -639,22 +671,29 @@ __device__ __forceinline__ void epilogue_staged_fn(const GemmArgs& g, const Tile
           for (int x = 0; x < 4; ++x) {
             if (FAST == FAST_MUL_AUX) v[x] *= t[x];
             else if (FAST == FAST_ADD_AUX) v[x] += t[x];
+            else if (FAST == FAST_RESID) v[x] = fmaf(lam[4 * j + qd][x], t[x], v[x]);
             else v[x] *= (1.f - t[x] * t[x]);
           }
         }
+        if (TWO_OUT) {
+          float dz[4];
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            const float a = v[x];
+            const float phi = 0.5f * (1.0f + erff(a * 0.70710678118654752440f));
+            v[x] = a * phi;
+            dz[x] = phi + a * __expf(-0.5f * a * a) * 0.39894228040143267794f;
+          }
+          second[4 * j + qd] = make_uint2(pack2(dz[0], dz[1]), pack2(dz[2], dz[3]));
+        }
         *reinterpret_cast<uint2*>(m_base + (((4 * j + qd) ^ m_sw) << 4)) = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
       }
-    __builtin_amdgcn_wave_barrier();
-    const uint4v o0 = *reinterpret_cast<const uint4v*>(p0);
-    const uint4v o1 = *reinterpret_cast<const uint4v*>(p1);
-    const uint4v o2 = *reinterpret_cast<const uint4v*>(p2);
-    const uint4v o3 = *reinterpret_cast<const uint4v*>(p3);
-    __builtin_amdgcn_wave_barrier();      // the next round's writes stay behind these reads
-    bf16_t* c = cp + (long)(32 * i) * g.ldc;
-    __builtin_nontemporal_store(o0, reinterpret_cast<uint4v*>(c));
-    __builtin_nontemporal_store(o1, reinterpret_cast<uint4v*>(c + ld8));
-    __builtin_nontemporal_store(o2, reinterpret_cast<uint4v*>(c + 2 * ld8));
-    __builtin_nontemporal_store(o3, reinterpret_cast<uint4v*>(c + 3 * ld8));
+    flush(cp + (long)(32 * i) * g.ldc);
+    if (TWO_OUT) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k) *reinterpret_cast<uint2*>(m_base + ((k ^ m_sw) << 4)) = second[k];
+      flush(cp2 + (long)(32 * i) * g.ldc);
+    }
   };
   Quad16 qa = {}, qb = {};
   if (HAS_AUX) { fetch(qa, 0); fetch(qb, 1); }
@@ -665,8 +704,8 @@ __device__ __forceinline__ void epilogue_staged_fn(const GemmArgs& g, const Tile
   round(std::integral_constant<int, 2>(), qa);
   round(std::integral_constant<int, 3>(), qb);
 }
-template <int FAST> struct StagedOps {   // vector-memory operations per wave of one epilogue
-  static constexpr int value = FAST == FAST_STORE_F32 ? 32 : FAST == FAST_STORE ? 16 : 32;
+template <int FAST> struct StagedOps {   // vector-memory operations per wave of one epilogue (a lower bound: the
+  static constexpr int value = FAST == FAST_STORE_F32 ? 32 : FAST == FAST_STORE ? 16 : 32;   // waits stay safe with more)
 };
 
 constexpr int LEAN_NST = 4;                              // 4 x 32 KB, + 4 KB per wave for the epilogue
@@ -964,7 +1003,9 @@ bool launch_gemm_mfma(const GemmArgs& g, hipStream_t s, hipError_t* err) {
     if (lean && plain && (g.c_is_f32 || g.split_k > 1)) *err = launch_lean<false, false, FAST_STORE_F32>(g, s);
     else *err = launch_variant<false, false, false>(g, s);
   } else if (a_kc && b_kc) {             // forward; VJP contractions against transposed weights
-    if (lean && bf16_out && g.mode == EPI_STORE) *err = launch_lean<true, true, FAST_STORE>(g, s);
+    if (lean && bf16_out && g.mode == EPI_ACT_GELU && g.out2) *err = launch_lean<true, true, FAST_ACT_GELU>(g, s);
+    else if (lean && bf16_out && g.mode == EPI_RESID && g.aux && !g.lambda_mn) *err = launch_lean<true, true, FAST_RESID>(g, s);
+    else if (lean && bf16_out && g.mode == EPI_STORE) *err = launch_lean<true, true, FAST_STORE>(g, s);
     else if (lean && bf16_out && g.mode == EPI_MUL_AUX) *err = launch_lean<true, true, FAST_MUL_AUX>(g, s);
     else if (lean && bf16_out && g.mode == EPI_MUL_1MZ2) *err = launch_lean<true, true, FAST_MUL_1MZ2>(g, s);
     else if (lean && bf16_out && g.mode == EPI_ADD_AUX) *err = launch_lean<true, true, FAST_ADD_AUX>(g, s);
