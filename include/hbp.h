@@ -194,13 +194,15 @@ hbp_status hbp_workspace_size(const hbp_desc* desc, size_t* bytes);
  * calls need) without touching the device. */
 hbp_status hbp_check(const hbp_desc* desc, const hbp_buffers* bufs);
 
-/* Support: runs the stack forward from x[0] and fills x[1..L], y, rinv, z, dphi. */
+/* Runs the stack forward from x[0] and fills x[1..L], y, rinv, z, dphi (the cells: z and lambda; HBP_TRANSFORMER: also
+ * qkv, attn_o, lse): the state the backward calls read.  Part of hbp_train_step; otherwise support. */
 hbp_status hbp_forward(const hbp_desc* desc, hbp_buffers* bufs, void* stream);
 
 /* g := w^k, the sum of all gradient paths through at most k block Jacobians
  * (Theorem 2; with desc->gamma > 0, of the re-split pair J + gamma K and
  * (1 - gamma) K).  k = 0 gives the residual-path-only estimate; k >= L is exact.
- * Reads W1, W2, lambda, y (or x), rinv, z, dphi, e; writes g and the workspace. */
+ * Reads W1, W2, lambda, y (or x), rinv, z, dphi, e (HBP_TRANSFORMER: also Wqkv, Wo, qkv, attn_o, lse); writes g and the
+ * workspace. */
 hbp_status hbp_backward(const hbp_desc* desc, int k, hbp_buffers* bufs, void* stream);
 
 /* The initial estimate alone, g := w^0 = CumSumProd(e, K) (Theorem 2; K scaled by 1 - gamma), by a
@@ -239,7 +241,8 @@ hbp_status hbp_exact_backward(const hbp_desc* desc, hbp_buffers* bufs, void* str
 /* The parameter gradients from the state-gradient estimate currently in bufs.g (sentence after Theorem 2:
  * dL/dtheta_l = w_{l+1} . d f_l / d theta_l, with the current estimate w^k in place of the exact gradient):
  * da_l = (g_{l+1} W2_l) (.) act'(a_l); dW2_l = sum_n g_{l+1}[n]^T z_l[n];
- * dW1_l = sum_n da_l[n]^T y_l[n]; dU = sum da^T xin.  Shared weights sum over l too.  Long contractions over
+ * dW1_l = sum_n da_l[n]^T y_l[n]; dU = sum da^T xin; attention sub-blocks: dWo = sum_n g[n]^T o[n] and
+ * dWqkv = sum_n d[q|k|v][n]^T y[n].  Shared weights sum over l too.  Long contractions over
  * tokens are computed in shares whose partial sums a second kernel adds in a fixed order (bitwise repeatable). */
 hbp_status hbp_param_grads(const hbp_desc* desc, hbp_buffers* bufs, void* stream);
 
