@@ -129,6 +129,16 @@ CASES = {
     "tfm_loss_all": synth.scaled(W["gpt2_paper"], name="tfm_loss_all", L=4, N=96, seq_len=48, d=128, heads=2,
                                  d_ff=256, norm="none", w2_scale=0.5, loss_every_state=True, lam="uniform",
                                  lam_lo=0.8, lam_hi=1.0, ks=(0, 1, 3)),
+    # sequences of one token (the softmax is 1: o = v), of exactly one tile, and of five tiles (two workgroups of
+    # query tiles, the second with one live wavefront) with and without the causal mask
+    "tfm_one_token": synth.scaled(W["gpt2_paper"], name="tfm_one_token", L=4, N=24, seq_len=1, d=128, heads=2, d_ff=128,
+                                  w1_std=0.0, w2_std=0.0, w2_scale=0.6, ks=(0, 2)),
+    "tfm_one_tile": synth.scaled(W["gpt2_paper"], name="tfm_one_tile", L=2, N=96, seq_len=32, d=64, heads=1, d_ff=128,
+                                 w1_std=0.0, w2_std=0.0, w2_scale=0.6, ks=(1, 2)),
+    "tfm_five_tiles": synth.scaled(W["gpt2_paper"], name="tfm_five_tiles", L=4, N=320, seq_len=160, d=192, heads=3,
+                                   d_ff=256, w1_std=0.0, w2_std=0.0, w2_scale=0.6, ks=(1, 3)),
+    "tfm_five_tiles_bidir": synth.scaled(W["gpt2_paper"], name="tfm_five_tiles_bidir", L=2, N=298, seq_len=149, d=128,
+                                         heads=2, d_ff=128, w1_std=0.0, w2_std=0.0, w2_scale=0.6, causal=False, ks=(1, 2)),
     "tfm_splitk": synth.scaled(W["gpt2_paper"], name="tfm_splitk", L=2, N=8192, seq_len=128, d=128, heads=2,
                                d_ff=256, w1_std=0.0, w2_std=0.0, w2_scale=0.6, ks=(0, 2)),
     # the LSTM cell (state [c | h]; the contraction's result lands in the hidden half of v with the full row stride)
@@ -204,7 +214,7 @@ CASES = {
 SPLITK_CASES = ["mlp_splitk", "mlp_splitk_odd", "rnn_splitk", "rnn_splitk_odd", "gated_splitk", "lstm_splitk",
                 "gru_splitk"]       # (tfm_splitk is listed with the transformer cases)
 TFM_CASES = ["tfm_f32", "tfm_f32_bidir", "tfm_small", "tfm_bidir", "tfm_heads_32", "tfm_aligned", "tfm_loss_all",
-             "tfm_splitk"]
+             "tfm_splitk", "tfm_one_token", "tfm_one_tile", "tfm_five_tiles", "tfm_five_tiles_bidir"]
 GRU_CASES = ["gru_small", "gru_f32", "gru_long", "gru_width_72", "gru_aligned", "gru_last_loss"]
 
 
