@@ -38,7 +38,8 @@ and erf are the only library steps; no blocking, fusion or reordering):
              its two sub-layers, so that L = 2 x layers: block l even is multi-head self-attention on the normed state,
              [q | k | v] = norm(x) Wqkv^T, per sequence and head softmax(q k^T / sqrt(dh)) v (keys after the query
              masked out when causal), heads side by side, times Wo^T; block l odd is the two-matrix MLP.  The residual
-             function is r(x, z) = lam (.) x + z as for 'mlp' (the decomposition with gamma applies as for any kind);
+             function is r(x, z) = lam (.) x + z as for 'mlp' (the decomposition with gamma applies as for any kind;
+             post = 'rms' with norm = 'none' gives the post-norm transformer of the appendix's RoBERTa paragraph);
              a token's block output now depends on the other tokens of its sequence, so J couples the rows of a state.
   exact BP   Section "Backpropagation as a system of equations" and the first
              line of the proof of Theorem 1 (chain rule through J + K).
@@ -139,7 +140,7 @@ class Stack:
             assert self.W1.ndim == 3 and self.W2.ndim == 3
             self.L = self.W1.shape[0]
         elif self.kind == "transformer":
-            assert self.W1.ndim == 3 and self.W2.ndim == 3 and self.post == "none"
+            assert self.W1.ndim == 3 and self.W2.ndim == 3 and self.post in ("none", "rms")
             self.Wqkv = np.asarray(self.Wqkv, dtype=F64)
             self.Wo = np.asarray(self.Wo, dtype=F64)
             assert self.Wqkv.shape == (self.W1.shape[0], 3 * self.W2.shape[1], self.W2.shape[1])
@@ -295,11 +296,11 @@ def forward(st: Stack, x0: np.ndarray, xin: Optional[np.ndarray] = None) -> Dict
             qkv[l] = y[l] @ st.w1(l).T
             o[l] = attention(st, qkv[l])
             x[l + 1] = st.lam_row(l) * x[l] + o[l] @ st.w2(l).T
-            continue
-        a[l] = y[l] @ st.w1(l).T
-        if st.kind == "rnn":
-            a[l] += np.asarray(xin[l], dtype=F64) @ st.U.T
-        x[l + 1] = st.lam_row(l) * x[l] + act_fn(st.act, a[l]) @ st.w2(l).T
+        else:
+            a[l] = y[l] @ st.w1(l).T
+            if st.kind == "rnn":
+                a[l] += np.asarray(xin[l], dtype=F64) @ st.U.T
+            x[l + 1] = st.lam_row(l) * x[l] + act_fn(st.act, a[l]) @ st.w2(l).T
         if st.post == "relu":
             mask[l] = (x[l + 1] > 0.0).astype(F64)
             x[l + 1] = np.maximum(x[l + 1], 0.0)

@@ -862,23 +862,24 @@ def test_gru_cell_parameter_gradients_by_finite_differences():
 
 
 # ---------------------------------------------------------------- attention sub-blocks (appendix, GPT-2 paragraph)
-def small_transformer(layers=2, d=8, dff=12, T=4, heads=2, causal=True, norm="rms", lam="rand", seed=0):
+def small_transformer(layers=2, d=8, dff=12, T=4, heads=2, causal=True, norm="rms", lam="rand", seed=0, post="none"):
     r = np.random.default_rng(seed)
     W1 = r.standard_normal((layers, dff, d)) / math.sqrt(d)
     W2 = r.standard_normal((layers, d, dff)) / math.sqrt(dff)
     Wqkv = r.standard_normal((layers, 3 * d, d)) / math.sqrt(d) * 1.5
     Wo = r.standard_normal((layers, d, d)) / math.sqrt(d)
     lm = None if lam == "one" else r.uniform(0.5, 1.1, (2 * layers, d))
-    return O.Stack("transformer", "gelu", norm, W1, W2, lam=lm, Wqkv=Wqkv, Wo=Wo, T=T, heads=heads, causal=causal)
+    return O.Stack("transformer", "gelu", norm, W1, W2, lam=lm, Wqkv=Wqkv, Wo=Wo, T=T, heads=heads, causal=causal, post=post)
 
 
-@pytest.mark.parametrize("causal,norm", [(True, "rms"), (False, "rms"), (True, "none")])
-def test_transformer_stack_against_torch_autograd(causal, norm):
+@pytest.mark.parametrize("causal,norm,post", [(True, "rms", "none"), (False, "rms", "none"), (True, "none", "none"),
+                                              (False, "none", "rms"), (True, "none", "rms")])
+def test_transformer_stack_against_torch_autograd(causal, norm, post):
     """The alternating attention / MLP stack written with torch fp64 ops, the attention itself by torch's own
     scaled_dot_product_attention, differentiated by autograd: states, state gradients, all four weight gradients."""
     r = np.random.default_rng(31)
     B, T, heads = 3, 5, 2
-    st = small_transformer(layers=2, d=8, dff=12, T=T, heads=heads, causal=causal, norm=norm)
+    st = small_transformer(layers=2, d=8, dff=12, T=T, heads=heads, causal=causal, norm=norm, post=post)
     d = st.d
     x0 = r.standard_normal((B * T, d))
     c = r.standard_normal((st.L + 1, B * T, d))
@@ -897,10 +898,16 @@ def test_transformer_stack_against_torch_autograd(causal, norm):
             nxt = lam[l] * x + o.permute(0, 2, 1, 3).reshape(B * T, d) @ Wo[l // 2].T
         else:
             nxt = lam[l] * x + torch.nn.functional.gelu(y @ W1[l // 2].T) @ W2[l // 2].T
+        if post == "rms":      # post-norm: the norm after the residual sum
+            nxt = nxt / torch.sqrt((nxt * nxt).mean(dim=1, keepdim=True) + st.eps)
         nxt.retain_grad()
         xs.append(nxt)
     loss = sum((torch.tensor(c[l]) * xs[l]).sum() for l in range(st.L + 1))
     loss.backward()
+    for k in (0, 1, st.L):     # the iteration ends at the exact gradient for this residual function too
+        w = O.hbp_backward(st, sv, c, k, gamma=0.8 if post == "rms" else 0.0)
+        if k == st.L:
+            np.testing.assert_allclose(w, G, rtol=1e-9, atol=1e-11)
     for l in range(st.L + 1):
         np.testing.assert_allclose(sv["x"][l], xs[l].detach().numpy(), rtol=1e-11, atol=1e-12)
         np.testing.assert_allclose(G[l], xs[l].grad.numpy(), rtol=1e-9, atol=1e-11)
