@@ -149,7 +149,7 @@ def transformer_work(w, k):
     b2m = lambda nb: nb * (N * dff * s + N * d * s + e_aux + d * dff * s)
     b2a = lambda nb: nb * (N * 3 * d * s + N * d * s + e_aux + 3 * d * d * s)
     S = float(L) * N * d
-    streams_in = 1 + (1 if w.norm == "rms" else 0) + (1 if (w.loss_every_state and w.norm == "rms") else 0)
+    streams_in = 1 + (1 if (w.norm == "rms" or w.post == "rms") else 0) + (1 if (w.loss_every_state and w.norm == "rms") else 0)
     return {
         "vjp1": mlp_f * (sum(n_mlp) + Lh) + wo_f * (sum(n_attn) + Lh),
         "vjp2": mlp_f * sum(n_mlp) + qkv_f * sum(n_attn),
@@ -251,7 +251,7 @@ def cpu_baseline(w, k, budget_tokens):
     inp = synth.make_inputs(w, tokens=slice(0, n))
     if w.kind == "transformer":      # n is a whole number of sequences
         st = O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], eps=w.eps, Wqkv=inp["Wqkv"],
-                     Wo=inp["Wo"], T=w.seq_len, heads=w.heads, causal=w.causal)
+                     Wo=inp["Wo"], T=w.seq_len, heads=w.heads, causal=w.causal, post=w.post)
     elif w.kind in ("gated", "lstm", "gru"):
         st = O.Stack(w.kind, w.act, w.norm, inp["W1"], None, U=inp["U"], L=w.L)
     else:
@@ -508,7 +508,7 @@ def main():
         n = args.cpu_tokens or {"mlp_small_f32": 128, "resnet_like": 8192, "resnet_postact": 8192, "postnorm_mlp": 2048, "transformer_mlp": 2048,
                                 "deep_large": 256, "gated_rnn": 16, "gated_rnn_contractive": 16,
                                 "gated_rnn_token_gates": 16, "gru_cell": 16, "gru_std_cell": 12, "lstm_cell": 8,
-                                "gpt2_paper": 16 * 256, "transformer_attn": 1024}.get(w.name, 64)
+                                "gpt2_paper": 16 * 256, "transformer_attn": 1024, "roberta_like": 8 * 128}.get(w.name, 64)
         out["cpu_baseline"] = cpu_baseline(w, k, n)
 
     def finite(o):   # JSON has no NaN/Infinity: overflowed error figures become null

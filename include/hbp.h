@@ -97,7 +97,8 @@ typedef enum { HBP_F32 = 0, HBP_BF16 = 1 } hbp_dtype;
  * uses gamma = 0.2 on this stack).  Shapes: W1 [L/2,d_ff,d], W2 [L/2,d,d_ff], Wqkv [L/2,3d,d], Wo [L/2,d,d]; z, dphi
  * [L/2,N,d_ff]; qkv [L/2,N,3d], attn_o [L/2,N,d] (the attention's output before Wo) and lse [L/2, N heads] are
  * written by hbp_forward and read by the backward calls; x, y, rinv, lambda, e, g are per state / block as for
- * HBP_MLP.  post = HBP_POST_NONE, d_in = 0; dh a multiple of 8 (bf16 with dh = 64 runs on the matrix cores, any other
+ * HBP_MLP.  post = HBP_POST_NONE, or HBP_POST_RMS with norm = HBP_NORM_NONE (post-norm layers, the RoBERTa paragraph of the
+ * appendix: use gamma around 0.8); d_in = 0; dh a multiple of 8 (bf16 with dh = 64 runs on the matrix cores, any other
  * case on plain kernels that need seq_len <= 8192). */
 typedef enum { HBP_MLP = 0, HBP_RNN = 1, HBP_GATED = 2, HBP_LSTM = 3, HBP_GRU = 4, HBP_TRANSFORMER = 5 } hbp_kind;
 /* GELU is the exact erf form a*Phi(a); IDENTITY makes blocks linear (tests). */
@@ -119,7 +120,8 @@ typedef enum { HBP_POST_NONE = 0, HBP_POST_RELU = 1, HBP_POST_RMS = 2 } hbp_post
  * no norm of its own: norm = HBP_NORM_NONE).  With rho_l = 1/rms of the sum (one number per token, written to rinv by
  * hbp_forward): K_l = diag(lambda_l rho_l), J_l = the layer's Jacobian minus K_l.  As with RELU the backward calls
  * keep g[l] (l >= 1) taken through the norm that made x_l: g[l] = rho_{l-1} (G_l - x_l mean(G_l (.) x_l)), the
- * gradient with respect to the sum; g[0] = dL/dx_0.  HBP_MLP, lambda ONE or CHANNEL, d <= 4096 (2048 with gamma > 0).
+ * gradient with respect to the sum; g[0] = dL/dx_0.  HBP_MLP or HBP_TRANSFORMER, lambda ONE or CHANNEL, d <= 4096 (2048 with
+ * gamma > 0).
  * On deep post-norm stacks the plain split (gamma = 0) diverges with k, as the paper reports for transformers: use
  * gamma around 0.5 .. 0.8. */
 

@@ -150,7 +150,7 @@ hbp_status check_desc(const hbp_desc* d) {
   if (tfm(d)) {
     if (d->L % 2 || d->heads <= 0 || d->seq_len <= 0 || (d->causal != 0 && d->causal != 1)) return HBP_E_INVALID_ARG;
     if (d->N % d->seq_len || d->d % d->heads) return HBP_E_INVALID_ARG;
-    if (d->post != HBP_POST_NONE || head_w(d) % 8) return HBP_E_UNSUPPORTED;
+    if (d->post == HBP_POST_RELU || head_w(d) % 8) return HBP_E_UNSUPPORTED;
     if (!attn_supported(d->dtype, d->seq_len, (int)head_w(d))) return HBP_E_UNSUPPORTED;
   }
   if (d->norm == HBP_NORM_RMS && !(d->eps >= 0.f)) return HBP_E_INVALID_ARG;
@@ -158,7 +158,7 @@ hbp_status check_desc(const hbp_desc* d) {
   if (d->norm == HBP_NORM_RMS && d->d > 4096) return HBP_E_UNSUPPORTED;
   if (!(d->gamma >= 0.f && d->gamma <= 1.f)) return HBP_E_INVALID_ARG;
   if (d->post < HBP_POST_NONE || d->post > HBP_POST_RMS) return HBP_E_INVALID_ARG;
-  if (d->post != HBP_POST_NONE && d->kind != HBP_MLP) return HBP_E_UNSUPPORTED;
+  if (d->post != HBP_POST_NONE && d->kind != HBP_MLP && !(tfm(d) && d->post == HBP_POST_RMS)) return HBP_E_UNSUPPORTED;
   if (d->post == HBP_POST_RELU && d->gamma != 0.f) return HBP_E_UNSUPPORTED;
   if (d->post == HBP_POST_RMS && (d->norm != HBP_NORM_NONE || d->lambda_kind == HBP_LAMBDA_TOKEN || d->d > 4096 ||
                                   (d->gamma != 0.f && d->d > 2048)))
@@ -725,6 +725,10 @@ hbp_status hbp_forward(const hbp_desc* d, hbp_buffers* b, void* stream) {
       ga.lambda = d->lambda_kind == HBP_LAMBDA_CHANNEL ? reinterpret_cast<const float*>(b->lambda) + l * D : nullptr;
       ga.lambda_mn = d->lambda_kind == HBP_LAMBDA_TOKEN ? at(b->lambda, xo) : nullptr;
       HBP_RUN(run_gemm(d, ga, s, HBP_PROF_FORWARD));
+      if (d->post == HBP_POST_RMS) {     // post-norm: the norm after the residual sum, as for the MLP sub-blocks below
+        ProfScope ps(HBP_PROF_FORWARD, s);
+        HBP_TRY(launch_rmsnorm_inplace(d->dtype, at(b->x, xo + (size_t)N * D * es), b->rinv + l * N, N, D, d->eps, s));
+      }
       continue;
     }
     if (gru(d)) {

@@ -98,6 +98,11 @@ WORKLOADS["gpt2_paper"] = Workload("gpt2_paper", "transformer", "bf16", "gelu", 
 WORKLOADS["transformer_attn"] = Workload("transformer_attn", "transformer", "bf16", "gelu", "rms", L=24, N=16 * 1024,
                                          d=1024, d_ff=4096, w1_std=0.02, w2_std=0.02, w2_scale=1.0 / np.sqrt(24.0),
                                          heads=16, seq_len=1024, causal=True, gamma=0.2, ks=(1, 2, 3))
+# The paper's RoBERTa configuration (12 post-norm layers, hidden 768, 12 heads, inputs of 128 tokens, batch 32; run with
+# gamma = 0.8), random weights, RMS norm after each residual sum, no biases
+WORKLOADS["roberta_like"] = Workload("roberta_like", "transformer", "bf16", "gelu", "none", L=24, N=32 * 128, d=768,
+                                     d_ff=3072, w1_std=0.02, w2_std=0.02, heads=12, seq_len=128, causal=False,
+                                     post="rms", gamma=0.8, ks=(1, 2, 3))
 # contractive variant of the RNN (recurrent weights x 0.25): the stack as
 # specified is chaotic, so exact BPTT gradients overflow over 4096 steps.
 WORKLOADS["gated_rnn_contractive"] = replace(WORKLOADS["gated_rnn"], name="gated_rnn_contractive",

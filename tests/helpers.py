@@ -16,7 +16,7 @@ def oracle_stack(w: synth.Workload, inp) -> O.Stack:
         return O.Stack(w.kind, w.act, w.norm, inp["W1"], None, U=inp["U"], L=w.L)
     if w.kind == "transformer":
         return O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], eps=w.eps, Wqkv=inp["Wqkv"],
-                       Wo=inp["Wo"], T=w.seq_len, heads=w.heads, causal=w.causal)
+                       Wo=inp["Wo"], T=w.seq_len, heads=w.heads, causal=w.causal, post=w.post)
     return O.Stack(w.kind, w.act, w.norm, inp["W1"], inp["W2"], lam=inp["lam"], U=inp["U"], eps=w.eps, L=w.L,
                    post=w.post)
 

@@ -111,7 +111,8 @@ def test_transformer_descriptor_rules():
         assert B.lib().hbp_workspace_size(C.byref(_desc(**{**ok, **bad})), C.byref(n)) == 1, bad
     # heads must be whole 16-byte vectors; a ReLU or norm after the sum is not built for this kind; the plain
     # kernels (fp32, or heads other than 64 wide) hold a row of scores in LDS
-    for bad in (dict(d=96, heads=8), dict(post="relu"), dict(dtype="f32", N=16384, seq_len=16384),
+    assert B.lib().hbp_workspace_size(C.byref(_desc(**{**ok, "post": "rms", "norm": "none"})), C.byref(n)) == 0
+    for bad in (dict(d=96, heads=8), dict(post="relu"), dict(post="rms"), dict(dtype="f32", N=16384, seq_len=16384),
                 dict(heads=4, N=16384, seq_len=16384)):
         assert B.lib().hbp_workspace_size(C.byref(_desc(**{**ok, **bad})), C.byref(n)) == 2, bad
     assert B.lib().hbp_workspace_size(C.byref(_desc(**{**ok, "N": 16384, "seq_len": 16384})), C.byref(n)) == 0

@@ -65,12 +65,13 @@ def _projection_check(p, w, inp, tol):
         # three layers; the gradient of [q | k | v] by torch's autograd through torch's own attention, in fp64, on the
         # library's saved q, k, v and its do = g Wo
         Bn, T, Hn, d = w.N // w.seq_len, w.seq_len, w.heads, w.d
+        ys = p.y if p.y is not None else p.x          # the blocks' input: the normed state, or the state itself
         for j in sorted({0, L // 4, L // 2 - 1}):
-            gm, zl, ym = p.g[2 * j + 2].double(), p.z[j].double(), p.y[2 * j + 1].double()
+            gm, zl, ym = p.g[2 * j + 2].double(), p.z[j].double(), ys[2 * j + 1].double()
             da = (gm @ p.W2[j].double()) * p.dphi[j].double()
             check(f"dW2[{j}]", p.dW2[j], gm, zl)
             check(f"dW1[{j}]", p.dW1[j], da, ym)
-            ga, ya = p.g[2 * j + 1].double(), p.y[2 * j].double()
+            ga, ya = p.g[2 * j + 1].double(), ys[2 * j].double()
             check(f"dWo[{j}]", p.dWo[j], ga, p.attn_o[j].double())
             qkv = p.qkv[j].double().reshape(Bn, T, 3, Hn, d // Hn).permute(2, 0, 3, 1, 4).clone().requires_grad_(True)
             o = torch.nn.functional.scaled_dot_product_attention(qkv[0], qkv[1], qkv[2], is_causal=w.causal)
@@ -134,10 +135,19 @@ def _run(B, w, ks, rows_count, shared_state=False, check_exact=True):
     if shared_state:
         # the oracle's forward state of the sampled rows, rounded to storage, replaces the library's
         sv = H.oracle_saved_rounded(w, sv)
+        tfm = w.kind == "transformer"
+        put = lambda t, a: t.__setitem__((slice(None), rows_t), torch.from_numpy(np.ascontiguousarray(a, np.float32)).to(t.device).to(t.dtype))
         for name, t in (("x", p.x), ("y", p.y), ("z", p.z), ("dphi", p.dphi),
                         ("rpost" if w.post == "rms" else "rinv", p.rinv)):
             if t is not None:
-                t[:, rows_t] = torch.from_numpy(sv[name].astype(np.float32)).to(t.device).to(t.dtype)
+                put(t, sv[name][1::2] if (tfm and name in ("z", "dphi")) else sv[name])
+        if tfm:      # the attention sub-blocks' saved state, and their row statistics per (sequence, head, position)
+            put(p.qkv, sv["qkv"][0::2])
+            put(p.attn_o, sv["o"][0::2])
+            seqs = torch.from_numpy(rows[::w.seq_len] // w.seq_len).to(p.x.device)
+            stats = np.stack([H.attn_row_stats(st, sv["qkv"][l]) for l in range(0, w.L, 2)])
+            lse = p.lse.view(w.L // 2, w.N // w.seq_len, w.heads, w.seq_len)
+            lse[:, seqs] = torch.from_numpy(stats.reshape(w.L // 2, len(seqs), w.heads, w.seq_len).astype(np.float32)).to(lse.device)
         if p.mask is not None:
             bits = np.packbits(sv["mask"].astype(np.uint8), axis=-1, bitorder="little")
             p.mask[:, rows_t] = torch.from_numpy(bits).to(p.mask.device)
@@ -220,6 +230,14 @@ def test_gpt2_paper_full(B):
     # the paper's GPT-2 configuration whole (128 sequences of 256 tokens); the oracle recomputes the last sequence and
     # three others
     _run(B, W["gpt2_paper"], ks=(1, 3), rows_count=3)
+
+
+@pytest.mark.timeout(300)
+def test_roberta_like_full_shared_state(B):
+    # 12 post-norm layers at width 768, 12 heads, 32 sequences of 128 tokens, not causal, gamma = 0.8; the oracle
+    # recomputes the last sequence and two others; as for the post-norm MLP stack the backward is compared on the
+    # oracle's forward state of those sequences
+    _run(B, W["roberta_like"], ks=(1, 3), rows_count=2, shared_state=True)
 
 
 @pytest.mark.timeout(300)

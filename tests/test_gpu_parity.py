@@ -139,6 +139,13 @@ CASES = {
                                    d_ff=256, w1_std=0.0, w2_std=0.0, w2_scale=0.6, ks=(1, 3)),
     "tfm_five_tiles_bidir": synth.scaled(W["gpt2_paper"], name="tfm_five_tiles_bidir", L=2, N=298, seq_len=149, d=128,
                                          heads=2, d_ff=128, w1_std=0.0, w2_std=0.0, w2_scale=0.6, causal=False, ks=(1, 2)),
+    # post-norm transformer layers (the norm after each residual sum), run with the gamma split they need
+    "tfm_postnorm_f32": synth.scaled(W["gpt2_paper"], name="tfm_postnorm_f32", dtype="f32", L=4, N=36, seq_len=12, d=32,
+                                     heads=2, d_ff=64, norm="none", post="rms", w1_std=0.0, w2_std=0.0, w2_scale=0.7,
+                                     causal=False, gamma=0.8, ks=(0, 1, 2, 4)),
+    "tfm_postnorm": synth.scaled(W["gpt2_paper"], name="tfm_postnorm", L=6, N=150, seq_len=50, d=128, heads=2, d_ff=256,
+                                 norm="none", post="rms", w1_std=0.0, w2_std=0.0, w2_scale=0.6, causal=False, gamma=0.8,
+                                 ks=(0, 1, 3, 6)),
     "tfm_splitk": synth.scaled(W["gpt2_paper"], name="tfm_splitk", L=2, N=8192, seq_len=128, d=128, heads=2,
                                d_ff=256, w1_std=0.0, w2_std=0.0, w2_scale=0.6, ks=(0, 2)),
     # the LSTM cell (state [c | h]; the contraction's result lands in the hidden half of v with the full row stride)
@@ -215,6 +222,7 @@ SPLITK_CASES = ["mlp_splitk", "mlp_splitk_odd", "rnn_splitk", "rnn_splitk_odd", 
                 "gru_splitk"]       # (tfm_splitk is listed with the transformer cases)
 TFM_CASES = ["tfm_f32", "tfm_f32_bidir", "tfm_small", "tfm_bidir", "tfm_heads_32", "tfm_aligned", "tfm_loss_all",
              "tfm_splitk", "tfm_one_token", "tfm_one_tile", "tfm_five_tiles", "tfm_five_tiles_bidir"]
+TFM_POSTNORM = ["tfm_postnorm_f32", "tfm_postnorm"]
 GRU_CASES = ["gru_small", "gru_f32", "gru_long", "gru_width_72", "gru_aligned", "gru_last_loss"]
 
 
@@ -284,7 +292,7 @@ def _check_backward(B, w, p, st, sv_oracle, inp, tag, exact=True):
                                   "gated_aligned", "lstm_small", "lstm_f32", "lstm_long", "lstm_width_80",
                                   "lstm_aligned", "ragged_tokens", "postnorm_f32", "postnorm_small",
                                   "gated_last_loss", "lstm_last_loss", "odd_widths"] + SPLITK_CASES + GRU_CASES
-                         + TFM_CASES)
+                         + TFM_CASES + ["tfm_postnorm_f32"])
 def test_backward_end_to_end(B, name):
     """Own forward on each side, then Highway-BP at every k of the case, exact BP
     and the parameter gradients."""
@@ -294,7 +302,7 @@ def test_backward_end_to_end(B, name):
     _check_backward(B, w, p, st, sv, inp, name)
 
 
-@pytest.mark.parametrize("name", TFM_CASES)
+@pytest.mark.parametrize("name", TFM_CASES + TFM_POSTNORM)
 def test_forward_of_the_transformer_stack(B, name):
     """States, the MLP sub-blocks' inner state, [q | k | v], the attention's output and its row statistics."""
     w = CASES[name]
@@ -388,7 +396,7 @@ def test_forward_with_relu_after_the_sum(B, name):
                                   "postact_f32_deep", "gated_small", "gated_long", "lstm_small", "lstm_long",
                                   "postnorm_small", "postnorm_wide", "postnorm_aligned", "postnorm_f32",
                                   "postact_loss_all", "gru_small", "gru_long", "tfm_f32", "tfm_small", "tfm_bidir",
-                                  "tfm_heads_32"])
+                                  "tfm_heads_32"] + TFM_POSTNORM)
 def test_backward_shared_state(B, name):
     """Both backward passes read the same (storage-rounded) forward state."""
     w = CASES[name]
@@ -410,7 +418,7 @@ def test_backward_shared_state(B, name):
                                         ("rnn_token_gates_long", 1.0), ("mlp_token_gates", 0.3),
                                         ("gated_small", 0.3), ("gated_long", 1.0), ("gated_f32", 0.6),
                                         ("lstm_small", 0.3), ("lstm_long", 0.7), ("gru_small", 0.3), ("gru_long", 1.0),
-                                        ("tfm_f32", 0.2), ("tfm_small", 0.2), ("tfm_small", 1.0),
+                                        ("tfm_f32", 0.2), ("tfm_small", 0.2), ("tfm_small", 1.0), ("tfm_postnorm", 0.5),
                                         ("postnorm_small", 0.5), ("postnorm_wide", 0.8), ("postnorm_f32", 1.0),
                                         ("postnorm_aligned", 0.2)])
 def test_gamma_iterates(B, name, gamma):
