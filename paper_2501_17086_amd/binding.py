@@ -286,12 +286,11 @@ class OptimState:
     loss: "object"        # device float: the last loss value
 
     def struct(self) -> hbp_optim_state:
-        three = lambda ts: [_ptr(t) for t in ts[:3]]
-        two = lambda ts: [_ptr(t) for t in (tuple(ts[3:]) + (None, None))[:2]]
-        qo = [x for pair in zip(two(self.master), two(self.m), two(self.v)) for x in pair]   # masterQ, mQ, vQ, masterO, ...
-        return hbp_optim_state(C.sizeof(hbp_optim_state), *three(self.master), *three(self.m), *three(self.v),
-                               _ptr(self.scratch), self.scratch.numel() * self.scratch.element_size(),
-                               qo[0], qo[3], qo[1], qo[4], qo[2], qo[5])
+        ptrs = lambda ts: [_ptr(t) for t in (tuple(ts) + (None,) * 5)[:5]]     # W1, W2, U, Wqkv, Wo
+        ma, m, v = ptrs(self.master), ptrs(self.m), ptrs(self.v)
+        return hbp_optim_state(C.sizeof(hbp_optim_state), *ma[:3], *m[:3], *v[:3], _ptr(self.scratch),
+                               self.scratch.numel() * self.scratch.element_size(),
+                               ma[3], ma[4], m[3], m[4], v[3], v[4])
 
 
 def allocate_optim(p: Problem, adamw: bool, master: bool = True) -> OptimState:

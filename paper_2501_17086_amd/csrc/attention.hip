@@ -179,33 +179,24 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // A wavefront's LDS tile: 32 rows x 64 bf16 (128-byte rows), 16-byte chunk c of row r at chunk c ^ ((r >> 1) & 7).
 __device__ __forceinline__ int swz(int r) { return (r >> 1) & 7; }
 
-// Lanes read what other lanes of the same wavefront wrote (and the next step overwrites what they read): the LDS
-// executes a wavefront's instructions in order, so no wait is needed, only that the compiler keeps the order.
-__device__ __forceinline__ void lds_handover() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 // Addresses: a wavefront-uniform pointer to row 0 of the 32-row tile plus one 32-bit byte offset per lane, which is
 // the same for every whole tile (LaneOffsets, computed once); a tile that runs past the last row re-reads that row
 // instead (CLAMP: rows_left < 32 rows are there).
 struct LaneOffsets {
   unsigned frag;       // fragment loads: row l % 32, 16 bytes at column 8 (l / 32)  (+ 32 bytes per step kk)
-  unsigned tile;       // tile loads: row l / 8 (+ 8 rows per load), 16-byte chunk l % 8
   unsigned ldb;        // row stride in bytes
 };
 __device__ __forceinline__ LaneOffsets lane_offsets(unsigned ldb, int lane) {
   LaneOffsets o;
   o.ldb = ldb;
   o.frag = (unsigned)(lane & 31) * ldb + (unsigned)(lane >> 5) * 16u;
-  o.tile = (unsigned)(lane >> 3) * ldb + (unsigned)(lane & 7) * 16u;
   return o;
 }
 // Tiles reach LDS by direct copies (global_load_lds_dwordx4: 16 bytes per lane from memory to lds_base + 16 lane,
-// no staging registers), issued one step ahead into the other of two buffers.  A copy instruction fills 8 rows of
-// the tile; the chunk swizzle is applied on the memory side: LDS position (row r, slot c) receives chunk c ^ swz(r)
-// of the row.  The compiler sees neither the LDS write nor when it lands: copies_landed() comes before the reads.
+// no staging registers), issued steps ahead into a ring of buffers.  A copy instruction fills 8 rows of the tile; the
+// chunk swizzle is applied on the memory side: LDS position (row r, slot c) receives chunk c ^ swz(r) of the row.  The
+// compiler sees neither the LDS write nor when it lands: a counted wait (copies_in_flight) and the workgroup's barrier
+// (workgroup_handover) come before the reads.
 struct CopyOffsets { unsigned o[4]; };
 __device__ __forceinline__ CopyOffsets copy_offsets(unsigned ldb, int lane) {
   CopyOffsets c;
@@ -228,11 +219,6 @@ __device__ __forceinline__ void copy16_to_lds(unsigned off, const void* sbase_in
 // 4 bytes per lane from a per-lane address to lds_base + 4 lane
 __device__ __forceinline__ void copy4_to_lds(const void* gptr, unsigned lds_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off\n" :: "v"(gptr), "s"(lds_base) : "memory");
-}
-__device__ __forceinline__ void copies_landed() {
-  __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0)
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_sched_barrier(0);
 }
 // 32 rows x 128 bytes from `base` (row 0 of the tile, wave-uniform) to the tile at LDS address lds_tile; CLAMP: only
 // rows_left < 32 rows exist, the others repeat the last one
