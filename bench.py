@@ -48,6 +48,8 @@ MEASURED_TRAFFIC = {
                   "vjp1": 9.441e8, "vjp2": 9.397e8, "dw": 6.041e8, "scan": 6.381e8},
     "gpt2_paper": {"source": "profiles/bench_gpt2_paper_hbm_traffic.txt",
                    "vjp1": 1.770e9, "vjp2": 5.341e8, "dw": 8.934e8, "attn": 1.426e9, "scan": 1.242e9},
+    "roberta_like": {"source": "profiles/bench_roberta_like_hbm_traffic.txt",
+                     "vjp1": 9.033e8, "vjp2": 3.344e8, "dw": 5.582e8, "attn": 4.585e8, "scan": 5.220e8},
     "transformer_attn": {"source": "profiles/bench_transformer_attn_hbm_traffic.txt",
                          "vjp1": 5.507e9, "vjp2": 1.432e9, "dw": 2.181e9, "attn": 5.312e9, "scan": 2.458e9},
     "lstm_cell": {"source": "profiles/bench_lstm_cell_hbm_traffic.txt",
