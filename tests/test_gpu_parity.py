@@ -319,6 +319,20 @@ def test_forward_of_the_transformer_stack(B, name):
     assert np.abs(H.to_np(p.lse) - want).max() < (1e-4 if w.dtype == "f32" else 0.05)
 
 
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("T", [2, 31, 32, 33, 63, 64, 65, 96, 127, 128, 129, 160, 255, 257])
+def test_attention_around_tile_and_workgroup_boundaries(B, T, causal):
+    """One layer pair (attention + MLP) on two sequences of every length around the 32-row tiles and the 128-row
+    workgroup blocks of the attention kernels: forward state, Highway-BP at k = 1, 2 and all parameter gradients."""
+    w = synth.scaled(W["gpt2_paper"], name=f"tfm_T{T}", L=2, N=2 * T, seq_len=T, d=64, heads=1, d_ff=64, w1_std=0.0,
+                     w2_std=0.0, w2_scale=0.6, causal=causal, ks=(1, 2))
+    inp, st, sv, p = _setup(B, w)
+    B.hbp_forward(p)
+    torch.cuda.synchronize()
+    H.assert_close(H.to_np(p.attn_o), sv["o"][0::2], H.TOL[w.dtype], f"{w.name} attention output")
+    _check_backward(B, w, p, st, sv, inp, w.name, exact=False)
+
+
 @pytest.mark.parametrize("name", ["gated_small", "gated_f32", "gated_width_72", "gated_aligned"])
 def test_forward_of_the_gated_cell(B, name):
     """States, both gates ([u | c] side by side) and the residual coefficient 1 - u that the forward writes."""
