@@ -256,6 +256,13 @@ template <int N>
 __device__ __forceinline__ void copies_in_flight() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
+// A value loaded from memory before the loop is made to arrive here.  Without this the compiler places its own counted
+// waits for such loads at their first use inside the loop, and since it does not know of the direct copies, those
+// waits would also drain the copies that were just issued for three steps ahead, on every step.
+template <typename V>
+__device__ __forceinline__ void landed(V& v) {
+  asm volatile("" : "+v"(v));
+}
 // every wavefront of the workgroup has passed its wait: the tile is complete, and the buffer of the step before is free
 __device__ __forceinline__ void workgroup_handover() {
   asm volatile("" ::: "memory");
@@ -330,6 +337,36 @@ __device__ __forceinline__ float dot8(bf16x8 a, bf16x8 b) {
 constexpr int AT_WAVES = 4;    // wavefronts per workgroup: 4 tiles of 32 queries (dk/dv kernel: keys) that share the streamed tiles
 constexpr int AT_NST = 4;      // stages of the ring of streamed tile pairs (8 KB each): copies run AT_NST - 1 steps ahead
 
+// Which (sequence, head) problem and which block of AT_WAVES tiles a workgroup takes.  Consecutive workgroup ids go to
+// the eight XCDs in turn, each with an L2 of its own, and all blocks of one problem stream the same k / v (q / do)
+// tiles.  by_problem (large grids): the blocks of a problem get ids that land on ONE XCD, next to each other in its
+// dispatch order, so they start together, stream in step and the tiles come from memory once per problem instead of
+// once per block.  Otherwise (a grid of a few rounds of workgroups, where the tail decides): every problem's
+// longest block first, then the next longest.  The grid holds 8 ceil(P / 8) nblk workgroups; one whose problem does
+// not exist leaves at once (the whole workgroup, before any barrier).
+struct BlockOf { unsigned p; int slot; bool exists; };
+__device__ __forceinline__ BlockOf block_of(const AttnArgs& a, int nblk) {
+  const unsigned P = (unsigned)(a.seqs * a.heads), id = blockIdx.x;
+  BlockOf b;
+  if (a.by_problem) {
+    const unsigned xcd = id & 7u, turn = id >> 3, j = turn / (unsigned)nblk;
+    b.p = xcd + 8u * j;
+    b.slot = (int)(turn - j * (unsigned)nblk);
+  } else {
+    const unsigned Pr = (P + 7u) & ~7u;
+    b.slot = (int)(id / Pr);
+    b.p = id - (unsigned)b.slot * Pr;
+  }
+  b.exists = b.p < P;
+  return b;
+}
+// grids from about eight rounds of resident workgroups per XCD on: problem by problem
+constexpr long BY_PROBLEM_FROM = 8 * 1024;
+inline long attn_grid(const AttnArgs& a) {
+  const long P = a.seqs * a.heads, nblk = ((a.T + 31) / 32 + AT_WAVES - 1) / AT_WAVES;
+  return 8 * ((P + 7) / 8) * nblk;
+}
+
 // One (sequence, head): wavefront-uniform byte pointers to row 0 of q, k, v (row stride 6 d bytes) and of the
 // d-wide arrays (row stride 2 d bytes), all at the head's 64 columns.
 struct Head {
@@ -367,10 +404,12 @@ __global__ __launch_bounds__(64 * AT_WAVES, 2) void attn_fwd_mfma_kernel(AttnArg
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int T = (int)a.T, nt = (T + 31) >> 5;
   const int nblk = (nt + AT_WAVES - 1) / AT_WAVES;
-  const int blk = nblk - 1 - (int)blockIdx.y;                      // long rows first
+  const BlockOf bo = block_of(a, nblk);
+  if (!bo.exists) return;
+  const int blk = nblk - 1 - bo.slot;                              // long rows first
   const int qt = AT_WAVES * blk + wave;
   const bool live = qt < nt;                                       // a ragged workgroup's spare wavefronts only copy
-  const unsigned p = blockIdx.x;
+  const unsigned p = bo.p;
   const Head hd = head_of(a, p);
   const LaneOffsets lo = lane_offsets((unsigned)(hd.ld * 2), lane);
   const unsigned lds0 = lds_address(smem);
@@ -392,10 +431,12 @@ __global__ __launch_bounds__(64 * AT_WAVES, 2) void attn_fwd_mfma_kernel(AttnArg
       copy_tile_quarter<false>(kb + hd.d * 2, own, lo.ldb, 32, dst + 4096u, wave, lane);
     }
   };
+  for (int kt = 0; kt < AT_NST - 1 && kt < nkt; ++kt) issue(kt);
   bf16x8 fq[4];
 #pragma unroll
   for (int kk = 0; kk < 4; ++kk) fq[kk] = frag_cols_mem<true>(hd.q + (long)(live ? q0 : 0) * lo.ldb, lo, live ? T - q0 : 1, kk, lane);
-  for (int kt = 0; kt < AT_NST - 1 && kt < nkt; ++kt) issue(kt);
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) landed(fq[kk]);
   float16v o0, o1;
 #pragma unroll
   for (int r = 0; r < 16; ++r) { o0[r] = 0.f; o1[r] = 0.f; }
@@ -409,8 +450,15 @@ __global__ __launch_bounds__(64 * AT_WAVES, 2) void attn_fwd_mfma_kernel(AttnArg
     float16v s;
 #pragma unroll
     for (int r = 0; r < 16; ++r) s[r] = 0.f;
+    // every operand read of the step goes out here: those of the second product land while the scores are reduced
+    bf16x8 fk[4];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) s = mfma(frag_cols_lds(tk, kk, lane), fq[kk], s);
+    for (int kk = 0; kk < 4; ++kk) fk[kk] = frag_cols_lds(tk, kk, lane);
+    const bf16x8 v00 = frag_rows_lds(tv, 0, 0, lane), v01 = frag_rows_lds(tv, 0, 1, lane);
+    const bf16x8 v10 = frag_rows_lds(tv, 1, 0, lane), v11 = frag_rows_lds(tv, 1, 1, lane);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) s = mfma(fk[kk], fq[kk], s);
     float sv[16];
     float tmax = -INFINITY;
 #pragma unroll
@@ -434,10 +482,10 @@ __global__ __launch_bounds__(64 * AT_WAVES, 2) void attn_fwd_mfma_kernel(AttnArg
 #pragma unroll
     for (int r = 0; r < 16; ++r) { o0[r] *= alpha; o1[r] *= alpha; }
     const bf16x8 p0 = pack8(sv), p1 = pack8(sv + 8);
-    o0 = mfma(frag_rows_lds(tv, 0, 0, lane), p0, o0);
-    o0 = mfma(frag_rows_lds(tv, 0, 1, lane), p1, o0);
-    o1 = mfma(frag_rows_lds(tv, 1, 0, lane), p0, o1);
-    o1 = mfma(frag_rows_lds(tv, 1, 1, lane), p1, o1);
+    o0 = mfma(v00, p0, o0);
+    o1 = mfma(v10, p0, o1);
+    o0 = mfma(v01, p1, o0);
+    o1 = mfma(v11, p1, o1);
   };
   // tile kt complete and visible to the workgroup, the buffer of tile kt - 1 free and refilled
   auto advance = [&](int kt) __attribute__((always_inline)) {
@@ -468,10 +516,12 @@ __global__ __launch_bounds__(64 * AT_WAVES, 2) void attn_bwd_q_mfma_kernel(AttnA
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int T = (int)a.T, nt = (T + 31) >> 5;
   const int nblk = (nt + AT_WAVES - 1) / AT_WAVES;
-  const int blk = nblk - 1 - (int)blockIdx.y;
+  const BlockOf bo = block_of(a, nblk);
+  if (!bo.exists) return;
+  const int blk = nblk - 1 - bo.slot;
   const int qt = AT_WAVES * blk + wave;
   const bool live = qt < nt;
-  const unsigned p = blockIdx.x;
+  const unsigned p = bo.p;
   const Head hd = head_of(a, p);
   const LaneOffsets lo = lane_offsets((unsigned)(hd.ld * 2), lane);
   const LaneOffsets lw = lane_offsets((unsigned)(hd.d * 2), lane);
@@ -495,7 +545,8 @@ __global__ __launch_bounds__(64 * AT_WAVES, 2) void attn_bwd_q_mfma_kernel(AttnA
       copy_tile_quarter<false>(kb + hd.d * 2, own, lo.ldb, 32, dst + 4096u, wave, lane);
     }
   };
-  const float L2 = a.lse[(long)p * a.T + qc];
+  for (int kt = 0; kt < AT_NST - 1 && kt < nkt; ++kt) issue(kt);
+  float L2 = a.lse[(long)p * a.T + qc];
   bf16x8 fq[4], fdo[4];
   float D = 0.f;
   {
@@ -509,8 +560,10 @@ __global__ __launch_bounds__(64 * AT_WAVES, 2) void attn_bwd_q_mfma_kernel(AttnA
     }
     D += __shfl_xor(D, 32, 64);
     if (live && hh == 0 && qi < T) a.dsum[(long)p * a.T + qi] = D;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) { landed(fq[kk]); landed(fdo[kk]); }
+    landed(L2);
   }
-  for (int kt = 0; kt < AT_NST - 1 && kt < nkt; ++kt) issue(kt);
   float16v dq0, dq1;
 #pragma unroll
   for (int r = 0; r < 16; ++r) { dq0[r] = 0.f; dq1[r] = 0.f; }
@@ -522,11 +575,21 @@ __global__ __launch_bounds__(64 * AT_WAVES, 2) void attn_bwd_q_mfma_kernel(AttnA
     float16v s, dp;
 #pragma unroll
     for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = -D; }      // dp comes out as dP - D
+    // All operand reads of a phase go out before its first product (the compiler's counted waits then let the
+    // products start as their operands arrive), and those of the third product while the scores become dS: a read
+    // issued right before its product would expose the LDS latency a dozen times per step.
+    bf16x8 fk[4], fv[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) { fk[kk] = frag_cols_lds(tk, kk, lane); fv[kk] = frag_cols_lds(tv, kk, lane); }
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      s = mfma(frag_cols_lds(tk, kk, lane), fq[kk], s);
-      dp = mfma(frag_cols_lds(tv, kk, lane), fdo[kk], dp);
+      s = mfma(fk[kk], fq[kk], s);
+      dp = mfma(fv[kk], fdo[kk], dp);
     }
+    const bf16x8 k00 = frag_rows_lds(tk, 0, 0, lane), k01 = frag_rows_lds(tk, 0, 1, lane);
+    const bf16x8 k10 = frag_rows_lds(tk, 1, 0, lane), k11 = frag_rows_lds(tk, 1, 1, lane);
+    __builtin_amdgcn_sched_barrier(0);
     float ds[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -538,10 +601,11 @@ __global__ __launch_bounds__(64 * AT_WAVES, 2) void attn_bwd_q_mfma_kernel(AttnA
       ds[r] = pr * dp[r];
     }
     const bf16x8 d0 = pack8(ds), d1 = pack8(ds + 8);
-    dq0 = mfma(frag_rows_lds(tk, 0, 0, lane), d0, dq0);
-    dq0 = mfma(frag_rows_lds(tk, 0, 1, lane), d1, dq0);
-    dq1 = mfma(frag_rows_lds(tk, 1, 0, lane), d0, dq1);
-    dq1 = mfma(frag_rows_lds(tk, 1, 1, lane), d1, dq1);
+    __builtin_amdgcn_sched_barrier(0);
+    dq0 = mfma(k00, d0, dq0);
+    dq1 = mfma(k10, d0, dq1);
+    dq0 = mfma(k01, d1, dq0);
+    dq1 = mfma(k11, d1, dq1);
   };
   // tile kt complete and visible to the workgroup, the buffer of tile kt - 1 free and refilled
   auto advance = [&](int kt) __attribute__((always_inline)) {
@@ -564,17 +628,19 @@ __global__ __launch_bounds__(64 * AT_WAVES, 2) void attn_bwd_q_mfma_kernel(AttnA
 
 // dk, dv of four tiles of 32 keys (after the dq kernel: reads D)
 template <bool CAUSAL>
-__global__ __launch_bounds__(64 * AT_WAVES, 2) void attn_bwd_kv_mfma_kernel(AttnArgs a) {
+__global__ __launch_bounds__(64 * AT_WAVES, 3) void attn_bwd_kv_mfma_kernel(AttnArgs a) {
   __shared__ __attribute__((aligned(1024))) unsigned char smem[AT_NST][2][4096];   // [stage][q | do]
-  __shared__ __attribute__((aligned(1024))) unsigned char own[AT_WAVES][2][4096];   // [wave][k | v]: the wavefront's own keys
+  __shared__ __attribute__((aligned(1024))) unsigned char own[AT_WAVES][4096];      // [wave]: the v rows of the wavefront's own keys
   __shared__ __attribute__((aligned(256))) float stats[AT_WAVES][AT_NST][64];       // [wave][stage][L2 | D] (a copy per wavefront)
   const int lane = threadIdx.x & 63, hh = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int T = (int)a.T, nt = (T + 31) >> 5;
-  const int blk = (int)blockIdx.y;                                 // causal: early keys see the most queries
+  const BlockOf bo = block_of(a, (nt + AT_WAVES - 1) / AT_WAVES);
+  if (!bo.exists) return;
+  const int blk = bo.slot;                                         // causal: early keys see the most queries
   const int kt = AT_WAVES * blk + wave;
   const bool live = kt < nt;
-  const unsigned p = blockIdx.x;
+  const unsigned p = bo.p;
   const Head hd = head_of(a, p);
   const LaneOffsets lo = lane_offsets((unsigned)(hd.ld * 2), lane);
   const unsigned ldw = (unsigned)(hd.d * 2);
@@ -603,16 +669,17 @@ __global__ __launch_bounds__(64 * AT_WAVES, 2) void attn_bwd_kv_mfma_kernel(Attn
     }
     copy4_to_lds(stat_src + q0 + r, lds_s + (unsigned)b * 256u);
   };
-  {   // the wavefront's own k and v tiles stay in LDS for the whole loop (copied before the ring's first tiles, so they
-      // have landed when the first of those has)
-    const CopyOffsets co = copy_offsets(lo.ldb, lane);
-    const unsigned dst = lds_address(own[wave]);
-    copy_tile<true>(hd.k + (long)k0 * lo.ldb, co, lo.ldb, T - k0, dst, lane);
-    copy_tile<true>(hd.v + (long)k0 * lo.ldb, co, lo.ldb, T - k0, dst + 4096u, lane);
-  }
-  const unsigned char* ok = own[wave][0];
-  const unsigned char* ov = own[wave][1];
+  // The wavefront's own v tile stays in LDS for the whole loop (copied before the ring's first tiles, so it has landed
+  // when the first of those has), its own k tile in registers: LDS and registers then both leave room for three
+  // workgroups on a compute unit.
+  copy_tile<true>(hd.v + (long)k0 * lo.ldb, copy_offsets(lo.ldb, lane), lo.ldb, T - k0, lds_address(own[wave]), lane);
+  const unsigned char* ov = own[wave];
   for (int qt = q_first; qt < q_first + AT_NST - 1 && qt < nt; ++qt) issue(qt);
+  bf16x8 fk[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) fk[kk] = frag_cols_mem<true>(hd.k + (long)k0 * lo.ldb, lo, T - k0, kk, lane);
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) landed(fk[kk]);
   float16v dk0, dk1, dv0, dv1;
 #pragma unroll
   for (int r = 0; r < 16; ++r) { dk0[r] = 0.f; dk1[r] = 0.f; dv0[r] = 0.f; dv1[r] = 0.f; }
@@ -634,7 +701,7 @@ __global__ __launch_bounds__(64 * AT_WAVES, 2) void attn_bwd_kv_mfma_kernel(Attn
     }
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
-      s = mfma(frag_cols_lds(tq, kk, lane), frag_cols_lds(ok, kk, lane), s);
+      s = mfma(frag_cols_lds(tq, kk, lane), fk[kk], s);
       dp = mfma(frag_cols_lds(td, kk, lane), frag_cols_lds(ov, kk, lane), dp);
     }
     __builtin_amdgcn_sched_barrier(0);   // (keeps the second products' operand reads below: fewer live registers)
@@ -694,9 +761,12 @@ bool attn_supported(int dtype, long T, int dh) {
 hipError_t launch_attn_fwd(int dtype, const AttnArgs& a, hipStream_t s) {
   const long P = a.seqs * a.heads;
   if (use_mfma(dtype, a)) {
-    const dim3 grid((unsigned)P, (unsigned)(((a.T + 31) / 32 + AT_WAVES - 1) / AT_WAVES)), block(64 * AT_WAVES);
-    if (a.causal) hipLaunchKernelGGL(attn_fwd_mfma_kernel<true>, grid, block, 0, s, a);
-    else hipLaunchKernelGGL(attn_fwd_mfma_kernel<false>, grid, block, 0, s, a);
+    if (attn_grid(a) > 0x7fffffffL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)attn_grid(a)), block(64 * AT_WAVES);
+    AttnArgs m = a;
+    m.by_problem = attn_grid(a) >= BY_PROBLEM_FROM;
+    if (a.causal) hipLaunchKernelGGL(attn_fwd_mfma_kernel<true>, grid, block, 0, s, m);
+    else hipLaunchKernelGGL(attn_fwd_mfma_kernel<false>, grid, block, 0, s, m);
     return hipGetLastError();
   }
   const dim3 grid((unsigned)P, (unsigned)a.T), block(64);
@@ -709,12 +779,17 @@ hipError_t launch_attn_fwd(int dtype, const AttnArgs& a, hipStream_t s) {
 hipError_t launch_attn_bwd(int dtype, const AttnArgs& a, hipStream_t s) {
   const long P = a.seqs * a.heads;
   if (use_mfma(dtype, a)) {
-    const dim3 grid((unsigned)P, (unsigned)(((a.T + 31) / 32 + AT_WAVES - 1) / AT_WAVES)), block(64 * AT_WAVES);
+    if (attn_grid(a) > 0x7fffffffL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)attn_grid(a)), block(64 * AT_WAVES);
+    // dq is bound by its tile stream and gains from one XCD per problem; dk/dv is bound by its arithmetic and by the
+    // tail, and keeps the longest-first order (by_problem = 0 as the caller leaves it)
+    AttnArgs m = a;
+    m.by_problem = attn_grid(a) >= BY_PROBLEM_FROM;
     if (a.causal) {
-      hipLaunchKernelGGL(attn_bwd_q_mfma_kernel<true>, grid, block, 0, s, a);
+      hipLaunchKernelGGL(attn_bwd_q_mfma_kernel<true>, grid, block, 0, s, m);
       hipLaunchKernelGGL(attn_bwd_kv_mfma_kernel<true>, grid, block, 0, s, a);
     } else {
-      hipLaunchKernelGGL(attn_bwd_q_mfma_kernel<false>, grid, block, 0, s, a);
+      hipLaunchKernelGGL(attn_bwd_q_mfma_kernel<false>, grid, block, 0, s, m);
       hipLaunchKernelGGL(attn_bwd_kv_mfma_kernel<false>, grid, block, 0, s, a);
     }
     return hipGetLastError();

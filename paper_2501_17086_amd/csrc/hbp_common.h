@@ -165,6 +165,7 @@ struct AttnArgs {
   long seqs, T;
   int heads, dh, causal;
   float scale;          // 1 / sqrt(dh)
+  int by_problem;       // set by the launchers: how workgroup ids map to (problem, block of tiles)
 };
 bool attn_supported(int dtype, long T, int dh);
 hipError_t launch_attn_fwd(int dtype, const AttnArgs& a, hipStream_t s);
