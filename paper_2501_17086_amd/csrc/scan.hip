@@ -1210,6 +1210,133 @@ __global__ __launch_bounds__(256) void scan_post_kernel(PostScanArgs a) {
   }
 }
 
+// The iteration's scan (mode 0) for rows of at most 2048 channels, written for memory-level parallelism: a row is
+// split over WPR wavefronts of 512 channels each (a workgroup of four wavefronts holds 4 / WPR rows), so a wavefront's
+// state is 8 values per lane whatever the width, and the operands of layer l - 1 (block input gradient, injected
+// gradient, state, old estimate; raw 16-byte vectors) are in flight while layer l is reduced.  The row's mean is the
+// sum of the wavefronts' partial sums in a fixed order, exchanged through LDS with one barrier per layer (two sets of
+// slots, used in turn: a set is rewritten two barriers after it was read).  The barrier is preceded by a wait on
+// LDS traffic only: the loads of the next layer stay in flight across it.  Same arithmetic as scan_post_kernel.
+template <typename T, int WPR, bool GAMMA>
+__global__ __launch_bounds__(256) void scan_post_split_kernel(PostScanArgs a) {
+  __shared__ float red[2][4];
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int part = wave % WPR;
+  const long row_raw = (long)blockIdx.x * (4 / WPR) + wave / WPR;
+  const bool row_ok = row_raw < a.N;                        // a spare row of the last workgroup computes row N - 1
+  const long row = row_ok ? row_raw : a.N - 1;              // again and stores nothing: every wavefront meets every barrier
+  const long c = (long)part * 512 + lane * 8;
+  const bool on = c < a.d;
+  const bool store = on && row_ok;
+  const long layer = a.N * a.d;
+  const long off = row * a.d + (on ? c : 0);
+  T* g = reinterpret_cast<T*>(a.g);
+  const T* dn = reinterpret_cast<const T*>(a.dn);
+  const T* e = reinterpret_cast<const T*>(a.e);
+  const T* x = reinterpret_cast<const T*>(a.x);
+  const float inv_d = 1.0f / (float)a.d;
+  const float keep = 1.f - a.gamma;
+  int set = 0;
+  auto row_sum = [&](float v) {
+    v = wave_sum_dpp(v);
+    if (WPR == 1) return v;
+    if (lane == 0) red[set][wave] = v;
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);                     // lgkmcnt(0): the slot is written; vector loads stay in flight
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    float t = red[set][wave - part];
+#pragma unroll
+    for (int k = 1; k < WPR; ++k) t += red[set][wave - part + k];
+    set ^= 1;
+    return t;
+  };
+  struct Stage {
+    Raw8<T> dn, e, x, g;
+    Raw8<float> lam;
+    float rl, mo, rp;
+  };
+  auto issue = [&](Stage& st, long l) {
+    const long base = l * layer + off;
+    if (dn) st.dn.load_nt(dn + base);
+    if (e) st.e.load_nt(e + base);
+    st.x.load(x + base);                                    // (read again by the next sweep's block products)
+    if (GAMMA) st.g.load(g + base);
+    if (a.lambda) st.lam.load(a.lambda + l * a.d + (on ? c : 0));
+    st.rl = a.rho[l * a.N + row];
+    st.mo = dn ? a.m_old[l * a.N + row] : 0.f;
+    st.rp = a.rho[(l >= 1 ? l - 1 : 0) * a.N + row];
+  };
+  float carry[8], xn[8], gold[8];
+  // G (fp32, in `carry`) of state l, projected through the norm that made x_l (in xn) and stored as g[l]
+  auto project_store = [&](long l, float rp) {
+    float dot = 0.f;
+    if (on) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) dot = fmaf(carry[i], xn[i], dot);
+    }
+    const float m = row_sum(dot) * inv_d;
+    if (lane == 0 && part == 0 && row_ok) a.m_new[(l - 1) * a.N + row] = m;
+    float o[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = rp * (carry[i] - xn[i] * m);
+    if (store) store8(g + l * layer + off, o);
+  };
+  {   // the top: G_L = e_L
+    load8(reinterpret_cast<const T*>(a.e_top) + off, carry);
+    if (GAMMA) load8(g + a.l_hi * layer + off, gold);
+    load8(x + a.l_hi * layer + off, xn);
+    project_store(a.l_hi, a.rho[(a.l_hi - 1) * a.N + row]);
+  }
+  auto consume = [&](const Stage& st, long l) {
+    float t[8], lam[8];
+    if (dn) {
+      st.dn.unpack(t);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t[i] = 0.f;
+    }
+    if (e) {
+      float ee[8];
+      st.e.unpack(ee);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t[i] += ee[i];
+    }
+    if (a.lambda) {
+      st.lam.unpack(lam);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) lam[i] = 1.f;
+    }
+    const float rl = st.rl, mo = st.mo;
+    if (GAMMA) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) t[i] = fmaf(a.blk_gamma * lam[i], gold[i], t[i]);
+      st.g.unpack(gold);                                    // the old g[l], for the step below
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) carry[i] = fmaf(keep * lam[i] * rl, carry[i] - xn[i] * mo, t[i]);
+    if (l >= 1) {
+      st.x.unpack(xn);
+      project_store(l, st.rp);
+    } else if (store) {
+      store8(g + off, carry);
+    }
+  };
+  Stage s0, s1;
+  long l = a.l_hi - 1;
+  issue(s0, l);
+  while (true) {
+    issue(s1, l - 1 > a.l_lo ? l - 1 : a.l_lo);
+    consume(s0, l);
+    if (--l < a.l_lo) break;
+    issue(s0, l - 1 > a.l_lo ? l - 1 : a.l_lo);
+    consume(s1, l);
+    if (--l < a.l_lo) break;
+  }
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_inplace_kernel(T* x, float* rinv, long rows, long d, float eps) {
   const int lane = threadIdx.x & 63;
@@ -1264,10 +1391,26 @@ __global__ __launch_bounds__(256) void mask_apply_kernel(T* __restrict__ g, cons
 }
 }  // namespace
 
+template <typename T, bool GAMMA>
+hipError_t launch_scan_post_split(const PostScanArgs& a, hipStream_t s) {
+  const int nch = (int)((a.d + 511) / 512);
+  const int wpr = nch <= 1 ? 1 : nch == 2 ? 2 : 4;
+  const long rows_wg = 4 / wpr;
+  dim3 grid((unsigned)((a.N + rows_wg - 1) / rows_wg)), block(256);
+  switch (wpr) {
+    case 1: hipLaunchKernelGGL((scan_post_split_kernel<T, 1, GAMMA>), grid, block, 0, s, a); break;
+    case 2: hipLaunchKernelGGL((scan_post_split_kernel<T, 2, GAMMA>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((scan_post_split_kernel<T, 4, GAMMA>), grid, block, 0, s, a); break;
+  }
+  return hipGetLastError();
+}
+
 template <typename T>
 hipError_t launch_scan_post_t(const PostScanArgs& a, hipStream_t s) {
   const int nch = (int)((a.d + 511) / 512);
   dim3 grid((unsigned)((a.N + 3) / 4)), block(256);
+  if (a.mode == 0 && nch <= 4 && a.d % 8 == 0)
+    return a.blk_gamma != 0.f ? launch_scan_post_split<T, true>(a, s) : launch_scan_post_split<T, false>(a, s);
   if (a.blk_gamma != 0.f && a.mode == 0) {
     switch (nch) {
       case 1: hipLaunchKernelGGL((scan_post_kernel<T, 1, true>), grid, block, 0, s, a); break;
