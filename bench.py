@@ -43,15 +43,15 @@ MEASURED_TRAFFIC = {
     "resnet_like": {"source": "profiles/bench_resnet_like_hbm_traffic.txt",
                     "vjp1": 2.692e9, "vjp2": 1.591e9, "dw": 1.483e9, "scan": 6.481e8},
     "postnorm_mlp": {"source": "profiles/bench_postnorm_mlp_hbm_traffic.txt",
-                     "vjp1": 5.650e9, "vjp2": 2.760e9, "dw": 2.824e9, "scan": 1.120e9},
+                     "vjp1": 5.678e9, "vjp2": 2.760e9, "dw": 2.828e9, "scan": 1.149e9},
     "gated_rnn": {"source": "profiles/bench_gated_rnn_hbm_traffic.txt",
                   "vjp1": 9.441e8, "vjp2": 9.397e8, "dw": 6.041e8, "scan": 6.381e8},
     "gpt2_paper": {"source": "profiles/bench_gpt2_paper_hbm_traffic.txt",
-                   "vjp1": 1.770e9, "vjp2": 5.341e8, "dw": 8.934e8, "attn": 1.426e9, "scan": 1.242e9},
+                   "vjp1": 1.770e9, "vjp2": 5.341e8, "dw": 8.919e8, "attn": 1.326e9, "scan": 1.242e9},
     "roberta_like": {"source": "profiles/bench_roberta_like_hbm_traffic.txt",
-                     "vjp1": 9.033e8, "vjp2": 3.344e8, "dw": 5.582e8, "attn": 4.585e8, "scan": 5.220e8},
+                     "vjp1": 9.039e8, "vjp2": 3.345e8, "dw": 5.588e8, "attn": 4.581e8, "scan": 5.377e8},
     "transformer_attn": {"source": "profiles/bench_transformer_attn_hbm_traffic.txt",
-                         "vjp1": 5.507e9, "vjp2": 1.432e9, "dw": 2.181e9, "attn": 5.312e9, "scan": 2.458e9},
+                         "vjp1": 5.526e9, "vjp2": 1.433e9, "dw": 2.193e9, "attn": 3.903e9, "scan": 2.458e9},
     "lstm_cell": {"source": "profiles/bench_lstm_cell_hbm_traffic.txt",
                   "vjp1": 3.491e9, "vjp2": 2.150e9, "dw": 2.029e9, "scan": 1.702e9},
 }
