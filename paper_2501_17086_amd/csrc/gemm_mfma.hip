@@ -708,12 +708,35 @@ template <int FAST> struct StagedOps {   // vector-memory operations per wave of
   static constexpr int value = FAST == FAST_STORE_F32 ? 32 : FAST == FAST_STORE ? 16 : 32;   // waits stay safe with more)
 };
 
+constexpr int PAIR_AREA = 2 * A_BYTES;                   // 256 rows x 128 bytes: two slices of a K-contiguous operand
+// Byte offset of this lane's 16 bytes of the first of a wave's four copies of a pair (rows 8 wave .. + 7 of the
+// first 64; the lane's LDS place l % 8 in row l / 8 holds chunk (l % 8) ^ (row / 2 % 8) of the row's 128 bytes)
+__device__ __forceinline__ unsigned pair_src_offset(long ld, int wave, int lane) {
+  const int r = 8 * wave + (lane >> 3);
+  const int c = (lane & 7) ^ ((r >> 1) & 7);
+  return (unsigned)(r * ld + 8 * c) * 2u;
+}
+// 32 rows x 16 k fragment out of a pair area: lane l holds row (l % 32), chunk c0 + l / 32 of the row's eight
+__device__ __forceinline__ bf16x8 frag_pair(const unsigned char* area, int row0, int c0, int lane) {
+  const int r = row0 + (lane & 31);
+  const int c = c0 + (lane >> 5);
+  const uint4 v = *reinterpret_cast<const uint4*>(area + r * 128 + ((c ^ ((r >> 1) & 7)) << 4));
+  return __builtin_bit_cast(bf16x8, v);
+}
+
 constexpr int LEAN_NST = 4;                              // 4 x 32 KB, + 4 KB per wave for the epilogue
 constexpr int LEAN_LDS = LEAN_NST * STAGE_BYTES + NW * 4096;
 
-template <bool A_KC, bool B_KC, int FAST, bool ONE_AT_A_TIME>
+// PAIR (A contiguous along K, every tile's range an even number of slices): A is copied two slices at a time, 128
+// bytes of every row, so that each request for A takes a whole 128-byte line out of L2 (a 64-byte row segment costs
+// L2 a whole line as well, and the other half is asked for again one slice later: half as much again in L2 reads
+// for the pairing with one K-contiguous operand, which is bound by them).  LDS then holds two areas of 256 rows x
+// 128 bytes for A (chunk k of row r at chunk k ^ (r/2 % 8)), refilled at every even step with the pair two steps
+// ahead, and the ring of four 16 KB stages for B behind them; everything else is as without it.
+template <bool A_KC, bool B_KC, int FAST, bool ONE_AT_A_TIME, bool PAIR>
 __global__ __launch_bounds__(NTHR, 1) void gemm_mfma_lean_kernel(GemmArgs g, int tiles_m, int tiles_n, long total,
                                                                  long per_xcd) {
+  static_assert(!PAIR || A_KC, "pairs of slices are copied for a K-contiguous A only");
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -738,10 +761,12 @@ __global__ __launch_bounds__(NTHR, 1) void gemm_mfma_lean_kernel(GemmArgs g, int
   const long ldb = B_KC ? g.b_sn : g.b_sk;
   const long step_a = (A_KC ? BK : BK * lda) * 2, step_b = (B_KC ? BK : BK * ldb) * 2;   // bytes per slice
   // per-lane byte offsets of the wave's two copies per operand (the second is 128 rows / 16 k rows further)
-  const unsigned offA0 = lane_src_offset<A_KC>(lda, 0, wave, lane);
+  // (PAIR: copy i of 4 covers rows 64 i + 8 wave .. + 7, 8 lanes to a row; its offset is added to the scalar base)
+  const unsigned offA0 = PAIR ? pair_src_offset(lda, wave, lane) : lane_src_offset<A_KC>(lda, 0, wave, lane);
   const unsigned offB0 = lane_src_offset<B_KC>(ldb, 0, wave, lane);
   const unsigned offA1 = offA0 + (unsigned)((A_KC ? 128 : 16) * lda * 2);
   const unsigned offB1 = offB0 + (unsigned)((B_KC ? 128 : 16) * ldb * 2);
+  const long pair_rows64 = 64 * lda * 2;                  // bytes between the rows of consecutive copies of a pair
 
   // ---- producer (wave-uniform): first byte of the next slice to copy per operand, slices left in
   // the tile it copies from, that tile's index, the stage the slice goes to ----
@@ -749,7 +774,8 @@ __global__ __launch_bounds__(NTHR, 1) void gemm_mfma_lean_kernel(GemmArgs g, int
   const unsigned char* qb;
   int p_left, pt = t;
   bool p_more = true;
-  unsigned p_off = 0;      // byte offset of the producer's stage in the ring
+  unsigned p_off = 0;      // byte offset of the producer's stage in the ring (PAIR: of its B stage behind the A areas)
+  unsigned p_aoff = 0;     // PAIR: byte offset of the A area the next pair goes to
   auto aim = [&](const TileCoord& c) {
     qa = reinterpret_cast<const unsigned char*>(reinterpret_cast<const bf16_t*>(g.A) + c.batch * g.a_sb +
                                                 (A_KC ? c.m0 * lda + c.k_begin : c.m0 + c.k_begin * lda));
@@ -758,14 +784,32 @@ __global__ __launch_bounds__(NTHR, 1) void gemm_mfma_lean_kernel(GemmArgs g, int
     p_left = c.KT;
   };
   auto copy_slice = [&]() {
-    const unsigned dst = lds_wave + p_off;
-    dma16_c<0>(offA0, qa, dst);
-    dma16_c<NW * 1024>(offA1, qa, dst);
-    dma16_c<A_BYTES>(offB0, qb, dst);
-    dma16_c<A_BYTES + NW * 1024>(offB1, qb, dst);
-    qa += step_a;
-    qb += step_b;
-    p_off = p_off == (LEAN_NST - 1) * STAGE_BYTES ? 0u : p_off + STAGE_BYTES;
+    if (PAIR) {
+      // an odd slice of its tile (an odd number of slices left): first the pair of A it completes, then its B
+      if (p_left & 1) {
+        const unsigned dsta = lds_wave + p_aoff;
+        dma16_c<0>(offA0, qa, dsta);
+        dma16_c<NW * 1024>(offA0, qa + pair_rows64, dsta);
+        dma16_c<2 * NW * 1024>(offA0, qa + 2 * pair_rows64, dsta);
+        dma16_c<3 * NW * 1024>(offA0, qa + 3 * pair_rows64, dsta);
+        qa += 2 * step_a;
+        p_aoff ^= (unsigned)PAIR_AREA;
+      }
+      const unsigned dst = lds_wave + 2 * PAIR_AREA + p_off;
+      dma16_c<0>(offB0, qb, dst);
+      dma16_c<NW * 1024>(offB1, qb, dst);
+      qb += step_b;
+      p_off = p_off == (LEAN_NST - 1) * B_BYTES ? 0u : p_off + B_BYTES;
+    } else {
+      const unsigned dst = lds_wave + p_off;
+      dma16_c<0>(offA0, qa, dst);
+      dma16_c<NW * 1024>(offA1, qa, dst);
+      dma16_c<A_BYTES>(offB0, qb, dst);
+      dma16_c<A_BYTES + NW * 1024>(offB1, qb, dst);
+      qa += step_a;
+      qb += step_b;
+      p_off = p_off == (LEAN_NST - 1) * STAGE_BYTES ? 0u : p_off + STAGE_BYTES;
+    }
     if (--p_left == 0) {
       pt += t_stride;
       if (pt < t_end) aim(decode_tile(g, pt, tiles_m, tiles_n));
@@ -781,6 +825,12 @@ __global__ __launch_bounds__(NTHR, 1) void gemm_mfma_lean_kernel(GemmArgs g, int
   constexpr int AHEAD = LEAN_NST - 1;                      // slices copied ahead of the one being multiplied
   constexpr int W_PLAIN = (AHEAD - 1) * PER_SLICE;
   constexpr int W_EPI = W_PLAIN + E > 63 ? 63 : W_PLAIN + E;
+  // PAIR: a wave issues 4 copies of A and 2 of B in an even step, 2 of B in an odd one.  At the end of an even
+  // step c the B of slice c + 1 (issued two steps before) must have landed: what may be outstanding is what was
+  // issued after it, 2 + 4 + 2 copies (and a recent epilogue's operations); at the end of an odd step the pair
+  // that holds slice c + 1, issued in the step before: 2 + 2 copies.
+  constexpr int W_EVEN = 8, W_EVEN_EPI = W_EVEN + E > 63 ? 63 : W_EVEN + E, W_ODD = 4;
+  unsigned c_aoff = 0;     // PAIR: byte offset of the A area being read
 
   // One slice: load phase, barrier, compute phase, barrier.
   // Barrier intervals ("ticks"): group 0 loads slice c in tick 2c and multiplies it in tick 2c+1;
@@ -788,25 +838,45 @@ __global__ __launch_bounds__(NTHR, 1) void gemm_mfma_lean_kernel(GemmArgs g, int
   // the stage of slice c-1, which its last reader (group 1, tick 2c-1) has left.  Every wave waits
   // for its own share of slice c+1 at the end of its load phase of slice c, a barrier or more
   // before the first reader of slice c+1 starts.
-  auto step = [&](auto first_c) {
+  auto step = [&](auto first_c, auto odd_c) {
     constexpr bool FIRST = decltype(first_c)::value;
+    constexpr bool ODD = decltype(odd_c)::value;         // (PAIR only: the slice's place in its pair)
     const bool copying = p_more;
     if (copying) copy_slice();
-    const unsigned char* st = smem + c_off;
+    if (PAIR) {
+      const unsigned char* stb = smem + 2 * PAIR_AREA + c_off;
+      const unsigned char* sta = smem + c_aoff;
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+      for (int h = 0; h < 2; ++h)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) fb[j][h] = frag<B_KC>(st + A_BYTES, wn0 + 32 * j, 16 * h, lane);
+        for (int j = 0; j < 2; ++j) fb[j][h] = frag<B_KC>(stb, wn0 + 32 * j, 16 * h, lane);
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
+      for (int h = 0; h < 2; ++h)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) fa[i][h] = frag<A_KC>(st, wm0 + 32 * i, 16 * h, lane);
-    c_off = c_off == (LEAN_NST - 1) * STAGE_BYTES ? 0u : c_off + STAGE_BYTES;
-    // this wave's share of the next slice has landed once only what it issued for the slices after
-    // that one (and a recent epilogue's operations, which lie among them) is outstanding
-    if (!copying) wait_vm_lds<0>();
-    else if (epi_recent > 0) { wait_vm_lds<W_EPI>(); --epi_recent; }
-    else wait_vm_lds<W_PLAIN>();
+        for (int i = 0; i < 4; ++i) fa[i][h] = frag_pair(sta, wm0 + 32 * i, (ODD ? 4 : 0) + 2 * h, lane);
+      c_off = c_off == (LEAN_NST - 1) * B_BYTES ? 0u : c_off + B_BYTES;
+      if (ODD) c_aoff ^= (unsigned)PAIR_AREA;
+      if (!copying) wait_vm_lds<0>();
+      else if (ODD) wait_vm_lds<W_ODD>();
+      else if (epi_recent > 0) { wait_vm_lds<W_EVEN_EPI>(); epi_recent = 0; }
+      else wait_vm_lds<W_EVEN>();
+    } else {
+      const unsigned char* st = smem + c_off;
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) fb[j][h] = frag<B_KC>(st + A_BYTES, wn0 + 32 * j, 16 * h, lane);
+#pragma unroll
+      for (int h = 0; h < 2; ++h)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) fa[i][h] = frag<A_KC>(st, wm0 + 32 * i, 16 * h, lane);
+      c_off = c_off == (LEAN_NST - 1) * STAGE_BYTES ? 0u : c_off + STAGE_BYTES;
+      // this wave's share of the next slice has landed once only what it issued for the slices after
+      // that one (and a recent epilogue's operations, which lie among them) is outstanding
+      if (!copying) wait_vm_lds<0>();
+      else if (epi_recent > 0) { wait_vm_lds<W_EPI>(); --epi_recent; }
+      else wait_vm_lds<W_PLAIN>();
+    }
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
@@ -834,15 +904,27 @@ __global__ __launch_bounds__(NTHR, 1) void gemm_mfma_lean_kernel(GemmArgs g, int
 #pragma unroll 1
   for (; pro < AHEAD && p_more; ++pro) copy_slice();
   // slice 0 has landed once at most the pro - 1 slices after it are outstanding
-  if (pro >= 4) wait_vm<3 * PER_SLICE>(); else if (pro == 3) wait_vm<2 * PER_SLICE>();
+  if (PAIR) {              // (issued: B of slice 0, the first pair of A, B of slices 1 and 2)
+    if (pro == 3) wait_vm<4>(); else wait_vm<0>();
+  } else if (pro >= 4) wait_vm<3 * PER_SLICE>(); else if (pro == 3) wait_vm<2 * PER_SLICE>();
   else if (pro == 2) wait_vm<PER_SLICE>(); else wait_vm<0>();
   __builtin_amdgcn_s_barrier();                 // slice 0 is in LDS
   if (grp == 1) __builtin_amdgcn_s_barrier();   // group 1 runs one tick behind
 
   while (true) {
-    step(std::true_type());
+    if (PAIR) {
+      step(std::true_type(), std::false_type());
+      step(std::false_type(), std::true_type());
 #pragma unroll 1
-    for (int k = 1; k < cc.KT; ++k) step(std::false_type());
+      for (int k = 2; k < cc.KT; k += 2) {
+        step(std::false_type(), std::false_type());
+        step(std::false_type(), std::true_type());
+      }
+    } else {
+      step(std::true_type(), std::false_type());
+#pragma unroll 1
+      for (int k = 1; k < cc.KT; ++k) step(std::false_type(), std::false_type());
+    }
     if (FAST == FAST_STORE_F32) epilogue_fast_fn<FAST>(g, cc, acc, wm0, wn0, lane);
     else epilogue_staged_fn<FAST>(g, cc, acc, wm0, wn0, lane, smem + LEAN_NST * STAGE_BYTES + wave * 4096);
     epi_recent = AHEAD - 1;
@@ -868,10 +950,10 @@ inline hipError_t raise_lds_limit(const void* kern, int bytes, std::atomic<bool>
   return hipSuccess;
 }
 
-template <bool A_KC, bool B_KC, int FAST, bool ONE_AT_A_TIME>
+template <bool A_KC, bool B_KC, int FAST, bool ONE_AT_A_TIME, bool PAIR>
 hipError_t launch_lean_walk(const GemmArgs& g, hipStream_t s) {
   static std::atomic<bool> attr_set[MAX_DEVICES];
-  auto kern = gemm_mfma_lean_kernel<A_KC, B_KC, FAST, ONE_AT_A_TIME>;
+  auto kern = gemm_mfma_lean_kernel<A_KC, B_KC, FAST, ONE_AT_A_TIME, PAIR>;
   {
     hipError_t e = raise_lds_limit(reinterpret_cast<const void*>(kern), LEAN_LDS, attr_set);
     if (e != hipSuccess) return e;
@@ -889,7 +971,14 @@ hipError_t launch_lean(const GemmArgs& g, hipStream_t s) {
   // a batch of matrices whose operands run to tens of megabytes each: the chip takes them one at a time (measured
   // on 96 blocks of 16384 x 8192 x 2048: 8-10 % faster; on 32 blocks of 8192 x 2048 x 512: 10 % slower)
   const bool one_at_a_time = g.batch > 1 && (g.M + g.N) * g.K * 2 >= (64L << 20);
-  return one_at_a_time ? launch_lean_walk<A_KC, B_KC, FAST, true>(g, s) : launch_lean_walk<A_KC, B_KC, FAST, false>(g, s);
+  if constexpr (A_KC) {
+    // every tile's share of K an even number of slices: A in pairs of slices
+    if (g.K % ((long)g.split_k * 2 * BK) == 0)
+      return one_at_a_time ? launch_lean_walk<A_KC, B_KC, FAST, true, true>(g, s)
+                           : launch_lean_walk<A_KC, B_KC, FAST, false, true>(g, s);
+  }
+  return one_at_a_time ? launch_lean_walk<A_KC, B_KC, FAST, true, false>(g, s)
+                       : launch_lean_walk<A_KC, B_KC, FAST, false, false>(g, s);
 }
 // every tile inside the matrix, every tile's share of K a whole number of slices
 inline bool lean_ok(const GemmArgs& g) {
