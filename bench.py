@@ -37,23 +37,23 @@ PEAK_HBM_GBS = 8000.0
 # report null.
 MEASURED_TRAFFIC = {
     "deep_large": {"source": "profiles/bench_deep_large_hbm_traffic.txt",
-                   "vjp1": 1.323e11, "vjp2": 8.408e10, "dw": 3.064e11, "scan": 1.543e10},
+                   "vjp1": 1.363e11, "vjp2": 8.394e10, "dw": 3.043e11, "scan": 1.545e10},
     "transformer_mlp": {"source": "profiles/bench_transformer_mlp_hbm_traffic.txt",
-                        "vjp1": 2.247e10, "vjp2": 1.116e10, "dw": 2.335e10, "scan": 3.815e9},
+                        "vjp1": 2.347e10, "vjp2": 1.131e10, "dw": 2.446e10, "scan": 3.815e9},
     "resnet_like": {"source": "profiles/bench_resnet_like_hbm_traffic.txt",
-                    "vjp1": 2.692e9, "vjp2": 1.591e9, "dw": 1.483e9, "scan": 6.481e8},
+                    "vjp1": 2.687e9, "vjp2": 1.610e9, "dw": 1.477e9, "scan": 6.481e8},
     "postnorm_mlp": {"source": "profiles/bench_postnorm_mlp_hbm_traffic.txt",
-                     "vjp1": 5.678e9, "vjp2": 2.760e9, "dw": 2.828e9, "scan": 1.149e9},
+                     "vjp1": 5.608e9, "vjp2": 2.760e9, "dw": 2.832e9, "scan": 1.149e9},
     "gated_rnn": {"source": "profiles/bench_gated_rnn_hbm_traffic.txt",
-                  "vjp1": 9.441e8, "vjp2": 9.397e8, "dw": 6.041e8, "scan": 6.381e8},
+                  "vjp1": 9.402e8, "vjp2": 9.398e8, "dw": 6.041e8, "scan": 6.420e8},
     "gpt2_paper": {"source": "profiles/bench_gpt2_paper_hbm_traffic.txt",
-                   "vjp1": 1.770e9, "vjp2": 5.341e8, "dw": 8.919e8, "attn": 1.326e9, "scan": 1.242e9},
+                   "vjp1": 1.771e9, "vjp2": 5.335e8, "dw": 8.941e8, "attn": 1.326e9, "scan": 1.242e9},
     "roberta_like": {"source": "profiles/bench_roberta_like_hbm_traffic.txt",
-                     "vjp1": 9.039e8, "vjp2": 3.345e8, "dw": 5.588e8, "attn": 4.581e8, "scan": 5.377e8},
+                     "vjp1": 9.128e8, "vjp2": 3.332e8, "dw": 5.590e8, "attn": 4.581e8, "scan": 5.377e8},
     "transformer_attn": {"source": "profiles/bench_transformer_attn_hbm_traffic.txt",
-                         "vjp1": 5.526e9, "vjp2": 1.433e9, "dw": 2.193e9, "attn": 3.903e9, "scan": 2.458e9},
+                         "vjp1": 5.563e9, "vjp2": 1.432e9, "dw": 2.169e9, "attn": 3.903e9, "scan": 2.458e9},
     "lstm_cell": {"source": "profiles/bench_lstm_cell_hbm_traffic.txt",
-                  "vjp1": 3.491e9, "vjp2": 2.150e9, "dw": 2.029e9, "scan": 1.702e9},
+                  "vjp1": 3.491e9, "vjp2": 2.148e9, "dw": 1.838e9, "scan": 1.701e9},
 }
 
 

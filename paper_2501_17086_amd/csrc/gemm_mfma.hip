@@ -972,10 +972,12 @@ hipError_t launch_lean(const GemmArgs& g, hipStream_t s) {
   // on 96 blocks of 16384 x 8192 x 2048: 8-10 % faster; on 32 blocks of 8192 x 2048 x 512: 10 % slower)
   const bool one_at_a_time = g.batch > 1 && (g.M + g.N) * g.K * 2 >= (64L << 20);
   if constexpr (A_KC) {
-    // every tile's share of K an even number of slices: A in pairs of slices
-    if (g.K % ((long)g.split_k * 2 * BK) == 0)
-      return one_at_a_time ? launch_lean_walk<A_KC, B_KC, FAST, true, true>(g, s)
-                           : launch_lean_walk<A_KC, B_KC, FAST, false, true>(g, s);
+    // Every tile's share of K an even number of slices: A in pairs of slices.  Measured: 2-10 % on matrices that
+    // the caches hold (L2 reads down by a third); on the one-at-a-time walk over 96 blocks of 16384 x 8192 x 2048
+    // the same time (fewer cycles at a lower clock: the chip is at its power limit there) with twice the fills from
+    // memory, the pairs being asked for closer to their use: not taken there.
+    if (!one_at_a_time && g.K % ((long)g.split_k * 2 * BK) == 0)
+      return launch_lean_walk<A_KC, B_KC, FAST, false, true>(g, s);
   }
   return one_at_a_time ? launch_lean_walk<A_KC, B_KC, FAST, true, false>(g, s)
                        : launch_lean_walk<A_KC, B_KC, FAST, false, false>(g, s);
