@@ -170,6 +170,12 @@ CASES = {
                                   lam="uniform", lam_lo=0.8, lam_hi=1.0, ks=(0, 1, 3)),
     "postnorm_aligned": synth.scaled(W["postnorm_mlp"], name="postnorm_aligned", L=9, N=512, d=256, d_ff=512,
                                      ks=(0, 2, 4)),
+    # rows split over four wavefronts (the last one past the width) with one row per workgroup, and over two
+    # (the second one partly past the width) with a spare row in the last workgroup
+    "postnorm_four_waves": synth.scaled(W["postnorm_mlp"], name="postnorm_four_waves", L=5, N=37, d=1536, d_ff=256,
+                                        lam="uniform", lam_lo=0.8, lam_hi=1.0, ks=(0, 1, 3)),
+    "postnorm_two_waves_odd": synth.scaled(W["postnorm_mlp"], name="postnorm_two_waves_odd", L=7, N=45, d=640,
+                                           d_ff=256, loss_every_state=True, ks=(0, 2, 4)),
     "postnorm_f32": synth.scaled(W["postnorm_mlp"], name="postnorm_f32", dtype="f32", L=5, N=203, d=72, d_ff=136,
                                  w1_std=0.0, w2_std=0.0, lam="uniform", lam_lo=0.8, lam_hi=1.0,
                                  loss_every_state=True, ks=(0, 1, 2, 5)),
@@ -409,6 +415,7 @@ def test_forward_with_relu_after_the_sum(B, name):
                                   "postact_rms", "postact_wide", "postact_aligned", "postact_f32_none",
                                   "postact_f32_deep", "gated_small", "gated_long", "lstm_small", "lstm_long",
                                   "postnorm_small", "postnorm_wide", "postnorm_aligned", "postnorm_f32",
+                                  "postnorm_four_waves", "postnorm_two_waves_odd",
                                   "postact_loss_all", "gru_small", "gru_long", "tfm_f32", "tfm_small", "tfm_bidir",
                                   "tfm_heads_32"] + TFM_POSTNORM)
 def test_backward_shared_state(B, name):
@@ -434,7 +441,8 @@ def test_backward_shared_state(B, name):
                                         ("lstm_small", 0.3), ("lstm_long", 0.7), ("gru_small", 0.3), ("gru_long", 1.0),
                                         ("tfm_f32", 0.2), ("tfm_small", 0.2), ("tfm_small", 1.0), ("tfm_postnorm", 0.5),
                                         ("postnorm_small", 0.5), ("postnorm_wide", 0.8), ("postnorm_f32", 1.0),
-                                        ("postnorm_aligned", 0.2)])
+                                        ("postnorm_aligned", 0.2), ("postnorm_four_waves", 0.5),
+                                        ("postnorm_two_waves_odd", 0.8)])
 def test_gamma_iterates(B, name, gamma):
     """The iteration on the re-split pair (J + gamma K, (1 - gamma) K): every k of
     the case against the oracle on a shared forward state; gamma = 1 is the
