@@ -360,8 +360,8 @@ __device__ __forceinline__ BlockOf block_of(const AttnArgs& a, int nblk) {
   b.exists = b.p < P;
   return b;
 }
-// grids from about eight rounds of resident workgroups per XCD on: problem by problem
-constexpr long BY_PROBLEM_FROM = 8 * 1024;
+// grids from about four rounds of resident workgroups per XCD on: problem by problem
+constexpr long BY_PROBLEM_FROM = 4 * 1024;
 inline long attn_grid(const AttnArgs& a) {
   const long P = a.seqs * a.heads, nblk = ((a.T + 31) / 32 + AT_WAVES - 1) / AT_WAVES;
   return 8 * ((P + 7) / 8) * nblk;

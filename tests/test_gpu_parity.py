@@ -339,6 +339,19 @@ def test_attention_around_tile_and_workgroup_boundaries(B, T, causal):
     _check_backward(B, w, p, st, sv, inp, w.name, exact=False)
 
 
+def test_attention_problem_by_problem_with_a_ragged_problem_count(B):
+    """Enough (sequence, head) problems that the attention kernels take their workgroups problem by problem, one XCD
+    per problem (grids of 4096 workgroups and more), and a problem count that is no multiple of the eight XCDs:
+    forward state and Highway-BP at k = 1 on 2052 sequences of 129 tokens (two blocks of tiles each)."""
+    w = synth.scaled(W["gpt2_paper"], name="tfm_many_sequences", L=2, N=2052 * 129, seq_len=129, d=64, heads=1, d_ff=64,
+                     w1_std=0.0, w2_std=0.0, w2_scale=0.6, ks=(1,))
+    inp, st, sv, p = _setup(B, w)
+    B.hbp_forward(p)
+    torch.cuda.synchronize()
+    H.assert_close(H.to_np(p.attn_o), sv["o"][0::2], H.TOL[w.dtype], f"{w.name} attention output")
+    _check_backward(B, w, p, st, sv, inp, w.name, exact=False)
+
+
 @pytest.mark.parametrize("name", ["gated_small", "gated_f32", "gated_width_72", "gated_aligned"])
 def test_forward_of_the_gated_cell(B, name):
     """States, both gates ([u | c] side by side) and the residual coefficient 1 - u that the forward writes."""
