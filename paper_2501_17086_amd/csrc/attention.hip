@@ -748,6 +748,177 @@ __global__ __launch_bounds__(64 * AT_WAVES, 3) void attn_bwd_kv_mfma_kernel(Attn
   }
 }
 
+// Backward of a whole (sequence, head) problem of at most 32 NT positions in ONE workgroup of NT wavefronts: the q, k,
+// v and do tiles of the problem go to LDS once (each wavefront copies the four tiles of its own 32 positions), one
+// barrier, and then nothing is streamed and nothing waited for: wavefront w first takes its positions as queries
+// (dq: over the key tiles it sees) and then as keys (dk, dv: over the query tiles that see it).  Under a causal mask
+// that is w + 1 and NT - w steps: every wavefront has the same number of steps.  Each tensor is read from memory once
+// (the two-kernel form reads q, k, v and do twice and keeps D in memory between the kernels); the arithmetic is that
+// of the two kernels, in the same order per output element.
+template <bool CAUSAL, int NT>
+__global__ __launch_bounds__(64 * NT, 1) void attn_bwd_short_mfma_kernel(AttnArgs a) {
+  __shared__ __attribute__((aligned(1024))) unsigned char tiles[4][NT][4096];   // [q | k | v | do][tile of 32 positions]
+  __shared__ __attribute__((aligned(256))) float stats[NT][64];                 // per tile: L2 of its 32 queries, then D
+  const int lane = threadIdx.x & 63, hh = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int T = (int)a.T, nt = (T + 31) >> 5;
+  const bool live = wave < nt;
+  const bool ragged = (T & 31) != 0;
+  const unsigned p = blockIdx.x;
+  const Head hd = head_of(a, p);
+  const LaneOffsets lo = lane_offsets((unsigned)(hd.ld * 2), lane);
+  const unsigned ldw = (unsigned)(hd.d * 2);
+  const LaneOffsets lw = lane_offsets(ldw, lane);
+  const unsigned char* dob = reinterpret_cast<const unsigned char*>(a.dout) + hd.wide_off;
+  const unsigned char* ob = reinterpret_cast<const unsigned char*>(a.o) + hd.wide_off;
+  const int r0 = live ? 32 * wave : 0;                     // (a spare wavefront repeats tile 0's loads and keeps nothing)
+  const int ri = 32 * wave + (lane & 31);                  // this lane's position, as a query and as a key
+  const float c = a.scale * LOG2E;
+  // 1. the wavefront's four tiles (rows past the end repeat the last one), and the statistics of its queries
+  if (live) {
+    const CopyOffsets co = copy_offsets(lo.ldb, lane), cw = copy_offsets(ldw, lane);
+    copy_tile<true>(hd.q + (long)r0 * lo.ldb, co, lo.ldb, T - r0, lds_address(tiles[0][wave]), lane);
+    copy_tile<true>(hd.k + (long)r0 * lo.ldb, co, lo.ldb, T - r0, lds_address(tiles[1][wave]), lane);
+    copy_tile<true>(hd.v + (long)r0 * lo.ldb, co, lo.ldb, T - r0, lds_address(tiles[2][wave]), lane);
+    copy_tile<true>(dob + (long)r0 * ldw, cw, ldw, T - r0, lds_address(tiles[3][wave]), lane);
+  }
+  float L2 = a.lse[(long)p * a.T + (ri < T ? ri : T - 1)];
+  float D = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+    D += dot8(frag_cols_mem<true>(dob + (long)r0 * ldw, lw, T - r0, kk, lane),
+              frag_cols_mem<true>(ob + (long)r0 * ldw, lw, T - r0, kk, lane));
+  D += __shfl_xor(D, 32, 64);
+  if (hh == 0) { stats[wave][lane] = L2; stats[wave][32 + lane] = D; }
+  copies_in_flight<0>();
+  __builtin_amdgcn_s_waitcnt(0xC07F);                      // (lgkmcnt(0): the statistics are written)
+  workgroup_handover();
+  if (!live) return;
+  // 2. the positions as queries: dq
+  {
+    bf16x8 fq[4], fdo[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) { fq[kk] = frag_cols_lds(tiles[0][wave], kk, lane); fdo[kk] = frag_cols_lds(tiles[3][wave], kk, lane); }
+    float16v dq0, dq1;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dq0[r] = 0.f; dq1[r] = 0.f; }
+    auto step = [&](int kt, auto masked_c) __attribute__((always_inline)) {
+      constexpr bool MASKED = decltype(masked_c)::value;
+      const unsigned char* tk = tiles[1][kt];
+      const unsigned char* tv = tiles[2][kt];
+      float16v s, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = -D; }      // dp comes out as dP - D
+      bf16x8 fk[4], fv[4];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) { fk[kk] = frag_cols_lds(tk, kk, lane); fv[kk] = frag_cols_lds(tv, kk, lane); }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        s = mfma(fk[kk], fq[kk], s);
+        dp = mfma(fv[kk], fdo[kk], dp);
+      }
+      const bf16x8 k00 = frag_rows_lds(tk, 0, 0, lane), k01 = frag_rows_lds(tk, 0, 1, lane);
+      const bf16x8 k10 = frag_rows_lds(tk, 1, 0, lane), k11 = frag_rows_lds(tk, 1, 1, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      float ds[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float pr = fast_exp2(fmaf(s[r], c, -L2));
+        if (MASKED) {
+          const int kj = 32 * kt + tile_row_of(r, hh);
+          if (!(CAUSAL ? kj <= ri : kj < T)) pr = 0.f;
+        }
+        ds[r] = pr * dp[r];
+      }
+      const bf16x8 d0 = pack8(ds), d1 = pack8(ds + 8);
+      __builtin_amdgcn_sched_barrier(0);
+      dq0 = mfma(k00, d0, dq0);
+      dq1 = mfma(k10, d0, dq1);
+      dq0 = mfma(k01, d1, dq0);
+      dq1 = mfma(k11, d1, dq1);
+    };
+    const int n_own = CAUSAL ? wave + 1 : nt;
+    const int n_plain = CAUSAL ? n_own - 1 : (ragged ? n_own - 1 : n_own);
+    int kt = 0;
+    for (; kt < n_plain; ++kt) step(kt, std::false_type());
+    if (kt < n_own) step(kt, std::true_type());
+    if (ri < T)
+      store_row(reinterpret_cast<bf16_t*>(reinterpret_cast<unsigned char*>(a.dqkv) + (hd.q - reinterpret_cast<const unsigned char*>(a.qkv))) +
+                    (long)ri * hd.ld, dq0, dq1, a.scale, hh);
+  }
+  // 3. the positions as keys: dk, dv
+  {
+    bf16x8 fk[4], fv[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) { fk[kk] = frag_cols_lds(tiles[1][wave], kk, lane); fv[kk] = frag_cols_lds(tiles[2][wave], kk, lane); }
+    float16v dk0, dk1, dv0, dv1;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dk0[r] = 0.f; dk1[r] = 0.f; dv0[r] = 0.f; dv1[r] = 0.f; }
+    const float ninv_c = -1.0f / c;
+    auto step = [&](int qt, auto masked_c) __attribute__((always_inline)) {
+      constexpr bool MASKED = decltype(masked_c)::value;
+      const unsigned char* tq = tiles[0][qt];
+      const unsigned char* td = tiles[3][qt];
+      const float* st = stats[qt];
+      float16v s, dp;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {       // the statistics of the lane's 16 queries: rows 8 g + 4 hh .. + 3
+        const float4 a4 = *reinterpret_cast<const float4*>(st + 8 * g + 4 * hh);
+        const float4 d4 = *reinterpret_cast<const float4*>(st + 32 + 8 * g + 4 * hh);
+        // the products start from -L2 / c and -D: they come out as (s c - L2) / c and dP - D
+        s[4 * g] = a4.x * ninv_c; s[4 * g + 1] = a4.y * ninv_c; s[4 * g + 2] = a4.z * ninv_c; s[4 * g + 3] = a4.w * ninv_c;
+        dp[4 * g] = -d4.x; dp[4 * g + 1] = -d4.y; dp[4 * g + 2] = -d4.z; dp[4 * g + 3] = -d4.w;
+      }
+      bf16x8 fqs[4], fds[4];
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) { fqs[kk] = frag_cols_lds(tq, kk, lane); fds[kk] = frag_cols_lds(td, kk, lane); }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        s = mfma(fqs[kk], fk[kk], s);
+        dp = mfma(fds[kk], fv[kk], dp);
+      }
+      const bf16x8 t00 = frag_rows_lds(td, 0, 0, lane), t01 = frag_rows_lds(td, 0, 1, lane);
+      const bf16x8 t10 = frag_rows_lds(td, 1, 0, lane), t11 = frag_rows_lds(td, 1, 1, lane);
+      const bf16x8 u00 = frag_rows_lds(tq, 0, 0, lane), u01 = frag_rows_lds(tq, 0, 1, lane);
+      const bf16x8 u10 = frag_rows_lds(tq, 1, 0, lane), u11 = frag_rows_lds(tq, 1, 1, lane);
+      __builtin_amdgcn_sched_barrier(0);
+      float pr[16], ds[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        pr[r] = fast_exp2(s[r] * c);
+        if (MASKED) {
+          const int qi = 32 * qt + tile_row_of(r, hh);
+          if (!(qi < T && (!CAUSAL || ri <= qi))) pr[r] = 0.f;
+        }
+        ds[r] = pr[r] * dp[r];
+      }
+      const bf16x8 p0 = pack8(pr), p1 = pack8(pr + 8), d0 = pack8(ds), d1 = pack8(ds + 8);
+      __builtin_amdgcn_sched_barrier(0);
+      dv0 = mfma(t00, p0, dv0);
+      dv1 = mfma(t10, p0, dv1);
+      dk0 = mfma(u00, d0, dk0);
+      dk1 = mfma(u10, d0, dk1);
+      dv0 = mfma(t01, p1, dv0);
+      dv1 = mfma(t11, p1, dv1);
+      dk0 = mfma(u01, d1, dk0);
+      dk1 = mfma(u11, d1, dk1);
+    };
+    int qt = CAUSAL ? wave : 0;
+    if (CAUSAL) { step(qt, std::true_type()); ++qt; }
+    const int plain_end = ragged ? nt - 1 : nt;
+    for (; qt < plain_end; ++qt) step(qt, std::false_type());
+    if (qt < nt) step(qt, std::true_type());
+    if (ri < T) {
+      bf16_t* row = reinterpret_cast<bf16_t*>(reinterpret_cast<unsigned char*>(a.dqkv) + (hd.k - reinterpret_cast<const unsigned char*>(a.qkv))) +
+                    (long)ri * hd.ld;
+      store_row(row, dk0, dk1, a.scale, hh);
+      store_row(row + hd.d, dv0, dv1, 1.f, hh);
+    }
+  }
+}
+
 inline bool use_mfma(int dtype, const AttnArgs& a) { return dtype == 1 && a.dh == 64; }
 
 }  // namespace
@@ -779,6 +950,18 @@ hipError_t launch_attn_fwd(int dtype, const AttnArgs& a, hipStream_t s) {
 hipError_t launch_attn_bwd(int dtype, const AttnArgs& a, hipStream_t s) {
   const long P = a.seqs * a.heads;
   if (use_mfma(dtype, a)) {
+    if (a.T <= 256) {        // a whole problem per workgroup
+      if (P > 0x7fffffffL) return hipErrorInvalidValue;
+      const dim3 grid((unsigned)P);
+      if (a.T <= 128) {
+        if (a.causal) hipLaunchKernelGGL((attn_bwd_short_mfma_kernel<true, 4>), grid, dim3(256), 0, s, a);
+        else hipLaunchKernelGGL((attn_bwd_short_mfma_kernel<false, 4>), grid, dim3(256), 0, s, a);
+      } else {
+        if (a.causal) hipLaunchKernelGGL((attn_bwd_short_mfma_kernel<true, 8>), grid, dim3(512), 0, s, a);
+        else hipLaunchKernelGGL((attn_bwd_short_mfma_kernel<false, 8>), grid, dim3(512), 0, s, a);
+      }
+      return hipGetLastError();
+    }
     if (attn_grid(a) > 0x7fffffffL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)attn_grid(a)), block(64 * AT_WAVES);
     // dq is bound by its tile stream and gains from one XCD per problem; dk/dv is bound by its arithmetic and by the
