@@ -47,9 +47,9 @@ MEASURED_TRAFFIC = {
     "gated_rnn": {"source": "profiles/bench_gated_rnn_hbm_traffic.txt",
                   "vjp1": 9.402e8, "vjp2": 9.398e8, "dw": 6.041e8, "scan": 6.420e8},
     "gpt2_paper": {"source": "profiles/bench_gpt2_paper_hbm_traffic.txt",
-                   "vjp1": 1.771e9, "vjp2": 5.335e8, "dw": 8.941e8, "attn": 1.326e9, "scan": 1.242e9},
+                   "vjp1": 1.771e9, "vjp2": 5.342e8, "dw": 8.928e8, "attn": 1.620e9, "scan": 1.242e9},
     "roberta_like": {"source": "profiles/bench_roberta_like_hbm_traffic.txt",
-                     "vjp1": 9.128e8, "vjp2": 3.332e8, "dw": 5.590e8, "attn": 4.581e8, "scan": 5.377e8},
+                     "vjp1": 9.146e8, "vjp2": 3.333e8, "dw": 5.587e8, "attn": 6.076e8, "scan": 5.378e8},
     "transformer_attn": {"source": "profiles/bench_transformer_attn_hbm_traffic.txt",
                          "vjp1": 5.563e9, "vjp2": 1.432e9, "dw": 2.169e9, "attn": 3.903e9, "scan": 2.458e9},
     "lstm_cell": {"source": "profiles/bench_lstm_cell_hbm_traffic.txt",
