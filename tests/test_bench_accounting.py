@@ -80,3 +80,13 @@ def test_recurrent_counts():
 
 def test_published_peaks():
     assert bench.PEAK_MFMA_BF16_TFLOPS == 2500.0 and bench.PEAK_HBM_GBS == 8000.0
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    """bench.py runs on one GPU: any other --gpus exits with status 2 and says why, before anything touches a GPU."""
+    import os, subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2", "--steps", "1", "--warmup", "0"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
